@@ -1,0 +1,78 @@
+"""Reference scheduler of the CPU oracle: depth, signature tuples, canonical batches.
+
+TEST INFRASTRUCTURE ONLY; shares no code with the GPU scheduler and uses no hash:
+signatures are compared as full tuples.
+
+Follows Section 3.2.  Depth-based batching: the depth of a node is the maximum
+length of a path from a leaf to it, and nodes with identical depth and
+signature form one batch.  Signatures follow Section 3.2 ("computing
+compatibility groups") and Appendix A: the operation, plus dimensions where
+they matter, plus the identity of shared parameters (the A and y of A x + y are
+shared, the x is not).
+
+Where the paper is silent (order of batches inside a depth, order of nodes in
+a batch) the canonical order is: nodes ascending by id inside a batch; batches
+ascending by depth, then by the smallest node id they hold.
+"""
+from __future__ import annotations
+
+import numpy as np
+
+OP_LOOKUP, OP_MATVEC, OP_SLICE = 1, 2, 8
+
+
+def depths(g, n=None) -> np.ndarray:
+    """depth[v] = 0 for a node without node operands, else 1 + max over operands."""
+    n = g.n if n is None else n
+    in_off = g.in_off.tolist()
+    in_idx = g.in_idx.tolist()
+    d = [0] * n
+    for v in range(n):
+        lo, hi = in_off[v], in_off[v + 1]
+        if hi > lo:
+            d[v] = 1 + max(d[u] for u in in_idx[lo:hi])
+    return np.asarray(d, np.int64)
+
+
+def signature(g, v: int) -> tuple:
+    """(op, out_dim, arity, W id, bias id, lo, hi, operand dims...).
+
+    LOOKUP's row, PICK_NLS's label and INPUT's payload are data, not part of
+    the signature; a SLICE carries its range (Section 3.2's slice example).
+    """
+    lo, hi = int(g.in_off[v]), int(g.in_off[v + 1])
+    op = int(g.op[v])
+    s_lo = int(g.aux0[v]) if op == OP_SLICE else 0
+    s_hi = int(g.aux1[v]) if op == OP_SLICE else 0
+    in_dims = tuple(int(g.out_dim[u]) for u in g.in_idx[lo:hi])
+    return (op, int(g.out_dim[v]), hi - lo, int(g.param[v]), int(g.bias[v]), s_lo, s_hi) + in_dims
+
+
+def by_depth(g, n=None):
+    """Canonical depth-based schedule.
+
+    Returns (batch_off[nb+1], node_ids[n], batch_depth[nb]) as int64 arrays.
+    """
+    n = g.n if n is None else n
+    d = depths(g, n)
+    groups = {}
+    for v in range(n):
+        groups.setdefault((int(d[v]), signature(g, v)), []).append(v)
+    batches = sorted(groups.items(), key=lambda kv: (kv[0][0], kv[1][0]))
+    batch_off = [0]
+    node_ids = []
+    batch_depth = []
+    for (dep, _sig), nodes in batches:
+        node_ids.extend(nodes)          # appended in ascending id
+        batch_off.append(len(node_ids))
+        batch_depth.append(dep)
+    return (np.asarray(batch_off, np.int64), np.asarray(node_ids, np.int64),
+            np.asarray(batch_depth, np.int64))
+
+
+def no_batching(g, n=None):
+    """Unbatched execution (Section 2: each operation performed sequentially):
+    one batch per node in id order; batch_depth holds the step index (= node id)."""
+    n = g.n if n is None else n
+    ids = np.arange(n, dtype=np.int64)
+    return np.arange(n + 1, dtype=np.int64), ids, ids.copy()

@@ -1,0 +1,109 @@
+"""Pins of the oracle's reference scheduler: invariants checked by an independent validator,
+the closed-form depth-based schedule of the RNN workload, brute force on tiny graphs."""
+import itertools
+
+import numpy as np
+import pytest
+
+from oracle import schedule as S
+from paper_1705_07860_amd import workloads as wl
+from tests.helpers import longest_path_depths, sig_string, validate_schedule
+
+
+@pytest.mark.parametrize("name", ["rnn", "tagger", "tree", "parser"])
+def test_schedule_invariants_on_configs(name, workload_cache):
+    p, g, _ = workload_cache(name)
+    bo, ids, bd = S.by_depth(g)
+    depth_of = validate_schedule(g, bo, ids, bd)
+    assert np.array_equal(depth_of, S.depths(g))
+
+
+def test_schedule_invariants_char_config_sample():
+    p = wl.tagger_params(with_char=True)
+    g = wl.tagger_minibatch(p, seed=5, n_sent=6, with_char=True)
+    bo, ids, bd = S.by_depth(g)
+    validate_schedule(g, bo, ids, bd)
+    assert np.array_equal(longest_path_depths(g), S.depths(g))
+
+
+def test_closed_form_schedule_of_rnn_chains():
+    """With h_t = tanh(W x_t + U h_{t-1} + b) built as MATVEC, MATVEC, ADD, TANH: depth(h_t) = 3t;
+    the U-product, sum and tanh batches of step t hold #{i : n_i >= t} nodes; every W-product
+    sits in one depth-1 batch; the loss nodes of unequal-length sequences land at different
+    depths (the weakness of depth-based batching named in Section 3.2)."""
+    lengths = [3, 7, 7, 4, 10, 3, 5, 7]
+    p = wl.rnn_params()
+    g = wl.rnn_minibatch(p, seed=1, lengths=lengths)
+    bo, ids, bd = S.by_depth(g)
+    sizes = np.diff(bo)
+    by = {}
+    for b in range(len(bd)):
+        h = int(ids[bo[b]])
+        key = (int(bd[b]), int(g.op[h]), int(g.param[h]))
+        assert key not in by
+        by[key] = int(sizes[b])
+    nmax = max(lengths)
+    assert by[(0, wl.OP_INPUT, -1)] == len(lengths) + sum(lengths)
+    assert by[(1, wl.OP_MATVEC, 0)] == sum(lengths)
+    for t in range(1, nmax + 1):
+        alive = sum(1 for n in lengths if n >= t)
+        assert by[(3 * t - 2, wl.OP_MATVEC, 1)] == alive
+        assert by[(3 * t - 1, wl.OP_ADD, -1)] == alive
+        assert by[(3 * t, wl.OP_TANH, -1)] == alive
+    for n in set(lengths):
+        assert by[(3 * n + 1, wl.OP_SQNORM, -1)] == lengths.count(n)
+    last = max(3 * n + 2 for n in lengths)
+    assert by[(last, wl.OP_ADD, -1)] == 1
+    assert len(bd) == 1 + 1 + 3 * nmax + len(set(lengths)) + 1
+    # equal lengths: the loss nodes do batch together
+    g2 = wl.rnn_minibatch(p, seed=1, lengths=[6] * 5)
+    bo2, ids2, bd2 = S.by_depth(g2)
+    sq = [b for b in range(len(bd2)) if g2.op[ids2[bo2[b]]] == wl.OP_SQNORM]
+    assert len(sq) == 1 and bo2[sq[0] + 1] - bo2[sq[0]] == 5
+
+
+@pytest.mark.parametrize("seed", range(8))
+def test_brute_force_grouping_on_tiny_random_graphs(seed):
+    """Two nodes share a batch exactly when their longest-path depths (by path enumeration)
+    and their paper-style signature strings agree; checked for every pair."""
+    p, g = wl.random_dag(100 + seed, n_nodes=12, dim=4)
+    bo, ids, bd = S.by_depth(g)
+    depth = longest_path_depths(g)
+    batch_of = np.empty(g.n, np.int64)
+    for b in range(len(bd)):
+        batch_of[ids[bo[b]:bo[b + 1]]] = b
+    for u, v in itertools.combinations(range(g.n), 2):
+        same = depth[u] == depth[v] and sig_string(g, u) == sig_string(g, v)
+        assert (batch_of[u] == batch_of[v]) == same, (u, v)
+    validate_schedule(g, bo, ids, bd)
+
+
+def test_signature_contents():
+    p = wl.tagger_params()
+    g = wl.tagger_minibatch(p, seed=3, lengths=[4, 2])
+    look = [v for v in range(g.n) if g.op[v] == wl.OP_LOOKUP]
+    assert len({S.signature(g, v) for v in look}) == 1          # row is not in the signature
+    pick = [v for v in range(g.n) if g.op[v] == wl.OP_PICK_NLS]
+    assert len({S.signature(g, v) for v in pick}) == 1          # label is not in the signature
+    mv = [v for v in range(g.n) if g.op[v] == wl.OP_MATVEC]
+    assert {(S.signature(g, v)[3], S.signature(g, v)[4]) for v in mv} == \
+        {(int(g.param[v]), int(g.bias[v])) for v in mv}          # shared A and y are in it
+    sl = [v for v in range(g.n) if g.op[v] == wl.OP_SLICE]
+    assert len({S.signature(g, v) for v in sl}) == 4             # the range is in it
+
+
+def test_no_batching_schedule():
+    p, g = wl.make("rnn")
+    bo, ids, bd = S.no_batching(g)
+    assert np.array_equal(np.diff(bo), np.ones(g.n))
+    assert np.array_equal(ids, np.arange(g.n))
+
+
+def test_permuting_instances_permutes_the_schedule():
+    p = wl.rnn_params()
+    ga = wl.rnn_minibatch(p, seed=2, lengths=[3, 5])
+    gb = wl.rnn_minibatch(p, seed=2, lengths=[5, 3])
+    boa, _, bda = S.by_depth(ga)
+    bob, _, bdb = S.by_depth(gb)
+    assert np.array_equal(np.diff(boa), np.diff(bob))
+    assert np.array_equal(bda, bdb)
