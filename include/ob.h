@@ -1,0 +1,184 @@
+/*
+ * ob.h - C ABI of the on-the-fly operation batching library for AMD MI355X (gfx950).
+ *
+ * The calls follow the paper's problem statement (Section 2, Train-Batch-Naive):
+ * New-Graph, append the nodes of every instance, Forward(L), Backward(L), read
+ * values and gradients.  Graph definition is lazy (Section 3.1): adding a node
+ * computes nothing; ob_forward schedules every pending node on the GPU
+ * (Section 3.2: signatures, depth, batches) and executes each batch as one
+ * batched operation (Section 3.3).  The caller keeps seeing the unbatched node
+ * ids (Section 3.3, single -> batch node conversion is internal).
+ *
+ * Conventions
+ *  - Every function returns 0 (OB_OK) or a negative OB_E_* code; node adders
+ *    return the new node id (>= 0) or a negative code.  No C++ type, exception
+ *    or torch type crosses this boundary.
+ *  - "host" pointers are ordinary CPU memory owned by the caller and copied (in)
+ *    or filled (out) during the call.  "device" pointers are HIP device memory.
+ *  - Output buffers carry a capacity in elements; a too-small buffer fails with
+ *    OB_E_RANGE and writes nothing.
+ *  - The device arena and the stream are owned by the caller and must outlive the
+ *    context.  The library allocates no device memory of its own: parameters,
+ *    graph tables, values and gradients are carved out of the arena.
+ *  - A context is not thread-safe.  Work is enqueued on the context's stream;
+ *    reads synchronise that stream.
+ *  - Graph errors (forward reference, dimension mismatch, label or slice out of
+ *    range) are detected on the host when the node is added, so the GPU never sees
+ *    a malformed graph.
+ *  - Matrices are row-major fp32.  A bias is a rows x 1 parameter.
+ */
+#ifndef OB_H
+#define OB_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct ob_ctx ob_ctx;
+
+/* error codes */
+#define OB_OK 0
+#define OB_E_BADID (-1)    /* unknown node / parameter id, or forward reference */
+#define OB_E_DIM (-2)      /* operand dimensions do not fit the operation */
+#define OB_E_RANGE (-3)    /* row / label / slice / capacity out of range */
+#define OB_E_NOTSCALAR (-4) /* backward root is not a 1-element node */
+#define OB_E_OOM (-5)      /* the caller's arena is too small */
+#define OB_E_STATE (-6)    /* call not valid in the current state, or an internal check failed */
+#define OB_E_HIP (-7)      /* a HIP runtime call failed; see ob_last_error */
+#define OB_E_ARG (-8)      /* null pointer or otherwise invalid argument */
+
+/* operation codes of the graph data format */
+#define OB_OP_INPUT 0      /* v = payload                                   */
+#define OB_OP_LOOKUP 1     /* v = E[row, :]                                 */
+#define OB_OP_MATVEC 2     /* v = W x (+ b)       shared W, b (Appendix A)   */
+#define OB_OP_ADD 3        /* v = x_1 + ... + x_k                           */
+#define OB_OP_CMULT 4      /* v = a * b component-wise                      */
+#define OB_OP_TANH 5
+#define OB_OP_SIGMOID 6
+#define OB_OP_CONCAT 7     /* v = [x_1; ...; x_k]                           */
+#define OB_OP_SLICE 8      /* v = x[lo:hi)                                  */
+#define OB_OP_PICK_NLS 9   /* v = logsumexp(x) - x[label]  (scalar)         */
+#define OB_OP_SQNORM 10    /* v = sum_i x_i^2               (scalar)         */
+
+/* batching modes (Section 4.1: NoAuto / ByDepth / ByAgenda) */
+#define OB_NOBATCH 0       /* one launch per node forward and per node backward */
+#define OB_BYDEPTH 1       /* depth-based batching (Section 3.2)                */
+#define OB_BYAGENDA 2      /* agenda-based batching: not built, OB_E_STATE      */
+
+/* how the per-step launches are issued */
+#define OB_LAUNCH_STREAM 0     /* one kernel launch per step on the stream            */
+#define OB_LAUNCH_GRAPH 1      /* the per-step launches captured in a hipGraph        */
+#define OB_LAUNCH_PERSISTENT 2 /* one cooperative kernel walks all steps, grid barrier */
+
+/* ---- context ------------------------------------------------------------------------- */
+
+/* arena_dev: device memory, at least 256-byte aligned; hip_stream: a hipStream_t (or NULL
+ * for the default stream).  Touches no GPU state until the first upload. */
+int ob_ctx_create(void *arena_dev, size_t arena_bytes, void *hip_stream, ob_ctx **out);
+int ob_ctx_destroy(ob_ctx *ctx);
+int ob_ctx_set_mode(ob_ctx *ctx, int mode);
+int ob_ctx_set_launch(ob_ctx *ctx, int launch);
+/* Library-owned message for the last failing call on this context (valid until the next
+ * call); ctx may be NULL for errors of ob_ctx_create. */
+const char *ob_last_error(ob_ctx *ctx);
+
+/* ---- parameters (persist across graphs) ------------------------------------------------- */
+
+/* host_init: rows*cols fp32, row-major (host).  Writes the new parameter id to *id.
+ * Parameters must be created before the first graph is uploaded. */
+int ob_param_create(ob_ctx *ctx, int rows, int cols, const float *host_init, int *id);
+int ob_param_write(ob_ctx *ctx, int id, const float *host_data);
+int ob_param_read(ob_ctx *ctx, int id, float *host_out, size_t cap);
+/* Gradients accumulate over ob_backward calls until zeroed. */
+int ob_param_grad_zero(ob_ctx *ctx);
+int ob_param_grad_read(ob_ctx *ctx, int id, float *host_out, size_t cap);
+
+/* ---- graph definition (Section 3.1; host only, nothing is computed) ---------------------- */
+
+int ob_graph_new(ob_ctx *ctx); /* drops all nodes, keeps parameters and their gradients */
+int ob_graph_size(ob_ctx *ctx, int *n_nodes, int *n_edges);
+
+int ob_add_input(ob_ctx *ctx, int dim, const float *host_data);
+int ob_add_lookup(ob_ctx *ctx, int table, int row);
+int ob_add_matvec(ob_ctx *ctx, int w, int bias_or_neg1, int x);
+int ob_add_unary(ob_ctx *ctx, int op, int x);                 /* OB_OP_TANH, OB_OP_SIGMOID */
+int ob_add_nary(ob_ctx *ctx, int op, int k, const int *xs);   /* OB_OP_ADD, OB_OP_CMULT (k=2), OB_OP_CONCAT */
+int ob_add_slice(ob_ctx *ctx, int x, int lo, int hi);
+int ob_add_pick_nls(ob_ctx *ctx, int x, int label);
+int ob_add_sqnorm(ob_ctx *ctx, int x);
+
+/* Appends n nodes given as flat arrays (all host).  in_off has n+1 entries, relative to
+ * this call's in_idx; in_idx holds absolute node ids (existing nodes or earlier nodes of
+ * this call).  aux0: LOOKUP row, SLICE lo, PICK_NLS label, INPUT offset into `payload`;
+ * aux1: SLICE hi.  out_dim is checked against the dimension the operation implies.
+ * Returns the id of the first appended node.  On error no node is appended. */
+int ob_add_bulk(ob_ctx *ctx, int n, const uint8_t *op, const uint32_t *out_dim,
+                const uint32_t *in_off, const uint32_t *in_idx, const int32_t *param,
+                const int32_t *bias, const int32_t *aux0, const int32_t *aux1,
+                const float *payload, size_t payload_len);
+
+/* ---- execution ------------------------------------------------------------------------------ */
+
+/* Copies pending nodes to the device (asynchronous).  Implied by ob_forward. */
+int ob_upload(ob_ctx *ctx);
+/* Evaluates every node with id <= node (Section 3.1: evaluation happens when a value is
+ * requested).  Schedules on the GPU (Section 3.2), then runs the batches in order
+ * (Section 3.3).  Asynchronous except for one small read of the schedule header. */
+int ob_forward(ob_ctx *ctx, int node);
+/* Reverse-mode differentiation from a 1-element node that ob_forward covered: batches in
+ * reverse order (Section 3.3).  Node gradients are overwritten, parameter gradients
+ * accumulate. */
+int ob_backward(ob_ctx *ctx, int node);
+int ob_sync(ob_ctx *ctx);
+
+/* ---- reads (synchronise the stream) ---------------------------------------------------------- */
+
+int ob_value_read(ob_ctx *ctx, int node, float *host_out, size_t cap);
+int ob_grad_read(ob_ctx *ctx, int node, float *host_out, size_t cap);
+/* All node values (which = 0) or node gradients (which = 1) concatenated in node-id order. */
+int ob_all_read(ob_ctx *ctx, int which, float *host_out, size_t cap);
+
+/* The schedule of the last ob_forward: batch b holds node_ids[batch_off[b] .. batch_off[b+1]).
+ * batch_depth is the depth (OB_BYDEPTH) or the step index (OB_NOBATCH); batch_sig is the
+ * 64-bit signature hash (Appendix B) and is informational.  cap_batches / cap_nodes are the
+ * capacities of the per-batch arrays (batch_off needs cap_batches + 1) and of node_ids. */
+int ob_schedule_read(ob_ctx *ctx, int *n_batches, int *batch_depth, uint64_t *batch_sig,
+                     int *batch_off, int *node_ids, size_t cap_batches, size_t cap_nodes);
+
+/* Counters and phase times of the last forward / backward. */
+typedef struct ob_stats {
+    int32_t n_nodes, n_edges, n_steps, n_batches;
+    int32_t n_tiles_fwd, n_tiles_bwd_pull, n_tiles_bwd_dx, n_param_uses;
+    int32_t n_launch_fwd, n_launch_bwd, n_launch_sched, reserved0;
+    uint64_t value_floats, grad_floats, arena_used_bytes, upload_bytes;
+    float ms_upload, ms_schedule, ms_forward, ms_backward; /* hipEvent times on the stream */
+    float ms_param_grads, ms_graph_build, reserved1, reserved2;
+} ob_stats;
+int ob_stats_read(ob_ctx *ctx, ob_stats *out);
+
+/* Internal device tables of the last schedule, for stage-by-stage parity tests.
+ * which: OB_DBG_*; elements are copied as 32-bit words (64-bit tables as two words each). */
+#define OB_DBG_DEPTH 0     /* u32[n]  step (depth) per node        */
+#define OB_DBG_SIG 1       /* u64[n]  signature hash per node      */
+#define OB_DBG_SUCC_OFF 2  /* u32[n+1] successor CSR offsets       */
+#define OB_DBG_SUCC_EDGE 3 /* u32[E]  edge ids sorted by producer  */
+#define OB_DBG_ORDER 4     /* u32[n]  node ids in schedule order   */
+#define OB_DBG_VAL_OFF 5   /* u32[n]  element offset of each node's row in the value arena */
+int ob_debug_read(ob_ctx *ctx, int which, uint32_t *host_out, size_t cap_words, size_t *n_words);
+
+/* Stand-alone device primitives, exposed so that tests can check them directly.  All
+ * pointers are host; the context's arena beyond its current use serves as scratch. */
+int ob_test_sort(ob_ctx *ctx, size_t n, const uint64_t *keys, const uint32_t *vals, int lo_bit,
+                 int n_bits, uint64_t *keys_out, uint32_t *vals_out);
+int ob_test_scan(ob_ctx *ctx, size_t n, const uint32_t *in, uint32_t *out_exclusive,
+                 uint32_t *total);
+/* C[M x N] = A[M x K] * B[N x K]^T through the library's MFMA tile routine. */
+int ob_test_gemm(ob_ctx *ctx, int M, int N, int K, const float *A, const float *B, float *C);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* OB_H */

@@ -1,0 +1,810 @@
+// C ABI of the library (see include/ob.h): host-side graph store with validation at add time,
+// upload, and the forward / backward / read entry points.
+#include "../../include/ob.h"
+#include "ob_ctx.h"
+
+#include <chrono>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+
+static std::string g_create_error;
+
+int ctx_fail(ob_ctx *ctx, int code, const char *fmt, ...)
+{
+    char buf[512];
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(buf, sizeof buf, fmt, ap);
+    va_end(ap);
+    if (ctx) ctx->err = buf; else g_create_error = buf;
+    return code;
+}
+
+static inline size_t up256(size_t x) { return (x + 255) & ~(size_t)255; }
+
+void *arena_alloc(ob_ctx *ctx, size_t bytes)
+{
+    const size_t need = up256(bytes ? bytes : 1);
+    if (ctx->top + need > ctx->arena_bytes) return nullptr;
+    void *p = ctx->arena + ctx->top;
+    ctx->top += need;
+    return p;
+}
+
+#define CHECK_CTX(ctx) do { if (!(ctx)) return OB_E_ARG; } while (0)
+
+extern "C" {
+
+const char *ob_last_error(ob_ctx *ctx) { return ctx ? ctx->err.c_str() : g_create_error.c_str(); }
+
+int ob_ctx_create(void *arena_dev, size_t arena_bytes, void *hip_stream, ob_ctx **out)
+{
+    if (!out) return ctx_fail(nullptr, OB_E_ARG, "ob_ctx_create: out is null");
+    if (((uintptr_t)arena_dev & 255u) != 0) return ctx_fail(nullptr, OB_E_ARG, "arena must be 256-byte aligned");
+    ob_ctx *c = new (std::nothrow) ob_ctx();
+    if (!c) return ctx_fail(nullptr, OB_E_OOM, "out of host memory");
+    c->arena = (char *)arena_dev;
+    c->arena_bytes = arena_dev ? arena_bytes : 0;
+    c->stream = (hipStream_t)hip_stream;
+    c->in_off.push_back(0);
+    *out = c;
+    return OB_OK;
+}
+
+int ob_ctx_destroy(ob_ctx *ctx)
+{
+    CHECK_CTX(ctx);
+    if (ctx->uploaded) (void)hipStreamSynchronize(ctx->stream);
+    if (ctx->gexec_fwd) (void)hipGraphExecDestroy(ctx->gexec_fwd);
+    if (ctx->gexec_bwd) (void)hipGraphExecDestroy(ctx->gexec_bwd);
+    if (ctx->graph_fwd) (void)hipGraphDestroy(ctx->graph_fwd);
+    if (ctx->graph_bwd) (void)hipGraphDestroy(ctx->graph_bwd);
+    if (ctx->ev_ok) for (auto &e : ctx->ev) (void)hipEventDestroy(e);
+    if (ctx->pinned) (void)hipHostFree(ctx->pinned);
+    if (ctx->hdr_pinned) (void)hipHostFree(ctx->hdr_pinned);
+    delete ctx;
+    return OB_OK;
+}
+
+int ob_ctx_set_mode(ob_ctx *ctx, int mode)
+{
+    CHECK_CTX(ctx);
+    if (mode == OB_BYAGENDA) return ctx_fail(ctx, OB_E_STATE, "agenda-based batching is not built");
+    if (mode != OB_NOBATCH && mode != OB_BYDEPTH) return ctx_fail(ctx, OB_E_ARG, "unknown mode %d", mode);
+    ctx->mode = mode;
+    return OB_OK;
+}
+
+int ob_ctx_set_launch(ob_ctx *ctx, int launch)
+{
+    CHECK_CTX(ctx);
+    if (launch == OB_LAUNCH_PERSISTENT) return ctx_fail(ctx, OB_E_STATE, "persistent launch is not built");
+    if (launch != OB_LAUNCH_STREAM && launch != OB_LAUNCH_GRAPH) return ctx_fail(ctx, OB_E_ARG, "unknown launch %d", launch);
+    ctx->launch = launch;
+    return OB_OK;
+}
+
+// ---- parameters ---------------------------------------------------------------------------------
+
+}  // extern "C"
+
+// Parameter data written before the GPU is first touched waits in host copies.
+static int params_to_device(ob_ctx *ctx)
+{
+    if (ctx->pending.empty()) return 0;
+    if (!ctx->arena) return ctx_fail(ctx, OB_E_STATE, "the context has no device arena");
+    for (size_t i = 0; i < ctx->pending.size(); ++i) {
+        auto &v = ctx->pending[i];
+        if (v.empty()) continue;
+        HIP_TRY(ctx, hipMemcpyAsync(ctx->params[i].data, v.data(), v.size() * 4, hipMemcpyHostToDevice, ctx->stream));
+        HIP_TRY(ctx, hipMemsetAsync(ctx->params[i].grad, 0, v.size() * 4, ctx->stream));
+    }
+    HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
+    ctx->pending.clear();
+    return 0;
+}
+
+extern "C" {
+
+int ob_param_create(ob_ctx *ctx, int rows, int cols, const float *host_init, int *id)
+{
+    CHECK_CTX(ctx);
+    if (!host_init || !id) return ctx_fail(ctx, OB_E_ARG, "ob_param_create: null argument");
+    if (rows <= 0 || cols <= 0) return ctx_fail(ctx, OB_E_DIM, "parameter shape %d x %d", rows, cols);
+    if (ctx->top != ctx->persist_top)
+        return ctx_fail(ctx, OB_E_STATE, "parameters must be created while no graph is on the device");
+    const size_t count = (size_t)rows * cols;
+    HostParam p;
+    p.rows = rows; p.cols = cols;
+    p.data = arena_array<float>(ctx, count);
+    p.grad = arena_array<float>(ctx, count);
+    if (ctx->arena && (!p.data || !p.grad)) return ctx_fail(ctx, OB_E_OOM, "arena too small for a %d x %d parameter", rows, cols);
+    ctx->persist_top = ctx->top;
+    ctx->params.push_back(p);
+    ctx->pending.resize(ctx->params.size());
+    ctx->pending.back().assign(host_init, host_init + count);
+    ctx->params_dirty = true;
+    if (rows > ctx->max_param_rows) ctx->max_param_rows = rows;
+    *id = (int)ctx->params.size() - 1;
+    return OB_OK;
+}
+
+static int check_param(ob_ctx *ctx, int id)
+{
+    if (id < 0 || id >= (int)ctx->params.size()) return ctx_fail(ctx, OB_E_BADID, "unknown parameter id %d", id);
+    return 0;
+}
+
+int ob_param_write(ob_ctx *ctx, int id, const float *host_data)
+{
+    CHECK_CTX(ctx);
+    if (!host_data) return ctx_fail(ctx, OB_E_ARG, "null data");
+    if (int rc = check_param(ctx, id)) return rc;
+    const size_t count = (size_t)ctx->params[id].rows * ctx->params[id].cols;
+    if ((size_t)id < ctx->pending.size() && !ctx->pending[id].empty()) {
+        ctx->pending[id].assign(host_data, host_data + count);
+        return OB_OK;
+    }
+    HIP_TRY(ctx, hipMemcpyAsync(ctx->params[id].data, host_data, count * 4, hipMemcpyHostToDevice, ctx->stream));
+    HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
+    return OB_OK;
+}
+
+static int param_read_impl(ob_ctx *ctx, int id, float *out, size_t cap, bool grad)
+{
+    if (!out) return ctx_fail(ctx, OB_E_ARG, "null output");
+    if (int rc = check_param(ctx, id)) return rc;
+    const size_t count = (size_t)ctx->params[id].rows * ctx->params[id].cols;
+    if (cap < count) return ctx_fail(ctx, OB_E_RANGE, "buffer holds %zu of %zu elements", cap, count);
+    if (int rc = params_to_device(ctx)) return rc;
+    HIP_TRY(ctx, hipMemcpyAsync(out, grad ? ctx->params[id].grad : ctx->params[id].data, count * 4,
+                                hipMemcpyDeviceToHost, ctx->stream));
+    HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
+    return OB_OK;
+}
+
+int ob_param_read(ob_ctx *ctx, int id, float *host_out, size_t cap)
+{
+    CHECK_CTX(ctx);
+    return param_read_impl(ctx, id, host_out, cap, false);
+}
+
+int ob_param_grad_read(ob_ctx *ctx, int id, float *host_out, size_t cap)
+{
+    CHECK_CTX(ctx);
+    return param_read_impl(ctx, id, host_out, cap, true);
+}
+
+int ob_param_grad_zero(ob_ctx *ctx)
+{
+    CHECK_CTX(ctx);
+    if (int rc = params_to_device(ctx)) return rc;
+    // parameters and their gradients are adjacent allocations; zero each gradient block
+    for (auto &p : ctx->params)
+        HIP_TRY(ctx, hipMemsetAsync(p.grad, 0, (size_t)p.rows * p.cols * 4, ctx->stream));
+    return OB_OK;
+}
+
+// ---- graph definition ----------------------------------------------------------------------------
+
+int ob_graph_new(ob_ctx *ctx)
+{
+    CHECK_CTX(ctx);
+    if (ctx->uploaded) HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
+    ctx->op.clear(); ctx->out_dim.clear(); ctx->in_off.assign(1, 0); ctx->in_idx.clear();
+    ctx->param.clear(); ctx->bias.clear(); ctx->aux0.clear(); ctx->aux1.clear(); ctx->payload.clear();
+    ctx->items_upto.clear();
+    ctx->sum_out_dim = 0;
+    ctx->sum_mv_k = 0;
+    ctx->top = ctx->persist_top;
+    ctx->uploaded = false;
+    ctx->n_sched = 0;
+    ctx->forward_done = ctx->backward_done = false;
+    return OB_OK;
+}
+
+int ob_graph_size(ob_ctx *ctx, int *n_nodes, int *n_edges)
+{
+    CHECK_CTX(ctx);
+    if (n_nodes) *n_nodes = (int)ctx->op.size();
+    if (n_edges) *n_edges = (int)ctx->in_idx.size();
+    return OB_OK;
+}
+
+}  // extern "C"
+
+// Validates one node against the graph so far and computes the dimension it implies.
+// `n_before` = number of nodes that exist (operands must be smaller).
+static int validate_node(ob_ctx *ctx, u32 n_before, const std::vector<u32> &dims, int op, const u32 *ins, u32 arity,
+                         int param, int bias, int a0, int a1, u32 *dim_out, u32 in_dim_hint)
+{
+    for (u32 j = 0; j < arity; ++j)
+        if (ins[j] >= n_before) return ctx_fail(ctx, OB_E_BADID, "operand id %u of node %u does not exist yet", ins[j], n_before);
+    auto pshape_ok = [&](int id) { return id >= 0 && id < (int)ctx->params.size(); };
+    switch (op) {
+    case OB_OP_INPUT:
+        if (arity != 0) return ctx_fail(ctx, OB_E_DIM, "INPUT takes no operands");
+        if (in_dim_hint == 0) return ctx_fail(ctx, OB_E_DIM, "INPUT of dimension 0");
+        *dim_out = in_dim_hint;
+        return 0;
+    case OB_OP_LOOKUP:
+        if (arity != 0) return ctx_fail(ctx, OB_E_DIM, "LOOKUP takes no operands");
+        if (!pshape_ok(param)) return ctx_fail(ctx, OB_E_BADID, "unknown table id %d", param);
+        if (a0 < 0 || a0 >= ctx->params[param].rows) return ctx_fail(ctx, OB_E_RANGE, "row %d outside table of %d rows", a0, ctx->params[param].rows);
+        *dim_out = (u32)ctx->params[param].cols;
+        return 0;
+    case OB_OP_MATVEC:
+        if (arity != 1) return ctx_fail(ctx, OB_E_DIM, "MATVEC takes one operand");
+        if (!pshape_ok(param)) return ctx_fail(ctx, OB_E_BADID, "unknown matrix id %d", param);
+        if ((u32)ctx->params[param].cols != dims[ins[0]])
+            return ctx_fail(ctx, OB_E_DIM, "MATVEC: matrix has %d columns, operand has %u elements", ctx->params[param].cols, dims[ins[0]]);
+        if (bias != -1) {
+            if (!pshape_ok(bias)) return ctx_fail(ctx, OB_E_BADID, "unknown bias id %d", bias);
+            if (ctx->params[bias].cols != 1 || ctx->params[bias].rows != ctx->params[param].rows)
+                return ctx_fail(ctx, OB_E_DIM, "bias must be %d x 1", ctx->params[param].rows);
+        }
+        *dim_out = (u32)ctx->params[param].rows;
+        return 0;
+    case OB_OP_ADD:
+    case OB_OP_CMULT:
+        if (arity < 1 || (op == OB_OP_CMULT && arity != 2)) return ctx_fail(ctx, OB_E_DIM, "wrong operand count %u", arity);
+        for (u32 j = 1; j < arity; ++j)
+            if (dims[ins[j]] != dims[ins[0]]) return ctx_fail(ctx, OB_E_DIM, "operand dimensions differ (%u vs %u)", dims[ins[j]], dims[ins[0]]);
+        *dim_out = dims[ins[0]];
+        return 0;
+    case OB_OP_TANH:
+    case OB_OP_SIGMOID:
+        if (arity != 1) return ctx_fail(ctx, OB_E_DIM, "unary op takes one operand");
+        *dim_out = dims[ins[0]];
+        return 0;
+    case OB_OP_CONCAT: {
+        if (arity < 1) return ctx_fail(ctx, OB_E_DIM, "CONCAT needs operands");
+        u64 d = 0;
+        for (u32 j = 0; j < arity; ++j) d += dims[ins[j]];
+        if (d > 0x7fffffffu) return ctx_fail(ctx, OB_E_DIM, "CONCAT too long");
+        *dim_out = (u32)d;
+        return 0;
+    }
+    case OB_OP_SLICE:
+        if (arity != 1) return ctx_fail(ctx, OB_E_DIM, "SLICE takes one operand");
+        if (a0 < 0 || a1 <= a0 || (u32)a1 > dims[ins[0]]) return ctx_fail(ctx, OB_E_RANGE, "slice [%d,%d) outside %u elements", a0, a1, dims[ins[0]]);
+        *dim_out = (u32)(a1 - a0);
+        return 0;
+    case OB_OP_PICK_NLS:
+        if (arity != 1) return ctx_fail(ctx, OB_E_DIM, "PICK_NLS takes one operand");
+        if (a0 < 0 || (u32)a0 >= dims[ins[0]]) return ctx_fail(ctx, OB_E_RANGE, "label %d outside %u classes", a0, dims[ins[0]]);
+        *dim_out = 1;
+        return 0;
+    case OB_OP_SQNORM:
+        if (arity != 1) return ctx_fail(ctx, OB_E_DIM, "SQNORM takes one operand");
+        *dim_out = 1;
+        return 0;
+    default:
+        return ctx_fail(ctx, OB_E_ARG, "unknown op %d", op);
+    }
+}
+
+static int append_node(ob_ctx *ctx, int op, const u32 *ins, u32 arity, int param, int bias, int a0, int a1, u32 dim)
+{
+    if (ctx->n_sched) return ctx_fail(ctx, OB_E_STATE, "the graph was already evaluated; incremental forward is not built");
+    if (ctx->op.size() >= 0x7ffffff0u) return ctx_fail(ctx, OB_E_RANGE, "too many nodes");
+    ctx->op.push_back((u8)op);
+    ctx->out_dim.push_back(dim);
+    ctx->in_idx.insert(ctx->in_idx.end(), ins, ins + arity);
+    ctx->in_off.push_back((u32)ctx->in_idx.size());
+    ctx->param.push_back(param);
+    ctx->bias.push_back(bias);
+    ctx->aux0.push_back(a0);
+    ctx->aux1.push_back(a1);
+    const u32 items = (op == OB_OP_MATVEC) ? (1u + (bias >= 0 ? 1u : 0u)) : (op == OB_OP_LOOKUP ? 1u : 0u);
+    ctx->items_upto.push_back((ctx->items_upto.empty() ? 0u : ctx->items_upto.back()) + items);
+    ctx->sum_out_dim += dim;
+    if (op == OB_OP_MATVEC) {
+        ctx->sum_mv_k += (u64)ctx->params[param].cols;
+        if (!ctx->params_used_w[param]) { ctx->params_used_w[param] = 1; ctx->params_dirty = true; }
+        if (bias >= 0 && !ctx->params_used_b[bias]) { ctx->params_used_b[bias] = 1; ctx->params_dirty = true; }
+    }
+    ctx->uploaded = false;
+    return (int)ctx->op.size() - 1;
+}
+
+static void sync_used_flags(ob_ctx *ctx)
+{
+    ctx->params_used_w.resize(ctx->params.size(), 0);
+    ctx->params_used_b.resize(ctx->params.size(), 0);
+}
+
+static int add_one(ob_ctx *ctx, int op, const u32 *ins, u32 arity, int param, int bias, int a0, int a1, u32 in_dim_hint,
+                   const float *payload)
+{
+    sync_used_flags(ctx);
+    u32 dim = 0;
+    if (int rc = validate_node(ctx, (u32)ctx->op.size(), ctx->out_dim, op, ins, arity, param, bias, a0, a1, &dim, in_dim_hint))
+        return rc;
+    if (op == OB_OP_INPUT) {
+        if (!payload) return ctx_fail(ctx, OB_E_ARG, "INPUT without data");
+        a0 = (int)ctx->payload.size();
+        ctx->payload.insert(ctx->payload.end(), payload, payload + dim);
+    }
+    return append_node(ctx, op, ins, arity, param, bias, a0, a1, dim);
+}
+
+extern "C" {
+
+int ob_add_input(ob_ctx *ctx, int dim, const float *host_data)
+{
+    CHECK_CTX(ctx);
+    if (dim <= 0) return ctx_fail(ctx, OB_E_DIM, "INPUT of dimension %d", dim);
+    return add_one(ctx, OB_OP_INPUT, nullptr, 0, -1, -1, 0, 0, (u32)dim, host_data);
+}
+
+int ob_add_lookup(ob_ctx *ctx, int table, int row)
+{
+    CHECK_CTX(ctx);
+    return add_one(ctx, OB_OP_LOOKUP, nullptr, 0, table, -1, row, 0, 0, nullptr);
+}
+
+int ob_add_matvec(ob_ctx *ctx, int w, int bias_or_neg1, int x)
+{
+    CHECK_CTX(ctx);
+    if (x < 0) return ctx_fail(ctx, OB_E_BADID, "negative operand id");
+    if (bias_or_neg1 < -1) return ctx_fail(ctx, OB_E_BADID, "bias id %d", bias_or_neg1);
+    const u32 in = (u32)x;
+    return add_one(ctx, OB_OP_MATVEC, &in, 1, w, bias_or_neg1, 0, 0, 0, nullptr);
+}
+
+int ob_add_unary(ob_ctx *ctx, int op, int x)
+{
+    CHECK_CTX(ctx);
+    if (op != OB_OP_TANH && op != OB_OP_SIGMOID) return ctx_fail(ctx, OB_E_ARG, "op %d is not unary", op);
+    if (x < 0) return ctx_fail(ctx, OB_E_BADID, "negative operand id");
+    const u32 in = (u32)x;
+    return add_one(ctx, op, &in, 1, -1, -1, 0, 0, 0, nullptr);
+}
+
+int ob_add_nary(ob_ctx *ctx, int op, int k, const int *xs)
+{
+    CHECK_CTX(ctx);
+    if (op != OB_OP_ADD && op != OB_OP_CMULT && op != OB_OP_CONCAT) return ctx_fail(ctx, OB_E_ARG, "op %d is not n-ary", op);
+    if (k <= 0 || !xs) return ctx_fail(ctx, OB_E_ARG, "no operands");
+    std::vector<u32> ins((size_t)k);
+    for (int j = 0; j < k; ++j) {
+        if (xs[j] < 0) return ctx_fail(ctx, OB_E_BADID, "negative operand id");
+        ins[j] = (u32)xs[j];
+    }
+    return add_one(ctx, op, ins.data(), (u32)k, -1, -1, 0, 0, 0, nullptr);
+}
+
+int ob_add_slice(ob_ctx *ctx, int x, int lo, int hi)
+{
+    CHECK_CTX(ctx);
+    if (x < 0) return ctx_fail(ctx, OB_E_BADID, "negative operand id");
+    const u32 in = (u32)x;
+    return add_one(ctx, OB_OP_SLICE, &in, 1, -1, -1, lo, hi, 0, nullptr);
+}
+
+int ob_add_pick_nls(ob_ctx *ctx, int x, int label)
+{
+    CHECK_CTX(ctx);
+    if (x < 0) return ctx_fail(ctx, OB_E_BADID, "negative operand id");
+    const u32 in = (u32)x;
+    return add_one(ctx, OB_OP_PICK_NLS, &in, 1, -1, -1, label, 0, 0, nullptr);
+}
+
+int ob_add_sqnorm(ob_ctx *ctx, int x)
+{
+    CHECK_CTX(ctx);
+    if (x < 0) return ctx_fail(ctx, OB_E_BADID, "negative operand id");
+    const u32 in = (u32)x;
+    return add_one(ctx, OB_OP_SQNORM, &in, 1, -1, -1, 0, 0, 0, nullptr);
+}
+
+int ob_add_bulk(ob_ctx *ctx, int n, const uint8_t *op, const uint32_t *out_dim, const uint32_t *in_off,
+                const uint32_t *in_idx, const int32_t *param, const int32_t *bias, const int32_t *aux0,
+                const int32_t *aux1, const float *payload, size_t payload_len)
+{
+    CHECK_CTX(ctx);
+    if (n <= 0) return ctx_fail(ctx, OB_E_ARG, "n = %d", n);
+    if (!op || !out_dim || !in_off || !param || !bias || !aux0 || !aux1) return ctx_fail(ctx, OB_E_ARG, "null array");
+    if (ctx->n_sched) return ctx_fail(ctx, OB_E_STATE, "the graph was already evaluated; incremental forward is not built");
+    sync_used_flags(ctx);
+    const u32 n0 = (u32)ctx->op.size();
+    if ((u64)n0 + (u64)n >= 0x7ffffff0ull) return ctx_fail(ctx, OB_E_RANGE, "too many nodes");
+    if (in_off[0] != 0) return ctx_fail(ctx, OB_E_ARG, "in_off[0] must be 0");
+    // pass 1: validate everything against a scratch copy of the dimensions (nothing is appended on error)
+    std::vector<u32> dims(ctx->out_dim);
+    dims.reserve((size_t)n0 + n);
+    for (int i = 0; i < n; ++i) {
+        if (in_off[i + 1] < in_off[i]) return ctx_fail(ctx, OB_E_ARG, "in_off not monotone at %d", i);
+        const u32 ar = in_off[i + 1] - in_off[i];
+        if (ar && !in_idx) return ctx_fail(ctx, OB_E_ARG, "null in_idx");
+        u32 dim = 0;
+        u32 hint = 0;
+        if (op[i] == OB_OP_INPUT) {
+            hint = out_dim[i];
+            if (aux0[i] < 0 || (size_t)aux0[i] + out_dim[i] > payload_len || (!payload && out_dim[i]))
+                return ctx_fail(ctx, OB_E_RANGE, "INPUT payload of node %d outside the payload array", i);
+        }
+        if (int rc = validate_node(ctx, n0 + (u32)i, dims, op[i], in_idx + in_off[i], ar, param[i], bias[i], aux0[i],
+                                   aux1[i], &dim, hint))
+            return rc;
+        if (dim != out_dim[i]) return ctx_fail(ctx, OB_E_DIM, "node %d: out_dim %u but the operation implies %u", i, out_dim[i], dim);
+        dims.push_back(dim);
+    }
+    // pass 2: append
+    const u32 pay0 = (u32)ctx->payload.size();
+    if (payload_len) ctx->payload.insert(ctx->payload.end(), payload, payload + payload_len);
+    for (int i = 0; i < n; ++i) {
+        const u32 ar = in_off[i + 1] - in_off[i];
+        const int a0 = (op[i] == OB_OP_INPUT) ? (int)(pay0 + (u32)aux0[i]) : aux0[i];
+        append_node(ctx, op[i], in_idx + in_off[i], ar, param[i], bias[i], a0, aux1[i], out_dim[i]);
+    }
+    return (int)n0;
+}
+
+// ---- upload ---------------------------------------------------------------------------------------
+
+static int ensure_events(ob_ctx *ctx)
+{
+    if (ctx->ev_ok) return 0;
+    for (auto &e : ctx->ev) HIP_TRY(ctx, hipEventCreate(&e));
+    ctx->ev_ok = true;
+    return 0;
+}
+
+static int upload_param_tables(ob_ctx *ctx)
+{
+    // descriptor array + static tiles of the deferred parameter-gradient kernels (persistent region)
+    sync_used_flags(ctx);
+    ctx->wtiles.clear(); ctx->btiles.clear();
+    std::vector<ParamDesc> desc(ctx->params.size());
+    for (size_t p = 0; p < ctx->params.size(); ++p) {
+        const HostParam &hp = ctx->params[p];
+        desc[p].data = hp.data; desc[p].grad = hp.grad; desc[p].rows = hp.rows; desc[p].cols = hp.cols;
+        if (ctx->params_used_w[p])
+            for (int i0 = 0; i0 < hp.rows; i0 += GT)
+                for (int j0 = 0; j0 < hp.cols; j0 += GT) ctx->wtiles.push_back(PTile{(i32)p, i0, j0, 0});
+        if (ctx->params_used_b[p])
+            for (int i0 = 0; i0 < hp.rows; i0 += WG) ctx->btiles.push_back(PTile{(i32)p, i0, 0, 0});
+    }
+    ctx->params_dev = arena_array<ParamDesc>(ctx, desc.size() + 1);
+    ctx->wtiles_dev = arena_array<PTile>(ctx, ctx->wtiles.size() + 1);
+    ctx->btiles_dev = arena_array<PTile>(ctx, ctx->btiles.size() + 1);
+    if (!ctx->params_dev || !ctx->wtiles_dev || !ctx->btiles_dev) return ctx_fail(ctx, OB_E_OOM, "arena too small for parameter tables");
+    ctx->persist_top = ctx->top;
+    if (!desc.empty())
+        HIP_TRY(ctx, hipMemcpyAsync(ctx->params_dev, desc.data(), desc.size() * sizeof(ParamDesc), hipMemcpyHostToDevice, ctx->stream));
+    if (!ctx->wtiles.empty())
+        HIP_TRY(ctx, hipMemcpyAsync(ctx->wtiles_dev, ctx->wtiles.data(), ctx->wtiles.size() * sizeof(PTile), hipMemcpyHostToDevice, ctx->stream));
+    if (!ctx->btiles.empty())
+        HIP_TRY(ctx, hipMemcpyAsync(ctx->btiles_dev, ctx->btiles.data(), ctx->btiles.size() * sizeof(PTile), hipMemcpyHostToDevice, ctx->stream));
+    HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));   // the host vectors may change after return
+    ctx->params_dirty = false;
+    return 0;
+}
+
+int ob_upload(ob_ctx *ctx)
+{
+    CHECK_CTX(ctx);
+    if (ctx->uploaded) return OB_OK;
+    if (!ctx->arena) return ctx_fail(ctx, OB_E_STATE, "the context has no device arena");
+    if (ctx->op.empty()) return ctx_fail(ctx, OB_E_STATE, "empty graph");
+    if (ctx->n_sched) return ctx_fail(ctx, OB_E_STATE, "the graph was already evaluated; incremental forward is not built");
+    if (int rc = ensure_events(ctx)) return rc;
+    if (int rc = params_to_device(ctx)) return rc;
+    ctx->top = ctx->persist_top;
+    if (ctx->params_dirty)
+        if (int rc = upload_param_tables(ctx)) return rc;
+    if (!ctx->hdr_pinned) {
+        ctx->hdr_pinned_bytes = 1 << 16;
+        HIP_TRY(ctx, hipHostMalloc(&ctx->hdr_pinned, ctx->hdr_pinned_bytes, hipHostMallocDefault));
+    }
+
+    const size_t n = ctx->op.size(), E = ctx->in_idx.size(), P = ctx->payload.size();
+    // one packed image: op | out_dim | in_off | in_idx | param | bias | aux0 | aux1 | payload
+    size_t off[10];
+    size_t cur = 0;
+    const size_t sizes[9] = {n, n * 4, (n + 1) * 4, (E + 1) * 4, n * 4, n * 4, n * 4, n * 4, (P + 1) * 4};
+    for (int i = 0; i < 9; ++i) { off[i] = cur; cur += up256(sizes[i]); }
+    off[9] = cur;
+    if (cur > ctx->pinned_bytes) {
+        if (ctx->pinned) HIP_TRY(ctx, hipHostFree(ctx->pinned));
+        ctx->pinned = nullptr;
+        ctx->pinned_bytes = cur + cur / 2;
+        HIP_TRY(ctx, hipHostMalloc(&ctx->pinned, ctx->pinned_bytes, hipHostMallocDefault));
+    }
+    char *img = (char *)ctx->pinned;
+    memcpy(img + off[0], ctx->op.data(), n);
+    memcpy(img + off[1], ctx->out_dim.data(), n * 4);
+    memcpy(img + off[2], ctx->in_off.data(), (n + 1) * 4);
+    if (E) memcpy(img + off[3], ctx->in_idx.data(), E * 4);
+    memcpy(img + off[4], ctx->param.data(), n * 4);
+    memcpy(img + off[5], ctx->bias.data(), n * 4);
+    memcpy(img + off[6], ctx->aux0.data(), n * 4);
+    memcpy(img + off[7], ctx->aux1.data(), n * 4);
+    if (P) memcpy(img + off[8], ctx->payload.data(), P * 4);
+    char *dev = (char *)arena_alloc(ctx, cur);
+    if (!dev) return ctx_fail(ctx, OB_E_OOM, "arena too small for the graph (%zu bytes)", cur);
+    HIP_TRY(ctx, hipEventRecord(ctx->ev[0], ctx->stream));
+    HIP_TRY(ctx, hipMemcpyAsync(dev, img, cur, hipMemcpyHostToDevice, ctx->stream));
+    HIP_TRY(ctx, hipEventRecord(ctx->ev[1], ctx->stream));
+    Tables &T = ctx->T;
+    T = Tables{};
+    T.op = (const u8 *)(dev + off[0]); T.out_dim = (const u32 *)(dev + off[1]); T.in_off = (const u32 *)(dev + off[2]);
+    T.in_idx = (const u32 *)(dev + off[3]); T.param = (const i32 *)(dev + off[4]); T.bias = (const i32 *)(dev + off[5]);
+    T.aux0 = (const i32 *)(dev + off[6]); T.aux1 = (const i32 *)(dev + off[7]); T.payload = (const float *)(dev + off[8]);
+    T.params = ctx->params_dev;
+    T.n_params = (u32)ctx->params.size();
+    T.root = 0xffffffffu;
+    ctx->upload_bytes = cur;
+    ctx->graph_top = ctx->top;
+    ctx->uploaded = true;
+    return OB_OK;
+}
+
+// ---- execution ------------------------------------------------------------------------------------
+
+int ob_forward(ob_ctx *ctx, int node)
+{
+    CHECK_CTX(ctx);
+    if (node < 0 || node >= (int)ctx->op.size()) return ctx_fail(ctx, OB_E_BADID, "unknown node id %d", node);
+    if (ctx->n_sched) {
+        if ((u32)node < ctx->n_sched) return OB_OK;   // already evaluated
+        return ctx_fail(ctx, OB_E_STATE, "incremental forward (nodes beyond the evaluated prefix) is not built");
+    }
+    if (int rc = ob_upload(ctx)) return rc;
+    Tables &T = ctx->T;
+    T.n = (u32)node + 1;
+    T.E = ctx->in_off[T.n];
+    ctx->top = ctx->graph_top;
+    ctx->ms_graph = 0;
+    HIP_TRY(ctx, hipEventRecord(ctx->ev[7], ctx->stream));
+    if (int rc = sched_run(ctx)) return rc;
+    HIP_TRY(ctx, hipEventRecord(ctx->ev[2], ctx->stream));
+    if (int rc = exec_forward(ctx)) return rc;
+    HIP_TRY(ctx, hipEventRecord(ctx->ev[3], ctx->stream));
+    ctx->n_sched = T.n;
+    ctx->forward_done = true;
+    ctx->backward_done = false;
+    return OB_OK;
+}
+
+int ob_backward(ob_ctx *ctx, int node)
+{
+    CHECK_CTX(ctx);
+    if (!ctx->forward_done) return ctx_fail(ctx, OB_E_STATE, "ob_backward before ob_forward");
+    if (node < 0 || (u32)node >= ctx->n_sched) return ctx_fail(ctx, OB_E_BADID, "node %d was not evaluated", node);
+    if (ctx->out_dim[node] != 1) return ctx_fail(ctx, OB_E_NOTSCALAR, "node %d has %u elements", node, ctx->out_dim[node]);
+    ctx->T.root = (u32)node;
+    HIP_TRY(ctx, hipEventRecord(ctx->ev[4], ctx->stream));
+    if (int rc = exec_backward(ctx)) return rc;
+    HIP_TRY(ctx, hipEventRecord(ctx->ev[5], ctx->stream));
+    ctx->backward_done = true;
+    return OB_OK;
+}
+
+int ob_sync(ob_ctx *ctx)
+{
+    CHECK_CTX(ctx);
+    HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
+    return OB_OK;
+}
+
+// ---- reads ----------------------------------------------------------------------------------------
+
+static int node_read(ob_ctx *ctx, int node, float *out, size_t cap, bool grad)
+{
+    if (!out) return ctx_fail(ctx, OB_E_ARG, "null output");
+    if (!ctx->forward_done || (grad && !ctx->backward_done)) return ctx_fail(ctx, OB_E_STATE, "nothing to read yet");
+    if (node < 0 || (u32)node >= ctx->n_sched) return ctx_fail(ctx, OB_E_BADID, "node %d was not evaluated", node);
+    const u32 d = ctx->out_dim[node];
+    if (cap < d) return ctx_fail(ctx, OB_E_RANGE, "buffer holds %zu of %u elements", cap, d);
+    u32 off = 0;
+    HIP_TRY(ctx, hipMemcpyAsync(&off, ctx->T.val_off + node, 4, hipMemcpyDeviceToHost, ctx->stream));
+    HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
+    HIP_TRY(ctx, hipMemcpyAsync(out, (grad ? ctx->T.G : ctx->T.V) + off, (size_t)d * 4, hipMemcpyDeviceToHost, ctx->stream));
+    HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
+    return OB_OK;
+}
+
+int ob_value_read(ob_ctx *ctx, int node, float *host_out, size_t cap)
+{
+    CHECK_CTX(ctx);
+    return node_read(ctx, node, host_out, cap, false);
+}
+
+int ob_grad_read(ob_ctx *ctx, int node, float *host_out, size_t cap)
+{
+    CHECK_CTX(ctx);
+    return node_read(ctx, node, host_out, cap, true);
+}
+
+int ob_all_read(ob_ctx *ctx, int which, float *host_out, size_t cap)
+{
+    CHECK_CTX(ctx);
+    if (!host_out) return ctx_fail(ctx, OB_E_ARG, "null output");
+    if (!ctx->forward_done || (which && !ctx->backward_done)) return ctx_fail(ctx, OB_E_STATE, "nothing to read yet");
+    const u32 n = ctx->n_sched;
+    std::vector<u32> off((size_t)n + 1);
+    u64 tot = 0;
+    for (u32 v = 0; v < n; ++v) { off[v] = (u32)tot; tot += ctx->out_dim[v]; }
+    if (tot > 0xffffffffull) return ctx_fail(ctx, OB_E_RANGE, "too many elements");
+    if (cap < tot) return ctx_fail(ctx, OB_E_RANGE, "buffer holds %zu of %llu elements", cap, (unsigned long long)tot);
+    const size_t save = ctx->top;
+    u32 *off_dev = arena_array<u32>(ctx, (size_t)n + 1);
+    float *dst = arena_array<float>(ctx, tot + 1);
+    if (!off_dev || !dst) { ctx->top = save; return ctx_fail(ctx, OB_E_OOM, "arena too small for the read-back staging"); }
+    int rc = OB_OK;
+    do {
+        hipError_t e = hipMemcpyAsync(off_dev, off.data(), (size_t)n * 4, hipMemcpyHostToDevice, ctx->stream);
+        if (e == hipSuccess) e = exec_gather_all(ctx->T, which, dst, off_dev, ctx->stream);
+        if (e == hipSuccess) e = hipMemcpyAsync(host_out, dst, tot * 4, hipMemcpyDeviceToHost, ctx->stream);
+        if (e == hipSuccess) e = hipStreamSynchronize(ctx->stream);
+        if (e != hipSuccess) rc = ctx_fail(ctx, OB_E_HIP, "read-back failed: %s", hipGetErrorString(e));
+    } while (0);
+    ctx->top = save;
+    return rc;
+}
+
+int ob_schedule_read(ob_ctx *ctx, int *n_batches, int *batch_depth, uint64_t *batch_sig, int *batch_off, int *node_ids,
+                     size_t cap_batches, size_t cap_nodes)
+{
+    CHECK_CTX(ctx);
+    if (!ctx->forward_done) return ctx_fail(ctx, OB_E_STATE, "no schedule yet");
+    const u32 nb = ctx->hdr.n_batches, n = ctx->n_sched;
+    if (n_batches) *n_batches = (int)nb;
+    if (!batch_depth && !batch_sig && !batch_off && !node_ids) return OB_OK;
+    if (cap_batches < nb || cap_nodes < n) return ctx_fail(ctx, OB_E_RANGE, "schedule has %u batches, %u nodes", nb, n);
+    std::vector<BatchRec> recs(nb);
+    HIP_TRY(ctx, hipMemcpyAsync(recs.data(), ctx->T.batches, (size_t)nb * sizeof(BatchRec), hipMemcpyDeviceToHost, ctx->stream));
+    std::vector<u64> sig;
+    std::vector<u32> order(n);
+    HIP_TRY(ctx, hipMemcpyAsync(order.data(), ctx->T.order, (size_t)n * 4, hipMemcpyDeviceToHost, ctx->stream));
+    if (batch_sig) {
+        sig.resize(n);
+        HIP_TRY(ctx, hipMemcpyAsync(sig.data(), ctx->T.sig, (size_t)n * 8, hipMemcpyDeviceToHost, ctx->stream));
+    }
+    HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
+    for (u32 b = 0; b < nb; ++b) {
+        if (batch_depth) batch_depth[b] = (int)recs[b].step;
+        if (batch_off) batch_off[b] = (int)recs[b].pos0;
+        if (batch_sig) batch_sig[b] = sig[order[recs[b].pos0]];
+    }
+    if (batch_off) batch_off[nb] = (int)n;
+    if (node_ids) for (u32 p = 0; p < n; ++p) node_ids[p] = (int)order[p];
+    return OB_OK;
+}
+
+int ob_stats_read(ob_ctx *ctx, ob_stats *out)
+{
+    CHECK_CTX(ctx);
+    if (!out) return ctx_fail(ctx, OB_E_ARG, "null output");
+    memset(out, 0, sizeof *out);
+    out->n_nodes = (int32_t)ctx->op.size();
+    out->n_edges = (int32_t)ctx->in_idx.size();
+    if (!ctx->forward_done) return OB_OK;
+    HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
+    out->n_nodes = (int32_t)ctx->n_sched;
+    out->n_edges = (int32_t)ctx->T.E;
+    out->n_steps = (int32_t)ctx->hdr.n_steps;
+    out->n_batches = (int32_t)ctx->hdr.n_batches;
+    out->n_tiles_fwd = (int32_t)ctx->hdr.tiles_fwd;
+    out->n_tiles_bwd_pull = (int32_t)ctx->hdr.tiles_pull;
+    out->n_tiles_bwd_dx = (int32_t)ctx->hdr.tiles_dx;
+    out->n_param_uses = (int32_t)ctx->hdr.n_items;
+    out->n_launch_fwd = ctx->n_launch_fwd;
+    out->n_launch_bwd = ctx->n_launch_bwd;
+    out->n_launch_sched = ctx->n_launch_sched;
+    out->value_floats = ctx->hdr.val_floats;
+    out->grad_floats = ctx->hdr.grad_floats;
+    out->arena_used_bytes = ctx->top;
+    out->upload_bytes = ctx->upload_bytes;
+    (void)hipEventElapsedTime(&out->ms_upload, ctx->ev[0], ctx->ev[1]);
+    (void)hipEventElapsedTime(&out->ms_schedule, ctx->ev[7], ctx->ev[2]);
+    (void)hipEventElapsedTime(&out->ms_forward, ctx->ev[2], ctx->ev[3]);
+    if (ctx->backward_done) {
+        (void)hipEventElapsedTime(&out->ms_backward, ctx->ev[4], ctx->ev[5]);
+        (void)hipEventElapsedTime(&out->ms_param_grads, ctx->ev[6], ctx->ev[5]);
+    }
+    out->ms_graph_build = ctx->ms_graph;
+    (void)hipGetLastError();
+    return OB_OK;
+}
+
+int ob_debug_read(ob_ctx *ctx, int which, uint32_t *host_out, size_t cap_words, size_t *n_words)
+{
+    CHECK_CTX(ctx);
+    if (!ctx->forward_done) return ctx_fail(ctx, OB_E_STATE, "no schedule yet");
+    const Tables &T = ctx->T;
+    const void *src = nullptr;
+    size_t words = 0;
+    switch (which) {
+    case OB_DBG_DEPTH: src = T.step; words = T.n; break;
+    case OB_DBG_SIG: src = T.sig; words = (size_t)T.n * 2; break;
+    case OB_DBG_SUCC_OFF: src = T.succ_off; words = (size_t)T.n + 1; break;
+    case OB_DBG_SUCC_EDGE: src = T.succ_edge; words = T.E; break;
+    case OB_DBG_ORDER: src = T.order; words = T.n; break;
+    case OB_DBG_VAL_OFF: src = T.val_off; words = T.n; break;
+    default: return ctx_fail(ctx, OB_E_ARG, "unknown table %d", which);
+    }
+    if (n_words) *n_words = words;
+    if (!host_out) return OB_OK;
+    if (cap_words < words) return ctx_fail(ctx, OB_E_RANGE, "table has %zu words", words);
+    if (words) HIP_TRY(ctx, hipMemcpyAsync(host_out, src, words * 4, hipMemcpyDeviceToHost, ctx->stream));
+    HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
+    return OB_OK;
+}
+
+// ---- stand-alone primitives for tests ----------------------------------------------------------
+
+int ob_test_sort(ob_ctx *ctx, size_t n, const uint64_t *keys, const uint32_t *vals, int lo_bit, int n_bits,
+                 uint64_t *keys_out, uint32_t *vals_out)
+{
+    CHECK_CTX(ctx);
+    if (!ctx->arena) return ctx_fail(ctx, OB_E_STATE, "no arena");
+    if (n == 0) return OB_OK;
+    const size_t save = ctx->top;
+    u64 *ka = arena_array<u64>(ctx, n), *kb = arena_array<u64>(ctx, n);
+    u32 *va = arena_array<u32>(ctx, n), *vb = arena_array<u32>(ctx, n);
+    void *scratch = arena_alloc(ctx, prim_sort_scratch_bytes(n));
+    int rc = OB_OK;
+    if (!ka || !kb || !va || !vb || !scratch) rc = ctx_fail(ctx, OB_E_OOM, "arena too small");
+    if (rc == OB_OK) {
+        hipError_t e = hipMemcpyAsync(ka, keys, n * 8, hipMemcpyHostToDevice, ctx->stream);
+        if (e == hipSuccess) e = hipMemcpyAsync(va, vals, n * 4, hipMemcpyHostToDevice, ctx->stream);
+        if (e == hipSuccess) e = prim_sort_pairs(ka, va, kb, vb, n, lo_bit, n_bits, scratch, ctx->stream, nullptr);
+        if (e == hipSuccess) e = hipMemcpyAsync(keys_out, ka, n * 8, hipMemcpyDeviceToHost, ctx->stream);
+        if (e == hipSuccess) e = hipMemcpyAsync(vals_out, va, n * 4, hipMemcpyDeviceToHost, ctx->stream);
+        if (e == hipSuccess) e = hipStreamSynchronize(ctx->stream);
+        if (e != hipSuccess) rc = ctx_fail(ctx, OB_E_HIP, "sort failed: %s", hipGetErrorString(e));
+    }
+    ctx->top = save;
+    return rc;
+}
+
+int ob_test_scan(ob_ctx *ctx, size_t n, const uint32_t *in, uint32_t *out_exclusive, uint32_t *total)
+{
+    CHECK_CTX(ctx);
+    if (!ctx->arena) return ctx_fail(ctx, OB_E_STATE, "no arena");
+    const size_t save = ctx->top;
+    u32 *a = arena_array<u32>(ctx, n + 1), *b = arena_array<u32>(ctx, n + 1), *t = arena_array<u32>(ctx, 1);
+    void *scratch = arena_alloc(ctx, prim_scan_scratch_bytes(n + 1, 4));
+    int rc = OB_OK;
+    if (!a || !b || !t || !scratch) rc = ctx_fail(ctx, OB_E_OOM, "arena too small");
+    if (rc == OB_OK) {
+        hipError_t e = n ? hipMemcpyAsync(a, in, n * 4, hipMemcpyHostToDevice, ctx->stream) : hipSuccess;
+        if (e == hipSuccess) e = prim_scan_u32(a, b, n, t, scratch, ctx->stream);
+        if (e == hipSuccess && n) e = hipMemcpyAsync(out_exclusive, b, n * 4, hipMemcpyDeviceToHost, ctx->stream);
+        if (e == hipSuccess) e = hipMemcpyAsync(total, t, 4, hipMemcpyDeviceToHost, ctx->stream);
+        if (e == hipSuccess) e = hipStreamSynchronize(ctx->stream);
+        if (e != hipSuccess) rc = ctx_fail(ctx, OB_E_HIP, "scan failed: %s", hipGetErrorString(e));
+    }
+    ctx->top = save;
+    return rc;
+}
+
+int ob_test_gemm(ob_ctx *ctx, int M, int N, int K, const float *A, const float *B, float *C)
+{
+    CHECK_CTX(ctx);
+    if (!ctx->arena) return ctx_fail(ctx, OB_E_STATE, "no arena");
+    if (M <= 0 || N <= 0 || K <= 0) return ctx_fail(ctx, OB_E_ARG, "bad shape");
+    const size_t save = ctx->top;
+    float *a = arena_array<float>(ctx, (size_t)M * K), *b = arena_array<float>(ctx, (size_t)N * K);
+    float *c = arena_array<float>(ctx, (size_t)M * N);
+    int rc = OB_OK;
+    if (!a || !b || !c) rc = ctx_fail(ctx, OB_E_OOM, "arena too small");
+    if (rc == OB_OK) {
+        hipError_t e = hipMemcpyAsync(a, A, (size_t)M * K * 4, hipMemcpyHostToDevice, ctx->stream);
+        if (e == hipSuccess) e = hipMemcpyAsync(b, B, (size_t)N * K * 4, hipMemcpyHostToDevice, ctx->stream);
+        if (e == hipSuccess) e = exec_test_gemm(M, N, K, a, b, c, ctx->stream);
+        if (e == hipSuccess) e = hipMemcpyAsync(C, c, (size_t)M * N * 4, hipMemcpyDeviceToHost, ctx->stream);
+        if (e == hipSuccess) e = hipStreamSynchronize(ctx->stream);
+        if (e != hipSuccess) rc = ctx_fail(ctx, OB_E_HIP, "gemm failed: %s", hipGetErrorString(e));
+    }
+    ctx->top = save;
+    return rc;
+}
+
+}  // extern "C"

@@ -1,0 +1,93 @@
+// Host-side context of the library (not part of the ABI).
+#pragma once
+
+#include <string>
+#include <vector>
+
+#include "ob_internal.h"
+
+struct HostParam {
+    int rows, cols;
+    float *data;   // device, inside the arena
+    float *grad;   // device, inside the arena
+};
+
+struct ob_ctx {
+    // caller-owned resources
+    char *arena = nullptr;
+    size_t arena_bytes = 0;
+    hipStream_t stream = nullptr;
+    int mode = 1;      // OB_BYDEPTH
+    int launch = 0;    // OB_LAUNCH_STREAM
+    std::string err;
+
+    // arena bump allocator: [0, persist_top) parameters; [persist_top, top) current graph
+    size_t persist_top = 0;
+    size_t top = 0;
+
+    // parameters
+    std::vector<HostParam> params;
+    ParamDesc *params_dev = nullptr;   // in arena, uploaded lazily
+    bool params_dirty = true;
+    bool params_frozen = false;        // set by the first graph upload
+    std::vector<PTile> wtiles, btiles; // static tiles of the deferred dW / db kernels
+    PTile *wtiles_dev = nullptr, *btiles_dev = nullptr;
+    int max_param_rows = 1;
+    std::vector<std::vector<float>> pending;      // host copies of parameter data not yet on the device
+    std::vector<u8> params_used_w, params_used_b; // parameter appeared as a MATVEC matrix / bias
+
+    // host graph store (pinned staging is allocated on upload)
+    std::vector<u8> op;
+    std::vector<u32> out_dim, in_off, in_idx;
+    std::vector<i32> param, bias, aux0, aux1;
+    std::vector<float> payload;
+    std::vector<u32> items_upto;       // parameter-use items among nodes [0, v]
+    u64 sum_out_dim = 0;               // bounds the tile lists
+    u64 sum_mv_k = 0;                  // sum of matrix columns over MATVEC nodes (bounds the dX tiles)
+    size_t graph_top = 0;              // arena top right after the uploaded graph image
+
+    // device state of the current graph
+    void *pinned = nullptr;
+    size_t pinned_bytes = 0;
+    bool uploaded = false;
+    u32 n_sched = 0;                   // nodes covered by the last schedule (0 = none)
+    bool forward_done = false, backward_done = false;
+    Tables T{};
+    SchedHeader hdr{};
+    std::vector<u32> step_tf, step_ta, step_tb, step_first;   // host mirrors (n_steps + 1 each)
+    void *scratch = nullptr;           // scan / sort scratch in the arena
+    u64 *key_a = nullptr, *key_b = nullptr;
+    u32 *val_a = nullptr, *val_b = nullptr;
+    u32 *tmp_u32_a = nullptr, *tmp_u32_b = nullptr;   // n+1 words each
+    Lay *lay_in = nullptr, *lay_total = nullptr;
+    u32 *scalars = nullptr;            // small device scalars
+    void *hdr_pinned = nullptr;        // pinned host mirror for the header + step tables
+    size_t hdr_pinned_bytes = 0;
+
+    // events / stats
+    hipEvent_t ev[8] = {};
+    bool ev_ok = false;
+    float ms_upload = 0, ms_schedule = 0, ms_forward = 0, ms_backward = 0, ms_param_grads = 0, ms_graph = 0;
+    int n_launch_fwd = 0, n_launch_bwd = 0, n_launch_sched = 0;
+    size_t upload_bytes = 0;
+
+    // hipGraph of the per-step launches (rebuilt per schedule)
+    hipGraph_t graph_fwd = nullptr, graph_bwd = nullptr;
+    hipGraphExec_t gexec_fwd = nullptr, gexec_bwd = nullptr;
+};
+
+int ctx_fail(ob_ctx *ctx, int code, const char *fmt, ...);
+#define HIP_TRY(ctx, expr)                                                                   \
+    do {                                                                                     \
+        hipError_t _e = (expr);                                                              \
+        if (_e != hipSuccess)                                                                \
+            return ctx_fail((ctx), -7, "%s failed: %s (%s:%d)", #expr, hipGetErrorString(_e), \
+                            __FILE__, __LINE__);                                             \
+    } while (0)
+
+// Bump allocation inside the caller's arena (256-byte aligned); nullptr when it does not fit.
+void *arena_alloc(ob_ctx *ctx, size_t bytes);
+template <typename T> inline T *arena_array(ob_ctx *ctx, size_t count)
+{
+    return (T *)arena_alloc(ctx, count * sizeof(T));
+}

@@ -1,0 +1,622 @@
+// Batched execution (Section 3.3): every batch of the schedule runs as one batched operation.
+// A step (= one depth level, or one node when batching is off) is one launch of a tile
+// interpreter: each workgroup takes tiles of the step's batches and runs the matching routine.
+//  - shared-weight matrix-vector groups W h_i become one W H product on fp32 MFMA, operand rows
+//    gathered through the batch's row-offset list (the sparse-to-dense copy of Appendix B is
+//    fused into the operand load), results written to the batch's contiguous block (so the
+//    dense-to-sparse copy is the identity);
+//  - component-wise groups, slices, concatenations and lookups are gathers fused with the op;
+//  - log-softmax picks, squared norms and wide sums are per-row wavefront reductions.
+// Backward mirrors it in reverse step order without atomics: a node's gradient is the sum, in
+// fixed (consumer, slot) order, of what each consumer edge contributes ("pull"), and the
+// weight, bias and embedding gradients are reduced once per parameter over all their uses.
+#include "ob_ctx.h"
+
+#include <chrono>
+
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+
+namespace {
+
+__device__ inline float4 ld4(const float *p) { return *reinterpret_cast<const float4 *>(p); }
+__device__ inline void st4(float *p, float4 v) { *reinterpret_cast<float4 *>(p) = v; }
+__device__ inline float sigmoidf_(float x) { return 1.0f / (1.0f + expf(-x)); }
+
+__device__ inline float wave_sum(float v)
+{
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
+    return v;
+}
+__device__ inline float wave_max(float v)
+{
+    for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o));
+    return v;
+}
+
+// ------------------------------------------------------------------------------------------------
+// forward: component-wise / copy family
+// ------------------------------------------------------------------------------------------------
+__device__ inline float ew_value(const Tables &T, const BatchRec &r, u32 row, u32 col)
+{
+    const u32 *opnd = T.opnd_off + r.opnd;
+    switch (r.op) {
+    case OP_INPUT: return T.payload[T.s_aux0[r.pos0 + row] + col];
+    case OP_LOOKUP: {
+        const ParamDesc P = T.params[r.param];
+        return P.data[(size_t)T.s_aux0[r.pos0 + row] * P.cols + col];
+    }
+    case OP_ADD: {
+        float acc = 0.f;
+        for (u32 j = 0; j < r.arity; ++j) acc += T.V[opnd[j * r.B + row] + col];
+        return acc;
+    }
+    case OP_CMULT: return T.V[opnd[row] + col] * T.V[opnd[r.B + row] + col];
+    case OP_TANH: return tanhf(T.V[opnd[row] + col]);
+    case OP_SIGMOID: return sigmoidf_(T.V[opnd[row] + col]);
+    case OP_SLICE: return T.V[opnd[row] + (u32)r.aux0 + col];
+    case OP_CONCAT: {
+        u32 c = col;
+        for (u32 j = 0; j < r.arity; ++j) {
+            const u32 dj = T.b_indim[r.indim + j];
+            if (c < dj) return T.V[opnd[j * r.B + row] + c];
+            c -= dj;
+        }
+        return 0.f;
+    }
+    default: return 0.f;
+    }
+}
+
+__device__ inline float4 ew_value4(const Tables &T, const BatchRec &r, u32 row, u32 col)
+{
+    const u32 *opnd = T.opnd_off + r.opnd;
+    switch (r.op) {
+    case OP_INPUT: return ld4(T.payload + T.s_aux0[r.pos0 + row] + col);
+    case OP_LOOKUP: {
+        const ParamDesc P = T.params[r.param];
+        return ld4(P.data + (size_t)T.s_aux0[r.pos0 + row] * P.cols + col);
+    }
+    case OP_ADD: {
+        float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+        for (u32 j = 0; j < r.arity; ++j) {
+            const float4 x = ld4(T.V + opnd[j * r.B + row] + col);
+            acc.x += x.x; acc.y += x.y; acc.z += x.z; acc.w += x.w;
+        }
+        return acc;
+    }
+    case OP_CMULT: {
+        const float4 a = ld4(T.V + opnd[row] + col), b = ld4(T.V + opnd[r.B + row] + col);
+        return make_float4(a.x * b.x, a.y * b.y, a.z * b.z, a.w * b.w);
+    }
+    case OP_TANH: {
+        const float4 a = ld4(T.V + opnd[row] + col);
+        return make_float4(tanhf(a.x), tanhf(a.y), tanhf(a.z), tanhf(a.w));
+    }
+    case OP_SIGMOID: {
+        const float4 a = ld4(T.V + opnd[row] + col);
+        return make_float4(sigmoidf_(a.x), sigmoidf_(a.y), sigmoidf_(a.z), sigmoidf_(a.w));
+    }
+    case OP_SLICE: return ld4(T.V + opnd[row] + (u32)r.aux0 + col);
+    case OP_CONCAT: {
+        u32 c = col;
+        for (u32 j = 0; j < r.arity; ++j) {
+            const u32 dj = T.b_indim[r.indim + j];
+            if (c < dj) return ld4(T.V + opnd[j * r.B + row] + c);
+            c -= dj;
+        }
+        return make_float4(0.f, 0.f, 0.f, 0.f);
+    }
+    default: return make_float4(0.f, 0.f, 0.f, 0.f);
+    }
+}
+
+__device__ inline void ew_fwd_tile(const Tables &T, const BatchRec &r, u32 t)
+{
+    const u32 total = r.B * r.d;
+    float *out = T.V + r.val_off;
+    if (r.vec4 & 1u) {
+        const u32 e = t * EW_TILE + threadIdx.x * 4;
+        if (e < total) st4(out + e, ew_value4(T, r, e / r.d, e % r.d));
+    } else {
+        for (int i = 0; i < EW_TILE / WG; ++i) {
+            const u32 e = t * EW_TILE + i * WG + threadIdx.x;
+            if (e < total) out[e] = ew_value(T, r, e / r.d, e % r.d);
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
+// forward: per-row reductions (one wave per row)
+// ------------------------------------------------------------------------------------------------
+__device__ inline void red_fwd_tile(const Tables &T, const BatchRec &r, u32 t)
+{
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    const u32 row = t * ROWS_PER_RED_TILE + w;
+    if (row >= r.B) return;
+    const float *x = T.V + T.opnd_off[r.opnd + row];
+    const u32 K = r.k;
+    if (r.op == OP_SQNORM) {
+        float acc = 0.f;
+        for (u32 c = lane; c < K; c += 64) { const float a = x[c]; acc += a * a; }
+        acc = wave_sum(acc);
+        if (lane == 0) T.V[r.val_off + row] = acc;
+    } else {  // OP_PICK_NLS: logsumexp(x) - x[label], shifted by the row maximum
+        float mx = -INFINITY;
+        for (u32 c = lane; c < K; c += 64) mx = fmaxf(mx, x[c]);
+        mx = wave_max(mx);
+        float s = 0.f;
+        for (u32 c = lane; c < K; c += 64) s += expf(x[c] - mx);
+        s = wave_sum(s);
+        if (lane == 0) T.V[r.val_off + row] = mx + logf(s) - x[T.s_aux0[r.pos0 + row]];
+    }
+}
+
+// wide sum: one workgroup per row, operands strided over threads, fixed-shape tree in LDS
+__device__ inline void wide_add_tile(const Tables &T, const BatchRec &r, u32 row, float *lds)
+{
+    const u32 *opnd = T.opnd_off + r.opnd;
+    for (u32 c = 0; c < r.d; ++c) {
+        float acc = 0.f;
+        for (u32 j = threadIdx.x; j < r.arity; j += WG) acc += T.V[opnd[j * r.B + row] + c];
+        lds[threadIdx.x] = acc;
+        __syncthreads();
+        for (int o = WG / 2; o > 0; o >>= 1) {
+            if ((int)threadIdx.x < o) lds[threadIdx.x] += lds[threadIdx.x + o];
+            __syncthreads();
+        }
+        if (threadIdx.x == 0) T.V[r.val_off + row * r.d + c] = lds[0];
+        __syncthreads();
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
+// MFMA tile: one 32x32 fp32 accumulator block per workgroup; the 4 waves split the contraction
+// and their partial blocks are summed through LDS in wave order.
+// v_mfma_f32_32x32x2f32: lane l supplies A[l%32][l/32] and B[l/32][l%32]; accumulator register v
+// of lane l is C[8*(v/4) + 4*(l/32) + v%4][l%32].
+// ------------------------------------------------------------------------------------------------
+__device__ inline floatx16 mfma4(float4 a, float4 b, floatx16 acc)
+{
+    acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a.x, b.x, acc, 0, 0, 0);
+    acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a.y, b.y, acc, 0, 0, 0);
+    acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a.z, b.z, acc, 0, 0, 0);
+    acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a.w, b.w, acc, 0, 0, 0);
+    return acc;
+}
+
+// Sums the four waves' accumulators; on return wave w holds in out[0..3] the rows
+// 8w + 4*(lane/32) + 0..3 of column lane%32.
+__device__ inline void reduce_waves(const floatx16 &acc, float *lds, float out[4])
+{
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    for (int v = 0; v < 16; ++v) lds[(w * 16 + v) * 64 + lane] = acc[v];
+    __syncthreads();
+    for (int i = 0; i < 4; ++i) {
+        const int v = 4 * w + i;
+        float s = lds[(0 * 16 + v) * 64 + lane];
+        s += lds[(1 * 16 + v) * 64 + lane];
+        s += lds[(2 * 16 + v) * 64 + lane];
+        s += lds[(3 * 16 + v) * 64 + lane];
+        out[i] = s;
+    }
+    __syncthreads();
+}
+
+// split [0, total) in units of 8 over the 4 waves
+__device__ inline void wave_range(u32 total, u32 &lo, u32 &hi)
+{
+    const u32 w = threadIdx.x >> 6;
+    const u32 n8 = (total + 7) / 8;
+    const u32 per = (n8 + 3) / 4;
+    lo = w * per * 8;
+    hi = (w + 1) * per * 8;
+    const u32 pad = n8 * 8;
+    if (lo > pad) lo = pad;
+    if (hi > pad) hi = pad;
+}
+
+// Y[B x m] = X[B x K] W^T + b.   X rows gathered by offset `xoff(row)`, W row-major [m x K].
+template <typename XOff>
+__device__ inline void gemm_nt_tile(const float *Xbase, XOff xoff, u32 B, const float *W, const float *bias, u32 m,
+                                    u32 K, bool fast, float *Y, u32 r0, u32 i0, float *lds)
+{
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    const u32 l32 = lane & 31, h = lane >> 5;
+    const u32 row = r0 + l32, col = i0 + l32;
+    const bool row_ok = row < B, col_ok = col < m;
+    const float *xrow = Xbase + (row_ok ? xoff(row) : 0u);
+    const float *wrow = W + (size_t)(col_ok ? col : 0u) * K;
+    u32 lo, hi;
+    wave_range(K, lo, hi);
+    floatx16 acc = {0.f};
+    for (int v = 0; v < 16; ++v) acc[v] = 0.f;
+    for (u32 kb = lo; kb < hi; kb += 8) {
+        const u32 k0 = kb + 4 * h;
+        float4 a = make_float4(0.f, 0.f, 0.f, 0.f), b = a;
+        if (fast) {
+            if (k0 < K) {
+                if (row_ok) a = ld4(xrow + k0);
+                if (col_ok) b = ld4(wrow + k0);
+            }
+        } else {
+            float av[4] = {0.f, 0.f, 0.f, 0.f}, bv[4] = {0.f, 0.f, 0.f, 0.f};
+            for (int s = 0; s < 4; ++s)
+                if (k0 + s < K) {
+                    if (row_ok) av[s] = xrow[k0 + s];
+                    if (col_ok) bv[s] = wrow[k0 + s];
+                }
+            a = make_float4(av[0], av[1], av[2], av[3]);
+            b = make_float4(bv[0], bv[1], bv[2], bv[3]);
+        }
+        acc = mfma4(a, b, acc);
+    }
+    float out[4];
+    reduce_waves(acc, lds, out);
+    if (col_ok) {
+        const float bb = bias ? bias[col] : 0.f;
+        for (int i = 0; i < 4; ++i) {
+            const u32 rr = r0 + 8 * w + 4 * h + i;
+            if (rr < B) Y[(size_t)rr * m + col] = out[i] + bb;
+        }
+    }
+}
+
+__device__ inline void matvec_fwd_tile(const Tables &T, const BatchRec &r, u32 t, float *lds)
+{
+    const u32 ntn = (r.d + GT - 1) / GT;
+    const u32 r0 = (t / ntn) * GT, i0 = (t % ntn) * GT;
+    const ParamDesc P = T.params[r.param];
+    const float *bias = r.bias >= 0 ? T.params[r.bias].data : nullptr;
+    const u32 *opnd = T.opnd_off + r.opnd;
+    const bool fast = (r.vec4 & 2u) && (r.k & 3u) == 0;
+    gemm_nt_tile(T.V, [opnd](u32 row) { return opnd[row]; }, r.B, P.data, bias, r.d, r.k, fast, T.V + r.val_off, r0,
+                 i0, lds);
+}
+
+// dX[B x K] = G[B x m] W, contraction over m.  G rows are the batch's own contiguous block.
+__device__ inline void matvec_dx_tile(const Tables &T, const BatchRec &r, u32 t, float *lds)
+{
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    const u32 l32 = lane & 31, h = lane >> 5;
+    const u32 K = r.k, m = r.d;
+    const u32 ntn = (K + GT - 1) / GT;
+    const u32 r0 = (t / ntn) * GT, c0 = (t % ntn) * GT;
+    const ParamDesc P = T.params[r.param];
+    const u32 row = r0 + l32, col = c0 + l32;
+    const bool row_ok = row < r.B, col_ok = col < K;
+    const float *grow = T.G + r.val_off + (size_t)(row_ok ? row : 0u) * m;
+    const float *wcol = P.data + (col_ok ? col : 0u);
+    const bool fast = (m & 3u) == 0;
+    u32 lo, hi;
+    wave_range(m, lo, hi);
+    floatx16 acc;
+    for (int v = 0; v < 16; ++v) acc[v] = 0.f;
+    for (u32 ib = lo; ib < hi; ib += 8) {
+        const u32 i0 = ib + 4 * h;
+        float av[4] = {0.f, 0.f, 0.f, 0.f}, bv[4] = {0.f, 0.f, 0.f, 0.f};
+        if (fast) {
+            if (i0 < m && row_ok) { const float4 a = ld4(grow + i0); av[0] = a.x; av[1] = a.y; av[2] = a.z; av[3] = a.w; }
+        } else {
+            for (int s = 0; s < 4; ++s) if (i0 + s < m && row_ok) av[s] = grow[i0 + s];
+        }
+        for (int s = 0; s < 4; ++s) if (i0 + s < m && col_ok) bv[s] = wcol[(size_t)(i0 + s) * K];
+        acc = mfma4(make_float4(av[0], av[1], av[2], av[3]), make_float4(bv[0], bv[1], bv[2], bv[3]), acc);
+    }
+    float out[4];
+    reduce_waves(acc, lds, out);
+    if (col_ok) {
+        float *dX = T.G + r.dx_off;
+        for (int i = 0; i < 4; ++i) {
+            const u32 rr = r0 + 8 * w + 4 * h + i;
+            if (rr < r.B) dX[(size_t)rr * K + col] = out[i];
+        }
+    }
+}
+
+// dW[m x K] += sum over uses of g x^T (deferred: once per parameter over every use in the graph)
+__device__ inline void param_w_tile(const Tables &T, const PTile &pt, float *lds)
+{
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    const u32 l32 = lane & 31, h = lane >> 5;
+    const u32 slot = (u32)pt.param * 4u;
+    const u32 start = T.pu_start[slot], end = T.pu_end[slot];
+    if (start == end) return;
+    const ParamDesc P = T.params[pt.param];
+    const u32 m = (u32)P.rows, K = (u32)P.cols;
+    const u32 i = (u32)pt.i0 + l32, j = (u32)pt.j0 + l32;
+    const bool i_ok = i < m, j_ok = j < K;
+    u32 lo, hi;
+    wave_range(end - start, lo, hi);
+    floatx16 acc;
+    for (int v = 0; v < 16; ++v) acc[v] = 0.f;
+    for (u32 ib = lo; ib < hi; ib += 8) {
+        float av[4], bv[4];
+        for (int s = 0; s < 4; ++s) {
+            const u32 it = start + ib + 4 * h + s;
+            const bool ok = it < end;
+            av[s] = (ok && i_ok) ? T.G[T.it_goff[it] + i] : 0.f;
+            bv[s] = (ok && j_ok) ? T.V[T.it_xoff[it] + j] : 0.f;
+        }
+        acc = mfma4(make_float4(av[0], av[1], av[2], av[3]), make_float4(bv[0], bv[1], bv[2], bv[3]), acc);
+    }
+    float out[4];
+    reduce_waves(acc, lds, out);
+    if (j_ok) {
+        for (int q = 0; q < 4; ++q) {
+            const u32 rr = (u32)pt.i0 + 8 * w + 4 * h + q;
+            if (rr < m) P.grad[(size_t)rr * K + j] += out[q];
+        }
+    }
+}
+
+// db[i] += sum over uses of g[i]; one thread per row, uses in sorted order
+__device__ inline void param_b_tile(const Tables &T, const PTile &pt)
+{
+    const u32 slot = (u32)pt.param * 4u + 1u;
+    const u32 start = T.pu_start[slot], end = T.pu_end[slot];
+    if (start == end) return;
+    const ParamDesc P = T.params[pt.param];
+    const u32 i = (u32)pt.i0 + threadIdx.x;
+    if (i >= (u32)P.rows) return;
+    float acc = 0.f;
+    for (u32 it = start; it < end; ++it) acc += T.G[T.it_goff[it] + i];
+    P.grad[i] += acc;
+}
+
+// ------------------------------------------------------------------------------------------------
+// backward pull: gradient of every node of a batch from its consumer edges
+// ------------------------------------------------------------------------------------------------
+__device__ inline void pull_tile(const Tables &T, const BatchRec &r, u32 t)
+{
+    const u32 total = r.B * r.d;
+    for (int i = 0; i < EW_TILE / WG; ++i) {
+        const u32 e = t * EW_TILE + i * WG + threadIdx.x;
+        if (e >= total) continue;
+        const u32 row = e / r.d, col = e % r.d;
+        const u32 u = T.order[r.pos0 + row];
+        const u32 q1 = T.succ_off[u + 1];
+        const u32 own = r.val_off + row * r.d;
+        float acc = (u == T.root) ? 1.0f : 0.0f;
+        for (u32 q = T.succ_off[u]; q < q1; ++q) {
+            const EdgeRec er = T.edges[q];
+            switch (er.kind) {
+            case EK_PLAIN: acc += T.G[er.goff + col]; break;
+            case EK_RANGE:
+                if ((i32)col >= er.a0 && (i32)col < er.a1) acc += T.G[er.goff + col - (u32)er.a0];
+                break;
+            case EK_MUL: acc += T.G[er.goff + col] * T.V[er.voff + col]; break;
+            case EK_DTANH: { const float y = T.V[er.voff + col]; acc += T.G[er.goff + col] * (1.0f - y * y); break; }
+            case EK_DSIGM: { const float y = T.V[er.voff + col]; acc += T.G[er.goff + col] * y * (1.0f - y); break; }
+            case EK_NLS: {
+                const float lse = T.V[er.voff] + T.V[own + (u32)er.a0];
+                float p = expf(T.V[own + col] - lse);
+                if ((i32)col == er.a0) p -= 1.0f;
+                acc += T.G[er.goff] * p;
+                break;
+            }
+            case EK_SQN: acc += 2.0f * T.G[er.goff] * T.V[own + col]; break;
+            default: break;
+            }
+        }
+        T.G[own + col] = acc;
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
+// kernels
+// ------------------------------------------------------------------------------------------------
+constexpr int LDS_FLOATS = 4 * 16 * 64;   // 16 KB: the four waves' accumulator blocks
+
+__global__ __launch_bounds__(WG) void k_fwd_step(Tables T, u32 tile_lo, u32 tile_hi)
+{
+    __shared__ float lds[LDS_FLOATS];
+    for (u32 tile = tile_lo + blockIdx.x; tile < tile_hi; tile += gridDim.x) {
+        const TileRec tr = T.tiles_f[tile];
+        const BatchRec r = T.batches[tr.batch];
+        switch (r.op) {
+        case OP_MATVEC: matvec_fwd_tile(T, r, tr.t, lds); break;
+        case OP_PICK_NLS:
+        case OP_SQNORM: red_fwd_tile(T, r, tr.t); break;
+        case OP_ADD:
+            if (r.arity >= (u32)WIDE_ADD_ARITY) { wide_add_tile(T, r, tr.t, lds); break; }
+            ew_fwd_tile(T, r, tr.t);
+            break;
+        default: ew_fwd_tile(T, r, tr.t); break;
+        }
+    }
+}
+
+__global__ __launch_bounds__(WG) void k_bwd_pull_step(Tables T, u32 tile_lo, u32 tile_hi)
+{
+    for (u32 tile = tile_lo + blockIdx.x; tile < tile_hi; tile += gridDim.x) {
+        const TileRec tr = T.tiles_a[tile];
+        const BatchRec r = T.batches[tr.batch];
+        pull_tile(T, r, tr.t);
+    }
+}
+
+__global__ __launch_bounds__(WG) void k_bwd_dx_step(Tables T, u32 tile_lo, u32 tile_hi)
+{
+    __shared__ float lds[LDS_FLOATS];
+    for (u32 tile = tile_lo + blockIdx.x; tile < tile_hi; tile += gridDim.x) {
+        const TileRec tr = T.tiles_b[tile];
+        const BatchRec r = T.batches[tr.batch];
+        matvec_dx_tile(T, r, tr.t, lds);
+    }
+}
+
+__global__ __launch_bounds__(WG) void k_param_w(Tables T, const PTile *tiles)
+{
+    __shared__ float lds[LDS_FLOATS];
+    param_w_tile(T, tiles[blockIdx.x], lds);
+}
+
+__global__ __launch_bounds__(WG) void k_param_b(Tables T, const PTile *tiles)
+{
+    param_b_tile(T, tiles[blockIdx.x]);
+}
+
+// dE[row, :] += sum of the gradients of every LOOKUP of (table, row): one wave per run of equal
+// keys in the sorted item list, rows summed in sorted (= schedule) order
+__global__ __launch_bounds__(WG) void k_param_e(Tables T, u32 n_items)
+{
+    const int lane = threadIdx.x & 63;
+    const u32 wave = (blockIdx.x * WG + threadIdx.x) >> 6;
+    const u32 n_waves = (gridDim.x * WG) >> 6;
+    for (u32 i = wave; i < n_items; i += n_waves) {
+        const u64 k = T.it_key[i];
+        const u32 slot = (u32)(k >> 32);
+        if ((slot & 3u) != 2u) continue;
+        if (i > 0 && T.it_key[i - 1] == k) continue;
+        const ParamDesc P = T.params[slot >> 2];
+        const u32 rowi = (u32)k;
+        u32 end = i + 1;
+        while (end < n_items && T.it_key[end] == k) ++end;
+        for (u32 c = lane; c < (u32)P.cols; c += 64) {
+            float acc = 0.f;
+            for (u32 it = i; it < end; ++it) acc += T.G[T.it_goff[it] + c];
+            P.grad[(size_t)rowi * P.cols + c] += acc;
+        }
+    }
+}
+
+__global__ void k_gather_all(Tables T, const float *src, float *dst, const u32 *dst_off)
+{
+    const u32 v = blockIdx.x;
+    const u32 d = T.out_dim[v];
+    const float *s = src + T.val_off[v];
+    float *o = dst + dst_off[v];
+    for (u32 c = threadIdx.x; c < d; c += blockDim.x) o[c] = s[c];
+}
+
+__global__ __launch_bounds__(WG) void k_test_gemm(const float *A, const float *Bm, float *C, int M, int N, int K)
+{
+    __shared__ float lds[LDS_FLOATS];
+    const u32 ntn = (N + GT - 1) / GT;
+    const u32 r0 = (blockIdx.x / ntn) * GT, i0 = (blockIdx.x % ntn) * GT;
+    const u32 Ku = (u32)K;
+    gemm_nt_tile(A, [Ku](u32 row) { return row * Ku; }, (u32)M, Bm, nullptr, (u32)N, Ku, (Ku & 3u) == 0, C, r0, i0, lds);
+}
+
+inline u32 grid_for(u32 tiles, u32 cap) { return tiles < cap ? tiles : cap; }
+constexpr u32 GRID_CAP = 4096;
+
+}  // namespace
+
+// ---- host side -----------------------------------------------------------------------------------
+
+static int launch_forward_steps(ob_ctx *ctx)
+{
+    const Tables &T = ctx->T;
+    hipStream_t s = ctx->stream;
+    const u32 ns = ctx->hdr.n_steps;
+    for (u32 st = 0; st < ns; ++st) {
+        const u32 lo = ctx->step_tf[st], hi = ctx->step_tf[st + 1];
+        if (hi > lo) {
+            hipLaunchKernelGGL(k_fwd_step, dim3(grid_for(hi - lo, GRID_CAP)), dim3(WG), 0, s, T, lo, hi);
+            ++ctx->n_launch_fwd;
+        }
+    }
+    return 0;
+}
+
+static int launch_backward_steps(ob_ctx *ctx)
+{
+    const Tables &T = ctx->T;
+    hipStream_t s = ctx->stream;
+    const u32 ns = ctx->hdr.n_steps;
+    for (u32 st = ns; st-- > 0;) {
+        const u32 alo = ctx->step_ta[st], ahi = ctx->step_ta[st + 1];
+        if (ahi > alo) {
+            hipLaunchKernelGGL(k_bwd_pull_step, dim3(grid_for(ahi - alo, GRID_CAP)), dim3(WG), 0, s, T, alo, ahi);
+            ++ctx->n_launch_bwd;
+        }
+        const u32 blo = ctx->step_tb[st], bhi = ctx->step_tb[st + 1];
+        if (bhi > blo) {
+            hipLaunchKernelGGL(k_bwd_dx_step, dim3(grid_for(bhi - blo, GRID_CAP)), dim3(WG), 0, s, T, blo, bhi);
+            ++ctx->n_launch_bwd;
+        }
+    }
+    return 0;
+}
+
+static int launch_param_grads(ob_ctx *ctx)
+{
+    const Tables &T = ctx->T;
+    hipStream_t s = ctx->stream;
+    if (ctx->hdr.n_items == 0) return 0;
+    if (!ctx->wtiles.empty()) {
+        hipLaunchKernelGGL(k_param_w, dim3((unsigned)ctx->wtiles.size()), dim3(WG), 0, s, T, ctx->wtiles_dev);
+        ++ctx->n_launch_bwd;
+    }
+    if (!ctx->btiles.empty()) {
+        hipLaunchKernelGGL(k_param_b, dim3((unsigned)ctx->btiles.size()), dim3(WG), 0, s, T, ctx->btiles_dev);
+        ++ctx->n_launch_bwd;
+    }
+    u32 blocks = (ctx->hdr.n_items + 3) / 4;
+    if (blocks > 2048) blocks = 2048;
+    hipLaunchKernelGGL(k_param_e, dim3(blocks), dim3(WG), 0, s, T, ctx->hdr.n_items);
+    ++ctx->n_launch_bwd;
+    return 0;
+}
+
+// Runs `body` either directly on the stream or captured into a hipGraph that is instantiated
+// and launched once (the graph differs per minibatch, so building it is part of the cost).
+template <typename F>
+static int run_maybe_graph(ob_ctx *ctx, hipGraph_t *graph, hipGraphExec_t *gexec, F body)
+{
+    if (ctx->launch != 1) return body();
+    if (!ctx->stream) return ctx_fail(ctx, -6, "hipGraph launch needs a stream other than the default stream");
+    auto t0 = std::chrono::steady_clock::now();
+    if (*gexec) { HIP_TRY(ctx, hipGraphExecDestroy(*gexec)); *gexec = nullptr; }
+    if (*graph) { HIP_TRY(ctx, hipGraphDestroy(*graph)); *graph = nullptr; }
+    HIP_TRY(ctx, hipStreamBeginCapture(ctx->stream, hipStreamCaptureModeThreadLocal));
+    int rc = body();
+    hipError_t e = hipStreamEndCapture(ctx->stream, graph);
+    if (rc) return rc;
+    HIP_TRY(ctx, e);
+    HIP_TRY(ctx, hipGraphInstantiate(gexec, *graph, nullptr, nullptr, 0));
+    auto t1 = std::chrono::steady_clock::now();
+    ctx->ms_graph += std::chrono::duration<float, std::milli>(t1 - t0).count();
+    HIP_TRY(ctx, hipGraphLaunch(*gexec, ctx->stream));
+    return 0;
+}
+
+int exec_forward(ob_ctx *ctx)
+{
+    ctx->n_launch_fwd = 0;
+    int rc = run_maybe_graph(ctx, &ctx->graph_fwd, &ctx->gexec_fwd, [ctx]() { return launch_forward_steps(ctx); });
+    if (rc) return rc;
+    HIP_TRY(ctx, hipGetLastError());
+    return 0;
+}
+
+int exec_backward(ob_ctx *ctx)
+{
+    ctx->n_launch_bwd = 0;
+    int rc = run_maybe_graph(ctx, &ctx->graph_bwd, &ctx->gexec_bwd, [ctx]() {
+        int r = launch_backward_steps(ctx);
+        if (r) return r;
+        return 0;
+    });
+    if (rc) return rc;
+    HIP_TRY(ctx, hipEventRecord(ctx->ev[6], ctx->stream));
+    rc = launch_param_grads(ctx);
+    if (rc) return rc;
+    HIP_TRY(ctx, hipGetLastError());
+    return 0;
+}
+
+hipError_t exec_gather_all(const Tables &T, int which, float *dst, const u32 *dst_off, hipStream_t s)
+{
+    if (T.n == 0) return hipSuccess;
+    hipLaunchKernelGGL(k_gather_all, dim3(T.n), dim3(64), 0, s, T, which ? T.G : T.V, dst, dst_off);
+    return hipGetLastError();
+}
+
+hipError_t exec_test_gemm(int M, int N, int K, const float *A, const float *B, float *C, hipStream_t s)
+{
+    const unsigned tiles = (unsigned)(((M + GT - 1) / GT) * ((N + GT - 1) / GT));
+    hipLaunchKernelGGL(k_test_gemm, dim3(tiles), dim3(WG), 0, s, A, B, C, M, N, K);
+    return hipGetLastError();
+}

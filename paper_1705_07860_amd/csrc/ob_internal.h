@@ -1,0 +1,133 @@
+// Internal declarations shared by the library's translation units (not part of the ABI).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+
+typedef uint32_t u32;
+typedef uint64_t u64;
+typedef int32_t i32;
+typedef uint8_t u8;
+
+// ---- graph data format -------------------------------------------------------------------
+enum : u32 {
+    OP_INPUT = 0, OP_LOOKUP, OP_MATVEC, OP_ADD, OP_CMULT, OP_TANH, OP_SIGMOID,
+    OP_CONCAT, OP_SLICE, OP_PICK_NLS, OP_SQNORM, OP_COUNT
+};
+
+// ---- execution geometry --------------------------------------------------------------------
+constexpr int WG = 256;               // threads per workgroup of every tile kernel (4 wave64)
+constexpr int EW_TILE = 1024;         // elements of one elementwise / pull tile
+constexpr int GT = 32;                // GEMM tile edge (one 32x32 MFMA accumulator block)
+constexpr int ROWS_PER_RED_TILE = 4;  // rows of one row-reduction tile (one wave per row)
+constexpr int WIDE_ADD_ARITY = 9;     // ADD with at least this many operands reduces per row
+constexpr u32 VAL_ALIGN = 64;         // batch blocks start at multiples of 64 floats (256 B)
+
+// Kinds of consumer-edge records read by the backward pull (one per graph edge).
+enum : u32 {
+    EK_PLAIN = 0,   // += G[goff + c]                       (ADD, CONCAT, MATVEC dX block)
+    EK_RANGE,       // += G[goff + c - lo] if lo <= c < hi  (SLICE)
+    EK_MUL,         // += G[goff + c] * V[voff + c]         (CMULT, voff = the other operand)
+    EK_DTANH,       // += G[goff + c] * (1 - V[voff + c]^2)
+    EK_DSIGM,       // += G[goff + c] * V[voff + c] * (1 - V[voff + c])
+    EK_NLS,         // += G[goff] * (exp(x_c - lse) - [c == label]), lse = V[voff] + x_label
+    EK_SQN          // += 2 G[goff] x_c
+};
+
+struct EdgeRec {   // 20 bytes, one per graph edge, ordered by (producer, consumer, slot)
+    u32 kind, goff, voff;
+    i32 a0, a1;
+};
+
+struct BatchRec {  // one per batch, 64 bytes
+    u32 pos0;      // first position in schedule order
+    u32 B;         // number of nodes (rows)
+    u32 op;
+    u32 d;         // out_dim
+    u32 arity;
+    i32 param, bias;
+    i32 aux0, aux1;      // SLICE lo / hi (the only aux fields that are part of a signature)
+    u32 step;
+    u32 val_off;         // element offset of row 0 in the value arena (same in the grad arena)
+    u32 dx_off;          // MATVEC: element offset of the dX block in the grad arena
+    u32 opnd;            // base into opnd_off[], slot-major: opnd_off[opnd + j*B + r]
+    u32 k;               // dimension of operand 0 (MATVEC: columns of W)
+    u32 indim;           // base into b_indim[] (operand dimensions, `arity` entries)
+    u32 vec4;            // 1 when every row and operand row is 16-byte aligned and d % 4 == 0
+};
+
+struct ParamDesc {
+    float *data;
+    float *grad;
+    i32 rows, cols;
+};
+
+struct TileRec { u32 batch, t; };
+
+// Static tile of the deferred parameter-gradient kernels (built on the host per parameter set).
+struct PTile { i32 param; i32 i0, j0; i32 pad; };
+
+// Scan element of the per-batch layout pass.
+struct Lay {
+    u64 val, dx;           // floats
+    u32 tf, ta, tb, ind;   // forward tiles, pull tiles, dX tiles, operand-dimension slots
+    __host__ __device__ Lay operator+(const Lay &o) const {
+        Lay r; r.val = val + o.val; r.dx = dx + o.dx; r.tf = tf + o.tf; r.ta = ta + o.ta;
+        r.tb = tb + o.tb; r.ind = ind + o.ind; return r;
+    }
+};
+
+// Header the host reads back after scheduling (one small D2H copy).
+struct SchedHeader {
+    u32 n_steps, n_batches, n_items, err;
+    u64 val_floats, grad_floats;
+    u32 tiles_fwd, tiles_pull, tiles_dx, frontier_done;
+};
+enum : u32 { ERR_CYCLE = 1, ERR_COLLISION = 2, ERR_TABLE_FULL = 4, ERR_OVERFLOW = 8 };
+
+// All device pointers of one scheduled graph.  Passed by value to kernels.
+struct Tables {
+    u32 n, E;              // nodes / edges covered by the schedule
+    u32 root;              // backward root (node id), 0xffffffff when none
+    u32 n_params;
+    // graph as uploaded
+    const u8 *op; const u32 *out_dim; const u32 *in_off; const u32 *in_idx;
+    const i32 *param; const i32 *bias; const i32 *aux0; const i32 *aux1;
+    const float *payload;
+    const ParamDesc *params;
+    // scheduler tables
+    u64 *sig; u32 *step; u32 *indeg; u32 *outdeg; u32 *succ_off; u32 *succ_edge; u32 *edge_cons;
+    u32 *queue; u32 *qcount;            // frontier queue, [0]=tail
+    u64 *ht_keys; u32 *ht_vals; u32 ht_mask; u32 *ht_slot;
+    u32 *order; u32 *pos_of; u32 *batch_of_pos; u32 *s_aux0; u32 *s_in_off;
+    u32 *batch_off; BatchRec *batches; Lay *lay; u32 *b_indim;
+    u32 *val_off; u32 *dx_off; u32 *opnd_off;
+    u32 *step_first; u32 *step_tf; u32 *step_ta; u32 *step_tb;
+    TileRec *tiles_f; TileRec *tiles_a; TileRec *tiles_b;
+    EdgeRec *edges;
+    // parameter-use items (deferred dW / db / dE)
+    u64 *it_key; u32 *it_pos; u32 *it_goff; u32 *it_xoff; u32 *pu_start; u32 *pu_end;
+    SchedHeader *hdr;
+    // arenas
+    float *V; float *G;
+};
+
+// ---- primitives (ob_prims.hip) ------------------------------------------------------------
+size_t prim_scan_scratch_bytes(size_t n, size_t elem);
+hipError_t prim_fill_u32(u32 *p, u32 v, size_t n, hipStream_t s);
+hipError_t prim_scan_u32(const u32 *in, u32 *out, size_t n, u32 *total_dev, void *scratch, hipStream_t s);
+hipError_t prim_scan_lay(const Lay *in, Lay *out, size_t n, Lay *total_dev, void *scratch, hipStream_t s);
+size_t prim_sort_scratch_bytes(size_t n);
+// Stable LSD radix sort of (key, val) pairs on bits [lo_bit, lo_bit + n_bits) of the key.
+// keys/vals are overwritten with the sorted result; tmp arrays have the same sizes.
+hipError_t prim_sort_pairs(u64 *keys, u32 *vals, u64 *keys_tmp, u32 *vals_tmp, size_t n, int lo_bit,
+                           int n_bits, void *scratch, hipStream_t s, int *n_launches);
+
+// ---- scheduler / executor entry points ---------------------------------------------------
+struct ob_ctx;
+int sched_run(ob_ctx *ctx);
+int exec_forward(ob_ctx *ctx);
+int exec_backward(ob_ctx *ctx);
+hipError_t exec_gather_all(const Tables &T, int which, float *dst, const u32 *dst_off, hipStream_t s);
+hipError_t exec_test_gemm(int M, int N, int K, const float *A, const float *B, float *C, hipStream_t s);

@@ -1,0 +1,264 @@
+// Device-wide primitives of the GPU scheduler: fill, exclusive scan, stable LSD radix sort.
+// Written for wave64 (gfx950): ranking inside a wave uses 64-bit ballots.
+#include "ob_internal.h"
+
+namespace {
+
+constexpr int SCAN_THREADS = 256;
+constexpr int SCAN_ITEMS = 4;
+constexpr int SCAN_BLOCK = SCAN_THREADS * SCAN_ITEMS;  // 1024 elements per block
+
+__global__ void k_fill_u32(u32 *p, u32 v, size_t n)
+{
+    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (; i < n; i += stride) p[i] = v;
+}
+
+template <typename T> __device__ inline T zero_of();
+template <> __device__ inline u32 zero_of<u32>() { return 0u; }
+template <> __device__ inline Lay zero_of<Lay>() { Lay z; z.val = 0; z.dx = 0; z.tf = z.ta = z.tb = z.ind = 0; return z; }
+
+// Exclusive scan of the 256 per-thread values of a block through LDS (Kogge-Stone).
+// Returns the exclusive prefix of this thread; *block_total gets the sum of all 256.
+template <typename T>
+__device__ inline T block_exclusive(T mine, T *lds, T *block_total)
+{
+    const int t = threadIdx.x;
+    lds[t] = mine;
+    __syncthreads();
+    for (int off = 1; off < SCAN_THREADS; off <<= 1) {
+        T add = zero_of<T>();
+        if (t >= off) add = lds[t - off];
+        __syncthreads();
+        if (t >= off) lds[t] = lds[t] + add;
+        __syncthreads();
+    }
+    T incl = lds[t];
+    T total = lds[SCAN_THREADS - 1];
+    __syncthreads();
+    *block_total = total;
+    // exclusive = inclusive of the previous thread
+    T excl = zero_of<T>();
+    lds[t] = incl;
+    __syncthreads();
+    if (t > 0) excl = lds[t - 1];
+    __syncthreads();
+    return excl;
+}
+
+template <typename T>
+__global__ __launch_bounds__(SCAN_THREADS) void k_scan_local(const T *in, T *out, T *block_sums, size_t n)
+{
+    __shared__ T lds[SCAN_THREADS];
+    const size_t base = (size_t)blockIdx.x * SCAN_BLOCK + (size_t)threadIdx.x * SCAN_ITEMS;
+    T item[SCAN_ITEMS];
+    T sum = zero_of<T>();
+    for (int i = 0; i < SCAN_ITEMS; ++i) {
+        item[i] = (base + i < n) ? in[base + i] : zero_of<T>();
+        sum = sum + item[i];
+    }
+    T total;
+    T run = block_exclusive<T>(sum, lds, &total);
+    for (int i = 0; i < SCAN_ITEMS; ++i) {
+        if (base + i < n) out[base + i] = run;
+        run = run + item[i];
+    }
+    if (threadIdx.x == 0) block_sums[blockIdx.x] = total;
+}
+
+// One block turns the per-block sums into exclusive offsets, chunk by chunk with a carry.
+template <typename T>
+__global__ __launch_bounds__(SCAN_THREADS) void k_scan_sums(T *block_sums, size_t nblk, T *total_out)
+{
+    __shared__ T lds[SCAN_THREADS];
+    T carry = zero_of<T>();
+    for (size_t c0 = 0; c0 < nblk; c0 += SCAN_THREADS) {
+        const size_t i = c0 + threadIdx.x;
+        T mine = (i < nblk) ? block_sums[i] : zero_of<T>();
+        T total;
+        T ex = block_exclusive<T>(mine, lds, &total);
+        if (i < nblk) block_sums[i] = carry + ex;
+        carry = carry + total;
+    }
+    if (threadIdx.x == 0 && total_out) *total_out = carry;
+}
+
+template <typename T>
+__global__ __launch_bounds__(SCAN_THREADS) void k_scan_add(T *out, const T *block_sums, size_t n)
+{
+    const T add = block_sums[blockIdx.x];
+    const size_t base = (size_t)blockIdx.x * SCAN_BLOCK + (size_t)threadIdx.x * SCAN_ITEMS;
+    for (int i = 0; i < SCAN_ITEMS; ++i)
+        if (base + i < n) out[base + i] = out[base + i] + add;
+}
+
+template <typename T>
+hipError_t scan_impl(const T *in, T *out, size_t n, T *total_dev, void *scratch, hipStream_t s)
+{
+    if (n == 0) {
+        // total = 0
+        if (total_dev) return hipMemsetAsync(total_dev, 0, sizeof(T), s);
+        return hipSuccess;
+    }
+    const size_t nblk = (n + SCAN_BLOCK - 1) / SCAN_BLOCK;
+    T *sums = (T *)scratch;
+    hipLaunchKernelGGL(k_scan_local<T>, dim3((unsigned)nblk), dim3(SCAN_THREADS), 0, s, in, out, sums, n);
+    hipLaunchKernelGGL(k_scan_sums<T>, dim3(1), dim3(SCAN_THREADS), 0, s, sums, nblk, total_dev);
+    if (nblk > 1)
+        hipLaunchKernelGGL(k_scan_add<T>, dim3((unsigned)nblk), dim3(SCAN_THREADS), 0, s, out, sums, n);
+    return hipGetLastError();
+}
+
+// ---- radix sort ------------------------------------------------------------------------------
+constexpr int RS_BITS = 8;
+constexpr int RS_RADIX = 1 << RS_BITS;
+constexpr int RS_THREADS = 256;                  // 4 waves
+constexpr int RS_WAVES = RS_THREADS / 64;
+constexpr int RS_ROUNDS = 4;                     // keys per lane
+constexpr int RS_WAVE_KEYS = 64 * RS_ROUNDS;     // 256 consecutive keys per wave
+constexpr int RS_BLOCK = RS_WAVE_KEYS * RS_WAVES;  // 1024 keys per block
+
+__device__ inline u32 digit_of(u64 key, int shift, u32 mask) { return (u32)(key >> shift) & mask; }
+
+// table[d * nblk + blk] = number of keys of block blk whose digit is d
+__global__ __launch_bounds__(RS_THREADS) void k_rs_hist(const u64 *keys, size_t n, int shift, u32 mask,
+                                                       u32 *table, u32 nblk)
+{
+    __shared__ u32 hist[RS_RADIX];
+    hist[threadIdx.x] = 0;
+    __syncthreads();
+    const size_t base = (size_t)blockIdx.x * RS_BLOCK;
+    for (int i = 0; i < RS_BLOCK / RS_THREADS; ++i) {
+        const size_t idx = base + (size_t)i * RS_THREADS + threadIdx.x;
+        if (idx < n) atomicAdd(&hist[digit_of(keys[idx], shift, mask)], 1u);
+    }
+    __syncthreads();
+    table[(size_t)threadIdx.x * nblk + blockIdx.x] = hist[threadIdx.x];
+}
+
+// Stable scatter.  Wave w of a block owns keys [w*256, w*256+256) of the block's chunk and
+// walks them in 4 rounds of 64; inside a round lanes with equal digits are ranked by lane id.
+__global__ __launch_bounds__(RS_THREADS) void k_rs_scatter(const u64 *keys, const u32 *vals, u64 *keys_out,
+                                                          u32 *vals_out, size_t n, int shift, u32 mask,
+                                                          const u32 *table, u32 nblk)
+{
+    __shared__ u32 cnt[RS_WAVES][RS_RADIX];
+    const int lane = threadIdx.x & 63;
+    const int w = threadIdx.x >> 6;
+    for (int i = 0; i < RS_WAVES; ++i) cnt[i][threadIdx.x] = 0;
+    __syncthreads();
+
+    const size_t wbase = (size_t)blockIdx.x * RS_BLOCK + (size_t)w * RS_WAVE_KEYS;
+    u64 key[RS_ROUNDS];
+    u32 val[RS_ROUNDS];
+    bool ok[RS_ROUNDS];
+    for (int r = 0; r < RS_ROUNDS; ++r) {
+        const size_t idx = wbase + (size_t)r * 64 + lane;
+        ok[r] = idx < n;
+        key[r] = ok[r] ? keys[idx] : 0;
+        val[r] = ok[r] ? vals[idx] : 0;
+        if (ok[r]) atomicAdd(&cnt[w][digit_of(key[r], shift, mask)], 1u);
+    }
+    __syncthreads();
+    {   // thread d turns the per-wave counts of digit d into per-wave start positions
+        const int d = threadIdx.x;
+        u32 run = table[(size_t)d * nblk + blockIdx.x];
+        for (int i = 0; i < RS_WAVES; ++i) {
+            const u32 c = cnt[i][d];
+            cnt[i][d] = run;
+            run += c;
+        }
+    }
+    __syncthreads();
+    for (int r = 0; r < RS_ROUNDS; ++r) {
+        const u32 d = digit_of(key[r], shift, mask);
+        u64 peers = __ballot(ok[r]);
+        for (int b = 0; b < RS_BITS; ++b) {
+            const bool bit = (d >> b) & 1u;
+            const u64 m = __ballot(bit);
+            peers &= bit ? m : ~m;
+        }
+        if (!ok[r]) peers = 0;
+        const u32 rank = (u32)__popcll(peers & ((1ull << lane) - 1ull));
+        const u32 count = (u32)__popcll(peers);
+        const int leader = peers ? (__ffsll((unsigned long long)peers) - 1) : lane;
+        u32 start = 0;
+        if (ok[r] && leader == lane) start = atomicAdd(&cnt[w][d], count);
+        start = __shfl(start, leader);
+        if (ok[r]) {
+            keys_out[start + rank] = key[r];
+            vals_out[start + rank] = val[r];
+        }
+    }
+}
+
+}  // namespace
+
+// ---- host wrappers -------------------------------------------------------------------------------
+
+static inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
+
+size_t prim_scan_scratch_bytes(size_t n, size_t elem)
+{
+    return align256(((n + SCAN_BLOCK - 1) / SCAN_BLOCK + 1) * elem);
+}
+
+hipError_t prim_fill_u32(u32 *p, u32 v, size_t n, hipStream_t s)
+{
+    if (n == 0) return hipSuccess;
+    size_t blocks = (n + 1023) / 1024;
+    if (blocks > 2048) blocks = 2048;
+    hipLaunchKernelGGL(k_fill_u32, dim3((unsigned)blocks), dim3(256), 0, s, p, v, n);
+    return hipGetLastError();
+}
+
+hipError_t prim_scan_u32(const u32 *in, u32 *out, size_t n, u32 *total_dev, void *scratch, hipStream_t s)
+{
+    return scan_impl<u32>(in, out, n, total_dev, scratch, s);
+}
+
+hipError_t prim_scan_lay(const Lay *in, Lay *out, size_t n, Lay *total_dev, void *scratch, hipStream_t s)
+{
+    return scan_impl<Lay>(in, out, n, total_dev, scratch, s);
+}
+
+size_t prim_sort_scratch_bytes(size_t n)
+{
+    const size_t nblk = (n + RS_BLOCK - 1) / RS_BLOCK;
+    const size_t table = align256((size_t)RS_RADIX * (nblk ? nblk : 1) * sizeof(u32));
+    return table + prim_scan_scratch_bytes((size_t)RS_RADIX * (nblk ? nblk : 1), sizeof(u32));
+}
+
+hipError_t prim_sort_pairs(u64 *keys, u32 *vals, u64 *keys_tmp, u32 *vals_tmp, size_t n, int lo_bit,
+                           int n_bits, void *scratch, hipStream_t s, int *n_launches)
+{
+    if (n <= 1 || n_bits <= 0) return hipSuccess;
+    const u32 nblk = (u32)((n + RS_BLOCK - 1) / RS_BLOCK);
+    u32 *table = (u32 *)scratch;
+    void *scan_scratch = (char *)scratch + align256((size_t)RS_RADIX * nblk * sizeof(u32));
+    u64 *kin = keys, *kout = keys_tmp;
+    u32 *vin = vals, *vout = vals_tmp;
+    int passes = 0;
+    for (int b = 0; b < n_bits; b += RS_BITS) {
+        const int bits = (n_bits - b < RS_BITS) ? (n_bits - b) : RS_BITS;
+        const u32 mask = (1u << bits) - 1u;
+        const int shift = lo_bit + b;
+        hipLaunchKernelGGL(k_rs_hist, dim3(nblk), dim3(RS_THREADS), 0, s, kin, n, shift, mask, table, nblk);
+        hipError_t e = scan_impl<u32>(table, table, (size_t)RS_RADIX * nblk, (u32 *)nullptr, scan_scratch, s);
+        if (e != hipSuccess) return e;
+        hipLaunchKernelGGL(k_rs_scatter, dim3(nblk), dim3(RS_THREADS), 0, s, kin, vin, kout, vout, n, shift,
+                           mask, table, nblk);
+        u64 *tk = kin; kin = kout; kout = tk;
+        u32 *tv = vin; vin = vout; vout = tv;
+        ++passes;
+        if (n_launches) *n_launches += 2 + ((size_t)RS_RADIX * nblk > SCAN_BLOCK ? 3 : 2);
+    }
+    if (passes & 1) {  // result sits in the tmp arrays: copy back
+        hipError_t e = hipMemcpyAsync(keys, kin, n * sizeof(u64), hipMemcpyDeviceToDevice, s);
+        if (e != hipSuccess) return e;
+        e = hipMemcpyAsync(vals, vin, n * sizeof(u32), hipMemcpyDeviceToDevice, s);
+        if (e != hipSuccess) return e;
+    }
+    return hipGetLastError();
+}

@@ -1,0 +1,269 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle on the same seeded
+inputs.  Schedules must match bit-exactly; every node value, node gradient and parameter
+gradient must agree within 1e-4 relative to the largest magnitude of its tensor."""
+import sys
+
+import numpy as np
+import pytest
+
+from oracle import schedule as S
+from oracle.interp import Oracle
+from paper_1705_07860_amd import workloads as wl
+from tests.helpers import rel_err, segment_rel_err
+
+pytestmark = pytest.mark.gpu
+
+TOL = 1e-4   # max_i |gpu_i - ref_i| <= TOL * max_i |ref_i| per tensor (fp32 path vs fp64 oracle)
+
+
+def say(msg):
+    print(msg, flush=True)
+    sys.stdout.flush()
+
+
+def run_gpu(p, g, mode, launch=0, arena=2 << 30, n_nodes=None):
+    from paper_1705_07860_amd import binding as ob
+    c = ob.Context(arena_bytes=arena, mode=mode, launch=launch)
+    pids = c.params_create(p)
+    assert pids == list(range(len(p.mats)))
+    c.param_grad_zero()
+    c.add_bulk(g)
+    root = g.root if n_nodes is None else n_nodes - 1
+    c.forward(root)
+    return c, root
+
+
+def check_against_oracle(c, p, g, o, root, tol=TOL, what=""):
+    n = o.n
+    total = int(o.v_off[-1])
+    vals = c.all_read(0, total)
+    ev = segment_rel_err(vals, o.val[:total], o.v_off)
+    say(f"  {what} values: worst tensor rel err {ev:.2e}")
+    assert ev <= tol
+    c.backward(root)
+    grads = c.all_read(1, total)
+    eg = segment_rel_err(grads, o.grad[:total], o.v_off)
+    say(f"  {what} node gradients: worst tensor rel err {eg:.2e}")
+    assert eg <= tol
+    worst = 0.0
+    for pid, m in enumerate(p.mats):
+        got = c.param_grad_read(pid, m.shape)
+        e = rel_err(got, o.param_grad(pid))
+        worst = max(worst, e)
+        assert e <= tol, (p.names[pid], e)
+    say(f"  {what} parameter gradients: worst tensor rel err {worst:.2e}")
+    loss = c.value_read(root, 1)[0]
+    assert abs(loss - o.value(root)[0]) <= tol * abs(o.value(root)[0])
+
+
+# ------------------------------------------------------------------ scheduler stages
+
+@pytest.mark.parametrize("name", ["rnn", "tagger", "tagger_char", "tree", "parser"])
+def test_schedule_bit_exact(name, workload_cache):
+    from paper_1705_07860_amd import binding as ob
+    p, g, o = workload_cache(name)
+    say(f"schedule {name}: n={g.n} E={g.n_edges}")
+    c, root = run_gpu(p, g, ob.OB_BYDEPTH)
+    depth = c.debug_read(ob.OB_DBG_DEPTH)
+    assert np.array_equal(depth.astype(np.int64), S.depths(g))
+    succ_off = c.debug_read(ob.OB_DBG_SUCC_OFF).astype(np.int64)
+    succ_edge = c.debug_read(ob.OB_DBG_SUCC_EDGE).astype(np.int64)
+    ref_edge = np.argsort(g.in_idx, kind="stable")
+    assert np.array_equal(succ_edge, ref_edge)
+    assert np.array_equal(np.diff(succ_off), np.bincount(g.in_idx, minlength=g.n))
+    bo, ids, bd, sig = c.schedule_read()
+    rbo, rids, rbd = S.by_depth(g)
+    assert np.array_equal(bo, rbo)
+    assert np.array_equal(ids, rids)
+    assert np.array_equal(bd, rbd)
+    st = c.stats()
+    say(f"  steps={st['n_steps']} batches={st['n_batches']} sched {st['ms_schedule']:.3f} ms "
+        f"fwd {st['ms_forward']:.3f} ms launches(sched)={st['n_launch_sched']}")
+    c.close()
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_schedule_bit_exact_random_dags(seed):
+    from paper_1705_07860_amd import binding as ob
+    p, g = wl.random_dag(500 + seed, n_nodes=30 + 40 * seed, dim=4 + 2 * (seed % 3))
+    c, root = run_gpu(p, g, ob.OB_BYDEPTH, arena=64 << 20)
+    bo, ids, bd, _ = c.schedule_read()
+    rbo, rids, rbd = S.by_depth(g)
+    assert np.array_equal(bo, rbo) and np.array_equal(ids, rids) and np.array_equal(bd, rbd)
+    o = Oracle(g, p, "f64")
+    o.forward()
+    o.backward(g.root)
+    check_against_oracle(c, p, g, o, root, what=f"dag{seed}")
+    c.close()
+
+
+def test_nobatch_schedule_is_one_node_per_batch(workload_cache):
+    from paper_1705_07860_amd import binding as ob
+    p, g, o = workload_cache("rnn")
+    c, root = run_gpu(p, g, ob.OB_NOBATCH, arena=64 << 20)
+    bo, ids, bd, _ = c.schedule_read()
+    rbo, rids, rbd = S.no_batching(g)
+    assert np.array_equal(bo, rbo) and np.array_equal(ids, rids) and np.array_equal(bd, rbd)
+    check_against_oracle(c, p, g, o, root, what="rnn/nobatch")
+    c.close()
+
+
+# ------------------------------------------------------------------ values and gradients
+
+@pytest.mark.parametrize("name", ["rnn", "tagger", "tagger_char", "tree", "parser"])
+def test_values_and_gradients_by_depth(name, workload_cache):
+    from paper_1705_07860_amd import binding as ob
+    p, g, o = workload_cache(name)
+    say(f"parity {name}: n={g.n}")
+    c, root = run_gpu(p, g, ob.OB_BYDEPTH)
+    check_against_oracle(c, p, g, o, root, what=name)
+    st = c.stats()
+    say(f"  sched {st['ms_schedule']:.3f} ms fwd {st['ms_forward']:.3f} ms bwd {st['ms_backward']:.3f} ms "
+        f"(param grads {st['ms_param_grads']:.3f}) launches fwd={st['n_launch_fwd']} bwd={st['n_launch_bwd']}")
+    c.close()
+
+
+@pytest.mark.parametrize("name", ["tagger", "tree"])
+def test_hipgraph_launch_matches(name, workload_cache):
+    from paper_1705_07860_amd import binding as ob
+    p, g, o = workload_cache(name)
+    c, root = run_gpu(p, g, ob.OB_BYDEPTH, launch=ob.OB_LAUNCH_GRAPH)
+    check_against_oracle(c, p, g, o, root, what=f"{name}/hipgraph")
+    st = c.stats()
+    say(f"  graph build {st['ms_graph_build']:.3f} ms fwd {st['ms_forward']:.3f} bwd {st['ms_backward']:.3f}")
+    c.close()
+
+
+def test_nobatch_matches_on_a_small_tagger():
+    from paper_1705_07860_amd import binding as ob
+    p = wl.tagger_params()
+    g = wl.tagger_minibatch(p, seed=31, lengths=[3, 6, 1])
+    o = Oracle(g, p, "f64")
+    o.forward()
+    o.backward(g.root)
+    c, root = run_gpu(p, g, ob.OB_NOBATCH, arena=512 << 20)
+    check_against_oracle(c, p, g, o, root, what="tagger3/nobatch")
+    c.close()
+
+
+def test_runs_are_bit_identical(workload_cache):
+    """No atomics on floating point anywhere: two runs give the same bits."""
+    from paper_1705_07860_amd import binding as ob
+    p, g, o = workload_cache("tree")
+    outs = []
+    for _ in range(2):
+        c, root = run_gpu(p, g, ob.OB_BYDEPTH)
+        total = int(o.v_off[-1])
+        c.backward(root)
+        outs.append((c.all_read(0, total).copy(), c.all_read(1, total).copy(),
+                     [c.param_grad_read(i, m.shape).copy() for i, m in enumerate(p.mats)]))
+        c.close()
+    assert np.array_equal(outs[0][0], outs[1][0])
+    assert np.array_equal(outs[0][1], outs[1][1])
+    for a, b in zip(outs[0][2], outs[1][2]):
+        assert np.array_equal(a, b)
+
+
+# ------------------------------------------------------------------ edge cases
+
+def test_edge_cases_single_node_and_prefix_forward():
+    from paper_1705_07860_amd import binding as ob
+    p = wl.rnn_params()
+    # a one-node graph
+    c = ob.Context(arena_bytes=16 << 20)
+    c.params_create(p)
+    x = c.add_input(np.arange(1, 2, dtype=np.float32))
+    c.forward(x)
+    assert c.value_read(x, 1)[0] == 1.0
+    c.backward(x)
+    assert c.grad_read(x, 1)[0] == 1.0
+    with pytest.raises(ob.ObError) as e:
+        c.add_input(np.zeros(3))                     # incremental forward is not built
+    assert e.value.code == -6
+    # graph_new starts over; forward of a prefix evaluates only ids <= node
+    c.graph_new()
+    g = wl.rnn_minibatch(p, seed=5, lengths=[2, 4])
+    c.add_bulk(g)
+    first_sq = int(np.nonzero(g.op == wl.OP_SQNORM)[0][0])
+    c.forward(first_sq)
+    o = Oracle(g, p, "f64", n_nodes=first_sq + 1)
+    o.forward()
+    o.backward(first_sq)
+    total = int(o.v_off[-1])
+    assert segment_rel_err(c.all_read(0, total), o.val[:total], o.v_off) <= TOL
+    c.param_grad_zero()
+    c.backward(first_sq)
+    assert segment_rel_err(c.all_read(1, total), o.grad[:total], o.v_off) <= TOL
+    with pytest.raises(ob.ObError) as e:
+        c.backward(first_sq - 1)                     # not a scalar
+    assert e.value.code == -4
+    with pytest.raises(ob.ObError) as e:
+        c.value_read(g.n - 1, 1)                     # beyond the evaluated prefix
+    assert e.value.code == -1
+    with pytest.raises(ob.ObError) as e:
+        c.value_read(0, 3)                           # capacity too small
+    assert e.value.code == -3
+    c.close()
+
+
+def test_arena_too_small_is_an_error_not_a_crash():
+    from paper_1705_07860_amd import binding as ob
+    p, g = wl.make("rnn")
+    c = ob.Context(arena_bytes=64 << 10)
+    c.params_create(p)
+    c.add_bulk(g)
+    with pytest.raises(ob.ObError) as e:
+        c.forward(g.root)
+    assert e.value.code == -5
+    c.close()
+
+
+def test_odd_dimensions_duplicate_lookups_and_wide_sum():
+    """Dimensions that are not multiples of 4 or 32, the same table row looked up many times, a
+    node used twice by one consumer, and a sum over many operands."""
+    from paper_1705_07860_amd import binding as ob
+    rng = np.random.default_rng(12)
+    pb = wl.ParamBuilder(rng, std=0.4)
+    E = pb.add("E", 5, 37)
+    W = pb.add("W", 45, 37)
+    b = pb.add("b", 45, 1)
+    W2 = pb.add("W2", 3, 45)
+    p = pb.done()
+    gb = wl.GraphBuilder(p)
+    losses = []
+    for i in range(70):
+        x = gb.lookup(E, i % 3)                      # rows 0..2 many times, rows 3,4 never
+        h = gb.tanh(gb.matvec(W, b, x))
+        hh = gb.cmult(h, h)                          # same operand twice
+        s = gb.slice(hh, 3, 44)
+        z = gb.concat((s, gb.slice(h, 0, 4)))        # 41 + 4 = 45
+        q = gb.add((z, h, hh))
+        sc = gb.matvec(W2, -1, gb.sigmoid(q))
+        losses.append(gb.pick_nls(sc, i % 3))
+        losses.append(gb.sqnorm(s))
+    g = gb.finish(gb.add(losses), 70)
+    o = Oracle(g, p, "f64")
+    o.forward()
+    o.backward(g.root)
+    c, root = run_gpu(p, g, ob.OB_BYDEPTH, arena=64 << 20)
+    bo, ids, bd, _ = c.schedule_read()
+    rbo, rids, rbd = S.by_depth(g)
+    assert np.array_equal(bo, rbo) and np.array_equal(ids, rids) and np.array_equal(bd, rbd)
+    check_against_oracle(c, p, g, o, root, what="odd")
+    assert not np.any(c.param_grad_read(E, (5, 37))[3:])     # untouched rows stay zero
+    c.close()
+
+
+def test_parameter_gradients_accumulate_until_zeroed(workload_cache):
+    from paper_1705_07860_amd import binding as ob
+    p, g, o = workload_cache("rnn")
+    c, root = run_gpu(p, g, ob.OB_BYDEPTH, arena=64 << 20)
+    c.backward(root)
+    g1 = c.param_grad_read(0, p.mats[0].shape)
+    c.backward(root)
+    g2 = c.param_grad_read(0, p.mats[0].shape)
+    assert rel_err(g2, 2 * g1.astype(np.float64)) < 1e-6
+    c.param_grad_zero()
+    c.backward(root)
+    assert np.array_equal(c.param_grad_read(0, p.mats[0].shape), g1)
+    c.close()
