@@ -1,0 +1,242 @@
+#!/usr/bin/env python3
+"""Benchmark of the hot path on one MI355X: schedule + batched forward + batched backward of one
+minibatch graph per step (the BiLSTM tagger workload: 64 sentences), graph arrays already
+resident in HBM when the timed region starts.
+
+Prints ONE JSON line: training instances/s (autobatched, depth-based), the roofline figures of
+the dominant kernel from HIP events recorded by the library on its stream, the same graphs with
+batching off (one launch per node), and the CPU oracle timed on a bounded sample.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+from paper_1705_07860_amd import workloads as wl  # noqa: E402
+
+HBM_PEAK_GBS = 8000.0
+MFMA_FP32_PEAK_TFLOPS = 157.3
+R_IDX = 4  # bytes of one gathered-row index
+
+
+def algorithmic_cost(g, params, batch_off, node_ids):
+    """Bytes and flops the method itself must move / do for one forward+backward of this
+    schedule (per-batch formulas: operands read once, results written once, one 4-byte row index
+    per gathered operand row; a shared matrix is read once per batch; dW is read-modify-written
+    once per parameter because its reduction is deferred over all uses)."""
+    heads = node_ids[batch_off[:-1]]
+    B = np.diff(batch_off).astype(np.float64)
+    op = g.op[heads].astype(np.int64)
+    d = g.out_dim[heads].astype(np.float64)
+    ar = (g.in_off[heads + 1] - g.in_off[heads]).astype(np.float64)
+    first_in = g.in_idx[np.minimum(g.in_off[heads], max(len(g.in_idx) - 1, 0))]
+    k = np.where(ar > 0, g.out_dim[first_in], 0).astype(np.float64)
+    fb = np.zeros(len(heads))
+    bb = np.zeros(len(heads))
+    fl_f = np.zeros(len(heads))
+    fl_b = np.zeros(len(heads))
+    un = (op == wl.OP_TANH) | (op == wl.OP_SIGMOID)
+    fb[un] = (8 * d + R_IDX)[un] * B[un]
+    bb[un] = (12 * d * B)[un]
+    m = op == wl.OP_ADD
+    fb[m] = ((4 * d * (ar + 1) + ar * R_IDX) * B)[m]
+    bb[m] = (4 * d * (ar + 1) * B)[m]
+    m = op == wl.OP_CMULT
+    fb[m] = ((12 * d + 2 * R_IDX) * B)[m]
+    bb[m] = (20 * d * B)[m]
+    m = (op == wl.OP_SLICE) | (op == wl.OP_CONCAT)
+    fb[m] = ((8 * d + ar * R_IDX) * B)[m]
+    bb[m] = (8 * d * B)[m]
+    m = (op == wl.OP_LOOKUP) | (op == wl.OP_INPUT)
+    fb[m] = (8 * d * B)[m]
+    bb[op == wl.OP_LOOKUP] = (16 * d * B)[op == wl.OP_LOOKUP]
+    m = (op == wl.OP_PICK_NLS) | (op == wl.OP_SQNORM)
+    fb[m] = ((4 * k + 4 + R_IDX) * B)[m]
+    bb[m] = (8 * k * B)[m]
+    m = op == wl.OP_MATVEC
+    fb[m] = (4 * (d * k + k * B + d * B) + R_IDX * B)[m]
+    bb[m] = (4 * (d * k + d * B + k * B) + 4 * (d * B + k * B))[m]
+    fl_f[m] = (2 * d * k * B)[m]
+    fl_b[m] = (4 * d * k * B)[m]
+    used_w = np.unique(g.param[g.op == wl.OP_MATVEC])
+    dW_rmw = float(sum(8 * params.mats[int(p)].size for p in used_w))
+    return dict(fwd_bytes=float(fb.sum()), bwd_bytes=float(bb.sum()) + dW_rmw,
+                fwd_flops=float(fl_f.sum()), bwd_flops=float(fl_b.sum()))
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=30)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="tagger", choices=list(wl.CONFIGS))
+    ap.add_argument("--pool", type=int, default=6, help="distinct seeded minibatches cycled through")
+    ap.add_argument("--launch", default="stream", choices=["stream", "graph"])
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
+    ap.add_argument("--no-nobatch", action="store_true", help="skip the unbatched GPU leg")
+    ap.add_argument("--cpu-samples", type=int, default=4)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU; --gpus must be 1 (the path has no multi-GPU part)",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_1705_07860_amd import binding as ob
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
+        sys.exit(3)
+
+    cfg = wl.CONFIGS[args.workload]
+    params = cfg["params"]()
+    pool = max(1, min(args.pool, args.steps + args.warmup))
+    graphs = [cfg["batch"](params, j) for j in range(pool)]
+    launch = ob.OB_LAUNCH_GRAPH if args.launch == "graph" else ob.OB_LAUNCH_STREAM
+
+    # one context per pooled minibatch, graph arrays uploaded before the timed region
+    # every context works on the same stream, so consecutive steps are serial on the GPU (as a
+    # training loop with a parameter update between minibatches would be); the host may run ahead
+    stream = torch.cuda.Stream()
+    ctxs = []
+    t_up = []
+    for g in graphs:
+        c = ob.Context(arena_bytes=1 << 30, stream=stream, mode=ob.OB_BYDEPTH, launch=launch)
+        c.params_create(params)
+        c.param_grad_zero()
+        t0 = time.perf_counter()
+        c.add_bulk(g)
+        c.upload()
+        c.sync()
+        t_up.append(time.perf_counter() - t0)
+        ctxs.append(c)
+
+    def step(i):
+        c = ctxs[i % pool]
+        g = graphs[i % pool]
+        c.reset()
+        c.param_grad_zero()
+        c.forward(g.root)
+        c.backward(g.root)
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    phase = dict(ms_schedule=0.0, ms_forward=0.0, ms_backward=0.0, ms_param_grads=0.0)
+    launches = dict(n_launch_fwd=0, n_launch_bwd=0)
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(args.warmup + i)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    # per-phase HIP-event times (events were recorded inside the timed region; reading them is not timed)
+    per_ctx_stats = [c.stats() for c in ctxs]
+    for i in range(args.steps):
+        st = per_ctx_stats[(args.warmup + i) % pool]
+        for k_ in phase:
+            phase[k_] += st[k_]
+        for k_ in launches:
+            launches[k_] += st[k_]
+    n_inst = sum(graphs[(args.warmup + i) % pool].n_instances for i in range(args.steps))
+    n_nodes = sum(graphs[(args.warmup + i) % pool].n for i in range(args.steps))
+    ms_per_step = elapsed / args.steps * 1e3
+    value = n_inst / elapsed
+
+    # algorithmic bytes / flops from the realised schedules
+    cost = dict(fwd_bytes=0.0, bwd_bytes=0.0, fwd_flops=0.0, bwd_flops=0.0)
+    for i in range(args.steps):
+        j = (args.warmup + i) % pool
+        if "cost" not in graphs[j].meta:
+            bo, ids, bd, _ = ctxs[j].schedule_read()
+            graphs[j].meta["cost"] = algorithmic_cost(graphs[j], params, bo, ids)
+        for k_ in cost:
+            cost[k_] += graphs[j].meta["cost"][k_]
+
+    # dominant kernel: the forward or backward step interpreter, whichever took longer
+    if phase["ms_backward"] - phase["ms_param_grads"] >= phase["ms_forward"]:
+        kname, kms = "k_bwd_pull_step+k_bwd_dx_step", phase["ms_backward"] - phase["ms_param_grads"]
+        kbytes, klaunch = cost["bwd_bytes"], launches["n_launch_bwd"]
+    else:
+        kname, kms, kbytes, klaunch = "k_fwd_step", phase["ms_forward"], cost["fwd_bytes"], launches["n_launch_fwd"]
+    achieved = kbytes / (kms * 1e-3) / 1e9
+    roofline = dict(bound="hbm", kernel=kname, achieved=round(achieved, 2), peak=HBM_PEAK_GBS, unit="GB/s",
+                    frac=round(achieved / HBM_PEAK_GBS, 5), traffic=None,
+                    launches=klaunch, avg_launch_us=round(kms * 1e3 / max(klaunch, 1), 3),
+                    algorithmic_bytes_per_launch=round(kbytes / max(klaunch, 1), 1),
+                    mfma=dict(fwd_tflops=round(cost["fwd_flops"] / (phase["ms_forward"] * 1e-3) / 1e12, 3),
+                              bwd_tflops=round(cost["bwd_flops"] / (phase["ms_backward"] * 1e-3) / 1e12, 3),
+                              peak=MFMA_FP32_PEAK_TFLOPS))
+
+    # unbatched GPU run of the same graphs (one launch per node forward, per node backward)
+    nobatch = None
+    if not args.no_nobatch:
+        c = ob.Context(arena_bytes=1 << 30, stream=stream, mode=ob.OB_NOBATCH, launch=ob.OB_LAUNCH_STREAM)
+        c.params_create(params)
+        c.param_grad_zero()
+        c.add_bulk(graphs[0])
+        c.upload()
+        reps = 2
+        for r in range(reps + 1):
+            if r == 1:
+                torch.cuda.synchronize()
+                t1 = time.perf_counter()
+            c.reset()
+            c.param_grad_zero()
+            c.forward(graphs[0].root)
+            c.backward(graphs[0].root)
+        torch.cuda.synchronize()
+        dt = (time.perf_counter() - t1) / reps
+        nobatch = dict(value=round(graphs[0].n_instances / dt, 2), unit="instances/s", ms_per_step=round(dt * 1e3, 2),
+                       speedup_autobatch=round(value / (graphs[0].n_instances / dt), 2))
+        c.close()
+
+    cpu = None
+    if not args.no_cpu:
+        from oracle.interp import Oracle
+        ns = max(1, min(args.cpu_samples, pool))
+        t1 = time.perf_counter()
+        inst = 0
+        for j in range(ns):
+            o = Oracle(graphs[j], params, "f32")
+            o.forward()
+            o.backward(graphs[j].root)
+            inst += graphs[j].n_instances
+        dt = time.perf_counter() - t1
+        cpu = dict(value=round(inst / dt, 2), unit="instances/s", cores=1, kind="oracle",
+                   sample=f"{ns} of the {pool} pooled minibatches ({inst} instances), fp32 build of the "
+                          f"node-at-a-time interpreter, forward+backward, 1 thread of {os.cpu_count()} host cores")
+
+    out = {
+        "metric": "training instances/sec (fwd+bwd, autobatched)",
+        "value": round(value, 2), "unit": "instances/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"config {cfg['index']}: {args.workload} (BASELINE.json configs[{cfg['index'] - 1}])",
+                   "instances_per_step": graphs[0].n_instances, "mode": "bydepth", "launch": args.launch,
+                   "pool": pool, "nodes_per_step": round(n_nodes / args.steps, 1)},
+        "nodes_per_s": round(n_nodes / elapsed, 1),
+        "phase_ms_per_step": {k_: round(v / args.steps, 4) for k_, v in phase.items()},
+        "launches_per_step": {k_: round(v / args.steps, 1) for k_, v in launches.items()},
+        "steps_levels": per_ctx_stats[0]["n_steps"], "batches": per_ctx_stats[0]["n_batches"],
+        "upload_ms_host_to_hbm": round(float(np.mean(t_up)) * 1e3, 3),
+        "value_including_upload": round(n_inst / (elapsed + float(np.mean(t_up)) * args.steps), 2),
+        "roofline": roofline,
+        "nobatch_gpu": nobatch,
+        "cpu_baseline": cpu,
+        "paper_context": "Table 1, BiLSTM, ByDepth on a Tesla K80: 337 sentences/s (other hardware and dimensions)",
+    }
+    print(json.dumps(out))
+    for c in ctxs:
+        c.close()
+
+
+if __name__ == "__main__":
+    main()

@@ -133,6 +133,10 @@ int ob_forward(ob_ctx *ctx, int node);
  * accumulate. */
 int ob_backward(ob_ctx *ctx, int node);
 int ob_sync(ob_ctx *ctx);
+/* Forgets the schedule, values and gradients of the current graph but keeps its nodes (and
+ * their device copy): the next ob_forward schedules and evaluates it again, e.g. after the
+ * parameters changed (the update step of Section 2's training loop). */
+int ob_reset(ob_ctx *ctx);
 
 /* ---- reads (synchronise the stream) ---------------------------------------------------------- */
 

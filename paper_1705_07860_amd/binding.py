@@ -90,6 +90,7 @@ def lib():
             "ob_forward": (i, [vp, i]),
             "ob_backward": (i, [vp, i]),
             "ob_sync": (i, [vp]),
+            "ob_reset": (i, [vp]),
             "ob_value_read": (i, [vp, i, vp, sz]),
             "ob_grad_read": (i, [vp, i, vp, sz]),
             "ob_all_read": (i, [vp, i, vp, sz]),
@@ -249,6 +250,9 @@ class Context:
 
     def sync(self):
         self._ck(self.L.ob_sync(self.h))
+
+    def reset(self):
+        self._ck(self.L.ob_reset(self.h))
 
     # -- reads
     def value_read(self, node: int, dim: int) -> np.ndarray:

@@ -585,6 +585,16 @@ int ob_backward(ob_ctx *ctx, int node)
     return OB_OK;
 }
 
+int ob_reset(ob_ctx *ctx)
+{
+    CHECK_CTX(ctx);
+    if (ctx->uploaded) HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
+    ctx->n_sched = 0;
+    ctx->forward_done = ctx->backward_done = false;
+    if (ctx->uploaded) ctx->top = ctx->graph_top;
+    return OB_OK;
+}
+
 int ob_sync(ob_ctx *ctx)
 {
     CHECK_CTX(ctx);
