@@ -197,7 +197,7 @@ int ob_graph_new(ob_ctx *ctx)
     ctx->param.clear(); ctx->bias.clear(); ctx->aux0.clear(); ctx->aux1.clear(); ctx->payload.clear();
     ctx->items_upto.clear();
     ctx->sum_out_dim = 0;
-    ctx->sum_mv_k = 0;
+    ctx->sum_mv_d32 = ctx->sum_mv_k32 = 0;
     ctx->top = ctx->persist_top;
     ctx->uploaded = false;
     ctx->n_sched = 0;
@@ -302,7 +302,8 @@ static int append_node(ob_ctx *ctx, int op, const u32 *ins, u32 arity, int param
     ctx->items_upto.push_back((ctx->items_upto.empty() ? 0u : ctx->items_upto.back()) + items);
     ctx->sum_out_dim += dim;
     if (op == OB_OP_MATVEC) {
-        ctx->sum_mv_k += (u64)ctx->params[param].cols;
+        ctx->sum_mv_d32 += (u64)ctx->params[param].rows / GT + 1;
+        ctx->sum_mv_k32 += (u64)ctx->params[param].cols / GT + 1;
         if (!ctx->params_used_w[param]) { ctx->params_used_w[param] = 1; ctx->params_dirty = true; }
         if (bias >= 0 && !ctx->params_used_b[bias]) { ctx->params_used_b[bias] = 1; ctx->params_dirty = true; }
     }
@@ -467,7 +468,7 @@ static int upload_param_tables(ob_ctx *ctx)
             for (int i0 = 0; i0 < hp.rows; i0 += GT)
                 for (int j0 = 0; j0 < hp.cols; j0 += GT) ctx->wtiles.push_back(PTile{(i32)p, i0, j0, 0});
         if (ctx->params_used_b[p])
-            for (int i0 = 0; i0 < hp.rows; i0 += WG) ctx->btiles.push_back(PTile{(i32)p, i0, 0, 0});
+            for (int i0 = 0; i0 < hp.rows; i0 += 32) ctx->btiles.push_back(PTile{(i32)p, i0, 0, 0});
     }
     ctx->params_dev = arena_array<ParamDesc>(ctx, desc.size() + 1);
     ctx->wtiles_dev = arena_array<PTile>(ctx, ctx->wtiles.size() + 1);

@@ -36,29 +36,48 @@ __device__ inline float wave_max(float v)
 // ------------------------------------------------------------------------------------------------
 // forward: component-wise / copy family
 // ------------------------------------------------------------------------------------------------
-__device__ inline float ew_value(const Tables &T, const BatchRec &r, u32 row, u32 col)
+// Element offset of operand slot j of batch row `row`.  When the descriptor says the tile's
+// operand rows are consecutive, the address is computed and the row-offset list is not read.
+__device__ inline u32 opnd_row(const Tables &T, const TileDesc &d, u32 j, u32 row)
 {
-    const u32 *opnd = T.opnd_off + r.opnd;
-    switch (r.op) {
-    case OP_INPUT: return T.payload[T.s_aux0[r.pos0 + row] + col];
+    // written slot by slot so that the descriptor stays in scalar registers (no dynamic indexing)
+    if (j == 0 && (d.contig & 1u)) return d.base[0] + (row - d.row0) * d.sdim[0];
+    if (j == 1 && (d.contig & 2u)) return d.base[1] + (row - d.row0) * d.sdim[1];
+    if (j == 2 && (d.contig & 4u)) return d.base[2] + (row - d.row0) * d.sdim[2];
+    if (j == 3 && (d.contig & 8u)) return d.base[3] + (row - d.row0) * d.sdim[3];
+    return T.opnd_off[d.opnd + j * d.B + row];
+}
+__device__ inline u32 slot_dim(const Tables &T, const TileDesc &d, u32 j)
+{
+    if (j == 0) return d.sdim[0];
+    if (j == 1) return d.sdim[1];
+    if (j == 2) return d.sdim[2];
+    if (j == 3) return d.sdim[3];
+    return T.b_indim[d.indim + j];
+}
+
+__device__ inline float ew_value(const Tables &T, const TileDesc &d, u32 row, u32 col)
+{
+    switch (d.op) {
+    case OP_INPUT: return T.payload[T.s_aux0[d.pos0 + row] + col];
     case OP_LOOKUP: {
-        const ParamDesc P = T.params[r.param];
-        return P.data[(size_t)T.s_aux0[r.pos0 + row] * P.cols + col];
+        const ParamDesc P = T.params[d.param];
+        return P.data[(size_t)T.s_aux0[d.pos0 + row] * P.cols + col];
     }
     case OP_ADD: {
         float acc = 0.f;
-        for (u32 j = 0; j < r.arity; ++j) acc += T.V[opnd[j * r.B + row] + col];
+        for (u32 j = 0; j < d.arity; ++j) acc += T.V[opnd_row(T, d, j, row) + col];
         return acc;
     }
-    case OP_CMULT: return T.V[opnd[row] + col] * T.V[opnd[r.B + row] + col];
-    case OP_TANH: return tanhf(T.V[opnd[row] + col]);
-    case OP_SIGMOID: return sigmoidf_(T.V[opnd[row] + col]);
-    case OP_SLICE: return T.V[opnd[row] + (u32)r.aux0 + col];
+    case OP_CMULT: return T.V[opnd_row(T, d, 0, row) + col] * T.V[opnd_row(T, d, 1, row) + col];
+    case OP_TANH: return tanhf(T.V[opnd_row(T, d, 0, row) + col]);
+    case OP_SIGMOID: return sigmoidf_(T.V[opnd_row(T, d, 0, row) + col]);
+    case OP_SLICE: return T.V[opnd_row(T, d, 0, row) + (u32)d.aux0 + col];
     case OP_CONCAT: {
         u32 c = col;
-        for (u32 j = 0; j < r.arity; ++j) {
-            const u32 dj = T.b_indim[r.indim + j];
-            if (c < dj) return T.V[opnd[j * r.B + row] + c];
+        for (u32 j = 0; j < d.arity; ++j) {
+            const u32 dj = slot_dim(T, d, j);
+            if (c < dj) return T.V[opnd_row(T, d, j, row) + c];
             c -= dj;
         }
         return 0.f;
@@ -67,41 +86,40 @@ __device__ inline float ew_value(const Tables &T, const BatchRec &r, u32 row, u3
     }
 }
 
-__device__ inline float4 ew_value4(const Tables &T, const BatchRec &r, u32 row, u32 col)
+__device__ inline float4 ew_value4(const Tables &T, const TileDesc &d, u32 row, u32 col)
 {
-    const u32 *opnd = T.opnd_off + r.opnd;
-    switch (r.op) {
-    case OP_INPUT: return ld4(T.payload + T.s_aux0[r.pos0 + row] + col);
+    switch (d.op) {
+    case OP_INPUT: return ld4(T.payload + T.s_aux0[d.pos0 + row] + col);
     case OP_LOOKUP: {
-        const ParamDesc P = T.params[r.param];
-        return ld4(P.data + (size_t)T.s_aux0[r.pos0 + row] * P.cols + col);
+        const ParamDesc P = T.params[d.param];
+        return ld4(P.data + (size_t)T.s_aux0[d.pos0 + row] * P.cols + col);
     }
     case OP_ADD: {
         float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
-        for (u32 j = 0; j < r.arity; ++j) {
-            const float4 x = ld4(T.V + opnd[j * r.B + row] + col);
+        for (u32 j = 0; j < d.arity; ++j) {
+            const float4 x = ld4(T.V + opnd_row(T, d, j, row) + col);
             acc.x += x.x; acc.y += x.y; acc.z += x.z; acc.w += x.w;
         }
         return acc;
     }
     case OP_CMULT: {
-        const float4 a = ld4(T.V + opnd[row] + col), b = ld4(T.V + opnd[r.B + row] + col);
+        const float4 a = ld4(T.V + opnd_row(T, d, 0, row) + col), b = ld4(T.V + opnd_row(T, d, 1, row) + col);
         return make_float4(a.x * b.x, a.y * b.y, a.z * b.z, a.w * b.w);
     }
     case OP_TANH: {
-        const float4 a = ld4(T.V + opnd[row] + col);
+        const float4 a = ld4(T.V + opnd_row(T, d, 0, row) + col);
         return make_float4(tanhf(a.x), tanhf(a.y), tanhf(a.z), tanhf(a.w));
     }
     case OP_SIGMOID: {
-        const float4 a = ld4(T.V + opnd[row] + col);
+        const float4 a = ld4(T.V + opnd_row(T, d, 0, row) + col);
         return make_float4(sigmoidf_(a.x), sigmoidf_(a.y), sigmoidf_(a.z), sigmoidf_(a.w));
     }
-    case OP_SLICE: return ld4(T.V + opnd[row] + (u32)r.aux0 + col);
+    case OP_SLICE: return ld4(T.V + opnd_row(T, d, 0, row) + (u32)d.aux0 + col);
     case OP_CONCAT: {
         u32 c = col;
-        for (u32 j = 0; j < r.arity; ++j) {
-            const u32 dj = T.b_indim[r.indim + j];
-            if (c < dj) return ld4(T.V + opnd[j * r.B + row] + c);
+        for (u32 j = 0; j < d.arity; ++j) {
+            const u32 dj = slot_dim(T, d, j);
+            if (c < dj) return ld4(T.V + opnd_row(T, d, j, row) + c);
             c -= dj;
         }
         return make_float4(0.f, 0.f, 0.f, 0.f);
@@ -110,17 +128,17 @@ __device__ inline float4 ew_value4(const Tables &T, const BatchRec &r, u32 row, 
     }
 }
 
-__device__ inline void ew_fwd_tile(const Tables &T, const BatchRec &r, u32 t)
+__device__ inline void ew_fwd_tile(const Tables &T, const TileDesc &d)
 {
-    const u32 total = r.B * r.d;
-    float *out = T.V + r.val_off;
-    if (r.vec4 & 1u) {
-        const u32 e = t * EW_TILE + threadIdx.x * 4;
-        if (e < total) st4(out + e, ew_value4(T, r, e / r.d, e % r.d));
+    const u32 total = d.B * d.d;
+    float *out = T.V + d.val_off;
+    if (d.flags & 1u) {
+        const u32 e = d.t * EW_TILE + threadIdx.x * 4;
+        if (e < total) st4(out + e, ew_value4(T, d, e / d.d, e % d.d));
     } else {
         for (int i = 0; i < EW_TILE / WG; ++i) {
-            const u32 e = t * EW_TILE + i * WG + threadIdx.x;
-            if (e < total) out[e] = ew_value(T, r, e / r.d, e % r.d);
+            const u32 e = d.t * EW_TILE + i * WG + threadIdx.x;
+            if (e < total) out[e] = ew_value(T, d, e / d.d, e % d.d);
         }
     }
 }
@@ -128,18 +146,18 @@ __device__ inline void ew_fwd_tile(const Tables &T, const BatchRec &r, u32 t)
 // ------------------------------------------------------------------------------------------------
 // forward: per-row reductions (one wave per row)
 // ------------------------------------------------------------------------------------------------
-__device__ inline void red_fwd_tile(const Tables &T, const BatchRec &r, u32 t)
+__device__ inline void red_fwd_tile(const Tables &T, const TileDesc &d)
 {
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
-    const u32 row = t * ROWS_PER_RED_TILE + w;
-    if (row >= r.B) return;
-    const float *x = T.V + T.opnd_off[r.opnd + row];
-    const u32 K = r.k;
-    if (r.op == OP_SQNORM) {
+    const u32 row = d.t * ROWS_PER_RED_TILE + w;
+    if (row >= d.B) return;
+    const float *x = T.V + opnd_row(T, d, 0, row);
+    const u32 K = d.k;
+    if (d.op == OP_SQNORM) {
         float acc = 0.f;
         for (u32 c = lane; c < K; c += 64) { const float a = x[c]; acc += a * a; }
         acc = wave_sum(acc);
-        if (lane == 0) T.V[r.val_off + row] = acc;
+        if (lane == 0) T.V[d.val_off + row] = acc;
     } else {  // OP_PICK_NLS: logsumexp(x) - x[label], shifted by the row maximum
         float mx = -INFINITY;
         for (u32 c = lane; c < K; c += 64) mx = fmaxf(mx, x[c]);
@@ -147,24 +165,25 @@ __device__ inline void red_fwd_tile(const Tables &T, const BatchRec &r, u32 t)
         float s = 0.f;
         for (u32 c = lane; c < K; c += 64) s += expf(x[c] - mx);
         s = wave_sum(s);
-        if (lane == 0) T.V[r.val_off + row] = mx + logf(s) - x[T.s_aux0[r.pos0 + row]];
+        if (lane == 0) T.V[d.val_off + row] = mx + logf(s) - x[T.s_aux0[d.pos0 + row]];
     }
 }
 
 // wide sum: one workgroup per row, operands strided over threads, fixed-shape tree in LDS
-__device__ inline void wide_add_tile(const Tables &T, const BatchRec &r, u32 row, float *lds)
+__device__ inline void wide_add_tile(const Tables &T, const TileDesc &d, float *lds)
 {
-    const u32 *opnd = T.opnd_off + r.opnd;
-    for (u32 c = 0; c < r.d; ++c) {
+    const u32 row = d.t;
+    const u32 *opnd = T.opnd_off + d.opnd;
+    for (u32 c = 0; c < d.d; ++c) {
         float acc = 0.f;
-        for (u32 j = threadIdx.x; j < r.arity; j += WG) acc += T.V[opnd[j * r.B + row] + c];
+        for (u32 j = threadIdx.x; j < d.arity; j += WG) acc += T.V[opnd[j * d.B + row] + c];
         lds[threadIdx.x] = acc;
         __syncthreads();
         for (int o = WG / 2; o > 0; o >>= 1) {
             if ((int)threadIdx.x < o) lds[threadIdx.x] += lds[threadIdx.x + o];
             __syncthreads();
         }
-        if (threadIdx.x == 0) T.V[r.val_off + row * r.d + c] = lds[0];
+        if (threadIdx.x == 0) T.V[d.val_off + row * d.d + c] = lds[0];
         __syncthreads();
     }
 }
@@ -173,7 +192,9 @@ __device__ inline void wide_add_tile(const Tables &T, const BatchRec &r, u32 row
 // MFMA tile: one 32x32 fp32 accumulator block per workgroup; the 4 waves split the contraction
 // and their partial blocks are summed through LDS in wave order.
 // v_mfma_f32_32x32x2f32: lane l supplies A[l%32][l/32] and B[l/32][l%32]; accumulator register v
-// of lane l is C[8*(v/4) + 4*(l/32) + v%4][l%32].
+// of lane l is C[8*(v/4) + 4*(l/32) + v%4][l%32].  The contraction index may be permuted freely as
+// long as A and B use the same permutation: within a block of 8, lane half h takes the four
+// consecutive indices 4h..4h+3, so that K-contiguous operands are read as one float4.
 // ------------------------------------------------------------------------------------------------
 __device__ inline floatx16 mfma4(float4 a, float4 b, floatx16 acc)
 {
@@ -215,40 +236,46 @@ __device__ inline void wave_range(u32 total, u32 &lo, u32 &hi)
     if (hi > pad) hi = pad;
 }
 
-// Y[B x m] = X[B x K] W^T + b.   X rows gathered by offset `xoff(row)`, W row-major [m x K].
-template <typename XOff>
-__device__ inline void gemm_nt_tile(const float *Xbase, XOff xoff, u32 B, const float *W, const float *bias, u32 m,
+constexpr int KU = 4;   // blocks of 8 contraction indices whose loads are issued together
+
+// Y[B x m] = X[B x K] W^T + b.   xrow: this lane's X row (valid when row_ok), W row-major [m x K].
+__device__ inline void gemm_nt_tile(const float *xrow, bool row_ok, u32 B, const float *W, const float *bias, u32 m,
                                     u32 K, bool fast, float *Y, u32 r0, u32 i0, float *lds)
 {
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
     const u32 l32 = lane & 31, h = lane >> 5;
-    const u32 row = r0 + l32, col = i0 + l32;
-    const bool row_ok = row < B, col_ok = col < m;
-    const float *xrow = Xbase + (row_ok ? xoff(row) : 0u);
+    const u32 col = i0 + l32;
+    const bool col_ok = col < m;
     const float *wrow = W + (size_t)(col_ok ? col : 0u) * K;
     u32 lo, hi;
     wave_range(K, lo, hi);
-    floatx16 acc = {0.f};
+    floatx16 acc;
     for (int v = 0; v < 16; ++v) acc[v] = 0.f;
-    for (u32 kb = lo; kb < hi; kb += 8) {
-        const u32 k0 = kb + 4 * h;
-        float4 a = make_float4(0.f, 0.f, 0.f, 0.f), b = a;
-        if (fast) {
-            if (k0 < K) {
-                if (row_ok) a = ld4(xrow + k0);
-                if (col_ok) b = ld4(wrow + k0);
+    const float4 z4 = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (fast) {
+        for (u32 kb = lo; kb < hi; kb += 8 * KU) {
+            float4 a[KU], b[KU];
+#pragma unroll
+            for (int u = 0; u < KU; ++u) {
+                const u32 k0 = kb + 8 * u + 4 * h;
+                const bool in = kb + 8 * u < hi && k0 < K;
+                a[u] = (in && row_ok) ? ld4(xrow + k0) : z4;
+                b[u] = (in && col_ok) ? ld4(wrow + k0) : z4;
             }
-        } else {
+#pragma unroll
+            for (int u = 0; u < KU; ++u) acc = mfma4(a[u], b[u], acc);
+        }
+    } else {
+        for (u32 kb = lo; kb < hi; kb += 8) {
+            const u32 k0 = kb + 4 * h;
             float av[4] = {0.f, 0.f, 0.f, 0.f}, bv[4] = {0.f, 0.f, 0.f, 0.f};
             for (int s = 0; s < 4; ++s)
                 if (k0 + s < K) {
                     if (row_ok) av[s] = xrow[k0 + s];
                     if (col_ok) bv[s] = wrow[k0 + s];
                 }
-            a = make_float4(av[0], av[1], av[2], av[3]);
-            b = make_float4(bv[0], bv[1], bv[2], bv[3]);
+            acc = mfma4(make_float4(av[0], av[1], av[2], av[3]), make_float4(bv[0], bv[1], bv[2], bv[3]), acc);
         }
-        acc = mfma4(a, b, acc);
     }
     float out[4];
     reduce_waves(acc, lds, out);
@@ -261,54 +288,75 @@ __device__ inline void gemm_nt_tile(const float *Xbase, XOff xoff, u32 B, const 
     }
 }
 
-__device__ inline void matvec_fwd_tile(const Tables &T, const BatchRec &r, u32 t, float *lds)
+__device__ inline void matvec_fwd_tile(const Tables &T, const TileDesc &d, float *lds)
 {
-    const u32 ntn = (r.d + GT - 1) / GT;
-    const u32 r0 = (t / ntn) * GT, i0 = (t % ntn) * GT;
-    const ParamDesc P = T.params[r.param];
-    const float *bias = r.bias >= 0 ? T.params[r.bias].data : nullptr;
-    const u32 *opnd = T.opnd_off + r.opnd;
-    const bool fast = (r.vec4 & 2u) && (r.k & 3u) == 0;
-    gemm_nt_tile(T.V, [opnd](u32 row) { return opnd[row]; }, r.B, P.data, bias, r.d, r.k, fast, T.V + r.val_off, r0,
-                 i0, lds);
+    const u32 ntn = (d.d + GT - 1) / GT;
+    const u32 r0 = (d.t / ntn) * GT, i0 = (d.t % ntn) * GT;
+    const ParamDesc P = T.params[d.param];
+    const float *bias = d.bias >= 0 ? T.params[d.bias].data : nullptr;
+    const bool fast = (d.flags & 2u) && (d.k & 3u) == 0;
+    const u32 row = r0 + (threadIdx.x & 31);
+    const bool row_ok = row < d.B;
+    const float *xrow = T.V + (row_ok ? opnd_row(T, d, 0, row) : 0u);
+    gemm_nt_tile(xrow, row_ok, d.B, P.data, bias, d.d, d.k, fast, T.V + d.val_off, r0, i0, lds);
 }
 
 // dX[B x K] = G[B x m] W, contraction over m.  G rows are the batch's own contiguous block.
-__device__ inline void matvec_dx_tile(const Tables &T, const BatchRec &r, u32 t, float *lds)
+__device__ inline void matvec_dx_tile(const Tables &T, const TileDesc &d, float *lds)
 {
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
     const u32 l32 = lane & 31, h = lane >> 5;
-    const u32 K = r.k, m = r.d;
+    const u32 K = d.k, m = d.d;
     const u32 ntn = (K + GT - 1) / GT;
-    const u32 r0 = (t / ntn) * GT, c0 = (t % ntn) * GT;
-    const ParamDesc P = T.params[r.param];
+    const u32 r0 = (d.t / ntn) * GT, c0 = (d.t % ntn) * GT;
+    const ParamDesc P = T.params[d.param];
     const u32 row = r0 + l32, col = c0 + l32;
-    const bool row_ok = row < r.B, col_ok = col < K;
-    const float *grow = T.G + r.val_off + (size_t)(row_ok ? row : 0u) * m;
+    const bool row_ok = row < d.B, col_ok = col < K;
+    const float *grow = T.G + d.val_off + (size_t)(row_ok ? row : 0u) * m;
     const float *wcol = P.data + (col_ok ? col : 0u);
     const bool fast = (m & 3u) == 0;
     u32 lo, hi;
     wave_range(m, lo, hi);
     floatx16 acc;
     for (int v = 0; v < 16; ++v) acc[v] = 0.f;
-    for (u32 ib = lo; ib < hi; ib += 8) {
-        const u32 i0 = ib + 4 * h;
-        float av[4] = {0.f, 0.f, 0.f, 0.f}, bv[4] = {0.f, 0.f, 0.f, 0.f};
-        if (fast) {
-            if (i0 < m && row_ok) { const float4 a = ld4(grow + i0); av[0] = a.x; av[1] = a.y; av[2] = a.z; av[3] = a.w; }
-        } else {
-            for (int s = 0; s < 4; ++s) if (i0 + s < m && row_ok) av[s] = grow[i0 + s];
+    const float4 z4 = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (fast) {
+        for (u32 ib = lo; ib < hi; ib += 8 * KU) {
+            float4 a[KU], b[KU];
+#pragma unroll
+            for (int u = 0; u < KU; ++u) {
+                const u32 i0 = ib + 8 * u + 4 * h;
+                const bool in = ib + 8 * u < hi && i0 < m;
+                a[u] = (in && row_ok) ? ld4(grow + i0) : z4;
+                if (in && col_ok) {
+                    const float *wp = wcol + (size_t)i0 * K;
+                    b[u] = make_float4(wp[0], wp[K], wp[2 * (size_t)K], wp[3 * (size_t)K]);
+                } else {
+                    b[u] = z4;
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < KU; ++u) acc = mfma4(a[u], b[u], acc);
         }
-        for (int s = 0; s < 4; ++s) if (i0 + s < m && col_ok) bv[s] = wcol[(size_t)(i0 + s) * K];
-        acc = mfma4(make_float4(av[0], av[1], av[2], av[3]), make_float4(bv[0], bv[1], bv[2], bv[3]), acc);
+    } else {
+        for (u32 ib = lo; ib < hi; ib += 8) {
+            const u32 i0 = ib + 4 * h;
+            float av[4] = {0.f, 0.f, 0.f, 0.f}, bv[4] = {0.f, 0.f, 0.f, 0.f};
+            for (int s = 0; s < 4; ++s)
+                if (i0 + s < m) {
+                    if (row_ok) av[s] = grow[i0 + s];
+                    if (col_ok) bv[s] = wcol[(size_t)(i0 + s) * K];
+                }
+            acc = mfma4(make_float4(av[0], av[1], av[2], av[3]), make_float4(bv[0], bv[1], bv[2], bv[3]), acc);
+        }
     }
     float out[4];
     reduce_waves(acc, lds, out);
     if (col_ok) {
-        float *dX = T.G + r.dx_off;
+        float *dX = T.G + d.dx_off;
         for (int i = 0; i < 4; ++i) {
             const u32 rr = r0 + 8 * w + 4 * h + i;
-            if (rr < r.B) dX[(size_t)rr * K + col] = out[i];
+            if (rr < d.B) dX[(size_t)rr * K + col] = out[i];
         }
     }
 }
@@ -329,15 +377,30 @@ __device__ inline void param_w_tile(const Tables &T, const PTile &pt, float *lds
     wave_range(end - start, lo, hi);
     floatx16 acc;
     for (int v = 0; v < 16; ++v) acc[v] = 0.f;
-    for (u32 ib = lo; ib < hi; ib += 8) {
-        float av[4], bv[4];
-        for (int s = 0; s < 4; ++s) {
-            const u32 it = start + ib + 4 * h + s;
-            const bool ok = it < end;
-            av[s] = (ok && i_ok) ? T.G[T.it_goff[it] + i] : 0.f;
-            bv[s] = (ok && j_ok) ? T.V[T.it_xoff[it] + j] : 0.f;
-        }
-        acc = mfma4(make_float4(av[0], av[1], av[2], av[3]), make_float4(bv[0], bv[1], bv[2], bv[3]), acc);
+    for (u32 ib = lo; ib < hi; ib += 8 * KU) {
+        u32 go[KU][4], xo[KU][4];
+        bool ok[KU][4];
+#pragma unroll
+        for (int u = 0; u < KU; ++u)
+#pragma unroll
+            for (int s = 0; s < 4; ++s) {
+                const u32 it = start + ib + 8 * u + 4 * h + s;
+                ok[u][s] = ib + 8 * u < hi && it < end;
+                go[u][s] = ok[u][s] ? T.it_goff[it] : 0u;
+                xo[u][s] = ok[u][s] ? T.it_xoff[it] : 0u;
+            }
+        float av[KU][4], bv[KU][4];
+#pragma unroll
+        for (int u = 0; u < KU; ++u)
+#pragma unroll
+            for (int s = 0; s < 4; ++s) {
+                av[u][s] = (ok[u][s] && i_ok) ? T.G[go[u][s] + i] : 0.f;
+                bv[u][s] = (ok[u][s] && j_ok) ? T.V[xo[u][s] + j] : 0.f;
+            }
+#pragma unroll
+        for (int u = 0; u < KU; ++u)
+            acc = mfma4(make_float4(av[u][0], av[u][1], av[u][2], av[u][3]),
+                        make_float4(bv[u][0], bv[u][1], bv[u][2], bv[u][3]), acc);
     }
     float out[4];
     reduce_waves(acc, lds, out);
@@ -349,53 +412,84 @@ __device__ inline void param_w_tile(const Tables &T, const PTile &pt, float *lds
     }
 }
 
-// db[i] += sum over uses of g[i]; one thread per row, uses in sorted order
-__device__ inline void param_b_tile(const Tables &T, const PTile &pt)
+// db[i] += sum over uses of g[i].  A tile is 32 rows; the 8 groups of 32 threads take every 8th
+// use and their partial sums are added in group order.
+__device__ inline void param_b_tile(const Tables &T, const PTile &pt, float *lds)
 {
     const u32 slot = (u32)pt.param * 4u + 1u;
     const u32 start = T.pu_start[slot], end = T.pu_end[slot];
     if (start == end) return;
     const ParamDesc P = T.params[pt.param];
-    const u32 i = (u32)pt.i0 + threadIdx.x;
-    if (i >= (u32)P.rows) return;
+    const u32 l32 = threadIdx.x & 31, grp = threadIdx.x >> 5;
+    const u32 i = (u32)pt.i0 + l32;
+    const bool i_ok = i < (u32)P.rows;
     float acc = 0.f;
-    for (u32 it = start; it < end; ++it) acc += T.G[T.it_goff[it] + i];
-    P.grad[i] += acc;
+    for (u32 it0 = start + grp; it0 < end; it0 += 8 * 4) {
+        u32 go[4];
+        bool ok[4];
+#pragma unroll
+        for (int s = 0; s < 4; ++s) { const u32 it = it0 + 8 * s; ok[s] = it < end; go[s] = ok[s] ? T.it_goff[it] : 0u; }
+        float g[4];
+#pragma unroll
+        for (int s = 0; s < 4; ++s) g[s] = (ok[s] && i_ok) ? T.G[go[s] + i] : 0.f;
+        acc += (g[0] + g[1]) + (g[2] + g[3]);
+    }
+    lds[grp * 32 + l32] = acc;
+    __syncthreads();
+    if (grp == 0 && i_ok) {
+        float s = 0.f;
+        for (int q = 0; q < 8; ++q) s += lds[q * 32 + l32];
+        P.grad[i] += s;
+    }
 }
 
 // ------------------------------------------------------------------------------------------------
 // backward pull: gradient of every node of a batch from its consumer edges
 // ------------------------------------------------------------------------------------------------
-__device__ inline void pull_tile(const Tables &T, const BatchRec &r, u32 t)
+__device__ inline float edge_term(const Tables &T, u32 kind, u32 goff, u32 voff, i32 a0, i32 a1, u32 own, u32 col)
 {
-    const u32 total = r.B * r.d;
+    switch (kind) {
+    case EK_PLAIN: return T.G[goff + col];
+    case EK_RANGE: return ((i32)col >= a0 && (i32)col < a1) ? T.G[goff + col - (u32)a0] : 0.f;
+    case EK_MUL: return T.G[goff + col] * T.V[voff + col];
+    case EK_DTANH: { const float y = T.V[voff + col]; return T.G[goff + col] * (1.0f - y * y); }
+    case EK_DSIGM: { const float y = T.V[voff + col]; return T.G[goff + col] * y * (1.0f - y); }
+    case EK_NLS: {
+        const float lse = T.V[voff] + T.V[own + (u32)a0];
+        float p = expf(T.V[own + col] - lse);
+        if ((i32)col == a0) p -= 1.0f;
+        return T.G[goff] * p;
+    }
+    case EK_SQN: return 2.0f * T.G[goff] * T.V[own + col];
+    default: return 0.f;
+    }
+}
+
+__device__ inline void pull_tile(const Tables &T, const PullDesc &d)
+{
+    const u32 total = d.B * d.d;
+    const u32 root_pos = T.root_pos[0];
     for (int i = 0; i < EW_TILE / WG; ++i) {
-        const u32 e = t * EW_TILE + i * WG + threadIdx.x;
+        const u32 e = d.t * EW_TILE + i * WG + threadIdx.x;
         if (e >= total) continue;
-        const u32 row = e / r.d, col = e % r.d;
-        const u32 u = T.order[r.pos0 + row];
-        const u32 q1 = T.succ_off[u + 1];
-        const u32 own = r.val_off + row * r.d;
-        float acc = (u == T.root) ? 1.0f : 0.0f;
-        for (u32 q = T.succ_off[u]; q < q1; ++q) {
-            const EdgeRec er = T.edges[q];
-            switch (er.kind) {
-            case EK_PLAIN: acc += T.G[er.goff + col]; break;
-            case EK_RANGE:
-                if ((i32)col >= er.a0 && (i32)col < er.a1) acc += T.G[er.goff + col - (u32)er.a0];
-                break;
-            case EK_MUL: acc += T.G[er.goff + col] * T.V[er.voff + col]; break;
-            case EK_DTANH: { const float y = T.V[er.voff + col]; acc += T.G[er.goff + col] * (1.0f - y * y); break; }
-            case EK_DSIGM: { const float y = T.V[er.voff + col]; acc += T.G[er.goff + col] * y * (1.0f - y); break; }
-            case EK_NLS: {
-                const float lse = T.V[er.voff] + T.V[own + (u32)er.a0];
-                float p = expf(T.V[own + col] - lse);
-                if ((i32)col == er.a0) p -= 1.0f;
-                acc += T.G[er.goff] * p;
-                break;
+        const u32 row = e / d.d, col = e % d.d;
+        const u32 own = d.val_off + row * d.d;
+        float acc = (d.pos0 + row == root_pos) ? 1.0f : 0.0f;
+        if (d.n_uni != PULL_GENERIC) {
+            const u32 dr = row - d.row0;
+#pragma unroll
+            for (u32 j = 0; j < 4; ++j) {
+                if (j < d.n_uni) {
+                    const UEdge ue = d.e[j];
+                    acc += edge_term(T, ue.kind, ue.goff + dr * ue.gs, ue.voff + dr * ue.vs, ue.a0, ue.a1, own, col);
+                }
             }
-            case EK_SQN: acc += 2.0f * T.G[er.goff] * T.V[own + col]; break;
-            default: break;
+        } else {
+            const u32 u = T.order[d.pos0 + row];
+            const u32 q1 = T.succ_off[u + 1];
+            for (u32 q = T.succ_off[u]; q < q1; ++q) {
+                const EdgeRec er = T.edges[q];
+                acc += edge_term(T, er.kind, er.goff, er.voff, er.a0, er.a1, own, col);
             }
         }
         T.G[own + col] = acc;
@@ -411,17 +505,16 @@ __global__ __launch_bounds__(WG) void k_fwd_step(Tables T, u32 tile_lo, u32 tile
 {
     __shared__ float lds[LDS_FLOATS];
     for (u32 tile = tile_lo + blockIdx.x; tile < tile_hi; tile += gridDim.x) {
-        const TileRec tr = T.tiles_f[tile];
-        const BatchRec r = T.batches[tr.batch];
-        switch (r.op) {
-        case OP_MATVEC: matvec_fwd_tile(T, r, tr.t, lds); break;
+        const TileDesc d = T.tiles_f[tile];
+        switch (d.op) {
+        case OP_MATVEC: matvec_fwd_tile(T, d, lds); break;
         case OP_PICK_NLS:
-        case OP_SQNORM: red_fwd_tile(T, r, tr.t); break;
+        case OP_SQNORM: red_fwd_tile(T, d); break;
         case OP_ADD:
-            if (r.arity >= (u32)WIDE_ADD_ARITY) { wide_add_tile(T, r, tr.t, lds); break; }
-            ew_fwd_tile(T, r, tr.t);
+            if (d.arity >= (u32)WIDE_ADD_ARITY) { wide_add_tile(T, d, lds); break; }
+            ew_fwd_tile(T, d);
             break;
-        default: ew_fwd_tile(T, r, tr.t); break;
+        default: ew_fwd_tile(T, d); break;
         }
     }
 }
@@ -429,9 +522,8 @@ __global__ __launch_bounds__(WG) void k_fwd_step(Tables T, u32 tile_lo, u32 tile
 __global__ __launch_bounds__(WG) void k_bwd_pull_step(Tables T, u32 tile_lo, u32 tile_hi)
 {
     for (u32 tile = tile_lo + blockIdx.x; tile < tile_hi; tile += gridDim.x) {
-        const TileRec tr = T.tiles_a[tile];
-        const BatchRec r = T.batches[tr.batch];
-        pull_tile(T, r, tr.t);
+        const PullDesc d = T.tiles_a[tile];
+        pull_tile(T, d);
     }
 }
 
@@ -439,11 +531,12 @@ __global__ __launch_bounds__(WG) void k_bwd_dx_step(Tables T, u32 tile_lo, u32 t
 {
     __shared__ float lds[LDS_FLOATS];
     for (u32 tile = tile_lo + blockIdx.x; tile < tile_hi; tile += gridDim.x) {
-        const TileRec tr = T.tiles_b[tile];
-        const BatchRec r = T.batches[tr.batch];
-        matvec_dx_tile(T, r, tr.t, lds);
+        const TileDesc d = T.tiles_b[tile];
+        matvec_dx_tile(T, d, lds);
     }
 }
+
+__global__ void k_set_root(Tables T) { T.root_pos[0] = T.pos_of[T.root]; }
 
 __global__ __launch_bounds__(WG) void k_param_w(Tables T, const PTile *tiles)
 {
@@ -453,7 +546,8 @@ __global__ __launch_bounds__(WG) void k_param_w(Tables T, const PTile *tiles)
 
 __global__ __launch_bounds__(WG) void k_param_b(Tables T, const PTile *tiles)
 {
-    param_b_tile(T, tiles[blockIdx.x]);
+    __shared__ float lds[WG];
+    param_b_tile(T, tiles[blockIdx.x], lds);
 }
 
 // dE[row, :] += sum of the gradients of every LOOKUP of (table, row): one wave per run of equal
@@ -495,7 +589,10 @@ __global__ __launch_bounds__(WG) void k_test_gemm(const float *A, const float *B
     const u32 ntn = (N + GT - 1) / GT;
     const u32 r0 = (blockIdx.x / ntn) * GT, i0 = (blockIdx.x % ntn) * GT;
     const u32 Ku = (u32)K;
-    gemm_nt_tile(A, [Ku](u32 row) { return row * Ku; }, (u32)M, Bm, nullptr, (u32)N, Ku, (Ku & 3u) == 0, C, r0, i0, lds);
+    const u32 row = r0 + (threadIdx.x & 31);
+    const bool row_ok = row < (u32)M;
+    gemm_nt_tile(A + (size_t)(row_ok ? row : 0u) * Ku, row_ok, (u32)M, Bm, nullptr, (u32)N, Ku, (Ku & 3u) == 0, C, r0,
+                 i0, lds);
 }
 
 inline u32 grid_for(u32 tiles, u32 cap) { return tiles < cap ? tiles : cap; }
@@ -525,6 +622,8 @@ static int launch_backward_steps(ob_ctx *ctx)
     const Tables &T = ctx->T;
     hipStream_t s = ctx->stream;
     const u32 ns = ctx->hdr.n_steps;
+    hipLaunchKernelGGL(k_set_root, dim3(1), dim3(1), 0, s, T);
+    ++ctx->n_launch_bwd;
     for (u32 st = ns; st-- > 0;) {
         const u32 alo = ctx->step_ta[st], ahi = ctx->step_ta[st + 1];
         if (ahi > alo) {

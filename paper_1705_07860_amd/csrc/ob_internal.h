@@ -54,7 +54,7 @@ struct BatchRec {  // one per batch, 64 bytes
     u32 opnd;            // base into opnd_off[], slot-major: opnd_off[opnd + j*B + r]
     u32 k;               // dimension of operand 0 (MATVEC: columns of W)
     u32 indim;           // base into b_indim[] (operand dimensions, `arity` entries)
-    u32 vec4;            // 1 when every row and operand row is 16-byte aligned and d % 4 == 0
+    u32 vec4;            // bit 0: float4 component-wise path allowed; bit 1: operand rows 16-byte aligned
 };
 
 struct ParamDesc {
@@ -63,7 +63,37 @@ struct ParamDesc {
     i32 rows, cols;
 };
 
-struct TileRec { u32 batch, t; };
+// One forward (or dX) tile: everything the tile routine needs in one 128-byte record, so that a
+// workgroup starts its data loads after a single descriptor load.  For up to four operand slots
+// the record says whether the operand rows of THIS tile are consecutive in the value arena
+// (then row r of slot j sits at base[j] + (r - row0) * sdim[j] and the row-offset list is not
+// read at all: the inputs are used as they are, without an index hop).
+struct TileDesc {
+    u32 op, B, d, arity;
+    u32 pos0, val_off, dx_off, k;
+    i32 param, bias, aux0, aux1;
+    u32 opnd, indim, flags, t;       // flags: bit 0 float4 path allowed, bit 1 operand rows 16-byte aligned
+    u32 contig, row0;                // contig bit j: slot j consecutive over the rows of this tile
+    u32 base[4];
+    u32 sdim[4];                     // dimension of operand slot j
+    u32 pad[6];
+};
+static_assert(sizeof(TileDesc) == 128, "TileDesc must be 128 bytes");
+
+// A consumer edge that is the same for every row of a pull tile up to constant row strides.
+struct UEdge { u32 kind, goff, voff, gs, vs; i32 a0, a1; };
+
+// One backward pull tile.  n_uni <= 4: every row of the tile has exactly n_uni consumer edges and
+// edge j of row r is e[j] shifted by (r - row0) * (gs, vs); n_uni == PULL_GENERIC: rows differ,
+// walk the consumer CSR per element.
+constexpr u32 PULL_GENERIC = 0xffffffffu;
+struct PullDesc {
+    u32 pos0, B, d, val_off;
+    u32 t, row0, n_uni, flags;
+    UEdge e[4];
+    u32 pad[4];
+};
+static_assert(sizeof(PullDesc) == 160, "PullDesc must be 160 bytes");
 
 // Static tile of the deferred parameter-gradient kernels (built on the host per parameter set).
 struct PTile { i32 param; i32 i0, j0; i32 pad; };
@@ -104,7 +134,8 @@ struct Tables {
     u32 *batch_off; BatchRec *batches; Lay *lay; u32 *b_indim;
     u32 *val_off; u32 *dx_off; u32 *opnd_off;
     u32 *step_first; u32 *step_tf; u32 *step_ta; u32 *step_tb;
-    TileRec *tiles_f; TileRec *tiles_a; TileRec *tiles_b;
+    TileDesc *tiles_f; PullDesc *tiles_a; TileDesc *tiles_b;
+    u32 *root_pos;         // [0] = schedule position of the backward root
     EdgeRec *edges;
     // parameter-use items (deferred dW / db / dE)
     u64 *it_key; u32 *it_pos; u32 *it_goff; u32 *it_xoff; u32 *pu_start; u32 *pu_end;

@@ -22,7 +22,9 @@ __device__ inline u64 comb(u64 h, u64 x) { return mix64(h ^ (x + 0x9e3779b97f4a7
 // ---- stage 1: signatures, dependency counters, out-degrees, initial frontier ---------------
 // Signature tuple (Section 3.2 / Appendix A): operation, output dimension, arity, shared
 // parameter ids (the A and y of A x + y), slice range, operand dimensions.  LOOKUP's row,
-// PICK_NLS's label and INPUT's payload are data and stay out.
+// PICK_NLS's label and INPUT's payload are data and stay out.  The node's own fields are hashed
+// here; every operand edge then adds a position-salted hash of the operand's dimension
+// (k_edge_init), so nodes with thousands of operands cost no more than a thread per edge.
 __global__ void k_node_init(Tables T, int by_depth)
 {
     const u32 v = blockIdx.x * blockDim.x + threadIdx.x;
@@ -36,12 +38,6 @@ __global__ void k_node_init(Tables T, int by_depth)
     h = comb(h, (u64)(u32)(T.bias[v] + 1));
     h = comb(h, o == OP_SLICE ? (u64)(u32)T.aux0[v] : 0);
     h = comb(h, o == OP_SLICE ? (u64)(u32)T.aux1[v] : 0);
-    for (u32 e = lo; e < hi; ++e) {
-        const u32 u = T.in_idx[e];
-        h = comb(h, T.out_dim[u]);
-        T.edge_cons[e] = v;
-        atomicAdd(&T.outdeg[u], 1u);
-    }
     T.sig[v] = h;
     T.indeg[v] = hi - lo;
     if (by_depth) {
@@ -55,11 +51,28 @@ __global__ void k_node_init(Tables T, int by_depth)
     }
 }
 
-__global__ void k_edge_keys(Tables T, u64 *keys, u32 *vals)
+// consumer node of edge e: the v with in_off[v] <= e < in_off[v+1]
+__device__ inline u32 consumer_of(const Tables &T, u32 e)
+{
+    u32 lo = 0, hi = T.n;   // invariant: in_off[lo] <= e < in_off[hi]
+    while (hi - lo > 1) {
+        const u32 mid = (lo + hi) >> 1;
+        if (T.in_off[mid] <= e) lo = mid; else hi = mid;
+    }
+    return lo;
+}
+
+__global__ void k_edge_init(Tables T, u64 *keys, u32 *vals)
 {
     const u32 e = blockIdx.x * blockDim.x + threadIdx.x;
     if (e >= T.E) return;
-    keys[e] = T.in_idx[e];
+    const u32 v = consumer_of(T, e);
+    const u32 u = T.in_idx[e];
+    const u32 j = e - T.in_off[v];
+    T.edge_cons[e] = v;
+    atomicAdd(&T.outdeg[u], 1u);
+    atomicAdd((unsigned long long *)&T.sig[v], (unsigned long long)mix64(comb(0x5bd1e995ULL + j, T.out_dim[u])));
+    keys[e] = u;
     vals[e] = e;
 }
 
@@ -258,65 +271,167 @@ __global__ void k_node_offsets(Tables T)
     T.dx_off[v] = (r.op == OP_MATVEC) ? r.dx_off + row * r.k : 0u;
 }
 
-// operand row offsets per batch (slot-major), operand dimensions, alignment flag, and the
-// check that every member of a batch really has the signature tuple of the batch head
-// (a 64-bit hash collision would otherwise merge incompatible nodes).
-__global__ void k_opnd(Tables T)
+// Per node: the check that every member of a batch really has the signature tuple of the batch
+// head (a 64-bit hash collision would otherwise merge incompatible nodes), and whether the
+// float4 component-wise path is allowed.
+__global__ void k_member_check(Tables T)
 {
     const u32 p = blockIdx.x * blockDim.x + threadIdx.x;
     if (p >= T.n) return;
-    const u32 b = T.batch_of_pos[p];
-    BatchRec &r = T.batches[b];
-    const u32 row = p - r.pos0;
+    BatchRec &r = T.batches[T.batch_of_pos[p]];
     const u32 v = T.order[p];
-    const u32 lo = T.in_off[v];
-    const u32 ar = T.in_off[v + 1] - lo;
-    const u32 h = T.order[r.pos0];
+    const u32 ar = T.in_off[v + 1] - T.in_off[v];
     bool same = T.op[v] == r.op && T.out_dim[v] == r.d && ar == r.arity && T.param[v] == r.param &&
                 T.bias[v] == r.bias && T.step[v] == r.step;
     if (r.op == OP_SLICE) same = same && T.aux0[v] == r.aux0 && T.aux1[v] == r.aux1;
-    bool vec = (r.d & 3u) == 0, aligned = true;
+    bool vec = (r.d & 3u) == 0;
     if (r.op == OP_SLICE) vec = vec && ((u32)r.aux0 & 3u) == 0;
     if (r.op == OP_INPUT) vec = vec && ((u32)T.aux0[v] & 3u) == 0;
-    if (same) {
-        const u32 hlo = T.in_off[h];
-        for (u32 j = 0; j < ar; ++j) {
-            const u32 u = T.in_idx[lo + j];
-            const u32 du = T.out_dim[u];
-            if (du != T.out_dim[T.in_idx[hlo + j]]) same = false;
-            const u32 off = T.val_off[u];
-            T.opnd_off[r.opnd + j * r.B + row] = off;
-            if (row == 0) T.b_indim[r.indim + j] = du;
-            if (off & 3u) aligned = false;
-            if (r.op == OP_CONCAT && (du & 3u)) vec = false;
-        }
-    }
     if (!same) atomicOr(&T.hdr->err, (u32)ERR_COLLISION);
-    if (!aligned) atomicAnd(&r.vec4, 0u);
-    else if (!vec) atomicAnd(&r.vec4, 2u);
+    if (!vec) atomicAnd(&r.vec4, 2u);
 }
 
-// materialised tile lists: tile index -> (batch, tile inside the batch)
+// Per edge: operand row offsets per batch (slot-major), operand dimensions of the batch, the
+// operand part of the membership check, and the alignment flags.
+__global__ void k_opnd(Tables T)
+{
+    const u32 e = blockIdx.x * blockDim.x + threadIdx.x;
+    if (e >= T.E) return;
+    const u32 v = T.edge_cons[e];
+    const u32 j = e - T.in_off[v];
+    const u32 p = T.pos_of[v];
+    BatchRec &r = T.batches[T.batch_of_pos[p]];
+    const u32 row = p - r.pos0;
+    const u32 h = T.order[r.pos0];
+    const u32 u = T.in_idx[e];
+    const u32 du = T.out_dim[u];
+    if (j >= r.arity || du != T.out_dim[T.in_idx[T.in_off[h] + j]]) {
+        atomicOr(&T.hdr->err, (u32)ERR_COLLISION);
+        return;
+    }
+    const u32 off = T.val_off[u];
+    T.opnd_off[r.opnd + j * r.B + row] = off;
+    if (row == 0) T.b_indim[r.indim + j] = du;
+    if (off & 3u) atomicAnd(&r.vec4, 0u);
+    else if (r.op == OP_CONCAT && (du & 3u)) atomicAnd(&r.vec4, 2u);
+}
+
+// ---- tile descriptors ------------------------------------------------------------------------------
 __device__ inline u32 tiles_field(const Lay &L, int which) { return which == 0 ? L.tf : (which == 1 ? L.ta : L.tb); }
 
-__global__ void k_tiles(Tables T, const Lay *lay_ex, const Lay *total, u32 cap)
+// batch that owns global tile index t of list `which`: the largest b with offset(b) <= t
+__device__ inline u32 batch_of_tile(const Lay *lay_ex, u32 nb, int which, u32 t)
+{
+    u32 lo = 0, hi = nb;
+    while (hi - lo > 1) {
+        const u32 mid = (lo + hi) >> 1;
+        if (tiles_field(lay_ex[mid], which) <= t) lo = mid; else hi = mid;
+    }
+    return lo;
+}
+
+constexpr u32 CONTIG_MAX_ROWS = 32;   // tiles with more rows skip the contiguity test
+
+__device__ inline void fill_tile_desc(const Tables &T, const BatchRec &r, u32 t, bool dx, TileDesc &d)
+{
+    d.op = r.op; d.B = r.B; d.d = r.d; d.arity = r.arity;
+    d.pos0 = r.pos0; d.val_off = r.val_off; d.dx_off = r.dx_off; d.k = r.k;
+    d.param = r.param; d.bias = r.bias; d.aux0 = r.aux0; d.aux1 = r.aux1;
+    d.opnd = r.opnd; d.indim = r.indim; d.flags = r.vec4; d.t = t;
+    d.contig = 0; d.row0 = 0;
+    for (int j = 0; j < 4; ++j) { d.base[j] = 0; d.sdim[j] = 0; }
+    for (int j = 0; j < 6; ++j) d.pad[j] = 0;
+    if (dx || r.arity == 0) return;
+    // rows this tile touches
+    u32 r_lo, r_hi;
+    if (r.op == OP_MATVEC) {
+        const u32 ntn = (r.d + GT - 1) / GT;
+        r_lo = (t / ntn) * GT; r_hi = r_lo + GT - 1;
+    } else if (r.op == OP_PICK_NLS || r.op == OP_SQNORM) {
+        r_lo = t * ROWS_PER_RED_TILE; r_hi = r_lo + ROWS_PER_RED_TILE - 1;
+    } else if (r.op == OP_ADD && r.arity >= (u32)WIDE_ADD_ARITY) {
+        r_lo = r_hi = t;
+    } else {
+        r_lo = (u32)(((u64)t * EW_TILE) / r.d);
+        r_hi = (u32)(((u64)t * EW_TILE + EW_TILE - 1) / r.d);
+    }
+    if (r_hi >= r.B) r_hi = r.B - 1;
+    d.row0 = r_lo;
+    const u32 ns = r.arity < 4 ? r.arity : 4;
+    for (u32 j = 0; j < ns; ++j) {
+        const u32 *op = T.opnd_off + r.opnd + j * r.B;
+        const u32 sd = T.b_indim[r.indim + j];
+        const u32 base = op[r_lo];
+        d.base[j] = base; d.sdim[j] = sd;
+        bool ok = (r_hi - r_lo) < CONTIG_MAX_ROWS;
+        for (u32 rr = r_lo + 1; ok && rr <= r_hi; ++rr) ok = op[rr] == base + (rr - r_lo) * sd;
+        if (ok) d.contig |= 1u << j;
+    }
+}
+
+constexpr u32 PULL_MAX_ROWS = 16;
+
+__device__ inline void fill_pull_desc(const Tables &T, const BatchRec &r, u32 t, PullDesc &d)
+{
+    d.pos0 = r.pos0; d.B = r.B; d.d = r.d; d.val_off = r.val_off;
+    d.t = t; d.flags = 0; d.n_uni = PULL_GENERIC;
+    for (int j = 0; j < 4; ++j) { UEdge z; z.kind = 0; z.goff = z.voff = z.gs = z.vs = 0; z.a0 = z.a1 = 0; d.e[j] = z; }
+    for (int j = 0; j < 4; ++j) d.pad[j] = 0;
+    u32 r_lo = (u32)(((u64)t * EW_TILE) / r.d);
+    u32 r_hi = (u32)(((u64)t * EW_TILE + EW_TILE - 1) / r.d);
+    if (r_hi >= r.B) r_hi = r.B - 1;
+    d.row0 = r_lo;
+    if (r_hi - r_lo >= PULL_MAX_ROWS) return;
+    const u32 u0 = T.order[r.pos0 + r_lo];
+    const u32 q0 = T.succ_off[u0];
+    const u32 cnt = T.succ_off[u0 + 1] - q0;
+    if (cnt > 4) return;
+    EdgeRec first[4];
+    for (u32 j = 0; j < cnt; ++j) {
+        first[j] = T.edges[q0 + j];
+        if (first[j].kind == EK_NLS) return;     // the label is per-row data
+        UEdge ue; ue.kind = first[j].kind; ue.goff = first[j].goff; ue.voff = first[j].voff;
+        ue.gs = ue.vs = 0; ue.a0 = first[j].a0; ue.a1 = first[j].a1;
+        d.e[j] = ue;
+    }
+    for (u32 rr = r_lo + 1; rr <= r_hi; ++rr) {
+        const u32 u = T.order[r.pos0 + rr];
+        const u32 q = T.succ_off[u];
+        if (T.succ_off[u + 1] - q != cnt) return;
+        for (u32 j = 0; j < cnt; ++j) {
+            const EdgeRec er = T.edges[q + j];
+            if (er.kind != first[j].kind || er.a0 != first[j].a0 || er.a1 != first[j].a1) return;
+            const u32 dg = er.goff - first[j].goff, dv = er.voff - first[j].voff;
+            if (rr == r_lo + 1) { d.e[j].gs = dg; d.e[j].vs = dv; }
+            else if (dg != d.e[j].gs * (rr - r_lo) || dv != d.e[j].vs * (rr - r_lo)) return;
+        }
+    }
+    d.n_uni = cnt;
+}
+
+__global__ void k_tiles(Tables T, const Lay *lay_ex, const Lay *total, u32 cap_f, u32 cap_a, u32 cap_b)
 {
     const u32 nb = T.hdr->n_batches;
     for (int which = 0; which < 3; ++which) {
         u32 nt = tiles_field(*total, which);
+        const u32 cap = which == 0 ? cap_f : (which == 1 ? cap_a : cap_b);
         if (nt > cap) {   // cannot happen with the host's bound; never write past the lists
             if (blockIdx.x == 0 && threadIdx.x == 0) atomicOr(&T.hdr->err, (u32)ERR_OVERFLOW);
             nt = cap;
         }
-        TileRec *out = which == 0 ? T.tiles_f : (which == 1 ? T.tiles_a : T.tiles_b);
         for (u32 t = blockIdx.x * blockDim.x + threadIdx.x; t < nt; t += gridDim.x * blockDim.x) {
-            u32 lo = 0, hi = nb;   // largest b with offset(b) <= t
-            while (hi - lo > 1) {
-                const u32 mid = (lo + hi) >> 1;
-                if (tiles_field(lay_ex[mid], which) <= t) lo = mid; else hi = mid;
+            const u32 b = batch_of_tile(lay_ex, nb, which, t);
+            const BatchRec r = T.batches[b];
+            const u32 tt = t - tiles_field(lay_ex[b], which);
+            if (which == 1) {
+                PullDesc d;
+                fill_pull_desc(T, r, tt, d);
+                T.tiles_a[t] = d;
+            } else {
+                TileDesc d;
+                fill_tile_desc(T, r, tt, which == 2, d);
+                (which == 0 ? T.tiles_f : T.tiles_b)[t] = d;
             }
-            TileRec tr; tr.batch = lo; tr.t = t - tiles_field(lay_ex[lo], which);
-            out[t] = tr;
         }
     }
 }
@@ -417,7 +532,10 @@ int sched_run(ob_ctx *ctx)
     u32 ht_size = 1;
     while (ht_size < 2 * n) ht_size <<= 1;
     if (!by_depth) ht_size = 1;
-    const size_t tile_cap = (size_t)(ctx->sum_out_dim / 32) + (size_t)(ctx->sum_mv_k / 32) + 2 * (size_t)n + 16;
+    // upper bounds of the three tile lists from sums the host keeps while nodes are added
+    const size_t cap_f = (size_t)(ctx->sum_out_dim / EW_TILE) + 2 * (size_t)n + (size_t)ctx->sum_mv_d32 + 16;
+    const size_t cap_a = (size_t)(ctx->sum_out_dim / EW_TILE) + (size_t)n + 16;
+    const size_t cap_b = (size_t)ctx->sum_mv_k32 + 16;
 #define A(field, type, count)                                               \
     do {                                                                    \
         field = arena_array<type>(ctx, (count));                            \
@@ -433,7 +551,8 @@ int sched_run(ob_ctx *ctx)
     A(T.batch_off, u32, n + 1); A(T.batches, BatchRec, n); A(T.lay, Lay, n); A(T.b_indim, u32, E + 1);
     A(T.val_off, u32, n); A(T.dx_off, u32, n); A(T.opnd_off, u32, E + 1);
     A(T.step_first, u32, n + 2); A(T.step_tf, u32, n + 2); A(T.step_ta, u32, n + 2); A(T.step_tb, u32, n + 2);
-    A(T.tiles_f, TileRec, tile_cap); A(T.tiles_a, TileRec, tile_cap); A(T.tiles_b, TileRec, tile_cap);
+    A(T.tiles_f, TileDesc, cap_f); A(T.tiles_a, PullDesc, cap_a); A(T.tiles_b, TileDesc, cap_b);
+    A(T.root_pos, u32, 64);
     A(T.edges, EdgeRec, E + 1);
     A(T.it_key, u64, n_items + 1); A(T.it_pos, u32, n_items + 1); A(T.it_goff, u32, n_items + 1);
     A(T.it_xoff, u32, n_items + 1); A(T.pu_start, u32, n_slots); A(T.pu_end, u32, n_slots);
@@ -460,10 +579,10 @@ int sched_run(ob_ctx *ctx)
     HIP_TRY(ctx, hipMemsetAsync(T.pu_start, 0, n_slots * 4, s));
     HIP_TRY(ctx, hipMemsetAsync(T.pu_end, 0, n_slots * 4, s));
     K(k_node_init, n, T, by_depth);
+    if (E > 0) K(k_edge_init, E, T, ctx->key_a, ctx->val_a);
     HIP_TRY(ctx, prim_scan_u32(T.outdeg, T.succ_off, (size_t)n + 1, nullptr, ctx->scratch, s));
     ctx->n_launch_sched += 3;
     if (E > 0) {
-        K(k_edge_keys, E, T, ctx->key_a, ctx->val_a);
         HIP_TRY(ctx, prim_sort_pairs(ctx->key_a, ctx->val_a, ctx->key_b, ctx->val_b, E, 0,
                                      bit_width_u32(n - 1), ctx->scratch, s, &ctx->n_launch_sched));
         K(k_succ_finish, E, T, ctx->val_a, succ_node);
@@ -499,10 +618,12 @@ int sched_run(ob_ctx *ctx)
     ctx->n_launch_sched += 3;
     K(k_batch_finish, n, T, T.lay, ctx->lay_total);
     K(k_node_offsets, n, T);
-    K(k_opnd, n, T);
-    hipLaunchKernelGGL(k_tiles, dim3(512), dim3(TPB), 0, s, T, T.lay, ctx->lay_total, (u32)tile_cap);
-    ++ctx->n_launch_sched;
+    K(k_member_check, n, T);
+    if (E > 0) K(k_opnd, E, T);
     if (E > 0) K(k_edges, E, T);
+    hipLaunchKernelGGL(k_tiles, dim3(1024), dim3(TPB), 0, s, T, T.lay, ctx->lay_total, (u32)cap_f, (u32)cap_a,
+                       (u32)cap_b);
+    ++ctx->n_launch_sched;
 
     // ---- parameter-use items ----
     if (n_items > 0) {
