@@ -81,6 +81,11 @@ int ob_ctx_create(void *arena_dev, size_t arena_bytes, void *hip_stream, ob_ctx 
 int ob_ctx_destroy(ob_ctx *ctx);
 int ob_ctx_set_mode(ob_ctx *ctx, int mode);
 int ob_ctx_set_launch(ob_ctx *ctx, int launch);
+/* Launch fusion (default on, OB_BYDEPTH only): component-wise batches whose operands are
+ * row-aligned with their producer batch run inside the producer's launch (Section 3.3: inputs
+ * that are already contiguous and in order are used as they are), so a chain of such batches
+ * costs one launch instead of one per depth level.  Batches and their order do not change. */
+int ob_ctx_set_fusion(ob_ctx *ctx, int on);
 /* Library-owned message for the last failing call on this context (valid until the next
  * call); ctx may be NULL for errors of ob_ctx_create. */
 const char *ob_last_error(ob_ctx *ctx);
@@ -156,7 +161,7 @@ int ob_schedule_read(ob_ctx *ctx, int *n_batches, int *batch_depth, uint64_t *ba
 typedef struct ob_stats {
     int32_t n_nodes, n_edges, n_steps, n_batches;
     int32_t n_tiles_fwd, n_tiles_bwd_pull, n_tiles_bwd_dx, n_param_uses;
-    int32_t n_launch_fwd, n_launch_bwd, n_launch_sched, reserved0;
+    int32_t n_launch_fwd, n_launch_bwd, n_launch_sched, n_slots;
     uint64_t value_floats, grad_floats, arena_used_bytes, upload_bytes;
     float ms_upload, ms_schedule, ms_forward, ms_backward; /* hipEvent times on the stream */
     float ms_param_grads, ms_graph_build, reserved1, reserved2;

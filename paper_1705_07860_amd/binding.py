@@ -35,7 +35,7 @@ class ObError(RuntimeError):
 class ObStats(ctypes.Structure):
     _fields_ = [(n, c_int32) for n in (
         "n_nodes", "n_edges", "n_steps", "n_batches", "n_tiles_fwd", "n_tiles_bwd_pull", "n_tiles_bwd_dx",
-        "n_param_uses", "n_launch_fwd", "n_launch_bwd", "n_launch_sched", "reserved0")] + \
+        "n_param_uses", "n_launch_fwd", "n_launch_bwd", "n_launch_sched", "n_slots")] + \
         [(n, c_uint64) for n in ("value_floats", "grad_floats", "arena_used_bytes", "upload_bytes")] + \
         [(n, c_float) for n in ("ms_upload", "ms_schedule", "ms_forward", "ms_backward", "ms_param_grads",
                                 "ms_graph_build", "reserved1", "reserved2")]
@@ -69,6 +69,7 @@ def lib():
             "ob_ctx_destroy": (i, [vp]),
             "ob_ctx_set_mode": (i, [vp, i]),
             "ob_ctx_set_launch": (i, [vp, i]),
+            "ob_ctx_set_fusion": (i, [vp, i]),
             "ob_last_error": (ctypes.c_char_p, [vp]),
             "ob_param_create": (i, [vp, i, i, vp, pi]),
             "ob_param_write": (i, [vp, i, vp]),
@@ -164,6 +165,9 @@ class Context:
 
     def set_launch(self, launch: int):
         self._ck(self.L.ob_ctx_set_launch(self.h, launch))
+
+    def set_fusion(self, on: bool):
+        self._ck(self.L.ob_ctx_set_fusion(self.h, 1 if on else 0))
 
     # -- parameters
     def param_create(self, mat: np.ndarray) -> int:

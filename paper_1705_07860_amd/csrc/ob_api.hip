@@ -77,6 +77,13 @@ int ob_ctx_set_mode(ob_ctx *ctx, int mode)
     return OB_OK;
 }
 
+int ob_ctx_set_fusion(ob_ctx *ctx, int on)
+{
+    CHECK_CTX(ctx);
+    ctx->fuse = on ? 1 : 0;
+    return OB_OK;
+}
+
 int ob_ctx_set_launch(ob_ctx *ctx, int launch)
 {
     CHECK_CTX(ctx);
@@ -708,6 +715,7 @@ int ob_stats_read(ob_ctx *ctx, ob_stats *out)
     out->n_launch_fwd = ctx->n_launch_fwd;
     out->n_launch_bwd = ctx->n_launch_bwd;
     out->n_launch_sched = ctx->n_launch_sched;
+    out->n_slots = (int32_t)ctx->hdr.n_slots;
     out->value_floats = ctx->hdr.val_floats;
     out->grad_floats = ctx->hdr.grad_floats;
     out->arena_used_bytes = ctx->top;

@@ -19,6 +19,7 @@ struct ob_ctx {
     hipStream_t stream = nullptr;
     int mode = 1;      // OB_BYDEPTH
     int launch = 0;    // OB_LAUNCH_STREAM
+    int fuse = 1;      // run row-aligned component-wise chains inside one launch
     std::string err;
 
     // arena bump allocator: [0, persist_top) parameters; [persist_top, top) current graph
@@ -54,7 +55,7 @@ struct ob_ctx {
     bool forward_done = false, backward_done = false;
     Tables T{};
     SchedHeader hdr{};
-    std::vector<u32> step_tf, step_ta, step_tb, step_first;   // host mirrors (n_steps + 1 each)
+    std::vector<u32> slot_wf, slot_wa, slot_tb;   // host mirrors of the per-slot launch tables (n_slots + 1 each)
     void *scratch = nullptr;           // scan / sort scratch in the arena
     u64 *key_a = nullptr, *key_b = nullptr;
     u32 *val_a = nullptr, *val_b = nullptr;

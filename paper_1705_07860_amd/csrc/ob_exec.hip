@@ -15,6 +15,7 @@
 #include <chrono>
 
 typedef float floatx16 __attribute__((ext_vector_type(16)));
+constexpr int LDS_FLOATS = 4 * 16 * 64;   // 16 KB: the four waves' accumulator blocks
 
 namespace {
 
@@ -128,18 +129,15 @@ __device__ inline float4 ew_value4(const Tables &T, const TileDesc &d, u32 row, 
     }
 }
 
+// rows [row0, row0 + nrows) of the batch, all columns
 __device__ inline void ew_fwd_tile(const Tables &T, const TileDesc &d)
 {
-    const u32 total = d.B * d.d;
+    const u32 e_lo = d.row0 * d.d, e_hi = e_lo + d.nrows * d.d;
     float *out = T.V + d.val_off;
     if (d.flags & 1u) {
-        const u32 e = d.t * EW_TILE + threadIdx.x * 4;
-        if (e < total) st4(out + e, ew_value4(T, d, e / d.d, e % d.d));
+        for (u32 e = e_lo + threadIdx.x * 4; e < e_hi; e += WG * 4) st4(out + e, ew_value4(T, d, e / d.d, e % d.d));
     } else {
-        for (int i = 0; i < EW_TILE / WG; ++i) {
-            const u32 e = d.t * EW_TILE + i * WG + threadIdx.x;
-            if (e < total) out[e] = ew_value(T, d, e / d.d, e % d.d);
-        }
+        for (u32 e = e_lo + threadIdx.x; e < e_hi; e += WG) out[e] = ew_value(T, d, e / d.d, e % d.d);
     }
 }
 
@@ -467,11 +465,9 @@ __device__ inline float edge_term(const Tables &T, u32 kind, u32 goff, u32 voff,
 
 __device__ inline void pull_tile(const Tables &T, const PullDesc &d)
 {
-    const u32 total = d.B * d.d;
+    const u32 e_lo = d.row0 * d.d, e_hi = e_lo + d.nrows * d.d;
     const u32 root_pos = T.root_pos[0];
-    for (int i = 0; i < EW_TILE / WG; ++i) {
-        const u32 e = d.t * EW_TILE + i * WG + threadIdx.x;
-        if (e >= total) continue;
+    for (u32 e = e_lo + threadIdx.x; e < e_hi; e += WG) {
         const u32 row = e / d.d, col = e % d.d;
         const u32 own = d.val_off + row * d.d;
         float acc = (d.pos0 + row == root_pos) ? 1.0f : 0.0f;
@@ -499,31 +495,49 @@ __device__ inline void pull_tile(const Tables &T, const PullDesc &d)
 // ------------------------------------------------------------------------------------------------
 // kernels
 // ------------------------------------------------------------------------------------------------
-constexpr int LDS_FLOATS = 4 * 16 * 64;   // 16 KB: the four waves' accumulator blocks
+__device__ inline void run_fwd_tile(const Tables &T, const TileDesc &d, float *lds)
+{
+    switch (d.op) {
+    case OP_MATVEC: matvec_fwd_tile(T, d, lds); break;
+    case OP_PICK_NLS:
+    case OP_SQNORM: red_fwd_tile(T, d); break;
+    case OP_ADD:
+        if (d.arity >= (u32)WIDE_ADD_ARITY) { wide_add_tile(T, d, lds); break; }
+        ew_fwd_tile(T, d);
+        break;
+    default: ew_fwd_tile(T, d); break;
+    }
+}
 
-__global__ __launch_bounds__(WG) void k_fwd_step(Tables T, u32 tile_lo, u32 tile_hi)
+// One launch = one slot.  A work item is a run of tiles that one workgroup executes in order;
+// runs longer than one tile are fused chains of row-aligned component-wise batches over the same
+// block of rows, and a workgroup barrier separates members of different depth.
+__global__ __launch_bounds__(WG) void k_fwd_step(Tables T, u32 work_lo, u32 work_hi)
 {
     __shared__ float lds[LDS_FLOATS];
-    for (u32 tile = tile_lo + blockIdx.x; tile < tile_hi; tile += gridDim.x) {
-        const TileDesc d = T.tiles_f[tile];
-        switch (d.op) {
-        case OP_MATVEC: matvec_fwd_tile(T, d, lds); break;
-        case OP_PICK_NLS:
-        case OP_SQNORM: red_fwd_tile(T, d); break;
-        case OP_ADD:
-            if (d.arity >= (u32)WIDE_ADD_ARITY) { wide_add_tile(T, d, lds); break; }
-            ew_fwd_tile(T, d);
-            break;
-        default: ew_fwd_tile(T, d); break;
+    for (u32 w = work_lo + blockIdx.x; w < work_hi; w += gridDim.x) {
+        const WorkRec wr = T.works_f[w];
+        TileDesc d = T.tiles_f[wr.first];
+        for (u32 i = 0; i < wr.len; ++i) {
+            const TileDesc cur = d;
+            if (i + 1 < wr.len) d = T.tiles_f[wr.first + i + 1];   // next descriptor in flight during this tile
+            run_fwd_tile(T, cur, lds);
+            if (i + 1 < wr.len && d.depth != cur.depth) __syncthreads();
         }
     }
 }
 
-__global__ __launch_bounds__(WG) void k_bwd_pull_step(Tables T, u32 tile_lo, u32 tile_hi)
+__global__ __launch_bounds__(WG) void k_bwd_pull_step(Tables T, u32 work_lo, u32 work_hi)
 {
-    for (u32 tile = tile_lo + blockIdx.x; tile < tile_hi; tile += gridDim.x) {
-        const PullDesc d = T.tiles_a[tile];
-        pull_tile(T, d);
+    for (u32 w = work_lo + blockIdx.x; w < work_hi; w += gridDim.x) {
+        const WorkRec wr = T.works_a[w];
+        PullDesc d = T.tiles_a[wr.first];
+        for (u32 i = 0; i < wr.len; ++i) {
+            const PullDesc cur = d;
+            if (i + 1 < wr.len) d = T.tiles_a[wr.first + i + 1];
+            pull_tile(T, cur);
+            if (i + 1 < wr.len && d.depth != cur.depth) __syncthreads();
+        }
     }
 }
 
@@ -606,9 +620,9 @@ static int launch_forward_steps(ob_ctx *ctx)
 {
     const Tables &T = ctx->T;
     hipStream_t s = ctx->stream;
-    const u32 ns = ctx->hdr.n_steps;
+    const u32 ns = ctx->hdr.n_slots;
     for (u32 st = 0; st < ns; ++st) {
-        const u32 lo = ctx->step_tf[st], hi = ctx->step_tf[st + 1];
+        const u32 lo = ctx->slot_wf[st], hi = ctx->slot_wf[st + 1];
         if (hi > lo) {
             hipLaunchKernelGGL(k_fwd_step, dim3(grid_for(hi - lo, GRID_CAP)), dim3(WG), 0, s, T, lo, hi);
             ++ctx->n_launch_fwd;
@@ -621,16 +635,16 @@ static int launch_backward_steps(ob_ctx *ctx)
 {
     const Tables &T = ctx->T;
     hipStream_t s = ctx->stream;
-    const u32 ns = ctx->hdr.n_steps;
+    const u32 ns = ctx->hdr.n_slots;
     hipLaunchKernelGGL(k_set_root, dim3(1), dim3(1), 0, s, T);
     ++ctx->n_launch_bwd;
     for (u32 st = ns; st-- > 0;) {
-        const u32 alo = ctx->step_ta[st], ahi = ctx->step_ta[st + 1];
+        const u32 alo = ctx->slot_wa[st], ahi = ctx->slot_wa[st + 1];
         if (ahi > alo) {
             hipLaunchKernelGGL(k_bwd_pull_step, dim3(grid_for(ahi - alo, GRID_CAP)), dim3(WG), 0, s, T, alo, ahi);
             ++ctx->n_launch_bwd;
         }
-        const u32 blo = ctx->step_tb[st], bhi = ctx->step_tb[st + 1];
+        const u32 blo = ctx->slot_tb[st], bhi = ctx->slot_tb[st + 1];
         if (bhi > blo) {
             hipLaunchKernelGGL(k_bwd_dx_step, dim3(grid_for(bhi - blo, GRID_CAP)), dim3(WG), 0, s, T, blo, bhi);
             ++ctx->n_launch_bwd;

@@ -76,7 +76,8 @@ struct TileDesc {
     u32 contig, row0;                // contig bit j: slot j consecutive over the rows of this tile
     u32 base[4];
     u32 sdim[4];                     // dimension of operand slot j
-    u32 pad[6];
+    u32 nrows, depth;                // component-wise tiles cover rows [row0, row0 + nrows); depth of the batch
+    u32 pad[4];
 };
 static_assert(sizeof(TileDesc) == 128, "TileDesc must be 128 bytes");
 
@@ -89,11 +90,30 @@ struct UEdge { u32 kind, goff, voff, gs, vs; i32 a0, a1; };
 constexpr u32 PULL_GENERIC = 0xffffffffu;
 struct PullDesc {
     u32 pos0, B, d, val_off;
-    u32 t, row0, n_uni, flags;
+    u32 depth, row0, n_uni, nrows;   // rows [row0, row0 + nrows) of the batch, all columns
     UEdge e[4];
     u32 pad[4];
 };
 static_assert(sizeof(PullDesc) == 160, "PullDesc must be 160 bytes");
+
+// A launch chain: batches that run in the same launch slot.  A fused chain holds component-wise
+// batches with equal row counts whose in-chain operands are row-aligned (row r of the consumer
+// reads row r of the producer), so one workgroup can own a block of rows and run the members
+// one after the other with workgroup barriers only.  Every other batch is a chain of its own.
+struct ChainRec {
+    u32 first, k;          // members are lorder[first .. first + k)
+    u32 slot, fused;       // fused: component-wise members tiled by row blocks
+    u32 B, R, nrb, pad;    // rows, rows per block, number of row blocks
+};
+struct CLay {              // scan element of the per-chain launch layout
+    u32 tf, wf, ta, wa, tb, p0, p1, p2;   // forward tiles/work items, pull tiles/work items, dX tiles
+    __host__ __device__ CLay operator+(const CLay &o) const {
+        CLay r; r.tf = tf + o.tf; r.wf = wf + o.wf; r.ta = ta + o.ta; r.wa = wa + o.wa; r.tb = tb + o.tb;
+        r.p0 = r.p1 = r.p2 = 0; return r;
+    }
+};
+struct WorkRec { u32 first, len; };   // a workgroup runs tiles [first, first + len) in order
+struct BEdge { u32 cons, prod, w; };  // batch-level dependency; w = 0 when it can be fused
 
 // Static tile of the deferred parameter-gradient kernels (built on the host per parameter set).
 struct PTile { i32 param; i32 i0, j0; i32 pad; };
@@ -101,10 +121,9 @@ struct PTile { i32 param; i32 i0, j0; i32 pad; };
 // Scan element of the per-batch layout pass.
 struct Lay {
     u64 val, dx;           // floats
-    u32 tf, ta, tb, ind;   // forward tiles, pull tiles, dX tiles, operand-dimension slots
+    u32 ind, p0, p1, p2;   // operand-dimension slots
     __host__ __device__ Lay operator+(const Lay &o) const {
-        Lay r; r.val = val + o.val; r.dx = dx + o.dx; r.tf = tf + o.tf; r.ta = ta + o.ta;
-        r.tb = tb + o.tb; r.ind = ind + o.ind; return r;
+        Lay r; r.val = val + o.val; r.dx = dx + o.dx; r.ind = ind + o.ind; r.p0 = r.p1 = r.p2 = 0; return r;
     }
 };
 
@@ -113,6 +132,8 @@ struct SchedHeader {
     u32 n_steps, n_batches, n_items, err;
     u64 val_floats, grad_floats;
     u32 tiles_fwd, tiles_pull, tiles_dx, frontier_done;
+    u32 n_slots, n_chains, works_fwd, works_pull;
+    u32 n_bedges, slot_sweeps, p0, p1;
 };
 enum : u32 { ERR_CYCLE = 1, ERR_COLLISION = 2, ERR_TABLE_FULL = 4, ERR_OVERFLOW = 8 };
 
@@ -133,7 +154,11 @@ struct Tables {
     u32 *order; u32 *pos_of; u32 *batch_of_pos; u32 *s_aux0; u32 *s_in_off;
     u32 *batch_off; BatchRec *batches; Lay *lay; u32 *b_indim;
     u32 *val_off; u32 *dx_off; u32 *opnd_off;
-    u32 *step_first; u32 *step_tf; u32 *step_ta; u32 *step_tb;
+    u32 *b_align;          // per (batch, slot): 1 when the slot is row-aligned to one producer batch
+    BEdge *bedges; u32 *slot_of; u32 *label_of; u32 *lorder;
+    ChainRec *chains; CLay *clay; u32 *chain_of_lpos;
+    u32 *slot_wf; u32 *slot_wa; u32 *slot_tb;     // per launch slot: first forward work, pull work, dX tile
+    WorkRec *works_f; WorkRec *works_a;
     TileDesc *tiles_f; PullDesc *tiles_a; TileDesc *tiles_b;
     u32 *root_pos;         // [0] = schedule position of the backward root
     EdgeRec *edges;
@@ -149,6 +174,7 @@ size_t prim_scan_scratch_bytes(size_t n, size_t elem);
 hipError_t prim_fill_u32(u32 *p, u32 v, size_t n, hipStream_t s);
 hipError_t prim_scan_u32(const u32 *in, u32 *out, size_t n, u32 *total_dev, void *scratch, hipStream_t s);
 hipError_t prim_scan_lay(const Lay *in, Lay *out, size_t n, Lay *total_dev, void *scratch, hipStream_t s);
+hipError_t prim_scan_clay(const CLay *in, CLay *out, size_t n, CLay *total_dev, void *scratch, hipStream_t s);
 size_t prim_sort_scratch_bytes(size_t n);
 // Stable LSD radix sort of (key, val) pairs on bits [lo_bit, lo_bit + n_bits) of the key.
 // keys/vals are overwritten with the sorted result; tmp arrays have the same sizes.

@@ -17,7 +17,8 @@ __global__ void k_fill_u32(u32 *p, u32 v, size_t n)
 
 template <typename T> __device__ inline T zero_of();
 template <> __device__ inline u32 zero_of<u32>() { return 0u; }
-template <> __device__ inline Lay zero_of<Lay>() { Lay z; z.val = 0; z.dx = 0; z.tf = z.ta = z.tb = z.ind = 0; return z; }
+template <> __device__ inline Lay zero_of<Lay>() { Lay z; z.val = 0; z.dx = 0; z.ind = z.p0 = z.p1 = z.p2 = 0; return z; }
+template <> __device__ inline CLay zero_of<CLay>() { CLay z; z.tf = z.wf = z.ta = z.wa = z.tb = z.p0 = z.p1 = z.p2 = 0; return z; }
 
 // Exclusive scan of the 256 per-thread values of a block through LDS (Kogge-Stone).
 // Returns the exclusive prefix of this thread; *block_total gets the sum of all 256.
@@ -221,6 +222,11 @@ hipError_t prim_scan_u32(const u32 *in, u32 *out, size_t n, u32 *total_dev, void
 hipError_t prim_scan_lay(const Lay *in, Lay *out, size_t n, Lay *total_dev, void *scratch, hipStream_t s)
 {
     return scan_impl<Lay>(in, out, n, total_dev, scratch, s);
+}
+
+hipError_t prim_scan_clay(const CLay *in, CLay *out, size_t n, CLay *total_dev, void *scratch, hipStream_t s)
+{
+    return scan_impl<CLay>(in, out, n, total_dev, scratch, s);
 }
 
 size_t prim_sort_scratch_bytes(size_t n)

@@ -190,23 +190,12 @@ __global__ void k_batch_off(Tables T, const u32 *head_flag, const u32 *head_excl
 
 __host__ __device__ inline u32 cdiv(u64 a, u32 b) { return (u32)((a + b - 1) / b); }
 
-__device__ inline u32 fwd_tiles_of(u32 op, u32 B, u32 d, u32 arity)
-{
-    switch (op) {
-    case OP_MATVEC: return cdiv(B, GT) * cdiv(d, GT);
-    case OP_PICK_NLS:
-    case OP_SQNORM: return cdiv(B, ROWS_PER_RED_TILE);
-    case OP_ADD: if (arity >= (u32)WIDE_ADD_ARITY) return B;  // fallthrough for narrow sums
-    default: return cdiv((u64)B * d, EW_TILE);
-    }
-}
-
 // one thread per batch: record + sizes for the layout scan (entries b >= n_batches are zero)
 __global__ void k_batch_layout(Tables T, Lay *lay_in)
 {
     const u32 b = blockIdx.x * blockDim.x + threadIdx.x;
     if (b >= T.n) return;
-    Lay L; L.val = 0; L.dx = 0; L.tf = L.ta = L.tb = L.ind = 0;
+    Lay L; L.val = 0; L.dx = 0; L.ind = L.p0 = L.p1 = L.p2 = 0;
     if (b < T.hdr->n_batches) {
         const u32 p0 = T.batch_off[b], B = T.batch_off[b + 1] - p0;
         const u32 h = T.order[p0];
@@ -223,12 +212,9 @@ __global__ void k_batch_layout(Tables T, Lay *lay_in)
         T.batches[b] = r;
         const u64 vs = (u64)B * r.d;
         L.val = (vs + VAL_ALIGN - 1) / VAL_ALIGN * VAL_ALIGN;
-        L.tf = fwd_tiles_of(r.op, B, r.d, r.arity);
-        L.ta = cdiv(vs, EW_TILE);
         if (r.op == OP_MATVEC) {
             const u64 xs = (u64)B * r.k;
             L.dx = (xs + VAL_ALIGN - 1) / VAL_ALIGN * VAL_ALIGN;
-            L.tb = cdiv(B, GT) * cdiv(r.k, GT);
         }
         L.ind = r.arity;
     }
@@ -246,16 +232,10 @@ __global__ void k_batch_finish(Tables T, const Lay *lay_ex, const Lay *total)
     r.val_off = (u32)L.val;
     r.dx_off = (u32)(tot.val + L.dx);
     r.indim = L.ind;
-    const u32 s = r.step;
-    if (b == 0 || T.batches[b - 1].step != s) {
-        T.step_first[s] = b; T.step_tf[s] = L.tf; T.step_ta[s] = L.ta; T.step_tb[s] = L.tb;
-    }
     if (b == nb - 1) {
-        T.step_first[s + 1] = nb; T.step_tf[s + 1] = tot.tf; T.step_ta[s + 1] = tot.ta; T.step_tb[s + 1] = tot.tb;
-        T.hdr->n_steps = s + 1;
+        T.hdr->n_steps = r.step + 1;
         T.hdr->val_floats = tot.val;
         T.hdr->grad_floats = tot.val + tot.dx;
-        T.hdr->tiles_fwd = tot.tf; T.hdr->tiles_pull = tot.ta; T.hdr->tiles_dx = tot.tb;
         if (tot.val + tot.dx >= 0xffffffffULL) atomicOr(&T.hdr->err, (u32)ERR_OVERFLOW);
     }
 }
@@ -316,47 +296,250 @@ __global__ void k_opnd(Tables T)
     else if (r.op == OP_CONCAT && (du & 3u)) atomicAnd(&r.vec4, 2u);
 }
 
-// ---- tile descriptors ------------------------------------------------------------------------------
-__device__ inline u32 tiles_field(const Lay &L, int which) { return which == 0 ? L.tf : (which == 1 ? L.ta : L.tb); }
+// ---- launch planning ---------------------------------------------------------------------------------
+// The schedule (which nodes form a batch, and the order of batches) is fixed above.  What follows
+// only decides which batches share a kernel launch.  Component-wise batches whose operands are
+// row-aligned with their producer (row r reads row r) can run in the producer's launch: a
+// workgroup that owns a block of rows walks such a chain with workgroup barriers, no grid-wide
+// synchronisation is needed.  Every other dependency costs one launch boundary.
 
-// batch that owns global tile index t of list `which`: the largest b with offset(b) <= t
-__device__ inline u32 batch_of_tile(const Lay *lay_ex, u32 nb, int which, u32 t)
+__device__ inline bool op_chainable(u32 op, u32 arity)
 {
-    u32 lo = 0, hi = nb;
-    while (hi - lo > 1) {
-        const u32 mid = (lo + hi) >> 1;
-        if (tiles_field(lay_ex[mid], which) <= t) lo = mid; else hi = mid;
+    switch (op) {
+    case OP_ADD: return arity < (u32)WIDE_ADD_ARITY;
+    case OP_CMULT: case OP_TANH: case OP_SIGMOID: case OP_CONCAT: case OP_SLICE: return true;
+    default: return false;
     }
-    return lo;
+}
+__device__ inline bool op_chain_source(u32 op, u32 arity)
+{
+    return op == OP_INPUT || op == OP_LOOKUP || op_chainable(op, arity);
 }
 
+// producer batch of operand slot j of the node at schedule position p, and whether the producer
+// row index equals `row`
+__device__ inline u32 producer_batch(const Tables &T, u32 p, u32 j, u32 row, bool *same_row)
+{
+    const u32 v = T.order[p];
+    const u32 pu = T.pos_of[T.in_idx[T.in_off[v] + j]];
+    const u32 by = T.batch_of_pos[pu];
+    *same_row = (pu - T.batches[by].pos0) == row;
+    return by;
+}
+
+// per edge: clears b_align[(batch, slot)] unless the slot reads, row for row, one producer batch
+// with the same number of rows
+__global__ void k_align(Tables T)
+{
+    const u32 e = blockIdx.x * blockDim.x + threadIdx.x;
+    if (e >= T.E) return;
+    const u32 v = T.edge_cons[e];
+    const u32 j = e - T.in_off[v];
+    const u32 p = T.pos_of[v];
+    const u32 b = T.batch_of_pos[p];
+    const BatchRec &r = T.batches[b];
+    const u32 row = p - r.pos0;
+    bool same0, same;
+    const u32 by0 = producer_batch(T, r.pos0, j, 0, &same0);
+    const u32 by = producer_batch(T, p, j, row, &same);
+    const BatchRec &y = T.batches[by0];
+    const bool ok = same && by == by0 && y.B == r.B && op_chainable(r.op, r.arity) && op_chain_source(y.op, y.arity);
+    if (!ok) T.b_align[r.indim + j] = 0;
+}
+
+// per edge: emits one batch-level dependency per run of rows with the same producer batch
+__global__ void k_bedges(Tables T)
+{
+    const u32 e = blockIdx.x * blockDim.x + threadIdx.x;
+    if (e >= T.E) return;
+    const u32 v = T.edge_cons[e];
+    const u32 j = e - T.in_off[v];
+    const u32 p = T.pos_of[v];
+    const u32 b = T.batch_of_pos[p];
+    const BatchRec &r = T.batches[b];
+    const u32 row = p - r.pos0;
+    bool dummy;
+    const u32 by = producer_batch(T, p, j, row, &dummy);
+    if (row > 0 && producer_batch(T, p - 1, j, row - 1, &dummy) == by) return;
+    BEdge be; be.cons = b; be.prod = by; be.w = T.b_align[r.indim + j] ? 0u : 1u;
+    T.bedges[atomicAdd(&T.hdr->n_bedges, 1u)] = be;
+}
+
+// One workgroup: launch slot of every batch = longest path over the batch dependencies with
+// weight 0 for fusable edges and 1 otherwise (relaxed to a fixed point in LDS), then a chain
+// label = smallest batch id reachable over fusable edges inside the same slot.
+constexpr u32 SLOT_MAX_NB = 7168;   // two u32 tables in 56 KB of LDS
+constexpr int SLOT_THREADS = 1024;
+__global__ __launch_bounds__(SLOT_THREADS) void k_slots(Tables T, int fuse)
+{
+    __shared__ u32 s_slot[SLOT_MAX_NB];
+    __shared__ u32 s_label[SLOT_MAX_NB];
+    __shared__ u32 s_changed;
+    const u32 nb = T.hdr->n_batches;
+    const u32 ne = T.hdr->n_bedges;
+    if (!fuse || nb > SLOT_MAX_NB) {   // one slot per step, no fusion
+        for (u32 b = threadIdx.x; b < nb; b += SLOT_THREADS) { T.slot_of[b] = T.batches[b].step; T.label_of[b] = b; }
+        if (threadIdx.x == 0) { T.hdr->n_slots = T.hdr->n_steps; T.hdr->slot_sweeps = 0; }
+        return;
+    }
+    for (u32 b = threadIdx.x; b < nb; b += SLOT_THREADS) { s_slot[b] = 0; s_label[b] = b; }
+    u32 sweeps = 0;
+    while (true) {
+        if (threadIdx.x == 0) s_changed = 0;
+        __syncthreads();
+        for (u32 e = threadIdx.x; e < ne; e += SLOT_THREADS) {
+            const BEdge be = T.bedges[e];
+            const u32 want = s_slot[be.prod] + be.w;
+            if (want > s_slot[be.cons]) { atomicMax(&s_slot[be.cons], want); s_changed = 1; }
+        }
+        __syncthreads();
+        ++sweeps;
+        const u32 ch = s_changed;
+        __syncthreads();
+        if (!ch || sweeps > nb + 1) break;
+    }
+    while (true) {
+        if (threadIdx.x == 0) s_changed = 0;
+        __syncthreads();
+        for (u32 e = threadIdx.x; e < ne; e += SLOT_THREADS) {
+            const BEdge be = T.bedges[e];
+            if (be.w == 0 && s_slot[be.prod] == s_slot[be.cons]) {
+                const u32 a = s_label[be.prod], c = s_label[be.cons];
+                if (a != c) { const u32 m = a < c ? a : c; atomicMin(&s_label[be.prod], m); atomicMin(&s_label[be.cons], m); s_changed = 1; }
+            }
+        }
+        __syncthreads();
+        ++sweeps;
+        const u32 ch = s_changed;
+        __syncthreads();
+        if (!ch || sweeps > 3 * nb + 3) break;
+    }
+    u32 mx = 0;
+    for (u32 b = threadIdx.x; b < nb; b += SLOT_THREADS) {
+        T.slot_of[b] = s_slot[b]; T.label_of[b] = s_label[b];
+        mx = s_slot[b] > mx ? s_slot[b] : mx;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) s_changed = 0;
+    __syncthreads();
+    atomicMax(&s_changed, mx);
+    __syncthreads();
+    if (threadIdx.x == 0) { T.hdr->n_slots = s_changed + 1; T.hdr->slot_sweeps = sweeps; }
+}
+
+__global__ void k_launch_keys(Tables T, u64 *keys, u32 *vals)
+{
+    const u32 b = blockIdx.x * blockDim.x + threadIdx.x;
+    if (b >= T.hdr->n_batches) { if (b < T.n) { keys[b] = ~0ull; vals[b] = b; } return; }
+    keys[b] = ((u64)T.slot_of[b] << 32) | T.label_of[b];
+    vals[b] = b;
+}
+
+__device__ inline u32 rows_per_block(u32 d) { return d >= (u32)EW_TILE ? 1u : (u32)EW_TILE / d; }
+
+// chains from the launch order: head flags, then one thread per chain head fills the record
+__global__ void k_chain_flags(Tables T, const u64 *skey, const u32 *sval, u32 *flag)
+{
+    const u32 i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= T.n) return;
+    const u32 nb = T.hdr->n_batches;
+    if (i < nb) T.lorder[i] = sval[i];
+    flag[i] = (i < nb && (i == 0 || skey[i] != skey[i - 1])) ? 1u : 0u;
+}
+
+__global__ void k_chain_recs(Tables T, const u64 *skey, const u32 *flag, const u32 *flag_excl, CLay *clay_in)
+{
+    const u32 i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= T.n) return;
+    const u32 nb = T.hdr->n_batches;
+    CLay L; L.tf = L.wf = L.ta = L.wa = L.tb = L.p0 = L.p1 = L.p2 = 0;
+    if (i < nb) {
+        const u32 c = flag_excl[i] + flag[i] - 1;
+        T.chain_of_lpos[i] = c;
+        if (i == nb - 1) T.hdr->n_chains = c + 1;
+    }
+    if (i < nb && flag[i]) {
+        const u32 c = flag_excl[i];
+        u32 k = 1;
+        while (i + k < nb && skey[i + k] == skey[i]) ++k;
+        const BatchRec r0 = T.batches[T.lorder[i]];
+        ChainRec cr;
+        cr.first = i; cr.k = k; cr.slot = (u32)(skey[i] >> 32); cr.B = r0.B; cr.pad = 0;
+        cr.fused = (op_chainable(r0.op, r0.arity) || r0.op == OP_INPUT || r0.op == OP_LOOKUP) ? 1u : 0u;
+        u32 dmax = r0.d;
+        for (u32 m = 1; m < k; ++m) { const u32 dm = T.batches[T.lorder[i + m]].d; dmax = dm > dmax ? dm : dmax; }
+        cr.R = rows_per_block(dmax);
+        cr.nrb = cdiv(cr.B, cr.R);
+        if (cr.fused) {
+            L.tf = L.ta = cr.nrb * k;
+            L.wf = L.wa = cr.nrb;
+        } else {
+            switch (r0.op) {
+            case OP_MATVEC: L.tf = cdiv(r0.B, GT) * cdiv(r0.d, GT); L.tb = cdiv(r0.B, GT) * cdiv(r0.k, GT); break;
+            case OP_PICK_NLS:
+            case OP_SQNORM: L.tf = cdiv(r0.B, ROWS_PER_RED_TILE); break;
+            default: L.tf = r0.B; break;   // wide sum: one workgroup per row
+            }
+            L.wf = L.tf;
+            L.ta = L.wa = cr.nrb;          // pull tiles are row blocks of the batch
+        }
+        T.chains[c] = cr;
+        clay_in[c] = L;
+    }
+}
+
+__global__ void k_clay_zero(Tables T, CLay *clay_in)
+{
+    const u32 i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= T.n) return;
+    CLay L; L.tf = L.wf = L.ta = L.wa = L.tb = L.p0 = L.p1 = L.p2 = 0;
+    clay_in[i] = L;
+}
+
+// per chain: first work item / dX tile of every launch slot, totals in the header
+__global__ void k_slot_tables(Tables T, const CLay *clay_ex, const CLay *total)
+{
+    const u32 c = blockIdx.x * blockDim.x + threadIdx.x;
+    const u32 nc = T.hdr->n_chains;
+    if (c >= nc) return;
+    const u32 s = T.chains[c].slot;
+    const CLay L = clay_ex[c];
+    if (c == 0 || T.chains[c - 1].slot != s) { T.slot_wf[s] = L.wf; T.slot_wa[s] = L.wa; T.slot_tb[s] = L.tb; }
+    if (c == nc - 1) {
+        const CLay t = *total;
+        T.slot_wf[s + 1] = t.wf; T.slot_wa[s + 1] = t.wa; T.slot_tb[s + 1] = t.tb;
+        T.hdr->tiles_fwd = t.tf; T.hdr->tiles_pull = t.ta; T.hdr->tiles_dx = t.tb;
+        T.hdr->works_fwd = t.wf; T.hdr->works_pull = t.wa;
+    }
+}
+
+// ---- tile descriptors ------------------------------------------------------------------------------
 constexpr u32 CONTIG_MAX_ROWS = 32;   // tiles with more rows skip the contiguity test
 
-__device__ inline void fill_tile_desc(const Tables &T, const BatchRec &r, u32 t, bool dx, TileDesc &d)
+// descriptor of tile t of batch r (forward or dX); component-wise tiles cover rows [row0, row0+nrows)
+__device__ inline void fill_tile_desc(const Tables &T, const BatchRec &r, u32 t, bool dx, bool row_block, u32 row0,
+                                      u32 nrows, TileDesc &d)
 {
     d.op = r.op; d.B = r.B; d.d = r.d; d.arity = r.arity;
     d.pos0 = r.pos0; d.val_off = r.val_off; d.dx_off = r.dx_off; d.k = r.k;
     d.param = r.param; d.bias = r.bias; d.aux0 = r.aux0; d.aux1 = r.aux1;
     d.opnd = r.opnd; d.indim = r.indim; d.flags = r.vec4; d.t = t;
-    d.contig = 0; d.row0 = 0;
-    for (int j = 0; j < 4; ++j) { d.base[j] = 0; d.sdim[j] = 0; }
-    for (int j = 0; j < 6; ++j) d.pad[j] = 0;
+    d.contig = 0; d.row0 = row0; d.nrows = nrows; d.depth = r.step;
+    for (int j = 0; j < 4; ++j) { d.base[j] = 0; d.sdim[j] = 0; d.pad[j] = 0; }
     if (dx || r.arity == 0) return;
-    // rows this tile touches
-    u32 r_lo, r_hi;
-    if (r.op == OP_MATVEC) {
+    u32 r_lo, r_hi;   // rows this tile touches
+    if (row_block) {
+        r_lo = row0; r_hi = row0 + nrows - 1;
+    } else if (r.op == OP_MATVEC) {
         const u32 ntn = (r.d + GT - 1) / GT;
         r_lo = (t / ntn) * GT; r_hi = r_lo + GT - 1;
     } else if (r.op == OP_PICK_NLS || r.op == OP_SQNORM) {
         r_lo = t * ROWS_PER_RED_TILE; r_hi = r_lo + ROWS_PER_RED_TILE - 1;
-    } else if (r.op == OP_ADD && r.arity >= (u32)WIDE_ADD_ARITY) {
-        r_lo = r_hi = t;
     } else {
-        r_lo = (u32)(((u64)t * EW_TILE) / r.d);
-        r_hi = (u32)(((u64)t * EW_TILE + EW_TILE - 1) / r.d);
+        r_lo = r_hi = t;   // wide sum
     }
     if (r_hi >= r.B) r_hi = r.B - 1;
-    d.row0 = r_lo;
+    if (!row_block) d.row0 = r_lo;
     const u32 ns = r.arity < 4 ? r.arity : 4;
     for (u32 j = 0; j < ns; ++j) {
         const u32 *op = T.opnd_off + r.opnd + j * r.B;
@@ -371,17 +554,13 @@ __device__ inline void fill_tile_desc(const Tables &T, const BatchRec &r, u32 t,
 
 constexpr u32 PULL_MAX_ROWS = 16;
 
-__device__ inline void fill_pull_desc(const Tables &T, const BatchRec &r, u32 t, PullDesc &d)
+__device__ inline void fill_pull_desc(const Tables &T, const BatchRec &r, u32 row0, u32 nrows, PullDesc &d)
 {
     d.pos0 = r.pos0; d.B = r.B; d.d = r.d; d.val_off = r.val_off;
-    d.t = t; d.flags = 0; d.n_uni = PULL_GENERIC;
-    for (int j = 0; j < 4; ++j) { UEdge z; z.kind = 0; z.goff = z.voff = z.gs = z.vs = 0; z.a0 = z.a1 = 0; d.e[j] = z; }
-    for (int j = 0; j < 4; ++j) d.pad[j] = 0;
-    u32 r_lo = (u32)(((u64)t * EW_TILE) / r.d);
-    u32 r_hi = (u32)(((u64)t * EW_TILE + EW_TILE - 1) / r.d);
-    if (r_hi >= r.B) r_hi = r.B - 1;
-    d.row0 = r_lo;
-    if (r_hi - r_lo >= PULL_MAX_ROWS) return;
+    d.depth = r.step; d.row0 = row0; d.nrows = nrows; d.n_uni = PULL_GENERIC;
+    for (int j = 0; j < 4; ++j) { UEdge z; z.kind = 0; z.goff = z.voff = z.gs = z.vs = 0; z.a0 = z.a1 = 0; d.e[j] = z; d.pad[j] = 0; }
+    if (nrows > PULL_MAX_ROWS) return;
+    const u32 r_lo = row0, r_hi = row0 + nrows - 1;
     const u32 u0 = T.order[r.pos0 + r_lo];
     const u32 q0 = T.succ_off[u0];
     const u32 cnt = T.succ_off[u0 + 1] - q0;
@@ -409,28 +588,65 @@ __device__ inline void fill_pull_desc(const Tables &T, const BatchRec &r, u32 t,
     d.n_uni = cnt;
 }
 
-__global__ void k_tiles(Tables T, const Lay *lay_ex, const Lay *total, u32 cap_f, u32 cap_a, u32 cap_b)
+// chain that owns global tile / work index x of list `which` (0 fwd tiles, 1 pull tiles, 2 dX tiles,
+// 3 fwd works, 4 pull works): the largest c with offset(c) <= x
+__device__ inline u32 clay_field(const CLay &L, int which)
 {
-    const u32 nb = T.hdr->n_batches;
-    for (int which = 0; which < 3; ++which) {
-        u32 nt = tiles_field(*total, which);
-        const u32 cap = which == 0 ? cap_f : (which == 1 ? cap_a : cap_b);
+    switch (which) { case 0: return L.tf; case 1: return L.ta; case 2: return L.tb; case 3: return L.wf; default: return L.wa; }
+}
+__device__ inline u32 chain_of_index(const CLay *clay_ex, u32 nc, int which, u32 x)
+{
+    u32 lo = 0, hi = nc;
+    while (hi - lo > 1) {
+        const u32 mid = (lo + hi) >> 1;
+        if (clay_field(clay_ex[mid], which) <= x) lo = mid; else hi = mid;
+    }
+    return lo;
+}
+
+__global__ void k_tiles(Tables T, const CLay *clay_ex, const CLay *total, u32 cap_f, u32 cap_a, u32 cap_b)
+{
+    const u32 nc = T.hdr->n_chains;
+    const u32 gtid = blockIdx.x * blockDim.x + threadIdx.x, gsz = gridDim.x * blockDim.x;
+    for (int which = 0; which < 5; ++which) {
+        u32 nt = clay_field(*total, which);
+        const u32 cap = (which == 0 || which == 3) ? cap_f : ((which == 1 || which == 4) ? cap_a : cap_b);
         if (nt > cap) {   // cannot happen with the host's bound; never write past the lists
-            if (blockIdx.x == 0 && threadIdx.x == 0) atomicOr(&T.hdr->err, (u32)ERR_OVERFLOW);
+            if (gtid == 0) atomicOr(&T.hdr->err, (u32)ERR_OVERFLOW);
             nt = cap;
         }
-        for (u32 t = blockIdx.x * blockDim.x + threadIdx.x; t < nt; t += gridDim.x * blockDim.x) {
-            const u32 b = batch_of_tile(lay_ex, nb, which, t);
-            const BatchRec r = T.batches[b];
-            const u32 tt = t - tiles_field(lay_ex[b], which);
-            if (which == 1) {
+        for (u32 x = gtid; x < nt; x += gsz) {
+            const u32 c = chain_of_index(clay_ex, nc, which, x);
+            const ChainRec cr = T.chains[c];
+            const u32 xx = x - clay_field(clay_ex[c], which);
+            if (which >= 3) {   // work items
+                WorkRec w;
+                const bool fwd = which == 3;
+                if (cr.fused || !fwd) { w.first = (fwd ? clay_ex[c].tf : clay_ex[c].ta) + xx * (cr.fused ? cr.k : 1u); w.len = cr.fused ? cr.k : 1u; }
+                else { w.first = clay_ex[c].tf + xx; w.len = 1; }
+                (fwd ? T.works_f : T.works_a)[x] = w;
+            } else if (which == 1) {   // pull tile: row block rb of a member, deepest member first
+                const u32 k = cr.fused ? cr.k : 1u;
+                const u32 rb = xx / k, i = xx % k;
+                const BatchRec r = T.batches[T.lorder[cr.first + (k - 1 - i)]];
+                const u32 row0 = rb * cr.R;
+                const u32 nrows = (row0 + cr.R <= r.B) ? cr.R : r.B - row0;
                 PullDesc d;
-                fill_pull_desc(T, r, tt, d);
-                T.tiles_a[t] = d;
-            } else {
+                fill_pull_desc(T, r, row0, nrows, d);
+                T.tiles_a[x] = d;
+            } else if (which == 0 && cr.fused) {
+                const u32 rb = xx / cr.k, i = xx % cr.k;
+                const BatchRec r = T.batches[T.lorder[cr.first + i]];
+                const u32 row0 = rb * cr.R;
+                const u32 nrows = (row0 + cr.R <= r.B) ? cr.R : r.B - row0;
                 TileDesc d;
-                fill_tile_desc(T, r, tt, which == 2, d);
-                (which == 0 ? T.tiles_f : T.tiles_b)[t] = d;
+                fill_tile_desc(T, r, xx, false, true, row0, nrows, d);
+                T.tiles_f[x] = d;
+            } else {
+                const BatchRec r = T.batches[T.lorder[cr.first]];
+                TileDesc d;
+                fill_tile_desc(T, r, xx, which == 2, false, 0, 0, d);
+                (which == 0 ? T.tiles_f : T.tiles_b)[x] = d;
             }
         }
     }
@@ -533,8 +749,9 @@ int sched_run(ob_ctx *ctx)
     while (ht_size < 2 * n) ht_size <<= 1;
     if (!by_depth) ht_size = 1;
     // upper bounds of the three tile lists from sums the host keeps while nodes are added
-    const size_t cap_f = (size_t)(ctx->sum_out_dim / EW_TILE) + 2 * (size_t)n + (size_t)ctx->sum_mv_d32 + 16;
-    const size_t cap_a = (size_t)(ctx->sum_out_dim / EW_TILE) + (size_t)n + 16;
+    // (a node contributes at most one component-wise / reduction tile; MATVEC nodes their GEMM tiles)
+    const size_t cap_f = (size_t)n + (size_t)ctx->sum_mv_d32 + 16;
+    const size_t cap_a = (size_t)n + 16;
     const size_t cap_b = (size_t)ctx->sum_mv_k32 + 16;
 #define A(field, type, count)                                               \
     do {                                                                    \
@@ -550,7 +767,10 @@ int sched_run(ob_ctx *ctx)
     A(T.s_in_off, u32, n + 1);
     A(T.batch_off, u32, n + 1); A(T.batches, BatchRec, n); A(T.lay, Lay, n); A(T.b_indim, u32, E + 1);
     A(T.val_off, u32, n); A(T.dx_off, u32, n); A(T.opnd_off, u32, E + 1);
-    A(T.step_first, u32, n + 2); A(T.step_tf, u32, n + 2); A(T.step_ta, u32, n + 2); A(T.step_tb, u32, n + 2);
+    A(T.b_align, u32, E + 1); A(T.bedges, BEdge, E + 1); A(T.slot_of, u32, n); A(T.label_of, u32, n);
+    A(T.lorder, u32, n); A(T.chains, ChainRec, n); A(T.clay, CLay, n); A(T.chain_of_lpos, u32, n);
+    A(T.slot_wf, u32, n + 2); A(T.slot_wa, u32, n + 2); A(T.slot_tb, u32, n + 2);
+    A(T.works_f, WorkRec, cap_f); A(T.works_a, WorkRec, cap_a);
     A(T.tiles_f, TileDesc, cap_f); A(T.tiles_a, PullDesc, cap_a); A(T.tiles_b, TileDesc, cap_b);
     A(T.root_pos, u32, 64);
     A(T.edges, EdgeRec, E + 1);
@@ -564,6 +784,8 @@ int sched_run(ob_ctx *ctx)
     u32 *tmp_c, *tmp_d;
     A(tmp_c, u32, n + 1); A(tmp_d, u32, n + 1);
     A(ctx->lay_in, Lay, n); A(ctx->lay_total, Lay, 1);
+    CLay *clay_in, *clay_total;
+    A(clay_in, CLay, n); A(clay_total, CLay, 1);
     {
         size_t sb = prim_sort_scratch_bytes(maxne);
         size_t sc = prim_scan_scratch_bytes(maxne, sizeof(Lay));
@@ -621,7 +843,34 @@ int sched_run(ob_ctx *ctx)
     K(k_member_check, n, T);
     if (E > 0) K(k_opnd, E, T);
     if (E > 0) K(k_edges, E, T);
-    hipLaunchKernelGGL(k_tiles, dim3(1024), dim3(TPB), 0, s, T, T.lay, ctx->lay_total, (u32)cap_f, (u32)cap_a,
+
+    // ---- launch planning: slots, chains, tile descriptors ----
+    const int fuse = by_depth && ctx->fuse;
+    if (fuse && E > 0) {
+        HIP_TRY(ctx, prim_fill_u32(T.b_align, 1u, (size_t)E + 1, s));
+        K(k_align, E, T);
+        K(k_bedges, E, T);
+        ctx->n_launch_sched += 1;
+    }
+    hipLaunchKernelGGL(k_slots, dim3(1), dim3(SLOT_THREADS), 0, s, T, fuse);
+    ++ctx->n_launch_sched;
+    K(k_launch_keys, n, T, ctx->key_a, ctx->val_a);
+    if (fuse) {
+        const int lb = bit_width_u32(n);
+        HIP_TRY(ctx, prim_sort_pairs(ctx->key_a, ctx->val_a, ctx->key_b, ctx->val_b, n, 0, lb, ctx->scratch, s,
+                                     &ctx->n_launch_sched));
+        HIP_TRY(ctx, prim_sort_pairs(ctx->key_a, ctx->val_a, ctx->key_b, ctx->val_b, n, 32, lb, ctx->scratch, s,
+                                     &ctx->n_launch_sched));
+    }
+    u32 *cflag = ctx->tmp_u32_a, *cflag_excl = ctx->tmp_u32_b;
+    K(k_chain_flags, n, T, ctx->key_a, ctx->val_a, cflag);
+    HIP_TRY(ctx, prim_scan_u32(cflag, cflag_excl, n, nullptr, ctx->scratch, s));
+    K(k_clay_zero, n, T, clay_in);
+    K(k_chain_recs, n, T, ctx->key_a, cflag, cflag_excl, clay_in);
+    HIP_TRY(ctx, prim_scan_clay(clay_in, T.clay, n, clay_total, ctx->scratch, s));
+    ctx->n_launch_sched += 6;
+    K(k_slot_tables, n, T, T.clay, clay_total);
+    hipLaunchKernelGGL(k_tiles, dim3(1024), dim3(TPB), 0, s, T, T.clay, clay_total, (u32)cap_f, (u32)cap_a,
                        (u32)cap_b);
     ++ctx->n_launch_sched;
 
@@ -648,24 +897,22 @@ int sched_run(ob_ctx *ctx)
     if (ctx->hdr.err & ERR_COLLISION) return ctx_fail(ctx, -6, "signature hash collision detected");
     if (ctx->hdr.err & ERR_TABLE_FULL) return ctx_fail(ctx, -6, "signature table full");
     if (ctx->hdr.err & ERR_OVERFLOW) return ctx_fail(ctx, -5, "value arena exceeds 2^32 elements");
-    const u32 ns = ctx->hdr.n_steps;
+    const u32 ns = ctx->hdr.n_slots;
     const size_t words = (size_t)ns + 1;
-    if (words * 16 > ctx->hdr_pinned_bytes) {
+    if (words * 12 > ctx->hdr_pinned_bytes) {
         if (ctx->hdr_pinned) HIP_TRY(ctx, hipHostFree(ctx->hdr_pinned));
         ctx->hdr_pinned = nullptr;
-        ctx->hdr_pinned_bytes = words * 16 + 4096;
+        ctx->hdr_pinned_bytes = words * 12 + 4096;
         HIP_TRY(ctx, hipHostMalloc(&ctx->hdr_pinned, ctx->hdr_pinned_bytes, hipHostMallocDefault));
     }
     u32 *hp = (u32 *)ctx->hdr_pinned;
-    HIP_TRY(ctx, hipMemcpyAsync(hp, T.step_tf, words * 4, hipMemcpyDeviceToHost, s));
-    HIP_TRY(ctx, hipMemcpyAsync(hp + words, T.step_ta, words * 4, hipMemcpyDeviceToHost, s));
-    HIP_TRY(ctx, hipMemcpyAsync(hp + 2 * words, T.step_tb, words * 4, hipMemcpyDeviceToHost, s));
-    HIP_TRY(ctx, hipMemcpyAsync(hp + 3 * words, T.step_first, words * 4, hipMemcpyDeviceToHost, s));
+    HIP_TRY(ctx, hipMemcpyAsync(hp, T.slot_wf, words * 4, hipMemcpyDeviceToHost, s));
+    HIP_TRY(ctx, hipMemcpyAsync(hp + words, T.slot_wa, words * 4, hipMemcpyDeviceToHost, s));
+    HIP_TRY(ctx, hipMemcpyAsync(hp + 2 * words, T.slot_tb, words * 4, hipMemcpyDeviceToHost, s));
     HIP_TRY(ctx, hipStreamSynchronize(s));
-    ctx->step_tf.assign(hp, hp + words);
-    ctx->step_ta.assign(hp + words, hp + 2 * words);
-    ctx->step_tb.assign(hp + 2 * words, hp + 3 * words);
-    ctx->step_first.assign(hp + 3 * words, hp + 4 * words);
+    ctx->slot_wf.assign(hp, hp + words);
+    ctx->slot_wa.assign(hp + words, hp + 2 * words);
+    ctx->slot_tb.assign(hp + 2 * words, hp + 3 * words);
 
     // ---- value and gradient arenas ----
     T.V = arena_array<float>(ctx, ctx->hdr.val_floats + VAL_ALIGN);

@@ -21,9 +21,10 @@ def say(msg):
     sys.stdout.flush()
 
 
-def run_gpu(p, g, mode, launch=0, arena=2 << 30, n_nodes=None):
+def run_gpu(p, g, mode, launch=0, arena=2 << 30, n_nodes=None, fuse=True):
     from paper_1705_07860_amd import binding as ob
     c = ob.Context(arena_bytes=arena, mode=mode, launch=launch)
+    c.set_fusion(fuse)
     pids = c.params_create(p)
     assert pids == list(range(len(p.mats)))
     c.param_grad_zero()
@@ -77,7 +78,7 @@ def test_schedule_bit_exact(name, workload_cache):
     assert np.array_equal(ids, rids)
     assert np.array_equal(bd, rbd)
     st = c.stats()
-    say(f"  steps={st['n_steps']} batches={st['n_batches']} sched {st['ms_schedule']:.3f} ms "
+    say(f"  steps={st['n_steps']} slots={st['n_slots']} batches={st['n_batches']} sched {st['ms_schedule']:.3f} ms "
         f"fwd {st['ms_forward']:.3f} ms launches(sched)={st['n_launch_sched']}")
     c.close()
 
@@ -120,6 +121,21 @@ def test_values_and_gradients_by_depth(name, workload_cache):
     st = c.stats()
     say(f"  sched {st['ms_schedule']:.3f} ms fwd {st['ms_forward']:.3f} ms bwd {st['ms_backward']:.3f} ms "
         f"(param grads {st['ms_param_grads']:.3f}) launches fwd={st['n_launch_fwd']} bwd={st['n_launch_bwd']}")
+    c.close()
+
+
+@pytest.mark.parametrize("name", ["rnn", "tagger", "parser"])
+def test_without_launch_fusion(name, workload_cache):
+    """One launch per depth level (fusion off) gives the same schedule and the same numbers."""
+    from paper_1705_07860_amd import binding as ob
+    p, g, o = workload_cache(name)
+    c, root = run_gpu(p, g, ob.OB_BYDEPTH, fuse=False)
+    bo, ids, bd, _ = c.schedule_read()
+    rbo, rids, rbd = S.by_depth(g)
+    assert np.array_equal(bo, rbo) and np.array_equal(ids, rids) and np.array_equal(bd, rbd)
+    st = c.stats()
+    assert st["n_slots"] == st["n_steps"]
+    check_against_oracle(c, p, g, o, root, what=f"{name}/nofuse")
     c.close()
 
 
