@@ -37,15 +37,16 @@ __device__ inline float wave_max(float v)
 // ------------------------------------------------------------------------------------------------
 // forward: component-wise / copy family
 // ------------------------------------------------------------------------------------------------
-// Element offset of operand slot j of batch row `row`.  When the descriptor says the tile's
-// operand rows are consecutive, the address is computed and the row-offset list is not read.
-__device__ inline u32 opnd_row(const Tables &T, const TileDesc &d, u32 j, u32 row)
+// Element offset of operand slot j for the i-th row of the tile (batch row `row`).  When the
+// descriptor says the tile's operand rows are evenly spaced, the address is computed and the
+// row-offset list is not read.
+__device__ inline u32 opnd_row(const Tables &T, const TileDesc &d, u32 j, u32 i, u32 row)
 {
     // written slot by slot so that the descriptor stays in scalar registers (no dynamic indexing)
-    if (j == 0 && (d.contig & 1u)) return d.base[0] + (row - d.row0) * d.sdim[0];
-    if (j == 1 && (d.contig & 2u)) return d.base[1] + (row - d.row0) * d.sdim[1];
-    if (j == 2 && (d.contig & 4u)) return d.base[2] + (row - d.row0) * d.sdim[2];
-    if (j == 3 && (d.contig & 8u)) return d.base[3] + (row - d.row0) * d.sdim[3];
+    if (j == 0 && (d.contig & 1u)) return d.base[0] + i * d.sstride[0];
+    if (j == 1 && (d.contig & 2u)) return d.base[1] + i * d.sstride[1];
+    if (j == 2 && (d.contig & 4u)) return d.base[2] + i * d.sstride[2];
+    if (j == 3 && (d.contig & 8u)) return d.base[3] + i * d.sstride[3];
     return T.opnd_off[d.opnd + j * d.B + row];
 }
 __device__ inline u32 slot_dim(const Tables &T, const TileDesc &d, u32 j)
@@ -57,7 +58,7 @@ __device__ inline u32 slot_dim(const Tables &T, const TileDesc &d, u32 j)
     return T.b_indim[d.indim + j];
 }
 
-__device__ inline float ew_value(const Tables &T, const TileDesc &d, u32 row, u32 col)
+__device__ inline float ew_value(const Tables &T, const TileDesc &d, u32 i, u32 row, u32 col)
 {
     switch (d.op) {
     case OP_INPUT: return T.payload[T.s_aux0[d.pos0 + row] + col];
@@ -67,18 +68,18 @@ __device__ inline float ew_value(const Tables &T, const TileDesc &d, u32 row, u3
     }
     case OP_ADD: {
         float acc = 0.f;
-        for (u32 j = 0; j < d.arity; ++j) acc += T.V[opnd_row(T, d, j, row) + col];
+        for (u32 j = 0; j < d.arity; ++j) acc += T.V[opnd_row(T, d, j, i, row) + col];
         return acc;
     }
-    case OP_CMULT: return T.V[opnd_row(T, d, 0, row) + col] * T.V[opnd_row(T, d, 1, row) + col];
-    case OP_TANH: return tanhf(T.V[opnd_row(T, d, 0, row) + col]);
-    case OP_SIGMOID: return sigmoidf_(T.V[opnd_row(T, d, 0, row) + col]);
-    case OP_SLICE: return T.V[opnd_row(T, d, 0, row) + (u32)d.aux0 + col];
+    case OP_CMULT: return T.V[opnd_row(T, d, 0, i, row) + col] * T.V[opnd_row(T, d, 1, i, row) + col];
+    case OP_TANH: return tanhf(T.V[opnd_row(T, d, 0, i, row) + col]);
+    case OP_SIGMOID: return sigmoidf_(T.V[opnd_row(T, d, 0, i, row) + col]);
+    case OP_SLICE: return T.V[opnd_row(T, d, 0, i, row) + (u32)d.aux0 + col];
     case OP_CONCAT: {
         u32 c = col;
         for (u32 j = 0; j < d.arity; ++j) {
             const u32 dj = slot_dim(T, d, j);
-            if (c < dj) return T.V[opnd_row(T, d, j, row) + c];
+            if (c < dj) return T.V[opnd_row(T, d, j, i, row) + c];
             c -= dj;
         }
         return 0.f;
@@ -87,7 +88,7 @@ __device__ inline float ew_value(const Tables &T, const TileDesc &d, u32 row, u3
     }
 }
 
-__device__ inline float4 ew_value4(const Tables &T, const TileDesc &d, u32 row, u32 col)
+__device__ inline float4 ew_value4(const Tables &T, const TileDesc &d, u32 i, u32 row, u32 col)
 {
     switch (d.op) {
     case OP_INPUT: return ld4(T.payload + T.s_aux0[d.pos0 + row] + col);
@@ -98,29 +99,29 @@ __device__ inline float4 ew_value4(const Tables &T, const TileDesc &d, u32 row, 
     case OP_ADD: {
         float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
         for (u32 j = 0; j < d.arity; ++j) {
-            const float4 x = ld4(T.V + opnd_row(T, d, j, row) + col);
+            const float4 x = ld4(T.V + opnd_row(T, d, j, i, row) + col);
             acc.x += x.x; acc.y += x.y; acc.z += x.z; acc.w += x.w;
         }
         return acc;
     }
     case OP_CMULT: {
-        const float4 a = ld4(T.V + opnd_row(T, d, 0, row) + col), b = ld4(T.V + opnd_row(T, d, 1, row) + col);
+        const float4 a = ld4(T.V + opnd_row(T, d, 0, i, row) + col), b = ld4(T.V + opnd_row(T, d, 1, i, row) + col);
         return make_float4(a.x * b.x, a.y * b.y, a.z * b.z, a.w * b.w);
     }
     case OP_TANH: {
-        const float4 a = ld4(T.V + opnd_row(T, d, 0, row) + col);
+        const float4 a = ld4(T.V + opnd_row(T, d, 0, i, row) + col);
         return make_float4(tanhf(a.x), tanhf(a.y), tanhf(a.z), tanhf(a.w));
     }
     case OP_SIGMOID: {
-        const float4 a = ld4(T.V + opnd_row(T, d, 0, row) + col);
+        const float4 a = ld4(T.V + opnd_row(T, d, 0, i, row) + col);
         return make_float4(sigmoidf_(a.x), sigmoidf_(a.y), sigmoidf_(a.z), sigmoidf_(a.w));
     }
-    case OP_SLICE: return ld4(T.V + opnd_row(T, d, 0, row) + (u32)d.aux0 + col);
+    case OP_SLICE: return ld4(T.V + opnd_row(T, d, 0, i, row) + (u32)d.aux0 + col);
     case OP_CONCAT: {
         u32 c = col;
         for (u32 j = 0; j < d.arity; ++j) {
             const u32 dj = slot_dim(T, d, j);
-            if (c < dj) return ld4(T.V + opnd_row(T, d, j, row) + c);
+            if (c < dj) return ld4(T.V + opnd_row(T, d, j, i, row) + c);
             c -= dj;
         }
         return make_float4(0.f, 0.f, 0.f, 0.f);
@@ -129,15 +130,21 @@ __device__ inline float4 ew_value4(const Tables &T, const TileDesc &d, u32 row, 
     }
 }
 
-// rows [row0, row0 + nrows) of the batch, all columns
-__device__ inline void ew_fwd_tile(const Tables &T, const TileDesc &d)
+// rows row0 + i * rstride (i < nrows) of the batch, all columns; worked by threads tid < nthr
+__device__ inline void ew_fwd_tile(const Tables &T, const TileDesc &d, u32 tid, u32 nthr)
 {
-    const u32 e_lo = d.row0 * d.d, e_hi = e_lo + d.nrows * d.d;
+    const u32 total = d.nrows * d.d;
     float *out = T.V + d.val_off;
     if (d.flags & 1u) {
-        for (u32 e = e_lo + threadIdx.x * 4; e < e_hi; e += WG * 4) st4(out + e, ew_value4(T, d, e / d.d, e % d.d));
+        for (u32 x = tid * 4; x < total; x += nthr * 4) {
+            const u32 i = x / d.d, col = x % d.d, row = d.row0 + i * d.rstride;
+            st4(out + row * d.d + col, ew_value4(T, d, i, row, col));
+        }
     } else {
-        for (u32 e = e_lo + threadIdx.x; e < e_hi; e += WG) out[e] = ew_value(T, d, e / d.d, e % d.d);
+        for (u32 x = tid; x < total; x += nthr) {
+            const u32 i = x / d.d, col = x % d.d, row = d.row0 + i * d.rstride;
+            out[row * d.d + col] = ew_value(T, d, i, row, col);
+        }
     }
 }
 
@@ -149,7 +156,7 @@ __device__ inline void red_fwd_tile(const Tables &T, const TileDesc &d)
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
     const u32 row = d.t * ROWS_PER_RED_TILE + w;
     if (row >= d.B) return;
-    const float *x = T.V + opnd_row(T, d, 0, row);
+    const float *x = T.V + opnd_row(T, d, 0, row - d.row0, row);
     const u32 K = d.k;
     if (d.op == OP_SQNORM) {
         float acc = 0.f;
@@ -295,7 +302,7 @@ __device__ inline void matvec_fwd_tile(const Tables &T, const TileDesc &d, float
     const bool fast = (d.flags & 2u) && (d.k & 3u) == 0;
     const u32 row = r0 + (threadIdx.x & 31);
     const bool row_ok = row < d.B;
-    const float *xrow = T.V + (row_ok ? opnd_row(T, d, 0, row) : 0u);
+    const float *xrow = T.V + (row_ok ? opnd_row(T, d, 0, row - d.row0, row) : 0u);
     gemm_nt_tile(xrow, row_ok, d.B, P.data, bias, d.d, d.k, fast, T.V + d.val_off, r0, i0, lds);
 }
 
@@ -463,16 +470,15 @@ __device__ inline float edge_term(const Tables &T, u32 kind, u32 goff, u32 voff,
     }
 }
 
-__device__ inline void pull_tile(const Tables &T, const PullDesc &d)
+__device__ inline void pull_tile(const Tables &T, const PullDesc &d, u32 tid, u32 nthr)
 {
-    const u32 e_lo = d.row0 * d.d, e_hi = e_lo + d.nrows * d.d;
+    const u32 total = d.nrows * d.d;
     const u32 root_pos = T.root_pos[0];
-    for (u32 e = e_lo + threadIdx.x; e < e_hi; e += WG) {
-        const u32 row = e / d.d, col = e % d.d;
+    for (u32 x = tid; x < total; x += nthr) {
+        const u32 dr = x / d.d, col = x % d.d, row = d.row0 + dr * d.rstride;
         const u32 own = d.val_off + row * d.d;
         float acc = (d.pos0 + row == root_pos) ? 1.0f : 0.0f;
         if (d.n_uni != PULL_GENERIC) {
-            const u32 dr = row - d.row0;
 #pragma unroll
             for (u32 j = 0; j < 4; ++j) {
                 if (j < d.n_uni) {
@@ -503,40 +509,84 @@ __device__ inline void run_fwd_tile(const Tables &T, const TileDesc &d, float *l
     case OP_SQNORM: red_fwd_tile(T, d); break;
     case OP_ADD:
         if (d.arity >= (u32)WIDE_ADD_ARITY) { wide_add_tile(T, d, lds); break; }
-        ew_fwd_tile(T, d);
+        ew_fwd_tile(T, d, threadIdx.x, WG);
         break;
-    default: ew_fwd_tile(T, d); break;
+    default: ew_fwd_tile(T, d, threadIdx.x, WG); break;
     }
 }
 
-// One launch = one slot.  A work item is a run of tiles that one workgroup executes in order;
-// runs longer than one tile are fused chains of row-aligned component-wise batches over the same
-// block of rows, and a workgroup barrier separates members of different depth.
+constexpr u32 RUN_STAGE = 32;   // descriptors of a fused run staged in LDS at a time
+
+// One launch = one slot.  A work item is a run of tiles that one workgroup executes in order.
+// Runs of one tile (GEMM, reduction and single-batch tiles) keep their descriptor in scalar
+// registers.  Longer runs are fused chains of group-aligned component-wise batches over one block
+// of groups: the descriptors are staged in LDS with one coalesced load, tiles of the same depth
+// are spread over the four waves, and a workgroup barrier separates depths.
 __global__ __launch_bounds__(WG) void k_fwd_step(Tables T, u32 work_lo, u32 work_hi)
 {
     __shared__ float lds[LDS_FLOATS];
+    __shared__ TileDesc sdesc[RUN_STAGE];
+    const u32 lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     for (u32 w = work_lo + blockIdx.x; w < work_hi; w += gridDim.x) {
         const WorkRec wr = T.works_f[w];
-        TileDesc d = T.tiles_f[wr.first];
-        for (u32 i = 0; i < wr.len; ++i) {
-            const TileDesc cur = d;
-            if (i + 1 < wr.len) d = T.tiles_f[wr.first + i + 1];   // next descriptor in flight during this tile
-            run_fwd_tile(T, cur, lds);
-            if (i + 1 < wr.len && d.depth != cur.depth) __syncthreads();
+        if (wr.len == 1) {
+            const TileDesc d = T.tiles_f[wr.first];
+            run_fwd_tile(T, d, lds);
+            continue;
+        }
+        for (u32 c0 = 0; c0 < wr.len; c0 += RUN_STAGE) {
+            const u32 cn = wr.len - c0 < RUN_STAGE ? wr.len - c0 : RUN_STAGE;
+            __syncthreads();
+            {   // stage cn descriptors (32 words each)
+                const u32 *src = reinterpret_cast<const u32 *>(T.tiles_f + wr.first + c0);
+                u32 *dst = reinterpret_cast<u32 *>(sdesc);
+                for (u32 x = threadIdx.x; x < cn * 32; x += WG) dst[x] = src[x];
+            }
+            __syncthreads();
+            u32 i = 0;
+            while (i < cn) {
+                u32 glen = sdesc[i].contig >> 16;
+                if (glen == 0) glen = 1;
+                if (glen > cn - i) glen = cn - i;   // a depth group cut by the staging window: still same depth
+                if (glen == 1) ew_fwd_tile(T, sdesc[i], threadIdx.x, WG);
+                else for (u32 t = i + wave; t < i + glen; t += WG / 64) ew_fwd_tile(T, sdesc[t], lane, 64);
+                i += glen;
+                if (i < cn || c0 + cn < wr.len) __syncthreads();
+            }
         }
     }
 }
 
 __global__ __launch_bounds__(WG) void k_bwd_pull_step(Tables T, u32 work_lo, u32 work_hi)
 {
+    __shared__ PullDesc sdesc[RUN_STAGE];
+    const u32 lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     for (u32 w = work_lo + blockIdx.x; w < work_hi; w += gridDim.x) {
         const WorkRec wr = T.works_a[w];
-        PullDesc d = T.tiles_a[wr.first];
-        for (u32 i = 0; i < wr.len; ++i) {
-            const PullDesc cur = d;
-            if (i + 1 < wr.len) d = T.tiles_a[wr.first + i + 1];
-            pull_tile(T, cur);
-            if (i + 1 < wr.len && d.depth != cur.depth) __syncthreads();
+        if (wr.len == 1) {
+            const PullDesc d = T.tiles_a[wr.first];
+            pull_tile(T, d, threadIdx.x, WG);
+            continue;
+        }
+        for (u32 c0 = 0; c0 < wr.len; c0 += RUN_STAGE) {
+            const u32 cn = wr.len - c0 < RUN_STAGE ? wr.len - c0 : RUN_STAGE;
+            __syncthreads();
+            {
+                const u32 *src = reinterpret_cast<const u32 *>(T.tiles_a + wr.first + c0);
+                u32 *dst = reinterpret_cast<u32 *>(sdesc);
+                for (u32 x = threadIdx.x; x < cn * (u32)(sizeof(PullDesc) / 4); x += WG) dst[x] = src[x];
+            }
+            __syncthreads();
+            u32 i = 0;
+            while (i < cn) {
+                u32 glen = sdesc[i].grp_len;
+                if (glen == 0) glen = 1;
+                if (glen > cn - i) glen = cn - i;
+                if (glen == 1) pull_tile(T, sdesc[i], threadIdx.x, WG);
+                else for (u32 t = i + wave; t < i + glen; t += WG / 64) pull_tile(T, sdesc[t], lane, 64);
+                i += glen;
+                if (i < cn || c0 + cn < wr.len) __syncthreads();
+            }
         }
     }
 }

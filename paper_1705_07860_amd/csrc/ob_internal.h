@@ -66,18 +66,20 @@ struct ParamDesc {
 // One forward (or dX) tile: everything the tile routine needs in one 128-byte record, so that a
 // workgroup starts its data loads after a single descriptor load.  For up to four operand slots
 // the record says whether the operand rows of THIS tile are consecutive in the value arena
-// (then row r of slot j sits at base[j] + (r - row0) * sdim[j] and the row-offset list is not
-// read at all: the inputs are used as they are, without an index hop).
+// (then the i-th row of the tile reads slot j at base[j] + i * sstride[j] and the row-offset list
+// is not read at all: the inputs are used as they are, without an index hop).
 struct TileDesc {
     u32 op, B, d, arity;
     u32 pos0, val_off, dx_off, k;
-    i32 param, bias, aux0, aux1;
+    i32 param, bias, aux0;
+    u32 rstride;                     // component-wise tiles cover rows row0 + i * rstride, i < nrows
     u32 opnd, indim, flags, t;       // flags: bit 0 float4 path allowed, bit 1 operand rows 16-byte aligned
-    u32 contig, row0;                // contig bit j: slot j consecutive over the rows of this tile
-    u32 base[4];
+    u32 contig, row0;                // contig bits 0..3: operand rows of slot j are evenly spaced over this tile;
+                                     // bits 16..31: tiles of the same depth that follow in the run, this one included
+    u32 base[4];                     // operand row offset of slot j for the tile's first row
     u32 sdim[4];                     // dimension of operand slot j
-    u32 nrows, depth;                // component-wise tiles cover rows [row0, row0 + nrows); depth of the batch
-    u32 pad[4];
+    u32 nrows, depth;
+    u32 sstride[4];                  // operand row spacing of slot j (elements per tile row step)
 };
 static_assert(sizeof(TileDesc) == 128, "TileDesc must be 128 bytes");
 
@@ -90,20 +92,21 @@ struct UEdge { u32 kind, goff, voff, gs, vs; i32 a0, a1; };
 constexpr u32 PULL_GENERIC = 0xffffffffu;
 struct PullDesc {
     u32 pos0, B, d, val_off;
-    u32 depth, row0, n_uni, nrows;   // rows [row0, row0 + nrows) of the batch, all columns
-    UEdge e[4];
-    u32 pad[4];
+    u32 depth, row0, n_uni, nrows;   // rows row0 + i * rstride, i < nrows, of the batch, all columns
+    UEdge e[4];                      // edge j of the i-th row: e[j] shifted by i * (gs, vs)
+    u32 rstride, grp_len, pad[2];    // grp_len: tiles of the same depth that follow in the run, this one included
 };
 static_assert(sizeof(PullDesc) == 160, "PullDesc must be 160 bytes");
 
 // A launch chain: batches that run in the same launch slot.  A fused chain holds component-wise
-// batches with equal row counts whose in-chain operands are row-aligned (row r of the consumer
-// reads row r of the producer), so one workgroup can own a block of rows and run the members
-// one after the other with workgroup barriers only.  Every other batch is a chain of its own.
+// batches whose rows fall into G groups (member b has B_b / G consecutive rows per group) such
+// that every in-chain operand of a row lies in the row's own group.  One workgroup then owns a
+// block of groups and runs the members one after the other with workgroup barriers only.
+// Every other batch is a chain of its own.
 struct ChainRec {
     u32 first, k;          // members are lorder[first .. first + k)
-    u32 slot, fused;       // fused: component-wise members tiled by row blocks
-    u32 B, R, nrb, pad;    // rows, rows per block, number of row blocks
+    u32 slot, fused;       // fused: component-wise members tiled by group blocks
+    u32 G, Rg, nrb, kt;    // groups, groups per block, number of blocks, tiles per block (sum of rows per group)
 };
 struct CLay {              // scan element of the per-chain launch layout
     u32 tf, wf, ta, wa, tb, p0, p1, p2;   // forward tiles/work items, pull tiles/work items, dX tiles

@@ -316,19 +316,22 @@ __device__ inline bool op_chain_source(u32 op, u32 arity)
     return op == OP_INPUT || op == OP_LOOKUP || op_chainable(op, arity);
 }
 
-// producer batch of operand slot j of the node at schedule position p, and whether the producer
-// row index equals `row`
-__device__ inline u32 producer_batch(const Tables &T, u32 p, u32 j, u32 row, bool *same_row)
+// producer batch of operand slot j of the node at schedule position p, and the producer's row
+__device__ inline u32 producer_batch(const Tables &T, u32 p, u32 j, u32 *prow)
 {
     const u32 v = T.order[p];
     const u32 pu = T.pos_of[T.in_idx[T.in_off[v] + j]];
     const u32 by = T.batch_of_pos[pu];
-    *same_row = (pu - T.batches[by].pos0) == row;
+    *prow = pu - T.batches[by].pos0;
     return by;
 }
 
-// per edge: clears b_align[(batch, slot)] unless the slot reads, row for row, one producer batch
-// with the same number of rows
+constexpr u32 FUSE_MAX_MULT = 4;
+__device__ inline u32 gcd_u32(u32 a, u32 b) { while (b) { const u32 t = a % b; a = b; b = t; } return a; }
+
+// per edge: clears b_align[(batch, slot)] unless every row of the slot reads a component-wise (or
+// leaf) producer batch row of its own group, where with G = gcd of the two row counts the
+// consumer group is row / (B_cons / G) and the producer group is row / (B_prod / G)
 __global__ void k_align(Tables T)
 {
     const u32 e = blockIdx.x * blockDim.x + threadIdx.x;
@@ -339,16 +342,23 @@ __global__ void k_align(Tables T)
     const u32 b = T.batch_of_pos[p];
     const BatchRec &r = T.batches[b];
     const u32 row = p - r.pos0;
-    bool same0, same;
-    const u32 by0 = producer_batch(T, r.pos0, j, 0, &same0);
-    const u32 by = producer_batch(T, p, j, row, &same);
-    const BatchRec &y = T.batches[by0];
-    const bool ok = same && by == by0 && y.B == r.B && op_chainable(r.op, r.arity) && op_chain_source(y.op, y.arity);
+    u32 prow;
+    const u32 by = producer_batch(T, p, j, &prow);
+    const BatchRec &y = T.batches[by];
+    bool ok = op_chainable(r.op, r.arity) && op_chain_source(y.op, y.arity);
+    if (ok) {
+        // a group may hold at most FUSE_MAX_MULT rows of a batch: fusing must keep B / that many
+        // independent groups, or the fused launch would serialise what a launch per level runs wide
+        const u32 G = gcd_u32(r.B, y.B);
+        const u32 mc = r.B / G, mp = y.B / G;
+        ok = mc <= FUSE_MAX_MULT && mp <= FUSE_MAX_MULT && row / mc == prow / mp;
+    }
     if (!ok) T.b_align[r.indim + j] = 0;
 }
 
-// per edge: emits one batch-level dependency per run of rows with the same producer batch
-__global__ void k_bedges(Tables T)
+// per edge, in schedule order (index s_in_off[p] + j): consumer batch, producer batch, and
+// whether a launch boundary is needed (0: the edge can be fused)
+__global__ void k_erecs(Tables T, u32 *rec_cons, u32 *rec_prod, u32 *rec_w, u32 *lvl_eoff)
 {
     const u32 e = blockIdx.x * blockDim.x + threadIdx.x;
     if (e >= T.E) return;
@@ -357,100 +367,162 @@ __global__ void k_bedges(Tables T)
     const u32 p = T.pos_of[v];
     const u32 b = T.batch_of_pos[p];
     const BatchRec &r = T.batches[b];
-    const u32 row = p - r.pos0;
-    bool dummy;
-    const u32 by = producer_batch(T, p, j, row, &dummy);
-    if (row > 0 && producer_batch(T, p - 1, j, row - 1, &dummy) == by) return;
-    BEdge be; be.cons = b; be.prod = by; be.w = T.b_align[r.indim + j] ? 0u : 1u;
-    T.bedges[atomicAdd(&T.hdr->n_bedges, 1u)] = be;
+    u32 prow;
+    const u32 by = producer_batch(T, p, j, &prow);
+    const u32 es = T.s_in_off[p] + j;
+    rec_cons[es] = b;
+    rec_prod[es] = by;
+    rec_w[es] = T.b_align[r.indim + j] ? 0u : 1u;
+    if (j == 0) {   // level boundaries of the schedule-ordered edge list
+        const u32 st = r.step;
+        if (p == 0 || T.step[T.order[p - 1]] != st) lvl_eoff[st] = es;
+    }
 }
 
-// One workgroup: launch slot of every batch = longest path over the batch dependencies with
-// weight 0 for fusable edges and 1 otherwise (relaxed to a fixed point in LDS), then a chain
-// label = smallest batch id reachable over fusable edges inside the same slot.
-constexpr u32 SLOT_MAX_NB = 7168;   // two u32 tables in 56 KB of LDS
+// edges of level l are [lvl_eoff[l], lvl_eoff[l+1]); levels without edges inherit the next start
+__global__ void k_lvl_fix(Tables T, u32 *lvl_eoff)
+{
+    // single thread: walk backwards filling levels that no node with operands started
+    const u32 L = T.hdr->n_steps;
+    u32 next = T.E;
+    lvl_eoff[L] = T.E;
+    for (u32 l = L; l-- > 0;) {
+        if (lvl_eoff[l] == 0xffffffffu) lvl_eoff[l] = next; else next = lvl_eoff[l];
+    }
+}
+
+// One workgroup.  Launch slot of a batch = longest path over its dependencies, where an edge that
+// can be fused (row groups aligned, both sides component-wise) costs 0 and any other edge costs
+// one launch boundary.  Levels are walked in order, so every producer's slot is final when it is
+// read; the records of the next level are loaded while the current one is reduced.  Batches
+// joined by fusable edges inside one slot then get a common chain label.
+constexpr u32 SLOT_MAX_NB = 4096;     // 16 KB slots + 16 KB labels + 24 KB pair table of LDS
+constexpr u32 PAIR_TBL = 6143;        // open-addressing set of fused (consumer, producer) batch pairs
+constexpr int SLOT_BITS = 13;         // bits of a slot or a label when the plan is fused
 constexpr int SLOT_THREADS = 1024;
-__global__ __launch_bounds__(SLOT_THREADS) void k_slots(Tables T, int fuse)
+
+__device__ inline void pair_insert(u32 *tbl, u32 c, u32 y, u32 *overflow)
+{
+    const u32 key = ((c << SLOT_BITS) | y) + 1u;
+    u32 h = (key * 2654435761u) % PAIR_TBL;
+    for (u32 probe = 0; probe < PAIR_TBL; ++probe) {
+        const u32 old = atomicCAS(&tbl[h], 0u, key);
+        if (old == 0u || old == key) return;
+        h = h + 1 == PAIR_TBL ? 0 : h + 1;
+    }
+    *overflow = 1;
+}
+
+__global__ __launch_bounds__(SLOT_THREADS) void k_slots(Tables T, int fuse, const u32 *rec_cons, const u32 *rec_prod,
+                                                        const u32 *rec_w, const u32 *lvl_eoff)
 {
     __shared__ u32 s_slot[SLOT_MAX_NB];
     __shared__ u32 s_label[SLOT_MAX_NB];
-    __shared__ u32 s_changed;
+    __shared__ u32 s_pair[PAIR_TBL];
+    __shared__ u32 s_over, s_changed;
     const u32 nb = T.hdr->n_batches;
-    const u32 ne = T.hdr->n_bedges;
-    if (!fuse || nb > SLOT_MAX_NB) {   // one slot per step, no fusion
-        for (u32 b = threadIdx.x; b < nb; b += SLOT_THREADS) { T.slot_of[b] = T.batches[b].step; T.label_of[b] = b; }
-        if (threadIdx.x == 0) { T.hdr->n_slots = T.hdr->n_steps; T.hdr->slot_sweeps = 0; }
-        return;
-    }
-    for (u32 b = threadIdx.x; b < nb; b += SLOT_THREADS) { s_slot[b] = 0; s_label[b] = b; }
-    u32 sweeps = 0;
-    while (true) {
-        if (threadIdx.x == 0) s_changed = 0;
+    const u32 L = T.hdr->n_steps;
+    const u32 tid = threadIdx.x;
+    bool fallback = !fuse || nb > SLOT_MAX_NB;
+    if (!fallback) {
+        for (u32 b = tid; b < nb; b += SLOT_THREADS) { s_slot[b] = 0; s_label[b] = b; }
+        for (u32 i = tid; i < PAIR_TBL; i += SLOT_THREADS) s_pair[i] = 0;
+        if (tid == 0) s_over = 0;
         __syncthreads();
-        for (u32 e = threadIdx.x; e < ne; e += SLOT_THREADS) {
-            const BEdge be = T.bedges[e];
-            const u32 want = s_slot[be.prod] + be.w;
-            if (want > s_slot[be.cons]) { atomicMax(&s_slot[be.cons], want); s_changed = 1; }
+        u32 lo = lvl_eoff[0], hi = L > 0 ? lvl_eoff[1] : lo;
+        u32 c = 0, y = 0, w = 0;
+        bool have = lo + tid < hi;
+        if (have) { c = rec_cons[lo + tid]; y = rec_prod[lo + tid]; w = rec_w[lo + tid]; }
+        for (u32 l = 0; l < L; ++l) {
+            // the first record of the next level is loaded while this level is reduced
+            const u32 nlo = hi, nhi = (l + 1 < L) ? lvl_eoff[l + 2] : hi;
+            u32 nc = 0, ny = 0, nw = 0;
+            const bool nhave = (l + 1 < L) && nlo + tid < nhi;
+            if (nhave) { nc = rec_cons[nlo + tid]; ny = rec_prod[nlo + tid]; nw = rec_w[nlo + tid]; }
+            if (have) atomicMax(&s_slot[c], s_slot[y] + w);
+            for (u32 e = lo + tid + SLOT_THREADS; e < hi; e += SLOT_THREADS)
+                atomicMax(&s_slot[rec_cons[e]], s_slot[rec_prod[e]] + rec_w[e]);
+            __syncthreads();
+            // slots of this level are final: remember the fused pairs that stay inside a slot
+            if (have && w == 0u && s_slot[y] == s_slot[c]) pair_insert(s_pair, c, y, &s_over);
+            for (u32 e = lo + tid + SLOT_THREADS; e < hi; e += SLOT_THREADS) {
+                const u32 cc = rec_cons[e], yy = rec_prod[e];
+                if (rec_w[e] == 0u && s_slot[yy] == s_slot[cc]) pair_insert(s_pair, cc, yy, &s_over);
+            }
+            lo = nlo; hi = nhi; c = nc; y = ny; w = nw; have = nhave;
         }
         __syncthreads();
-        ++sweeps;
-        const u32 ch = s_changed;
-        __syncthreads();
-        if (!ch || sweeps > nb + 1) break;
+        if (s_over) fallback = true;
     }
+    if (fallback) {   // one slot per step, no fusion
+        for (u32 b = tid; b < nb; b += SLOT_THREADS) { T.slot_of[b] = T.batches[b].step; T.label_of[b] = b; }
+        if (tid == 0) { T.hdr->n_slots = T.hdr->n_steps; T.hdr->slot_sweeps = 0; T.hdr->p0 = 1; }
+        return;
+    }
+    u32 sweeps = 0, npairs = 0;
     while (true) {
-        if (threadIdx.x == 0) s_changed = 0;
+        if (tid == 0) s_changed = 0;
         __syncthreads();
-        for (u32 e = threadIdx.x; e < ne; e += SLOT_THREADS) {
-            const BEdge be = T.bedges[e];
-            if (be.w == 0 && s_slot[be.prod] == s_slot[be.cons]) {
-                const u32 a = s_label[be.prod], c = s_label[be.cons];
-                if (a != c) { const u32 m = a < c ? a : c; atomicMin(&s_label[be.prod], m); atomicMin(&s_label[be.cons], m); s_changed = 1; }
+        for (u32 i = tid; i < PAIR_TBL; i += SLOT_THREADS) {
+            const u32 key = s_pair[i];
+            if (!key) continue;
+            if (sweeps == 0) ++npairs;
+            const u32 cc = (key - 1u) >> SLOT_BITS, yy = (key - 1u) & ((1u << SLOT_BITS) - 1u);
+            const u32 a = s_label[cc], bb = s_label[yy];
+            if (a != bb) {
+                const u32 m = a < bb ? a : bb;
+                atomicMin(&s_label[cc], m);
+                atomicMin(&s_label[yy], m);
+                s_changed = 1;
             }
         }
         __syncthreads();
         ++sweeps;
         const u32 ch = s_changed;
         __syncthreads();
-        if (!ch || sweeps > 3 * nb + 3) break;
+        if (!ch || sweeps > nb + 2) break;
     }
     u32 mx = 0;
-    for (u32 b = threadIdx.x; b < nb; b += SLOT_THREADS) {
+    for (u32 b = tid; b < nb; b += SLOT_THREADS) {
         T.slot_of[b] = s_slot[b]; T.label_of[b] = s_label[b];
         mx = s_slot[b] > mx ? s_slot[b] : mx;
     }
-    __syncthreads();
-    if (threadIdx.x == 0) s_changed = 0;
+    if (tid == 0) s_changed = 0;
     __syncthreads();
     atomicMax(&s_changed, mx);
+    atomicAdd(&T.hdr->n_bedges, npairs);
     __syncthreads();
-    if (threadIdx.x == 0) { T.hdr->n_slots = s_changed + 1; T.hdr->slot_sweeps = sweeps; }
+    if (tid == 0) { T.hdr->n_slots = s_changed + 1; T.hdr->slot_sweeps = sweeps; }
 }
 
-__global__ void k_launch_keys(Tables T, u64 *keys, u32 *vals)
+__global__ void k_launch_keys(Tables T, u64 *keys, u32 *vals, u32 n_pad)
 {
     const u32 b = blockIdx.x * blockDim.x + threadIdx.x;
-    if (b >= T.hdr->n_batches) { if (b < T.n) { keys[b] = ~0ull; vals[b] = b; } return; }
-    keys[b] = ((u64)T.slot_of[b] << 32) | T.label_of[b];
+    if (b >= n_pad) return;
     vals[b] = b;
+    if (b >= T.hdr->n_batches) { keys[b] = ~0ull; return; }
+    // unfused plans are already in launch order (slot = step): equal keys keep that order
+    keys[b] = T.hdr->p0 ? 0ull : (((u64)T.slot_of[b] << SLOT_BITS) | T.label_of[b]);
 }
 
 __device__ inline u32 rows_per_block(u32 d) { return d >= (u32)EW_TILE ? 1u : (u32)EW_TILE / d; }
 
 // chains from the launch order: head flags, then one thread per chain head fills the record
-__global__ void k_chain_flags(Tables T, const u64 *skey, const u32 *sval, u32 *flag)
+__device__ inline u64 chain_key(const Tables &T, u32 b) { return ((u64)T.slot_of[b] << 32) | T.label_of[b]; }
+
+__global__ void k_chain_flags(Tables T, const u32 *sval, u32 *flag, u32 n_pad)
 {
     const u32 i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (i >= T.n) return;
+    if (i >= n_pad) return;
     const u32 nb = T.hdr->n_batches;
     if (i < nb) T.lorder[i] = sval[i];
-    flag[i] = (i < nb && (i == 0 || skey[i] != skey[i - 1])) ? 1u : 0u;
+    flag[i] = (i < nb && (i == 0 || chain_key(T, sval[i]) != chain_key(T, sval[i - 1]))) ? 1u : 0u;
 }
 
-__global__ void k_chain_recs(Tables T, const u64 *skey, const u32 *flag, const u32 *flag_excl, CLay *clay_in)
+__global__ void k_chain_recs(Tables T, const u32 *flag, const u32 *flag_excl, CLay *clay_in, u32 n_pad)
 {
     const u32 i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (i >= T.n) return;
+    if (i >= n_pad) return;
     const u32 nb = T.hdr->n_batches;
     CLay L; L.tf = L.wf = L.ta = L.wa = L.tb = L.p0 = L.p1 = L.p2 = 0;
     if (i < nb) {
@@ -461,17 +533,22 @@ __global__ void k_chain_recs(Tables T, const u64 *skey, const u32 *flag, const u
     if (i < nb && flag[i]) {
         const u32 c = flag_excl[i];
         u32 k = 1;
-        while (i + k < nb && skey[i + k] == skey[i]) ++k;
+        while (i + k < nb && !flag[i + k]) ++k;
         const BatchRec r0 = T.batches[T.lorder[i]];
         ChainRec cr;
-        cr.first = i; cr.k = k; cr.slot = (u32)(skey[i] >> 32); cr.B = r0.B; cr.pad = 0;
+        cr.first = i; cr.k = k; cr.slot = T.slot_of[T.lorder[i]];
         cr.fused = (op_chainable(r0.op, r0.arity) || r0.op == OP_INPUT || r0.op == OP_LOOKUP) ? 1u : 0u;
-        u32 dmax = r0.d;
-        for (u32 m = 1; m < k; ++m) { const u32 dm = T.batches[T.lorder[i + m]].d; dmax = dm > dmax ? dm : dmax; }
-        cr.R = rows_per_block(dmax);
-        cr.nrb = cdiv(cr.B, cr.R);
+        u32 dmax = r0.d, G = r0.B;
+        for (u32 m = 1; m < k; ++m) {
+            const BatchRec &rm = T.batches[T.lorder[i + m]];
+            dmax = rm.d > dmax ? rm.d : dmax;
+            G = gcd_u32(G, rm.B);
+        }
+        u32 kt = 0;
+        for (u32 m = 0; m < k; ++m) kt += T.batches[T.lorder[i + m]].B / G;
+        cr.G = G; cr.Rg = rows_per_block(dmax); cr.nrb = cdiv(G, cr.Rg); cr.kt = cr.fused ? kt : 1u;
         if (cr.fused) {
-            L.tf = L.ta = cr.nrb * k;
+            L.tf = L.ta = cr.nrb * kt;
             L.wf = L.wa = cr.nrb;
         } else {
             switch (r0.op) {
@@ -488,10 +565,10 @@ __global__ void k_chain_recs(Tables T, const u64 *skey, const u32 *flag, const u
     }
 }
 
-__global__ void k_clay_zero(Tables T, CLay *clay_in)
+__global__ void k_clay_zero(CLay *clay_in, u32 n_pad)
 {
     const u32 i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (i >= T.n) return;
+    if (i >= n_pad) return;
     CLay L; L.tf = L.wf = L.ta = L.wa = L.tb = L.p0 = L.p1 = L.p2 = 0;
     clay_in[i] = L;
 }
@@ -514,54 +591,59 @@ __global__ void k_slot_tables(Tables T, const CLay *clay_ex, const CLay *total)
 }
 
 // ---- tile descriptors ------------------------------------------------------------------------------
-constexpr u32 CONTIG_MAX_ROWS = 32;   // tiles with more rows skip the contiguity test
+constexpr u32 CONTIG_MAX_ROWS = 32;   // tiles with more rows skip the even-spacing test
 
-// descriptor of tile t of batch r (forward or dX); component-wise tiles cover rows [row0, row0+nrows)
+// descriptor of a forward or dX tile of batch r.  Component-wise tiles (row_block) cover the rows
+// row0 + i * rstride, i < nrows; the other kinds derive their rows from the tile index t.
 __device__ inline void fill_tile_desc(const Tables &T, const BatchRec &r, u32 t, bool dx, bool row_block, u32 row0,
-                                      u32 nrows, TileDesc &d)
+                                      u32 nrows, u32 rstride, TileDesc &d)
 {
     d.op = r.op; d.B = r.B; d.d = r.d; d.arity = r.arity;
     d.pos0 = r.pos0; d.val_off = r.val_off; d.dx_off = r.dx_off; d.k = r.k;
-    d.param = r.param; d.bias = r.bias; d.aux0 = r.aux0; d.aux1 = r.aux1;
+    d.param = r.param; d.bias = r.bias; d.aux0 = r.aux0; d.rstride = rstride;
     d.opnd = r.opnd; d.indim = r.indim; d.flags = r.vec4; d.t = t;
     d.contig = 0; d.row0 = row0; d.nrows = nrows; d.depth = r.step;
-    for (int j = 0; j < 4; ++j) { d.base[j] = 0; d.sdim[j] = 0; d.pad[j] = 0; }
+    for (int j = 0; j < 4; ++j) { d.base[j] = 0; d.sdim[j] = 0; d.sstride[j] = 0; }
     if (dx || r.arity == 0) return;
-    u32 r_lo, r_hi;   // rows this tile touches
-    if (row_block) {
-        r_lo = row0; r_hi = row0 + nrows - 1;
-    } else if (r.op == OP_MATVEC) {
-        const u32 ntn = (r.d + GT - 1) / GT;
-        r_lo = (t / ntn) * GT; r_hi = r_lo + GT - 1;
-    } else if (r.op == OP_PICK_NLS || r.op == OP_SQNORM) {
-        r_lo = t * ROWS_PER_RED_TILE; r_hi = r_lo + ROWS_PER_RED_TILE - 1;
-    } else {
-        r_lo = r_hi = t;   // wide sum
+    if (!row_block) {
+        u32 r_lo, r_hi;
+        if (r.op == OP_MATVEC) {
+            const u32 ntn = (r.d + GT - 1) / GT;
+            r_lo = (t / ntn) * GT; r_hi = r_lo + GT - 1;
+        } else if (r.op == OP_PICK_NLS || r.op == OP_SQNORM) {
+            r_lo = t * ROWS_PER_RED_TILE; r_hi = r_lo + ROWS_PER_RED_TILE - 1;
+        } else {
+            r_lo = r_hi = t;   // wide sum
+        }
+        if (r_hi >= r.B) r_hi = r.B - 1;
+        d.row0 = row0 = r_lo; d.nrows = nrows = r_hi - r_lo + 1; d.rstride = rstride = 1;
     }
-    if (r_hi >= r.B) r_hi = r.B - 1;
-    if (!row_block) d.row0 = r_lo;
     const u32 ns = r.arity < 4 ? r.arity : 4;
     for (u32 j = 0; j < ns; ++j) {
         const u32 *op = T.opnd_off + r.opnd + j * r.B;
-        const u32 sd = T.b_indim[r.indim + j];
-        const u32 base = op[r_lo];
-        d.base[j] = base; d.sdim[j] = sd;
-        bool ok = (r_hi - r_lo) < CONTIG_MAX_ROWS;
-        for (u32 rr = r_lo + 1; ok && rr <= r_hi; ++rr) ok = op[rr] == base + (rr - r_lo) * sd;
+        const u32 base = op[row0];
+        d.base[j] = base; d.sdim[j] = T.b_indim[r.indim + j];
+        bool ok = nrows <= CONTIG_MAX_ROWS;
+        u32 ss = 0;
+        if (ok && nrows > 1) {
+            ss = op[row0 + rstride] - base;
+            for (u32 i = 2; ok && i < nrows; ++i) ok = op[row0 + i * rstride] == base + i * ss;
+        }
+        d.sstride[j] = ss;
         if (ok) d.contig |= 1u << j;
     }
 }
 
 constexpr u32 PULL_MAX_ROWS = 16;
 
-__device__ inline void fill_pull_desc(const Tables &T, const BatchRec &r, u32 row0, u32 nrows, PullDesc &d)
+__device__ inline void fill_pull_desc(const Tables &T, const BatchRec &r, u32 row0, u32 nrows, u32 rstride, PullDesc &d)
 {
     d.pos0 = r.pos0; d.B = r.B; d.d = r.d; d.val_off = r.val_off;
-    d.depth = r.step; d.row0 = row0; d.nrows = nrows; d.n_uni = PULL_GENERIC;
-    for (int j = 0; j < 4; ++j) { UEdge z; z.kind = 0; z.goff = z.voff = z.gs = z.vs = 0; z.a0 = z.a1 = 0; d.e[j] = z; d.pad[j] = 0; }
+    d.depth = r.step; d.row0 = row0; d.nrows = nrows; d.n_uni = PULL_GENERIC; d.rstride = rstride;
+    for (int j = 0; j < 4; ++j) { UEdge z; z.kind = 0; z.goff = z.voff = z.gs = z.vs = 0; z.a0 = z.a1 = 0; d.e[j] = z; }
+    d.grp_len = 1; d.pad[0] = d.pad[1] = 0;
     if (nrows > PULL_MAX_ROWS) return;
-    const u32 r_lo = row0, r_hi = row0 + nrows - 1;
-    const u32 u0 = T.order[r.pos0 + r_lo];
+    const u32 u0 = T.order[r.pos0 + row0];
     const u32 q0 = T.succ_off[u0];
     const u32 cnt = T.succ_off[u0 + 1] - q0;
     if (cnt > 4) return;
@@ -573,16 +655,16 @@ __device__ inline void fill_pull_desc(const Tables &T, const BatchRec &r, u32 ro
         ue.gs = ue.vs = 0; ue.a0 = first[j].a0; ue.a1 = first[j].a1;
         d.e[j] = ue;
     }
-    for (u32 rr = r_lo + 1; rr <= r_hi; ++rr) {
-        const u32 u = T.order[r.pos0 + rr];
+    for (u32 i = 1; i < nrows; ++i) {
+        const u32 u = T.order[r.pos0 + row0 + i * rstride];
         const u32 q = T.succ_off[u];
         if (T.succ_off[u + 1] - q != cnt) return;
         for (u32 j = 0; j < cnt; ++j) {
             const EdgeRec er = T.edges[q + j];
             if (er.kind != first[j].kind || er.a0 != first[j].a0 || er.a1 != first[j].a1) return;
             const u32 dg = er.goff - first[j].goff, dv = er.voff - first[j].voff;
-            if (rr == r_lo + 1) { d.e[j].gs = dg; d.e[j].vs = dv; }
-            else if (dg != d.e[j].gs * (rr - r_lo) || dv != d.e[j].vs * (rr - r_lo)) return;
+            if (i == 1) { d.e[j].gs = dg; d.e[j].vs = dv; }
+            else if (dg != d.e[j].gs * i || dv != d.e[j].vs * i) return;
         }
     }
     d.n_uni = cnt;
@@ -619,34 +701,68 @@ __global__ void k_tiles(Tables T, const CLay *clay_ex, const CLay *total, u32 ca
             const u32 c = chain_of_index(clay_ex, nc, which, x);
             const ChainRec cr = T.chains[c];
             const u32 xx = x - clay_field(clay_ex[c], which);
-            if (which >= 3) {   // work items
+            if (which >= 3) {   // work item = one block of a fused chain, or one tile
                 WorkRec w;
                 const bool fwd = which == 3;
-                if (cr.fused || !fwd) { w.first = (fwd ? clay_ex[c].tf : clay_ex[c].ta) + xx * (cr.fused ? cr.k : 1u); w.len = cr.fused ? cr.k : 1u; }
-                else { w.first = clay_ex[c].tf + xx; w.len = 1; }
+                const u32 len = cr.fused ? cr.kt : 1u;
+                w.first = (fwd ? clay_ex[c].tf : clay_ex[c].ta) + xx * len;
+                w.len = len;
                 (fwd ? T.works_f : T.works_a)[x] = w;
-            } else if (which == 1) {   // pull tile: row block rb of a member, deepest member first
-                const u32 k = cr.fused ? cr.k : 1u;
-                const u32 rb = xx / k, i = xx % k;
-                const BatchRec r = T.batches[T.lorder[cr.first + (k - 1 - i)]];
-                const u32 row0 = rb * cr.R;
-                const u32 nrows = (row0 + cr.R <= r.B) ? cr.R : r.B - row0;
-                PullDesc d;
-                fill_pull_desc(T, r, row0, nrows, d);
-                T.tiles_a[x] = d;
-            } else if (which == 0 && cr.fused) {
-                const u32 rb = xx / cr.k, i = xx % cr.k;
-                const BatchRec r = T.batches[T.lorder[cr.first + i]];
-                const u32 row0 = rb * cr.R;
-                const u32 nrows = (row0 + cr.R <= r.B) ? cr.R : r.B - row0;
-                TileDesc d;
-                fill_tile_desc(T, r, xx, false, true, row0, nrows, d);
-                T.tiles_f[x] = d;
-            } else {
+            } else if (which == 2 || (which == 0 && !cr.fused)) {
                 const BatchRec r = T.batches[T.lorder[cr.first]];
                 TileDesc d;
-                fill_tile_desc(T, r, xx, which == 2, false, 0, 0, d);
+                fill_tile_desc(T, r, xx, which == 2, false, 0, 0, 1, d);
                 (which == 0 ? T.tiles_f : T.tiles_b)[x] = d;
+            } else {
+                // tile `it` of block rb: member m, its q-th row of every group in the block
+                // (pull tiles walk the members deepest first)
+                const u32 rb = xx / cr.kt;
+                u32 it = xx % cr.kt;
+                if (which == 1) it = cr.kt - 1 - it;
+                u32 m = 0, mult = 1;
+                if (cr.fused) {
+                    for (;; ++m) {
+                        mult = T.batches[T.lorder[cr.first + m]].B / cr.G;
+                        if (it < mult) break;
+                        it -= mult;
+                    }
+                } else {
+                    it = 0;
+                }
+                const BatchRec r = T.batches[T.lorder[cr.first + m]];
+                const u32 g0 = rb * cr.Rg;
+                const u32 ng = (g0 + cr.Rg <= cr.G) ? cr.Rg : cr.G - g0;
+                const u32 row0 = g0 * mult + it;
+                // tiles of the same depth that follow this one in run order (this one included)
+                u32 glen = 1;
+                if (cr.fused) {
+                    if (which == 0) {
+                        glen = mult - it;
+                        for (u32 mm = m + 1; mm < cr.k; ++mm) {
+                            const BatchRec &rn = T.batches[T.lorder[cr.first + mm]];
+                            if (rn.step != r.step) break;
+                            glen += rn.B / cr.G;
+                        }
+                    } else {
+                        glen = it + 1;
+                        for (u32 mm = m; mm-- > 0;) {
+                            const BatchRec &rn = T.batches[T.lorder[cr.first + mm]];
+                            if (rn.step != r.step) break;
+                            glen += rn.B / cr.G;
+                        }
+                    }
+                }
+                if (which == 1) {
+                    PullDesc d;
+                    fill_pull_desc(T, r, row0, ng, mult, d);
+                    d.grp_len = glen;
+                    T.tiles_a[x] = d;
+                } else {
+                    TileDesc d;
+                    fill_tile_desc(T, r, xx, false, true, row0, ng, mult, d);
+                    d.contig |= (glen > 0xffffu ? 0xffffu : glen) << 16;
+                    T.tiles_f[x] = d;
+                }
             }
         }
     }
@@ -786,6 +902,8 @@ int sched_run(ob_ctx *ctx)
     A(ctx->lay_in, Lay, n); A(ctx->lay_total, Lay, 1);
     CLay *clay_in, *clay_total;
     A(clay_in, CLay, n); A(clay_total, CLay, 1);
+    u32 *lvl_eoff;
+    A(lvl_eoff, u32, n + 2);
     {
         size_t sb = prim_sort_scratch_bytes(maxne);
         size_t sc = prim_scan_scratch_bytes(maxne, sizeof(Lay));
@@ -846,27 +964,29 @@ int sched_run(ob_ctx *ctx)
 
     // ---- launch planning: slots, chains, tile descriptors ----
     const int fuse = by_depth && ctx->fuse;
+    u32 *rec_cons = ctx->val_b, *rec_prod = (u32 *)ctx->key_b, *rec_w = rec_prod + (E + 1);
     if (fuse && E > 0) {
         HIP_TRY(ctx, prim_fill_u32(T.b_align, 1u, (size_t)E + 1, s));
+        HIP_TRY(ctx, prim_fill_u32(lvl_eoff, 0xffffffffu, (size_t)n + 2, s));
         K(k_align, E, T);
-        K(k_bedges, E, T);
-        ctx->n_launch_sched += 1;
+        K(k_erecs, E, T, rec_cons, rec_prod, rec_w, lvl_eoff);
+        hipLaunchKernelGGL(k_lvl_fix, dim3(1), dim3(1), 0, s, T, lvl_eoff);
+        ctx->n_launch_sched += 3;
     }
-    hipLaunchKernelGGL(k_slots, dim3(1), dim3(SLOT_THREADS), 0, s, T, fuse);
+    hipLaunchKernelGGL(k_slots, dim3(1), dim3(SLOT_THREADS), 0, s, T, (fuse && E > 0) ? 1 : 0, rec_cons, rec_prod,
+                       rec_w, lvl_eoff);
     ++ctx->n_launch_sched;
-    K(k_launch_keys, n, T, ctx->key_a, ctx->val_a);
-    if (fuse) {
-        const int lb = bit_width_u32(n);
-        HIP_TRY(ctx, prim_sort_pairs(ctx->key_a, ctx->val_a, ctx->key_b, ctx->val_b, n, 0, lb, ctx->scratch, s,
-                                     &ctx->n_launch_sched));
-        HIP_TRY(ctx, prim_sort_pairs(ctx->key_a, ctx->val_a, ctx->key_b, ctx->val_b, n, 32, lb, ctx->scratch, s,
-                                     &ctx->n_launch_sched));
+    K(k_launch_keys, n, T, ctx->key_a, ctx->val_a, n);
+    if (fuse && E > 0) {
+        const size_t n_sort = n < SLOT_MAX_NB + 1 ? n : SLOT_MAX_NB + 1;
+        HIP_TRY(ctx, prim_sort_pairs(ctx->key_a, ctx->val_a, ctx->key_b, ctx->val_b, n_sort, 0, 2 * SLOT_BITS,
+                                     ctx->scratch, s, &ctx->n_launch_sched));
     }
     u32 *cflag = ctx->tmp_u32_a, *cflag_excl = ctx->tmp_u32_b;
-    K(k_chain_flags, n, T, ctx->key_a, ctx->val_a, cflag);
+    K(k_chain_flags, n, T, ctx->val_a, cflag, n);
     HIP_TRY(ctx, prim_scan_u32(cflag, cflag_excl, n, nullptr, ctx->scratch, s));
-    K(k_clay_zero, n, T, clay_in);
-    K(k_chain_recs, n, T, ctx->key_a, cflag, cflag_excl, clay_in);
+    K(k_clay_zero, n, clay_in, n);
+    K(k_chain_recs, n, T, cflag, cflag_excl, clay_in, n);
     HIP_TRY(ctx, prim_scan_clay(clay_in, T.clay, n, clay_total, ctx->scratch, s));
     ctx->n_launch_sched += 6;
     K(k_slot_tables, n, T, T.clay, clay_total);
