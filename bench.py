@@ -80,6 +80,9 @@ def main():
     ap.add_argument("--workload", default="tagger", choices=list(wl.CONFIGS))
     ap.add_argument("--pool", type=int, default=6, help="distinct seeded minibatches cycled through")
     ap.add_argument("--launch", default="stream", choices=["stream", "graph"])
+    ap.add_argument("--no-pipeline", action="store_true",
+                    help="schedule and execute each step back to back on one stream (no overlap between steps)")
+    ap.add_argument("--no-fusion", action="store_true", help="one launch per depth level")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
     ap.add_argument("--no-nobatch", action="store_true", help="skip the unbatched GPU leg")
     ap.add_argument("--cpu-samples", type=int, default=4)
@@ -101,39 +104,63 @@ def main():
     graphs = [cfg["batch"](params, j) for j in range(pool)]
     launch = ob.OB_LAUNCH_GRAPH if args.launch == "graph" else ob.OB_LAUNCH_STREAM
 
-    # one context per pooled minibatch, graph arrays uploaded before the timed region
-    # every context works on the same stream, so consecutive steps are serial on the GPU (as a
-    # training loop with a parameter update between minibatches would be); the host may run ahead
+    # One context per pooled minibatch, all sharing one parameter set (forks of the first) and one
+    # execution stream, so the executions of consecutive steps are serial on the GPU as a training
+    # loop with a parameter update in between would be.  Graph arrays are uploaded before the timed
+    # region.  With pipelining (default) scheduling runs on a second stream: while step i executes,
+    # the GPU already schedules step i+1 (scheduling reads only the graph, never the parameters).
+    pipeline = not args.no_pipeline
     stream = torch.cuda.Stream()
+    sched_stream = torch.cuda.Stream() if pipeline else None
     ctxs = []
     t_up = []
-    for g in graphs:
-        c = ob.Context(arena_bytes=1 << 30, stream=stream, mode=ob.OB_BYDEPTH, launch=launch)
-        c.params_create(params)
-        c.param_grad_zero()
+    for j, g in enumerate(graphs):
+        if j == 0:
+            c = ob.Context(arena_bytes=1 << 30, stream=stream, mode=ob.OB_BYDEPTH, launch=launch,
+                           sched_stream=sched_stream)
+            c.set_fusion(not args.no_fusion)
+            c.params_create(params)
+            c.param_grad_zero()
+        else:
+            c = ctxs[0].fork(arena_bytes=1 << 30, stream=stream, sched_stream=sched_stream)
         t0 = time.perf_counter()
         c.add_bulk(g)
         c.upload()
         c.sync()
+        torch.cuda.synchronize()
         t_up.append(time.perf_counter() - t0)
         ctxs.append(c)
 
-    def step(i):
+    def sched(i):
+        c = ctxs[i % pool]
+        c.reset()
+        c.schedule(graphs[i % pool].root)
+
+    def execute(i):
         c = ctxs[i % pool]
         g = graphs[i % pool]
-        c.reset()
         c.param_grad_zero()
         c.forward(g.root)
         c.backward(g.root)
 
-    for i in range(args.warmup):
-        step(i)
+    def run(first, count):
+        if pipeline:
+            sched(first)
+            for i in range(first, first + count):
+                execute(i)
+                if i + 1 < first + count:
+                    sched(i + 1)
+        else:
+            for i in range(first, first + count):
+                sched(i)
+                execute(i)
+
+    run(0, args.warmup)
     torch.cuda.synchronize()
     phase = dict(ms_schedule=0.0, ms_forward=0.0, ms_backward=0.0, ms_param_grads=0.0)
     launches = dict(n_launch_fwd=0, n_launch_bwd=0)
     t0 = time.perf_counter()
-    for i in range(args.steps):
-        step(args.warmup + i)
+    run(args.warmup, args.steps)
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
     # per-phase HIP-event times (events were recorded inside the timed region; reading them is not timed)
@@ -221,11 +248,15 @@ def main():
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": f"config {cfg['index']}: {args.workload} (BASELINE.json configs[{cfg['index'] - 1}])",
                    "instances_per_step": graphs[0].n_instances, "mode": "bydepth", "launch": args.launch,
+                   "fusion": not args.no_fusion,
+                   "pipeline": "scheduling of step i+1 overlaps execution of step i (second stream)" if pipeline
+                   else "none (schedule, forward, backward back to back)",
                    "pool": pool, "nodes_per_step": round(n_nodes / args.steps, 1)},
         "nodes_per_s": round(n_nodes / elapsed, 1),
         "phase_ms_per_step": {k_: round(v / args.steps, 4) for k_, v in phase.items()},
         "launches_per_step": {k_: round(v / args.steps, 1) for k_, v in launches.items()},
-        "steps_levels": per_ctx_stats[0]["n_steps"], "batches": per_ctx_stats[0]["n_batches"],
+        "depth_levels": per_ctx_stats[0]["n_steps"], "launch_slots": per_ctx_stats[0]["n_slots"],
+        "batches": per_ctx_stats[0]["n_batches"],
         "upload_ms_host_to_hbm": round(float(np.mean(t_up)) * 1e3, 3),
         "value_including_upload": round(n_inst / (elapsed + float(np.mean(t_up)) * args.steps), 2),
         "roofline": roofline,

@@ -78,7 +78,16 @@ typedef struct ob_ctx ob_ctx;
 /* arena_dev: device memory, at least 256-byte aligned; hip_stream: a hipStream_t (or NULL
  * for the default stream).  Touches no GPU state until the first upload. */
 int ob_ctx_create(void *arena_dev, size_t arena_bytes, void *hip_stream, ob_ctx **out);
+/* A second context over its own arena and stream that SHARES the parent's parameters (same
+ * device storage for values and gradients; it cannot create parameters of its own).  Lets one
+ * minibatch graph be uploaded and scheduled while another one executes (Section 3: graph
+ * definition and batching are separate from computation).  The parent must outlive the fork, and
+ * executions that touch the shared gradients must be ordered by the caller (e.g. same stream). */
+int ob_ctx_fork(ob_ctx *parent, void *arena_dev, size_t arena_bytes, void *hip_stream, ob_ctx **out);
 int ob_ctx_destroy(ob_ctx *ctx);
+/* Upload and scheduling go to this stream instead of the context's stream; execution waits for
+ * them through an event.  Call before the first upload. */
+int ob_ctx_set_schedule_stream(ob_ctx *ctx, void *hip_stream);
 int ob_ctx_set_mode(ob_ctx *ctx, int mode);
 int ob_ctx_set_launch(ob_ctx *ctx, int launch);
 /* Launch fusion (default on, OB_BYDEPTH only): component-wise batches whose operands are
@@ -133,6 +142,10 @@ int ob_upload(ob_ctx *ctx);
  * requested).  Schedules on the GPU (Section 3.2), then runs the batches in order
  * (Section 3.3).  Asynchronous except for one small read of the schedule header. */
 int ob_forward(ob_ctx *ctx, int node);
+/* Only the scheduling half of ob_forward (upload, Section 3.2's batching on the GPU, layout and
+ * launch plan); a later ob_forward of the same node then only executes.  Blocks the host for one
+ * small read of the schedule header. */
+int ob_schedule(ob_ctx *ctx, int node);
 /* Reverse-mode differentiation from a 1-element node that ob_forward covered: batches in
  * reverse order (Section 3.3).  Node gradients are overwritten, parameter gradients
  * accumulate. */

@@ -67,6 +67,9 @@ def lib():
         sigs = {
             "ob_ctx_create": (i, [vp, sz, vp, POINTER(vp)]),
             "ob_ctx_destroy": (i, [vp]),
+            "ob_ctx_fork": (i, [vp, vp, sz, vp, POINTER(vp)]),
+            "ob_ctx_set_schedule_stream": (i, [vp, vp]),
+            "ob_schedule": (i, [vp, i]),
             "ob_ctx_set_mode": (i, [vp, i]),
             "ob_ctx_set_launch": (i, [vp, i]),
             "ob_ctx_set_fusion": (i, [vp, i]),
@@ -121,9 +124,10 @@ class Context:
     device calls fail)."""
 
     def __init__(self, arena_bytes: int = 1 << 30, stream=None, mode: int = OB_BYDEPTH,
-                 launch: int = OB_LAUNCH_STREAM):
+                 launch: int = OB_LAUNCH_STREAM, parent: "Context | None" = None, sched_stream=None):
         self.L = lib()
         self._arena = None
+        self._parent = parent
         ptr, stream_ptr = None, None
         if arena_bytes:
             import torch
@@ -136,11 +140,19 @@ class Context:
             self._stream = s
             stream_ptr = s.cuda_stream
         self.h = c_void_p()
-        rc = self.L.ob_ctx_create(c_void_p(ptr), arena_bytes, c_void_p(stream_ptr), byref(self.h))
-        if rc:
-            raise ObError(rc, (self.L.ob_last_error(None) or b"").decode())
-        self.set_mode(mode)
-        self.set_launch(launch)
+        if parent is not None:
+            rc = self.L.ob_ctx_fork(parent.h, c_void_p(ptr), arena_bytes, c_void_p(stream_ptr), byref(self.h))
+            if rc:
+                raise ObError(rc, (self.L.ob_last_error(parent.h) or b"").decode())
+        else:
+            rc = self.L.ob_ctx_create(c_void_p(ptr), arena_bytes, c_void_p(stream_ptr), byref(self.h))
+            if rc:
+                raise ObError(rc, (self.L.ob_last_error(None) or b"").decode())
+            self.set_mode(mode)
+            self.set_launch(launch)
+        if sched_stream is not None:
+            self._sched_stream = sched_stream
+            self._ck(self.L.ob_ctx_set_schedule_stream(self.h, c_void_p(sched_stream.cuda_stream)))
 
     # -- plumbing
     def _ck(self, rc: int) -> int:
@@ -245,6 +257,13 @@ class Context:
     # -- execution
     def upload(self):
         self._ck(self.L.ob_upload(self.h))
+
+    def fork(self, arena_bytes: int = 1 << 30, stream=None, sched_stream=None) -> "Context":
+        """A context with its own graph, arena and stream that shares this one's parameters."""
+        return Context(arena_bytes=arena_bytes, stream=stream, parent=self, sched_stream=sched_stream)
+
+    def schedule(self, node: int):
+        self._ck(self.L.ob_schedule(self.h, node))
 
     def forward(self, node: int):
         self._ck(self.L.ob_forward(self.h, node))

@@ -48,7 +48,26 @@ int ob_ctx_create(void *arena_dev, size_t arena_bytes, void *hip_stream, ob_ctx 
     c->arena = (char *)arena_dev;
     c->arena_bytes = arena_dev ? arena_bytes : 0;
     c->stream = (hipStream_t)hip_stream;
+    c->sched_stream = c->stream;
     c->in_off.push_back(0);
+    *out = c;
+    return OB_OK;
+}
+
+static int params_to_device(ob_ctx *ctx);
+
+int ob_ctx_fork(ob_ctx *parent, void *arena_dev, size_t arena_bytes, void *hip_stream, ob_ctx **out)
+{
+    if (!parent) return OB_E_ARG;
+    if (!out || !arena_dev) return ctx_fail(parent, OB_E_ARG, "ob_ctx_fork: null argument");
+    if (int rc = params_to_device(parent)) return rc;
+    ob_ctx *c = nullptr;
+    if (int rc = ob_ctx_create(arena_dev, arena_bytes, hip_stream, &c)) return rc;
+    c->parent = parent;
+    c->params = parent->params;            // same device storage: values and gradients are shared
+    c->max_param_rows = parent->max_param_rows;
+    c->mode = parent->mode; c->launch = parent->launch; c->fuse = parent->fuse;
+    c->params_dirty = true;
     *out = c;
     return OB_OK;
 }
@@ -56,7 +75,7 @@ int ob_ctx_create(void *arena_dev, size_t arena_bytes, void *hip_stream, ob_ctx 
 int ob_ctx_destroy(ob_ctx *ctx)
 {
     CHECK_CTX(ctx);
-    if (ctx->uploaded) (void)hipStreamSynchronize(ctx->stream);
+    if (ctx->uploaded) { (void)hipStreamSynchronize(ctx->sched_stream); (void)hipStreamSynchronize(ctx->stream); }
     if (ctx->gexec_fwd) (void)hipGraphExecDestroy(ctx->gexec_fwd);
     if (ctx->gexec_bwd) (void)hipGraphExecDestroy(ctx->gexec_bwd);
     if (ctx->graph_fwd) (void)hipGraphDestroy(ctx->graph_fwd);
@@ -74,6 +93,14 @@ int ob_ctx_set_mode(ob_ctx *ctx, int mode)
     if (mode == OB_BYAGENDA) return ctx_fail(ctx, OB_E_STATE, "agenda-based batching is not built");
     if (mode != OB_NOBATCH && mode != OB_BYDEPTH) return ctx_fail(ctx, OB_E_ARG, "unknown mode %d", mode);
     ctx->mode = mode;
+    return OB_OK;
+}
+
+int ob_ctx_set_schedule_stream(ob_ctx *ctx, void *hip_stream)
+{
+    CHECK_CTX(ctx);
+    if (ctx->uploaded) return ctx_fail(ctx, OB_E_STATE, "set the schedule stream before the first upload of a graph");
+    ctx->sched_stream = (hipStream_t)hip_stream;
     return OB_OK;
 }
 
@@ -120,6 +147,7 @@ int ob_param_create(ob_ctx *ctx, int rows, int cols, const float *host_init, int
     CHECK_CTX(ctx);
     if (!host_init || !id) return ctx_fail(ctx, OB_E_ARG, "ob_param_create: null argument");
     if (rows <= 0 || cols <= 0) return ctx_fail(ctx, OB_E_DIM, "parameter shape %d x %d", rows, cols);
+    if (ctx->parent) return ctx_fail(ctx, OB_E_STATE, "a forked context shares its parent's parameters and cannot create its own");
     if (ctx->top != ctx->persist_top)
         return ctx_fail(ctx, OB_E_STATE, "parameters must be created while no graph is on the device");
     const size_t count = (size_t)rows * cols;
@@ -199,7 +227,10 @@ int ob_param_grad_zero(ob_ctx *ctx)
 int ob_graph_new(ob_ctx *ctx)
 {
     CHECK_CTX(ctx);
-    if (ctx->uploaded) HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
+    if (ctx->uploaded) {
+        HIP_TRY(ctx, hipStreamSynchronize(ctx->sched_stream));
+        HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
+    }
     ctx->op.clear(); ctx->out_dim.clear(); ctx->in_off.assign(1, 0); ctx->in_idx.clear();
     ctx->param.clear(); ctx->bias.clear(); ctx->aux0.clear(); ctx->aux1.clear(); ctx->payload.clear();
     ctx->items_upto.clear();
@@ -535,9 +566,9 @@ int ob_upload(ob_ctx *ctx)
     if (P) memcpy(img + off[8], ctx->payload.data(), P * 4);
     char *dev = (char *)arena_alloc(ctx, cur);
     if (!dev) return ctx_fail(ctx, OB_E_OOM, "arena too small for the graph (%zu bytes)", cur);
-    HIP_TRY(ctx, hipEventRecord(ctx->ev[0], ctx->stream));
-    HIP_TRY(ctx, hipMemcpyAsync(dev, img, cur, hipMemcpyHostToDevice, ctx->stream));
-    HIP_TRY(ctx, hipEventRecord(ctx->ev[1], ctx->stream));
+    HIP_TRY(ctx, hipEventRecord(ctx->ev[0], ctx->sched_stream));
+    HIP_TRY(ctx, hipMemcpyAsync(dev, img, cur, hipMemcpyHostToDevice, ctx->sched_stream));
+    HIP_TRY(ctx, hipEventRecord(ctx->ev[1], ctx->sched_stream));
     Tables &T = ctx->T;
     T = Tables{};
     T.op = (const u8 *)(dev + off[0]); T.out_dim = (const u32 *)(dev + off[1]); T.in_off = (const u32 *)(dev + off[2]);
@@ -554,12 +585,12 @@ int ob_upload(ob_ctx *ctx)
 
 // ---- execution ------------------------------------------------------------------------------------
 
-int ob_forward(ob_ctx *ctx, int node)
+int ob_schedule(ob_ctx *ctx, int node)
 {
     CHECK_CTX(ctx);
     if (node < 0 || node >= (int)ctx->op.size()) return ctx_fail(ctx, OB_E_BADID, "unknown node id %d", node);
     if (ctx->n_sched) {
-        if ((u32)node < ctx->n_sched) return OB_OK;   // already evaluated
+        if ((u32)node < ctx->n_sched) return OB_OK;   // already scheduled
         return ctx_fail(ctx, OB_E_STATE, "incremental forward (nodes beyond the evaluated prefix) is not built");
     }
     if (int rc = ob_upload(ctx)) return rc;
@@ -568,12 +599,24 @@ int ob_forward(ob_ctx *ctx, int node)
     T.E = ctx->in_off[T.n];
     ctx->top = ctx->graph_top;
     ctx->ms_graph = 0;
-    HIP_TRY(ctx, hipEventRecord(ctx->ev[7], ctx->stream));
+    HIP_TRY(ctx, hipEventRecord(ctx->ev[7], ctx->sched_stream));
     if (int rc = sched_run(ctx)) return rc;
-    HIP_TRY(ctx, hipEventRecord(ctx->ev[2], ctx->stream));
+    HIP_TRY(ctx, hipEventRecord(ctx->ev[9], ctx->sched_stream));
+    ctx->n_sched = T.n;
+    ctx->forward_done = ctx->backward_done = false;
+    return OB_OK;
+}
+
+int ob_forward(ob_ctx *ctx, int node)
+{
+    CHECK_CTX(ctx);
+    if (node < 0 || node >= (int)ctx->op.size()) return ctx_fail(ctx, OB_E_BADID, "unknown node id %d", node);
+    if (int rc = ob_schedule(ctx, node)) return rc;
+    if (ctx->forward_done) return OB_OK;              // already evaluated
+    if (ctx->sched_stream != ctx->stream) HIP_TRY(ctx, hipStreamWaitEvent(ctx->stream, ctx->ev[9], 0));
+    HIP_TRY(ctx, hipEventRecord(ctx->ev[8], ctx->stream));
     if (int rc = exec_forward(ctx)) return rc;
     HIP_TRY(ctx, hipEventRecord(ctx->ev[3], ctx->stream));
-    ctx->n_sched = T.n;
     ctx->forward_done = true;
     ctx->backward_done = false;
     return OB_OK;
@@ -593,10 +636,22 @@ int ob_backward(ob_ctx *ctx, int node)
     return OB_OK;
 }
 
+// waits until the work this context last enqueued has finished (its own events, not the whole
+// stream: other contexts may share the streams)
+static int wait_own_work(ob_ctx *ctx)
+{
+    if (!ctx->uploaded || !ctx->ev_ok) return 0;
+    if (ctx->backward_done) HIP_TRY(ctx, hipEventSynchronize(ctx->ev[5]));
+    else if (ctx->forward_done) HIP_TRY(ctx, hipEventSynchronize(ctx->ev[3]));
+    else if (ctx->n_sched) HIP_TRY(ctx, hipEventSynchronize(ctx->ev[9]));
+    else HIP_TRY(ctx, hipEventSynchronize(ctx->ev[1]));
+    return 0;
+}
+
 int ob_reset(ob_ctx *ctx)
 {
     CHECK_CTX(ctx);
-    if (ctx->uploaded) HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
+    if (int rc = wait_own_work(ctx)) return rc;
     ctx->n_sched = 0;
     ctx->forward_done = ctx->backward_done = false;
     if (ctx->uploaded) ctx->top = ctx->graph_top;
@@ -703,6 +758,7 @@ int ob_stats_read(ob_ctx *ctx, ob_stats *out)
     out->n_nodes = (int32_t)ctx->op.size();
     out->n_edges = (int32_t)ctx->in_idx.size();
     if (!ctx->forward_done) return OB_OK;
+    HIP_TRY(ctx, hipStreamSynchronize(ctx->sched_stream));
     HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
     out->n_nodes = (int32_t)ctx->n_sched;
     out->n_edges = (int32_t)ctx->T.E;
@@ -721,8 +777,8 @@ int ob_stats_read(ob_ctx *ctx, ob_stats *out)
     out->arena_used_bytes = ctx->top;
     out->upload_bytes = ctx->upload_bytes;
     (void)hipEventElapsedTime(&out->ms_upload, ctx->ev[0], ctx->ev[1]);
-    (void)hipEventElapsedTime(&out->ms_schedule, ctx->ev[7], ctx->ev[2]);
-    (void)hipEventElapsedTime(&out->ms_forward, ctx->ev[2], ctx->ev[3]);
+    (void)hipEventElapsedTime(&out->ms_schedule, ctx->ev[7], ctx->ev[9]);
+    (void)hipEventElapsedTime(&out->ms_forward, ctx->ev[8], ctx->ev[3]);
     if (ctx->backward_done) {
         (void)hipEventElapsedTime(&out->ms_backward, ctx->ev[4], ctx->ev[5]);
         (void)hipEventElapsedTime(&out->ms_param_grads, ctx->ev[6], ctx->ev[5]);

@@ -16,7 +16,9 @@ struct ob_ctx {
     // caller-owned resources
     char *arena = nullptr;
     size_t arena_bytes = 0;
-    hipStream_t stream = nullptr;
+    hipStream_t stream = nullptr;        // execution: forward, backward, reads
+    hipStream_t sched_stream = nullptr;  // upload + scheduling (same as `stream` unless set apart)
+    ob_ctx *parent = nullptr;            // forked contexts share the parent's parameters
     int mode = 1;      // OB_BYDEPTH
     int launch = 0;    // OB_LAUNCH_STREAM
     int fuse = 1;      // run row-aligned component-wise chains inside one launch
@@ -66,7 +68,7 @@ struct ob_ctx {
     size_t hdr_pinned_bytes = 0;
 
     // events / stats
-    hipEvent_t ev[8] = {};
+    hipEvent_t ev[10] = {};
     bool ev_ok = false;
     float ms_upload = 0, ms_schedule = 0, ms_forward = 0, ms_backward = 0, ms_param_grads = 0, ms_graph = 0;
     int n_launch_fwd = 0, n_launch_bwd = 0, n_launch_sched = 0;

@@ -210,30 +210,30 @@ __device__ inline floatx16 mfma4(float4 a, float4 b, floatx16 acc)
     return acc;
 }
 
-// Sums the four waves' accumulators; on return wave w holds in out[0..3] the rows
-// 8w + 4*(lane/32) + 0..3 of column lane%32.
-__device__ inline void reduce_waves(const floatx16 &acc, float *lds, float out[4])
+// Sums the NW waves' accumulators in wave order; on return wave w holds in out[0 .. 16/NW) the
+// accumulator registers v = (16/NW) * w + i, i.e. rows 8*(v/4) + 4*(lane/32) + v%4 of column lane%32.
+template <int NW>
+__device__ inline void reduce_waves(const floatx16 &acc, float *lds, float *out)
 {
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
     for (int v = 0; v < 16; ++v) lds[(w * 16 + v) * 64 + lane] = acc[v];
     __syncthreads();
-    for (int i = 0; i < 4; ++i) {
-        const int v = 4 * w + i;
-        float s = lds[(0 * 16 + v) * 64 + lane];
-        s += lds[(1 * 16 + v) * 64 + lane];
-        s += lds[(2 * 16 + v) * 64 + lane];
-        s += lds[(3 * 16 + v) * 64 + lane];
+    for (int i = 0; i < 16 / NW; ++i) {
+        const int v = (16 / NW) * w + i;
+        float s = lds[v * 64 + lane];
+        for (int ww = 1; ww < NW; ++ww) s += lds[(ww * 16 + v) * 64 + lane];
         out[i] = s;
     }
     __syncthreads();
 }
 
-// split [0, total) in units of 8 over the 4 waves
+// split [0, total) in units of 8 over the NW waves
+template <int NW>
 __device__ inline void wave_range(u32 total, u32 &lo, u32 &hi)
 {
     const u32 w = threadIdx.x >> 6;
     const u32 n8 = (total + 7) / 8;
-    const u32 per = (n8 + 3) / 4;
+    const u32 per = (n8 + NW - 1) / NW;
     lo = w * per * 8;
     hi = (w + 1) * per * 8;
     const u32 pad = n8 * 8;
@@ -241,7 +241,8 @@ __device__ inline void wave_range(u32 total, u32 &lo, u32 &hi)
     if (hi > pad) hi = pad;
 }
 
-constexpr int KU = 4;   // blocks of 8 contraction indices whose loads are issued together
+constexpr int KU = 8;   // blocks of 8 contraction indices whose loads are issued together
+constexpr int DX_WAVES = 8;   // the dX kernel splits its long contraction (rows of W) over 8 waves
 
 // Y[B x m] = X[B x K] W^T + b.   xrow: this lane's X row (valid when row_ok), W row-major [m x K].
 __device__ inline void gemm_nt_tile(const float *xrow, bool row_ok, u32 B, const float *W, const float *bias, u32 m,
@@ -253,7 +254,7 @@ __device__ inline void gemm_nt_tile(const float *xrow, bool row_ok, u32 B, const
     const bool col_ok = col < m;
     const float *wrow = W + (size_t)(col_ok ? col : 0u) * K;
     u32 lo, hi;
-    wave_range(K, lo, hi);
+    wave_range<4>(K, lo, hi);
     floatx16 acc;
     for (int v = 0; v < 16; ++v) acc[v] = 0.f;
     const float4 z4 = make_float4(0.f, 0.f, 0.f, 0.f);
@@ -283,7 +284,7 @@ __device__ inline void gemm_nt_tile(const float *xrow, bool row_ok, u32 B, const
         }
     }
     float out[4];
-    reduce_waves(acc, lds, out);
+    reduce_waves<4>(acc, lds, out);
     if (col_ok) {
         const float bb = bias ? bias[col] : 0.f;
         for (int i = 0; i < 4; ++i) {
@@ -321,7 +322,7 @@ __device__ inline void matvec_dx_tile(const Tables &T, const TileDesc &d, float 
     const float *wcol = P.data + (col_ok ? col : 0u);
     const bool fast = (m & 3u) == 0;
     u32 lo, hi;
-    wave_range(m, lo, hi);
+    wave_range<DX_WAVES>(m, lo, hi);
     floatx16 acc;
     for (int v = 0; v < 16; ++v) acc[v] = 0.f;
     const float4 z4 = make_float4(0.f, 0.f, 0.f, 0.f);
@@ -355,12 +356,13 @@ __device__ inline void matvec_dx_tile(const Tables &T, const TileDesc &d, float 
             acc = mfma4(make_float4(av[0], av[1], av[2], av[3]), make_float4(bv[0], bv[1], bv[2], bv[3]), acc);
         }
     }
-    float out[4];
-    reduce_waves(acc, lds, out);
+    float out[16 / DX_WAVES];
+    reduce_waves<DX_WAVES>(acc, lds, out);
     if (col_ok) {
         float *dX = T.G + d.dx_off;
-        for (int i = 0; i < 4; ++i) {
-            const u32 rr = r0 + 8 * w + 4 * h + i;
+        for (int i = 0; i < 16 / DX_WAVES; ++i) {
+            const int v = (16 / DX_WAVES) * w + i;
+            const u32 rr = r0 + 8 * (v / 4) + 4 * h + (v % 4);
             if (rr < d.B) dX[(size_t)rr * K + col] = out[i];
         }
     }
@@ -379,7 +381,7 @@ __device__ inline void param_w_tile(const Tables &T, const PTile &pt, float *lds
     const u32 i = (u32)pt.i0 + l32, j = (u32)pt.j0 + l32;
     const bool i_ok = i < m, j_ok = j < K;
     u32 lo, hi;
-    wave_range(end - start, lo, hi);
+    wave_range<4>(end - start, lo, hi);
     floatx16 acc;
     for (int v = 0; v < 16; ++v) acc[v] = 0.f;
     for (u32 ib = lo; ib < hi; ib += 8 * KU) {
@@ -408,7 +410,7 @@ __device__ inline void param_w_tile(const Tables &T, const PTile &pt, float *lds
                         make_float4(bv[u][0], bv[u][1], bv[u][2], bv[u][3]), acc);
     }
     float out[4];
-    reduce_waves(acc, lds, out);
+    reduce_waves<4>(acc, lds, out);
     if (j_ok) {
         for (int q = 0; q < 4; ++q) {
             const u32 rr = (u32)pt.i0 + 8 * w + 4 * h + q;
@@ -591,9 +593,9 @@ __global__ __launch_bounds__(WG) void k_bwd_pull_step(Tables T, u32 work_lo, u32
     }
 }
 
-__global__ __launch_bounds__(WG) void k_bwd_dx_step(Tables T, u32 tile_lo, u32 tile_hi)
+__global__ __launch_bounds__(DX_WAVES * 64) void k_bwd_dx_step(Tables T, u32 tile_lo, u32 tile_hi)
 {
-    __shared__ float lds[LDS_FLOATS];
+    __shared__ float lds[DX_WAVES * 16 * 64];
     for (u32 tile = tile_lo + blockIdx.x; tile < tile_hi; tile += gridDim.x) {
         const TileDesc d = T.tiles_b[tile];
         matvec_dx_tile(T, d, lds);
@@ -696,7 +698,7 @@ static int launch_backward_steps(ob_ctx *ctx)
         }
         const u32 blo = ctx->slot_tb[st], bhi = ctx->slot_tb[st + 1];
         if (bhi > blo) {
-            hipLaunchKernelGGL(k_bwd_dx_step, dim3(grid_for(bhi - blo, GRID_CAP)), dim3(WG), 0, s, T, blo, bhi);
+            hipLaunchKernelGGL(k_bwd_dx_step, dim3(grid_for(bhi - blo, GRID_CAP)), dim3(DX_WAVES * 64), 0, s, T, blo, bhi);
             ++ctx->n_launch_bwd;
         }
     }

@@ -851,7 +851,7 @@ inline int bit_width_u32(u32 x) { int b = 0; while (x) { ++b; x >>= 1; } return 
 int sched_run(ob_ctx *ctx)
 {
     Tables &T = ctx->T;
-    hipStream_t s = ctx->stream;
+    hipStream_t s = ctx->sched_stream;
     const u32 n = T.n, E = T.E;
     const int by_depth = ctx->mode == 1;
     ctx->n_launch_sched = 0;

@@ -283,3 +283,59 @@ def test_parameter_gradients_accumulate_until_zeroed(workload_cache):
     c.backward(root)
     assert np.array_equal(c.param_grad_read(0, p.mats[0].shape), g1)
     c.close()
+
+
+def test_forked_contexts_share_parameters_and_pipeline_scheduling():
+    """Two graphs in flight: a forked context schedules its graph on a second stream while the
+    first one executes; both share one parameter set, and the accumulated parameter gradient is
+    the sum of the two minibatches' gradients."""
+    import torch
+    from paper_1705_07860_amd import binding as ob
+    p = wl.tagger_params()
+    gs = [wl.tagger_minibatch(p, seed=41 + j, lengths=[4 + j, 9, 2, 6 + 2 * j]) for j in range(2)]
+    os_ = []
+    for g in gs:
+        o = Oracle(g, p, "f64")
+        o.forward()
+        o.backward(g.root)
+        os_.append(o)
+    ex, sc = torch.cuda.Stream(), torch.cuda.Stream()
+    a = ob.Context(arena_bytes=256 << 20, stream=ex, sched_stream=sc)
+    a.params_create(p)
+    a.param_grad_zero()
+    b = a.fork(arena_bytes=256 << 20, stream=ex, sched_stream=sc)
+    with pytest.raises(ob.ObError) as e:
+        b.param_create(np.zeros((2, 2), np.float32))
+    assert e.value.code == -6
+    cs = [a, b]
+    for c, g in zip(cs, gs):
+        c.add_bulk(g)
+        c.upload()
+    cs[0].schedule(gs[0].root)
+    for j in range(2):
+        cs[j].forward(gs[j].root)
+        cs[j].backward(gs[j].root)
+        if j == 0:
+            cs[1].schedule(gs[1].root)      # overlaps the execution of graph 0
+    for c, g, o in zip(cs, gs, os_):
+        total = int(o.v_off[-1])
+        assert segment_rel_err(c.all_read(0, total), o.val[:total], o.v_off) <= TOL
+        assert segment_rel_err(c.all_read(1, total), o.grad[:total], o.v_off) <= TOL
+        bo, ids, bd, _ = c.schedule_read()
+        rbo, rids, rbd = S.by_depth(g)
+        assert np.array_equal(bo, rbo) and np.array_equal(ids, rids) and np.array_equal(bd, rbd)
+    for pid, m in enumerate(p.mats):
+        ref = os_[0].param_grad(pid) + os_[1].param_grad(pid)
+        assert rel_err(b.param_grad_read(pid, m.shape), ref) <= TOL, p.names[pid]
+    # a second round on the same contexts after reset (the arenas are reused)
+    a.param_grad_zero()
+    for c, g in zip(cs, gs):
+        c.reset()
+        c.schedule(g.root)
+        c.forward(g.root)
+        c.backward(g.root)
+    for pid, m in enumerate(p.mats):
+        ref = os_[0].param_grad(pid) + os_[1].param_grad(pid)
+        assert rel_err(a.param_grad_read(pid, m.shape), ref) <= TOL, p.names[pid]
+    b.close()
+    a.close()
