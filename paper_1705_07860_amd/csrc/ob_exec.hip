@@ -62,10 +62,7 @@ __device__ inline float ew_value(const Tables &T, const TileDesc &d, u32 i, u32 
 {
     switch (d.op) {
     case OP_INPUT: return T.payload[T.s_aux0[d.pos0 + row] + col];
-    case OP_LOOKUP: {
-        const ParamDesc P = T.params[d.param];
-        return P.data[(size_t)T.s_aux0[d.pos0 + row] * P.cols + col];
-    }
+    case OP_LOOKUP: return d.w[(size_t)T.s_aux0[d.pos0 + row] * d.d + col];
     case OP_ADD: {
         float acc = 0.f;
         for (u32 j = 0; j < d.arity; ++j) acc += T.V[opnd_row(T, d, j, i, row) + col];
@@ -92,10 +89,7 @@ __device__ inline float4 ew_value4(const Tables &T, const TileDesc &d, u32 i, u3
 {
     switch (d.op) {
     case OP_INPUT: return ld4(T.payload + T.s_aux0[d.pos0 + row] + col);
-    case OP_LOOKUP: {
-        const ParamDesc P = T.params[d.param];
-        return ld4(P.data + (size_t)T.s_aux0[d.pos0 + row] * P.cols + col);
-    }
+    case OP_LOOKUP: return ld4(d.w + (size_t)T.s_aux0[d.pos0 + row] * d.d + col);
     case OP_ADD: {
         float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
         for (u32 j = 0; j < d.arity; ++j) {
@@ -298,13 +292,11 @@ __device__ inline void matvec_fwd_tile(const Tables &T, const TileDesc &d, float
 {
     const u32 ntn = (d.d + GT - 1) / GT;
     const u32 r0 = (d.t / ntn) * GT, i0 = (d.t % ntn) * GT;
-    const ParamDesc P = T.params[d.param];
-    const float *bias = d.bias >= 0 ? T.params[d.bias].data : nullptr;
     const bool fast = (d.flags & 2u) && (d.k & 3u) == 0;
     const u32 row = r0 + (threadIdx.x & 31);
     const bool row_ok = row < d.B;
     const float *xrow = T.V + (row_ok ? opnd_row(T, d, 0, row - d.row0, row) : 0u);
-    gemm_nt_tile(xrow, row_ok, d.B, P.data, bias, d.d, d.k, fast, T.V + d.val_off, r0, i0, lds);
+    gemm_nt_tile(xrow, row_ok, d.B, d.w, d.b, d.d, d.k, fast, T.V + d.val_off, r0, i0, lds);
 }
 
 // dX[B x K] = G[B x m] W, contraction over m.  G rows are the batch's own contiguous block.
@@ -315,11 +307,10 @@ __device__ inline void matvec_dx_tile(const Tables &T, const TileDesc &d, float 
     const u32 K = d.k, m = d.d;
     const u32 ntn = (K + GT - 1) / GT;
     const u32 r0 = (d.t / ntn) * GT, c0 = (d.t % ntn) * GT;
-    const ParamDesc P = T.params[d.param];
     const u32 row = r0 + l32, col = c0 + l32;
     const bool row_ok = row < d.B, col_ok = col < K;
     const float *grow = T.G + d.val_off + (size_t)(row_ok ? row : 0u) * m;
-    const float *wcol = P.data + (col_ok ? col : 0u);
+    const float *wcol = d.w + (col_ok ? col : 0u);
     const bool fast = (m & 3u) == 0;
     u32 lo, hi;
     wave_range<DX_WAVES>(m, lo, hi);
@@ -472,10 +463,58 @@ __device__ inline float edge_term(const Tables &T, u32 kind, u32 goff, u32 voff,
     }
 }
 
+// four consecutive columns of one uniform edge (all offsets are multiples of 4; EK_NLS never is uniform)
+__device__ inline float4 edge_term4(const Tables &T, u32 kind, u32 goff, u32 voff, i32 a0, i32 a1, u32 own, u32 col)
+{
+    const float4 z = make_float4(0.f, 0.f, 0.f, 0.f);
+    switch (kind) {
+    case EK_PLAIN: return ld4(T.G + goff + col);
+    case EK_RANGE: return ((i32)col >= a0 && (i32)col < a1) ? ld4(T.G + goff + col - (u32)a0) : z;
+    case EK_MUL: {
+        const float4 g = ld4(T.G + goff + col), v = ld4(T.V + voff + col);
+        return make_float4(g.x * v.x, g.y * v.y, g.z * v.z, g.w * v.w);
+    }
+    case EK_DTANH: {
+        const float4 g = ld4(T.G + goff + col), y = ld4(T.V + voff + col);
+        return make_float4(g.x * (1.0f - y.x * y.x), g.y * (1.0f - y.y * y.y), g.z * (1.0f - y.z * y.z),
+                           g.w * (1.0f - y.w * y.w));
+    }
+    case EK_DSIGM: {
+        const float4 g = ld4(T.G + goff + col), y = ld4(T.V + voff + col);
+        return make_float4(g.x * y.x * (1.0f - y.x), g.y * y.y * (1.0f - y.y), g.z * y.z * (1.0f - y.z),
+                           g.w * y.w * (1.0f - y.w));
+    }
+    case EK_SQN: {
+        const float g2 = 2.0f * T.G[goff];
+        const float4 x = ld4(T.V + own + col);
+        return make_float4(g2 * x.x, g2 * x.y, g2 * x.z, g2 * x.w);
+    }
+    default: return z;
+    }
+}
+
 __device__ inline void pull_tile(const Tables &T, const PullDesc &d, u32 tid, u32 nthr)
 {
     const u32 total = d.nrows * d.d;
     const u32 root_pos = T.root_pos[0];
+    if (d.n_uni != PULL_GENERIC && d.vec4) {
+        for (u32 x = tid * 4; x < total; x += nthr * 4) {
+            const u32 dr = x / d.d, col = x % d.d, row = d.row0 + dr * d.rstride;
+            const u32 own = d.val_off + row * d.d;
+            const float seed = (d.pos0 + row == root_pos) ? 1.0f : 0.0f;   // a root has d == 1, never here
+            float4 acc = make_float4(seed, seed, seed, seed);
+#pragma unroll
+            for (u32 j = 0; j < 4; ++j) {
+                if (j < d.n_uni) {
+                    const UEdge ue = d.e[j];
+                    const float4 t = edge_term4(T, ue.kind, ue.goff + dr * ue.gs, ue.voff + dr * ue.vs, ue.a0, ue.a1, own, col);
+                    acc.x += t.x; acc.y += t.y; acc.z += t.z; acc.w += t.w;
+                }
+            }
+            st4(T.G + own + col, acc);
+        }
+        return;
+    }
     for (u32 x = tid; x < total; x += nthr) {
         const u32 dr = x / d.d, col = x % d.d, row = d.row0 + dr * d.rstride;
         const u32 own = d.val_off + row * d.d;
@@ -542,7 +581,7 @@ __global__ __launch_bounds__(WG) void k_fwd_step(Tables T, u32 work_lo, u32 work
             {   // stage cn descriptors (32 words each)
                 const u32 *src = reinterpret_cast<const u32 *>(T.tiles_f + wr.first + c0);
                 u32 *dst = reinterpret_cast<u32 *>(sdesc);
-                for (u32 x = threadIdx.x; x < cn * 32; x += WG) dst[x] = src[x];
+                for (u32 x = threadIdx.x; x < cn * (u32)(sizeof(TileDesc) / 4); x += WG) dst[x] = src[x];
             }
             __syncthreads();
             u32 i = 0;

@@ -63,7 +63,7 @@ struct ParamDesc {
     i32 rows, cols;
 };
 
-// One forward (or dX) tile: everything the tile routine needs in one 128-byte record, so that a
+// One forward (or dX) tile: everything the tile routine needs in one 160-byte record, so that a
 // workgroup starts its data loads after a single descriptor load.  For up to four operand slots
 // the record says whether the operand rows of THIS tile are consecutive in the value arena
 // (then the i-th row of the tile reads slot j at base[j] + i * sstride[j] and the row-offset list
@@ -71,8 +71,10 @@ struct ParamDesc {
 struct TileDesc {
     u32 op, B, d, arity;
     u32 pos0, val_off, dx_off, k;
-    i32 param, bias, aux0;
+    i32 aux0;
     u32 rstride;                     // component-wise tiles cover rows row0 + i * rstride, i < nrows
+    const float *w;                  // MATVEC: matrix data; LOOKUP: table data (device pointers, so that
+    const float *b;                  // no parameter record has to be fetched first); b: bias data or null
     u32 opnd, indim, flags, t;       // flags: bit 0 float4 path allowed, bit 1 operand rows 16-byte aligned
     u32 contig, row0;                // contig bits 0..3: operand rows of slot j are evenly spaced over this tile;
                                      // bits 16..31: tiles of the same depth that follow in the run, this one included
@@ -80,8 +82,10 @@ struct TileDesc {
     u32 sdim[4];                     // dimension of operand slot j
     u32 nrows, depth;
     u32 sstride[4];                  // operand row spacing of slot j (elements per tile row step)
+    u32 lds_out, lds_src[4];         // reserved
+    u32 pad;
 };
-static_assert(sizeof(TileDesc) == 128, "TileDesc must be 128 bytes");
+static_assert(sizeof(TileDesc) == 160, "TileDesc must be 160 bytes");
 
 // A consumer edge that is the same for every row of a pull tile up to constant row strides.
 struct UEdge { u32 kind, goff, voff, gs, vs; i32 a0, a1; };
@@ -94,7 +98,8 @@ struct PullDesc {
     u32 pos0, B, d, val_off;
     u32 depth, row0, n_uni, nrows;   // rows row0 + i * rstride, i < nrows, of the batch, all columns
     UEdge e[4];                      // edge j of the i-th row: e[j] shifted by i * (gs, vs)
-    u32 rstride, grp_len, pad[2];    // grp_len: tiles of the same depth that follow in the run, this one included
+    u32 rstride, grp_len;            // grp_len: tiles of the same depth that follow in the run, this one included
+    u32 vec4, pad;                   // vec4: d % 4 == 0 and every offset / stride / range of e[] is a multiple of 4
 };
 static_assert(sizeof(PullDesc) == 160, "PullDesc must be 160 bytes");
 
@@ -116,7 +121,6 @@ struct CLay {              // scan element of the per-chain launch layout
     }
 };
 struct WorkRec { u32 first, len; };   // a workgroup runs tiles [first, first + len) in order
-struct BEdge { u32 cons, prod, w; };  // batch-level dependency; w = 0 when it can be fused
 
 // Static tile of the deferred parameter-gradient kernels (built on the host per parameter set).
 struct PTile { i32 param; i32 i0, j0; i32 pad; };
@@ -157,8 +161,7 @@ struct Tables {
     u32 *order; u32 *pos_of; u32 *batch_of_pos; u32 *s_aux0; u32 *s_in_off;
     u32 *batch_off; BatchRec *batches; Lay *lay; u32 *b_indim;
     u32 *val_off; u32 *dx_off; u32 *opnd_off;
-    u32 *b_align;          // per (batch, slot): 1 when the slot is row-aligned to one producer batch
-    BEdge *bedges; u32 *slot_of; u32 *label_of; u32 *lorder;
+    u32 *slot_of; u32 *label_of; u32 *lorder;
     ChainRec *chains; CLay *clay; u32 *chain_of_lpos;
     u32 *slot_wf; u32 *slot_wa; u32 *slot_tb;     // per launch slot: first forward work, pull work, dX tile
     WorkRec *works_f; WorkRec *works_a;

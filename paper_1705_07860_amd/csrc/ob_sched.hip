@@ -329,35 +329,14 @@ __device__ inline u32 producer_batch(const Tables &T, u32 p, u32 j, u32 *prow)
 constexpr u32 FUSE_MAX_MULT = 4;
 __device__ inline u32 gcd_u32(u32 a, u32 b) { while (b) { const u32 t = a % b; a = b; b = t; } return a; }
 
-// per edge: clears b_align[(batch, slot)] unless every row of the slot reads a component-wise (or
-// leaf) producer batch row of its own group, where with G = gcd of the two row counts the
-// consumer group is row / (B_cons / G) and the producer group is row / (B_prod / G)
-__global__ void k_align(Tables T)
-{
-    const u32 e = blockIdx.x * blockDim.x + threadIdx.x;
-    if (e >= T.E) return;
-    const u32 v = T.edge_cons[e];
-    const u32 j = e - T.in_off[v];
-    const u32 p = T.pos_of[v];
-    const u32 b = T.batch_of_pos[p];
-    const BatchRec &r = T.batches[b];
-    const u32 row = p - r.pos0;
-    u32 prow;
-    const u32 by = producer_batch(T, p, j, &prow);
-    const BatchRec &y = T.batches[by];
-    bool ok = op_chainable(r.op, r.arity) && op_chain_source(y.op, y.arity);
-    if (ok) {
-        // a group may hold at most FUSE_MAX_MULT rows of a batch: fusing must keep B / that many
-        // independent groups, or the fused launch would serialise what a launch per level runs wide
-        const u32 G = gcd_u32(r.B, y.B);
-        const u32 mc = r.B / G, mp = y.B / G;
-        ok = mc <= FUSE_MAX_MULT && mp <= FUSE_MAX_MULT && row / mc == prow / mp;
-    }
-    if (!ok) T.b_align[r.indim + j] = 0;
-}
-
 // per edge, in schedule order (index s_in_off[p] + j): consumer batch, producer batch, and
-// whether a launch boundary is needed (0: the edge can be fused)
+// whether a launch boundary is needed.  The edge can be fused (0) when both batches are
+// component-wise (the producer may also be a leaf) and, with G = gcd of the two row counts, the
+// consumer row and the producer row lie in the same group (consumer group = row / (B_cons / G),
+// producer group = row / (B_prod / G)).  A group may hold at most FUSE_MAX_MULT rows of a batch:
+// fusing must keep that many independent groups, or a fused launch would serialise what a launch
+// per level runs wide.  Two batches end up in one slot only if every edge between them is fusable
+// (any other edge pushes the consumer to a later slot), so the test is per edge.
 __global__ void k_erecs(Tables T, u32 *rec_cons, u32 *rec_prod, u32 *rec_w, u32 *lvl_eoff)
 {
     const u32 e = blockIdx.x * blockDim.x + threadIdx.x;
@@ -372,7 +351,14 @@ __global__ void k_erecs(Tables T, u32 *rec_cons, u32 *rec_prod, u32 *rec_w, u32 
     const u32 es = T.s_in_off[p] + j;
     rec_cons[es] = b;
     rec_prod[es] = by;
-    rec_w[es] = T.b_align[r.indim + j] ? 0u : 1u;
+    const BatchRec &y = T.batches[by];
+    bool ok = op_chainable(r.op, r.arity) && op_chain_source(y.op, y.arity);
+    if (ok) {
+        const u32 G = gcd_u32(r.B, y.B);
+        const u32 mc = r.B / G, mp = y.B / G;
+        ok = mc <= FUSE_MAX_MULT && mp <= FUSE_MAX_MULT && (p - r.pos0) / mc == prow / mp;
+    }
+    rec_w[es] = ok ? 0u : 1u;
     if (j == 0) {   // level boundaries of the schedule-ordered edge list
         const u32 st = r.step;
         if (p == 0 || T.step[T.order[p - 1]] != st) lvl_eoff[st] = es;
@@ -600,7 +586,12 @@ __device__ inline void fill_tile_desc(const Tables &T, const BatchRec &r, u32 t,
 {
     d.op = r.op; d.B = r.B; d.d = r.d; d.arity = r.arity;
     d.pos0 = r.pos0; d.val_off = r.val_off; d.dx_off = r.dx_off; d.k = r.k;
-    d.param = r.param; d.bias = r.bias; d.aux0 = r.aux0; d.rstride = rstride;
+    d.aux0 = r.aux0; d.rstride = rstride;
+    d.w = r.param >= 0 ? T.params[r.param].data : nullptr;
+    d.b = r.bias >= 0 ? T.params[r.bias].data : nullptr;
+    d.lds_out = 0;
+    for (int j = 0; j < 4; ++j) d.lds_src[j] = 0;
+    d.pad = 0;
     d.opnd = r.opnd; d.indim = r.indim; d.flags = r.vec4; d.t = t;
     d.contig = 0; d.row0 = row0; d.nrows = nrows; d.depth = r.step;
     for (int j = 0; j < 4; ++j) { d.base[j] = 0; d.sdim[j] = 0; d.sstride[j] = 0; }
@@ -641,7 +632,7 @@ __device__ inline void fill_pull_desc(const Tables &T, const BatchRec &r, u32 ro
     d.pos0 = r.pos0; d.B = r.B; d.d = r.d; d.val_off = r.val_off;
     d.depth = r.step; d.row0 = row0; d.nrows = nrows; d.n_uni = PULL_GENERIC; d.rstride = rstride;
     for (int j = 0; j < 4; ++j) { UEdge z; z.kind = 0; z.goff = z.voff = z.gs = z.vs = 0; z.a0 = z.a1 = 0; d.e[j] = z; }
-    d.grp_len = 1; d.pad[0] = d.pad[1] = 0;
+    d.grp_len = 1; d.vec4 = 0; d.pad = 0;
     if (nrows > PULL_MAX_ROWS) return;
     const u32 u0 = T.order[r.pos0 + row0];
     const u32 q0 = T.succ_off[u0];
@@ -668,6 +659,15 @@ __device__ inline void fill_pull_desc(const Tables &T, const BatchRec &r, u32 ro
         }
     }
     d.n_uni = cnt;
+    bool vec = (r.d & 3u) == 0;
+    for (u32 j = 0; j < cnt; ++j) {
+        const UEdge &ue = d.e[j];
+        const bool scalar_g = ue.kind == EK_SQN;                 // these read one gradient scalar per row
+        if (!scalar_g && ((ue.goff | ue.gs) & 3u)) vec = false;
+        if ((ue.kind == EK_MUL || ue.kind == EK_DTANH || ue.kind == EK_DSIGM) && ((ue.voff | ue.vs) & 3u)) vec = false;
+        if (ue.kind == EK_RANGE && (((u32)ue.a0 | (u32)ue.a1) & 3u)) vec = false;
+    }
+    d.vec4 = vec ? 1u : 0u;
 }
 
 // chain that owns global tile / work index x of list `which` (0 fwd tiles, 1 pull tiles, 2 dX tiles,
@@ -883,7 +883,7 @@ int sched_run(ob_ctx *ctx)
     A(T.s_in_off, u32, n + 1);
     A(T.batch_off, u32, n + 1); A(T.batches, BatchRec, n); A(T.lay, Lay, n); A(T.b_indim, u32, E + 1);
     A(T.val_off, u32, n); A(T.dx_off, u32, n); A(T.opnd_off, u32, E + 1);
-    A(T.b_align, u32, E + 1); A(T.bedges, BEdge, E + 1); A(T.slot_of, u32, n); A(T.label_of, u32, n);
+    A(T.slot_of, u32, n); A(T.label_of, u32, n);
     A(T.lorder, u32, n); A(T.chains, ChainRec, n); A(T.clay, CLay, n); A(T.chain_of_lpos, u32, n);
     A(T.slot_wf, u32, n + 2); A(T.slot_wa, u32, n + 2); A(T.slot_tb, u32, n + 2);
     A(T.works_f, WorkRec, cap_f); A(T.works_a, WorkRec, cap_a);
@@ -966,12 +966,10 @@ int sched_run(ob_ctx *ctx)
     const int fuse = by_depth && ctx->fuse;
     u32 *rec_cons = ctx->val_b, *rec_prod = (u32 *)ctx->key_b, *rec_w = rec_prod + (E + 1);
     if (fuse && E > 0) {
-        HIP_TRY(ctx, prim_fill_u32(T.b_align, 1u, (size_t)E + 1, s));
         HIP_TRY(ctx, prim_fill_u32(lvl_eoff, 0xffffffffu, (size_t)n + 2, s));
-        K(k_align, E, T);
         K(k_erecs, E, T, rec_cons, rec_prod, rec_w, lvl_eoff);
         hipLaunchKernelGGL(k_lvl_fix, dim3(1), dim3(1), 0, s, T, lvl_eoff);
-        ctx->n_launch_sched += 3;
+        ctx->n_launch_sched += 2;
     }
     hipLaunchKernelGGL(k_slots, dim3(1), dim3(SLOT_THREADS), 0, s, T, (fuse && E > 0) ? 1 : 0, rec_cons, rec_prod,
                        rec_w, lvl_eoff);
