@@ -134,7 +134,10 @@ def main():
     def sched(i):
         c = ctxs[i % pool]
         c.reset()
-        c.schedule(graphs[i % pool].root)
+        if pipeline:
+            c.schedule_async(graphs[i % pool].root)   # queued; forward() of that step collects it
+        else:
+            c.schedule(graphs[i % pool].root)
 
     def execute(i):
         c = ctxs[i % pool]
@@ -147,9 +150,9 @@ def main():
         if pipeline:
             sched(first)
             for i in range(first, first + count):
-                execute(i)
                 if i + 1 < first + count:
                     sched(i + 1)
+                execute(i)
         else:
             for i in range(first, first + count):
                 sched(i)

@@ -146,6 +146,9 @@ int ob_forward(ob_ctx *ctx, int node);
  * launch plan); a later ob_forward of the same node then only executes.  Blocks the host for one
  * small read of the schedule header. */
 int ob_schedule(ob_ctx *ctx, int node);
+/* Same, but only queues the scheduling work and returns; the next ob_schedule / ob_forward of
+ * this context waits for it and reads the header.  Errors found on the GPU surface there. */
+int ob_schedule_async(ob_ctx *ctx, int node);
 /* Reverse-mode differentiation from a 1-element node that ob_forward covered: batches in
  * reverse order (Section 3.3).  Node gradients are overwritten, parameter gradients
  * accumulate. */
@@ -197,6 +200,10 @@ int ob_test_sort(ob_ctx *ctx, size_t n, const uint64_t *keys, const uint32_t *va
                  int n_bits, uint64_t *keys_out, uint32_t *vals_out);
 int ob_test_scan(ob_ctx *ctx, size_t n, const uint32_t *in, uint32_t *out_exclusive,
                  uint32_t *total);
+/* Average duration in microseconds of n back-to-back launches of an empty kernel (touch = 0) or
+ * of a kernel whose one thread does a dependent load and store (touch = 1) on the context's
+ * stream: the floor of a launch boundary on this machine, reported by the benchmark. */
+int ob_test_launch_cost(ob_ctx *ctx, int n, int touch, float *us_per_launch);
 /* C[M x N] = A[M x K] * B[N x K]^T through the library's MFMA tile routine. */
 int ob_test_gemm(ob_ctx *ctx, int M, int N, int K, const float *A, const float *B, float *C);
 

@@ -70,6 +70,7 @@ def lib():
             "ob_ctx_fork": (i, [vp, vp, sz, vp, POINTER(vp)]),
             "ob_ctx_set_schedule_stream": (i, [vp, vp]),
             "ob_schedule": (i, [vp, i]),
+            "ob_schedule_async": (i, [vp, i]),
             "ob_ctx_set_mode": (i, [vp, i]),
             "ob_ctx_set_launch": (i, [vp, i]),
             "ob_ctx_set_fusion": (i, [vp, i]),
@@ -104,6 +105,7 @@ def lib():
             "ob_test_sort": (i, [vp, sz, vp, vp, i, i, vp, vp]),
             "ob_test_scan": (i, [vp, sz, vp, vp, vp]),
             "ob_test_gemm": (i, [vp, i, i, i, vp, vp, vp]),
+            "ob_test_launch_cost": (i, [vp, i, i, POINTER(c_float)]),
         }
         for name, (res, args) in sigs.items():
             fn = getattr(L, name)
@@ -265,6 +267,9 @@ class Context:
     def schedule(self, node: int):
         self._ck(self.L.ob_schedule(self.h, node))
 
+    def schedule_async(self, node: int):
+        self._ck(self.L.ob_schedule_async(self.h, node))
+
     def forward(self, node: int):
         self._ck(self.L.ob_forward(self.h, node))
 
@@ -334,6 +339,11 @@ class Context:
         tot = np.zeros(1, np.uint32)
         self._ck(self.L.ob_test_scan(self.h, a.shape[0], _ptr(a), _ptr(out), _ptr(tot)))
         return out[:a.shape[0]], int(tot[0])
+
+    def test_launch_cost(self, n: int = 2000, touch: int = 0) -> float:
+        out = c_float()
+        self._ck(self.L.ob_test_launch_cost(self.h, n, touch, byref(out)))
+        return float(out.value)
 
     def test_gemm(self, A, B):
         A = np.ascontiguousarray(A, np.float32)

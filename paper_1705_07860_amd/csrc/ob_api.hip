@@ -239,6 +239,7 @@ int ob_graph_new(ob_ctx *ctx)
     ctx->top = ctx->persist_top;
     ctx->uploaded = false;
     ctx->n_sched = 0;
+    ctx->sched_pending = false;
     ctx->forward_done = ctx->backward_done = false;
     return OB_OK;
 }
@@ -341,7 +342,7 @@ static int append_node(ob_ctx *ctx, int op, const u32 *ins, u32 arity, int param
     ctx->sum_out_dim += dim;
     if (op == OB_OP_MATVEC) {
         ctx->sum_mv_d32 += (u64)ctx->params[param].rows / GT + 1;
-        ctx->sum_mv_k32 += (u64)ctx->params[param].cols / GT + 1;
+        ctx->sum_mv_k32 += (u64)ctx->params[param].cols / DXT + 1;
         if (!ctx->params_used_w[param]) { ctx->params_used_w[param] = 1; ctx->params_dirty = true; }
         if (bias >= 0 && !ctx->params_used_b[bias]) { ctx->params_used_b[bias] = 1; ctx->params_dirty = true; }
     }
@@ -585,12 +586,11 @@ int ob_upload(ob_ctx *ctx)
 
 // ---- execution ------------------------------------------------------------------------------------
 
-int ob_schedule(ob_ctx *ctx, int node)
+static int schedule_begin(ob_ctx *ctx, int node)
 {
-    CHECK_CTX(ctx);
     if (node < 0 || node >= (int)ctx->op.size()) return ctx_fail(ctx, OB_E_BADID, "unknown node id %d", node);
     if (ctx->n_sched) {
-        if ((u32)node < ctx->n_sched) return OB_OK;   // already scheduled
+        if ((u32)node < ctx->n_sched) return OB_OK;   // already scheduled (or being scheduled)
         return ctx_fail(ctx, OB_E_STATE, "incremental forward (nodes beyond the evaluated prefix) is not built");
     }
     if (int rc = ob_upload(ctx)) return rc;
@@ -600,11 +600,33 @@ int ob_schedule(ob_ctx *ctx, int node)
     ctx->top = ctx->graph_top;
     ctx->ms_graph = 0;
     HIP_TRY(ctx, hipEventRecord(ctx->ev[7], ctx->sched_stream));
-    if (int rc = sched_run(ctx)) return rc;
+    if (int rc = sched_enqueue(ctx)) return rc;
     HIP_TRY(ctx, hipEventRecord(ctx->ev[9], ctx->sched_stream));
     ctx->n_sched = T.n;
+    ctx->sched_pending = true;
     ctx->forward_done = ctx->backward_done = false;
     return OB_OK;
+}
+
+static int schedule_end(ob_ctx *ctx)
+{
+    if (!ctx->sched_pending) return OB_OK;
+    ctx->sched_pending = false;
+    if (int rc = sched_finish(ctx)) { ctx->n_sched = 0; return rc; }
+    return OB_OK;
+}
+
+int ob_schedule_async(ob_ctx *ctx, int node)
+{
+    CHECK_CTX(ctx);
+    return schedule_begin(ctx, node);
+}
+
+int ob_schedule(ob_ctx *ctx, int node)
+{
+    CHECK_CTX(ctx);
+    if (int rc = schedule_begin(ctx, node)) return rc;
+    return schedule_end(ctx);
 }
 
 int ob_forward(ob_ctx *ctx, int node)
@@ -652,6 +674,7 @@ int ob_reset(ob_ctx *ctx)
 {
     CHECK_CTX(ctx);
     if (int rc = wait_own_work(ctx)) return rc;
+    ctx->sched_pending = false;
     ctx->n_sched = 0;
     ctx->forward_done = ctx->backward_done = false;
     if (ctx->uploaded) ctx->top = ctx->graph_top;
@@ -856,6 +879,22 @@ int ob_test_scan(ob_ctx *ctx, size_t n, const uint32_t *in, uint32_t *out_exclus
         if (e == hipSuccess) e = hipStreamSynchronize(ctx->stream);
         if (e != hipSuccess) rc = ctx_fail(ctx, OB_E_HIP, "scan failed: %s", hipGetErrorString(e));
     }
+    ctx->top = save;
+    return rc;
+}
+
+int ob_test_launch_cost(ob_ctx *ctx, int n, int touch, float *us_per_launch)
+{
+    CHECK_CTX(ctx);
+    if (!ctx->arena) return ctx_fail(ctx, OB_E_STATE, "no arena");
+    if (n <= 0 || !us_per_launch) return ctx_fail(ctx, OB_E_ARG, "bad argument");
+    const size_t save = ctx->top;
+    float *scratch = arena_array<float>(ctx, 64);
+    if (!scratch) return ctx_fail(ctx, OB_E_OOM, "arena too small");
+    int rc = OB_OK;
+    hipError_t e = hipMemsetAsync(scratch, 0, 256, ctx->stream);
+    if (e == hipSuccess) e = exec_launch_probe(scratch, n, touch, us_per_launch, ctx->stream);
+    if (e != hipSuccess) rc = ctx_fail(ctx, OB_E_HIP, "launch probe failed: %s", hipGetErrorString(e));
     ctx->top = save;
     return rc;
 }

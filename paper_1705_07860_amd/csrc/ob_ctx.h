@@ -54,6 +54,8 @@ struct ob_ctx {
     size_t pinned_bytes = 0;
     bool uploaded = false;
     u32 n_sched = 0;                   // nodes covered by the last schedule (0 = none)
+    bool sched_pending = false;        // scheduling is queued on the GPU, its results are not read yet
+    u32 hdr_window = 0, n_items_sched = 0;
     bool forward_done = false, backward_done = false;
     Tables T{};
     SchedHeader hdr{};

@@ -19,7 +19,8 @@ enum : u32 {
 // ---- execution geometry --------------------------------------------------------------------
 constexpr int WG = 256;               // threads per workgroup of every tile kernel (4 wave64)
 constexpr int EW_TILE = 1024;         // elements of one elementwise / pull tile
-constexpr int GT = 32;                // GEMM tile edge (one 32x32 MFMA accumulator block)
+constexpr int GT = 32;                // forward / dW GEMM tile edge (one 32x32 MFMA accumulator block)
+constexpr int DXT = 16;               // dX GEMM tile edge (16x16 blocks: its output is small, more tiles fill more CUs)
 constexpr int ROWS_PER_RED_TILE = 4;  // rows of one row-reduction tile (one wave per row)
 constexpr int WIDE_ADD_ARITY = 9;     // ADD with at least this many operands reduces per row
 constexpr u32 VAL_ALIGN = 64;         // batch blocks start at multiples of 64 floats (256 B)
@@ -189,8 +190,10 @@ hipError_t prim_sort_pairs(u64 *keys, u32 *vals, u64 *keys_tmp, u32 *vals_tmp, s
 
 // ---- scheduler / executor entry points ---------------------------------------------------
 struct ob_ctx;
-int sched_run(ob_ctx *ctx);
+int sched_enqueue(ob_ctx *ctx);
+int sched_finish(ob_ctx *ctx);
 int exec_forward(ob_ctx *ctx);
 int exec_backward(ob_ctx *ctx);
 hipError_t exec_gather_all(const Tables &T, int which, float *dst, const u32 *dst_off, hipStream_t s);
+hipError_t exec_launch_probe(float *scratch, int n, int touch, float *us_per_launch, hipStream_t s);
 hipError_t exec_test_gemm(int M, int N, int K, const float *A, const float *B, float *C, hipStream_t s);

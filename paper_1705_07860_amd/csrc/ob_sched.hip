@@ -538,7 +538,7 @@ __global__ void k_chain_recs(Tables T, const u32 *flag, const u32 *flag_excl, CL
             L.wf = L.wa = cr.nrb;
         } else {
             switch (r0.op) {
-            case OP_MATVEC: L.tf = cdiv(r0.B, GT) * cdiv(r0.d, GT); L.tb = cdiv(r0.B, GT) * cdiv(r0.k, GT); break;
+            case OP_MATVEC: L.tf = cdiv(r0.B, GT) * cdiv(r0.d, GT); L.tb = cdiv(r0.B, DXT) * cdiv(r0.k, DXT); break;
             case OP_PICK_NLS:
             case OP_SQNORM: L.tf = cdiv(r0.B, ROWS_PER_RED_TILE); break;
             default: L.tf = r0.B; break;   // wide sum: one workgroup per row
@@ -845,10 +845,12 @@ inline int bit_width_u32(u32 x) { int b = 0; while (x) { ++b; x >>= 1; } return 
         }                                                                                               \
     } while (0)
 
-// Allocates the scheduler tables for n nodes / E edges in the arena and runs every stage on the
-// context's stream.  Ends with one small device-to-host copy of the header and the per-step
-// tile offsets (the only synchronisation of a forward call).
-int sched_run(ob_ctx *ctx)
+constexpr size_t SLOT_WINDOW = 8192;   // per-slot table entries read back together with the header
+
+// First half of scheduling: allocates the scheduler tables for n nodes / E edges in the arena and
+// queues every stage on the schedule stream, ending with the device-to-host copies of the header
+// and the per-slot launch tables.  Does not wait.
+int sched_enqueue(ob_ctx *ctx)
 {
     Tables &T = ctx->T;
     hipStream_t s = ctx->sched_stream;
@@ -1004,33 +1006,56 @@ int sched_run(ob_ctx *ctx)
     }
     HIP_TRY(ctx, hipGetLastError());
 
-    // ---- read back the header and the per-step tile offsets ----
-    HIP_TRY(ctx, hipMemcpyAsync(ctx->hdr_pinned, T.hdr, sizeof(SchedHeader), hipMemcpyDeviceToHost, s));
+    // ---- queue the read-back of the header and of a first window of the per-slot tables ----
+    // pinned layout: [header 256 B][slot_wf window][slot_wa window][slot_tb window]
+    ctx->hdr_window = (u32)((size_t)n + 2 < SLOT_WINDOW ? (size_t)n + 2 : SLOT_WINDOW);
+    const size_t need = 256 + (size_t)ctx->hdr_window * 12;
+    if (need > ctx->hdr_pinned_bytes) {
+        if (ctx->hdr_pinned) HIP_TRY(ctx, hipHostFree(ctx->hdr_pinned));
+        ctx->hdr_pinned = nullptr;
+        ctx->hdr_pinned_bytes = need + 4096;
+        HIP_TRY(ctx, hipHostMalloc(&ctx->hdr_pinned, ctx->hdr_pinned_bytes, hipHostMallocDefault));
+    }
+    char *hp = (char *)ctx->hdr_pinned;
+    const size_t wb = (size_t)ctx->hdr_window * 4;
+    HIP_TRY(ctx, hipMemcpyAsync(hp, T.hdr, sizeof(SchedHeader), hipMemcpyDeviceToHost, s));
+    HIP_TRY(ctx, hipMemcpyAsync(hp + 256, T.slot_wf, wb, hipMemcpyDeviceToHost, s));
+    HIP_TRY(ctx, hipMemcpyAsync(hp + 256 + wb, T.slot_wa, wb, hipMemcpyDeviceToHost, s));
+    HIP_TRY(ctx, hipMemcpyAsync(hp + 256 + 2 * wb, T.slot_tb, wb, hipMemcpyDeviceToHost, s));
+    ctx->n_items_sched = n_items;
+    return 0;
+}
+
+// Second half of scheduling: waits for the queued work, checks the error flags, takes the
+// per-slot launch tables and carves the value and gradient arenas.
+int sched_finish(ob_ctx *ctx)
+{
+    Tables &T = ctx->T;
+    hipStream_t s = ctx->sched_stream;
     HIP_TRY(ctx, hipStreamSynchronize(s));
-    ctx->hdr = *(SchedHeader *)ctx->hdr_pinned;
-    ctx->hdr.n_items = n_items;
+    const char *hp = (const char *)ctx->hdr_pinned;
+    ctx->hdr = *(const SchedHeader *)hp;
+    ctx->hdr.n_items = ctx->n_items_sched;
     if (ctx->hdr.err & ERR_CYCLE)
         return ctx_fail(ctx, -6, "frontier pass resolved %u of %u nodes (cyclic or malformed graph)",
-                        ctx->hdr.frontier_done, n);
+                        ctx->hdr.frontier_done, T.n);
     if (ctx->hdr.err & ERR_COLLISION) return ctx_fail(ctx, -6, "signature hash collision detected");
     if (ctx->hdr.err & ERR_TABLE_FULL) return ctx_fail(ctx, -6, "signature table full");
     if (ctx->hdr.err & ERR_OVERFLOW) return ctx_fail(ctx, -5, "value arena exceeds 2^32 elements");
-    const u32 ns = ctx->hdr.n_slots;
-    const size_t words = (size_t)ns + 1;
-    if (words * 12 > ctx->hdr_pinned_bytes) {
-        if (ctx->hdr_pinned) HIP_TRY(ctx, hipHostFree(ctx->hdr_pinned));
-        ctx->hdr_pinned = nullptr;
-        ctx->hdr_pinned_bytes = words * 12 + 4096;
-        HIP_TRY(ctx, hipHostMalloc(&ctx->hdr_pinned, ctx->hdr_pinned_bytes, hipHostMallocDefault));
+    const size_t words = (size_t)ctx->hdr.n_slots + 1;
+    if (words <= ctx->hdr_window) {
+        const size_t wb = (size_t)ctx->hdr_window * 4;
+        const u32 *wf = (const u32 *)(hp + 256), *wa = (const u32 *)(hp + 256 + wb), *tb = (const u32 *)(hp + 256 + 2 * wb);
+        ctx->slot_wf.assign(wf, wf + words);
+        ctx->slot_wa.assign(wa, wa + words);
+        ctx->slot_tb.assign(tb, tb + words);
+    } else {   // more launch slots than the window (unbatched mode): plain copies
+        ctx->slot_wf.resize(words); ctx->slot_wa.resize(words); ctx->slot_tb.resize(words);
+        HIP_TRY(ctx, hipMemcpyAsync(ctx->slot_wf.data(), T.slot_wf, words * 4, hipMemcpyDeviceToHost, s));
+        HIP_TRY(ctx, hipMemcpyAsync(ctx->slot_wa.data(), T.slot_wa, words * 4, hipMemcpyDeviceToHost, s));
+        HIP_TRY(ctx, hipMemcpyAsync(ctx->slot_tb.data(), T.slot_tb, words * 4, hipMemcpyDeviceToHost, s));
+        HIP_TRY(ctx, hipStreamSynchronize(s));
     }
-    u32 *hp = (u32 *)ctx->hdr_pinned;
-    HIP_TRY(ctx, hipMemcpyAsync(hp, T.slot_wf, words * 4, hipMemcpyDeviceToHost, s));
-    HIP_TRY(ctx, hipMemcpyAsync(hp + words, T.slot_wa, words * 4, hipMemcpyDeviceToHost, s));
-    HIP_TRY(ctx, hipMemcpyAsync(hp + 2 * words, T.slot_tb, words * 4, hipMemcpyDeviceToHost, s));
-    HIP_TRY(ctx, hipStreamSynchronize(s));
-    ctx->slot_wf.assign(hp, hp + words);
-    ctx->slot_wa.assign(hp + words, hp + 2 * words);
-    ctx->slot_tb.assign(hp + 2 * words, hp + 3 * words);
 
     // ---- value and gradient arenas ----
     T.V = arena_array<float>(ctx, ctx->hdr.val_floats + VAL_ALIGN);

@@ -316,7 +316,7 @@ def test_forked_contexts_share_parameters_and_pipeline_scheduling():
         cs[j].forward(gs[j].root)
         cs[j].backward(gs[j].root)
         if j == 0:
-            cs[1].schedule(gs[1].root)      # overlaps the execution of graph 0
+            cs[1].schedule_async(gs[1].root)  # queued behind nothing: overlaps the execution of graph 0
     for c, g, o in zip(cs, gs, os_):
         total = int(o.v_off[-1])
         assert segment_rel_err(c.all_read(0, total), o.val[:total], o.v_off) <= TOL
