@@ -425,15 +425,17 @@ __global__ __launch_bounds__(SLOT_THREADS) void k_slots(Tables T, int fuse, cons
             u32 nc = 0, ny = 0, nw = 0;
             const bool nhave = (l + 1 < L) && nlo + tid < nhi;
             if (nhave) { nc = rec_cons[nlo + tid]; ny = rec_prod[nlo + tid]; nw = rec_w[nlo + tid]; }
-            if (have) atomicMax(&s_slot[c], s_slot[y] + w);
-            for (u32 e = lo + tid + SLOT_THREADS; e < hi; e += SLOT_THREADS)
-                atomicMax(&s_slot[rec_cons[e]], s_slot[rec_prod[e]] + rec_w[e]);
+            if (have) atomicMax(&s_slot[c], (s_slot[y] + (w & 1u)) | (w >> 1));
+            for (u32 e = lo + tid + SLOT_THREADS; e < hi; e += SLOT_THREADS) {
+                const u32 ww = rec_w[e];
+                atomicMax(&s_slot[rec_cons[e]], (s_slot[rec_prod[e]] + (ww & 1u)) | (ww >> 1));
+            }
             __syncthreads();
             // slots of this level are final: remember the fused pairs that stay inside a slot
-            if (have && w == 0u && s_slot[y] == s_slot[c]) pair_insert(s_pair, c, y, &s_over);
+            if (have && (w & 1u) == 0u && s_slot[y] == s_slot[c]) pair_insert(s_pair, c, y, &s_over);
             for (u32 e = lo + tid + SLOT_THREADS; e < hi; e += SLOT_THREADS) {
                 const u32 cc = rec_cons[e], yy = rec_prod[e];
-                if (rec_w[e] == 0u && s_slot[yy] == s_slot[cc]) pair_insert(s_pair, cc, yy, &s_over);
+                if ((rec_w[e] & 1u) == 0u && s_slot[yy] == s_slot[cc]) pair_insert(s_pair, cc, yy, &s_over);
             }
             lo = nlo; hi = nhi; c = nc; y = ny; w = nw; have = nhave;
         }
@@ -574,6 +576,17 @@ __global__ void k_slot_tables(Tables T, const CLay *clay_ex, const CLay *total)
         T.hdr->tiles_fwd = t.tf; T.hdr->tiles_pull = t.ta; T.hdr->tiles_dx = t.tb;
         T.hdr->works_fwd = t.wf; T.hdr->works_pull = t.wa;
     }
+}
+
+// launch slots that hold no batch (a matrix product moved to the next odd slot can leave one
+// behind) inherit the offsets of the next slot that does, so that their launch range is empty
+__global__ void k_slot_fill(Tables T)
+{
+    const u32 s = blockIdx.x * blockDim.x + threadIdx.x;
+    if (s >= T.hdr->n_slots) return;
+    u32 t = s;
+    while (T.slot_wf[t] == 0xffffffffu) ++t;   // entry n_slots is always set
+    if (t != s) { T.slot_wf[s] = T.slot_wf[t]; T.slot_wa[s] = T.slot_wa[t]; T.slot_tb[s] = T.slot_tb[t]; }
 }
 
 // ---- tile descriptors ------------------------------------------------------------------------------
@@ -887,7 +900,11 @@ int sched_enqueue(ob_ctx *ctx)
     A(T.val_off, u32, n); A(T.dx_off, u32, n); A(T.opnd_off, u32, E + 1);
     A(T.slot_of, u32, n); A(T.label_of, u32, n);
     A(T.lorder, u32, n); A(T.chains, ChainRec, n); A(T.clay, CLay, n); A(T.chain_of_lpos, u32, n);
-    A(T.slot_wf, u32, n + 2); A(T.slot_wa, u32, n + 2); A(T.slot_tb, u32, n + 2);
+    // slot_wf | slot_wa | slot_tb, adjacent; moving matrix products to odd slots can at most double
+    // the number of slots over the number of depth levels
+    const size_t slot_cap = 2 * (size_t)n + 4;
+    A(T.slot_wf, u32, 3 * slot_cap);
+    T.slot_wa = T.slot_wf + slot_cap; T.slot_tb = T.slot_wa + slot_cap;
     A(T.works_f, WorkRec, cap_f); A(T.works_a, WorkRec, cap_a);
     A(T.tiles_f, TileDesc, cap_f); A(T.tiles_a, PullDesc, cap_a); A(T.tiles_b, TileDesc, cap_b);
     A(T.root_pos, u32, 64);
@@ -989,7 +1006,14 @@ int sched_enqueue(ob_ctx *ctx)
     K(k_chain_recs, n, T, cflag, cflag_excl, clay_in, n);
     HIP_TRY(ctx, prim_scan_clay(clay_in, T.clay, n, clay_total, ctx->scratch, s));
     ctx->n_launch_sched += 6;
+    const size_t slot_used = fuse ? (slot_cap < 2 * (size_t)SLOT_MAX_NB + 4 ? slot_cap : 2 * (size_t)SLOT_MAX_NB + 4) : 0;
+    if (fuse) {   // only the first slot_used entries of each table can be touched by a fused plan
+        HIP_TRY(ctx, prim_fill_u32(T.slot_wf, 0xffffffffu, slot_used, s));
+        HIP_TRY(ctx, prim_fill_u32(T.slot_wa, 0xffffffffu, slot_used, s));
+        HIP_TRY(ctx, prim_fill_u32(T.slot_tb, 0xffffffffu, slot_used, s));
+    }
     K(k_slot_tables, n, T, T.clay, clay_total);
+    if (fuse) K(k_slot_fill, slot_used, T);
     hipLaunchKernelGGL(k_tiles, dim3(1024), dim3(TPB), 0, s, T, T.clay, clay_total, (u32)cap_f, (u32)cap_a,
                        (u32)cap_b);
     ++ctx->n_launch_sched;
@@ -1008,7 +1032,7 @@ int sched_enqueue(ob_ctx *ctx)
 
     // ---- queue the read-back of the header and of a first window of the per-slot tables ----
     // pinned layout: [header 256 B][slot_wf window][slot_wa window][slot_tb window]
-    ctx->hdr_window = (u32)((size_t)n + 2 < SLOT_WINDOW ? (size_t)n + 2 : SLOT_WINDOW);
+    ctx->hdr_window = (u32)(slot_cap < SLOT_WINDOW ? slot_cap : SLOT_WINDOW);
     const size_t need = 256 + (size_t)ctx->hdr_window * 12;
     if (need > ctx->hdr_pinned_bytes) {
         if (ctx->hdr_pinned) HIP_TRY(ctx, hipHostFree(ctx->hdr_pinned));

@@ -339,3 +339,31 @@ def test_forked_contexts_share_parameters_and_pipeline_scheduling():
         assert rel_err(a.param_grad_read(pid, m.shape), ref) <= TOL, p.names[pid]
     b.close()
     a.close()
+
+
+def test_stacked_matrix_products():
+    """MATVEC feeding MATVEC directly, with and without a non-linearity in between."""
+    from paper_1705_07860_amd import binding as ob
+    rng = np.random.default_rng(3)
+    pb = wl.ParamBuilder(rng, std=0.3)
+    W = [pb.add(f"W{i}", 24, 24) for i in range(4)]
+    b0 = pb.add("b0", 24, 1)
+    p = pb.done()
+    gb = wl.GraphBuilder(p)
+    losses = []
+    for i in range(9):
+        h = gb.input(rng.standard_normal(24))
+        h = gb.matvec(W[0], b0, h)
+        h = gb.matvec(W[1], -1, h)
+        h = gb.matvec(W[2], -1, gb.tanh(gb.matvec(W[3], -1, h)))
+        losses.append(gb.sqnorm(h))
+    g = gb.finish(gb.add(losses), 9)
+    o = Oracle(g, p, "f64")
+    o.forward()
+    o.backward(g.root)
+    c, root = run_gpu(p, g, ob.OB_BYDEPTH, arena=64 << 20)
+    bo, ids, bd, _ = c.schedule_read()
+    rbo, rids, rbd = S.by_depth(g)
+    assert np.array_equal(bo, rbo) and np.array_equal(ids, rids) and np.array_equal(bd, rbd)
+    check_against_oracle(c, p, g, o, root, what="stacked")
+    c.close()
