@@ -235,6 +235,7 @@ int ob_graph_new(ob_ctx *ctx)
     ctx->param.clear(); ctx->bias.clear(); ctx->aux0.clear(); ctx->aux1.clear(); ctx->payload.clear();
     ctx->items_upto.clear();
     ctx->sum_out_dim = 0;
+    ctx->max_arity = 0;
     ctx->sum_mv_d32 = ctx->sum_mv_k32 = 0;
     ctx->top = ctx->persist_top;
     ctx->uploaded = false;
@@ -340,6 +341,7 @@ static int append_node(ob_ctx *ctx, int op, const u32 *ins, u32 arity, int param
     const u32 items = (op == OB_OP_MATVEC) ? (1u + (bias >= 0 ? 1u : 0u)) : (op == OB_OP_LOOKUP ? 1u : 0u);
     ctx->items_upto.push_back((ctx->items_upto.empty() ? 0u : ctx->items_upto.back()) + items);
     ctx->sum_out_dim += dim;
+    if (arity > ctx->max_arity) ctx->max_arity = arity;
     if (op == OB_OP_MATVEC) {
         ctx->sum_mv_d32 += (u64)ctx->params[param].rows / GT + 1;
         ctx->sum_mv_k32 += (u64)ctx->params[param].cols / DXT + 1;

@@ -46,6 +46,7 @@ struct ob_ctx {
     std::vector<float> payload;
     std::vector<u32> items_upto;       // parameter-use items among nodes [0, v]
     u64 sum_out_dim = 0;               // bounds the tile lists
+    u32 max_arity = 0;
     u64 sum_mv_d32 = 0, sum_mv_k32 = 0; // sums over MATVEC nodes of rows/32+1 and cols/32+1 (bound the GEMM tiles)
     size_t graph_top = 0;              // arena top right after the uploaded graph image
 

@@ -158,6 +158,7 @@ struct Tables {
     // scheduler tables
     u64 *sig; u32 *step; u32 *indeg; u32 *outdeg; u32 *succ_off; u32 *succ_edge; u32 *edge_cons;
     u32 *queue; u32 *qcount;            // frontier queue, [0]=tail
+    u32 *ext_indeg;                     // operands owned by another range of the partitioned depth pass
     u64 *ht_keys; u32 *ht_vals; u32 ht_mask; u32 *ht_slot;
     u32 *order; u32 *pos_of; u32 *batch_of_pos; u32 *s_aux0; u32 *s_in_off;
     u32 *batch_off; BatchRec *batches; Lay *lay; u32 *b_indim;

@@ -62,6 +62,8 @@ __device__ inline u32 consumer_of(const Tables &T, u32 e)
     return lo;
 }
 
+constexpr u32 DEPTH_PART = 4096;      // nodes per workgroup of the partitioned depth pass
+
 __global__ void k_edge_init(Tables T, u64 *keys, u32 *vals)
 {
     const u32 e = blockIdx.x * blockDim.x + threadIdx.x;
@@ -71,6 +73,7 @@ __global__ void k_edge_init(Tables T, u64 *keys, u32 *vals)
     const u32 j = e - T.in_off[v];
     T.edge_cons[e] = v;
     atomicAdd(&T.outdeg[u], 1u);
+    if (u / DEPTH_PART != v / DEPTH_PART) atomicAdd(&T.ext_indeg[v], 1u);   // operand owned by another partition
     atomicAdd((unsigned long long *)&T.sig[v], (unsigned long long)mix64(comb(0x5bd1e995ULL + j, T.out_dim[u])));
     keys[e] = u;
     vals[e] = e;
@@ -122,6 +125,125 @@ __global__ __launch_bounds__(FRONTIER_THREADS) void k_depth_frontier(Tables T, c
     if (threadIdx.x == 0) {
         T.hdr->frontier_done = s_tail;
         if (s_tail != T.n) atomicOr(&T.hdr->err, (u32)ERR_CYCLE);
+    }
+}
+
+// Partitioned frontier pass: the same dependency-counter algorithm, with the node ids cut into
+// ranges of DEPTH_PART nodes, one workgroup per range.  A workgroup keeps the counters, the
+// partial depths, its frontier queue and the successor lists of its range in LDS, so advancing
+// its frontier costs LDS latency only.  An edge into another range resolves through global
+// atomics: the producer raises the consumer's depth bound and lowers its count of unresolved
+// external operands; whoever resolves the last one posts the node to the owner's inbox, where it
+// counts as one more resolved dependency.  Ids are a topological order, so a range only ever
+// waits for lower ranges and the lowest never waits; all workgroups are resident together
+// (at most one per CU), and every wait is bounded.
+constexpr u32 DEPTH_SCAP = 12288;
+constexpr u32 DEPTH_THREADS = 256;    // a range's frontier is small: four waves keep the barriers cheap     // successor entries of a range held in LDS
+constexpr u32 DEPTH_MAX_PARTS = 240;
+constexpr u32 DEPTH_SPIN_LIMIT = 1u << 21;
+__global__ __launch_bounds__(DEPTH_THREADS) void k_depth_partitioned(Tables T, const u32 *succ_node, u32 *g_dep,
+                                                                         u32 *inbox, u32 *inbox_tail)
+{
+    __shared__ u32 s_pending[DEPTH_PART];
+    __shared__ u32 s_dep[DEPTH_PART];
+    __shared__ unsigned short s_queue[DEPTH_PART];
+    __shared__ u32 s_soff[DEPTH_PART + 1];
+    __shared__ u32 s_snode[DEPTH_SCAP];
+    __shared__ u32 s_head, s_tail, s_next, s_done, s_seen, s_in_cnt, s_fail;
+    const u32 tid = threadIdx.x;
+    const u32 k = blockIdx.x;
+    const u32 lo = k * DEPTH_PART;
+    const u32 hi = lo + DEPTH_PART < T.n ? lo + DEPTH_PART : T.n;
+    const u32 cnt = hi - lo;
+    const u32 ebase = T.succ_off[lo];
+    const u32 ecnt = T.succ_off[hi] - ebase;
+    if (tid == 0) { s_head = 0; s_tail = 0; s_next = 0; s_done = 0; s_seen = 0; s_in_cnt = 0; s_fail = 0; }
+    __syncthreads();
+    for (u32 i = tid; i < cnt; i += DEPTH_THREADS) {
+        const u32 v = lo + i;
+        const u32 ext = T.ext_indeg[v];
+        const u32 pend = T.indeg[v] - ext + (ext ? 1u : 0u);
+        s_pending[i] = pend;
+        s_dep[i] = 0;
+        s_soff[i] = T.succ_off[v] - ebase;
+        if (pend == 0) s_queue[atomicAdd(&s_next, 1u)] = (unsigned short)i;
+    }
+    if (tid == 0) s_soff[cnt] = ecnt;
+    for (u32 e = tid; e < ecnt && e < DEPTH_SCAP; e += DEPTH_THREADS) s_snode[e] = succ_node[ebase + e];
+    __syncthreads();
+    if (tid == 0) s_tail = s_next;
+    __syncthreads();
+    u32 spin = 0, iter = 0;
+    while (true) {
+        const u32 head = s_head, tail = s_tail;
+        if (head == tail && s_done == cnt) break;
+        // One thread looks at the inbox, but only when the frontier is empty or every 8th pass:
+        // the load goes to coherent memory and the next barrier waits for it.  (Nothing else in the
+        // loop touches global memory unless an edge leaves the range: depths stay in LDS and are
+        // written out once at the end.)
+        const bool poll = head == tail || (iter & 7u) == 0;
+        ++iter;
+        if (poll && tid == DEPTH_THREADS - 1)
+            s_in_cnt = __hip_atomic_load(&inbox_tail[k], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        for (u32 i = head + tid; i < tail; i += DEPTH_THREADS) {
+            const u32 ul = s_queue[i];
+            const u32 d = s_dep[ul];
+            const u32 e1 = s_soff[ul + 1];
+            for (u32 e = s_soff[ul]; e < e1; ++e) {
+                const u32 sn = e < DEPTH_SCAP ? s_snode[e] : succ_node[ebase + e];
+                if (sn < hi) {   // successors have larger ids than u, so sn >= lo
+                    const u32 sl = sn - lo;
+                    atomicMax(&s_dep[sl], d + 1);
+                    if (atomicSub(&s_pending[sl], 1u) == 1u) s_queue[atomicAdd(&s_next, 1u)] = (unsigned short)sl;
+                } else {
+                    atomicMax(&g_dep[sn], d + 1);
+                    __threadfence();
+                    if (atomicSub(&T.ext_indeg[sn], 1u) == 1u) {
+                        const u32 k2 = sn / DEPTH_PART;
+                        const u32 slot = atomicAdd(&inbox_tail[k2], 1u);
+                        __hip_atomic_store(&inbox[k2 * DEPTH_PART + slot], sn, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+                    }
+                }
+            }
+        }
+        __syncthreads();
+        // inbox entries are posted after their slot is reserved: take them in order, stop at a hole
+        {
+            const u32 seen = s_seen, avail = s_in_cnt;
+            for (u32 j = seen + tid; j < avail; j += DEPTH_THREADS) {
+                const u32 sn = __hip_atomic_load(&inbox[k * DEPTH_PART + j], __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_AGENT);
+                if (sn == 0xffffffffu) { atomicMin(&s_in_cnt, j); continue; }
+            }
+            __syncthreads();
+            const u32 upto = s_in_cnt;
+            for (u32 j = seen + tid; j < upto; j += DEPTH_THREADS) {
+                const u32 sn = __hip_atomic_load(&inbox[k * DEPTH_PART + j], __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_AGENT);
+                const u32 sl = sn - lo;
+                atomicMax(&s_dep[sl], __hip_atomic_load(&g_dep[sn], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+                if (atomicSub(&s_pending[sl], 1u) == 1u) s_queue[atomicAdd(&s_next, 1u)] = (unsigned short)sl;
+            }
+            __syncthreads();
+            if (tid == 0) {
+                s_seen = upto;
+                s_done += tail - head;
+                s_head = tail;
+                s_tail = s_next;
+            }
+        }
+        __syncthreads();
+        if (head == tail && s_tail == tail) {   // nothing to do: waiting for another range
+            if (++spin > DEPTH_SPIN_LIMIT) { if (tid == 0) s_fail = 1; }
+            __builtin_amdgcn_s_sleep(8);
+        } else {
+            spin = 0;
+        }
+        __syncthreads();
+        if (s_fail) break;
+    }
+    for (u32 i = tid; i < cnt; i += DEPTH_THREADS) T.step[lo + i] = s_dep[i];
+    if (tid == 0) {
+        atomicAdd(&T.hdr->frontier_done, s_done);
+        if (s_done != cnt) atomicOr(&T.hdr->err, (u32)ERR_CYCLE);
     }
 }
 
@@ -329,18 +451,25 @@ __device__ inline u32 producer_batch(const Tables &T, u32 p, u32 j, u32 *prow)
 constexpr u32 FUSE_MAX_MULT = 4;
 __device__ inline u32 gcd_u32(u32 a, u32 b) { while (b) { const u32 t = a % b; a = b; b = t; } return a; }
 
-// per edge, in schedule order (index s_in_off[p] + j): consumer batch, producer batch, and
-// whether a launch boundary is needed.  The edge can be fused (0) when both batches are
-// component-wise (the producer may also be a leaf) and, with G = gcd of the two row counts, the
-// consumer row and the producer row lie in the same group (consumer group = row / (B_cons / G),
-// producer group = row / (B_prod / G)).  A group may hold at most FUSE_MAX_MULT rows of a batch:
-// fusing must keep that many independent groups, or a fused launch would serialise what a launch
-// per level runs wide.  Two batches end up in one slot only if every edge between them is fusable
-// (any other edge pushes the consumer to a later slot), so the test is per edge.
-__global__ void k_erecs(Tables T, u32 *rec_cons, u32 *rec_prod, u32 *rec_w, u32 *lvl_eoff)
+// Batch-level dependencies.  Per graph edge: consumer batch, producer batch, and whether a launch
+// boundary is needed.  The edge can be fused (weight 0) when both batches are component-wise (the
+// producer may also be a leaf) and, with G = gcd of the two row counts, the consumer row and the
+// producer row lie in the same group (consumer group = row / (B_cons / G), producer group =
+// row / (B_prod / G)).  A group may hold at most FUSE_MAX_MULT rows of a batch: fusing must keep
+// that many independent groups, or a fused launch would serialise what a launch per level runs
+// wide.  Two batches end up in one slot only if every edge between them is fusable (any other
+// edge pushes the consumer to a later slot), so the test is per edge.  Distinct (consumer,
+// producer, weight) triples are collected once each through a hash set.
+constexpr u32 SLOT_MAX_NB = 4096;     // batches a fused plan can hold (12-bit ids)
+constexpr u32 BSET_SIZE = 1u << 16;   // open-addressing set of packed triples
+constexpr u32 BLIST_MAX = 20480;      // distinct triples the slot kernel keeps in LDS (80 KB)
+constexpr int SLOT_BITS = 13;         // bits of a slot or a label when the plan is fused
+
+__global__ void k_bedges(Tables T, u32 *bset, u32 *blist)
 {
     const u32 e = blockIdx.x * blockDim.x + threadIdx.x;
     if (e >= T.E) return;
+    if (T.hdr->n_batches > SLOT_MAX_NB) return;
     const u32 v = T.edge_cons[e];
     const u32 j = e - T.in_off[v];
     const u32 p = T.pos_of[v];
@@ -348,9 +477,6 @@ __global__ void k_erecs(Tables T, u32 *rec_cons, u32 *rec_prod, u32 *rec_w, u32 
     const BatchRec &r = T.batches[b];
     u32 prow;
     const u32 by = producer_batch(T, p, j, &prow);
-    const u32 es = T.s_in_off[p] + j;
-    rec_cons[es] = b;
-    rec_prod[es] = by;
     const BatchRec &y = T.batches[by];
     bool ok = op_chainable(r.op, r.arity) && op_chain_source(y.op, y.arity);
     if (ok) {
@@ -358,109 +484,71 @@ __global__ void k_erecs(Tables T, u32 *rec_cons, u32 *rec_prod, u32 *rec_w, u32 
         const u32 mc = r.B / G, mp = y.B / G;
         ok = mc <= FUSE_MAX_MULT && mp <= FUSE_MAX_MULT && (p - r.pos0) / mc == prow / mp;
     }
-    rec_w[es] = ok ? 0u : 1u;
-    if (j == 0) {   // level boundaries of the schedule-ordered edge list
-        const u32 st = r.step;
-        if (p == 0 || T.step[T.order[p - 1]] != st) lvl_eoff[st] = es;
+    const u32 key = ((b << 13) | (by << 1) | (ok ? 0u : 1u)) + 1u;
+    u32 h = (key * 2654435761u) & (BSET_SIZE - 1);
+    for (u32 probe = 0; probe < BSET_SIZE; ++probe) {
+        const u32 old = atomicCAS(&bset[h], 0u, key);
+        if (old == key) return;
+        if (old == 0u) {
+            const u32 i = atomicAdd(&T.hdr->n_bedges, 1u);
+            if (i < BLIST_MAX) blist[i] = key;
+            return;
+        }
+        h = (h + 1) & (BSET_SIZE - 1);
     }
+    atomicAdd(&T.hdr->n_bedges, BLIST_MAX);   // table full: forces the unfused plan
 }
 
-// edges of level l are [lvl_eoff[l], lvl_eoff[l+1]); levels without edges inherit the next start
-__global__ void k_lvl_fix(Tables T, u32 *lvl_eoff)
-{
-    // single thread: walk backwards filling levels that no node with operands started
-    const u32 L = T.hdr->n_steps;
-    u32 next = T.E;
-    lvl_eoff[L] = T.E;
-    for (u32 l = L; l-- > 0;) {
-        if (lvl_eoff[l] == 0xffffffffu) lvl_eoff[l] = next; else next = lvl_eoff[l];
-    }
-}
-
-// One workgroup.  Launch slot of a batch = longest path over its dependencies, where an edge that
-// can be fused (row groups aligned, both sides component-wise) costs 0 and any other edge costs
-// one launch boundary.  Levels are walked in order, so every producer's slot is final when it is
-// read; the records of the next level are loaded while the current one is reduced.  Batches
-// joined by fusable edges inside one slot then get a common chain label.
-constexpr u32 SLOT_MAX_NB = 4096;     // 16 KB slots + 16 KB labels + 24 KB pair table of LDS
-constexpr u32 PAIR_TBL = 6143;        // open-addressing set of fused (consumer, producer) batch pairs
-constexpr int SLOT_BITS = 13;         // bits of a slot or a label when the plan is fused
+// One workgroup.  Launch slot of a batch = longest path over the batch dependencies, where a
+// fusable edge costs 0 and any other edge one launch boundary: relaxed to a fixed point over the
+// distinct dependencies held in LDS.  Batches joined by fusable edges inside one slot then get a
+// common chain label (the smallest batch id of the chain).
 constexpr int SLOT_THREADS = 1024;
-
-__device__ inline void pair_insert(u32 *tbl, u32 c, u32 y, u32 *overflow)
-{
-    const u32 key = ((c << SLOT_BITS) | y) + 1u;
-    u32 h = (key * 2654435761u) % PAIR_TBL;
-    for (u32 probe = 0; probe < PAIR_TBL; ++probe) {
-        const u32 old = atomicCAS(&tbl[h], 0u, key);
-        if (old == 0u || old == key) return;
-        h = h + 1 == PAIR_TBL ? 0 : h + 1;
-    }
-    *overflow = 1;
-}
-
-__global__ __launch_bounds__(SLOT_THREADS) void k_slots(Tables T, int fuse, const u32 *rec_cons, const u32 *rec_prod,
-                                                        const u32 *rec_w, const u32 *lvl_eoff)
+__global__ __launch_bounds__(SLOT_THREADS) void k_slots(Tables T, int fuse, const u32 *blist)
 {
     __shared__ u32 s_slot[SLOT_MAX_NB];
     __shared__ u32 s_label[SLOT_MAX_NB];
-    __shared__ u32 s_pair[PAIR_TBL];
-    __shared__ u32 s_over, s_changed;
+    __shared__ u32 s_edge[BLIST_MAX];
+    __shared__ u32 s_changed;
     const u32 nb = T.hdr->n_batches;
-    const u32 L = T.hdr->n_steps;
+    const u32 ne = T.hdr->n_bedges;
     const u32 tid = threadIdx.x;
-    bool fallback = !fuse || nb > SLOT_MAX_NB;
-    if (!fallback) {
-        for (u32 b = tid; b < nb; b += SLOT_THREADS) { s_slot[b] = 0; s_label[b] = b; }
-        for (u32 i = tid; i < PAIR_TBL; i += SLOT_THREADS) s_pair[i] = 0;
-        if (tid == 0) s_over = 0;
-        __syncthreads();
-        u32 lo = lvl_eoff[0], hi = L > 0 ? lvl_eoff[1] : lo;
-        u32 c = 0, y = 0, w = 0;
-        bool have = lo + tid < hi;
-        if (have) { c = rec_cons[lo + tid]; y = rec_prod[lo + tid]; w = rec_w[lo + tid]; }
-        for (u32 l = 0; l < L; ++l) {
-            // the first record of the next level is loaded while this level is reduced
-            const u32 nlo = hi, nhi = (l + 1 < L) ? lvl_eoff[l + 2] : hi;
-            u32 nc = 0, ny = 0, nw = 0;
-            const bool nhave = (l + 1 < L) && nlo + tid < nhi;
-            if (nhave) { nc = rec_cons[nlo + tid]; ny = rec_prod[nlo + tid]; nw = rec_w[nlo + tid]; }
-            if (have) atomicMax(&s_slot[c], (s_slot[y] + (w & 1u)) | (w >> 1));
-            for (u32 e = lo + tid + SLOT_THREADS; e < hi; e += SLOT_THREADS) {
-                const u32 ww = rec_w[e];
-                atomicMax(&s_slot[rec_cons[e]], (s_slot[rec_prod[e]] + (ww & 1u)) | (ww >> 1));
-            }
-            __syncthreads();
-            // slots of this level are final: remember the fused pairs that stay inside a slot
-            if (have && (w & 1u) == 0u && s_slot[y] == s_slot[c]) pair_insert(s_pair, c, y, &s_over);
-            for (u32 e = lo + tid + SLOT_THREADS; e < hi; e += SLOT_THREADS) {
-                const u32 cc = rec_cons[e], yy = rec_prod[e];
-                if ((rec_w[e] & 1u) == 0u && s_slot[yy] == s_slot[cc]) pair_insert(s_pair, cc, yy, &s_over);
-            }
-            lo = nlo; hi = nhi; c = nc; y = ny; w = nw; have = nhave;
-        }
-        __syncthreads();
-        if (s_over) fallback = true;
-    }
-    if (fallback) {   // one slot per step, no fusion
+    if (!fuse || nb > SLOT_MAX_NB || ne > BLIST_MAX) {   // one slot per step, no fusion
         for (u32 b = tid; b < nb; b += SLOT_THREADS) { T.slot_of[b] = T.batches[b].step; T.label_of[b] = b; }
         if (tid == 0) { T.hdr->n_slots = T.hdr->n_steps; T.hdr->slot_sweeps = 0; T.hdr->p0 = 1; }
         return;
     }
-    u32 sweeps = 0, npairs = 0;
+    for (u32 b = tid; b < nb; b += SLOT_THREADS) { s_slot[b] = 0; s_label[b] = b; }
+    for (u32 e = tid; e < ne; e += SLOT_THREADS) s_edge[e] = blist[e] - 1u;
+    u32 sweeps = 0;
     while (true) {
         if (tid == 0) s_changed = 0;
         __syncthreads();
-        for (u32 i = tid; i < PAIR_TBL; i += SLOT_THREADS) {
-            const u32 key = s_pair[i];
-            if (!key) continue;
-            if (sweeps == 0) ++npairs;
-            const u32 cc = (key - 1u) >> SLOT_BITS, yy = (key - 1u) & ((1u << SLOT_BITS) - 1u);
-            const u32 a = s_label[cc], bb = s_label[yy];
+        for (u32 e = tid; e < ne; e += SLOT_THREADS) {
+            const u32 k = s_edge[e];
+            const u32 c = k >> 13, y = (k >> 1) & 0xfffu;
+            const u32 want = s_slot[y] + (k & 1u);
+            if (want > s_slot[c]) { atomicMax(&s_slot[c], want); s_changed = 1; }
+        }
+        __syncthreads();
+        ++sweeps;
+        const u32 ch = s_changed;
+        __syncthreads();
+        if (!ch || sweeps > nb + 1) break;
+    }
+    while (true) {
+        if (tid == 0) s_changed = 0;
+        __syncthreads();
+        for (u32 e = tid; e < ne; e += SLOT_THREADS) {
+            const u32 k = s_edge[e];
+            if (k & 1u) continue;
+            const u32 c = k >> 13, y = (k >> 1) & 0xfffu;
+            if (s_slot[c] != s_slot[y]) continue;
+            const u32 a = s_label[c], bb = s_label[y];
             if (a != bb) {
                 const u32 m = a < bb ? a : bb;
-                atomicMin(&s_label[cc], m);
-                atomicMin(&s_label[yy], m);
+                atomicMin(&s_label[c], m);
+                atomicMin(&s_label[y], m);
                 s_changed = 1;
             }
         }
@@ -468,7 +556,7 @@ __global__ __launch_bounds__(SLOT_THREADS) void k_slots(Tables T, int fuse, cons
         ++sweeps;
         const u32 ch = s_changed;
         __syncthreads();
-        if (!ch || sweeps > nb + 2) break;
+        if (!ch || sweeps > 3 * nb + 3) break;
     }
     u32 mx = 0;
     for (u32 b = tid; b < nb; b += SLOT_THREADS) {
@@ -478,7 +566,6 @@ __global__ __launch_bounds__(SLOT_THREADS) void k_slots(Tables T, int fuse, cons
     if (tid == 0) s_changed = 0;
     __syncthreads();
     atomicMax(&s_changed, mx);
-    atomicAdd(&T.hdr->n_bedges, npairs);
     __syncthreads();
     if (tid == 0) { T.hdr->n_slots = s_changed + 1; T.hdr->slot_sweeps = sweeps; }
 }
@@ -891,7 +978,10 @@ int sched_enqueue(ob_ctx *ctx)
     } while (0)
     A(T.sig, u64, n); A(T.step, u32, n); A(T.indeg, u32, n); A(T.outdeg, u32, n + 1);
     A(T.succ_off, u32, n + 1); A(T.succ_edge, u32, E + 1); A(T.edge_cons, u32, E + 1);
-    A(T.queue, u32, n); A(T.qcount, u32, 64);
+    A(T.queue, u32, n); A(T.qcount, u32, 64); A(T.ext_indeg, u32, n + 1);
+    u32 *g_dep, *inbox, *inbox_tail;
+    const u32 n_parts = (n + DEPTH_PART - 1) / DEPTH_PART;
+    A(g_dep, u32, n + 1); A(inbox, u32, (size_t)n_parts * DEPTH_PART); A(inbox_tail, u32, n_parts + 1);
     A(T.ht_keys, u64, ht_size); A(T.ht_vals, u32, ht_size); A(T.ht_slot, u32, n);
     T.ht_mask = ht_size - 1;
     A(T.order, u32, n); A(T.pos_of, u32, n); A(T.batch_of_pos, u32, n); A(T.s_aux0, u32, n);
@@ -921,8 +1011,8 @@ int sched_enqueue(ob_ctx *ctx)
     A(ctx->lay_in, Lay, n); A(ctx->lay_total, Lay, 1);
     CLay *clay_in, *clay_total;
     A(clay_in, CLay, n); A(clay_total, CLay, 1);
-    u32 *lvl_eoff;
-    A(lvl_eoff, u32, n + 2);
+    u32 *bset, *blist;
+    A(bset, u32, BSET_SIZE); A(blist, u32, BLIST_MAX);
     {
         size_t sb = prim_sort_scratch_bytes(maxne);
         size_t sc = prim_scan_scratch_bytes(maxne, sizeof(Lay));
@@ -935,6 +1025,13 @@ int sched_enqueue(ob_ctx *ctx)
     HIP_TRY(ctx, hipMemsetAsync(T.hdr, 0, sizeof(SchedHeader), s));
     HIP_TRY(ctx, hipMemsetAsync(T.outdeg, 0, (size_t)(n + 1) * 4, s));
     HIP_TRY(ctx, hipMemsetAsync(T.qcount, 0, 64 * 4, s));
+    HIP_TRY(ctx, hipMemsetAsync(T.ext_indeg, 0, (size_t)(n + 1) * 4, s));
+    const bool part_depth = by_depth && n_parts <= DEPTH_MAX_PARTS && ctx->max_arity < 60000;
+    if (part_depth) {
+        HIP_TRY(ctx, hipMemsetAsync(g_dep, 0, (size_t)(n + 1) * 4, s));
+        HIP_TRY(ctx, hipMemsetAsync(inbox, 0xff, (size_t)n_parts * DEPTH_PART * 4, s));
+        HIP_TRY(ctx, hipMemsetAsync(inbox_tail, 0, (size_t)(n_parts + 1) * 4, s));
+    }
     HIP_TRY(ctx, hipMemsetAsync(T.pu_start, 0, n_slots * 4, s));
     HIP_TRY(ctx, hipMemsetAsync(T.pu_end, 0, n_slots * 4, s));
     K(k_node_init, n, T, by_depth);
@@ -949,7 +1046,11 @@ int sched_enqueue(ob_ctx *ctx)
 
     // ---- stage 2 / 3 ----
     if (by_depth) {
-        hipLaunchKernelGGL(k_depth_frontier, dim3(1), dim3(FRONTIER_THREADS), 0, s, T, succ_node);
+        if (part_depth)
+            hipLaunchKernelGGL(k_depth_partitioned, dim3(n_parts), dim3(DEPTH_THREADS), 0, s, T, succ_node, g_dep, inbox,
+                               inbox_tail);
+        else
+            hipLaunchKernelGGL(k_depth_frontier, dim3(1), dim3(FRONTIER_THREADS), 0, s, T, succ_node);
         ++ctx->n_launch_sched;
         HIP_TRY(ctx, hipMemsetAsync(T.ht_keys, 0, (size_t)ht_size * 8, s));
         HIP_TRY(ctx, hipMemsetAsync(T.ht_vals, 0xff, (size_t)ht_size * 4, s));
@@ -983,15 +1084,11 @@ int sched_enqueue(ob_ctx *ctx)
 
     // ---- launch planning: slots, chains, tile descriptors ----
     const int fuse = by_depth && ctx->fuse;
-    u32 *rec_cons = ctx->val_b, *rec_prod = (u32 *)ctx->key_b, *rec_w = rec_prod + (E + 1);
     if (fuse && E > 0) {
-        HIP_TRY(ctx, prim_fill_u32(lvl_eoff, 0xffffffffu, (size_t)n + 2, s));
-        K(k_erecs, E, T, rec_cons, rec_prod, rec_w, lvl_eoff);
-        hipLaunchKernelGGL(k_lvl_fix, dim3(1), dim3(1), 0, s, T, lvl_eoff);
-        ctx->n_launch_sched += 2;
+        HIP_TRY(ctx, hipMemsetAsync(bset, 0, (size_t)BSET_SIZE * 4, s));
+        K(k_bedges, E, T, bset, blist);
     }
-    hipLaunchKernelGGL(k_slots, dim3(1), dim3(SLOT_THREADS), 0, s, T, (fuse && E > 0) ? 1 : 0, rec_cons, rec_prod,
-                       rec_w, lvl_eoff);
+    hipLaunchKernelGGL(k_slots, dim3(1), dim3(SLOT_THREADS), 0, s, T, (fuse && E > 0) ? 1 : 0, blist);
     ++ctx->n_launch_sched;
     K(k_launch_keys, n, T, ctx->key_a, ctx->val_a, n);
     if (fuse && E > 0) {
