@@ -192,6 +192,9 @@ int ob_stats_read(ob_ctx *ctx, ob_stats *out);
 #define OB_DBG_SUCC_EDGE 3 /* u32[E]  edge ids sorted by producer  */
 #define OB_DBG_ORDER 4     /* u32[n]  node ids in schedule order   */
 #define OB_DBG_VAL_OFF 5   /* u32[n]  element offset of each node's row in the value arena */
+#define OB_DBG_TILES_FWD 6 /* forward tile descriptors in launch order, 40 words each (internal layout) */
+#define OB_DBG_TILES_PULL 7 /* backward pull tile descriptors in launch order, 48 words each (internal layout) */
+#define OB_DBG_CHAINS 8    /* launch chains, 8 words each: first, members, slot, fused, groups, groups per block, blocks, tiles per block */
 int ob_debug_read(ob_ctx *ctx, int which, uint32_t *host_out, size_t cap_words, size_t *n_words);
 
 /* Stand-alone device primitives, exposed so that tests can check them directly.  All

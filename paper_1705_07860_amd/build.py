@@ -35,6 +35,8 @@ def build(force: bool = True, verbose: bool = False) -> Path:
     deps = srcs + [(CSRC / h).resolve() for h in HEADERS]
     if not force and LIB.exists() and all(LIB.stat().st_mtime >= d.stat().st_mtime for d in deps):
         return LIB
+    if LIB.exists():
+        LIB.unlink()    # a failed build must not leave an older library behind to be loaded by mistake
     objdir = HERE / "_build"
     objdir.mkdir(exist_ok=True)
     procs = []

@@ -827,6 +827,9 @@ int ob_debug_read(ob_ctx *ctx, int which, uint32_t *host_out, size_t cap_words, 
     case OB_DBG_SUCC_EDGE: src = T.succ_edge; words = T.E; break;
     case OB_DBG_ORDER: src = T.order; words = T.n; break;
     case OB_DBG_VAL_OFF: src = T.val_off; words = T.n; break;
+    case OB_DBG_TILES_FWD: src = T.tiles_f; words = (size_t)ctx->hdr.tiles_fwd * (sizeof(TileDesc) / 4); break;
+    case OB_DBG_TILES_PULL: src = T.tiles_a; words = (size_t)ctx->hdr.tiles_pull * (sizeof(PullDesc) / 4); break;
+    case OB_DBG_CHAINS: src = T.chains; words = (size_t)ctx->hdr.n_chains * (sizeof(ChainRec) / 4); break;
     default: return ctx_fail(ctx, OB_E_ARG, "unknown table %d", which);
     }
     if (n_words) *n_words = words;

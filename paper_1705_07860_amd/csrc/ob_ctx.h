@@ -60,7 +60,7 @@ struct ob_ctx {
     bool forward_done = false, backward_done = false;
     Tables T{};
     SchedHeader hdr{};
-    std::vector<u32> slot_wf, slot_wa, slot_tb;   // host mirrors of the per-slot launch tables (n_slots + 1 each)
+    std::vector<SlotRec> slots;   // host mirror of the per-slot launch table (n_slots + 1 entries)
     void *scratch = nullptr;           // scan / sort scratch in the arena
     u64 *key_a = nullptr, *key_b = nullptr;
     u32 *val_a = nullptr, *val_b = nullptr;

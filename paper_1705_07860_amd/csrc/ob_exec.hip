@@ -58,25 +58,77 @@ __device__ inline u32 slot_dim(const Tables &T, const TileDesc &d, u32 j)
     return T.b_indim[d.indim + j];
 }
 
-__device__ inline float ew_value(const Tables &T, const TileDesc &d, u32 i, u32 row, u32 col)
+// The fused chains' LDS copy is always reached through an LDS-typed pointer, so that these
+// accesses are LDS instructions (a generic pointer would make them flat accesses, which also
+// wait on outstanding global stores).
+// Parameter pointers come out of descriptors as generic pointers; they always point to global
+// memory, and saying so keeps their loads global instructions.
+typedef __attribute__((address_space(1))) const float gl_float;
+typedef float vec4f __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(1))) const vec4f gl_vec4f;
+__device__ inline gl_float *as_global(const float *p) { return (gl_float *)p; }
+__device__ inline float4 gl_ld4(gl_float *p)
+{
+    const vec4f t = *reinterpret_cast<gl_vec4f *>(p);
+    return make_float4(t.x, t.y, t.z, t.w);
+}
+
+typedef __attribute__((address_space(3))) float lds_float;
+typedef __attribute__((address_space(3))) vec4f lds_vec4f;
+__device__ inline float4 lds_ld4(const lds_float *p)
+{
+    const vec4f t = *reinterpret_cast<const lds_vec4f *>(p);
+    return make_float4(t.x, t.y, t.z, t.w);
+}
+__device__ inline void lds_st4(lds_float *p, float4 v)
+{
+    vec4f t; t.x = v.x; t.y = v.y; t.z = v.z; t.w = v.w;
+    *reinterpret_cast<lds_vec4f *>(p) = t;
+}
+
+__device__ inline u32 slot_lds(const TileDesc &d, u32 j)
+{
+    if (j == 0) return d.lds_src[0];
+    if (j == 1) return d.lds_src[1];
+    if (j == 2) return d.lds_src[2];
+    return d.lds_src[3];
+}
+// Operand element at arena offset `off` of slot j: from the chain's LDS copy `cl` when the
+// descriptor says an earlier member of the same fused chain left it there, else from the arena.
+__device__ inline float ldv(const Tables &T, const TileDesc &d, const lds_float *cl, u32 j, u32 off)
+{
+    float v;
+    if (j < 4 && (d.flags & (TF_SRC_LDS << j))) v = cl[(u32)(off + slot_lds(d, j))];
+    else v = T.V[off];
+    return v;
+}
+__device__ inline float4 ldv4(const Tables &T, const TileDesc &d, const lds_float *cl, u32 j, u32 off)
+{
+    float4 v;
+    if (j < 4 && (d.flags & (TF_SRC_LDS << j))) v = lds_ld4(cl + (u32)(off + slot_lds(d, j)));
+    else v = ld4(T.V + off);
+    return v;
+}
+
+__device__ inline float ew_value(const Tables &T, const TileDesc &d, const lds_float *cl, u32 i, u32 row, u32 col)
 {
     switch (d.op) {
     case OP_INPUT: return T.payload[T.s_aux0[d.pos0 + row] + col];
-    case OP_LOOKUP: return d.w[(size_t)T.s_aux0[d.pos0 + row] * d.d + col];
+    case OP_LOOKUP: return as_global(d.w)[(size_t)T.s_aux0[d.pos0 + row] * d.d + col];
     case OP_ADD: {
         float acc = 0.f;
-        for (u32 j = 0; j < d.arity; ++j) acc += T.V[opnd_row(T, d, j, i, row) + col];
+        for (u32 j = 0; j < d.arity; ++j) acc += ldv(T, d, cl, j, opnd_row(T, d, j, i, row) + col);
         return acc;
     }
-    case OP_CMULT: return T.V[opnd_row(T, d, 0, i, row) + col] * T.V[opnd_row(T, d, 1, i, row) + col];
-    case OP_TANH: return tanhf(T.V[opnd_row(T, d, 0, i, row) + col]);
-    case OP_SIGMOID: return sigmoidf_(T.V[opnd_row(T, d, 0, i, row) + col]);
-    case OP_SLICE: return T.V[opnd_row(T, d, 0, i, row) + (u32)d.aux0 + col];
+    case OP_CMULT: return ldv(T, d, cl, 0, opnd_row(T, d, 0, i, row) + col) * ldv(T, d, cl, 1, opnd_row(T, d, 1, i, row) + col);
+    case OP_TANH: return tanhf(ldv(T, d, cl, 0, opnd_row(T, d, 0, i, row) + col));
+    case OP_SIGMOID: return sigmoidf_(ldv(T, d, cl, 0, opnd_row(T, d, 0, i, row) + col));
+    case OP_SLICE: return ldv(T, d, cl, 0, opnd_row(T, d, 0, i, row) + (u32)d.aux0 + col);
     case OP_CONCAT: {
         u32 c = col;
         for (u32 j = 0; j < d.arity; ++j) {
             const u32 dj = slot_dim(T, d, j);
-            if (c < dj) return T.V[opnd_row(T, d, j, i, row) + c];
+            if (c < dj) return ldv(T, d, cl, j, opnd_row(T, d, j, i, row) + c);
             c -= dj;
         }
         return 0.f;
@@ -85,37 +137,37 @@ __device__ inline float ew_value(const Tables &T, const TileDesc &d, u32 i, u32 
     }
 }
 
-__device__ inline float4 ew_value4(const Tables &T, const TileDesc &d, u32 i, u32 row, u32 col)
+__device__ inline float4 ew_value4(const Tables &T, const TileDesc &d, const lds_float *cl, u32 i, u32 row, u32 col)
 {
     switch (d.op) {
     case OP_INPUT: return ld4(T.payload + T.s_aux0[d.pos0 + row] + col);
-    case OP_LOOKUP: return ld4(d.w + (size_t)T.s_aux0[d.pos0 + row] * d.d + col);
+    case OP_LOOKUP: return gl_ld4(as_global(d.w) + (size_t)T.s_aux0[d.pos0 + row] * d.d + col);
     case OP_ADD: {
         float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
         for (u32 j = 0; j < d.arity; ++j) {
-            const float4 x = ld4(T.V + opnd_row(T, d, j, i, row) + col);
+            const float4 x = ldv4(T, d, cl, j, opnd_row(T, d, j, i, row) + col);
             acc.x += x.x; acc.y += x.y; acc.z += x.z; acc.w += x.w;
         }
         return acc;
     }
     case OP_CMULT: {
-        const float4 a = ld4(T.V + opnd_row(T, d, 0, i, row) + col), b = ld4(T.V + opnd_row(T, d, 1, i, row) + col);
+        const float4 a = ldv4(T, d, cl, 0, opnd_row(T, d, 0, i, row) + col), b = ldv4(T, d, cl, 1, opnd_row(T, d, 1, i, row) + col);
         return make_float4(a.x * b.x, a.y * b.y, a.z * b.z, a.w * b.w);
     }
     case OP_TANH: {
-        const float4 a = ld4(T.V + opnd_row(T, d, 0, i, row) + col);
+        const float4 a = ldv4(T, d, cl, 0, opnd_row(T, d, 0, i, row) + col);
         return make_float4(tanhf(a.x), tanhf(a.y), tanhf(a.z), tanhf(a.w));
     }
     case OP_SIGMOID: {
-        const float4 a = ld4(T.V + opnd_row(T, d, 0, i, row) + col);
+        const float4 a = ldv4(T, d, cl, 0, opnd_row(T, d, 0, i, row) + col);
         return make_float4(sigmoidf_(a.x), sigmoidf_(a.y), sigmoidf_(a.z), sigmoidf_(a.w));
     }
-    case OP_SLICE: return ld4(T.V + opnd_row(T, d, 0, i, row) + (u32)d.aux0 + col);
+    case OP_SLICE: return ldv4(T, d, cl, 0, opnd_row(T, d, 0, i, row) + (u32)d.aux0 + col);
     case OP_CONCAT: {
         u32 c = col;
         for (u32 j = 0; j < d.arity; ++j) {
             const u32 dj = slot_dim(T, d, j);
-            if (c < dj) return ld4(T.V + opnd_row(T, d, j, i, row) + c);
+            if (c < dj) return ldv4(T, d, cl, j, opnd_row(T, d, j, i, row) + c);
             c -= dj;
         }
         return make_float4(0.f, 0.f, 0.f, 0.f);
@@ -124,20 +176,26 @@ __device__ inline float4 ew_value4(const Tables &T, const TileDesc &d, u32 i, u3
     }
 }
 
-// rows row0 + i * rstride (i < nrows) of the batch, all columns; worked by threads tid < nthr
-__device__ inline void ew_fwd_tile(const Tables &T, const TileDesc &d, u32 tid, u32 nthr)
+// rows row0 + i * rstride (i < nrows) of the batch, all columns; worked by threads tid < nthr.
+// cl: the fused chain's LDS copy (results are written there too when the descriptor asks for it).
+__device__ inline void ew_fwd_tile(const Tables &T, const TileDesc &d, lds_float *cl, u32 tid, u32 nthr)
 {
     const u32 total = d.nrows * d.d;
     float *out = T.V + d.val_off;
-    if (d.flags & 1u) {
+    const bool keep = (d.flags & TF_OUT_LDS) != 0;
+    if (d.flags & TF_VEC4) {
         for (u32 x = tid * 4; x < total; x += nthr * 4) {
             const u32 i = x / d.d, col = x % d.d, row = d.row0 + i * d.rstride;
-            st4(out + row * d.d + col, ew_value4(T, d, i, row, col));
+            const float4 v = ew_value4(T, d, cl, i, row, col);
+            st4(out + row * d.d + col, v);
+            if (keep) lds_st4(cl + (u32)(d.val_off + row * d.d + col + d.lds_out), v);
         }
     } else {
         for (u32 x = tid; x < total; x += nthr) {
             const u32 i = x / d.d, col = x % d.d, row = d.row0 + i * d.rstride;
-            out[row * d.d + col] = ew_value(T, d, i, row, col);
+            const float v = ew_value(T, d, cl, i, row, col);
+            out[row * d.d + col] = v;
+            if (keep) cl[(u32)(d.val_off + row * d.d + col + d.lds_out)] = v;
         }
     }
 }
@@ -246,7 +304,7 @@ __device__ inline void gemm_nt_tile(const float *xrow, bool row_ok, u32 B, const
     const u32 l32 = lane & 31, h = lane >> 5;
     const u32 col = i0 + l32;
     const bool col_ok = col < m;
-    const float *wrow = W + (size_t)(col_ok ? col : 0u) * K;
+    gl_float *wrow = as_global(W) + (size_t)(col_ok ? col : 0u) * K;
     u32 lo, hi;
     wave_range<4>(K, lo, hi);
     floatx16 acc;
@@ -260,7 +318,7 @@ __device__ inline void gemm_nt_tile(const float *xrow, bool row_ok, u32 B, const
                 const u32 k0 = kb + 8 * u + 4 * h;
                 const bool in = kb + 8 * u < hi && k0 < K;
                 a[u] = (in && row_ok) ? ld4(xrow + k0) : z4;
-                b[u] = (in && col_ok) ? ld4(wrow + k0) : z4;
+                b[u] = (in && col_ok) ? gl_ld4(wrow + k0) : z4;
             }
 #pragma unroll
             for (int u = 0; u < KU; ++u) acc = mfma4(a[u], b[u], acc);
@@ -280,7 +338,7 @@ __device__ inline void gemm_nt_tile(const float *xrow, bool row_ok, u32 B, const
     float out[4];
     reduce_waves<4>(acc, lds, out);
     if (col_ok) {
-        const float bb = bias ? bias[col] : 0.f;
+        const float bb = bias ? as_global(bias)[col] : 0.f;
         for (int i = 0; i < 4; ++i) {
             const u32 rr = r0 + 8 * w + 4 * h + i;
             if (rr < B) Y[(size_t)rr * m + col] = out[i] + bb;
@@ -314,7 +372,7 @@ __device__ inline void matvec_dx_tile(const Tables &T, const TileDesc &d, float 
     const u32 row = r0 + l16, col = c0 + l16;
     const bool row_ok = row < d.B, col_ok = col < K;
     const float *grow = T.G + d.val_off + (size_t)(row_ok ? row : 0u) * m;
-    const float *wcol = d.w + (col_ok ? col : 0u);
+    gl_float *wcol = as_global(d.w) + (col_ok ? col : 0u);
     const bool fast = (m & 3u) == 0;
     // split [0, m) in units of 16 over the waves
     const u32 n16 = (m + 15) / 16, per = (n16 + DX_WAVES - 1) / DX_WAVES;
@@ -332,7 +390,7 @@ __device__ inline void matvec_dx_tile(const Tables &T, const TileDesc &d, float 
             if (fast) {
                 a[u] = (in && row_ok) ? ld4(grow + i0) : z4;
                 if (in && col_ok) {
-                    const float *wp = wcol + (size_t)i0 * K;
+                    gl_float *wp = wcol + (size_t)i0 * K;
                     b[u] = make_float4(wp[0], wp[K], wp[2 * (size_t)K], wp[3 * (size_t)K]);
                 } else {
                     b[u] = z4;
@@ -456,14 +514,32 @@ __device__ inline void param_b_tile(const Tables &T, const PTile &pt, float *lds
 // ------------------------------------------------------------------------------------------------
 // backward pull: gradient of every node of a batch from its consumer edges
 // ------------------------------------------------------------------------------------------------
-__device__ inline float edge_term(const Tables &T, u32 kind, u32 goff, u32 voff, i32 a0, i32 a1, u32 own, u32 col)
+// Consumer gradient at gradient-arena offset idx: from the fused chain's LDS copy (index idx + delta)
+// when the descriptor says the consumer ran earlier in the same launch, else from the arena.
+__device__ inline float ldg(const Tables &T, const lds_float *cl, bool from_lds, u32 delta, u32 idx)
+{
+    float v;
+    if (from_lds) v = cl[(u32)(idx + delta)];
+    else v = T.G[idx];
+    return v;
+}
+__device__ inline float4 ldg4(const Tables &T, const lds_float *cl, bool from_lds, u32 delta, u32 idx)
+{
+    float4 v;
+    if (from_lds) v = lds_ld4(cl + (u32)(idx + delta));
+    else v = ld4(T.G + idx);
+    return v;
+}
+
+__device__ inline float edge_term(const Tables &T, const lds_float *cl, bool fl, u32 dl, u32 kind, u32 goff, u32 voff, i32 a0,
+                                  i32 a1, u32 own, u32 col)
 {
     switch (kind) {
-    case EK_PLAIN: return T.G[goff + col];
-    case EK_RANGE: return ((i32)col >= a0 && (i32)col < a1) ? T.G[goff + col - (u32)a0] : 0.f;
-    case EK_MUL: return T.G[goff + col] * T.V[voff + col];
-    case EK_DTANH: { const float y = T.V[voff + col]; return T.G[goff + col] * (1.0f - y * y); }
-    case EK_DSIGM: { const float y = T.V[voff + col]; return T.G[goff + col] * y * (1.0f - y); }
+    case EK_PLAIN: return ldg(T, cl, fl, dl, goff + col);
+    case EK_RANGE: return ((i32)col >= a0 && (i32)col < a1) ? ldg(T, cl, fl, dl, goff + col - (u32)a0) : 0.f;
+    case EK_MUL: return ldg(T, cl, fl, dl, goff + col) * T.V[voff + col];
+    case EK_DTANH: { const float y = T.V[voff + col]; return ldg(T, cl, fl, dl, goff + col) * (1.0f - y * y); }
+    case EK_DSIGM: { const float y = T.V[voff + col]; return ldg(T, cl, fl, dl, goff + col) * y * (1.0f - y); }
     case EK_NLS: {
         const float lse = T.V[voff] + T.V[own + (u32)a0];
         float p = expf(T.V[own + col] - lse);
@@ -476,23 +552,24 @@ __device__ inline float edge_term(const Tables &T, u32 kind, u32 goff, u32 voff,
 }
 
 // four consecutive columns of one uniform edge (all offsets are multiples of 4; EK_NLS never is uniform)
-__device__ inline float4 edge_term4(const Tables &T, u32 kind, u32 goff, u32 voff, i32 a0, i32 a1, u32 own, u32 col)
+__device__ inline float4 edge_term4(const Tables &T, const lds_float *cl, bool fl, u32 dl, u32 kind, u32 goff, u32 voff, i32 a0,
+                                    i32 a1, u32 own, u32 col)
 {
     const float4 z = make_float4(0.f, 0.f, 0.f, 0.f);
     switch (kind) {
-    case EK_PLAIN: return ld4(T.G + goff + col);
-    case EK_RANGE: return ((i32)col >= a0 && (i32)col < a1) ? ld4(T.G + goff + col - (u32)a0) : z;
+    case EK_PLAIN: return ldg4(T, cl, fl, dl, goff + col);
+    case EK_RANGE: return ((i32)col >= a0 && (i32)col < a1) ? ldg4(T, cl, fl, dl, goff + col - (u32)a0) : z;
     case EK_MUL: {
-        const float4 g = ld4(T.G + goff + col), v = ld4(T.V + voff + col);
+        const float4 g = ldg4(T, cl, fl, dl, goff + col), v = ld4(T.V + voff + col);
         return make_float4(g.x * v.x, g.y * v.y, g.z * v.z, g.w * v.w);
     }
     case EK_DTANH: {
-        const float4 g = ld4(T.G + goff + col), y = ld4(T.V + voff + col);
+        const float4 g = ldg4(T, cl, fl, dl, goff + col), y = ld4(T.V + voff + col);
         return make_float4(g.x * (1.0f - y.x * y.x), g.y * (1.0f - y.y * y.y), g.z * (1.0f - y.z * y.z),
                            g.w * (1.0f - y.w * y.w));
     }
     case EK_DSIGM: {
-        const float4 g = ld4(T.G + goff + col), y = ld4(T.V + voff + col);
+        const float4 g = ldg4(T, cl, fl, dl, goff + col), y = ld4(T.V + voff + col);
         return make_float4(g.x * y.x * (1.0f - y.x), g.y * y.y * (1.0f - y.y), g.z * y.z * (1.0f - y.z),
                            g.w * y.w * (1.0f - y.w));
     }
@@ -505,10 +582,11 @@ __device__ inline float4 edge_term4(const Tables &T, u32 kind, u32 goff, u32 vof
     }
 }
 
-__device__ inline void pull_tile(const Tables &T, const PullDesc &d, u32 tid, u32 nthr)
+__device__ inline void pull_tile(const Tables &T, const PullDesc &d, lds_float *cl, u32 tid, u32 nthr)
 {
     const u32 total = d.nrows * d.d;
     const u32 root_pos = T.root_pos[0];
+    const bool keep = (d.lflags & TF_OUT_LDS) != 0;
     if (d.n_uni != PULL_GENERIC && d.vec4) {
         for (u32 x = tid * 4; x < total; x += nthr * 4) {
             const u32 dr = x / d.d, col = x % d.d, row = d.row0 + dr * d.rstride;
@@ -519,11 +597,13 @@ __device__ inline void pull_tile(const Tables &T, const PullDesc &d, u32 tid, u3
             for (u32 j = 0; j < 4; ++j) {
                 if (j < d.n_uni) {
                     const UEdge ue = d.e[j];
-                    const float4 t = edge_term4(T, ue.kind, ue.goff + dr * ue.gs, ue.voff + dr * ue.vs, ue.a0, ue.a1, own, col);
+                    const float4 t = edge_term4(T, cl, (d.lflags & (TF_SRC_LDS << j)) != 0, d.lds_g[j], ue.kind,
+                                                ue.goff + dr * ue.gs, ue.voff + dr * ue.vs, ue.a0, ue.a1, own, col);
                     acc.x += t.x; acc.y += t.y; acc.z += t.z; acc.w += t.w;
                 }
             }
             st4(T.G + own + col, acc);
+            if (keep) lds_st4(cl + (u32)(own + col + d.lds_out), acc);
         }
         return;
     }
@@ -536,7 +616,8 @@ __device__ inline void pull_tile(const Tables &T, const PullDesc &d, u32 tid, u3
             for (u32 j = 0; j < 4; ++j) {
                 if (j < d.n_uni) {
                     const UEdge ue = d.e[j];
-                    acc += edge_term(T, ue.kind, ue.goff + dr * ue.gs, ue.voff + dr * ue.vs, ue.a0, ue.a1, own, col);
+                    acc += edge_term(T, cl, (d.lflags & (TF_SRC_LDS << j)) != 0, d.lds_g[j], ue.kind, ue.goff + dr * ue.gs,
+                                     ue.voff + dr * ue.vs, ue.a0, ue.a1, own, col);
                 }
             }
         } else {
@@ -544,10 +625,11 @@ __device__ inline void pull_tile(const Tables &T, const PullDesc &d, u32 tid, u3
             const u32 q1 = T.succ_off[u + 1];
             for (u32 q = T.succ_off[u]; q < q1; ++q) {
                 const EdgeRec er = T.edges[q];
-                acc += edge_term(T, er.kind, er.goff, er.voff, er.a0, er.a1, own, col);
+                acc += edge_term(T, cl, false, 0u, er.kind, er.goff, er.voff, er.a0, er.a1, own, col);
             }
         }
         T.G[own + col] = acc;
+        if (keep) cl[(u32)(own + col + d.lds_out)] = acc;
     }
 }
 
@@ -562,26 +644,58 @@ __device__ inline void run_fwd_tile(const Tables &T, const TileDesc &d, float *l
     case OP_SQNORM: red_fwd_tile(T, d); break;
     case OP_ADD:
         if (d.arity >= (u32)WIDE_ADD_ARITY) { wide_add_tile(T, d, lds); break; }
-        ew_fwd_tile(T, d, threadIdx.x, WG);
+        ew_fwd_tile(T, d, (lds_float *)lds, threadIdx.x, WG);
         break;
-    default: ew_fwd_tile(T, d, threadIdx.x, WG); break;
+    default: ew_fwd_tile(T, d, (lds_float *)lds, threadIdx.x, WG); break;
     }
 }
 
 constexpr u32 RUN_STAGE = 32;   // descriptors of a fused run staged in LDS at a time
 
+// Barrier between two depths of a fused run.  When every result the next depth needs from this
+// launch is handed on through LDS, only the LDS writes have to be complete (the global copies
+// of the results are not waited for); otherwise the full workgroup barrier orders the global
+// stores and loads as well.
+__device__ inline void run_barrier(bool heavy)
+{
+    if (heavy) __syncthreads();
+    else asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+
+// Copies n descriptors of W words (a multiple of 4) from global memory to LDS.  All loads of a
+// thread are issued before the first is waited for.
+template <u32 W>
+__device__ inline void stage_descriptors(const void *src, void *dst, u32 n)
+{
+    static_assert(W % 4 == 0 && RUN_STAGE * W / 4 <= 2 * WG, "two float4 per thread cover a stage");
+    const uint4 *s4 = reinterpret_cast<const uint4 *>(src);
+    uint4 *d4 = reinterpret_cast<uint4 *>(dst);
+    const u32 n4 = n * (W / 4), x0 = threadIdx.x, x1 = threadIdx.x + WG;
+    uint4 v0 = make_uint4(0, 0, 0, 0), v1 = v0;
+    if (x0 < n4) v0 = s4[x0];
+    if (x1 < n4) v1 = s4[x1];
+    if (x0 < n4) d4[x0] = v0;
+    if (x1 < n4) d4[x1] = v1;
+}
+
 // One launch = one slot.  A work item is a run of tiles that one workgroup executes in order.
 // Runs of one tile (GEMM, reduction and single-batch tiles) keep their descriptor in scalar
 // registers.  Longer runs are fused chains of group-aligned component-wise batches over one block
 // of groups: the descriptors are staged in LDS with one coalesced load, tiles of the same depth
-// are spread over the four waves, and a workgroup barrier separates depths.
-__global__ __launch_bounds__(WG) void k_fwd_step(Tables T, u32 work_lo, u32 work_hi)
+// are spread over the four waves, and a workgroup barrier separates depths.  The LDS array is the
+// GEMM tiles' reduction space or the fused run's copy of its own results, whichever is running.
+// run_len != 0: every work item of the launch has run_len tiles, item w starts at tile
+// tile_lo + (w - work_lo) * run_len and the work records are not read.
+__global__ __launch_bounds__(WG) void k_fwd_step(Tables T, u32 work_lo, u32 work_hi, u32 tile_lo, u32 run_len)
 {
-    __shared__ float lds[LDS_FLOATS];
-    __shared__ TileDesc sdesc[RUN_STAGE];
-    const u32 lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    __shared__ __align__(16) float lds[CHAIN_LDS_FLOATS];
+    __shared__ __align__(16) TileDesc sdesc[RUN_STAGE];
+    static_assert(CHAIN_LDS_FLOATS >= (u32)LDS_FLOATS, "the GEMM reduction space must fit");
+    const u32 lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     for (u32 w = work_lo + blockIdx.x; w < work_hi; w += gridDim.x) {
-        const WorkRec wr = T.works_f[w];
+        WorkRec wr;
+        if (run_len) { wr.first = tile_lo + (w - work_lo) * run_len; wr.len = run_len; }
+        else wr = T.works_f[w];
         if (wr.len == 1) {
             const TileDesc d = T.tiles_f[wr.first];
             run_fwd_tile(T, d, lds);
@@ -590,57 +704,56 @@ __global__ __launch_bounds__(WG) void k_fwd_step(Tables T, u32 work_lo, u32 work
         for (u32 c0 = 0; c0 < wr.len; c0 += RUN_STAGE) {
             const u32 cn = wr.len - c0 < RUN_STAGE ? wr.len - c0 : RUN_STAGE;
             __syncthreads();
-            {   // stage cn descriptors (32 words each)
-                const u32 *src = reinterpret_cast<const u32 *>(T.tiles_f + wr.first + c0);
-                u32 *dst = reinterpret_cast<u32 *>(sdesc);
-                for (u32 x = threadIdx.x; x < cn * (u32)(sizeof(TileDesc) / 4); x += WG) dst[x] = src[x];
-            }
+            stage_descriptors<sizeof(TileDesc) / 4>(T.tiles_f + wr.first + c0, sdesc, cn);
             __syncthreads();
+            const bool heavy = __ballot(lane < cn && (sdesc[lane < cn ? lane : 0].flags & TF_GLOBAL_DEP)) != 0ull;
             u32 i = 0;
             while (i < cn) {
-                u32 glen = sdesc[i].contig >> 16;
+                u32 glen = __builtin_amdgcn_readfirstlane(sdesc[i].contig) >> 16;
                 if (glen == 0) glen = 1;
                 if (glen > cn - i) glen = cn - i;   // a depth group cut by the staging window: still same depth
-                if (glen == 1) ew_fwd_tile(T, sdesc[i], threadIdx.x, WG);
-                else for (u32 t = i + wave; t < i + glen; t += WG / 64) ew_fwd_tile(T, sdesc[t], lane, 64);
+                if (glen == 1) ew_fwd_tile(T, sdesc[i], (lds_float *)lds, threadIdx.x, WG);
+                else for (u32 t = i + wave; t < i + glen; t += WG / 64) ew_fwd_tile(T, sdesc[t], (lds_float *)lds, lane, 64);
                 i += glen;
-                if (i < cn || c0 + cn < wr.len) __syncthreads();
+                if (i < cn) run_barrier(heavy);
             }
         }
+        __syncthreads();   // the LDS copy is free for the next work item
     }
 }
 
-__global__ __launch_bounds__(WG) void k_bwd_pull_step(Tables T, u32 work_lo, u32 work_hi)
+__global__ __launch_bounds__(WG) void k_bwd_pull_step(Tables T, u32 work_lo, u32 work_hi, u32 tile_lo, u32 run_len)
 {
-    __shared__ PullDesc sdesc[RUN_STAGE];
-    const u32 lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    __shared__ __align__(16) float lds[CHAIN_LDS_FLOATS];
+    __shared__ __align__(16) PullDesc sdesc[RUN_STAGE];
+    const u32 lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     for (u32 w = work_lo + blockIdx.x; w < work_hi; w += gridDim.x) {
-        const WorkRec wr = T.works_a[w];
+        WorkRec wr;
+        if (run_len) { wr.first = tile_lo + (w - work_lo) * run_len; wr.len = run_len; }
+        else wr = T.works_a[w];
         if (wr.len == 1) {
             const PullDesc d = T.tiles_a[wr.first];
-            pull_tile(T, d, threadIdx.x, WG);
+            pull_tile(T, d, (lds_float *)lds, threadIdx.x, WG);
             continue;
         }
         for (u32 c0 = 0; c0 < wr.len; c0 += RUN_STAGE) {
             const u32 cn = wr.len - c0 < RUN_STAGE ? wr.len - c0 : RUN_STAGE;
             __syncthreads();
-            {
-                const u32 *src = reinterpret_cast<const u32 *>(T.tiles_a + wr.first + c0);
-                u32 *dst = reinterpret_cast<u32 *>(sdesc);
-                for (u32 x = threadIdx.x; x < cn * (u32)(sizeof(PullDesc) / 4); x += WG) dst[x] = src[x];
-            }
+            stage_descriptors<sizeof(PullDesc) / 4>(T.tiles_a + wr.first + c0, sdesc, cn);
             __syncthreads();
+            const bool heavy = __ballot(lane < cn && (sdesc[lane < cn ? lane : 0].lflags & TF_GLOBAL_DEP)) != 0ull;
             u32 i = 0;
             while (i < cn) {
-                u32 glen = sdesc[i].grp_len;
+                u32 glen = __builtin_amdgcn_readfirstlane(sdesc[i].grp_len);
                 if (glen == 0) glen = 1;
                 if (glen > cn - i) glen = cn - i;
-                if (glen == 1) pull_tile(T, sdesc[i], threadIdx.x, WG);
-                else for (u32 t = i + wave; t < i + glen; t += WG / 64) pull_tile(T, sdesc[t], lane, 64);
+                if (glen == 1) pull_tile(T, sdesc[i], (lds_float *)lds, threadIdx.x, WG);
+                else for (u32 t = i + wave; t < i + glen; t += WG / 64) pull_tile(T, sdesc[t], (lds_float *)lds, lane, 64);
                 i += glen;
-                if (i < cn || c0 + cn < wr.len) __syncthreads();
+                if (i < cn) run_barrier(heavy);
             }
         }
+        __syncthreads();
     }
 }
 
@@ -719,15 +832,20 @@ constexpr u32 GRID_CAP = 4096;
 
 // ---- host side -----------------------------------------------------------------------------------
 
+// run length to pass to a step kernel: the slot's common tiles-per-work-item count, or 0 when its
+// chains differ (the kernel then reads each work item's record)
+static inline u32 slot_run_len(const SlotRec &r) { return r.lmin == ~r.nlmax ? r.lmin : 0u; }
+
 static int launch_forward_steps(ob_ctx *ctx)
 {
     const Tables &T = ctx->T;
     hipStream_t s = ctx->stream;
     const u32 ns = ctx->hdr.n_slots;
     for (u32 st = 0; st < ns; ++st) {
-        const u32 lo = ctx->slot_wf[st], hi = ctx->slot_wf[st + 1];
+        const SlotRec &r = ctx->slots[st];
+        const u32 lo = r.wf, hi = ctx->slots[st + 1].wf;
         if (hi > lo) {
-            hipLaunchKernelGGL(k_fwd_step, dim3(grid_for(hi - lo, GRID_CAP)), dim3(WG), 0, s, T, lo, hi);
+            hipLaunchKernelGGL(k_fwd_step, dim3(grid_for(hi - lo, GRID_CAP)), dim3(WG), 0, s, T, lo, hi, r.tf, slot_run_len(r));
             ++ctx->n_launch_fwd;
         }
     }
@@ -742,14 +860,14 @@ static int launch_backward_steps(ob_ctx *ctx)
     hipLaunchKernelGGL(k_set_root, dim3(1), dim3(1), 0, s, T);
     ++ctx->n_launch_bwd;
     for (u32 st = ns; st-- > 0;) {
-        const u32 alo = ctx->slot_wa[st], ahi = ctx->slot_wa[st + 1];
-        if (ahi > alo) {
-            hipLaunchKernelGGL(k_bwd_pull_step, dim3(grid_for(ahi - alo, GRID_CAP)), dim3(WG), 0, s, T, alo, ahi);
+        const SlotRec &r = ctx->slots[st], &e = ctx->slots[st + 1];
+        if (e.wa > r.wa) {
+            hipLaunchKernelGGL(k_bwd_pull_step, dim3(grid_for(e.wa - r.wa, GRID_CAP)), dim3(WG), 0, s, T, r.wa, e.wa, r.ta,
+                               slot_run_len(r));
             ++ctx->n_launch_bwd;
         }
-        const u32 blo = ctx->slot_tb[st], bhi = ctx->slot_tb[st + 1];
-        if (bhi > blo) {
-            hipLaunchKernelGGL(k_bwd_dx_step, dim3(grid_for(bhi - blo, GRID_CAP)), dim3(DX_WAVES * 64), 0, s, T, blo, bhi);
+        if (e.tb > r.tb) {
+            hipLaunchKernelGGL(k_bwd_dx_step, dim3(grid_for(e.tb - r.tb, GRID_CAP)), dim3(DX_WAVES * 64), 0, s, T, r.tb, e.tb);
             ++ctx->n_launch_bwd;
         }
     }

@@ -24,6 +24,16 @@ constexpr int DXT = 16;               // dX GEMM tile edge (16x16 blocks: its ou
 constexpr int ROWS_PER_RED_TILE = 4;  // rows of one row-reduction tile (one wave per row)
 constexpr int WIDE_ADD_ARITY = 9;     // ADD with at least this many operands reduces per row
 constexpr u32 VAL_ALIGN = 64;         // batch blocks start at multiples of 64 floats (256 B)
+constexpr u32 CHAIN_LDS_FLOATS = 16384;   // LDS a fused chain may use to hand results from one member to the next (64 KB)
+
+// Descriptor flag bits of a tile inside a fused chain (TileDesc::flags, PullDesc::lflags).
+enum : u32 {
+    TF_VEC4 = 1u,            // float4 path allowed
+    TF_ALIGNED = 2u,         // operand rows 16-byte aligned
+    TF_SRC_LDS = 16u,        // << j: operand slot / consumer edge j is read from the chain's LDS copy
+    TF_OUT_LDS = 256u,       // the tile also writes its result to the chain's LDS copy
+    TF_GLOBAL_DEP = 512u     // reads a result of an earlier member of the same chain from global memory
+};
 
 // Kinds of consumer-edge records read by the backward pull (one per graph edge).
 enum : u32 {
@@ -83,8 +93,8 @@ struct TileDesc {
     u32 sdim[4];                     // dimension of operand slot j
     u32 nrows, depth;
     u32 sstride[4];                  // operand row spacing of slot j (elements per tile row step)
-    u32 lds_out, lds_src[4];         // reserved
-    u32 pad;
+    u32 lds_out, lds_src[4];         // LDS index = arena offset + lds_out (own result) / + lds_src[j] (operand slot j),
+    u32 pad;                         // in u32 wrap-around arithmetic; valid with TF_OUT_LDS / TF_SRC_LDS << j
 };
 static_assert(sizeof(TileDesc) == 160, "TileDesc must be 160 bytes");
 
@@ -100,9 +110,11 @@ struct PullDesc {
     u32 depth, row0, n_uni, nrows;   // rows row0 + i * rstride, i < nrows, of the batch, all columns
     UEdge e[4];                      // edge j of the i-th row: e[j] shifted by i * (gs, vs)
     u32 rstride, grp_len;            // grp_len: tiles of the same depth that follow in the run, this one included
-    u32 vec4, pad;                   // vec4: d % 4 == 0 and every offset / stride / range of e[] is a multiple of 4
+    u32 vec4, lflags;                // vec4: d % 4 == 0 and every offset / stride / range of e[] is a multiple of 4
+    u32 lds_out, lds_g[4];           // LDS index = gradient-arena offset + lds_out (own rows) / + lds_g[j] (edge j)
+    u32 pad[3];
 };
-static_assert(sizeof(PullDesc) == 160, "PullDesc must be 160 bytes");
+static_assert(sizeof(PullDesc) == 192, "PullDesc must be 192 bytes");
 
 // A launch chain: batches that run in the same launch slot.  A fused chain holds component-wise
 // batches whose rows fall into G groups (member b has B_b / G consecutive rows per group) such
@@ -111,7 +123,7 @@ static_assert(sizeof(PullDesc) == 160, "PullDesc must be 160 bytes");
 // Every other batch is a chain of its own.
 struct ChainRec {
     u32 first, k;          // members are lorder[first .. first + k)
-    u32 slot, fused;       // fused: component-wise members tiled by group blocks
+    u32 slot, fused;       // fused: component-wise members tiled by group blocks (2: with results handed on through LDS)
     u32 G, Rg, nrb, kt;    // groups, groups per block, number of blocks, tiles per block (sum of rows per group)
 };
 struct CLay {              // scan element of the per-chain launch layout
@@ -122,6 +134,12 @@ struct CLay {              // scan element of the per-chain launch layout
     }
 };
 struct WorkRec { u32 first, len; };   // a workgroup runs tiles [first, first + len) in order
+
+// Per launch slot (entry n_slots closes the ranges): first forward work item, pull work item,
+// dX tile, forward tile and pull tile of the slot, and the smallest / complement of the largest
+// run length (tiles per work item) over the slot's chains.  When the two lengths agree, work
+// item w of the slot runs tiles tf + (w - wf) * len onwards and its WorkRec need not be read.
+struct SlotRec { u32 wf, wa, tb, tf, ta, lmin, nlmax, pad; };
 
 // Static tile of the deferred parameter-gradient kernels (built on the host per parameter set).
 struct PTile { i32 param; i32 i0, j0; i32 pad; };
@@ -165,7 +183,7 @@ struct Tables {
     u32 *val_off; u32 *dx_off; u32 *opnd_off;
     u32 *slot_of; u32 *label_of; u32 *lorder;
     ChainRec *chains; CLay *clay; u32 *chain_of_lpos;
-    u32 *slot_wf; u32 *slot_wa; u32 *slot_tb;     // per launch slot: first forward work, pull work, dX tile
+    SlotRec *slots;
     WorkRec *works_f; WorkRec *works_a;
     TileDesc *tiles_f; PullDesc *tiles_a; TileDesc *tiles_b;
     u32 *root_pos;         // [0] = schedule position of the backward root

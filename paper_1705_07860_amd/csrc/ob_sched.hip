@@ -619,9 +619,20 @@ __global__ void k_chain_recs(Tables T, const u32 *flag, const u32 *flag_excl, CL
             dmax = rm.d > dmax ? rm.d : dmax;
             G = gcd_u32(G, rm.B);
         }
-        u32 kt = 0;
-        for (u32 m = 0; m < k; ++m) kt += T.batches[T.lorder[i + m]].B / G;
-        cr.G = G; cr.Rg = rows_per_block(dmax); cr.nrb = cdiv(G, cr.Rg); cr.kt = cr.fused ? kt : 1u;
+        u32 kt = 0, per_group = 0;   // tiles per block; floats one group of every member takes
+        for (u32 m = 0; m < k; ++m) {
+            const BatchRec &rm = T.batches[T.lorder[i + m]];
+            kt += rm.B / G;
+            per_group += (rm.B / G) * rm.d;
+        }
+        cr.G = G; cr.Rg = rows_per_block(dmax);
+        if (cr.fused && k > 1) {
+            // hand results from member to member through LDS when a block of groups fits (each
+            // member's region is rounded up to 4 floats); fewer groups per block if that is what it takes
+            const u32 fit = (CHAIN_LDS_FLOATS - 3u * k) / per_group;
+            if (fit >= 1) { cr.fused = 2u; if (fit < cr.Rg) cr.Rg = fit; }
+        }
+        cr.nrb = cdiv(G, cr.Rg); cr.kt = cr.fused ? kt : 1u;
         if (cr.fused) {
             L.tf = L.ta = cr.nrb * kt;
             L.wf = L.wa = cr.nrb;
@@ -648,18 +659,33 @@ __global__ void k_clay_zero(CLay *clay_in, u32 n_pad)
     clay_in[i] = L;
 }
 
-// per chain: first work item / dX tile of every launch slot, totals in the header
+// every entry a plan can use (n_slots + 1 <= n + 2) starts out as "no batch here"
+__global__ void k_slot_init(Tables T)
+{
+    const u32 s = blockIdx.x * blockDim.x + threadIdx.x;
+    if (s > T.hdr->n_slots) return;
+    SlotRec r; r.wf = r.wa = r.tb = r.tf = r.ta = r.lmin = r.nlmax = r.pad = 0xffffffffu;
+    T.slots[s] = r;
+}
+
+// per chain: first work item / tile of every launch slot and its run lengths, totals in the header
 __global__ void k_slot_tables(Tables T, const CLay *clay_ex, const CLay *total)
 {
     const u32 c = blockIdx.x * blockDim.x + threadIdx.x;
     const u32 nc = T.hdr->n_chains;
     if (c >= nc) return;
-    const u32 s = T.chains[c].slot;
+    const ChainRec cr = T.chains[c];
+    const u32 s = cr.slot;
     const CLay L = clay_ex[c];
-    if (c == 0 || T.chains[c - 1].slot != s) { T.slot_wf[s] = L.wf; T.slot_wa[s] = L.wa; T.slot_tb[s] = L.tb; }
+    SlotRec &S = T.slots[s];
+    if (c == 0 || T.chains[c - 1].slot != s) { S.wf = L.wf; S.wa = L.wa; S.tb = L.tb; S.tf = L.tf; S.ta = L.ta; }
+    const u32 len = cr.fused ? cr.kt : 1u;
+    atomicMin(&S.lmin, len);
+    atomicMin(&S.nlmax, ~len);
     if (c == nc - 1) {
         const CLay t = *total;
-        T.slot_wf[s + 1] = t.wf; T.slot_wa[s + 1] = t.wa; T.slot_tb[s + 1] = t.tb;
+        SlotRec &E = T.slots[s + 1];
+        E.wf = t.wf; E.wa = t.wa; E.tb = t.tb; E.tf = t.tf; E.ta = t.ta;
         T.hdr->tiles_fwd = t.tf; T.hdr->tiles_pull = t.ta; T.hdr->tiles_dx = t.tb;
         T.hdr->works_fwd = t.wf; T.hdr->works_pull = t.wa;
     }
@@ -672,17 +698,59 @@ __global__ void k_slot_fill(Tables T)
     const u32 s = blockIdx.x * blockDim.x + threadIdx.x;
     if (s >= T.hdr->n_slots) return;
     u32 t = s;
-    while (T.slot_wf[t] == 0xffffffffu) ++t;   // entry n_slots is always set
-    if (t != s) { T.slot_wf[s] = T.slot_wf[t]; T.slot_wa[s] = T.slot_wa[t]; T.slot_tb[s] = T.slot_tb[t]; }
+    while (T.slots[t].wf == 0xffffffffu) ++t;   // entry n_slots is always set
+    if (t != s) {
+        const SlotRec N = T.slots[t];
+        SlotRec &S = T.slots[s];
+        S.wf = N.wf; S.wa = N.wa; S.tb = N.tb; S.tf = N.tf; S.ta = N.ta;
+    }
 }
 
 // ---- tile descriptors ------------------------------------------------------------------------------
 constexpr u32 CONTIG_MAX_ROWS = 32;   // tiles with more rows skip the even-spacing test
 
+// Where a tile of a fused chain sits: chain, member, block of groups [g0, g0 + ng).
+struct ChainCtx { ChainRec cr; u32 m, g0, ng; };
+
+__device__ inline u32 chain_region(const ChainRec &cr, const BatchRec &r) { return (cr.Rg * (r.B / cr.G) * r.d + 3u) & ~3u; }
+
+// For up to four row-offset ranges [lo[j], hi[j]] (first element of the lowest / highest row read
+// through slot j; offsets in the value arena, which the gradient arena mirrors): state 0 = no
+// member of the chain produces these rows, 1 = all of them lie in this block's rows of one member
+// (LDS index = offset + delta[j]), 2 = produced in the chain but not covered by one region.
+__device__ inline void chain_lookup(const Tables &T, const ChainCtx &cc, u32 ns, const u32 *lo, const u32 *hi,
+                                    u32 *state, u32 *delta)
+{
+    for (u32 j = 0; j < ns; ++j) { state[j] = 0; delta[j] = 0; }
+    u32 lds = 0;
+    for (u32 mm = 0; mm < cc.cr.k; ++mm) {
+        const BatchRec &y = T.batches[T.lorder[cc.cr.first + mm]];
+        const u32 mult = y.B / cc.cr.G;
+        const u32 full_lo = y.val_off, full_hi = y.val_off + y.B * y.d;
+        const u32 ch_lo = y.val_off + cc.g0 * mult * y.d, ch_hi = ch_lo + cc.ng * mult * y.d;
+        if (mm != cc.m) {
+            for (u32 j = 0; j < ns; ++j) {
+                if (hi[j] < full_lo || lo[j] >= full_hi) continue;
+                if (state[j] == 0 && cc.cr.fused == 2u && lo[j] >= ch_lo && hi[j] < ch_hi) { state[j] = 1; delta[j] = lds - ch_lo; }
+                else state[j] = 2;
+            }
+        }
+        lds += chain_region(cc.cr, y);
+    }
+}
+
+// LDS index offset of the block's own rows of member cc.m (index = arena offset + result)
+__device__ inline u32 chain_own_delta(const Tables &T, const ChainCtx &cc, const BatchRec &r)
+{
+    u32 lds = 0;
+    for (u32 mm = 0; mm < cc.m; ++mm) lds += chain_region(cc.cr, T.batches[T.lorder[cc.cr.first + mm]]);
+    return lds - (r.val_off + cc.g0 * (r.B / cc.cr.G) * r.d);
+}
+
 // descriptor of a forward or dX tile of batch r.  Component-wise tiles (row_block) cover the rows
 // row0 + i * rstride, i < nrows; the other kinds derive their rows from the tile index t.
 __device__ inline void fill_tile_desc(const Tables &T, const BatchRec &r, u32 t, bool dx, bool row_block, u32 row0,
-                                      u32 nrows, u32 rstride, TileDesc &d)
+                                      u32 nrows, u32 rstride, TileDesc &d, const ChainCtx *cc = nullptr)
 {
     d.op = r.op; d.B = r.B; d.d = r.d; d.arity = r.arity;
     d.pos0 = r.pos0; d.val_off = r.val_off; d.dx_off = r.dx_off; d.k = r.k;
@@ -695,7 +763,7 @@ __device__ inline void fill_tile_desc(const Tables &T, const BatchRec &r, u32 t,
     d.opnd = r.opnd; d.indim = r.indim; d.flags = r.vec4; d.t = t;
     d.contig = 0; d.row0 = row0; d.nrows = nrows; d.depth = r.step;
     for (int j = 0; j < 4; ++j) { d.base[j] = 0; d.sdim[j] = 0; d.sstride[j] = 0; }
-    if (dx || r.arity == 0) return;
+    if (dx || (!row_block && r.arity == 0)) return;
     if (!row_block) {
         u32 r_lo, r_hi;
         if (r.op == OP_MATVEC) {
@@ -710,29 +778,53 @@ __device__ inline void fill_tile_desc(const Tables &T, const BatchRec &r, u32 t,
         d.row0 = row0 = r_lo; d.nrows = nrows = r_hi - r_lo + 1; d.rstride = rstride = 1;
     }
     const u32 ns = r.arity < 4 ? r.arity : 4;
+    u32 lo[4], hi[4];
     for (u32 j = 0; j < ns; ++j) {
         const u32 *op = T.opnd_off + r.opnd + j * r.B;
         const u32 base = op[row0];
         d.base[j] = base; d.sdim[j] = T.b_indim[r.indim + j];
         bool ok = nrows <= CONTIG_MAX_ROWS;
         u32 ss = 0;
+        lo[j] = hi[j] = base;
         if (ok && nrows > 1) {
             ss = op[row0 + rstride] - base;
-            for (u32 i = 2; ok && i < nrows; ++i) ok = op[row0 + i * rstride] == base + i * ss;
+            for (u32 i = 1; i < nrows; ++i) {
+                const u32 o = op[row0 + i * rstride];
+                ok = ok && o == base + i * ss;
+                lo[j] = o < lo[j] ? o : lo[j]; hi[j] = o > hi[j] ? o : hi[j];
+            }
         }
         d.sstride[j] = ss;
         if (ok) d.contig |= 1u << j;
+    }
+    if (!cc) return;
+    // tile of a fused chain: which operands come from the chain's LDS copy, and whether any
+    // operand produced earlier in the same launch still has to come from global memory
+    if (cc->cr.fused != 2u || nrows > CONTIG_MAX_ROWS || r.arity > 4) { d.flags |= TF_GLOBAL_DEP; }
+    if (cc->cr.fused != 2u) return;
+    d.lds_out = chain_own_delta(T, *cc, r);
+    d.flags |= TF_OUT_LDS;
+    if (d.lds_out & 3u) d.flags &= ~(u32)TF_VEC4;   // (never with d % 4 == 0: regions and block rows start at multiples of 4)
+    if (nrows > CONTIG_MAX_ROWS) return;
+    u32 state[4], delta[4];
+    chain_lookup(T, *cc, ns, lo, hi, state, delta);
+    for (u32 j = 0; j < ns; ++j) {
+        if (state[j] == 1 && (!(d.flags & TF_VEC4) || (delta[j] & 3u) == 0)) { d.flags |= TF_SRC_LDS << j; d.lds_src[j] = delta[j]; }
+        else if (state[j] != 0) d.flags |= TF_GLOBAL_DEP;
     }
 }
 
 constexpr u32 PULL_MAX_ROWS = 16;
 
-__device__ inline void fill_pull_desc(const Tables &T, const BatchRec &r, u32 row0, u32 nrows, u32 rstride, PullDesc &d)
+__device__ inline void fill_pull_base(const Tables &T, const BatchRec &r, u32 row0, u32 nrows, u32 rstride, PullDesc &d)
 {
+    d.lflags = 0; d.lds_out = 0;
+    for (int j = 0; j < 4; ++j) d.lds_g[j] = 0;
+    d.pad[0] = d.pad[1] = d.pad[2] = 0;
     d.pos0 = r.pos0; d.B = r.B; d.d = r.d; d.val_off = r.val_off;
     d.depth = r.step; d.row0 = row0; d.nrows = nrows; d.n_uni = PULL_GENERIC; d.rstride = rstride;
     for (int j = 0; j < 4; ++j) { UEdge z; z.kind = 0; z.goff = z.voff = z.gs = z.vs = 0; z.a0 = z.a1 = 0; d.e[j] = z; }
-    d.grp_len = 1; d.vec4 = 0; d.pad = 0;
+    d.grp_len = 1; d.vec4 = 0;
     if (nrows > PULL_MAX_ROWS) return;
     const u32 u0 = T.order[r.pos0 + row0];
     const u32 q0 = T.succ_off[u0];
@@ -768,6 +860,30 @@ __device__ inline void fill_pull_desc(const Tables &T, const BatchRec &r, u32 ro
         if (ue.kind == EK_RANGE && (((u32)ue.a0 | (u32)ue.a1) & 3u)) vec = false;
     }
     d.vec4 = vec ? 1u : 0u;
+}
+
+__device__ inline void fill_pull_desc(const Tables &T, const BatchRec &r, u32 row0, u32 nrows, u32 rstride, PullDesc &d,
+                                      const ChainCtx *cc = nullptr)
+{
+    fill_pull_base(T, r, row0, nrows, rstride, d);
+    if (!cc) return;
+    // tile of a fused chain: consumer gradients computed earlier in the same launch come from the
+    // chain's LDS copy where the whole tile finds them in one member's region
+    if (cc->cr.fused != 2u) { d.lflags = TF_GLOBAL_DEP; return; }
+    d.lds_out = chain_own_delta(T, *cc, r);
+    d.lflags = TF_OUT_LDS;
+    if (d.lds_out & 3u) d.vec4 = 0;
+    if (d.n_uni == PULL_GENERIC) { d.lflags |= TF_GLOBAL_DEP; return; }
+    u32 lo[4], hi[4], state[4], delta[4];
+    for (u32 j = 0; j < d.n_uni; ++j) {
+        const u32 a = d.e[j].goff, b = d.e[j].goff + (nrows - 1) * d.e[j].gs;
+        lo[j] = a < b ? a : b; hi[j] = a < b ? b : a;
+    }
+    chain_lookup(T, *cc, d.n_uni, lo, hi, state, delta);
+    for (u32 j = 0; j < d.n_uni; ++j) {
+        if (state[j] == 1 && (!d.vec4 || (delta[j] & 3u) == 0)) { d.lflags |= TF_SRC_LDS << j; d.lds_g[j] = delta[j]; }
+        else if (state[j] != 0) d.lflags |= TF_GLOBAL_DEP;
+    }
 }
 
 // chain that owns global tile / work index x of list `which` (0 fwd tiles, 1 pull tiles, 2 dX tiles,
@@ -852,14 +968,16 @@ __global__ void k_tiles(Tables T, const CLay *clay_ex, const CLay *total, u32 ca
                         }
                     }
                 }
+                ChainCtx cc; cc.cr = cr; cc.m = m; cc.g0 = g0; cc.ng = ng;
+                const ChainCtx *pcc = (cr.fused && cr.kt > 1) ? &cc : nullptr;
                 if (which == 1) {
                     PullDesc d;
-                    fill_pull_desc(T, r, row0, ng, mult, d);
+                    fill_pull_desc(T, r, row0, ng, mult, d, pcc);
                     d.grp_len = glen;
                     T.tiles_a[x] = d;
                 } else {
                     TileDesc d;
-                    fill_tile_desc(T, r, xx, false, true, row0, ng, mult, d);
+                    fill_tile_desc(T, r, xx, false, true, row0, ng, mult, d, pcc);
                     d.contig |= (glen > 0xffffu ? 0xffffu : glen) << 16;
                     T.tiles_f[x] = d;
                 }
@@ -945,7 +1063,7 @@ inline int bit_width_u32(u32 x) { int b = 0; while (x) { ++b; x >>= 1; } return 
         }                                                                                               \
     } while (0)
 
-constexpr size_t SLOT_WINDOW = 8192;   // per-slot table entries read back together with the header
+constexpr size_t SLOT_WINDOW = 2048;   // per-slot table entries read back together with the header
 
 // First half of scheduling: allocates the scheduler tables for n nodes / E edges in the arena and
 // queues every stage on the schedule stream, ending with the device-to-host copies of the header
@@ -990,11 +1108,10 @@ int sched_enqueue(ob_ctx *ctx)
     A(T.val_off, u32, n); A(T.dx_off, u32, n); A(T.opnd_off, u32, E + 1);
     A(T.slot_of, u32, n); A(T.label_of, u32, n);
     A(T.lorder, u32, n); A(T.chains, ChainRec, n); A(T.clay, CLay, n); A(T.chain_of_lpos, u32, n);
-    // slot_wf | slot_wa | slot_tb, adjacent; moving matrix products to odd slots can at most double
-    // the number of slots over the number of depth levels
+    // moving matrix products to odd slots can at most double the number of slots over the number
+    // of depth levels
     const size_t slot_cap = 2 * (size_t)n + 4;
-    A(T.slot_wf, u32, 3 * slot_cap);
-    T.slot_wa = T.slot_wf + slot_cap; T.slot_tb = T.slot_wa + slot_cap;
+    A(T.slots, SlotRec, slot_cap);
     A(T.works_f, WorkRec, cap_f); A(T.works_a, WorkRec, cap_a);
     A(T.tiles_f, TileDesc, cap_f); A(T.tiles_a, PullDesc, cap_a); A(T.tiles_b, TileDesc, cap_b);
     A(T.root_pos, u32, 64);
@@ -1103,14 +1220,9 @@ int sched_enqueue(ob_ctx *ctx)
     K(k_chain_recs, n, T, cflag, cflag_excl, clay_in, n);
     HIP_TRY(ctx, prim_scan_clay(clay_in, T.clay, n, clay_total, ctx->scratch, s));
     ctx->n_launch_sched += 6;
-    const size_t slot_used = fuse ? (slot_cap < 2 * (size_t)SLOT_MAX_NB + 4 ? slot_cap : 2 * (size_t)SLOT_MAX_NB + 4) : 0;
-    if (fuse) {   // only the first slot_used entries of each table can be touched by a fused plan
-        HIP_TRY(ctx, prim_fill_u32(T.slot_wf, 0xffffffffu, slot_used, s));
-        HIP_TRY(ctx, prim_fill_u32(T.slot_wa, 0xffffffffu, slot_used, s));
-        HIP_TRY(ctx, prim_fill_u32(T.slot_tb, 0xffffffffu, slot_used, s));
-    }
+    K(k_slot_init, (size_t)n + 2, T);
     K(k_slot_tables, n, T, T.clay, clay_total);
-    if (fuse) K(k_slot_fill, slot_used, T);
+    if (fuse) K(k_slot_fill, (size_t)n + 2, T);
     hipLaunchKernelGGL(k_tiles, dim3(1024), dim3(TPB), 0, s, T, T.clay, clay_total, (u32)cap_f, (u32)cap_a,
                        (u32)cap_b);
     ++ctx->n_launch_sched;
@@ -1128,9 +1240,9 @@ int sched_enqueue(ob_ctx *ctx)
     HIP_TRY(ctx, hipGetLastError());
 
     // ---- queue the read-back of the header and of a first window of the per-slot tables ----
-    // pinned layout: [header 256 B][slot_wf window][slot_wa window][slot_tb window]
+    // pinned layout: [header 256 B][first hdr_window entries of the slot table]
     ctx->hdr_window = (u32)(slot_cap < SLOT_WINDOW ? slot_cap : SLOT_WINDOW);
-    const size_t need = 256 + (size_t)ctx->hdr_window * 12;
+    const size_t need = 256 + (size_t)ctx->hdr_window * sizeof(SlotRec);
     if (need > ctx->hdr_pinned_bytes) {
         if (ctx->hdr_pinned) HIP_TRY(ctx, hipHostFree(ctx->hdr_pinned));
         ctx->hdr_pinned = nullptr;
@@ -1138,11 +1250,8 @@ int sched_enqueue(ob_ctx *ctx)
         HIP_TRY(ctx, hipHostMalloc(&ctx->hdr_pinned, ctx->hdr_pinned_bytes, hipHostMallocDefault));
     }
     char *hp = (char *)ctx->hdr_pinned;
-    const size_t wb = (size_t)ctx->hdr_window * 4;
     HIP_TRY(ctx, hipMemcpyAsync(hp, T.hdr, sizeof(SchedHeader), hipMemcpyDeviceToHost, s));
-    HIP_TRY(ctx, hipMemcpyAsync(hp + 256, T.slot_wf, wb, hipMemcpyDeviceToHost, s));
-    HIP_TRY(ctx, hipMemcpyAsync(hp + 256 + wb, T.slot_wa, wb, hipMemcpyDeviceToHost, s));
-    HIP_TRY(ctx, hipMemcpyAsync(hp + 256 + 2 * wb, T.slot_tb, wb, hipMemcpyDeviceToHost, s));
+    HIP_TRY(ctx, hipMemcpyAsync(hp + 256, T.slots, (size_t)ctx->hdr_window * sizeof(SlotRec), hipMemcpyDeviceToHost, s));
     ctx->n_items_sched = n_items;
     return 0;
 }
@@ -1165,16 +1274,11 @@ int sched_finish(ob_ctx *ctx)
     if (ctx->hdr.err & ERR_OVERFLOW) return ctx_fail(ctx, -5, "value arena exceeds 2^32 elements");
     const size_t words = (size_t)ctx->hdr.n_slots + 1;
     if (words <= ctx->hdr_window) {
-        const size_t wb = (size_t)ctx->hdr_window * 4;
-        const u32 *wf = (const u32 *)(hp + 256), *wa = (const u32 *)(hp + 256 + wb), *tb = (const u32 *)(hp + 256 + 2 * wb);
-        ctx->slot_wf.assign(wf, wf + words);
-        ctx->slot_wa.assign(wa, wa + words);
-        ctx->slot_tb.assign(tb, tb + words);
-    } else {   // more launch slots than the window (unbatched mode): plain copies
-        ctx->slot_wf.resize(words); ctx->slot_wa.resize(words); ctx->slot_tb.resize(words);
-        HIP_TRY(ctx, hipMemcpyAsync(ctx->slot_wf.data(), T.slot_wf, words * 4, hipMemcpyDeviceToHost, s));
-        HIP_TRY(ctx, hipMemcpyAsync(ctx->slot_wa.data(), T.slot_wa, words * 4, hipMemcpyDeviceToHost, s));
-        HIP_TRY(ctx, hipMemcpyAsync(ctx->slot_tb.data(), T.slot_tb, words * 4, hipMemcpyDeviceToHost, s));
+        const SlotRec *sr = (const SlotRec *)(hp + 256);
+        ctx->slots.assign(sr, sr + words);
+    } else {   // more launch slots than the window (unbatched mode): a plain copy
+        ctx->slots.resize(words);
+        HIP_TRY(ctx, hipMemcpyAsync(ctx->slots.data(), T.slots, words * sizeof(SlotRec), hipMemcpyDeviceToHost, s));
         HIP_TRY(ctx, hipStreamSynchronize(s));
     }
 
