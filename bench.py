@@ -77,7 +77,7 @@ def stored_traffic(args, kernel):
     runs, FETCH_SIZE and WRITE_SIZE, scaled by a plain copy of known size).  Counters cannot be
     read inside a timing run, so the figure is the stored one and only applies to the default
     launch configuration of the workload it was taken on; otherwise null."""
-    if args.launch != "stream" or args.no_fusion:
+    if args.launch != "stream" or args.no_fusion or args.placement != "late":
         return None
     path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles", f"{args.workload}_bydepth_hbm_traffic.json")
     try:
@@ -99,6 +99,8 @@ def main():
     ap.add_argument("--no-pipeline", action="store_true",
                     help="schedule and execute each step back to back on one stream (no overlap between steps)")
     ap.add_argument("--no-fusion", action="store_true", help="one launch per depth level")
+    ap.add_argument("--placement", default="late", choices=["early", "late"],
+                    help="fused plans launch a batch as early as its operands / as late as its consumers allow")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
     ap.add_argument("--no-nobatch", action="store_true", help="skip the unbatched GPU leg")
     ap.add_argument("--cpu-samples", type=int, default=4)
@@ -137,7 +139,7 @@ def main():
         if j == 0:
             c = ob.Context(arena_bytes=1 << 30, stream=stream, mode=ob.OB_BYDEPTH, launch=launch,
                            sched_stream=sched_stream)
-            c.set_fusion(not args.no_fusion)
+            c.set_fusion(0 if args.no_fusion else (2 if args.placement == "late" else 1))
             c.params_create(params)
             c.param_grad_zero()
         else:
@@ -282,7 +284,7 @@ def main():
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": f"config {cfg['index']}: {args.workload} (BASELINE.json configs[{cfg['index'] - 1}])",
                    "instances_per_step": graphs[0].n_instances, "mode": "bydepth", "launch": args.launch,
-                   "fusion": not args.no_fusion,
+                   "fusion": not args.no_fusion, "placement": args.placement,
                    "pipeline": "scheduling of step i+1 overlaps execution of step i (second stream)" if pipeline
                    else "none (schedule, forward, backward back to back)",
                    "pool": pool, "nodes_per_step": round(n_nodes / args.steps, 1)},

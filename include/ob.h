@@ -93,7 +93,10 @@ int ob_ctx_set_launch(ob_ctx *ctx, int launch);
 /* Launch fusion (default on, OB_BYDEPTH only): component-wise batches whose operands are
  * row-aligned with their producer batch run inside the producer's launch (Section 3.3: inputs
  * that are already contiguous and in order are used as they are), so a chain of such batches
- * costs one launch instead of one per depth level.  Batches and their order do not change. */
+ * costs one launch instead of one per depth level.  Batches and their order do not change.
+ * on: 0 = one launch per depth level; 1 = fused, every batch launched as early as its operands
+ * allow; 2 = fused, every batch launched as late as its consumers allow (batches off the longest
+ * dependency path then share the launches next to their consumers).  Other values: OB_E_ARG. */
 int ob_ctx_set_fusion(ob_ctx *ctx, int on);
 /* Library-owned message for the last failing call on this context (valid until the next
  * call); ctx may be NULL for errors of ob_ctx_create. */

@@ -181,8 +181,9 @@ class Context:
     def set_launch(self, launch: int):
         self._ck(self.L.ob_ctx_set_launch(self.h, launch))
 
-    def set_fusion(self, on: bool):
-        self._ck(self.L.ob_ctx_set_fusion(self.h, 1 if on else 0))
+    def set_fusion(self, on):
+        """0 / False: one launch per depth level; 1 / True: fused, early placement; 2: fused, late placement."""
+        self._ck(self.L.ob_ctx_set_fusion(self.h, int(on)))
 
     # -- parameters
     def param_create(self, mat: np.ndarray) -> int:

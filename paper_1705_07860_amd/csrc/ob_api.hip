@@ -107,7 +107,8 @@ int ob_ctx_set_schedule_stream(ob_ctx *ctx, void *hip_stream)
 int ob_ctx_set_fusion(ob_ctx *ctx, int on)
 {
     CHECK_CTX(ctx);
-    ctx->fuse = on ? 1 : 0;
+    if (on < 0 || on > 2) return ctx_fail(ctx, OB_E_ARG, "fusion level %d (0, 1 or 2)", on);
+    ctx->fuse = on;
     return OB_OK;
 }
 

@@ -499,15 +499,19 @@ __global__ void k_bedges(Tables T, u32 *bset, u32 *blist)
     atomicAdd(&T.hdr->n_bedges, BLIST_MAX);   // table full: forces the unfused plan
 }
 
-// One workgroup.  Launch slot of a batch = longest path over the batch dependencies, where a
-// fusable edge costs 0 and any other edge one launch boundary: relaxed to a fixed point over the
-// distinct dependencies held in LDS.  Batches joined by fusable edges inside one slot then get a
-// common chain label (the smallest batch id of the chain).
+// One workgroup.  Over the batch dependencies, where a fusable edge costs 0 and any other edge one
+// launch boundary, relaxed to a fixed point over the distinct dependencies held in LDS:
+// head(b) = longest path from any source to b, tail(b) = longest path from b to any sink.  The
+// plan has L + 1 slots, L = max head.  fuse == 1 places a batch as early as possible (slot =
+// head), fuse == 2 as late as possible (slot = L - tail): batches off the critical path then
+// gather in the slots next to their consumers instead of trailing the recurrence one small
+// launch at a time.  Batches joined by fusable edges inside one slot then get a common chain
+// label (the smallest batch id of the chain).
 constexpr int SLOT_THREADS = 1024;
 __global__ __launch_bounds__(SLOT_THREADS) void k_slots(Tables T, int fuse, const u32 *blist)
 {
     __shared__ u32 s_slot[SLOT_MAX_NB];
-    __shared__ u32 s_label[SLOT_MAX_NB];
+    __shared__ u32 s_label[SLOT_MAX_NB];   // tail lengths first, chain labels afterwards
     __shared__ u32 s_edge[BLIST_MAX];
     __shared__ u32 s_changed;
     const u32 nb = T.hdr->n_batches;
@@ -518,7 +522,7 @@ __global__ __launch_bounds__(SLOT_THREADS) void k_slots(Tables T, int fuse, cons
         if (tid == 0) { T.hdr->n_slots = T.hdr->n_steps; T.hdr->slot_sweeps = 0; T.hdr->p0 = 1; }
         return;
     }
-    for (u32 b = tid; b < nb; b += SLOT_THREADS) { s_slot[b] = 0; s_label[b] = b; }
+    for (u32 b = tid; b < nb; b += SLOT_THREADS) { s_slot[b] = 0; s_label[b] = 0; }
     for (u32 e = tid; e < ne; e += SLOT_THREADS) s_edge[e] = blist[e] - 1u;
     u32 sweeps = 0;
     while (true) {
@@ -529,12 +533,30 @@ __global__ __launch_bounds__(SLOT_THREADS) void k_slots(Tables T, int fuse, cons
             const u32 c = k >> 13, y = (k >> 1) & 0xfffu;
             const u32 want = s_slot[y] + (k & 1u);
             if (want > s_slot[c]) { atomicMax(&s_slot[c], want); s_changed = 1; }
+            const u32 tw = s_label[c] + (k & 1u);
+            if (tw > s_label[y]) { atomicMax(&s_label[y], tw); s_changed = 1; }
         }
         __syncthreads();
         ++sweeps;
         const u32 ch = s_changed;
         __syncthreads();
         if (!ch || sweeps > nb + 1) break;
+    }
+    {   // number of slots; late placement; labels start as the batch's own id
+        u32 mx = 0;
+        for (u32 b = tid; b < nb; b += SLOT_THREADS) mx = s_slot[b] > mx ? s_slot[b] : mx;
+        if (tid == 0) s_changed = 0;
+        __syncthreads();
+        atomicMax(&s_changed, mx);
+        __syncthreads();
+        const u32 L = s_changed;
+        __syncthreads();
+        for (u32 b = tid; b < nb; b += SLOT_THREADS) {
+            if (fuse == 2) s_slot[b] = L - s_label[b];
+            s_label[b] = b;
+        }
+        if (tid == 0) T.hdr->n_slots = L + 1;
+        __syncthreads();
     }
     while (true) {
         if (tid == 0) s_changed = 0;
@@ -558,16 +580,8 @@ __global__ __launch_bounds__(SLOT_THREADS) void k_slots(Tables T, int fuse, cons
         __syncthreads();
         if (!ch || sweeps > 3 * nb + 3) break;
     }
-    u32 mx = 0;
-    for (u32 b = tid; b < nb; b += SLOT_THREADS) {
-        T.slot_of[b] = s_slot[b]; T.label_of[b] = s_label[b];
-        mx = s_slot[b] > mx ? s_slot[b] : mx;
-    }
-    if (tid == 0) s_changed = 0;
-    __syncthreads();
-    atomicMax(&s_changed, mx);
-    __syncthreads();
-    if (tid == 0) { T.hdr->n_slots = s_changed + 1; T.hdr->slot_sweeps = sweeps; }
+    for (u32 b = tid; b < nb; b += SLOT_THREADS) { T.slot_of[b] = s_slot[b]; T.label_of[b] = s_label[b]; }
+    if (tid == 0) T.hdr->slot_sweeps = sweeps;
 }
 
 __global__ void k_launch_keys(Tables T, u64 *keys, u32 *vals, u32 n_pad)
@@ -1205,7 +1219,7 @@ int sched_enqueue(ob_ctx *ctx)
         HIP_TRY(ctx, hipMemsetAsync(bset, 0, (size_t)BSET_SIZE * 4, s));
         K(k_bedges, E, T, bset, blist);
     }
-    hipLaunchKernelGGL(k_slots, dim3(1), dim3(SLOT_THREADS), 0, s, T, (fuse && E > 0) ? 1 : 0, blist);
+    hipLaunchKernelGGL(k_slots, dim3(1), dim3(SLOT_THREADS), 0, s, T, (fuse && E > 0) ? ctx->fuse : 0, blist);
     ++ctx->n_launch_sched;
     K(k_launch_keys, n, T, ctx->key_a, ctx->val_a, n);
     if (fuse && E > 0) {

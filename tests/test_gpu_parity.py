@@ -21,10 +21,10 @@ def say(msg):
     sys.stdout.flush()
 
 
-def run_gpu(p, g, mode, launch=0, arena=2 << 30, n_nodes=None, fuse=True):
+def run_gpu(p, g, mode, launch=0, arena=2 << 30, n_nodes=None, fuse=2):
     from paper_1705_07860_amd import binding as ob
     c = ob.Context(arena_bytes=arena, mode=mode, launch=launch)
-    c.set_fusion(fuse)
+    c.set_fusion(int(fuse))
     pids = c.params_create(p)
     assert pids == list(range(len(p.mats)))
     c.param_grad_zero()
@@ -137,6 +137,30 @@ def test_without_launch_fusion(name, workload_cache):
     assert st["n_slots"] == st["n_steps"]
     check_against_oracle(c, p, g, o, root, what=f"{name}/nofuse")
     c.close()
+
+
+@pytest.mark.parametrize("name", ["rnn", "tagger_char", "tree"])
+def test_early_placement_and_launch_plan_invariants(name, workload_cache):
+    """Fusion level 1 (every batch launched as early as possible) and level 2 (as late as possible)
+    keep the schedule, give the same numbers (so no batch ran before a producer), and produce
+    launch plans in which every batch appears in exactly one chain and the slots are ordered."""
+    from paper_1705_07860_amd import binding as ob
+    p, g, o = workload_cache(name)
+    rbo, rids, rbd = S.by_depth(g)
+    slots = {}
+    for level in (1, 2):
+        c, root = run_gpu(p, g, ob.OB_BYDEPTH, fuse=level)
+        bo, ids, bd, _ = c.schedule_read()
+        assert np.array_equal(bo, rbo) and np.array_equal(ids, rids) and np.array_equal(bd, rbd)
+        ch = c.debug_read(ob.OB_DBG_CHAINS).reshape(-1, 8)
+        st = c.stats()
+        assert int(ch[:, 1].sum()) == st["n_batches"]                      # members partition the batches
+        assert np.array_equal(ch[:, 0], np.concatenate([[0], np.cumsum(ch[:, 1])[:-1]]))
+        assert np.all(np.diff(ch[:, 2].astype(np.int64)) >= 0) and int(ch[-1, 2]) == st["n_slots"] - 1
+        slots[level] = st["n_slots"]
+        check_against_oracle(c, p, g, o, root, what=f"{name}/placement{level}")
+        c.close()
+    assert slots[1] == slots[2]     # both placements keep the longest dependency path
 
 
 @pytest.mark.parametrize("name", ["tagger", "tree"])
