@@ -220,7 +220,7 @@ def main():
                     frac=round(achieved / HBM_PEAK_GBS, 5), traffic=stored_traffic(args, "k_fwd_step"),
                     launches=launches["n_launch_fwd"], avg_launch_us=round(fwd_ms * 1e3 / n_fwd, 3),
                     algorithmic_bytes_per_launch=round(cost["fwd_bytes"] / n_fwd, 1),
-                    backward=dict(kernel="k_bwd_pull_step+k_bwd_dx_step",
+                    backward=dict(kernel="k_bwd_step",
                                   achieved=round(cost["bwd_bytes"] / (bwd_ms * 1e-3) / 1e9, 2),
                                   launches=launches["n_launch_bwd"], avg_launch_us=round(bwd_ms * 1e3 / n_bwd, 3),
                                   algorithmic_bytes_per_launch=round(cost["bwd_bytes"] / n_bwd, 1)),

@@ -371,7 +371,11 @@ __device__ inline void matvec_dx_tile(const Tables &T, const TileDesc &d, float 
     const u32 r0 = (d.t / ntn) * DXT, c0 = (d.t % ntn) * DXT;
     const u32 row = r0 + l16, col = c0 + l16;
     const bool row_ok = row < d.B, col_ok = col < K;
-    const float *grow = T.G + d.val_off + (size_t)(row_ok ? row : 0u) * m;
+    // this lane's gradient row: the batch's own block, or (TF_G_ALIAS) the one consumer's row as it is
+    const u32 grow_row = row_ok ? row : r0;
+    const float *grow = T.G + ((d.flags & TF_G_ALIAS) ? ((d.contig & 1u) ? d.base[0] + (grow_row - r0) * d.sstride[0]
+                                                                             : T.dx_gsrc[d.pos0 + grow_row])
+                                                        : d.val_off + grow_row * m);
     gl_float *wcol = as_global(d.w) + (col_ok ? col : 0u);
     const bool fast = (m & 3u) == 0;
     // split [0, m) in units of 16 over the waves
@@ -664,13 +668,13 @@ __device__ inline void run_barrier(bool heavy)
 
 // Copies n descriptors of W words (a multiple of 4) from global memory to LDS.  All loads of a
 // thread are issued before the first is waited for.
-template <u32 W>
+template <u32 W, u32 NT>
 __device__ inline void stage_descriptors(const void *src, void *dst, u32 n)
 {
-    static_assert(W % 4 == 0 && RUN_STAGE * W / 4 <= 2 * WG, "two float4 per thread cover a stage");
+    static_assert(W % 4 == 0 && RUN_STAGE * W / 4 <= 2 * NT, "two float4 per thread cover a stage");
     const uint4 *s4 = reinterpret_cast<const uint4 *>(src);
     uint4 *d4 = reinterpret_cast<uint4 *>(dst);
-    const u32 n4 = n * (W / 4), x0 = threadIdx.x, x1 = threadIdx.x + WG;
+    const u32 n4 = n * (W / 4), x0 = threadIdx.x, x1 = threadIdx.x + NT;
     uint4 v0 = make_uint4(0, 0, 0, 0), v1 = v0;
     if (x0 < n4) v0 = s4[x0];
     if (x1 < n4) v1 = s4[x1];
@@ -704,7 +708,7 @@ __global__ __launch_bounds__(WG) void k_fwd_step(Tables T, u32 work_lo, u32 work
         for (u32 c0 = 0; c0 < wr.len; c0 += RUN_STAGE) {
             const u32 cn = wr.len - c0 < RUN_STAGE ? wr.len - c0 : RUN_STAGE;
             __syncthreads();
-            stage_descriptors<sizeof(TileDesc) / 4>(T.tiles_f + wr.first + c0, sdesc, cn);
+            stage_descriptors<sizeof(TileDesc) / 4, WG>(T.tiles_f + wr.first + c0, sdesc, cn);
             __syncthreads();
             const bool heavy = __ballot(lane < cn && (sdesc[lane < cn ? lane : 0].flags & TF_GLOBAL_DEP)) != 0ull;
             u32 i = 0;
@@ -722,24 +726,37 @@ __global__ __launch_bounds__(WG) void k_fwd_step(Tables T, u32 work_lo, u32 work
     }
 }
 
-__global__ __launch_bounds__(WG) void k_bwd_pull_step(Tables T, u32 work_lo, u32 work_hi, u32 tile_lo, u32 run_len)
+// One backward launch: the slot's dX tiles (blocks first: they run longest) and its pull work
+// items.  Both kinds may share a launch only when no dX tile reads a gradient that this slot's
+// pull computes; otherwise the host launches the pull range and the dX range one after the other.
+constexpr int BWD_THREADS = DX_WAVES * 64;
+__global__ __launch_bounds__(BWD_THREADS) void k_bwd_step(Tables T, u32 work_lo, u32 work_hi, u32 tile_lo, u32 run_len,
+                                                          u32 dx_lo, u32 dx_hi)
 {
     __shared__ __align__(16) float lds[CHAIN_LDS_FLOATS];
     __shared__ __align__(16) PullDesc sdesc[RUN_STAGE];
+    static_assert(CHAIN_LDS_FLOATS >= (u32)(DX_WAVES * 4 * 64), "the dX reduction space must fit");
     const u32 lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    for (u32 w = work_lo + blockIdx.x; w < work_hi; w += gridDim.x) {
+    const u32 n_dx = dx_hi - dx_lo, n_items = n_dx + (work_hi - work_lo);
+    for (u32 item = blockIdx.x; item < n_items; item += gridDim.x) {
+        if (item < n_dx) {
+            const TileDesc d = T.tiles_b[dx_lo + item];
+            matvec_dx_tile(T, d, lds);
+            continue;
+        }
+        const u32 w = work_lo + (item - n_dx);
         WorkRec wr;
         if (run_len) { wr.first = tile_lo + (w - work_lo) * run_len; wr.len = run_len; }
         else wr = T.works_a[w];
         if (wr.len == 1) {
             const PullDesc d = T.tiles_a[wr.first];
-            pull_tile(T, d, (lds_float *)lds, threadIdx.x, WG);
+            pull_tile(T, d, (lds_float *)lds, threadIdx.x, BWD_THREADS);
             continue;
         }
         for (u32 c0 = 0; c0 < wr.len; c0 += RUN_STAGE) {
             const u32 cn = wr.len - c0 < RUN_STAGE ? wr.len - c0 : RUN_STAGE;
             __syncthreads();
-            stage_descriptors<sizeof(PullDesc) / 4>(T.tiles_a + wr.first + c0, sdesc, cn);
+            stage_descriptors<sizeof(PullDesc) / 4, BWD_THREADS>(T.tiles_a + wr.first + c0, sdesc, cn);
             __syncthreads();
             const bool heavy = __ballot(lane < cn && (sdesc[lane < cn ? lane : 0].lflags & TF_GLOBAL_DEP)) != 0ull;
             u32 i = 0;
@@ -747,22 +764,13 @@ __global__ __launch_bounds__(WG) void k_bwd_pull_step(Tables T, u32 work_lo, u32
                 u32 glen = __builtin_amdgcn_readfirstlane(sdesc[i].grp_len);
                 if (glen == 0) glen = 1;
                 if (glen > cn - i) glen = cn - i;
-                if (glen == 1) pull_tile(T, sdesc[i], (lds_float *)lds, threadIdx.x, WG);
-                else for (u32 t = i + wave; t < i + glen; t += WG / 64) pull_tile(T, sdesc[t], (lds_float *)lds, lane, 64);
+                if (glen == 1) pull_tile(T, sdesc[i], (lds_float *)lds, threadIdx.x, BWD_THREADS);
+                else for (u32 t = i + wave; t < i + glen; t += BWD_THREADS / 64) pull_tile(T, sdesc[t], (lds_float *)lds, lane, 64);
                 i += glen;
                 if (i < cn) run_barrier(heavy);
             }
         }
         __syncthreads();
-    }
-}
-
-__global__ __launch_bounds__(DX_WAVES * 64) void k_bwd_dx_step(Tables T, u32 tile_lo, u32 tile_hi)
-{
-    __shared__ float lds[DX_WAVES * 4 * 64];
-    for (u32 tile = tile_lo + blockIdx.x; tile < tile_hi; tile += gridDim.x) {
-        const TileDesc d = T.tiles_b[tile];
-        matvec_dx_tile(T, d, lds);
     }
 }
 
@@ -861,13 +869,20 @@ static int launch_backward_steps(ob_ctx *ctx)
     ++ctx->n_launch_bwd;
     for (u32 st = ns; st-- > 0;) {
         const SlotRec &r = ctx->slots[st], &e = ctx->slots[st + 1];
-        if (e.wa > r.wa) {
-            hipLaunchKernelGGL(k_bwd_pull_step, dim3(grid_for(e.wa - r.wa, GRID_CAP)), dim3(WG), 0, s, T, r.wa, e.wa, r.ta,
-                               slot_run_len(r));
+        const u32 n_pull = e.wa - r.wa, n_dx = e.tb - r.tb;
+        if (n_pull && n_dx && r.dx_free) {
+            hipLaunchKernelGGL(k_bwd_step, dim3(grid_for(n_pull + n_dx, GRID_CAP)), dim3(BWD_THREADS), 0, s, T, r.wa, e.wa,
+                               r.ta, slot_run_len(r), r.tb, e.tb);
+            ++ctx->n_launch_bwd;
+            continue;
+        }
+        if (n_pull) {
+            hipLaunchKernelGGL(k_bwd_step, dim3(grid_for(n_pull, GRID_CAP)), dim3(BWD_THREADS), 0, s, T, r.wa, e.wa, r.ta,
+                               slot_run_len(r), 0u, 0u);
             ++ctx->n_launch_bwd;
         }
-        if (e.tb > r.tb) {
-            hipLaunchKernelGGL(k_bwd_dx_step, dim3(grid_for(e.tb - r.tb, GRID_CAP)), dim3(DX_WAVES * 64), 0, s, T, r.tb, e.tb);
+        if (n_dx) {
+            hipLaunchKernelGGL(k_bwd_step, dim3(grid_for(n_dx, GRID_CAP)), dim3(BWD_THREADS), 0, s, T, 0u, 0u, 0u, 0u, r.tb, e.tb);
             ++ctx->n_launch_bwd;
         }
     }

@@ -30,6 +30,7 @@ constexpr u32 CHAIN_LDS_FLOATS = 16384;   // LDS a fused chain may use to hand r
 enum : u32 {
     TF_VEC4 = 1u,            // float4 path allowed
     TF_ALIGNED = 2u,         // operand rows 16-byte aligned
+    TF_G_ALIAS = 4u,         // MATVEC batch: the gradient of every row is a plain copy of one consumer row
     TF_SRC_LDS = 16u,        // << j: operand slot / consumer edge j is read from the chain's LDS copy
     TF_OUT_LDS = 256u,       // the tile also writes its result to the chain's LDS copy
     TF_GLOBAL_DEP = 512u     // reads a result of an earlier member of the same chain from global memory
@@ -65,7 +66,7 @@ struct BatchRec {  // one per batch, 64 bytes
     u32 opnd;            // base into opnd_off[], slot-major: opnd_off[opnd + j*B + r]
     u32 k;               // dimension of operand 0 (MATVEC: columns of W)
     u32 indim;           // base into b_indim[] (operand dimensions, `arity` entries)
-    u32 vec4;            // bit 0: float4 component-wise path allowed; bit 1: operand rows 16-byte aligned
+    u32 vec4;            // TF_VEC4 | TF_ALIGNED | TF_G_ALIAS
 };
 
 struct ParamDesc {
@@ -139,7 +140,9 @@ struct WorkRec { u32 first, len; };   // a workgroup runs tiles [first, first + 
 // dX tile, forward tile and pull tile of the slot, and the smallest / complement of the largest
 // run length (tiles per work item) over the slot's chains.  When the two lengths agree, work
 // item w of the slot runs tiles tf + (w - wf) * len onwards and its WorkRec need not be read.
-struct SlotRec { u32 wf, wa, tb, tf, ta, lmin, nlmax, pad; };
+// dx_free != 0: no dX tile of the slot reads a gradient that the slot's own pull computes (every
+// MATVEC batch in it has TF_G_ALIAS), so the slot's pull and dX work can share one launch.
+struct SlotRec { u32 wf, wa, tb, tf, ta, lmin, nlmax, dx_free; };
 
 // Static tile of the deferred parameter-gradient kernels (built on the host per parameter set).
 struct PTile { i32 param; i32 i0, j0; i32 pad; };
@@ -176,11 +179,13 @@ struct Tables {
     // scheduler tables
     u64 *sig; u32 *step; u32 *indeg; u32 *outdeg; u32 *succ_off; u32 *succ_edge; u32 *edge_cons;
     u32 *queue; u32 *qcount;            // frontier queue, [0]=tail
-    u32 *ext_indeg;                     // operands owned by another range of the partitioned depth pass
+    u32 *ext_indeg;                     // operands owned by another range of the partitioned depth pass (fixed once counted)
+    u32 *ext_left;                      // the same count, taken down as those operands resolve
     u64 *ht_keys; u32 *ht_vals; u32 ht_mask; u32 *ht_slot;
     u32 *order; u32 *pos_of; u32 *batch_of_pos; u32 *s_aux0; u32 *s_in_off;
     u32 *batch_off; BatchRec *batches; Lay *lay; u32 *b_indim;
     u32 *val_off; u32 *dx_off; u32 *opnd_off;
+    u32 *dx_gsrc;          // per schedule position of a MATVEC node with one consumer: where that consumer's gradient row lies
     u32 *slot_of; u32 *label_of; u32 *lorder;
     ChainRec *chains; CLay *clay; u32 *chain_of_lpos;
     SlotRec *slots;

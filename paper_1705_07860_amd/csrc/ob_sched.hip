@@ -73,7 +73,7 @@ __global__ void k_edge_init(Tables T, u64 *keys, u32 *vals)
     const u32 j = e - T.in_off[v];
     T.edge_cons[e] = v;
     atomicAdd(&T.outdeg[u], 1u);
-    if (u / DEPTH_PART != v / DEPTH_PART) atomicAdd(&T.ext_indeg[v], 1u);   // operand owned by another partition
+    if (u / DEPTH_PART != v / DEPTH_PART) { atomicAdd(&T.ext_indeg[v], 1u); atomicAdd(&T.ext_left[v], 1u); }   // operand owned by another partition
     atomicAdd((unsigned long long *)&T.sig[v], (unsigned long long)mix64(comb(0x5bd1e995ULL + j, T.out_dim[u])));
     keys[e] = u;
     vals[e] = e;
@@ -135,8 +135,9 @@ __global__ __launch_bounds__(FRONTIER_THREADS) void k_depth_frontier(Tables T, c
 // atomics: the producer raises the consumer's depth bound and lowers its count of unresolved
 // external operands; whoever resolves the last one posts the node to the owner's inbox, where it
 // counts as one more resolved dependency.  Ids are a topological order, so a range only ever
-// waits for lower ranges and the lowest never waits; all workgroups are resident together
-// (at most one per CU), and every wait is bounded.
+// waits for lower ranges and the lowest never waits, whenever each workgroup happens to start (a
+// range reads its nodes' external counts from the fixed copy, never from the counters that lower
+// ranges are already taking down); every wait is bounded.
 constexpr u32 DEPTH_SCAP = 12288;
 constexpr u32 DEPTH_THREADS = 256;    // a range's frontier is small: four waves keep the barriers cheap     // successor entries of a range held in LDS
 constexpr u32 DEPTH_MAX_PARTS = 240;
@@ -198,7 +199,7 @@ __global__ __launch_bounds__(DEPTH_THREADS) void k_depth_partitioned(Tables T, c
                 } else {
                     atomicMax(&g_dep[sn], d + 1);
                     __threadfence();
-                    if (atomicSub(&T.ext_indeg[sn], 1u) == 1u) {
+                    if (atomicSub(&T.ext_left[sn], 1u) == 1u) {
                         const u32 k2 = sn / DEPTH_PART;
                         const u32 slot = atomicAdd(&inbox_tail[k2], 1u);
                         __hip_atomic_store(&inbox[k2 * DEPTH_PART + slot], sn, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
@@ -330,7 +331,7 @@ __global__ void k_batch_layout(Tables T, Lay *lay_in)
         r.k = r.arity ? T.out_dim[T.in_idx[T.in_off[h]]] : 0;
         r.val_off = r.dx_off = r.indim = 0;
         r.opnd = T.s_in_off[p0];
-        r.vec4 = 3;   // bit 0: float4 component-wise path; bit 1: operand rows are 16-byte aligned
+        r.vec4 = TF_VEC4 | TF_ALIGNED | TF_G_ALIAS;   // cleared below by whatever a member violates
         T.batches[b] = r;
         const u64 vs = (u64)B * r.d;
         L.val = (vs + VAL_ALIGN - 1) / VAL_ALIGN * VAL_ALIGN;
@@ -390,7 +391,8 @@ __global__ void k_member_check(Tables T)
     if (r.op == OP_SLICE) vec = vec && ((u32)r.aux0 & 3u) == 0;
     if (r.op == OP_INPUT) vec = vec && ((u32)T.aux0[v] & 3u) == 0;
     if (!same) atomicOr(&T.hdr->err, (u32)ERR_COLLISION);
-    if (!vec) atomicAnd(&r.vec4, 2u);
+    if (!vec) atomicAnd(&r.vec4, ~(u32)TF_VEC4);
+    if (r.op == OP_MATVEC && (T.outdeg[v] != 1 || v == T.root)) atomicAnd(&r.vec4, ~(u32)TF_G_ALIAS);
 }
 
 // Per edge: operand row offsets per batch (slot-major), operand dimensions of the batch, the
@@ -414,8 +416,8 @@ __global__ void k_opnd(Tables T)
     const u32 off = T.val_off[u];
     T.opnd_off[r.opnd + j * r.B + row] = off;
     if (row == 0) T.b_indim[r.indim + j] = du;
-    if (off & 3u) atomicAnd(&r.vec4, 0u);
-    else if (r.op == OP_CONCAT && (du & 3u)) atomicAnd(&r.vec4, 2u);
+    if (off & 3u) atomicAnd(&r.vec4, ~(u32)(TF_VEC4 | TF_ALIGNED));
+    else if (r.op == OP_CONCAT && (du & 3u)) atomicAnd(&r.vec4, ~(u32)TF_VEC4);
 }
 
 // ---- launch planning ---------------------------------------------------------------------------------
@@ -678,7 +680,7 @@ __global__ void k_slot_init(Tables T)
 {
     const u32 s = blockIdx.x * blockDim.x + threadIdx.x;
     if (s > T.hdr->n_slots) return;
-    SlotRec r; r.wf = r.wa = r.tb = r.tf = r.ta = r.lmin = r.nlmax = r.pad = 0xffffffffu;
+    SlotRec r; r.wf = r.wa = r.tb = r.tf = r.ta = r.lmin = r.nlmax = r.dx_free = 0xffffffffu;
     T.slots[s] = r;
 }
 
@@ -693,6 +695,8 @@ __global__ void k_slot_tables(Tables T, const CLay *clay_ex, const CLay *total)
     const CLay L = clay_ex[c];
     SlotRec &S = T.slots[s];
     if (c == 0 || T.chains[c - 1].slot != s) { S.wf = L.wf; S.wa = L.wa; S.tb = L.tb; S.tf = L.tf; S.ta = L.ta; }
+    const BatchRec &hb = T.batches[T.lorder[cr.first]];
+    if (hb.op == OP_MATVEC && !(hb.vec4 & TF_G_ALIAS)) S.dx_free = 0;   // this slot's dX tiles need the slot's own pull first
     const u32 len = cr.fused ? cr.kt : 1u;
     atomicMin(&S.lmin, len);
     atomicMin(&S.nlmax, ~len);
@@ -777,7 +781,28 @@ __device__ inline void fill_tile_desc(const Tables &T, const BatchRec &r, u32 t,
     d.opnd = r.opnd; d.indim = r.indim; d.flags = r.vec4; d.t = t;
     d.contig = 0; d.row0 = row0; d.nrows = nrows; d.depth = r.step;
     for (int j = 0; j < 4; ++j) { d.base[j] = 0; d.sdim[j] = 0; d.sstride[j] = 0; }
-    if (dx || (!row_block && r.arity == 0)) return;
+    if (dx) {
+        // dX tile: rows (t / ntn) * DXT ...; with TF_G_ALIAS the gradient rows are read where the
+        // consumer left them, evenly spaced or through the per-row list
+        if (r.vec4 & TF_G_ALIAS) {
+            const u32 ntn = (r.k + DXT - 1) / DXT;
+            const u32 r_lo = (t / ntn) * DXT;
+            u32 r_hi = r_lo + DXT - 1;
+            if (r_hi >= r.B) r_hi = r.B - 1;
+            const u32 *gs = T.dx_gsrc + r.pos0;
+            const u32 base = gs[r_lo];
+            bool ok = true;
+            u32 ss = 0;
+            if (r_hi > r_lo) {
+                ss = gs[r_lo + 1] - base;
+                for (u32 i = 2; ok && r_lo + i <= r_hi; ++i) ok = gs[r_lo + i] == base + i * ss;
+            }
+            d.base[0] = base; d.sstride[0] = ss;
+            if (ok) d.contig |= 1u;
+        }
+        return;
+    }
+    if (!row_block && r.arity == 0) return;
     if (!row_block) {
         u32 r_lo, r_hi;
         if (r.op == OP_MATVEC) {
@@ -1029,6 +1054,13 @@ __global__ void k_edges(Tables T)
     default: break;
     }
     T.edges[q] = r;
+    // a MATVEC node's own gradient row: with one plain consumer it is that consumer's row as it is
+    const u32 u = T.in_idx[e];
+    if (T.op[u] == OP_MATVEC) {
+        const u32 pu = T.pos_of[u];
+        T.dx_gsrc[pu] = r.goff;
+        if (r.kind != EK_PLAIN || (r.goff & 3u)) atomicAnd(&T.batches[T.batch_of_pos[pu]].vec4, ~(u32)TF_G_ALIAS);
+    }
 }
 
 // ---- parameter-use items: every MATVEC is a use of W (kind 0) and of its bias (kind 1), every
@@ -1110,7 +1142,7 @@ int sched_enqueue(ob_ctx *ctx)
     } while (0)
     A(T.sig, u64, n); A(T.step, u32, n); A(T.indeg, u32, n); A(T.outdeg, u32, n + 1);
     A(T.succ_off, u32, n + 1); A(T.succ_edge, u32, E + 1); A(T.edge_cons, u32, E + 1);
-    A(T.queue, u32, n); A(T.qcount, u32, 64); A(T.ext_indeg, u32, n + 1);
+    A(T.queue, u32, n); A(T.qcount, u32, 64); A(T.ext_indeg, u32, n + 1); A(T.ext_left, u32, n + 1);
     u32 *g_dep, *inbox, *inbox_tail;
     const u32 n_parts = (n + DEPTH_PART - 1) / DEPTH_PART;
     A(g_dep, u32, n + 1); A(inbox, u32, (size_t)n_parts * DEPTH_PART); A(inbox_tail, u32, n_parts + 1);
@@ -1119,7 +1151,7 @@ int sched_enqueue(ob_ctx *ctx)
     A(T.order, u32, n); A(T.pos_of, u32, n); A(T.batch_of_pos, u32, n); A(T.s_aux0, u32, n);
     A(T.s_in_off, u32, n + 1);
     A(T.batch_off, u32, n + 1); A(T.batches, BatchRec, n); A(T.lay, Lay, n); A(T.b_indim, u32, E + 1);
-    A(T.val_off, u32, n); A(T.dx_off, u32, n); A(T.opnd_off, u32, E + 1);
+    A(T.val_off, u32, n); A(T.dx_off, u32, n); A(T.opnd_off, u32, E + 1); A(T.dx_gsrc, u32, n);
     A(T.slot_of, u32, n); A(T.label_of, u32, n);
     A(T.lorder, u32, n); A(T.chains, ChainRec, n); A(T.clay, CLay, n); A(T.chain_of_lpos, u32, n);
     // moving matrix products to odd slots can at most double the number of slots over the number
@@ -1157,6 +1189,7 @@ int sched_enqueue(ob_ctx *ctx)
     HIP_TRY(ctx, hipMemsetAsync(T.outdeg, 0, (size_t)(n + 1) * 4, s));
     HIP_TRY(ctx, hipMemsetAsync(T.qcount, 0, 64 * 4, s));
     HIP_TRY(ctx, hipMemsetAsync(T.ext_indeg, 0, (size_t)(n + 1) * 4, s));
+    HIP_TRY(ctx, hipMemsetAsync(T.ext_left, 0, (size_t)(n + 1) * 4, s));
     const bool part_depth = by_depth && n_parts <= DEPTH_MAX_PARTS && ctx->max_arity < 60000;
     if (part_depth) {
         HIP_TRY(ctx, hipMemsetAsync(g_dep, 0, (size_t)(n + 1) * 4, s));
