@@ -346,8 +346,62 @@ __device__ inline void gemm_nt_tile(const float *xrow, bool row_ok, u32 B, const
     }
 }
 
+// Batches with many rows: a workgroup covers 64 x 64 outputs, wave w the 32x32 block (w / 2, w % 2)
+// over the whole contraction, so no partial sums cross waves and nothing goes through LDS.
+__device__ inline void matvec_fwd_tile_wide(const Tables &T, const TileDesc &d)
+{
+    const u32 lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    const u32 l32 = lane & 31, h = lane >> 5;
+    const u32 ntn = (d.d + GTW - 1) / GTW;
+    const u32 r0 = (d.t / ntn) * GTW + 32 * (w >> 1), i0 = (d.t % ntn) * GTW + 32 * (w & 1);
+    const u32 row = r0 + l32, col = i0 + l32;
+    const bool row_ok = row < d.B, col_ok = col < d.d;
+    const u32 K = d.k;
+    const float *xrow = T.V + (row_ok ? opnd_row(T, d, 0, row - d.row0, row) : 0u);
+    gl_float *wrow = as_global(d.w) + (size_t)(col_ok ? col : 0u) * K;
+    const bool fast = (d.flags & TF_ALIGNED) && (K & 3u) == 0;
+    floatx16 acc;
+    for (int v = 0; v < 16; ++v) acc[v] = 0.f;
+    const float4 z4 = make_float4(0.f, 0.f, 0.f, 0.f);
+    const u32 Kp = (K + 7u) & ~7u;
+    if (fast) {
+        for (u32 kb = 0; kb < Kp; kb += 8 * KU) {
+            float4 a[KU], b[KU];
+#pragma unroll
+            for (int u = 0; u < KU; ++u) {
+                const u32 k0 = kb + 8 * u + 4 * h;
+                const bool in = k0 < K;
+                a[u] = (in && row_ok) ? ld4(xrow + k0) : z4;
+                b[u] = (in && col_ok) ? gl_ld4(wrow + k0) : z4;
+            }
+#pragma unroll
+            for (int u = 0; u < KU; ++u) acc = mfma4(a[u], b[u], acc);
+        }
+    } else {
+        for (u32 kb = 0; kb < Kp; kb += 8) {
+            const u32 k0 = kb + 4 * h;
+            float av[4] = {0.f, 0.f, 0.f, 0.f}, bv[4] = {0.f, 0.f, 0.f, 0.f};
+            for (int s = 0; s < 4; ++s)
+                if (k0 + s < K) {
+                    if (row_ok) av[s] = xrow[k0 + s];
+                    if (col_ok) bv[s] = wrow[k0 + s];
+                }
+            acc = mfma4(make_float4(av[0], av[1], av[2], av[3]), make_float4(bv[0], bv[1], bv[2], bv[3]), acc);
+        }
+    }
+    if (col_ok) {
+        const float bb = d.b ? as_global(d.b)[col] : 0.f;
+        float *Y = T.V + d.val_off;
+        for (int v = 0; v < 16; ++v) {
+            const u32 rr = r0 + 8 * (v >> 2) + 4 * h + (v & 3);
+            if (rr < d.B) Y[(size_t)rr * d.d + col] = acc[v] + bb;
+        }
+    }
+}
+
 __device__ inline void matvec_fwd_tile(const Tables &T, const TileDesc &d, float *lds)
 {
+    if (d.flags & TF_WIDE) { matvec_fwd_tile_wide(T, d); return; }
     const u32 ntn = (d.d + GT - 1) / GT;
     const u32 r0 = (d.t / ntn) * GT, i0 = (d.t % ntn) * GT;
     const bool fast = (d.flags & 2u) && (d.k & 3u) == 0;
@@ -485,7 +539,8 @@ __device__ inline void param_w_tile(const Tables &T, const PTile &pt, float *lds
 }
 
 // db[i] += sum over uses of g[i].  A tile is 32 rows; the 8 groups of 32 threads take every 8th
-// use and their partial sums are added in group order.
+// use, 16 uses in flight per thread, and the partial sums are added in a fixed order.
+constexpr int PB_UNROLL = 16;
 __device__ inline void param_b_tile(const Tables &T, const PTile &pt, float *lds)
 {
     const u32 slot = (u32)pt.param * 4u + 1u;
@@ -496,15 +551,16 @@ __device__ inline void param_b_tile(const Tables &T, const PTile &pt, float *lds
     const u32 i = (u32)pt.i0 + l32;
     const bool i_ok = i < (u32)P.rows;
     float acc = 0.f;
-    for (u32 it0 = start + grp; it0 < end; it0 += 8 * 4) {
-        u32 go[4];
-        bool ok[4];
+    for (u32 it0 = start + grp; it0 < end; it0 += 8 * PB_UNROLL) {
+        u32 go[PB_UNROLL];
+        bool ok[PB_UNROLL];
 #pragma unroll
-        for (int s = 0; s < 4; ++s) { const u32 it = it0 + 8 * s; ok[s] = it < end; go[s] = ok[s] ? T.it_goff[it] : 0u; }
-        float g[4];
+        for (int s = 0; s < PB_UNROLL; ++s) { const u32 it = it0 + 8 * s; ok[s] = it < end; go[s] = ok[s] ? T.it_goff[it] : 0u; }
+        float g[PB_UNROLL];
 #pragma unroll
-        for (int s = 0; s < 4; ++s) g[s] = (ok[s] && i_ok) ? T.G[go[s] + i] : 0.f;
-        acc += (g[0] + g[1]) + (g[2] + g[3]);
+        for (int s = 0; s < PB_UNROLL; ++s) g[s] = (ok[s] && i_ok) ? T.G[go[s] + i] : 0.f;
+#pragma unroll
+        for (int s = 0; s < PB_UNROLL; s += 4) acc += (g[s] + g[s + 1]) + (g[s + 2] + g[s + 3]);
     }
     lds[grp * 32 + l32] = acc;
     __syncthreads();

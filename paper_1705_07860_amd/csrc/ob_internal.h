@@ -20,6 +20,8 @@ enum : u32 {
 constexpr int WG = 256;               // threads per workgroup of every tile kernel (4 wave64)
 constexpr int EW_TILE = 1024;         // elements of one elementwise / pull tile
 constexpr int GT = 32;                // forward / dW GEMM tile edge (one 32x32 MFMA accumulator block)
+constexpr int GTW = 64;               // forward GEMM tile edge of batches with at least WIDE_MIN_ROWS rows
+constexpr u32 WIDE_MIN_ROWS = 256;
 constexpr int DXT = 16;               // dX GEMM tile edge (16x16 blocks: its output is small, more tiles fill more CUs)
 constexpr int ROWS_PER_RED_TILE = 4;  // rows of one row-reduction tile (one wave per row)
 constexpr int WIDE_ADD_ARITY = 9;     // ADD with at least this many operands reduces per row
@@ -31,6 +33,7 @@ enum : u32 {
     TF_VEC4 = 1u,            // float4 path allowed
     TF_ALIGNED = 2u,         // operand rows 16-byte aligned
     TF_G_ALIAS = 4u,         // MATVEC batch: the gradient of every row is a plain copy of one consumer row
+    TF_WIDE = 8u,            // MATVEC batch with many rows: 64x64 forward tiles, one 32x32 block per wave, no split contraction
     TF_SRC_LDS = 16u,        // << j: operand slot / consumer edge j is read from the chain's LDS copy
     TF_OUT_LDS = 256u,       // the tile also writes its result to the chain's LDS copy
     TF_GLOBAL_DEP = 512u     // reads a result of an earlier member of the same chain from global memory

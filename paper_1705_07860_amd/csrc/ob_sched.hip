@@ -332,6 +332,7 @@ __global__ void k_batch_layout(Tables T, Lay *lay_in)
         r.val_off = r.dx_off = r.indim = 0;
         r.opnd = T.s_in_off[p0];
         r.vec4 = TF_VEC4 | TF_ALIGNED | TF_G_ALIAS;   // cleared below by whatever a member violates
+        if (r.op == OP_MATVEC && B >= WIDE_MIN_ROWS && r.d >= (u32)GTW) r.vec4 |= TF_WIDE;
         T.batches[b] = r;
         const u64 vs = (u64)B * r.d;
         L.val = (vs + VAL_ALIGN - 1) / VAL_ALIGN * VAL_ALIGN;
@@ -654,7 +655,11 @@ __global__ void k_chain_recs(Tables T, const u32 *flag, const u32 *flag_excl, CL
             L.wf = L.wa = cr.nrb;
         } else {
             switch (r0.op) {
-            case OP_MATVEC: L.tf = cdiv(r0.B, GT) * cdiv(r0.d, GT); L.tb = cdiv(r0.B, DXT) * cdiv(r0.k, DXT); break;
+            case OP_MATVEC: {
+                const u32 gt = (r0.vec4 & TF_WIDE) ? (u32)GTW : (u32)GT;
+                L.tf = cdiv(r0.B, gt) * cdiv(r0.d, gt); L.tb = cdiv(r0.B, DXT) * cdiv(r0.k, DXT);
+                break;
+            }
             case OP_PICK_NLS:
             case OP_SQNORM: L.tf = cdiv(r0.B, ROWS_PER_RED_TILE); break;
             default: L.tf = r0.B; break;   // wide sum: one workgroup per row
@@ -725,7 +730,7 @@ __global__ void k_slot_fill(Tables T)
 }
 
 // ---- tile descriptors ------------------------------------------------------------------------------
-constexpr u32 CONTIG_MAX_ROWS = 32;   // tiles with more rows skip the even-spacing test
+constexpr u32 CONTIG_MAX_ROWS = 64;   // tiles with more rows skip the even-spacing test
 
 // Where a tile of a fused chain sits: chain, member, block of groups [g0, g0 + ng).
 struct ChainCtx { ChainRec cr; u32 m, g0, ng; };
@@ -806,8 +811,9 @@ __device__ inline void fill_tile_desc(const Tables &T, const BatchRec &r, u32 t,
     if (!row_block) {
         u32 r_lo, r_hi;
         if (r.op == OP_MATVEC) {
-            const u32 ntn = (r.d + GT - 1) / GT;
-            r_lo = (t / ntn) * GT; r_hi = r_lo + GT - 1;
+            const u32 gt = (r.vec4 & TF_WIDE) ? (u32)GTW : (u32)GT;
+            const u32 ntn = (r.d + gt - 1) / gt;
+            r_lo = (t / ntn) * gt; r_hi = r_lo + gt - 1;
         } else if (r.op == OP_PICK_NLS || r.op == OP_SQNORM) {
             r_lo = t * ROWS_PER_RED_TILE; r_hi = r_lo + ROWS_PER_RED_TILE - 1;
         } else {

@@ -294,6 +294,40 @@ def test_odd_dimensions_duplicate_lookups_and_wide_sum():
     c.close()
 
 
+@pytest.mark.parametrize("dims", [(50, 70, 300), (64, 128, 523)])
+def test_large_batches_of_matrix_products(dims):
+    """Matrix-product batches with hundreds of rows (the wide forward tiles): ragged rows and
+    columns, a contraction length that is not a multiple of 4 in the first case, operands that are
+    gathered (every other lookup row) rather than evenly spaced."""
+    from paper_1705_07860_amd import binding as ob
+    k, m, nrow = dims
+    rng = np.random.default_rng(1000 + k)
+    pb = wl.ParamBuilder(rng, std=0.3)
+    E = pb.add("E", 40, k)
+    W = pb.add("W", m, k)
+    b = pb.add("b", m, 1)
+    U = pb.add("U", 3, m)
+    p = pb.done()
+    gb = wl.GraphBuilder(p)
+    losses = []
+    for i in range(nrow):
+        x = gb.lookup(E, (7 * i) % 40)
+        if i % 2:
+            x = gb.tanh(x)                           # half of the rows come from another batch
+        h = gb.tanh(gb.matvec(W, b, x))
+        losses.append(gb.pick_nls(gb.matvec(U, -1, h), i % 3))
+    g = gb.finish(gb.add(losses), nrow)
+    o = Oracle(g, p, "f64")
+    o.forward()
+    o.backward(g.root)
+    c, root = run_gpu(p, g, ob.OB_BYDEPTH, arena=256 << 20)
+    bo, ids, bd, _ = c.schedule_read()
+    rbo, rids, rbd = S.by_depth(g)
+    assert np.array_equal(bo, rbo) and np.array_equal(ids, rids) and np.array_equal(bd, rbd)
+    check_against_oracle(c, p, g, o, root, what=f"wide{dims}")
+    c.close()
+
+
 def test_parameter_gradients_accumulate_until_zeroed(workload_cache):
     from paper_1705_07860_amd import binding as ob
     p, g, o = workload_cache("rnn")
