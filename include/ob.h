@@ -210,6 +210,12 @@ int ob_test_scan(ob_ctx *ctx, size_t n, const uint32_t *in, uint32_t *out_exclus
  * of a kernel whose one thread does a dependent load and store (touch = 1) on the context's
  * stream: the floor of a launch boundary on this machine, reported by the benchmark. */
 int ob_test_launch_cost(ob_ctx *ctx, int n, int touch, float *us_per_launch);
+/* Cost and correctness of the library's grid-wide barrier: n_wg workgroups of one cooperative
+ * launch (all resident, or the launch fails with OB_E_HIP) run iters phases; in each a workgroup
+ * publishes a word, passes the barrier and reads its neighbour's word.  out3[0] = nanoseconds per
+ * phase, out3[1] = stale reads seen (must be 0), out3[2] = 1 if a wait ran into its poll limit (the
+ * kernel then ends early instead of hanging). */
+int ob_test_grid_barrier(ob_ctx *ctx, int n_wg, int iters, uint32_t *out3);
 /* C[M x N] = A[M x K] * B[N x K]^T through the library's MFMA tile routine. */
 int ob_test_gemm(ob_ctx *ctx, int M, int N, int K, const float *A, const float *B, float *C);
 

@@ -107,6 +107,7 @@ def lib():
             "ob_test_scan": (i, [vp, sz, vp, vp, vp]),
             "ob_test_gemm": (i, [vp, i, i, i, vp, vp, vp]),
             "ob_test_launch_cost": (i, [vp, i, i, POINTER(c_float)]),
+            "ob_test_grid_barrier": (i, [vp, i, i, vp]),
         }
         for name, (res, args) in sigs.items():
             fn = getattr(L, name)
@@ -346,6 +347,12 @@ class Context:
         out = c_float()
         self._ck(self.L.ob_test_launch_cost(self.h, n, touch, byref(out)))
         return float(out.value)
+
+    def test_grid_barrier(self, n_wg: int = 256, iters: int = 1000):
+        """(ns per barrier phase, stale reads, poll-limit flag) of the library's grid-wide barrier."""
+        out = np.zeros(3, np.uint32)
+        self._ck(self.L.ob_test_grid_barrier(self.h, n_wg, iters, _ptr(out)))
+        return int(out[0]), int(out[1]), int(out[2])
 
     def test_gemm(self, A, B):
         A = np.ascontiguousarray(A, np.float32)

@@ -905,6 +905,21 @@ int ob_test_launch_cost(ob_ctx *ctx, int n, int touch, float *us_per_launch)
     return rc;
 }
 
+int ob_test_grid_barrier(ob_ctx *ctx, int n_wg, int iters, uint32_t *out3)
+{
+    CHECK_CTX(ctx);
+    if (!ctx->arena) return ctx_fail(ctx, OB_E_STATE, "no arena");
+    if (n_wg <= 0 || n_wg > 4096 || iters <= 0 || iters > 100000 || !out3) return ctx_fail(ctx, OB_E_ARG, "bad argument");
+    const size_t save = ctx->top;
+    u32 *state = arena_array<u32>(ctx, 64 + (size_t)n_wg);
+    if (!state) return ctx_fail(ctx, OB_E_OOM, "arena too small");
+    int rc = OB_OK;
+    hipError_t e = exec_barrier_probe(state, n_wg, iters, out3, ctx->stream);
+    if (e != hipSuccess) rc = ctx_fail(ctx, OB_E_HIP, "barrier probe failed: %s", hipGetErrorString(e));
+    ctx->top = save;
+    return rc;
+}
+
 int ob_test_gemm(ob_ctx *ctx, int M, int N, int K, const float *A, const float *B, float *C)
 {
     CHECK_CTX(ctx);

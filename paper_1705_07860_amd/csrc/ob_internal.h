@@ -36,7 +36,8 @@ enum : u32 {
     TF_WIDE = 8u,            // MATVEC batch with many rows: 64x64 forward tiles, one 32x32 block per wave, no split contraction
     TF_SRC_LDS = 16u,        // << j: operand slot / consumer edge j is read from the chain's LDS copy
     TF_OUT_LDS = 256u,       // the tile also writes its result to the chain's LDS copy
-    TF_GLOBAL_DEP = 512u     // reads a result of an earlier member of the same chain from global memory
+    TF_GLOBAL_DEP = 512u,    // reads a result of an earlier member of the same chain from global memory
+    TF_SIMPLE = 1024u        // float4 tile of ADD (<= 4 operands) / CMULT / TANH / SIGMOID / SLICE whose operand rows are all evenly spaced
 };
 
 // Kinds of consumer-edge records read by the backward pull (one per graph edge).
@@ -223,4 +224,5 @@ int exec_forward(ob_ctx *ctx);
 int exec_backward(ob_ctx *ctx);
 hipError_t exec_gather_all(const Tables &T, int which, float *dst, const u32 *dst_off, hipStream_t s);
 hipError_t exec_launch_probe(float *scratch, int n, int touch, float *us_per_launch, hipStream_t s);
+hipError_t exec_barrier_probe(u32 *state, int n_wg, int iters, u32 *out3, hipStream_t s);
 hipError_t exec_test_gemm(int M, int N, int K, const float *A, const float *B, float *C, hipStream_t s);

@@ -842,6 +842,9 @@ __device__ inline void fill_tile_desc(const Tables &T, const BatchRec &r, u32 t,
         d.sstride[j] = ss;
         if (ok) d.contig |= 1u << j;
     }
+    if (row_block && (d.flags & TF_VEC4) && r.arity >= 1 && r.arity <= 4 && (d.contig & 0xfu) == (1u << r.arity) - 1u &&
+        (r.op == OP_ADD || r.op == OP_CMULT || r.op == OP_TANH || r.op == OP_SIGMOID || r.op == OP_SLICE))
+        d.flags |= TF_SIMPLE;
     if (!cc) return;
     // tile of a fused chain: which operands come from the chain's LDS copy, and whether any
     // operand produced earlier in the same launch still has to come from global memory
@@ -849,7 +852,7 @@ __device__ inline void fill_tile_desc(const Tables &T, const BatchRec &r, u32 t,
     if (cc->cr.fused != 2u) return;
     d.lds_out = chain_own_delta(T, *cc, r);
     d.flags |= TF_OUT_LDS;
-    if (d.lds_out & 3u) d.flags &= ~(u32)TF_VEC4;   // (never with d % 4 == 0: regions and block rows start at multiples of 4)
+    if (d.lds_out & 3u) d.flags &= ~(u32)(TF_VEC4 | TF_SIMPLE);   // (never with d % 4 == 0: regions and block rows start at multiples of 4)
     if (nrows > CONTIG_MAX_ROWS) return;
     u32 state[4], delta[4];
     chain_lookup(T, *cc, ns, lo, hi, state, delta);
