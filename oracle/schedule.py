@@ -13,12 +13,22 @@ shared, the x is not).
 Where the paper is silent (order of batches inside a depth, order of nodes in
 a batch) the canonical order is: nodes ascending by id inside a batch; batches
 ascending by depth, then by the smallest node id they hold.
+
+Agenda-based batching (Section 3.2, second strategy): an agenda of nodes whose
+operands are all resolved; each iteration takes every available node of one
+signature as a batch, and the signature is chosen by the smallest average
+depth of all nodes of the graph that carry it.  Readings where the text leaves
+a choice: averages are compared exactly (cross-multiplied integers); equal
+averages go to the cheaper operation class (the footnote's "cheap before
+heavy": leaf < component-wise / copy < per-row reduction < matrix product),
+then to the signature whose first node has the smaller id.
 """
 from __future__ import annotations
 
 import numpy as np
 
 OP_LOOKUP, OP_MATVEC, OP_SLICE = 1, 2, 8
+OP_INPUT, OP_PICK_NLS, OP_SQNORM = 0, 9, 10
 
 
 def depths(g, n=None) -> np.ndarray:
@@ -76,3 +86,76 @@ def no_batching(g, n=None):
     n = g.n if n is None else n
     ids = np.arange(n, dtype=np.int64)
     return np.arange(n + 1, dtype=np.int64), ids, ids.copy()
+
+
+def cost_class(op: int) -> int:
+    """Tie-break class of Section 3.2's footnote: cheap operations before heavy ones."""
+    if op in (OP_INPUT, OP_LOOKUP):
+        return 0
+    if op == OP_MATVEC:
+        return 3
+    if op in (OP_PICK_NLS, OP_SQNORM):
+        return 2
+    return 1
+
+
+def by_agenda(g, n=None):
+    """Agenda-based schedule (Section 3.2).
+
+    Returns (batch_off[nb+1], node_ids[n], batch_step[nb]): batch k is the k-th batch taken from
+    the agenda (batch_step[k] = k), its nodes ascending by id.
+    """
+    n = g.n if n is None else n
+    d = depths(g, n)
+    in_off = g.in_off.tolist()
+    in_idx = g.in_idx.tolist()
+    sig_of = [signature(g, v) for v in range(n)]
+    # per signature: sum of depths, count, first node id, cost class
+    stat = {}
+    for v in range(n):
+        st = stat.setdefault(sig_of[v], [0, 0, v, cost_class(int(g.op[v]))])
+        st[0] += int(d[v])
+        st[1] += 1
+    succ = [[] for _ in range(n)]
+    pending = [0] * n
+    for v in range(n):
+        for u in in_idx[in_off[v]:in_off[v + 1]]:
+            if u < n:
+                succ[u].append(v)
+        pending[v] = in_off[v + 1] - in_off[v]
+    agenda = {}                       # signature -> available nodes
+    for v in range(n):
+        if pending[v] == 0:
+            agenda.setdefault(sig_of[v], []).append(v)
+
+    def before(a, b):
+        """signature a is taken before signature b"""
+        sa, sb = stat[a], stat[b]
+        lhs, rhs = sa[0] * sb[1], sb[0] * sa[1]      # sa[0]/sa[1] < sb[0]/sb[1]
+        if lhs != rhs:
+            return lhs < rhs
+        if sa[3] != sb[3]:
+            return sa[3] < sb[3]
+        return sa[2] < sb[2]
+
+    batch_off = [0]
+    node_ids = []
+    done = 0
+    while done < n:
+        if not agenda:
+            raise ValueError("graph has a cycle or refers to nodes outside the prefix")
+        best = None
+        for sg in agenda:
+            if best is None or before(sg, best):
+                best = sg
+        nodes = sorted(agenda.pop(best))
+        node_ids.extend(nodes)
+        batch_off.append(len(node_ids))
+        done += len(nodes)
+        for u in nodes:
+            for v in succ[u]:
+                pending[v] -= 1
+                if pending[v] == 0:
+                    agenda.setdefault(sig_of[v], []).append(v)
+    nb = len(batch_off) - 1
+    return (np.asarray(batch_off, np.int64), np.asarray(node_ids, np.int64), np.arange(nb, dtype=np.int64))

@@ -155,3 +155,39 @@ def validate_schedule(g, batch_off, node_ids, batch_depth, n=None):
         for u in g.in_idx[int(g.in_off[v]):int(g.in_off[v + 1])]:
             assert depth_of[int(u)] < depth_of[v], f"edge {u}->{v} violates depth order"
     return depth_of
+
+
+def validate_agenda_schedule(g, batch_off, node_ids, n=None):
+    """Replays an agenda-based schedule (Section 3.2) step by step and checks every choice
+    independently of the code that made it: the batch holds every available node of its
+    signature, nothing else, and no other available signature had a smaller average depth
+    (exact fractions over all nodes carrying the signature; then operation class: leaf,
+    component-wise / copy, per-row reduction, matrix product; then smaller first node id).
+    Depths come from path enumeration, signatures from the string form."""
+    from fractions import Fraction
+    n = g.n if n is None else n
+    depth = longest_path_depths(g)[:n]
+    sig = [sig_string(g, v) for v in range(n)]
+    klass = {0: 0, 1: 0, 2: 3, 9: 2, 10: 2}
+    tot, cnt, first, cost = {}, {}, {}, {}
+    for v in range(n):
+        s = sig[v]
+        tot[s] = tot.get(s, 0) + int(depth[v])
+        cnt[s] = cnt.get(s, 0) + 1
+        first.setdefault(s, v)
+        cost[s] = klass.get(int(g.op[v]), 1)
+    rank = {s: (Fraction(tot[s], cnt[s]), cost[s], first[s]) for s in tot}
+    executed = np.zeros(n, bool)
+    nb = len(batch_off) - 1
+    assert batch_off[0] == 0 and batch_off[-1] == n
+    for b in range(nb):
+        ids = [int(v) for v in node_ids[batch_off[b]:batch_off[b + 1]]]
+        assert ids == sorted(ids) and len(ids) > 0
+        avail = [v for v in range(n) if not executed[v] and
+                 all(executed[int(u)] for u in g.in_idx[int(g.in_off[v]):int(g.in_off[v + 1])])]
+        s = sig[ids[0]]
+        assert ids == [v for v in avail if sig[v] == s], f"batch {b} is not all available nodes of its signature"
+        best = min(rank[sig[v]] for v in avail)
+        assert rank[s] == best, f"batch {b}: a signature with a smaller average depth was available"
+        executed[ids] = True
+    assert executed.all()

@@ -107,3 +107,65 @@ def test_permuting_instances_permutes_the_schedule():
     bob, _, bdb = S.by_depth(gb)
     assert np.array_equal(np.diff(boa), np.diff(bob))
     assert np.array_equal(bda, bdb)
+
+
+# ---------------------------------------------------------------- agenda-based batching
+
+@pytest.mark.parametrize("seed", range(8))
+def test_agenda_replay_on_tiny_random_graphs(seed):
+    from tests.helpers import validate_agenda_schedule
+    p, g = wl.random_dag(300 + seed, n_nodes=14, dim=4)
+    bo, ids, bs = S.by_agenda(g)
+    validate_schedule(g, bo, ids, bs)          # partition, one signature per batch, operands earlier
+    validate_agenda_schedule(g, bo, ids)
+
+
+def test_agenda_replay_on_small_workloads():
+    from tests.helpers import validate_agenda_schedule
+    p = wl.tagger_params()
+    g = wl.tagger_minibatch(p, seed=9, lengths=[3, 1, 4])
+    bo, ids, bs = S.by_agenda(g)
+    validate_schedule(g, bo, ids, bs)
+    validate_agenda_schedule(g, bo, ids)
+    tp = wl.tree_params()
+    tg = wl.tree_minibatch(tp, seed=4, leaf_counts=[3, 5, 2])
+    bo, ids, bs = S.by_agenda(tg)
+    validate_schedule(tg, bo, ids, bs)
+    validate_agenda_schedule(tg, bo, ids)
+
+
+def test_agenda_batches_the_losses_of_unequal_chains():
+    """Section 3.2's motivating case: with sequences of different lengths the loss nodes become
+    available at different times; their signature has the largest average depth but one, so they
+    wait until the recurrence is exhausted and form ONE batch (depth-based batching needs one per
+    distinct length).  Closed form for h_t = tanh(W x_t + U h_{t-1} + b) built as MATVEC, MATVEC,
+    ADD, TANH: inputs, all W products, then per step U product / sum / tanh over the sequences
+    still alive, then all losses, then the final sum."""
+    lengths = [3, 7, 7, 4, 10, 3, 5, 7]
+    p = wl.rnn_params()
+    g = wl.rnn_minibatch(p, seed=1, lengths=lengths)
+    bo, ids, bs = S.by_agenda(g)
+    sizes = np.diff(bo).tolist()
+    ops = [(int(g.op[ids[bo[b]]]), int(g.param[ids[bo[b]]])) for b in range(len(bs))]
+    nmax = max(lengths)
+    expect_ops = [(wl.OP_INPUT, -1), (wl.OP_MATVEC, 0)]
+    expect_sizes = [len(lengths) + sum(lengths), sum(lengths)]
+    for t in range(1, nmax + 1):
+        alive = sum(1 for n in lengths if n >= t)
+        expect_ops += [(wl.OP_MATVEC, 1), (wl.OP_ADD, -1), (wl.OP_TANH, -1)]
+        expect_sizes += [alive] * 3
+    expect_ops += [(wl.OP_SQNORM, -1), (wl.OP_ADD, -1)]
+    expect_sizes += [len(lengths), 1]
+    assert ops == expect_ops and sizes == expect_sizes
+    nb_depth = len(S.by_depth(g)[2])
+    assert len(bs) == nb_depth - (len(set(lengths)) - 1)
+
+
+@pytest.mark.parametrize("name", ["rnn", "tagger", "tree", "parser"])
+def test_agenda_invariants_on_configs(name, workload_cache):
+    p, g, _ = workload_cache(name)
+    bo, ids, bs = S.by_agenda(g)
+    validate_schedule(g, bo, ids, bs)
+    # (the heuristic does not always give fewer batches than depth-based batching: the tree
+    # workload gets more)
+    print(name, "batches: agenda", len(bs), "depth", len(S.by_depth(g)[2]))
