@@ -77,7 +77,7 @@ def stored_traffic(args, kernel):
     runs, FETCH_SIZE and WRITE_SIZE, scaled by a plain copy of known size).  Counters cannot be
     read inside a timing run, so the figure is the stored one and only applies to the default
     launch configuration of the workload it was taken on; otherwise null."""
-    if args.launch != "stream" or args.no_fusion or args.placement != "late":
+    if args.launch != "stream" or args.no_fusion or args.placement != "late" or args.mode != "depth":
         return None
     path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles", f"{args.workload}_bydepth_hbm_traffic.json")
     try:
@@ -96,6 +96,9 @@ def main():
     ap.add_argument("--workload", default="tagger", choices=list(wl.CONFIGS))
     ap.add_argument("--pool", type=int, default=6, help="distinct seeded minibatches cycled through")
     ap.add_argument("--launch", default="stream", choices=["stream", "graph"])
+    ap.add_argument("--mode", default="depth", choices=["depth", "agenda"],
+                    help="batching strategy of Section 3.2: depth-based (default, the configuration the stored "
+                         "profiles cover) or agenda-based")
     ap.add_argument("--no-pipeline", action="store_true",
                     help="schedule and execute each step back to back on one stream (no overlap between steps)")
     ap.add_argument("--no-fusion", action="store_true", help="one launch per depth level")
@@ -137,8 +140,8 @@ def main():
     t_up = []
     for j, g in enumerate(graphs):
         if j == 0:
-            c = ob.Context(arena_bytes=1 << 30, stream=stream, mode=ob.OB_BYDEPTH, launch=launch,
-                           sched_stream=sched_stream)
+            c = ob.Context(arena_bytes=1 << 30, stream=stream, launch=launch, sched_stream=sched_stream,
+                           mode=ob.OB_BYAGENDA if args.mode == "agenda" else ob.OB_BYDEPTH)
             c.set_fusion(0 if args.no_fusion else (2 if args.placement == "late" else 1))
             c.params_create(params)
             c.param_grad_zero()
@@ -283,7 +286,7 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": f"config {cfg['index']}: {args.workload} (BASELINE.json configs[{cfg['index'] - 1}])",
-                   "instances_per_step": graphs[0].n_instances, "mode": "bydepth", "launch": args.launch,
+                   "instances_per_step": graphs[0].n_instances, "mode": "by" + args.mode, "launch": args.launch,
                    "fusion": not args.no_fusion, "placement": args.placement,
                    "pipeline": "scheduling of step i+1 overlaps execution of step i (second stream)" if pipeline
                    else "none (schedule, forward, backward back to back)",

@@ -66,12 +66,15 @@ typedef struct ob_ctx ob_ctx;
 /* batching modes (Section 4.1: NoAuto / ByDepth / ByAgenda) */
 #define OB_NOBATCH 0       /* one launch per node forward and per node backward */
 #define OB_BYDEPTH 1       /* depth-based batching (Section 3.2)                */
-#define OB_BYAGENDA 2      /* agenda-based batching: not built, OB_E_STATE      */
+#define OB_BYAGENDA 2      /* agenda-based batching (Section 3.2): signatures ranked by the average depth of their
+                            * nodes (exact), then cheap before heavy operations, then first node id; at most 1024
+                            * distinct signatures per graph, else OB_E_STATE at schedule time */
 
 /* how the per-step launches are issued */
 #define OB_LAUNCH_STREAM 0     /* one kernel launch per step on the stream            */
 #define OB_LAUNCH_GRAPH 1      /* the per-step launches captured in a hipGraph        */
-#define OB_LAUNCH_PERSISTENT 2 /* one cooperative kernel walks all steps, grid barrier */
+#define OB_LAUNCH_PERSISTENT 2 /* one cooperative kernel for all steps: not built, OB_E_STATE (a grid-wide barrier
+                                * measures slower than a kernel boundary on this machine, see ob_test_grid_barrier) */
 
 /* ---- context ------------------------------------------------------------------------- */
 
@@ -170,7 +173,7 @@ int ob_grad_read(ob_ctx *ctx, int node, float *host_out, size_t cap);
 int ob_all_read(ob_ctx *ctx, int which, float *host_out, size_t cap);
 
 /* The schedule of the last ob_forward: batch b holds node_ids[batch_off[b] .. batch_off[b+1]).
- * batch_depth is the depth (OB_BYDEPTH) or the step index (OB_NOBATCH); batch_sig is the
+ * batch_depth is the depth (OB_BYDEPTH), the agenda iteration (OB_BYAGENDA) or the step index (OB_NOBATCH); batch_sig is the
  * 64-bit signature hash (Appendix B) and is informational.  cap_batches / cap_nodes are the
  * capacities of the per-batch arrays (batch_off needs cap_batches + 1) and of node_ids. */
 int ob_schedule_read(ob_ctx *ctx, int *n_batches, int *batch_depth, uint64_t *batch_sig,

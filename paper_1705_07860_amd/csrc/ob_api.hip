@@ -90,8 +90,7 @@ int ob_ctx_destroy(ob_ctx *ctx)
 int ob_ctx_set_mode(ob_ctx *ctx, int mode)
 {
     CHECK_CTX(ctx);
-    if (mode == OB_BYAGENDA) return ctx_fail(ctx, OB_E_STATE, "agenda-based batching is not built");
-    if (mode != OB_NOBATCH && mode != OB_BYDEPTH) return ctx_fail(ctx, OB_E_ARG, "unknown mode %d", mode);
+    if (mode != OB_NOBATCH && mode != OB_BYDEPTH && mode != OB_BYAGENDA) return ctx_fail(ctx, OB_E_ARG, "unknown mode %d", mode);
     ctx->mode = mode;
     return OB_OK;
 }

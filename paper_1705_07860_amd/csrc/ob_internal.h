@@ -168,7 +168,7 @@ struct SchedHeader {
     u32 n_slots, n_chains, works_fwd, works_pull;
     u32 n_bedges, slot_sweeps, p0, p1;
 };
-enum : u32 { ERR_CYCLE = 1, ERR_COLLISION = 2, ERR_TABLE_FULL = 4, ERR_OVERFLOW = 8 };
+enum : u32 { ERR_CYCLE = 1, ERR_COLLISION = 2, ERR_TABLE_FULL = 4, ERR_OVERFLOW = 8, ERR_CLASSES = 16 };
 
 // All device pointers of one scheduled graph.  Passed by value to kernels.
 struct Tables {

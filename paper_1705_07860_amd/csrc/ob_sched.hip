@@ -248,6 +248,193 @@ __global__ __launch_bounds__(DEPTH_THREADS) void k_depth_partitioned(Tables T, c
     }
 }
 
+// ---- agenda-based batching (Section 3.2, second strategy) -------------------------------------------
+// The agenda holds the nodes whose operands are all resolved.  Each iteration takes every
+// available node of one signature as a batch; the signature is the one with the smallest average
+// depth over ALL nodes of the graph that carry it (a fixed number per signature), equal averages
+// go to the cheaper operation class (leaf < component-wise / copy < per-row reduction < matrix
+// product), then to the signature whose first node has the smaller id.  Because the priority of a
+// signature never changes, signatures are ranked once; the agenda is then one ready list per rank
+// and "select" is the lowest rank with a non-empty list.  The iteration index becomes the node's
+// step, and everything downstream (grouping by (step, signature), layout, launch plan) is shared
+// with depth-based batching.
+constexpr u32 AG_TABLE = 4096;        // open-addressing table of signatures
+constexpr u32 AG_MAX_CLASSES = 1024;  // distinct signatures an agenda plan can rank
+constexpr u32 AG_NONE = 0xffffffffu;
+
+struct AgendaTables {
+    u64 *keys;        // [AG_TABLE] signature hash, 0 = empty
+    u64 *sum;         // [AG_TABLE] sum of depths
+    u32 *cnt;         // [AG_TABLE] nodes
+    u32 *first;       // [AG_TABLE] smallest node id
+    u32 *op;          // [AG_TABLE] operation of the signature
+    u32 *rank_of;     // [AG_TABLE] rank of the signature in a table slot
+    u32 *seg_off;     // [AG_MAX_CLASSES + 1] ready-list segment of each rank inside `seg`
+    u32 *n_classes;   // [1]
+    u32 *cls;         // [n] rank of each node's signature
+    u32 *pending;     // [n] unresolved operands
+    u32 *seg;         // [n] ready lists, one segment per rank (each node is appended once)
+};
+
+__device__ inline u32 ag_cost_class(u32 op)
+{
+    if (op == OP_INPUT || op == OP_LOOKUP) return 0;
+    if (op == OP_MATVEC) return 3;
+    if (op == OP_PICK_NLS || op == OP_SQNORM) return 2;
+    return 1;
+}
+
+// per node: find / create the table entry of its signature and add (depth, 1, id) to it.  Lanes
+// of a wave that carry the same signature are combined first, so the table sees one update per
+// distinct signature per wave.
+__global__ void k_class_insert(Tables T, AgendaTables A)
+{
+    const u32 v = blockIdx.x * blockDim.x + threadIdx.x;
+    const u32 lane = threadIdx.x & 63;
+    const bool active = v < T.n;
+    const u64 sig = active ? (T.sig[v] ? T.sig[v] : 1ull) : 0ull;
+    const u32 depth = active ? T.step[v] : 0u;
+    u64 todo = __ballot(active);
+    u32 my_slot = 0;
+    while (todo) {
+        const u32 leader = (u32)__builtin_ctzll(todo);
+        const u64 lsig = ((u64)(u32)__builtin_amdgcn_readlane((int)(u32)(sig >> 32), leader) << 32) |
+                         (u32)__builtin_amdgcn_readlane((int)(u32)sig, leader);
+        const bool mine = active && sig == lsig;
+        const u64 match = __ballot(mine);
+        u32 dsum = mine ? depth : 0u;
+        for (int o = 32; o > 0; o >>= 1) dsum += __shfl_xor(dsum, o);
+        u32 slot = 0;
+        if (lane == leader) {
+            slot = (u32)(lsig * 0x9e3779b97f4a7c15ull >> 52) & (AG_TABLE - 1);
+            bool placed = false;
+            for (u32 probe = 0; probe < AG_TABLE; ++probe) {
+                const u64 old = atomicCAS((unsigned long long *)&A.keys[slot], 0ULL, (unsigned long long)lsig);
+                if (old == 0 || old == lsig) { placed = true; break; }
+                slot = (slot + 1) & (AG_TABLE - 1);
+            }
+            if (!placed) { atomicOr(&T.hdr->err, (u32)ERR_CLASSES); slot = 0; }
+            else {
+                atomicAdd(&A.cnt[slot], (u32)__popcll(match));
+                atomicAdd((unsigned long long *)&A.sum[slot], (unsigned long long)dsum);
+                atomicMin(&A.first[slot], v);     // the leader is the lowest matching lane: the smallest id of the wave
+                A.op[slot] = T.op[v];
+            }
+        }
+        slot = (u32)__builtin_amdgcn_readlane((int)slot, leader);
+        if (mine) my_slot = slot;
+        todo &= ~match;
+    }
+    if (active) T.ht_slot[v] = my_slot;
+}
+
+// One workgroup: collect the used table entries, rank them, lay out the ready-list segments.
+__global__ __launch_bounds__(1024) void k_class_rank(Tables T, AgendaTables A)
+{
+    __shared__ u32 s_n;
+    __shared__ u32 s_slot[AG_MAX_CLASSES];
+    __shared__ u64 s_sum[AG_MAX_CLASSES];
+    __shared__ u32 s_cnt[AG_MAX_CLASSES];
+    __shared__ u32 s_key2[AG_MAX_CLASSES];   // cost class
+    __shared__ u32 s_first[AG_MAX_CLASSES];
+    __shared__ u32 s_cnt_by_rank[AG_MAX_CLASSES];
+    const u32 tid = threadIdx.x;
+    if (tid == 0) s_n = 0;
+    __syncthreads();
+    for (u32 slot = tid; slot < AG_TABLE; slot += 1024) {
+        if (A.keys[slot] != 0) {
+            const u32 i = atomicAdd(&s_n, 1u);
+            if (i < AG_MAX_CLASSES) s_slot[i] = slot;
+        }
+    }
+    __syncthreads();
+    u32 C = s_n;
+    if (C > AG_MAX_CLASSES) { if (tid == 0) atomicOr(&T.hdr->err, (u32)ERR_CLASSES); C = AG_MAX_CLASSES; }
+    if (tid < C) {
+        const u32 slot = s_slot[tid];
+        s_sum[tid] = A.sum[slot]; s_cnt[tid] = A.cnt[slot];
+        s_key2[tid] = ag_cost_class(A.op[slot]); s_first[tid] = A.first[slot];
+    }
+    __syncthreads();
+    if (tid < C) {
+        // rank = number of signatures taken before this one (first ids differ, so the order is strict)
+        const u64 si = s_sum[tid]; const u32 ci = s_cnt[tid], ki = s_key2[tid], fi = s_first[tid];
+        u32 rank = 0;
+        for (u32 j = 0; j < C; ++j) {
+            const u64 lhs = s_sum[j] * ci, rhs = si * s_cnt[j];    // avg_j < avg_i  <=>  sum_j * cnt_i < sum_i * cnt_j
+            bool before = lhs < rhs;
+            if (lhs == rhs) before = s_key2[j] < ki || (s_key2[j] == ki && s_first[j] < fi);
+            rank += before ? 1u : 0u;
+        }
+        A.rank_of[s_slot[tid]] = rank;
+        s_cnt_by_rank[rank] = ci;
+    }
+    __syncthreads();
+    if (tid == 0) {
+        u32 acc = 0;
+        for (u32 r = 0; r < C; ++r) { A.seg_off[r] = acc; acc += s_cnt_by_rank[r]; }
+        A.seg_off[C] = acc;
+        A.n_classes[0] = C;
+    }
+}
+
+__global__ void k_class_of(Tables T, AgendaTables A)
+{
+    const u32 v = blockIdx.x * blockDim.x + threadIdx.x;
+    if (v >= T.n) return;
+    A.cls[v] = A.rank_of[T.ht_slot[v]];
+    A.pending[v] = T.indeg[v];
+}
+
+// One workgroup runs the agenda.  head / tail of every rank's ready list live in LDS; the lists
+// themselves, the dependency counters and the successor lists are in global memory (this
+// workgroup's L2).  Nodes that become available while a batch is being taken are appended behind
+// the batch's end, so a node never joins the batch of one of its own operands.
+constexpr int AGENDA_THREADS = 1024;
+__global__ __launch_bounds__(AGENDA_THREADS) void k_agenda(Tables T, AgendaTables A, const u32 *succ_node)
+{
+    __shared__ u32 s_head[AG_MAX_CLASSES], s_tail[AG_MAX_CLASSES], s_off[AG_MAX_CLASSES + 1];
+    __shared__ u32 s_min, s_done, s_t;
+    const u32 tid = threadIdx.x;
+    const u32 C = A.n_classes[0] < AG_MAX_CLASSES ? A.n_classes[0] : AG_MAX_CLASSES;
+    for (u32 c = tid; c < C; c += AGENDA_THREADS) { s_head[c] = 0; s_tail[c] = 0; }
+    for (u32 c = tid; c <= C; c += AGENDA_THREADS) s_off[c] = A.seg_off[c];
+    if (tid == 0) { s_min = AG_NONE; s_done = 0; s_t = 0; }
+    __syncthreads();
+    for (u32 v = tid; v < T.n; v += AGENDA_THREADS) {
+        if (A.pending[v] == 0) {
+            const u32 c = A.cls[v];
+            A.seg[s_off[c] + atomicAdd(&s_tail[c], 1u)] = v;
+        }
+    }
+    __syncthreads();
+    while (true) {
+        for (u32 c = tid; c < C; c += AGENDA_THREADS)
+            if (s_tail[c] > s_head[c]) atomicMin(&s_min, c);
+        __syncthreads();
+        const u32 c = s_min;
+        if (c == AG_NONE) break;          // nothing available: all done, or a cycle
+        const u32 lo = s_head[c], hi = s_tail[c], base = s_off[c], t = s_t;
+        __syncthreads();
+        for (u32 i = lo + tid; i < hi; i += AGENDA_THREADS) {
+            const u32 v = A.seg[base + i];
+            T.step[v] = t;
+            const u32 e1 = T.succ_off[v + 1];
+            for (u32 e = T.succ_off[v]; e < e1; ++e) {
+                const u32 sn = succ_node[e];
+                if (atomicSub(&A.pending[sn], 1u) == 1u) {
+                    const u32 cs = A.cls[sn];
+                    A.seg[s_off[cs] + atomicAdd(&s_tail[cs], 1u)] = sn;
+                }
+            }
+        }
+        __syncthreads();
+        if (tid == 0) { s_head[c] = hi; s_done += hi - lo; s_t = t + 1; s_min = AG_NONE; }
+        __syncthreads();
+    }
+    if (tid == 0 && s_done != T.n) atomicOr(&T.hdr->err, (u32)ERR_CYCLE);
+}
+
 // ---- stage 3: batch representative = smallest node id with the same (depth, signature) ------
 __device__ inline u64 batch_key(u64 sig, u32 step)
 {
@@ -1128,7 +1315,8 @@ int sched_enqueue(ob_ctx *ctx)
     Tables &T = ctx->T;
     hipStream_t s = ctx->sched_stream;
     const u32 n = T.n, E = T.E;
-    const int by_depth = ctx->mode == 1;
+    const int by_depth = ctx->mode != 0;   // batched: steps are depths (mode 1) or agenda iterations (mode 2)
+    const int agenda = ctx->mode == 2;
     ctx->n_launch_sched = 0;
 
     const size_t maxne = (size_t)(n > E ? n : E) + 1;
@@ -1185,6 +1373,13 @@ int sched_enqueue(ob_ctx *ctx)
     A(clay_in, CLay, n); A(clay_total, CLay, 1);
     u32 *bset, *blist;
     A(bset, u32, BSET_SIZE); A(blist, u32, BLIST_MAX);
+    AgendaTables AG{};
+    if (agenda) {
+        A(AG.keys, u64, AG_TABLE); A(AG.sum, u64, AG_TABLE); A(AG.cnt, u32, AG_TABLE); A(AG.first, u32, AG_TABLE);
+        A(AG.op, u32, AG_TABLE); A(AG.rank_of, u32, AG_TABLE); A(AG.seg_off, u32, AG_MAX_CLASSES + 1);
+        A(AG.n_classes, u32, 64);
+        AG.cls = ctx->tmp_u32_a; AG.pending = ctx->tmp_u32_b; AG.seg = T.queue;
+    }
     {
         size_t sb = prim_sort_scratch_bytes(maxne);
         size_t sc = prim_scan_scratch_bytes(maxne, sizeof(Lay));
@@ -1225,6 +1420,17 @@ int sched_enqueue(ob_ctx *ctx)
         else
             hipLaunchKernelGGL(k_depth_frontier, dim3(1), dim3(FRONTIER_THREADS), 0, s, T, succ_node);
         ++ctx->n_launch_sched;
+        if (agenda) {   // steps become agenda iterations; T.step holds the depths until k_agenda rewrites it
+            HIP_TRY(ctx, hipMemsetAsync(AG.keys, 0, (size_t)AG_TABLE * 8, s));
+            HIP_TRY(ctx, hipMemsetAsync(AG.sum, 0, (size_t)AG_TABLE * 8, s));
+            HIP_TRY(ctx, hipMemsetAsync(AG.cnt, 0, (size_t)AG_TABLE * 4, s));
+            HIP_TRY(ctx, hipMemsetAsync(AG.first, 0xff, (size_t)AG_TABLE * 4, s));
+            K(k_class_insert, n, T, AG);
+            hipLaunchKernelGGL(k_class_rank, dim3(1), dim3(1024), 0, s, T, AG);
+            K(k_class_of, n, T, AG);
+            hipLaunchKernelGGL(k_agenda, dim3(1), dim3(AGENDA_THREADS), 0, s, T, AG, succ_node);
+            ctx->n_launch_sched += 2;
+        }
         HIP_TRY(ctx, hipMemsetAsync(T.ht_keys, 0, (size_t)ht_size * 8, s));
         HIP_TRY(ctx, hipMemsetAsync(T.ht_vals, 0xff, (size_t)ht_size * 4, s));
         K(k_rep_insert, n, T);
@@ -1328,6 +1534,7 @@ int sched_finish(ob_ctx *ctx)
     if (ctx->hdr.err & ERR_COLLISION) return ctx_fail(ctx, -6, "signature hash collision detected");
     if (ctx->hdr.err & ERR_TABLE_FULL) return ctx_fail(ctx, -6, "signature table full");
     if (ctx->hdr.err & ERR_OVERFLOW) return ctx_fail(ctx, -5, "value arena exceeds 2^32 elements");
+    if (ctx->hdr.err & ERR_CLASSES) return ctx_fail(ctx, -6, "more than 1024 distinct signatures: agenda-based batching cannot rank them");
     const size_t words = (size_t)ctx->hdr.n_slots + 1;
     if (words <= ctx->hdr_window) {
         const SlotRec *sr = (const SlotRec *)(hp + 256);

@@ -83,6 +83,39 @@ def test_schedule_bit_exact(name, workload_cache):
     c.close()
 
 
+@pytest.mark.parametrize("name", ["rnn", "tagger", "tagger_char", "tree", "parser"])
+def test_agenda_schedule_bit_exact_and_parity(name, workload_cache):
+    """Agenda-based batching (Section 3.2): the GPU schedule equals the reference agenda schedule
+    bit for bit, and values and gradients still match the oracle."""
+    from paper_1705_07860_amd import binding as ob
+    p, g, o = workload_cache(name)
+    c, root = run_gpu(p, g, ob.OB_BYAGENDA)
+    bo, ids, bd, _ = c.schedule_read()
+    rbo, rids, rbs = S.by_agenda(g)
+    assert np.array_equal(bo, rbo)
+    assert np.array_equal(ids, rids)
+    assert np.array_equal(bd, rbs)
+    st = c.stats()
+    say(f"agenda {name}: batches={st['n_batches']} slots={st['n_slots']} sched {st['ms_schedule']:.3f} ms")
+    check_against_oracle(c, p, g, o, root, what=f"{name}/agenda")
+    c.close()
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_agenda_schedule_random_dags(seed):
+    from paper_1705_07860_amd import binding as ob
+    p, g = wl.random_dag(700 + seed, n_nodes=30 + 40 * seed, dim=4 + 2 * (seed % 3))
+    c, root = run_gpu(p, g, ob.OB_BYAGENDA, arena=64 << 20)
+    bo, ids, bd, _ = c.schedule_read()
+    rbo, rids, rbs = S.by_agenda(g)
+    assert np.array_equal(bo, rbo) and np.array_equal(ids, rids) and np.array_equal(bd, rbs)
+    o = Oracle(g, p, "f64")
+    o.forward()
+    o.backward(g.root)
+    check_against_oracle(c, p, g, o, root, what=f"agenda dag{seed}")
+    c.close()
+
+
 @pytest.mark.parametrize("seed", range(6))
 def test_schedule_bit_exact_random_dags(seed):
     from paper_1705_07860_amd import binding as ob

@@ -172,9 +172,8 @@ def test_state_and_argument_errors_without_a_device():
     with pytest.raises(ob.ObError) as e:
         c.value_read(0, 32)
     assert e.value.code == -6
-    with pytest.raises(ob.ObError) as e:
-        c.set_mode(ob.OB_BYAGENDA)
-    assert e.value.code == -6
+    c.set_mode(ob.OB_BYAGENDA)
+    c.set_mode(ob.OB_BYDEPTH)
     with pytest.raises(ob.ObError) as e:
         c.set_mode(17)
     assert e.value.code == -8
