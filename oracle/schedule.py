@@ -19,8 +19,9 @@ operands are all resolved; each iteration takes every available node of one
 signature as a batch, and the signature is chosen by the smallest average
 depth of all nodes of the graph that carry it.  Readings where the text leaves
 a choice: averages are compared exactly (cross-multiplied integers); equal
-averages go to the cheaper operation class (the footnote's "cheap before
-heavy": leaf < component-wise / copy < per-row reduction < matrix product),
+averages go to the cheaper operation class (the section's footnote orders
+ties from inexpensive component-wise work to matrix products; here: leaf <
+component-wise / copy < per-row reduction < matrix product),
 then to the signature whose first node has the smaller id.
 """
 from __future__ import annotations
