@@ -460,9 +460,72 @@ __device__ inline void matvec_fwd_tile(const Tables &T, const TileDesc &d, float
 // 16x16 output tiles (v_mfma_f32_16x16x4f32: lane l supplies A[l%16][l/16] and B[l/16][l%16];
 // accumulator register v of lane l is C[4*(l/16) + v][l%16]); the DX_WAVES waves split the
 // contraction, lane quarter q takes the four consecutive indices 4q..4q+3 of every block of 16.
+// Batches with many rows: 32x32 dX tiles (v_mfma_f32_32x32x2f32), the DX_WAVES waves split the
+// contraction over the rows of W and their blocks are summed through LDS in wave order.
+__device__ inline void matvec_dx_tile_wide(const Tables &T, const TileDesc &d, float *lds)
+{
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    const u32 l32 = lane & 31, h = lane >> 5;
+    const u32 K = d.k, m = d.d;
+    const u32 ntn = (K + DXTW - 1) / DXTW;
+    const u32 r0 = (d.t / ntn) * DXTW, c0 = (d.t % ntn) * DXTW;
+    const u32 row = r0 + l32, col = c0 + l32;
+    const bool row_ok = row < d.B, col_ok = col < K;
+    const u32 grow_row = row_ok ? row : r0;
+    const float *grow = T.G + ((d.flags & TF_G_ALIAS) ? ((d.contig & 1u) ? d.base[0] + (grow_row - r0) * d.sstride[0]
+                                                                             : T.dx_gsrc[d.pos0 + grow_row])
+                                                        : d.val_off + grow_row * m);
+    gl_float *wcol = as_global(d.w) + (col_ok ? col : 0u);
+    const bool fast = (m & 3u) == 0;
+    u32 lo, hi;
+    wave_range<DX_WAVES>(m, lo, hi);
+    floatx16 acc;
+    for (int v = 0; v < 16; ++v) acc[v] = 0.f;
+    const float4 z4 = make_float4(0.f, 0.f, 0.f, 0.f);
+    for (u32 ib = lo; ib < hi; ib += 8 * KU) {
+        float4 a[KU], b[KU];
+#pragma unroll
+        for (int u = 0; u < KU; ++u) {
+            const u32 i0 = ib + 8 * u + 4 * h;
+            const bool in = ib + 8 * u < hi && i0 < m;
+            if (fast) {
+                a[u] = (in && row_ok) ? ld4(grow + i0) : z4;
+                if (in && col_ok) {
+                    gl_float *wp = wcol + (size_t)i0 * K;
+                    b[u] = make_float4(wp[0], wp[K], wp[2 * (size_t)K], wp[3 * (size_t)K]);
+                } else {
+                    b[u] = z4;
+                }
+            } else {
+                float av[4] = {0.f, 0.f, 0.f, 0.f}, bv[4] = {0.f, 0.f, 0.f, 0.f};
+                for (int s = 0; s < 4; ++s)
+                    if (in && i0 + s < m) {
+                        if (row_ok) av[s] = grow[i0 + s];
+                        if (col_ok) bv[s] = wcol[(size_t)(i0 + s) * K];
+                    }
+                a[u] = make_float4(av[0], av[1], av[2], av[3]);
+                b[u] = make_float4(bv[0], bv[1], bv[2], bv[3]);
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < KU; ++u) acc = mfma4(a[u], b[u], acc);
+    }
+    float out[16 / DX_WAVES];
+    reduce_waves<DX_WAVES>(acc, lds, out);
+    if (col_ok) {
+        float *dX = T.G + d.dx_off;
+        for (int i = 0; i < 16 / DX_WAVES; ++i) {
+            const int v = (16 / DX_WAVES) * w + i;
+            const u32 rr = r0 + 8 * (v >> 2) + 4 * h + (v & 3);
+            if (rr < d.B) dX[(size_t)rr * K + col] = out[i];
+        }
+    }
+}
+
 typedef float floatx4 __attribute__((ext_vector_type(4)));
 __device__ inline void matvec_dx_tile(const Tables &T, const TileDesc &d, float *lds)
 {
+    if (dx_tile_edge(d.flags, d.k) == (u32)DXTW) { matvec_dx_tile_wide(T, d, lds); return; }
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
     const u32 l16 = lane & 15, q = lane >> 4;
     const u32 K = d.k, m = d.d;

@@ -23,6 +23,9 @@ constexpr int GT = 32;                // forward / dW GEMM tile edge (one 32x32 
 constexpr int GTW = 64;               // forward GEMM tile edge of batches with at least WIDE_MIN_ROWS rows
 constexpr u32 WIDE_MIN_ROWS = 256;
 constexpr int DXT = 16;               // dX GEMM tile edge (16x16 blocks: its output is small, more tiles fill more CUs)
+constexpr int DXTW = 32;              // dX tile edge of batches with at least WIDE_MIN_ROWS rows (when the matrix has 32+ columns)
+// 8u = TF_WIDE of the batch flags
+__host__ __device__ inline u32 dx_tile_edge(u32 batch_flags, u32 k) { return ((batch_flags & 8u) && k >= (u32)DXTW) ? (u32)DXTW : (u32)DXT; }
 constexpr int ROWS_PER_RED_TILE = 4;  // rows of one row-reduction tile (one wave per row)
 constexpr int WIDE_ADD_ARITY = 9;     // ADD with at least this many operands reduces per row
 constexpr u32 VAL_ALIGN = 64;         // batch blocks start at multiples of 64 floats (256 B)

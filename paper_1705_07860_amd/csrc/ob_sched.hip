@@ -844,7 +844,8 @@ __global__ void k_chain_recs(Tables T, const u32 *flag, const u32 *flag_excl, CL
             switch (r0.op) {
             case OP_MATVEC: {
                 const u32 gt = (r0.vec4 & TF_WIDE) ? (u32)GTW : (u32)GT;
-                L.tf = cdiv(r0.B, gt) * cdiv(r0.d, gt); L.tb = cdiv(r0.B, DXT) * cdiv(r0.k, DXT);
+                const u32 dt = dx_tile_edge(r0.vec4, r0.k);
+                L.tf = cdiv(r0.B, gt) * cdiv(r0.d, gt); L.tb = cdiv(r0.B, dt) * cdiv(r0.k, dt);
                 break;
             }
             case OP_PICK_NLS:
@@ -977,9 +978,10 @@ __device__ inline void fill_tile_desc(const Tables &T, const BatchRec &r, u32 t,
         // dX tile: rows (t / ntn) * DXT ...; with TF_G_ALIAS the gradient rows are read where the
         // consumer left them, evenly spaced or through the per-row list
         if (r.vec4 & TF_G_ALIAS) {
-            const u32 ntn = (r.k + DXT - 1) / DXT;
-            const u32 r_lo = (t / ntn) * DXT;
-            u32 r_hi = r_lo + DXT - 1;
+            const u32 dt = dx_tile_edge(r.vec4, r.k);
+            const u32 ntn = (r.k + dt - 1) / dt;
+            const u32 r_lo = (t / ntn) * dt;
+            u32 r_hi = r_lo + dt - 1;
             if (r_hi >= r.B) r_hi = r.B - 1;
             const u32 *gs = T.dx_gsrc + r.pos0;
             const u32 base = gs[r_lo];
