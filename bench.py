@@ -231,6 +231,17 @@ def main():
                               bwd_tflops=round(cost["bwd_flops"] / (phase["ms_backward"] * 1e-3) / 1e12, 3),
                               peak=MFMA_FP32_PEAK_TFLOPS))
 
+    # What bounds the step: the dependent launches (measured floor of a launch boundary on this
+    # machine x launches per step) against the time the algorithmic bytes and flops would take at
+    # the chip's peaks.
+    floor_us = ctxs[0].test_launch_cost(2000, 0)
+    n_launch_step = (launches["n_launch_fwd"] + launches["n_launch_bwd"]) / args.steps
+    t_peak_ms = ((cost["fwd_bytes"] + cost["bwd_bytes"]) / (HBM_PEAK_GBS * 1e9) +
+                 (cost["fwd_flops"] + cost["bwd_flops"]) / (MFMA_FP32_PEAK_TFLOPS * 1e12)) / args.steps * 1e3
+    launch_model = dict(launch_floor_us=round(floor_us, 3), exec_launches_per_step=round(n_launch_step, 1),
+                        t_launch_ms=round(n_launch_step * floor_us * 1e-3, 4), t_at_peaks_ms=round(t_peak_ms, 4),
+                        exec_ms_per_step=round((phase["ms_forward"] + phase["ms_backward"]) / args.steps, 4))
+
     if args.copy_calibration:
         nbytes = args.copy_calibration << 20
         src = torch.empty(nbytes // 4, dtype=torch.float32, device="cuda").normal_()
@@ -299,6 +310,7 @@ def main():
         "upload_ms_host_to_hbm": round(float(np.mean(t_up)) * 1e3, 3),
         "value_including_upload": round(n_inst / (elapsed + float(np.mean(t_up)) * args.steps), 2),
         "roofline": roofline,
+        "launch_model": launch_model,
         "nobatch_gpu": nobatch,
         "cpu_baseline": cpu,
         "paper_context": "Table 1, BiLSTM, ByDepth on a Tesla K80: 337 sentences/s (other hardware and dimensions)",
