@@ -31,7 +31,8 @@ def algorithmic_cost(g, params, batch_off, node_ids):
     """Bytes and flops the method itself must move / do for one forward+backward of this
     schedule (per-batch formulas: operands read once, results written once, one 4-byte row index
     per gathered operand row; a shared matrix is read once per batch; dW is read-modify-written
-    once per parameter because its reduction is deferred over all uses)."""
+    once per parameter because its reduction is deferred over all uses).  bwd_bytes covers the
+    backward step kernel (gradient pull and dX), param_bytes the deferred dW / db / dE kernels."""
     heads = node_ids[batch_off[:-1]]
     B = np.diff(batch_off).astype(np.float64)
     op = g.op[heads].astype(np.int64)
@@ -63,12 +64,13 @@ def algorithmic_cost(g, params, batch_off, node_ids):
     bb[m] = (8 * k * B)[m]
     m = op == wl.OP_MATVEC
     fb[m] = (4 * (d * k + k * B + d * B) + R_IDX * B)[m]
-    bb[m] = (4 * (d * k + d * B + k * B) + 4 * (d * B + k * B))[m]
+    bb[m] = (4 * (d * k + d * B + k * B))[m]                 # dX = G W in the backward step kernel
+    pg = float((4 * (d * B + k * B))[m].sum())               # dW = G^T X in the deferred parameter kernels
     fl_f[m] = (2 * d * k * B)[m]
     fl_b[m] = (4 * d * k * B)[m]
     used_w = np.unique(g.param[g.op == wl.OP_MATVEC])
     dW_rmw = float(sum(8 * params.mats[int(p)].size for p in used_w))
-    return dict(fwd_bytes=float(fb.sum()), bwd_bytes=float(bb.sum()) + dW_rmw,
+    return dict(fwd_bytes=float(fb.sum()), bwd_bytes=float(bb.sum()), param_bytes=pg + dW_rmw,
                 fwd_flops=float(fl_f.sum()), bwd_flops=float(fl_b.sum()))
 
 
@@ -204,7 +206,7 @@ def main():
     value = n_inst / elapsed
 
     # algorithmic bytes / flops from the realised schedules
-    cost = dict(fwd_bytes=0.0, bwd_bytes=0.0, fwd_flops=0.0, bwd_flops=0.0)
+    cost = dict(fwd_bytes=0.0, bwd_bytes=0.0, param_bytes=0.0, fwd_flops=0.0, bwd_flops=0.0)
     for i in range(args.steps):
         j = (args.warmup + i) % pool
         if "cost" not in graphs[j].meta:
@@ -213,20 +215,27 @@ def main():
         for k_ in cost:
             cost[k_] += graphs[j].meta["cost"][k_]
 
-    # Dominant kernel: k_fwd_step, the forward step interpreter (the largest total in the kernel
-    # trace).  Its launches are bracketed by HIP events on the execution stream (ms_forward), so
-    # the average launch duration below is measured live; the backward pair is reported beside it.
+    # Dominant kernel: the forward step interpreter (k_fwd_step) or the backward one (k_bwd_step),
+    # whichever took more of the timed region.  Each kernel's launches are bracketed by HIP events on
+    # the execution stream (forward: ms_forward; backward: ms_backward minus the three deferred
+    # parameter-gradient kernels, which have events of their own), so the average launch duration
+    # is measured live.  The other kernel is reported beside it.
     fwd_ms, n_fwd = phase["ms_forward"], max(launches["n_launch_fwd"], 1)
     bwd_ms, n_bwd = phase["ms_backward"] - phase["ms_param_grads"], max(launches["n_launch_bwd"], 1)
-    achieved = cost["fwd_bytes"] / (fwd_ms * 1e-3) / 1e9
-    roofline = dict(bound="hbm", kernel="k_fwd_step", achieved=round(achieved, 2), peak=HBM_PEAK_GBS, unit="GB/s",
-                    frac=round(achieved / HBM_PEAK_GBS, 5), traffic=stored_traffic(args, "k_fwd_step"),
-                    launches=launches["n_launch_fwd"], avg_launch_us=round(fwd_ms * 1e3 / n_fwd, 3),
-                    algorithmic_bytes_per_launch=round(cost["fwd_bytes"] / n_fwd, 1),
-                    backward=dict(kernel="k_bwd_step",
-                                  achieved=round(cost["bwd_bytes"] / (bwd_ms * 1e-3) / 1e9, 2),
-                                  launches=launches["n_launch_bwd"], avg_launch_us=round(bwd_ms * 1e3 / n_bwd, 3),
-                                  algorithmic_bytes_per_launch=round(cost["bwd_bytes"] / n_bwd, 1)),
+
+    def kernel_figures(name, ms, nl, nbytes):
+        ach = nbytes / (ms * 1e-3) / 1e9
+        return dict(kernel=name, achieved=round(ach, 2), frac=round(ach / HBM_PEAK_GBS, 5), launches=nl,
+                    avg_launch_us=round(ms * 1e3 / nl, 3), algorithmic_bytes_per_launch=round(nbytes / nl, 1),
+                    traffic=stored_traffic(args, name))
+
+    kf = kernel_figures("k_fwd_step", fwd_ms, n_fwd, cost["fwd_bytes"])
+    kb = kernel_figures("k_bwd_step", bwd_ms, n_bwd, cost["bwd_bytes"])
+    dom, other = (kb, kf) if bwd_ms >= fwd_ms else (kf, kb)
+    roofline = dict(bound="hbm", kernel=dom["kernel"], achieved=dom["achieved"], peak=HBM_PEAK_GBS, unit="GB/s",
+                    frac=dom["frac"], traffic=dom["traffic"], launches=dom["launches"],
+                    avg_launch_us=dom["avg_launch_us"], algorithmic_bytes_per_launch=dom["algorithmic_bytes_per_launch"],
+                    other_step_kernel=other,
                     mfma=dict(fwd_tflops=round(cost["fwd_flops"] / (phase["ms_forward"] * 1e-3) / 1e12, 3),
                               bwd_tflops=round(cost["bwd_flops"] / (phase["ms_backward"] * 1e-3) / 1e12, 3),
                               peak=MFMA_FP32_PEAK_TFLOPS))
@@ -236,7 +245,7 @@ def main():
     # the chip's peaks.
     floor_us = ctxs[0].test_launch_cost(2000, 0)
     n_launch_step = (launches["n_launch_fwd"] + launches["n_launch_bwd"]) / args.steps
-    t_peak_ms = ((cost["fwd_bytes"] + cost["bwd_bytes"]) / (HBM_PEAK_GBS * 1e9) +
+    t_peak_ms = ((cost["fwd_bytes"] + cost["bwd_bytes"] + cost["param_bytes"]) / (HBM_PEAK_GBS * 1e9) +
                  (cost["fwd_flops"] + cost["bwd_flops"]) / (MFMA_FP32_PEAK_TFLOPS * 1e12)) / args.steps * 1e3
     launch_model = dict(launch_floor_us=round(floor_us, 3), exec_launches_per_step=round(n_launch_step, 1),
                         t_launch_ms=round(n_launch_step * floor_us * 1e-3, 4), t_at_peaks_ms=round(t_peak_ms, 4),
