@@ -150,7 +150,7 @@ __global__ __launch_bounds__(DEPTH_THREADS) void k_depth_partitioned(Tables T, c
     __shared__ unsigned short s_queue[DEPTH_PART];
     __shared__ u32 s_soff[DEPTH_PART + 1];
     __shared__ u32 s_snode[DEPTH_SCAP];
-    __shared__ u32 s_head, s_tail, s_next, s_done, s_seen, s_in_cnt, s_fail;
+    __shared__ u32 s_next, s_done;
     const u32 tid = threadIdx.x;
     const u32 k = blockIdx.x;
     const u32 lo = k * DEPTH_PART;
@@ -158,7 +158,7 @@ __global__ __launch_bounds__(DEPTH_THREADS) void k_depth_partitioned(Tables T, c
     const u32 cnt = hi - lo;
     const u32 ebase = T.succ_off[lo];
     const u32 ecnt = T.succ_off[hi] - ebase;
-    if (tid == 0) { s_head = 0; s_tail = 0; s_next = 0; s_done = 0; s_seen = 0; s_in_cnt = 0; s_fail = 0; }
+    if (tid == 0) { s_next = 0; s_done = 0; }
     __syncthreads();
     for (u32 i = tid; i < cnt; i += DEPTH_THREADS) {
         const u32 v = lo + i;
@@ -172,75 +172,74 @@ __global__ __launch_bounds__(DEPTH_THREADS) void k_depth_partitioned(Tables T, c
     if (tid == 0) s_soff[cnt] = ecnt;
     for (u32 e = tid; e < ecnt && e < DEPTH_SCAP; e += DEPTH_THREADS) s_snode[e] = succ_node[ebase + e];
     __syncthreads();
-    if (tid == 0) s_tail = s_next;
-    __syncthreads();
-    u32 spin = 0, iter = 0;
-    while (true) {
-        const u32 head = s_head, tail = s_tail;
-        if (head == tail && s_done == cnt) break;
-        // One thread looks at the inbox, but only when the frontier is empty or every 8th pass:
-        // the load goes to coherent memory and the next barrier waits for it.  (Nothing else in the
-        // loop touches global memory unless an edge leaves the range: depths stay in LDS and are
-        // written out once at the end.)
-        const bool poll = head == tail || (iter & 7u) == 0;
-        ++iter;
-        if (poll && tid == DEPTH_THREADS - 1)
-            s_in_cnt = __hip_atomic_load(&inbox_tail[k], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        for (u32 i = head + tid; i < tail; i += DEPTH_THREADS) {
-            const u32 ul = s_queue[i];
-            const u32 d = s_dep[ul];
-            const u32 e1 = s_soff[ul + 1];
-            for (u32 e = s_soff[ul]; e < e1; ++e) {
-                const u32 sn = e < DEPTH_SCAP ? s_snode[e] : succ_node[ebase + e];
-                if (sn < hi) {   // successors have larger ids than u, so sn >= lo
-                    const u32 sl = sn - lo;
-                    atomicMax(&s_dep[sl], d + 1);
-                    if (atomicSub(&s_pending[sl], 1u) == 1u) s_queue[atomicAdd(&s_next, 1u)] = (unsigned short)sl;
-                } else {
-                    atomicMax(&g_dep[sn], d + 1);
-                    __threadfence();
-                    if (atomicSub(&T.ext_left[sn], 1u) == 1u) {
-                        const u32 k2 = sn / DEPTH_PART;
-                        const u32 slot = atomicAdd(&inbox_tail[k2], 1u);
-                        __hip_atomic_store(&inbox[k2 * DEPTH_PART + slot], sn, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+    // The frontier of a range is small (tens of nodes per level), so after the cooperative set-up
+    // one wave runs the loop alone: its LDS operations complete in program order, the loop state
+    // sits in registers, and no workgroup barrier is needed between levels.  The other waves wait
+    // at the barrier behind the loop and help with the write-out.
+    if (tid < 64) {
+        const u32 lane = tid;
+        u32 head = 0, tail = __builtin_amdgcn_readfirstlane(s_next), done = 0, seen = 0, avail = 0, spin = 0, iter = 0;
+        while (!(head == tail && done == cnt)) {
+            // The inbox counter lives in coherent memory: look at it only when the frontier is
+            // empty or every 8th pass.  (Nothing else in the loop touches global memory unless an
+            // edge leaves the range: depths stay in LDS and are written out once at the end.)
+            if (head == tail || (iter & 7u) == 0)
+                avail = __builtin_amdgcn_readfirstlane(__hip_atomic_load(&inbox_tail[k], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+            ++iter;
+            for (u32 i = head + lane; i < tail; i += 64) {
+                const u32 ul = s_queue[i];
+                const u32 d = s_dep[ul];
+                const u32 e1 = s_soff[ul + 1];
+                for (u32 e = s_soff[ul]; e < e1; ++e) {
+                    const u32 sn = e < DEPTH_SCAP ? s_snode[e] : succ_node[ebase + e];
+                    if (sn < hi) {   // successors have larger ids than u, so sn >= lo
+                        const u32 sl = sn - lo;
+                        atomicMax(&s_dep[sl], d + 1);
+                        if (atomicSub(&s_pending[sl], 1u) == 1u) s_queue[atomicAdd(&s_next, 1u)] = (unsigned short)sl;
+                    } else {
+                        atomicMax(&g_dep[sn], d + 1);
+                        __threadfence();
+                        if (atomicSub(&T.ext_left[sn], 1u) == 1u) {
+                            const u32 k2 = sn / DEPTH_PART;
+                            const u32 slot = atomicAdd(&inbox_tail[k2], 1u);
+                            __hip_atomic_store(&inbox[k2 * DEPTH_PART + slot], sn, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+                        }
                     }
                 }
             }
-        }
-        __syncthreads();
-        // inbox entries are posted after their slot is reserved: take them in order, stop at a hole
-        {
-            const u32 seen = s_seen, avail = s_in_cnt;
-            for (u32 j = seen + tid; j < avail; j += DEPTH_THREADS) {
-                const u32 sn = __hip_atomic_load(&inbox[k * DEPTH_PART + j], __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_AGENT);
-                if (sn == 0xffffffffu) { atomicMin(&s_in_cnt, j); continue; }
+            __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
+            // inbox entries are posted after their slot is reserved: take them in order, stop at a hole
+            while (seen < avail) {
+                const u32 j = seen + lane;
+                u32 sn = 0xffffffffu;
+                if (j < avail) sn = __hip_atomic_load(&inbox[k * DEPTH_PART + j], __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_AGENT);
+                const u32 in_chunk = avail - seen < 64u ? avail - seen : 64u;
+                const u64 holes = __ballot(j < avail && sn == 0xffffffffu);
+                const u32 good = holes ? (u32)__builtin_ctzll(holes) : in_chunk;
+                if (lane < good) {
+                    const u32 sl = sn - lo;
+                    atomicMax(&s_dep[sl], __hip_atomic_load(&g_dep[sn], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+                    if (atomicSub(&s_pending[sl], 1u) == 1u) s_queue[atomicAdd(&s_next, 1u)] = (unsigned short)sl;
+                }
+                seen += good;
+                if (holes) break;
             }
-            __syncthreads();
-            const u32 upto = s_in_cnt;
-            for (u32 j = seen + tid; j < upto; j += DEPTH_THREADS) {
-                const u32 sn = __hip_atomic_load(&inbox[k * DEPTH_PART + j], __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_AGENT);
-                const u32 sl = sn - lo;
-                atomicMax(&s_dep[sl], __hip_atomic_load(&g_dep[sn], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
-                if (atomicSub(&s_pending[sl], 1u) == 1u) s_queue[atomicAdd(&s_next, 1u)] = (unsigned short)sl;
-            }
-            __syncthreads();
-            if (tid == 0) {
-                s_seen = upto;
-                s_done += tail - head;
-                s_head = tail;
-                s_tail = s_next;
+            __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
+            const u32 new_tail = __builtin_amdgcn_readfirstlane(s_next);
+            done += tail - head;
+            const bool idle = head == tail && new_tail == tail;   // nothing to do: waiting for another range
+            head = tail;
+            tail = new_tail;
+            if (idle) {
+                if (++spin > DEPTH_SPIN_LIMIT) break;
+                __builtin_amdgcn_s_sleep(8);
+            } else {
+                spin = 0;
             }
         }
-        __syncthreads();
-        if (head == tail && s_tail == tail) {   // nothing to do: waiting for another range
-            if (++spin > DEPTH_SPIN_LIMIT) { if (tid == 0) s_fail = 1; }
-            __builtin_amdgcn_s_sleep(8);
-        } else {
-            spin = 0;
-        }
-        __syncthreads();
-        if (s_fail) break;
+        if (lane == 0) s_done = done;
     }
+    __syncthreads();
     for (u32 i = tid; i < cnt; i += DEPTH_THREADS) T.step[lo + i] = s_dep[i];
     if (tid == 0) {
         atomicAdd(&T.hdr->frontier_done, s_done);
