@@ -240,6 +240,12 @@ def main():
                               bwd_tflops=round(cost["bwd_flops"] / (phase["ms_backward"] * 1e-3) / 1e12, 3),
                               peak=MFMA_FP32_PEAK_TFLOPS))
 
+    # batch-size histogram of the first pooled minibatch's schedule (bins: 1, 2-3, 4-7, ...)
+    bo0 = ctxs[0].schedule_read()[0]
+    sizes = np.diff(bo0)
+    bins = np.floor(np.log2(np.maximum(sizes, 1))).astype(np.int64)
+    batch_hist = {f"{1 << b}-{(2 << b) - 1}": int(c) for b, c in enumerate(np.bincount(bins)) if c}
+
     # What bounds the step: the dependent launches (measured floor of a launch boundary on this
     # machine x launches per step) against the time the algorithmic bytes and flops would take at
     # the chip's peaks.
@@ -315,7 +321,7 @@ def main():
         "phase_ms_per_step": {k_: round(v / args.steps, 4) for k_, v in phase.items()},
         "launches_per_step": {k_: round(v / args.steps, 1) for k_, v in launches.items()},
         "depth_levels": per_ctx_stats[0]["n_steps"], "launch_slots": per_ctx_stats[0]["n_slots"],
-        "batches": per_ctx_stats[0]["n_batches"],
+        "batches": per_ctx_stats[0]["n_batches"], "batch_size_histogram": batch_hist,
         "upload_ms_host_to_hbm": round(float(np.mean(t_up)) * 1e3, 3),
         "value_including_upload": round(n_inst / (elapsed + float(np.mean(t_up)) * args.steps), 2),
         "roofline": roofline,

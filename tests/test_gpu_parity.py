@@ -458,3 +458,60 @@ def test_stacked_matrix_products():
     assert np.array_equal(bo, rbo) and np.array_equal(ids, rids) and np.array_equal(bd, rbd)
     check_against_oracle(c, p, g, o, root, what="stacked")
     c.close()
+
+
+def test_long_chain_uses_the_unfused_plan_and_the_long_slot_table():
+    """More batches than a fused launch plan can hold (4096) and more launch slots than the
+    read-back window (2048): a 4300-deep chain of alternating tanh / sigmoid nodes runs with one
+    launch per depth level and still matches the oracle."""
+    from paper_1705_07860_amd import binding as ob
+    rng = np.random.default_rng(77)
+    pb = wl.ParamBuilder(rng, std=0.5)
+    E = pb.add("E", 3, 8)
+    p = pb.done()
+    gb = wl.GraphBuilder(p)
+    x = gb.lookup(E, 1)
+    y = gb.lookup(E, 2)
+    for i in range(4300):
+        x = gb.tanh(x) if i % 2 else gb.sigmoid(x)
+        if i % 500 == 0:
+            x = gb.add((x, y))
+    g = gb.finish(gb.sqnorm(x), 1)
+    o = Oracle(g, p, "f64")
+    o.forward()
+    o.backward(g.root)
+    c, root = run_gpu(p, g, ob.OB_BYDEPTH, arena=64 << 20)
+    st = c.stats()
+    assert st["n_batches"] > 4096 and st["n_slots"] == st["n_steps"] > 2048
+    bo, ids, bd, _ = c.schedule_read()
+    rbo, rids, rbd = S.by_depth(g)
+    assert np.array_equal(bo, rbo) and np.array_equal(ids, rids) and np.array_equal(bd, rbd)
+    check_against_oracle(c, p, g, o, root, what="long chain")
+    c.close()
+
+
+def test_agenda_rejects_more_signatures_than_it_can_rank():
+    """1100 slices with pairwise different ranges are 1100 signatures; agenda mode ranks at most
+    1024 and must fail cleanly (depth-based batching takes the same graph)."""
+    from paper_1705_07860_amd import binding as ob
+    rng = np.random.default_rng(78)
+    pb = wl.ParamBuilder(rng, std=0.5)
+    E = pb.add("E", 2, 1200)
+    p = pb.done()
+    gb = wl.GraphBuilder(p)
+    x = gb.lookup(E, 0)
+    parts = [gb.sqnorm(gb.slice(x, i, i + 3)) for i in range(1100)]
+    g = gb.finish(gb.add(parts), 1)
+    c = ob.Context(arena_bytes=64 << 20, mode=ob.OB_BYAGENDA)
+    c.params_create(p)
+    c.add_bulk(g)
+    with pytest.raises(ob.ObError) as e:
+        c.forward(g.root)
+    assert e.value.code == -6
+    c.close()
+    o = Oracle(g, p, "f64")
+    o.forward()
+    o.backward(g.root)
+    c, root = run_gpu(p, g, ob.OB_BYDEPTH, arena=64 << 20)
+    check_against_oracle(c, p, g, o, root, what="many signatures")
+    c.close()
