@@ -359,3 +359,42 @@ def test_float_build_tracks_double_build(workload_cache):
     o32.backward(g.root)
     assert rel_err(o32.val, o.val) < 1e-5
     assert rel_err(o32.pgrad, o.pgrad) < 1e-5
+
+
+def test_signature_examples_from_the_paper():
+    """tests/golden/signature_examples.txt restates the signature examples of Section 3.2 and
+    Appendix A; for every line two nodes that differ only in a 'must not depend on' field share
+    a signature and nodes that differ in a 'must contain' field do not."""
+    import os
+    from oracle import schedule as S
+    from paper_1705_07860_amd import workloads as wl
+    path = os.path.join(os.path.dirname(__file__), "golden", "signature_examples.txt")
+    rows = [ln.split("|") for ln in open(path) if ln.strip() and not ln.startswith("#")]
+    kinds = [r[0].strip() for r in rows]
+    assert kinds == ["tanh", "slice", "matvec", "affine"] and all(len(r) == 4 for r in rows)
+    rng = np.random.default_rng(5)
+    pb = wl.ParamBuilder(rng)
+    A1, A2 = pb.add("A1", 256, 256), pb.add("A2", 256, 256)
+    B1 = pb.add("B1", 256, 400)
+    y1, y2 = pb.add("y1", 256, 1), pb.add("y2", 256, 1)
+    p = pb.done()
+    gb = wl.GraphBuilder(p)
+    u, v = gb.input(np.ones(256)), gb.input(np.zeros(256))
+    w = gb.input(np.ones(400))
+    big1, big2 = gb.input(np.ones(500)), gb.input(np.zeros(500))
+    nodes = dict(
+        tanh_a=gb.tanh(u), tanh_b=gb.tanh(v), sig=gb.sigmoid(u),
+        sl_a=gb.slice(big1, 100, 200), sl_b=gb.slice(big2, 100, 200), sl_range=gb.slice(big1, 100, 201),
+        sl_size=gb.slice(gb.input(np.ones(400)), 100, 200),
+        mv_a=gb.matvec(A1, -1, u), mv_b=gb.matvec(A1, -1, v), mv_param=gb.matvec(A2, -1, u), mv_size=gb.matvec(B1, -1, w),
+        af_a=gb.matvec(A1, y1, u), af_b=gb.matvec(A1, y1, v), af_bias=gb.matvec(A1, y2, u), af_none=gb.matvec(A1, -1, u),
+    )
+    g = gb.finish(gb.sqnorm(nodes["tanh_a"]), 1)
+    s = {k: S.signature(g, n) for k, n in nodes.items()}
+    same = [("tanh_a", "tanh_b"), ("sl_a", "sl_b"), ("mv_a", "mv_b"), ("af_a", "af_b"), ("mv_a", "af_none")]
+    differ = [("tanh_a", "sig"), ("sl_a", "sl_range"), ("sl_a", "sl_size"), ("mv_a", "mv_param"), ("mv_a", "mv_size"),
+              ("af_a", "af_bias"), ("af_a", "mv_a")]
+    for a, b in same:
+        assert s[a] == s[b], (a, b)
+    for a, b in differ:
+        assert s[a] != s[b], (a, b)
