@@ -106,6 +106,9 @@ def main():
     ap.add_argument("--no-fusion", action="store_true", help="one launch per depth level")
     ap.add_argument("--placement", default="late", choices=["early", "late"],
                     help="fused plans launch a batch as early as its operands / as late as its consumers allow")
+    ap.add_argument("--update", action="store_true",
+                    help="close every step with the gradient-descent update of Section 2 (lr 0) instead of only "
+                         "zeroing the gradients; the headline metric is forward + backward, so this is off by default")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
     ap.add_argument("--no-nobatch", action="store_true", help="skip the unbatched GPU leg")
     ap.add_argument("--cpu-samples", type=int, default=4)
@@ -168,9 +171,12 @@ def main():
     def execute(i):
         c = ctxs[i % pool]
         g = graphs[i % pool]
-        c.param_grad_zero()
+        if not args.update:
+            c.param_grad_zero()
         c.forward(g.root)
         c.backward(g.root)
+        if args.update:
+            c.sgd_step(0.0, zero_grad=True)    # lr 0 keeps the pooled minibatches' numbers stationary
 
     def run(first, count):
         if pipeline:
@@ -313,7 +319,7 @@ def main():
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": f"config {cfg['index']}: {args.workload} (BASELINE.json configs[{cfg['index'] - 1}])",
                    "instances_per_step": graphs[0].n_instances, "mode": "by" + args.mode, "launch": args.launch,
-                   "fusion": not args.no_fusion, "placement": args.placement,
+                   "fusion": not args.no_fusion, "placement": args.placement, "update": bool(args.update),
                    "pipeline": "scheduling of step i+1 overlaps execution of step i (second stream)" if pipeline
                    else "none (schedule, forward, backward back to back)",
                    "pool": pool, "nodes_per_step": round(n_nodes / args.steps, 1)},

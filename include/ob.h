@@ -115,6 +115,11 @@ int ob_param_read(ob_ctx *ctx, int id, float *host_out, size_t cap);
 /* Gradients accumulate over ob_backward calls until zeroed. */
 int ob_param_grad_zero(ob_ctx *ctx);
 int ob_param_grad_read(ob_ctx *ctx, int id, float *host_out, size_t cap);
+/* The update of Section 2's training loop, plain gradient descent: every parameter becomes
+ * parameter - lr * gradient, queued on the context's stream behind the backward pass (contexts
+ * forked from one another share the parameters, so one call updates them for all).  zero_grad != 0
+ * also clears the gradients in the same pass.  OB_E_STATE before the first upload of a graph. */
+int ob_param_sgd_step(ob_ctx *ctx, float lr, int zero_grad);
 
 /* ---- graph definition (Section 3.1; host only, nothing is computed) ---------------------- */
 

@@ -128,3 +128,13 @@ class Oracle:
 
     def param_grad(self, p: int) -> np.ndarray:
         return self.pgrad[self.p_off[p]:self.p_off[p + 1]].reshape(self.p_rows[p], self.p_cols[p])
+
+    def sgd_params(self, lr: float) -> list:
+        """Parameters after one plain gradient-descent update (Section 2, the update that closes
+        each training step): theta - lr * dL/dtheta, per parameter, in the oracle's precision."""
+        assert self.pgrad is not None
+        out = []
+        for p in range(len(self.p_rows)):
+            theta = self.pdata[self.p_off[p]:self.p_off[p + 1]].reshape(self.p_rows[p], self.p_cols[p])
+            out.append(theta - lr * self.param_grad(p))
+        return out

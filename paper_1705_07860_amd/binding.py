@@ -103,6 +103,7 @@ def lib():
             "ob_schedule_read": (i, [vp, pi, vp, vp, vp, vp, sz, sz]),
             "ob_stats_read": (i, [vp, POINTER(ObStats)]),
             "ob_debug_read": (i, [vp, i, vp, sz, POINTER(sz)]),
+            "ob_param_sgd_step": (i, [vp, c_float, i]),
             "ob_test_sort": (i, [vp, sz, vp, vp, i, i, vp, vp]),
             "ob_test_scan": (i, [vp, sz, vp, vp, vp]),
             "ob_test_gemm": (i, [vp, i, i, i, vp, vp, vp]),
@@ -181,6 +182,9 @@ class Context:
 
     def set_launch(self, launch: int):
         self._ck(self.L.ob_ctx_set_launch(self.h, launch))
+
+    def sgd_step(self, lr: float, zero_grad: bool = True):
+        self._ck(self.L.ob_param_sgd_step(self.h, float(lr), 1 if zero_grad else 0))
 
     def set_fusion(self, on):
         """0 / False: one launch per depth level; 1 / True: fused, early placement; 2: fused, late placement."""

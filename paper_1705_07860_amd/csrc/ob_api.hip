@@ -222,6 +222,20 @@ int ob_param_grad_zero(ob_ctx *ctx)
     return OB_OK;
 }
 
+int ob_param_sgd_step(ob_ctx *ctx, float lr, int zero_grad)
+{
+    CHECK_CTX(ctx);
+    if (int rc = params_to_device(ctx)) return rc;
+    if (!ctx->params_dev || ctx->params_dirty)
+        return ctx_fail(ctx, OB_E_STATE, "ob_param_sgd_step: no gradients yet (upload a graph and run backward first)");
+    if (!(lr == lr)) return ctx_fail(ctx, OB_E_ARG, "learning rate is not a number");
+    size_t max_count = 0;
+    for (auto &p : ctx->params) { const size_t c = (size_t)p.rows * p.cols; if (c > max_count) max_count = c; }
+    hipError_t e = exec_sgd(ctx->params_dev, (u32)ctx->params.size(), max_count, lr, zero_grad ? 1 : 0, ctx->stream);
+    if (e != hipSuccess) return ctx_fail(ctx, OB_E_HIP, "sgd step failed: %s", hipGetErrorString(e));
+    return OB_OK;
+}
+
 // ---- graph definition ----------------------------------------------------------------------------
 
 int ob_graph_new(ob_ctx *ctx)

@@ -976,6 +976,18 @@ __global__ __launch_bounds__(WG) void k_param_e(Tables T, u32 n_items)
     }
 }
 
+// theta <- theta - lr * gradient for every parameter (blockIdx.y = parameter); with zero_grad the
+// gradient is cleared in the same pass, ready for the next minibatch
+__global__ __launch_bounds__(WG) void k_sgd(const ParamDesc *params, float lr, int zero_grad)
+{
+    const ParamDesc P = params[blockIdx.y];
+    const size_t count = (size_t)P.rows * P.cols;
+    for (size_t i = (size_t)blockIdx.x * WG + threadIdx.x; i < count; i += (size_t)gridDim.x * WG) {
+        P.data[i] -= lr * P.grad[i];
+        if (zero_grad) P.grad[i] = 0.f;
+    }
+}
+
 __global__ void k_gather_all(Tables T, const float *src, float *dst, const u32 *dst_off)
 {
     const u32 v = blockIdx.x;
@@ -1215,6 +1227,16 @@ hipError_t exec_barrier_probe(u32 *state, int n_wg, int iters, u32 *out3, hipStr
     e = hipStreamSynchronize(s);
     out3[0] = h[3]; out3[1] = h[2]; out3[2] = h[1];
     return e;
+}
+
+hipError_t exec_sgd(const ParamDesc *params_dev, u32 n_params, size_t max_count, float lr, int zero_grad, hipStream_t s)
+{
+    if (n_params == 0) return hipSuccess;
+    size_t bx = (max_count + WG * 4 - 1) / (WG * 4);
+    if (bx < 1) bx = 1;
+    if (bx > 1024) bx = 1024;
+    hipLaunchKernelGGL(k_sgd, dim3((unsigned)bx, n_params), dim3(WG), 0, s, params_dev, lr, zero_grad);
+    return hipGetLastError();
 }
 
 hipError_t exec_gather_all(const Tables &T, int which, float *dst, const u32 *dst_off, hipStream_t s)

@@ -227,5 +227,6 @@ int exec_forward(ob_ctx *ctx);
 int exec_backward(ob_ctx *ctx);
 hipError_t exec_gather_all(const Tables &T, int which, float *dst, const u32 *dst_off, hipStream_t s);
 hipError_t exec_launch_probe(float *scratch, int n, int touch, float *us_per_launch, hipStream_t s);
+hipError_t exec_sgd(const ParamDesc *params_dev, u32 n_params, size_t max_count, float lr, int zero_grad, hipStream_t s);
 hipError_t exec_barrier_probe(u32 *state, int n_wg, int iters, u32 *out3, hipStream_t s);
 hipError_t exec_test_gemm(int M, int N, int K, const float *A, const float *B, float *C, hipStream_t s);

@@ -515,3 +515,30 @@ def test_agenda_rejects_more_signatures_than_it_can_rank():
     c, root = run_gpu(p, g, ob.OB_BYDEPTH, arena=64 << 20)
     check_against_oracle(c, p, g, o, root, what="many signatures")
     c.close()
+
+
+def test_sgd_step_matches_the_oracle_and_lowers_the_loss():
+    """Section 2's update: after backward, theta - lr * grad on the GPU equals the oracle's update
+    of the same parameters; gradients are cleared; a second forward gives a smaller loss."""
+    from paper_1705_07860_amd import binding as ob
+    p = wl.tagger_params()
+    g = wl.tagger_minibatch(p, seed=wl.SEED_BASE + 31, lengths=[5, 2, 8, 3])
+    o = Oracle(g, p, "f64")
+    o.forward()
+    o.backward(g.root)
+    c, root = run_gpu(p, g, ob.OB_BYDEPTH, arena=512 << 20)
+    loss0 = float(c.value_read(root, 1)[0])
+    c.backward(root)
+    lr = 0.05
+    c.sgd_step(lr, zero_grad=True)
+    ref = o.sgd_params(lr)
+    for pid, m in enumerate(p.mats):
+        got = c.param_read(pid, m.shape)
+        assert rel_err(got, ref[pid]) <= TOL, p.names[pid]
+        assert not np.any(c.param_grad_read(pid, m.shape))
+    c.reset()
+    c.forward(root)
+    loss1 = float(c.value_read(root, 1)[0])
+    say(f"  loss {loss0:.5f} -> {loss1:.5f}")
+    assert loss1 < loss0
+    c.close()

@@ -398,3 +398,28 @@ def test_signature_examples_from_the_paper():
         assert s[a] == s[b], (a, b)
     for a, b in differ:
         assert s[a] != s[b], (a, b)
+
+
+def test_gradient_step_lowers_the_loss_to_first_order():
+    """The oracle's update theta - lr * grad, pinned by what a gradient step must do: for a small
+    lr the loss drops by lr * |grad|^2 up to second-order terms (checked at two step sizes: the
+    relative gap to the linear prediction shrinks with lr)."""
+    from oracle.interp import Oracle
+    from paper_1705_07860_amd import workloads as wl
+    p = wl.rnn_params()
+    g = wl.rnn_minibatch(p, seed=11, lengths=[3, 5, 4])
+    o = Oracle(g, p, "f64")
+    o.forward()
+    o.backward(g.root)
+    loss0 = float(o.value(g.root)[0])
+    g2 = float(np.sum(o.pgrad[:int(o.p_off[-1])] ** 2))
+    gaps = []
+    for lr in (1e-4, 1e-5):
+        new = o.sgd_params(lr)
+        o2 = Oracle(g, p, "f64")
+        o2.set_params(np.concatenate([m.ravel() for m in new]))
+        o2.forward()
+        drop = loss0 - float(o2.value(g.root)[0])
+        assert drop > 0
+        gaps.append(abs(drop - lr * g2) / (lr * g2))
+    assert gaps[0] < 1e-2 and gaps[1] < gaps[0]
