@@ -500,6 +500,52 @@ def parser_minibatch(params: Params, seed: int = SEED_BASE + 501, n_sent: int = 
 # Registry used by tests and bench
 # --------------------------------------------------------------------------
 
+# --------------------------------------------------------------------------
+# Extra workload: the equal-length synthetic sequence labeler of Section 4.1
+# --------------------------------------------------------------------------
+
+def sync_tagger_params(seed: int = SEED_BASE + 600, vocab: int = 1000, emb: int = 200,
+                       hidden: int = 256, tags: int = 300) -> Params:
+    """Two stacked BiLSTM layers of `hidden` units per direction over `emb`-dimensional
+    embeddings, then a linear layer to `tags` classes (the sizes Section 4.1 states)."""
+    pb = ParamBuilder(np.random.default_rng(seed))
+    pb.add("E", vocab, emb)
+    lstm_params(pb, "l1f", emb, hidden)
+    lstm_params(pb, "l1b", emb, hidden)
+    lstm_params(pb, "l2f", 2 * hidden, hidden)
+    lstm_params(pb, "l2b", 2 * hidden, hidden)
+    pb.add("out.W", tags, 2 * hidden)
+    pb.add("out.b", tags, 1)
+    return pb.done()
+
+
+def sync_tagger_minibatch(params: Params, seed: int = SEED_BASE + 601, n_sent: int = 64,
+                          length: int = 40) -> Graph:
+    """Every sequence has the same length (the case in which batching by hand is easiest)."""
+    rng = np.random.default_rng(seed)
+    P = params
+    E = P.index("E")
+    vocab = P.mats[E].shape[0]
+    hidden = P.mats[P.index("l1f.Wh")].shape[1]
+    tags = P.mats[P.index("out.W")].shape[0]
+    layers = [tuple((P.index(f"{n}.Wx"), P.index(f"{n}.Wh"), P.index(f"{n}.b")) for n in pair)
+              for pair in (("l1f", "l1b"), ("l2f", "l2b"))]
+    ow, ob = P.index("out.W"), P.index("out.b")
+    g = GraphBuilder(params)
+    losses = []
+    for _ in range(n_sent):
+        words = rng.integers(0, vocab, size=length)
+        labels = rng.integers(0, tags, size=length)
+        xs = [g.lookup(E, int(w)) for w in words]
+        for pf, pbk in layers:
+            f, b = bilstm_states(g, pf, pbk, hidden, xs)
+            xs = [g.concat((f[t], b[t])) for t in range(length)]
+        for t in range(length):
+            losses.append(g.pick_nls(g.matvec(ow, ob, xs[t]), int(labels[t])))
+    root = g.add(losses)
+    return g.finish(root, n_sent, lengths=[length] * n_sent, n_tokens=n_sent * length, workload="sync_tagger")
+
+
 CONFIGS = {
     "rnn": dict(index=1, params=lambda: rnn_params(SEED_BASE + 100),
                 batch=lambda p, j=0: rnn_minibatch(p, SEED_BASE + 101 + j)),
@@ -511,6 +557,9 @@ CONFIGS = {
                  batch=lambda p, j=0: tree_minibatch(p, SEED_BASE + 401 + j)),
     "parser": dict(index=5, params=lambda: parser_params(SEED_BASE + 500),
                    batch=lambda p, j=0: parser_minibatch(p, SEED_BASE + 501 + j)),
+    # not one of the five listed configurations: Section 4.1's synthetic benchmark (index 0)
+    "sync_tagger": dict(index=0, params=lambda: sync_tagger_params(SEED_BASE + 600),
+                        batch=lambda p, j=0: sync_tagger_minibatch(p, SEED_BASE + 601 + j)),
 }
 
 

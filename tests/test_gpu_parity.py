@@ -542,3 +542,20 @@ def test_sgd_step_matches_the_oracle_and_lowers_the_loss():
     say(f"  loss {loss0:.5f} -> {loss1:.5f}")
     assert loss1 < loss0
     c.close()
+
+
+def test_synthetic_equal_length_tagger_small():
+    """The stacked two-layer BiLSTM labeler of Section 4.1 at a small size, both batching strategies."""
+    from paper_1705_07860_amd import binding as ob
+    p = wl.sync_tagger_params(vocab=50, emb=24, hidden=16, tags=7)
+    g = wl.sync_tagger_minibatch(p, n_sent=5, length=6)
+    o = Oracle(g, p, "f64")
+    o.forward()
+    o.backward(g.root)
+    for mode, ref in ((ob.OB_BYDEPTH, S.by_depth), (ob.OB_BYAGENDA, S.by_agenda)):
+        c, root = run_gpu(p, g, mode, arena=256 << 20)
+        bo, ids, bd, _ = c.schedule_read()
+        rbo, rids, rbd = ref(g)
+        assert np.array_equal(bo, rbo) and np.array_equal(ids, rids) and np.array_equal(bd, rbd)
+        check_against_oracle(c, p, g, o, root, what=f"sync tagger mode {mode}")
+        c.close()
