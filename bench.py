@@ -124,7 +124,8 @@ def main():
                          "zeroing the gradients; the headline metric is forward + backward, so this is off by default")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
     ap.add_argument("--no-nobatch", action="store_true", help="skip the unbatched GPU leg")
-    ap.add_argument("--cpu-samples", type=int, default=4)
+    ap.add_argument("--cpu-samples", type=int, default=12,
+                    help="minibatches the CPU oracle leg runs (cycling through the pool): about 10-30 s of CPU work")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MiB",
                     help="also run one plain device copy of this many MiB (a kernel of known traffic, used to "
                          "scale the FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run)")
@@ -311,17 +312,18 @@ def main():
     cpu = None
     if not args.no_cpu:
         from oracle.interp import Oracle
-        ns = max(1, min(args.cpu_samples, pool))
+        ns = max(1, args.cpu_samples)
         t1 = time.perf_counter()
         inst = 0
         for j in range(ns):
-            o = Oracle(graphs[j], params, "f32")
+            gj = graphs[j % pool]
+            o = Oracle(gj, params, "f32")
             o.forward()
-            o.backward(graphs[j].root)
-            inst += graphs[j].n_instances
+            o.backward(gj.root)
+            inst += gj.n_instances
         dt = time.perf_counter() - t1
         cpu = dict(value=round(inst / dt, 2), unit="instances/s", cores=1, kind="oracle",
-                   sample=f"{ns} of the {pool} pooled minibatches ({inst} instances), fp32 build of the "
+                   sample=f"{ns} minibatches cycling through the {pool} pooled ones ({inst} instances, {dt:.1f} s), fp32 build of the "
                           f"node-at-a-time interpreter, forward+backward, 1 thread of {os.cpu_count()} host cores")
 
     out = {
