@@ -1,13 +1,14 @@
 // Batched execution (Section 3.3): every batch of the schedule runs as one batched operation.
-// A step (= one depth level, or one node when batching is off) is one launch of a tile
-// interpreter: each workgroup takes tiles of the step's batches and runs the matching routine.
+// One launch covers one launch slot (one or several depth levels whose batches need no grid-wide
+// ordering between them, or one node when batching is off) and runs a tile interpreter: each
+// workgroup takes work items of the slot's batches and runs the matching routine.
 //  - shared-weight matrix-vector groups W h_i become one W H product on fp32 MFMA, operand rows
 //    gathered through the batch's row-offset list (the sparse-to-dense copy of Appendix B is
 //    fused into the operand load), results written to the batch's contiguous block (so the
 //    dense-to-sparse copy is the identity);
 //  - component-wise groups, slices, concatenations and lookups are gathers fused with the op;
 //  - log-softmax picks, squared norms and wide sums are per-row wavefront reductions.
-// Backward mirrors it in reverse step order without atomics: a node's gradient is the sum, in
+// Backward mirrors it in reverse slot order without atomics: a node's gradient is the sum, in
 // fixed (consumer, slot) order, of what each consumer edge contributes ("pull"), and the
 // weight, bias and embedding gradients are reduced once per parameter over all their uses.
 #include "ob_ctx.h"

@@ -901,8 +901,9 @@ __global__ void k_slot_tables(Tables T, const CLay *clay_ex, const CLay *total)
     }
 }
 
-// launch slots that hold no batch (a matrix product moved to the next odd slot can leave one
-// behind) inherit the offsets of the next slot that does, so that their launch range is empty
+// launch slots that hold no batch (neither placement produces one today; the launch tables
+// simply do not rely on it) inherit the offsets of the next slot that does, so that their launch
+// range is empty
 __global__ void k_slot_fill(Tables T)
 {
     const u32 s = blockIdx.x * blockDim.x + threadIdx.x;
@@ -1352,8 +1353,7 @@ int sched_enqueue(ob_ctx *ctx)
     A(T.val_off, u32, n); A(T.dx_off, u32, n); A(T.opnd_off, u32, E + 1); A(T.dx_gsrc, u32, n);
     A(T.slot_of, u32, n); A(T.label_of, u32, n);
     A(T.lorder, u32, n); A(T.chains, ChainRec, n); A(T.clay, CLay, n); A(T.chain_of_lpos, u32, n);
-    // moving matrix products to odd slots can at most double the number of slots over the number
-    // of depth levels
+    // a plan has at most one slot per node; twice that leaves room for plans that insert slots
     const size_t slot_cap = 2 * (size_t)n + 4;
     A(T.slots, SlotRec, slot_cap);
     A(T.works_f, WorkRec, cap_f); A(T.works_a, WorkRec, cap_a);
@@ -1530,7 +1530,7 @@ int sched_finish(ob_ctx *ctx)
     ctx->hdr = *(const SchedHeader *)hp;
     ctx->hdr.n_items = ctx->n_items_sched;
     if (ctx->hdr.err & ERR_CYCLE)
-        return ctx_fail(ctx, -6, "frontier pass resolved %u of %u nodes (cyclic or malformed graph)",
+        return ctx_fail(ctx, -6, "the depth / agenda pass resolved %u of %u nodes (cyclic or malformed graph)",
                         ctx->hdr.frontier_done, T.n);
     if (ctx->hdr.err & ERR_COLLISION) return ctx_fail(ctx, -6, "signature hash collision detected");
     if (ctx->hdr.err & ERR_TABLE_FULL) return ctx_fail(ctx, -6, "signature table full");
