@@ -855,11 +855,12 @@ __device__ inline void stage_descriptors(const void *src, void *dst, u32 n)
 // GEMM tiles' reduction space or the fused run's copy of its own results, whichever is running.
 // run_len != 0: every work item of the launch has run_len tiles, item w starts at tile
 // tile_lo + (w - work_lo) * run_len and the work records are not read.
-__global__ __launch_bounds__(WG) void k_fwd_step(Tables T, u32 work_lo, u32 work_hi, u32 tile_lo, u32 run_len)
+extern __shared__ __align__(16) float dyn_lds[];   // sized per launch: GEMM reduction space or a fused chain's copy
+
+__global__ __launch_bounds__(WG, 4) void k_fwd_step(Tables T, u32 work_lo, u32 work_hi, u32 tile_lo, u32 run_len)
 {
-    __shared__ __align__(16) float lds[CHAIN_LDS_FLOATS];
+    float *lds = dyn_lds;
     __shared__ __align__(16) TileDesc sdesc[RUN_STAGE];
-    static_assert(CHAIN_LDS_FLOATS >= (u32)LDS_FLOATS, "the GEMM reduction space must fit");
     const u32 lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     for (u32 w = work_lo + blockIdx.x; w < work_hi; w += gridDim.x) {
         WorkRec wr;
@@ -895,12 +896,11 @@ __global__ __launch_bounds__(WG) void k_fwd_step(Tables T, u32 work_lo, u32 work
 // items.  Both kinds may share a launch only when no dX tile reads a gradient that this slot's
 // pull computes; otherwise the host launches the pull range and the dX range one after the other.
 constexpr int BWD_THREADS = DX_WAVES * 64;
-__global__ __launch_bounds__(BWD_THREADS) void k_bwd_step(Tables T, u32 work_lo, u32 work_hi, u32 tile_lo, u32 run_len,
-                                                          u32 dx_lo, u32 dx_hi)
+__global__ __launch_bounds__(BWD_THREADS, 4) void k_bwd_step(Tables T, u32 work_lo, u32 work_hi, u32 tile_lo, u32 run_len,
+                                                             u32 dx_lo, u32 dx_hi)
 {
-    __shared__ __align__(16) float lds[CHAIN_LDS_FLOATS];
+    float *lds = dyn_lds;
     __shared__ __align__(16) PullDesc sdesc[RUN_STAGE];
-    static_assert(CHAIN_LDS_FLOATS >= (u32)(DX_WAVES * 4 * 64), "the dX reduction space must fit");
     const u32 lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const u32 n_dx = dx_hi - dx_lo, n_items = n_dx + (work_hi - work_lo);
     for (u32 item = blockIdx.x; item < n_items; item += gridDim.x) {
@@ -1021,8 +1021,32 @@ constexpr u32 GRID_CAP = 4096;
 // chains differ (the kernel then reads each work item's record)
 static inline u32 slot_run_len(const SlotRec &r) { return r.lmin == ~r.nlmax ? r.lmin : 0u; }
 
+// dynamic LDS of a step launch: the slot's fused chains' need, at least the GEMM reduction space
+constexpr size_t FWD_LDS_MIN = (size_t)LDS_FLOATS * 4;                 // four waves' 32x32 accumulator blocks
+constexpr size_t BWD_LDS_MIN = (size_t)DX_WAVES * 16 * 64 * 4;         // eight waves' blocks of a wide dX tile
+static inline size_t slot_lds_bytes(const SlotRec &r, size_t floor_bytes)
+{
+    const size_t need = (size_t)r.lds_need * 4;
+    return need > floor_bytes ? need : floor_bytes;
+}
+
+// the step kernels may ask for a full fused-chain copy (64 KB) on top of their static descriptor
+// stage: raise their dynamic-LDS limit once per process
+static hipError_t allow_large_dynamic_lds()
+{
+    static hipError_t result = [] {
+        const int bytes = (int)(CHAIN_LDS_FLOATS * 4);
+        hipError_t e = hipFuncSetAttribute((const void *)k_fwd_step, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+        if (e == hipSuccess)
+            e = hipFuncSetAttribute((const void *)k_bwd_step, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+        return e;
+    }();
+    return result;
+}
+
 static int launch_forward_steps(ob_ctx *ctx)
 {
+    HIP_TRY(ctx, allow_large_dynamic_lds());
     const Tables &T = ctx->T;
     hipStream_t s = ctx->stream;
     const u32 ns = ctx->hdr.n_slots;
@@ -1030,7 +1054,8 @@ static int launch_forward_steps(ob_ctx *ctx)
         const SlotRec &r = ctx->slots[st];
         const u32 lo = r.wf, hi = ctx->slots[st + 1].wf;
         if (hi > lo) {
-            hipLaunchKernelGGL(k_fwd_step, dim3(grid_for(hi - lo, GRID_CAP)), dim3(WG), 0, s, T, lo, hi, r.tf, slot_run_len(r));
+            hipLaunchKernelGGL(k_fwd_step, dim3(grid_for(hi - lo, GRID_CAP)), dim3(WG), slot_lds_bytes(r, FWD_LDS_MIN), s, T,
+                               lo, hi, r.tf, slot_run_len(r));
             ++ctx->n_launch_fwd;
         }
     }
@@ -1039,6 +1064,7 @@ static int launch_forward_steps(ob_ctx *ctx)
 
 static int launch_backward_steps(ob_ctx *ctx)
 {
+    HIP_TRY(ctx, allow_large_dynamic_lds());
     const Tables &T = ctx->T;
     hipStream_t s = ctx->stream;
     const u32 ns = ctx->hdr.n_slots;
@@ -1047,19 +1073,21 @@ static int launch_backward_steps(ob_ctx *ctx)
     for (u32 st = ns; st-- > 0;) {
         const SlotRec &r = ctx->slots[st], &e = ctx->slots[st + 1];
         const u32 n_pull = e.wa - r.wa, n_dx = e.tb - r.tb;
+        const size_t lds_bytes = slot_lds_bytes(r, BWD_LDS_MIN);
         if (n_pull && n_dx && r.dx_free) {
-            hipLaunchKernelGGL(k_bwd_step, dim3(grid_for(n_pull + n_dx, GRID_CAP)), dim3(BWD_THREADS), 0, s, T, r.wa, e.wa,
-                               r.ta, slot_run_len(r), r.tb, e.tb);
+            hipLaunchKernelGGL(k_bwd_step, dim3(grid_for(n_pull + n_dx, GRID_CAP)), dim3(BWD_THREADS), lds_bytes, s, T, r.wa,
+                               e.wa, r.ta, slot_run_len(r), r.tb, e.tb);
             ++ctx->n_launch_bwd;
             continue;
         }
         if (n_pull) {
-            hipLaunchKernelGGL(k_bwd_step, dim3(grid_for(n_pull, GRID_CAP)), dim3(BWD_THREADS), 0, s, T, r.wa, e.wa, r.ta,
-                               slot_run_len(r), 0u, 0u);
+            hipLaunchKernelGGL(k_bwd_step, dim3(grid_for(n_pull, GRID_CAP)), dim3(BWD_THREADS), lds_bytes, s, T, r.wa, e.wa,
+                               r.ta, slot_run_len(r), 0u, 0u);
             ++ctx->n_launch_bwd;
         }
         if (n_dx) {
-            hipLaunchKernelGGL(k_bwd_step, dim3(grid_for(n_dx, GRID_CAP)), dim3(BWD_THREADS), 0, s, T, 0u, 0u, 0u, 0u, r.tb, e.tb);
+            hipLaunchKernelGGL(k_bwd_step, dim3(grid_for(n_dx, GRID_CAP)), dim3(BWD_THREADS), BWD_LDS_MIN, s, T, 0u, 0u, 0u, 0u,
+                               r.tb, e.tb);
             ++ctx->n_launch_bwd;
         }
     }

@@ -149,7 +149,10 @@ struct WorkRec { u32 first, len; };   // a workgroup runs tiles [first, first + 
 // item w of the slot runs tiles tf + (w - wf) * len onwards and its WorkRec need not be read.
 // dx_free != 0: no dX tile of the slot reads a gradient that the slot's own pull computes (every
 // MATVEC batch in it has TF_G_ALIAS), so the slot's pull and dX work can share one launch.
-struct SlotRec { u32 wf, wa, tb, tf, ta, lmin, nlmax, dx_free; };
+// lds_need: floats of LDS the slot's fused chains use to hand results on (0: none); the step
+// kernels are launched with that much dynamic LDS (and at least their GEMM reduction space), so
+// slots without such chains keep more workgroups resident per CU.
+struct SlotRec { u32 wf, wa, tb, tf, ta, lmin, nlmax, dx_free, lds_need, pad0, pad1, pad2; };
 
 // Static tile of the deferred parameter-gradient kernels (built on the host per parameter set).
 struct PTile { i32 param; i32 i0, j0; i32 pad; };

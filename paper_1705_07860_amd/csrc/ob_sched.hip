@@ -867,12 +867,16 @@ __global__ void k_clay_zero(CLay *clay_in, u32 n_pad)
     clay_in[i] = L;
 }
 
+// floats of a fused chain's LDS copy taken by one member: its rows of a block of groups, rounded up to 4
+__device__ inline u32 chain_region(const ChainRec &cr, const BatchRec &r) { return (cr.Rg * (r.B / cr.G) * r.d + 3u) & ~3u; }
+
 // every entry a plan can use (n_slots + 1 <= n + 2) starts out as "no batch here"
 __global__ void k_slot_init(Tables T)
 {
     const u32 s = blockIdx.x * blockDim.x + threadIdx.x;
     if (s > T.hdr->n_slots) return;
     SlotRec r; r.wf = r.wa = r.tb = r.tf = r.ta = r.lmin = r.nlmax = r.dx_free = 0xffffffffu;
+    r.lds_need = r.pad0 = r.pad1 = r.pad2 = 0;
     T.slots[s] = r;
 }
 
@@ -889,6 +893,11 @@ __global__ void k_slot_tables(Tables T, const CLay *clay_ex, const CLay *total)
     if (c == 0 || T.chains[c - 1].slot != s) { S.wf = L.wf; S.wa = L.wa; S.tb = L.tb; S.tf = L.tf; S.ta = L.ta; }
     const BatchRec &hb = T.batches[T.lorder[cr.first]];
     if (hb.op == OP_MATVEC && !(hb.vec4 & TF_G_ALIAS)) S.dx_free = 0;   // this slot's dX tiles need the slot's own pull first
+    if (cr.fused == 2u) {
+        u32 need = 0;
+        for (u32 m = 0; m < cr.k; ++m) need += chain_region(cr, T.batches[T.lorder[cr.first + m]]);
+        atomicMax(&S.lds_need, need);
+    }
     const u32 len = cr.fused ? cr.kt : 1u;
     atomicMin(&S.lmin, len);
     atomicMin(&S.nlmax, ~len);
@@ -923,7 +932,6 @@ constexpr u32 CONTIG_MAX_ROWS = 64;   // tiles with more rows skip the even-spac
 // Where a tile of a fused chain sits: chain, member, block of groups [g0, g0 + ng).
 struct ChainCtx { ChainRec cr; u32 m, g0, ng; };
 
-__device__ inline u32 chain_region(const ChainRec &cr, const BatchRec &r) { return (cr.Rg * (r.B / cr.G) * r.d + 3u) & ~3u; }
 
 // For up to four row-offset ranges [lo[j], hi[j]] (first element of the lowest / highest row read
 // through slot j; offsets in the value arena, which the gradient arena mirrors): state 0 = no
