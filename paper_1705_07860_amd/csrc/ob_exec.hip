@@ -445,9 +445,82 @@ __device__ inline void matvec_fwd_tile_wide(const Tables &T, const TileDesc &d)
     }
 }
 
+// The same 64 x 64 tile with the operands staged through LDS.  Reading one operand row per lane
+// straight from memory touches 64 different cache lines per load instruction, which the address
+// path serialises; here the workgroup loads each 64-float piece of a row with 16 adjacent lanes
+// (two full lines), writes it to LDS, and the MFMA operands (lane = row, four consecutive k) are
+// LDS reads.  The next 64-wide chunk of the contraction is loaded into registers while the
+// current one is multiplied.  Rows are padded to 68 floats so that the 32 rows read together by
+// a half-wave spread over the banks.  Needs K % 4 == 0 and 16-byte aligned operand rows.
+constexpr u32 WKC = 64;             // contraction chunk
+constexpr u32 WLD = WKC + 4;        // padded LDS row
+constexpr u32 WIDE_LDS_FLOATS = 2 * GTW * WLD;   // X tile + W tile
+__device__ inline void matvec_fwd_tile_wide_lds(const Tables &T, const TileDesc &d, float *lds)
+{
+    const u32 tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    const u32 l32 = lane & 31, h = lane >> 5;
+    const u32 ntn = (d.d + GTW - 1) / GTW;
+    const u32 r0 = (d.t / ntn) * GTW, i0 = (d.t % ntn) * GTW;
+    const u32 K = d.k, m = d.d;
+    lds_float *xs = (lds_float *)lds, *ws = xs + GTW * WLD;
+    // loader role: piece c4 (four floats) of rows lr + 16 p, p < 4
+    const u32 lr = tid >> 4, c4 = (tid & 15u) * 4u;
+    u32 xoff[4];
+    bool xok[4], wok[4];
+#pragma unroll
+    for (int p = 0; p < 4; ++p) {
+        const u32 row = r0 + lr + 16u * p, col = i0 + lr + 16u * p;
+        xok[p] = row < d.B;
+        wok[p] = col < m;
+        xoff[p] = xok[p] ? opnd_row(T, d, 0, row - d.row0, row) : 0u;
+    }
+    gl_float *W = as_global(d.w);
+    const float4 z4 = make_float4(0.f, 0.f, 0.f, 0.f);
+    float4 px[4], pw[4];
+    auto prefetch = [&](u32 kc) {
+        const u32 k = kc + c4;
+#pragma unroll
+        for (int p = 0; p < 4; ++p) {
+            px[p] = (xok[p] && k < K) ? ld4(T.V + xoff[p] + k) : z4;
+            pw[p] = (wok[p] && k < K) ? gl_ld4(W + (size_t)(i0 + lr + 16u * p) * K + k) : z4;
+        }
+    };
+    floatx16 acc;
+    for (int v = 0; v < 16; ++v) acc[v] = 0.f;
+    const u32 arow = (32u * (w >> 1) + l32) * WLD + 4u * h, brow = (32u * (w & 1u) + l32) * WLD + 4u * h;
+    prefetch(0);
+    for (u32 kc = 0; kc < K; kc += WKC) {
+        __syncthreads();            // the previous chunk has been read
+#pragma unroll
+        for (int p = 0; p < 4; ++p) {
+            lds_st4(xs + (lr + 16u * p) * WLD + c4, px[p]);
+            lds_st4(ws + (lr + 16u * p) * WLD + c4, pw[p]);
+        }
+        __syncthreads();
+        if (kc + WKC < K) prefetch(kc + WKC);
+#pragma unroll
+        for (u32 k8 = 0; k8 < WKC / 8; ++k8)
+            acc = mfma4(lds_ld4(xs + arow + 8u * k8), lds_ld4(ws + brow + 8u * k8), acc);
+    }
+    const u32 col = i0 + 32u * (w & 1u) + l32;
+    if (col < m) {
+        const float bb = d.b ? as_global(d.b)[col] : 0.f;
+        float *Y = T.V + d.val_off;
+        for (int v = 0; v < 16; ++v) {
+            const u32 rr = r0 + 32u * (w >> 1) + 8u * (v >> 2) + 4u * h + (v & 3);
+            if (rr < d.B) Y[(size_t)rr * m + col] = acc[v] + bb;
+        }
+    }
+    __syncthreads();                // the LDS space is free for the workgroup's next tile
+}
+
 __device__ inline void matvec_fwd_tile(const Tables &T, const TileDesc &d, float *lds)
 {
-    if (d.flags & TF_WIDE) { matvec_fwd_tile_wide(T, d); return; }
+    if (d.flags & TF_WIDE) {
+        if ((d.flags & TF_ALIGNED) && (d.k & 3u) == 0) matvec_fwd_tile_wide_lds(T, d, lds);
+        else matvec_fwd_tile_wide(T, d);
+        return;
+    }
     const u32 ntn = (d.d + GT - 1) / GT;
     const u32 r0 = (d.t / ntn) * GT, i0 = (d.t % ntn) * GT;
     const bool fast = (d.flags & 2u) && (d.k & 3u) == 0;
@@ -1022,7 +1095,7 @@ constexpr u32 GRID_CAP = 4096;
 static inline u32 slot_run_len(const SlotRec &r) { return r.lmin == ~r.nlmax ? r.lmin : 0u; }
 
 // dynamic LDS of a step launch: the slot's fused chains' need, at least the GEMM reduction space
-constexpr size_t FWD_LDS_MIN = (size_t)LDS_FLOATS * 4;                 // four waves' 32x32 accumulator blocks
+constexpr size_t FWD_LDS_MIN = (size_t)(WIDE_LDS_FLOATS > (u32)LDS_FLOATS ? WIDE_LDS_FLOATS : (u32)LDS_FLOATS) * 4;   // staged wide tile / accumulator blocks
 constexpr size_t BWD_LDS_MIN = (size_t)DX_WAVES * 16 * 64 * 4;         // eight waves' blocks of a wide dX tile
 static inline size_t slot_lds_bytes(const SlotRec &r, size_t floor_bytes)
 {
