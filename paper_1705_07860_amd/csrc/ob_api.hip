@@ -519,9 +519,30 @@ static int upload_param_tables(ob_ctx *ctx)
     for (size_t p = 0; p < ctx->params.size(); ++p) {
         const HostParam &hp = ctx->params[p];
         desc[p].data = hp.data; desc[p].grad = hp.grad; desc[p].rows = hp.rows; desc[p].cols = hp.cols;
-        if (ctx->params_used_w[p])
-            for (int i0 = 0; i0 < hp.rows; i0 += GT)
-                for (int j0 = 0; j0 < hp.cols; j0 += GT) ctx->wtiles.push_back(PTile{(i32)p, i0, j0, 0});
+        if (ctx->params_used_w[p]) {
+            // Workgroup g of a launch runs on XCD g % 8, and every XCD has its own L2.  A dW tile
+            // (i0, j0) reads columns i0.. of every gradient row and columns j0.. of every operand
+            // row, so tiles are ordered such that an XCD keeps to one eighth of the gradient
+            // columns: the (larger) gradient block is then fetched once instead of once per XCD.
+            const int R = (hp.rows + GT - 1) / GT, C = (hp.cols + GT - 1) / GT;
+            std::vector<std::vector<PTile>> group(8);
+            for (int rt = 0; rt < R; ++rt)
+                for (int ct = 0; ct < C; ++ct)
+                    group[(size_t)((long long)rt * 8 / R)].push_back(PTile{(i32)p, rt * GT, ct * GT, 0});
+            size_t left = (size_t)R * C;
+            std::vector<size_t> next(8, 0);
+            while (left) {
+                size_t x = ctx->wtiles.size() % 8;
+                if (next[x] >= group[x].size()) {     // this XCD's share is used up: take from the fullest other share
+                    size_t best = 0, most = 0;
+                    for (size_t y = 0; y < 8; ++y)
+                        if (group[y].size() - next[y] > most) { most = group[y].size() - next[y]; best = y; }
+                    x = best;
+                }
+                ctx->wtiles.push_back(group[x][next[x]++]);
+                --left;
+            }
+        }
         if (ctx->params_used_b[p])
             for (int i0 = 0; i0 < hp.rows; i0 += 32) ctx->btiles.push_back(PTile{(i32)p, i0, 0, 0});
     }
