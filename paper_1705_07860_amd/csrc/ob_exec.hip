@@ -930,7 +930,10 @@ __device__ inline void stage_descriptors(const void *src, void *dst, u32 n)
 // tile_lo + (w - work_lo) * run_len and the work records are not read.
 extern __shared__ __align__(16) float dyn_lds[];   // sized per launch: GEMM reduction space or a fused chain's copy
 
-__global__ __launch_bounds__(WG, 4) void k_fwd_step(Tables T, u32 work_lo, u32 work_hi, u32 tile_lo, u32 run_len)
+// LEAN: the launch holds component-wise work only; this instantiation carries no GEMM or
+// reduction code, needs half the registers and keeps twice the waves per CU.
+template <bool LEAN>
+__global__ __launch_bounds__(WG, LEAN ? 6 : 4) void k_fwd_step(Tables T, u32 work_lo, u32 work_hi, u32 tile_lo, u32 run_len)
 {
     float *lds = dyn_lds;
     __shared__ __align__(16) TileDesc sdesc[RUN_STAGE];
@@ -941,7 +944,8 @@ __global__ __launch_bounds__(WG, 4) void k_fwd_step(Tables T, u32 work_lo, u32 w
         else wr = T.works_f[w];
         if (wr.len == 1) {
             const TileDesc d = T.tiles_f[wr.first];
-            run_fwd_tile(T, d, lds);
+            if (LEAN) ew_fwd_tile(T, d, (lds_float *)lds, threadIdx.x, WG);
+            else run_fwd_tile(T, d, lds);
             continue;
         }
         for (u32 c0 = 0; c0 < wr.len; c0 += RUN_STAGE) {
@@ -969,15 +973,16 @@ __global__ __launch_bounds__(WG, 4) void k_fwd_step(Tables T, u32 work_lo, u32 w
 // items.  Both kinds may share a launch only when no dX tile reads a gradient that this slot's
 // pull computes; otherwise the host launches the pull range and the dX range one after the other.
 constexpr int BWD_THREADS = DX_WAVES * 64;
-__global__ __launch_bounds__(BWD_THREADS, 4) void k_bwd_step(Tables T, u32 work_lo, u32 work_hi, u32 tile_lo, u32 run_len,
-                                                             u32 dx_lo, u32 dx_hi)
+template <bool LEAN>
+__global__ __launch_bounds__(BWD_THREADS, LEAN ? 5 : 4) void k_bwd_step(Tables T, u32 work_lo, u32 work_hi, u32 tile_lo,
+                                                                        u32 run_len, u32 dx_lo, u32 dx_hi)
 {
     float *lds = dyn_lds;
     __shared__ __align__(16) PullDesc sdesc[RUN_STAGE];
     const u32 lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const u32 n_dx = dx_hi - dx_lo, n_items = n_dx + (work_hi - work_lo);
     for (u32 item = blockIdx.x; item < n_items; item += gridDim.x) {
-        if (item < n_dx) {
+        if (!LEAN && item < n_dx) {
             const TileDesc d = T.tiles_b[dx_lo + item];
             matvec_dx_tile(T, d, lds);
             continue;
@@ -1109,9 +1114,11 @@ static hipError_t allow_large_dynamic_lds()
 {
     static hipError_t result = [] {
         const int bytes = (int)(CHAIN_LDS_FLOATS * 4);
-        hipError_t e = hipFuncSetAttribute((const void *)k_fwd_step, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
-        if (e == hipSuccess)
-            e = hipFuncSetAttribute((const void *)k_bwd_step, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+        const void *kernels[4] = {(const void *)k_fwd_step<false>, (const void *)k_fwd_step<true>,
+                                  (const void *)k_bwd_step<false>, (const void *)k_bwd_step<true>};
+        hipError_t e = hipSuccess;
+        for (const void *k : kernels)
+            if (e == hipSuccess) e = hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
         return e;
     }();
     return result;
@@ -1127,8 +1134,12 @@ static int launch_forward_steps(ob_ctx *ctx)
         const SlotRec &r = ctx->slots[st];
         const u32 lo = r.wf, hi = ctx->slots[st + 1].wf;
         if (hi > lo) {
-            hipLaunchKernelGGL(k_fwd_step, dim3(grid_for(hi - lo, GRID_CAP)), dim3(WG), slot_lds_bytes(r, FWD_LDS_MIN), s, T,
-                               lo, hi, r.tf, slot_run_len(r));
+            if (r.plain)
+                hipLaunchKernelGGL(k_fwd_step<true>, dim3(grid_for(hi - lo, GRID_CAP)), dim3(WG), slot_lds_bytes(r, 16), s, T,
+                                   lo, hi, r.tf, slot_run_len(r));
+            else
+                hipLaunchKernelGGL(k_fwd_step<false>, dim3(grid_for(hi - lo, GRID_CAP)), dim3(WG),
+                                   slot_lds_bytes(r, FWD_LDS_MIN), s, T, lo, hi, r.tf, slot_run_len(r));
             ++ctx->n_launch_fwd;
         }
     }
@@ -1148,19 +1159,19 @@ static int launch_backward_steps(ob_ctx *ctx)
         const u32 n_pull = e.wa - r.wa, n_dx = e.tb - r.tb;
         const size_t lds_bytes = slot_lds_bytes(r, BWD_LDS_MIN);
         if (n_pull && n_dx && r.dx_free) {
-            hipLaunchKernelGGL(k_bwd_step, dim3(grid_for(n_pull + n_dx, GRID_CAP)), dim3(BWD_THREADS), lds_bytes, s, T, r.wa,
-                               e.wa, r.ta, slot_run_len(r), r.tb, e.tb);
+            hipLaunchKernelGGL(k_bwd_step<false>, dim3(grid_for(n_pull + n_dx, GRID_CAP)), dim3(BWD_THREADS), lds_bytes, s, T,
+                               r.wa, e.wa, r.ta, slot_run_len(r), r.tb, e.tb);
             ++ctx->n_launch_bwd;
             continue;
         }
         if (n_pull) {
-            hipLaunchKernelGGL(k_bwd_step, dim3(grid_for(n_pull, GRID_CAP)), dim3(BWD_THREADS), lds_bytes, s, T, r.wa, e.wa,
-                               r.ta, slot_run_len(r), 0u, 0u);
+            hipLaunchKernelGGL(k_bwd_step<true>, dim3(grid_for(n_pull, GRID_CAP)), dim3(BWD_THREADS), slot_lds_bytes(r, 16), s,
+                               T, r.wa, e.wa, r.ta, slot_run_len(r), 0u, 0u);
             ++ctx->n_launch_bwd;
         }
         if (n_dx) {
-            hipLaunchKernelGGL(k_bwd_step, dim3(grid_for(n_dx, GRID_CAP)), dim3(BWD_THREADS), BWD_LDS_MIN, s, T, 0u, 0u, 0u, 0u,
-                               r.tb, e.tb);
+            hipLaunchKernelGGL(k_bwd_step<false>, dim3(grid_for(n_dx, GRID_CAP)), dim3(BWD_THREADS), BWD_LDS_MIN, s, T, 0u, 0u,
+                               0u, 0u, r.tb, e.tb);
             ++ctx->n_launch_bwd;
         }
     }

@@ -152,7 +152,9 @@ struct WorkRec { u32 first, len; };   // a workgroup runs tiles [first, first + 
 // lds_need: floats of LDS the slot's fused chains use to hand results on (0: none); the step
 // kernels are launched with that much dynamic LDS (and at least their GEMM reduction space), so
 // slots without such chains keep more workgroups resident per CU.
-struct SlotRec { u32 wf, wa, tb, tf, ta, lmin, nlmax, dx_free, lds_need, pad0, pad1, pad2; };
+// plain != 0: every forward work item of the slot is component-wise (no GEMM, reduction or wide-sum
+// tile), so the slot can run the lean instantiation of the forward kernel.
+struct SlotRec { u32 wf, wa, tb, tf, ta, lmin, nlmax, dx_free, lds_need, plain, pad1, pad2; };
 
 // Static tile of the deferred parameter-gradient kernels (built on the host per parameter set).
 struct PTile { i32 param; i32 i0, j0; i32 pad; };

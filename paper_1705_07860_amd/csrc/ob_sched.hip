@@ -876,7 +876,8 @@ __global__ void k_slot_init(Tables T)
     const u32 s = blockIdx.x * blockDim.x + threadIdx.x;
     if (s > T.hdr->n_slots) return;
     SlotRec r; r.wf = r.wa = r.tb = r.tf = r.ta = r.lmin = r.nlmax = r.dx_free = 0xffffffffu;
-    r.lds_need = r.pad0 = r.pad1 = r.pad2 = 0;
+    r.lds_need = r.pad1 = r.pad2 = 0;
+    r.plain = 0xffffffffu;
     T.slots[s] = r;
 }
 
@@ -893,6 +894,7 @@ __global__ void k_slot_tables(Tables T, const CLay *clay_ex, const CLay *total)
     if (c == 0 || T.chains[c - 1].slot != s) { S.wf = L.wf; S.wa = L.wa; S.tb = L.tb; S.tf = L.tf; S.ta = L.ta; }
     const BatchRec &hb = T.batches[T.lorder[cr.first]];
     if (hb.op == OP_MATVEC && !(hb.vec4 & TF_G_ALIAS)) S.dx_free = 0;   // this slot's dX tiles need the slot's own pull first
+    if (!cr.fused) S.plain = 0;     // a GEMM, reduction or wide-sum batch runs in this slot
     if (cr.fused == 2u) {
         u32 need = 0;
         for (u32 m = 0; m < cr.k; ++m) need += chain_region(cr, T.batches[T.lorder[cr.first + m]]);
