@@ -239,7 +239,10 @@ def main():
     # whichever took more of the timed region.  Each kernel's launches are bracketed by HIP events on
     # the execution stream (forward: ms_forward; backward: ms_backward minus the three deferred
     # parameter-gradient kernels, which have events of their own), so the average launch duration
-    # is measured live.  The other kernel is reported beside it.
+    # is measured live.  The other kernel is reported beside it.  Each kernel has two instantiations
+    # (k_..._step<false>: any work; k_..._step<true>: launches with component-wise work only); the
+    # figures cover both, as do the stored traffic numbers, and the kernel trace's per-instantiation
+    # averages weighted by their call counts give the same average launch duration.
     fwd_ms, n_fwd = phase["ms_forward"], max(launches["n_launch_fwd"], 1)
     bwd_ms, n_bwd = phase["ms_backward"] - phase["ms_param_grads"], max(launches["n_launch_bwd"], 1)
 
