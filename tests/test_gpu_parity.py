@@ -559,3 +559,60 @@ def test_synthetic_equal_length_tagger_small():
         assert np.array_equal(bo, rbo) and np.array_equal(ids, rids) and np.array_equal(bd, rbd)
         check_against_oracle(c, p, g, o, root, what=f"sync tagger mode {mode}")
         c.close()
+
+
+def test_full_size_pipelined_loop_as_benchmarked(workload_cache):
+    """The loop bench.py times, at the tagger's full size: contexts forked from one parameter set,
+    one execution stream, scheduling of step i + 1 queued on a second stream before step i executes,
+    minibatches cycling through the contexts.  After the loop every context's values and node
+    gradients, and the parameter gradients of the last step, match the oracle."""
+    import torch
+    from paper_1705_07860_amd import binding as ob
+    p, g0, o0 = workload_cache("tagger")
+    cfg = wl.CONFIGS["tagger"]
+    graphs = [g0] + [cfg["batch"](p, j) for j in (1, 2)]
+    oracles = [o0]
+    for g in graphs[1:]:
+        o = Oracle(g, p, "f64")
+        o.forward()
+        o.backward(g.root)
+        oracles.append(o)
+    ex, sc = torch.cuda.Stream(), torch.cuda.Stream()
+    ctxs = []
+    for j, g in enumerate(graphs):
+        if j == 0:
+            c = ob.Context(arena_bytes=1 << 30, stream=ex, sched_stream=sc)
+            c.params_create(p)
+            c.param_grad_zero()
+        else:
+            c = ctxs[0].fork(arena_bytes=1 << 30, stream=ex, sched_stream=sc)
+        c.add_bulk(g)
+        c.upload()
+        ctxs.append(c)
+    pool, steps = len(graphs), 7
+
+    def sched(i):
+        c = ctxs[i % pool]
+        c.reset()
+        c.schedule_async(graphs[i % pool].root)
+
+    sched(0)
+    for i in range(steps):
+        if i + 1 < steps:
+            sched(i + 1)
+        c, g = ctxs[i % pool], graphs[i % pool]
+        c.param_grad_zero()
+        c.forward(g.root)
+        c.backward(g.root)
+    last = (steps - 1) % pool
+    for c, g, o in zip(ctxs, graphs, oracles):
+        total = int(o.v_off[-1])
+        assert segment_rel_err(c.all_read(0, total), o.val[:total], o.v_off) <= TOL
+        assert segment_rel_err(c.all_read(1, total), o.grad[:total], o.v_off) <= TOL
+        bo, ids, bd, _ = c.schedule_read()
+        rbo, rids, rbd = S.by_depth(g)
+        assert np.array_equal(bo, rbo) and np.array_equal(ids, rids) and np.array_equal(bd, rbd)
+    for pid, m in enumerate(p.mats):
+        assert rel_err(ctxs[0].param_grad_read(pid, m.shape), oracles[last].param_grad(pid)) <= TOL, p.names[pid]
+    for c in reversed(ctxs):
+        c.close()
