@@ -377,12 +377,18 @@ __global__ __launch_bounds__(1024) void k_class_rank(Tables T, AgendaTables A)
     }
 }
 
+// per node: rank of its signature, and one word holding that rank above the count of unresolved
+// operands ((rank << 22) | count), so that the decrement that resolves the last operand also
+// tells which ready list the node joins
+constexpr u32 AG_COUNT_BITS = 22;
 __global__ void k_class_of(Tables T, AgendaTables A)
 {
     const u32 v = blockIdx.x * blockDim.x + threadIdx.x;
     if (v >= T.n) return;
-    A.cls[v] = A.rank_of[T.ht_slot[v]];
-    A.pending[v] = T.indeg[v];
+    const u32 rank = A.rank_of[T.ht_slot[v]];
+    A.cls[v] = rank;
+    if (T.indeg[v] >> AG_COUNT_BITS) atomicOr(&T.hdr->err, (u32)ERR_CLASSES);
+    A.pending[v] = (rank << AG_COUNT_BITS) | T.indeg[v];
 }
 
 // One workgroup runs the agenda.  head / tail of every rank's ready list live in LDS; the lists
@@ -401,8 +407,9 @@ __global__ __launch_bounds__(AGENDA_THREADS) void k_agenda(Tables T, AgendaTable
     if (tid == 0) { s_min = AG_NONE; s_done = 0; s_t = 0; }
     __syncthreads();
     for (u32 v = tid; v < T.n; v += AGENDA_THREADS) {
-        if (A.pending[v] == 0) {
-            const u32 c = A.cls[v];
+        const u32 w = A.pending[v];
+        if ((w & ((1u << AG_COUNT_BITS) - 1u)) == 0) {
+            const u32 c = w >> AG_COUNT_BITS;
             A.seg[s_off[c] + atomicAdd(&s_tail[c], 1u)] = v;
         }
     }
@@ -421,8 +428,9 @@ __global__ __launch_bounds__(AGENDA_THREADS) void k_agenda(Tables T, AgendaTable
             const u32 e1 = T.succ_off[v + 1];
             for (u32 e = T.succ_off[v]; e < e1; ++e) {
                 const u32 sn = succ_node[e];
-                if (atomicSub(&A.pending[sn], 1u) == 1u) {
-                    const u32 cs = A.cls[sn];
+                const u32 was = atomicSub(&A.pending[sn], 1u);
+                if ((was & ((1u << AG_COUNT_BITS) - 1u)) == 1u) {
+                    const u32 cs = was >> AG_COUNT_BITS;
                     A.seg[s_off[cs] + atomicAdd(&s_tail[cs], 1u)] = sn;
                 }
             }
@@ -1545,7 +1553,7 @@ int sched_finish(ob_ctx *ctx)
     if (ctx->hdr.err & ERR_COLLISION) return ctx_fail(ctx, -6, "signature hash collision detected");
     if (ctx->hdr.err & ERR_TABLE_FULL) return ctx_fail(ctx, -6, "signature table full");
     if (ctx->hdr.err & ERR_OVERFLOW) return ctx_fail(ctx, -5, "value arena exceeds 2^32 elements");
-    if (ctx->hdr.err & ERR_CLASSES) return ctx_fail(ctx, -6, "more than 1024 distinct signatures: agenda-based batching cannot rank them");
+    if (ctx->hdr.err & ERR_CLASSES) return ctx_fail(ctx, -6, "more than 1024 distinct signatures (or a node with more than 4 million operands): agenda-based batching cannot handle the graph");
     const size_t words = (size_t)ctx->hdr.n_slots + 1;
     if (words <= ctx->hdr_window) {
         const SlotRec *sr = (const SlotRec *)(hp + 256);
