@@ -216,6 +216,14 @@ int ob_param_grad_zero(ob_ctx *ctx)
 {
     CHECK_CTX(ctx);
     if (int rc = params_to_device(ctx)) return rc;
+    if (ctx->params_dev && !ctx->params_dirty && !ctx->params.empty()) {
+        // the device copy of the parameter table is current: one launch clears every gradient
+        size_t max_count = 0;
+        for (auto &p : ctx->params) { const size_t c = (size_t)p.rows * p.cols; if (c > max_count) max_count = c; }
+        hipError_t e = exec_sgd(ctx->params_dev, (u32)ctx->params.size(), max_count, 0.f, 2, ctx->stream);
+        if (e != hipSuccess) return ctx_fail(ctx, OB_E_HIP, "clearing the gradients failed: %s", hipGetErrorString(e));
+        return OB_OK;
+    }
     // parameters and their gradients are adjacent allocations; zero each gradient block
     for (auto &p : ctx->params)
         HIP_TRY(ctx, hipMemsetAsync(p.grad, 0, (size_t)p.rows * p.cols * 4, ctx->stream));

@@ -1061,6 +1061,10 @@ __global__ __launch_bounds__(WG) void k_sgd(const ParamDesc *params, float lr, i
 {
     const ParamDesc P = params[blockIdx.y];
     const size_t count = (size_t)P.rows * P.cols;
+    if (zero_grad == 2) {   // only clear the gradients
+        for (size_t i = (size_t)blockIdx.x * WG + threadIdx.x; i < count; i += (size_t)gridDim.x * WG) P.grad[i] = 0.f;
+        return;
+    }
     for (size_t i = (size_t)blockIdx.x * WG + threadIdx.x; i < count; i += (size_t)gridDim.x * WG) {
         P.data[i] -= lr * P.grad[i];
         if (zero_grad) P.grad[i] = 0.f;

@@ -1357,13 +1357,27 @@ int sched_enqueue(ob_ctx *ctx)
         field = arena_array<type>(ctx, (count));                            \
         if (!field) return ctx_fail(ctx, -5, "arena too small for scheduler tables (%s)", #field); \
     } while (0)
-    A(T.sig, u64, n); A(T.step, u32, n); A(T.indeg, u32, n); A(T.outdeg, u32, n + 1);
-    A(T.succ_off, u32, n + 1); A(T.succ_edge, u32, E + 1); A(T.edge_cons, u32, E + 1);
-    A(T.queue, u32, n); A(T.qcount, u32, 64); A(T.ext_indeg, u32, n + 1); A(T.ext_left, u32, n + 1);
+    // Tables that must start at zero lie next to each other, and so do those that start as all ones:
+    // two fills clear them all.
     u32 *g_dep, *inbox, *inbox_tail;
     const u32 n_parts = (n + DEPTH_PART - 1) / DEPTH_PART;
-    A(g_dep, u32, n + 1); A(inbox, u32, (size_t)n_parts * DEPTH_PART); A(inbox_tail, u32, n_parts + 1);
-    A(T.ht_keys, u64, ht_size); A(T.ht_vals, u32, ht_size); A(T.ht_slot, u32, n);
+    u32 *bset, *blist;
+    AgendaTables AG{};
+    char *zero_lo = (char *)ctx->arena + ctx->top;
+    A(T.hdr, SchedHeader, 1);
+    A(T.outdeg, u32, n + 1); A(T.qcount, u32, 64); A(T.ext_indeg, u32, n + 1); A(T.ext_left, u32, n + 1);
+    A(g_dep, u32, n + 1); A(inbox_tail, u32, n_parts + 1);
+    A(T.pu_start, u32, n_slots); A(T.pu_end, u32, n_slots);
+    A(T.ht_keys, u64, ht_size); A(bset, u32, BSET_SIZE);
+    if (agenda) { A(AG.keys, u64, AG_TABLE); A(AG.sum, u64, AG_TABLE); A(AG.cnt, u32, AG_TABLE); }
+    char *zero_hi = (char *)ctx->arena + ctx->top;
+    A(inbox, u32, (size_t)n_parts * DEPTH_PART); A(T.ht_vals, u32, ht_size);
+    if (agenda) A(AG.first, u32, AG_TABLE);
+    char *ones_hi = (char *)ctx->arena + ctx->top;
+    A(T.sig, u64, n); A(T.step, u32, n); A(T.indeg, u32, n);
+    A(T.succ_off, u32, n + 1); A(T.succ_edge, u32, E + 1); A(T.edge_cons, u32, E + 1);
+    A(T.queue, u32, n);
+    A(T.ht_slot, u32, n);
     T.ht_mask = ht_size - 1;
     A(T.order, u32, n); A(T.pos_of, u32, n); A(T.batch_of_pos, u32, n); A(T.s_aux0, u32, n);
     A(T.s_in_off, u32, n + 1);
@@ -1379,8 +1393,7 @@ int sched_enqueue(ob_ctx *ctx)
     A(T.root_pos, u32, 64);
     A(T.edges, EdgeRec, E + 1);
     A(T.it_key, u64, n_items + 1); A(T.it_pos, u32, n_items + 1); A(T.it_goff, u32, n_items + 1);
-    A(T.it_xoff, u32, n_items + 1); A(T.pu_start, u32, n_slots); A(T.pu_end, u32, n_slots);
-    A(T.hdr, SchedHeader, 1);
+    A(T.it_xoff, u32, n_items + 1);
     u32 *succ_node;
     A(succ_node, u32, E + 1);
     A(ctx->key_a, u64, maxne); A(ctx->key_b, u64, maxne); A(ctx->val_a, u32, maxne); A(ctx->val_b, u32, maxne);
@@ -1390,11 +1403,8 @@ int sched_enqueue(ob_ctx *ctx)
     A(ctx->lay_in, Lay, n); A(ctx->lay_total, Lay, 1);
     CLay *clay_in, *clay_total;
     A(clay_in, CLay, n); A(clay_total, CLay, 1);
-    u32 *bset, *blist;
-    A(bset, u32, BSET_SIZE); A(blist, u32, BLIST_MAX);
-    AgendaTables AG{};
+    A(blist, u32, BLIST_MAX);
     if (agenda) {
-        A(AG.keys, u64, AG_TABLE); A(AG.sum, u64, AG_TABLE); A(AG.cnt, u32, AG_TABLE); A(AG.first, u32, AG_TABLE);
         A(AG.op, u32, AG_TABLE); A(AG.rank_of, u32, AG_TABLE); A(AG.seg_off, u32, AG_MAX_CLASSES + 1);
         A(AG.n_classes, u32, 64);
         AG.cls = ctx->tmp_u32_a; AG.pending = ctx->tmp_u32_b; AG.seg = T.queue;
@@ -1408,19 +1418,9 @@ int sched_enqueue(ob_ctx *ctx)
 #undef A
 
     // ---- stage 1 ----
-    HIP_TRY(ctx, hipMemsetAsync(T.hdr, 0, sizeof(SchedHeader), s));
-    HIP_TRY(ctx, hipMemsetAsync(T.outdeg, 0, (size_t)(n + 1) * 4, s));
-    HIP_TRY(ctx, hipMemsetAsync(T.qcount, 0, 64 * 4, s));
-    HIP_TRY(ctx, hipMemsetAsync(T.ext_indeg, 0, (size_t)(n + 1) * 4, s));
-    HIP_TRY(ctx, hipMemsetAsync(T.ext_left, 0, (size_t)(n + 1) * 4, s));
+    HIP_TRY(ctx, hipMemsetAsync(zero_lo, 0, (size_t)(zero_hi - zero_lo), s));
+    HIP_TRY(ctx, hipMemsetAsync(zero_hi, 0xff, (size_t)(ones_hi - zero_hi), s));
     const bool part_depth = by_depth && n_parts <= DEPTH_MAX_PARTS && ctx->max_arity < 60000;
-    if (part_depth) {
-        HIP_TRY(ctx, hipMemsetAsync(g_dep, 0, (size_t)(n + 1) * 4, s));
-        HIP_TRY(ctx, hipMemsetAsync(inbox, 0xff, (size_t)n_parts * DEPTH_PART * 4, s));
-        HIP_TRY(ctx, hipMemsetAsync(inbox_tail, 0, (size_t)(n_parts + 1) * 4, s));
-    }
-    HIP_TRY(ctx, hipMemsetAsync(T.pu_start, 0, n_slots * 4, s));
-    HIP_TRY(ctx, hipMemsetAsync(T.pu_end, 0, n_slots * 4, s));
     K(k_node_init, n, T, by_depth);
     if (E > 0) K(k_edge_init, E, T, ctx->key_a, ctx->val_a);
     HIP_TRY(ctx, prim_scan_u32(T.outdeg, T.succ_off, (size_t)n + 1, nullptr, ctx->scratch, s));
@@ -1440,18 +1440,12 @@ int sched_enqueue(ob_ctx *ctx)
             hipLaunchKernelGGL(k_depth_frontier, dim3(1), dim3(FRONTIER_THREADS), 0, s, T, succ_node);
         ++ctx->n_launch_sched;
         if (agenda) {   // steps become agenda iterations; T.step holds the depths until k_agenda rewrites it
-            HIP_TRY(ctx, hipMemsetAsync(AG.keys, 0, (size_t)AG_TABLE * 8, s));
-            HIP_TRY(ctx, hipMemsetAsync(AG.sum, 0, (size_t)AG_TABLE * 8, s));
-            HIP_TRY(ctx, hipMemsetAsync(AG.cnt, 0, (size_t)AG_TABLE * 4, s));
-            HIP_TRY(ctx, hipMemsetAsync(AG.first, 0xff, (size_t)AG_TABLE * 4, s));
             K(k_class_insert, n, T, AG);
             hipLaunchKernelGGL(k_class_rank, dim3(1), dim3(1024), 0, s, T, AG);
             K(k_class_of, n, T, AG);
             hipLaunchKernelGGL(k_agenda, dim3(1), dim3(AGENDA_THREADS), 0, s, T, AG, succ_node);
             ctx->n_launch_sched += 2;
         }
-        HIP_TRY(ctx, hipMemsetAsync(T.ht_keys, 0, (size_t)ht_size * 8, s));
-        HIP_TRY(ctx, hipMemsetAsync(T.ht_vals, 0xff, (size_t)ht_size * 4, s));
         K(k_rep_insert, n, T);
     }
     K(k_sort_keys, n, T, ctx->key_a, ctx->val_a, by_depth);
@@ -1482,10 +1476,7 @@ int sched_enqueue(ob_ctx *ctx)
 
     // ---- launch planning: slots, chains, tile descriptors ----
     const int fuse = by_depth && ctx->fuse;
-    if (fuse && E > 0) {
-        HIP_TRY(ctx, hipMemsetAsync(bset, 0, (size_t)BSET_SIZE * 4, s));
-        K(k_bedges, E, T, bset, blist);
-    }
+    if (fuse && E > 0) K(k_bedges, E, T, bset, blist);
     hipLaunchKernelGGL(k_slots, dim3(1), dim3(SLOT_THREADS), 0, s, T, (fuse && E > 0) ? ctx->fuse : 0, blist);
     ++ctx->n_launch_sched;
     K(k_launch_keys, n, T, ctx->key_a, ctx->val_a, n);
