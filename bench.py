@@ -110,6 +110,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="tagger", choices=list(wl.CONFIGS))
     ap.add_argument("--pool", type=int, default=6, help="distinct seeded minibatches cycled through")
+    ap.add_argument("--instances", type=int, default=None,
+                    help="instances per minibatch (default: the configuration's own count; other values are sweep "
+                         "points, not the headline workload)")
     ap.add_argument("--launch", default="stream", choices=["stream", "graph"])
     ap.add_argument("--mode", default="depth", choices=["depth", "agenda"],
                     help="batching strategy of Section 3.2: depth-based (default, the configuration the stored "
@@ -144,7 +147,9 @@ def main():
     cfg = wl.CONFIGS[args.workload]
     params = cfg["params"]()
     pool = max(1, min(args.pool, args.steps + args.warmup))
-    graphs = [cfg["batch"](params, j) for j in range(pool)]
+    graphs = [cfg["batch"](params, j, n=args.instances) for j in range(pool)]
+    # device arena per context: 1 GiB holds the configurations as listed; larger sweep points get more
+    arena_bytes = (1 << 30) * max(1, -(-graphs[0].n_instances // 64))
     launch = ob.OB_LAUNCH_GRAPH if args.launch == "graph" else ob.OB_LAUNCH_STREAM
 
     # One context per pooled minibatch, all sharing one parameter set (forks of the first) and one
@@ -159,13 +164,13 @@ def main():
     t_up = []
     for j, g in enumerate(graphs):
         if j == 0:
-            c = ob.Context(arena_bytes=1 << 30, stream=stream, launch=launch, sched_stream=sched_stream,
+            c = ob.Context(arena_bytes=arena_bytes, stream=stream, launch=launch, sched_stream=sched_stream,
                            mode=ob.OB_BYAGENDA if args.mode == "agenda" else ob.OB_BYDEPTH)
             c.set_fusion(0 if args.no_fusion else (2 if args.placement == "late" else 1))
             c.params_create(params)
             c.param_grad_zero()
         else:
-            c = ctxs[0].fork(arena_bytes=1 << 30, stream=stream, sched_stream=sched_stream)
+            c = ctxs[0].fork(arena_bytes=arena_bytes, stream=stream, sched_stream=sched_stream)
         t0 = time.perf_counter()
         c.add_bulk(g)
         c.upload()
@@ -292,7 +297,7 @@ def main():
     # unbatched GPU run of the same graphs (one launch per node forward, per node backward)
     nobatch = None
     if not args.no_nobatch:
-        c = ob.Context(arena_bytes=1 << 30, stream=stream, mode=ob.OB_NOBATCH, launch=ob.OB_LAUNCH_STREAM)
+        c = ob.Context(arena_bytes=arena_bytes, stream=stream, mode=ob.OB_NOBATCH, launch=ob.OB_LAUNCH_STREAM)
         c.params_create(params)
         c.param_grad_zero()
         c.add_bulk(graphs[0])
@@ -338,7 +343,10 @@ def main():
         "config": {"workload": (f"config {cfg['index']}: {args.workload} (BASELINE.json configs[{cfg['index'] - 1}])"
                                 if cfg["index"] else f"{args.workload}: the equal-length synthetic tagger of Section 4.1 "
                                                      "(not one of BASELINE.json's configs)"),
-                   "instances_per_step": graphs[0].n_instances, "mode": "by" + args.mode, "launch": args.launch,
+                   "instances_per_step": graphs[0].n_instances,
+                   "sweep_point": (None if args.instances is None else
+                                   f"{args.instances} instances per minibatch instead of the configuration's own count"),
+                   "mode": "by" + args.mode, "launch": args.launch,
                    "fusion": not args.no_fusion, "placement": args.placement, "update": bool(args.update),
                    "pipeline": "scheduling of step i+1 overlaps execution of step i (second stream)" if pipeline
                    else "none (schedule, forward, backward back to back)",

@@ -546,20 +546,30 @@ def sync_tagger_minibatch(params: Params, seed: int = SEED_BASE + 601, n_sent: i
     return g.finish(root, n_sent, lengths=[length] * n_sent, n_tokens=n_sent * length, workload="sync_tagger")
 
 
+def _sized(fn, key):
+    """Minibatch generator with an optional instance count (None: the configuration's own)."""
+    def batch(p, j=0, n=None, **kw):
+        if n is not None:
+            kw[key] = int(n)
+        return fn(p, j, **kw)
+    return batch
+
+
 CONFIGS = {
     "rnn": dict(index=1, params=lambda: rnn_params(SEED_BASE + 100),
-                batch=lambda p, j=0: rnn_minibatch(p, SEED_BASE + 101 + j)),
+                batch=_sized(lambda p, j, **kw: rnn_minibatch(p, SEED_BASE + 101 + j, **kw), "n_inst")),
     "tagger": dict(index=2, params=lambda: tagger_params(SEED_BASE + 200),
-                   batch=lambda p, j=0: tagger_minibatch(p, SEED_BASE + 201 + j)),
+                   batch=_sized(lambda p, j, **kw: tagger_minibatch(p, SEED_BASE + 201 + j, **kw), "n_sent")),
     "tagger_char": dict(index=3, params=lambda: tagger_params(SEED_BASE + 300, with_char=True),
-                        batch=lambda p, j=0: tagger_minibatch(p, SEED_BASE + 301 + j, with_char=True)),
+                        batch=_sized(lambda p, j, **kw: tagger_minibatch(p, SEED_BASE + 301 + j, with_char=True, **kw),
+                                     "n_sent")),
     "tree": dict(index=4, params=lambda: tree_params(SEED_BASE + 400),
-                 batch=lambda p, j=0: tree_minibatch(p, SEED_BASE + 401 + j)),
+                 batch=_sized(lambda p, j, **kw: tree_minibatch(p, SEED_BASE + 401 + j, **kw), "n_trees")),
     "parser": dict(index=5, params=lambda: parser_params(SEED_BASE + 500),
-                   batch=lambda p, j=0: parser_minibatch(p, SEED_BASE + 501 + j)),
+                   batch=_sized(lambda p, j, **kw: parser_minibatch(p, SEED_BASE + 501 + j, **kw), "n_sent")),
     # not one of the five listed configurations: Section 4.1's synthetic benchmark (index 0)
     "sync_tagger": dict(index=0, params=lambda: sync_tagger_params(SEED_BASE + 600),
-                        batch=lambda p, j=0: sync_tagger_minibatch(p, SEED_BASE + 601 + j)),
+                        batch=_sized(lambda p, j, **kw: sync_tagger_minibatch(p, SEED_BASE + 601 + j, **kw), "n_sent")),
 }
 
 
