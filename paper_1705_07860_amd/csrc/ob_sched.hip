@@ -1534,7 +1534,9 @@ int sched_finish(ob_ctx *ctx)
 {
     Tables &T = ctx->T;
     hipStream_t s = ctx->sched_stream;
-    HIP_TRY(ctx, hipStreamSynchronize(s));
+    // wait for this context's own scheduling work only (its event was recorded behind the header
+    // copy): other contexts may already have queued theirs on the same stream
+    HIP_TRY(ctx, hipEventSynchronize(ctx->ev[9]));
     const char *hp = (const char *)ctx->hdr_pinned;
     ctx->hdr = *(const SchedHeader *)hp;
     ctx->hdr.n_items = ctx->n_items_sched;
