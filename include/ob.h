@@ -151,7 +151,12 @@ int ob_add_bulk(ob_ctx *ctx, int n, const uint8_t *op, const uint32_t *out_dim,
 int ob_upload(ob_ctx *ctx);
 /* Evaluates every node with id <= node (Section 3.1: evaluation happens when a value is
  * requested).  Schedules on the GPU (Section 3.2), then runs the batches in order
- * (Section 3.3).  Asynchronous except for one small read of the schedule header. */
+ * (Section 3.3).  Asynchronous except for one small read of the schedule header.
+ * A node beyond the evaluated prefix (a later ob_forward with a larger id, or nodes added after
+ * an evaluation) makes the library drop the evaluation and schedule and evaluate the whole longer
+ * prefix again: results are the same as Section 3.1's evaluation of only the new nodes, the work
+ * is not saved.  Adding a node to an evaluated graph drops the evaluation at once: values and
+ * gradients cannot be read again before the next ob_forward. */
 int ob_forward(ob_ctx *ctx, int node);
 /* Only the scheduling half of ob_forward (upload, Section 3.2's batching on the GPU, layout and
  * launch plan); a later ob_forward of the same node then only executes.  Blocks the host for one

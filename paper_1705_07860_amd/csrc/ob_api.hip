@@ -348,9 +348,15 @@ static int validate_node(ob_ctx *ctx, u32 n_before, const std::vector<u32> &dims
     }
 }
 
+static int forget_evaluation(ob_ctx *ctx);
+
 static int append_node(ob_ctx *ctx, int op, const u32 *ins, u32 arity, int param, int bias, int a0, int a1, u32 dim)
 {
-    if (ctx->n_sched) return ctx_fail(ctx, OB_E_STATE, "the graph was already evaluated; incremental forward is not built");
+    // extending a graph that was already evaluated: the evaluation is dropped, the next ob_forward
+    // schedules and evaluates the whole graph again (Section 3.1's lazy evaluation, without the
+    // saving of evaluating only what is new)
+    if (ctx->n_sched)
+        if (int rc = forget_evaluation(ctx)) return rc;
     if (ctx->op.size() >= 0x7ffffff0u) return ctx_fail(ctx, OB_E_RANGE, "too many nodes");
     ctx->op.push_back((u8)op);
     ctx->out_dim.push_back(dim);
@@ -472,7 +478,8 @@ int ob_add_bulk(ob_ctx *ctx, int n, const uint8_t *op, const uint32_t *out_dim, 
     CHECK_CTX(ctx);
     if (n <= 0) return ctx_fail(ctx, OB_E_ARG, "n = %d", n);
     if (!op || !out_dim || !in_off || !param || !bias || !aux0 || !aux1) return ctx_fail(ctx, OB_E_ARG, "null array");
-    if (ctx->n_sched) return ctx_fail(ctx, OB_E_STATE, "the graph was already evaluated; incremental forward is not built");
+    if (ctx->n_sched)
+        if (int rc = forget_evaluation(ctx)) return rc;
     sync_used_flags(ctx);
     const u32 n0 = (u32)ctx->op.size();
     if ((u64)n0 + (u64)n >= 0x7ffffff0ull) return ctx_fail(ctx, OB_E_RANGE, "too many nodes");
@@ -576,7 +583,8 @@ int ob_upload(ob_ctx *ctx)
     if (ctx->uploaded) return OB_OK;
     if (!ctx->arena) return ctx_fail(ctx, OB_E_STATE, "the context has no device arena");
     if (ctx->op.empty()) return ctx_fail(ctx, OB_E_STATE, "empty graph");
-    if (ctx->n_sched) return ctx_fail(ctx, OB_E_STATE, "the graph was already evaluated; incremental forward is not built");
+    if (ctx->n_sched)
+        if (int rc = forget_evaluation(ctx)) return rc;
     if (int rc = ensure_events(ctx)) return rc;
     if (int rc = params_to_device(ctx)) return rc;
     ctx->top = ctx->persist_top;
@@ -636,7 +644,8 @@ static int schedule_begin(ob_ctx *ctx, int node)
     if (node < 0 || node >= (int)ctx->op.size()) return ctx_fail(ctx, OB_E_BADID, "unknown node id %d", node);
     if (ctx->n_sched) {
         if ((u32)node < ctx->n_sched) return OB_OK;   // already scheduled (or being scheduled)
-        return ctx_fail(ctx, OB_E_STATE, "incremental forward (nodes beyond the evaluated prefix) is not built");
+        // a node beyond the evaluated prefix: schedule and evaluate the longer prefix from the start
+        if (int rc = forget_evaluation(ctx)) return rc;
     }
     if (int rc = ob_upload(ctx)) return rc;
     Tables &T = ctx->T;
@@ -715,15 +724,20 @@ static int wait_own_work(ob_ctx *ctx)
     return 0;
 }
 
-int ob_reset(ob_ctx *ctx)
+static int forget_evaluation(ob_ctx *ctx)
 {
-    CHECK_CTX(ctx);
     if (int rc = wait_own_work(ctx)) return rc;
     ctx->sched_pending = false;
     ctx->n_sched = 0;
     ctx->forward_done = ctx->backward_done = false;
     if (ctx->uploaded) ctx->top = ctx->graph_top;
-    return OB_OK;
+    return 0;
+}
+
+int ob_reset(ob_ctx *ctx)
+{
+    CHECK_CTX(ctx);
+    return forget_evaluation(ctx);
 }
 
 int ob_sync(ob_ctx *ctx)

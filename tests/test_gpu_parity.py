@@ -250,9 +250,13 @@ def test_edge_cases_single_node_and_prefix_forward():
     assert c.value_read(x, 1)[0] == 1.0
     c.backward(x)
     assert c.grad_read(x, 1)[0] == 1.0
+    # extending an evaluated graph drops the evaluation; the next forward evaluates all of it again
+    y = c.add_input(np.full(1, 2.5, dtype=np.float32))
     with pytest.raises(ob.ObError) as e:
-        c.add_input(np.zeros(3))                     # incremental forward is not built
+        c.value_read(x, 1)                           # nothing is evaluated at the moment
     assert e.value.code == -6
+    c.forward(y)
+    assert c.value_read(x, 1)[0] == 1.0 and c.value_read(y, 1)[0] == 2.5
     # graph_new starts over; forward of a prefix evaluates only ids <= node
     c.graph_new()
     g = wl.rnn_minibatch(p, seed=5, lengths=[2, 4])
@@ -276,6 +280,52 @@ def test_edge_cases_single_node_and_prefix_forward():
     with pytest.raises(ob.ObError) as e:
         c.value_read(0, 3)                           # capacity too small
     assert e.value.code == -3
+    c.close()
+
+
+def _graph_part(g, lo, hi):
+    """Nodes lo .. hi-1 of a graph as the arrays of one bulk call (operand ids stay global)."""
+    from paper_1705_07860_amd.workloads import Graph
+    e0, e1 = int(g.in_off[lo]), int(g.in_off[hi])
+    return Graph(op=g.op[lo:hi], out_dim=g.out_dim[lo:hi], in_off=g.in_off[lo:hi + 1] - e0, in_idx=g.in_idx[e0:e1],
+                 param=g.param[lo:hi], bias=g.bias[lo:hi], aux0=g.aux0[lo:hi], aux1=g.aux1[lo:hi], payload=g.payload,
+                 root=hi - 1)
+
+
+def test_forward_in_stages_and_graph_extension(workload_cache):
+    """Section 3.1: evaluation happens when a value is asked for, and the graph may grow afterwards.
+    A forward of a longer prefix, and a forward after nodes were added to an evaluated graph, give
+    the same values and gradients as one forward of the finished graph (the library evaluates the
+    whole prefix again in both cases)."""
+    from paper_1705_07860_amd import binding as ob
+    p, g, o = workload_cache("rnn")
+    total = int(o.v_off[-1])
+    first_sq = int(np.nonzero(g.op == wl.OP_SQNORM)[0][0])
+    # (a) the whole graph is known; forward of a prefix, then of everything
+    c = ob.Context(arena_bytes=64 << 20)
+    c.params_create(p)
+    c.param_grad_zero()
+    c.add_bulk(g)
+    c.forward(first_sq)
+    early = c.value_read(first_sq, 1)[0]
+    assert abs(early - o.value(first_sq)[0]) <= TOL * abs(o.value(first_sq)[0])
+    c.forward(g.root)
+    check_against_oracle(c, p, g, o, g.root, what="rnn/staged forward")
+    c.close()
+    # (b) the graph is built in two parts around an evaluation
+    c = ob.Context(arena_bytes=64 << 20)
+    c.params_create(p)
+    c.param_grad_zero()
+    k = first_sq + 1
+    assert c.add_bulk(_graph_part(g, 0, k)) == 0
+    c.forward(first_sq)
+    assert c.value_read(first_sq, 1)[0] == early
+    assert c.add_bulk(_graph_part(g, k, g.n)) == k
+    c.forward(g.root)
+    check_against_oracle(c, p, g, o, g.root, what="rnn/extended graph")
+    bo, ids, bd, _ = c.schedule_read()
+    rbo, rids, rbd = S.by_depth(g)
+    assert np.array_equal(bo, rbo) and np.array_equal(ids, rids) and np.array_equal(bd, rbd)
     c.close()
 
 
