@@ -169,3 +169,19 @@ def test_agenda_invariants_on_configs(name, workload_cache):
     # (the heuristic does not always give fewer batches than depth-based batching: the tree
     # workload gets more)
     print(name, "batches: agenda", len(bs), "depth", len(S.by_depth(g)[2]))
+
+
+def test_generators_take_an_instance_count_and_keep_their_default():
+    """The benchmark's sweep asks the generators for other instance counts; without a count they
+    give the configuration as listed (same arrays as before for the same seed)."""
+    from paper_1705_07860_amd import workloads as wl
+    for name, default in (("rnn", 8), ("tagger", 64), ("tree", 64), ("parser", 64)):
+        cfg = wl.CONFIGS[name]
+        p = cfg["params"]()
+        g0 = cfg["batch"](p, 0)
+        g1 = cfg["batch"](p, 0, n=None)
+        assert g0.n_instances == default and g0.n == g1.n and np.array_equal(g0.in_idx, g1.in_idx)
+        small = cfg["batch"](p, 0, n=3)
+        assert small.n_instances == 3 and small.n < g0.n
+        bo, ids, bd = S.by_depth(small)
+        assert np.array_equal(np.sort(ids), np.arange(small.n))
