@@ -17,8 +17,12 @@ HEADERS = ["ob_internal.h", "ob_ctx.h", "../../include/ob.h"]
 
 # Packed fp32 instructions are switched off for all device code (the compiler would otherwise
 # form them from ordinary float arithmetic).
+# Leading scalar and pointer kernel arguments are preloaded into scalar registers at wave start
+# (the step kernels put what they need first there), so their first loads do not wait for a
+# read of the argument block.
 FLAGS = ["-O3", "-std=c++17", "-fPIC", "--offload-arch=gfx950", "-Wall", "-Wno-unused-function",
-         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
+         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+         "-mllvm", "-amdgpu-kernarg-preload-count=16"]
 
 
 def _hipcc() -> str:

@@ -933,17 +933,20 @@ extern __shared__ __align__(16) float dyn_lds[];   // sized per launch: GEMM red
 // LEAN: the launch holds component-wise work only; this instantiation carries no GEMM or
 // reduction code, needs half the registers and keeps twice the waves per CU.
 template <bool LEAN>
-__global__ __launch_bounds__(WG, LEAN ? 6 : 4) void k_fwd_step(Tables T, u32 work_lo, u32 work_hi, u32 tile_lo, u32 run_len)
+__global__ __launch_bounds__(WG, LEAN ? 6 : 4) void k_fwd_step(u32 work_lo, u32 work_hi, u32 tile_lo, u32 run_len,
+                                                                const TileDesc *tiles_f, const WorkRec *works_f, Tables T)
 {
+    // the leading arguments arrive in scalar registers with the wave (so the descriptor loads start
+    // at once); the table of pointers behind them is read from the argument block
     float *lds = dyn_lds;
     __shared__ __align__(16) TileDesc sdesc[RUN_STAGE];
     const u32 lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     for (u32 w = work_lo + blockIdx.x; w < work_hi; w += gridDim.x) {
         WorkRec wr;
         if (run_len) { wr.first = tile_lo + (w - work_lo) * run_len; wr.len = run_len; }
-        else wr = T.works_f[w];
+        else wr = works_f[w];
         if (wr.len == 1) {
-            const TileDesc d = T.tiles_f[wr.first];
+            const TileDesc d = tiles_f[wr.first];
             if (LEAN) ew_fwd_tile(T, d, (lds_float *)lds, threadIdx.x, WG);
             else run_fwd_tile(T, d, lds);
             continue;
@@ -951,7 +954,7 @@ __global__ __launch_bounds__(WG, LEAN ? 6 : 4) void k_fwd_step(Tables T, u32 wor
         for (u32 c0 = 0; c0 < wr.len; c0 += RUN_STAGE) {
             const u32 cn = wr.len - c0 < RUN_STAGE ? wr.len - c0 : RUN_STAGE;
             __syncthreads();
-            stage_descriptors<sizeof(TileDesc) / 4, WG>(T.tiles_f + wr.first + c0, sdesc, cn);
+            stage_descriptors<sizeof(TileDesc) / 4, WG>(tiles_f + wr.first + c0, sdesc, cn);
             __syncthreads();
             const bool heavy = __ballot(lane < cn && (sdesc[lane < cn ? lane : 0].flags & TF_GLOBAL_DEP)) != 0ull;
             u32 i = 0;
@@ -974,8 +977,9 @@ __global__ __launch_bounds__(WG, LEAN ? 6 : 4) void k_fwd_step(Tables T, u32 wor
 // pull computes; otherwise the host launches the pull range and the dX range one after the other.
 constexpr int BWD_THREADS = DX_WAVES * 64;
 template <bool LEAN>
-__global__ __launch_bounds__(BWD_THREADS, LEAN ? 5 : 4) void k_bwd_step(Tables T, u32 work_lo, u32 work_hi, u32 tile_lo,
-                                                                        u32 run_len, u32 dx_lo, u32 dx_hi)
+__global__ __launch_bounds__(BWD_THREADS, LEAN ? 5 : 4) void k_bwd_step(u32 work_lo, u32 work_hi, u32 tile_lo, u32 run_len,
+                                                                        u32 dx_lo, u32 dx_hi, const PullDesc *tiles_a,
+                                                                        const WorkRec *works_a, const TileDesc *tiles_b, Tables T)
 {
     float *lds = dyn_lds;
     __shared__ __align__(16) PullDesc sdesc[RUN_STAGE];
@@ -983,23 +987,23 @@ __global__ __launch_bounds__(BWD_THREADS, LEAN ? 5 : 4) void k_bwd_step(Tables T
     const u32 n_dx = dx_hi - dx_lo, n_items = n_dx + (work_hi - work_lo);
     for (u32 item = blockIdx.x; item < n_items; item += gridDim.x) {
         if (!LEAN && item < n_dx) {
-            const TileDesc d = T.tiles_b[dx_lo + item];
+            const TileDesc d = tiles_b[dx_lo + item];
             matvec_dx_tile(T, d, lds);
             continue;
         }
         const u32 w = work_lo + (item - n_dx);
         WorkRec wr;
         if (run_len) { wr.first = tile_lo + (w - work_lo) * run_len; wr.len = run_len; }
-        else wr = T.works_a[w];
+        else wr = works_a[w];
         if (wr.len == 1) {
-            const PullDesc d = T.tiles_a[wr.first];
+            const PullDesc d = tiles_a[wr.first];
             pull_tile(T, d, (lds_float *)lds, threadIdx.x, BWD_THREADS);
             continue;
         }
         for (u32 c0 = 0; c0 < wr.len; c0 += RUN_STAGE) {
             const u32 cn = wr.len - c0 < RUN_STAGE ? wr.len - c0 : RUN_STAGE;
             __syncthreads();
-            stage_descriptors<sizeof(PullDesc) / 4, BWD_THREADS>(T.tiles_a + wr.first + c0, sdesc, cn);
+            stage_descriptors<sizeof(PullDesc) / 4, BWD_THREADS>(tiles_a + wr.first + c0, sdesc, cn);
             __syncthreads();
             const bool heavy = __ballot(lane < cn && (sdesc[lane < cn ? lane : 0].lflags & TF_GLOBAL_DEP)) != 0ull;
             u32 i = 0;
@@ -1139,11 +1143,11 @@ static int launch_forward_steps(ob_ctx *ctx)
         const u32 lo = r.wf, hi = ctx->slots[st + 1].wf;
         if (hi > lo) {
             if (r.plain)
-                hipLaunchKernelGGL(k_fwd_step<true>, dim3(grid_for(hi - lo, GRID_CAP)), dim3(WG), slot_lds_bytes(r, 16), s, T,
-                                   lo, hi, r.tf, slot_run_len(r));
+                hipLaunchKernelGGL(k_fwd_step<true>, dim3(grid_for(hi - lo, GRID_CAP)), dim3(WG), slot_lds_bytes(r, 16), s,
+                                   lo, hi, r.tf, slot_run_len(r), T.tiles_f, T.works_f, T);
             else
                 hipLaunchKernelGGL(k_fwd_step<false>, dim3(grid_for(hi - lo, GRID_CAP)), dim3(WG),
-                                   slot_lds_bytes(r, FWD_LDS_MIN), s, T, lo, hi, r.tf, slot_run_len(r));
+                                   slot_lds_bytes(r, FWD_LDS_MIN), s, lo, hi, r.tf, slot_run_len(r), T.tiles_f, T.works_f, T);
             ++ctx->n_launch_fwd;
         }
     }
@@ -1163,19 +1167,19 @@ static int launch_backward_steps(ob_ctx *ctx)
         const u32 n_pull = e.wa - r.wa, n_dx = e.tb - r.tb;
         const size_t lds_bytes = slot_lds_bytes(r, BWD_LDS_MIN);
         if (n_pull && n_dx && r.dx_free) {
-            hipLaunchKernelGGL(k_bwd_step<false>, dim3(grid_for(n_pull + n_dx, GRID_CAP)), dim3(BWD_THREADS), lds_bytes, s, T,
-                               r.wa, e.wa, r.ta, slot_run_len(r), r.tb, e.tb);
+            hipLaunchKernelGGL(k_bwd_step<false>, dim3(grid_for(n_pull + n_dx, GRID_CAP)), dim3(BWD_THREADS), lds_bytes, s,
+                               r.wa, e.wa, r.ta, slot_run_len(r), r.tb, e.tb, T.tiles_a, T.works_a, T.tiles_b, T);
             ++ctx->n_launch_bwd;
             continue;
         }
         if (n_pull) {
             hipLaunchKernelGGL(k_bwd_step<true>, dim3(grid_for(n_pull, GRID_CAP)), dim3(BWD_THREADS), slot_lds_bytes(r, 16), s,
-                               T, r.wa, e.wa, r.ta, slot_run_len(r), 0u, 0u);
+                               r.wa, e.wa, r.ta, slot_run_len(r), 0u, 0u, T.tiles_a, T.works_a, T.tiles_b, T);
             ++ctx->n_launch_bwd;
         }
         if (n_dx) {
-            hipLaunchKernelGGL(k_bwd_step<false>, dim3(grid_for(n_dx, GRID_CAP)), dim3(BWD_THREADS), BWD_LDS_MIN, s, T, 0u, 0u,
-                               0u, 0u, r.tb, e.tb);
+            hipLaunchKernelGGL(k_bwd_step<false>, dim3(grid_for(n_dx, GRID_CAP)), dim3(BWD_THREADS), BWD_LDS_MIN, s, 0u, 0u,
+                               0u, 0u, r.tb, e.tb, T.tiles_a, T.works_a, T.tiles_b, T);
             ++ctx->n_launch_bwd;
         }
     }
