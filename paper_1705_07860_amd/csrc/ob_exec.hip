@@ -265,10 +265,18 @@ __device__ inline void red_fwd_tile(const Tables &T, const TileDesc &d)
         float mx = -INFINITY;
         for (u32 c = lane; c < K; c += 64) mx = fmaxf(mx, x[c]);
         mx = wave_max(mx);
+        // The first element that holds the maximum contributes exp(0) = 1: it stays out of the sum
+        // and log1p takes its place, so that a confident row (sum barely above 1) keeps the small
+        // part of its loss instead of rounding it away.
+        u32 am = 0xffffffffu;
+        for (u32 c = lane; c < K; c += 64)
+            if (x[c] == mx && c < am) am = c;
+        for (int o = 32; o > 0; o >>= 1) { const u32 t = (u32)__shfl_xor((int)am, o); am = t < am ? t : am; }
         float s = 0.f;
-        for (u32 c = lane; c < K; c += 64) s += expf(x[c] - mx);
+        for (u32 c = lane; c < K; c += 64)
+            if (c != am) s += expf(x[c] - mx);
         s = wave_sum(s);
-        if (lane == 0) T.V[d.val_off + row] = mx + logf(s) - x[T.s_aux0[d.pos0 + row]];
+        if (lane == 0) T.V[d.val_off + row] = log1pf(s) + (mx - x[T.s_aux0[d.pos0 + row]]);
     }
 }
 
@@ -782,10 +790,18 @@ __device__ inline float edge_term(const Tables &T, const lds_float *cl, bool fl,
     case EK_MUL: return ldg(T, cl, fl, dl, goff + col) * T.V[voff + col];
     case EK_DTANH: { const float y = T.V[voff + col]; return ldg(T, cl, fl, dl, goff + col) * (1.0f - y * y); }
     case EK_DSIGM: { const float y = T.V[voff + col]; return ldg(T, cl, fl, dl, goff + col) * y * (1.0f - y); }
-    case EK_NLS: {
+    case EK_NLS: {   // a1: the row's dimension
         const float lse = T.V[voff] + T.V[own + (u32)a0];
-        float p = expf(T.V[own + col] - lse);
-        if ((i32)col == a0) p -= 1.0f;
+        float p;
+        if ((i32)col == a0) {
+            // p_label - 1 as minus the sum of the other probabilities: no cancellation when p_label is close to 1
+            float others = 0.f;
+            for (i32 c = 0; c < a1; ++c)
+                if (c != a0) others += expf(T.V[own + (u32)c] - lse);
+            p = -others;
+        } else {
+            p = expf(T.V[own + col] - lse);
+        }
         return T.G[goff] * p;
     }
     case EK_SQN: return 2.0f * T.G[goff] * T.V[own + col];

@@ -50,7 +50,7 @@ enum : u32 {
     EK_MUL,         // += G[goff + c] * V[voff + c]         (CMULT, voff = the other operand)
     EK_DTANH,       // += G[goff + c] * (1 - V[voff + c]^2)
     EK_DSIGM,       // += G[goff + c] * V[voff + c] * (1 - V[voff + c])
-    EK_NLS,         // += G[goff] * (exp(x_c - lse) - [c == label]), lse = V[voff] + x_label
+    EK_NLS,         // += G[goff] * (exp(x_c - lse) - [c == label]), lse = V[voff] + x_label; a0 = label, a1 = dimension of x
     EK_SQN          // += 2 G[goff] x_c
 };
 

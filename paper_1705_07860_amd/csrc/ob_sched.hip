@@ -1265,7 +1265,7 @@ __global__ void k_edges(Tables T)
         break;
     }
     case OP_SLICE: r.kind = EK_RANGE; r.a0 = T.aux0[v]; r.a1 = T.aux1[v]; break;
-    case OP_PICK_NLS: r.kind = EK_NLS; r.voff = T.val_off[v]; r.a0 = T.aux0[v]; break;
+    case OP_PICK_NLS: r.kind = EK_NLS; r.voff = T.val_off[v]; r.a0 = T.aux0[v]; r.a1 = (i32)T.out_dim[T.in_idx[e]]; break;
     case OP_SQNORM: r.kind = EK_SQN; break;
     default: break;
     }

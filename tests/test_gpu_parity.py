@@ -131,6 +131,26 @@ def test_schedule_bit_exact_random_dags(seed):
     c.close()
 
 
+@pytest.mark.parametrize("seed", range(8))
+def test_random_dags_with_wider_rows(seed):
+    """Rows of 16 .. 64 elements take the float4 paths and larger weights make some predictions
+    confident: a PICK_NLS value close to zero (and the gradients behind it) must still be right
+    relative to its own size, which the kernels get from log1p of the sum without the maximum and
+    from the label's gradient as minus the sum of the other probabilities."""
+    from paper_1705_07860_amd import binding as ob
+    dim = (16, 32, 48, 64)[seed % 4]
+    p, g = wl.random_dag(920 + seed, n_nodes=60 + 25 * (seed % 7), dim=dim)
+    c, root = run_gpu(p, g, ob.OB_BYDEPTH, arena=256 << 20)
+    bo, ids, bd, _ = c.schedule_read()
+    rbo, rids, rbd = S.by_depth(g)
+    assert np.array_equal(bo, rbo) and np.array_equal(ids, rids) and np.array_equal(bd, rbd)
+    o = Oracle(g, p, "f64")
+    o.forward()
+    o.backward(g.root)
+    check_against_oracle(c, p, g, o, root, what=f"wide dag{seed} (dim {dim})")
+    c.close()
+
+
 def test_nobatch_schedule_is_one_node_per_batch(workload_cache):
     from paper_1705_07860_amd import binding as ob
     p, g, o = workload_cache("rnn")
