@@ -197,17 +197,23 @@ def main():
         if args.update:
             c.sgd_step(0.0, zero_grad=True)    # lr 0 keeps the pooled minibatches' numbers stationary
 
-    def run(first, count):
+    def run(first, count, marks=None):
         if pipeline:
             sched(first)
             for i in range(first, first + count):
                 if i + 1 < first + count:
                     sched(i + 1)
                 execute(i)
+                if marks is not None:
+                    marks.append(torch.cuda.Event(enable_timing=True))
+                    marks[-1].record(stream)
         else:
             for i in range(first, first + count):
                 sched(i)
                 execute(i)
+                if marks is not None:
+                    marks.append(torch.cuda.Event(enable_timing=True))
+                    marks[-1].record(stream)
 
     run(0, args.warmup)
     torch.cuda.synchronize()
@@ -219,6 +225,15 @@ def main():
     elapsed = time.perf_counter() - t0
     # per-phase HIP-event times (events were recorded inside the timed region; reading them is not timed)
     per_ctx_stats = [c.stats() for c in ctxs]
+    # spread of the step period: a second, untimed pass with one event per step on the execution
+    # stream (the events cost a little, so they stay out of the timed pass)
+    marks = []
+    run(args.warmup + args.steps, args.steps, marks)
+    torch.cuda.synchronize()
+    periods = sorted(a.elapsed_time(b) for a, b in zip(marks[:-1], marks[1:]))
+    step_period = (dict(median=round(periods[len(periods) // 2], 4), min=round(periods[0], 4), max=round(periods[-1], 4),
+                        note="ms between the ends of consecutive steps on the execution stream, untimed second pass")
+                   if periods else None)
     for i in range(args.steps):
         st = per_ctx_stats[(args.warmup + i) % pool]
         for k_ in phase:
@@ -352,6 +367,7 @@ def main():
                    else "none (schedule, forward, backward back to back)",
                    "pool": pool, "nodes_per_step": round(n_nodes / args.steps, 1)},
         "nodes_per_s": round(n_nodes / elapsed, 1),
+        "step_period_ms": step_period,
         "phase_ms_per_step": {k_: round(v / args.steps, 4) for k_, v in phase.items()},
         "launches_per_step": {k_: round(v / args.steps, 1) for k_, v in launches.items()},
         "depth_levels": per_ctx_stats[0]["n_steps"], "launch_slots": per_ctx_stats[0]["n_slots"],
