@@ -199,6 +199,7 @@ struct Tables {
     u32 *val_off; u32 *dx_off; u32 *opnd_off;
     u32 *dx_gsrc;          // per schedule position of a MATVEC node with one consumer: where that consumer's gradient row lies
     u32 *slot_of; u32 *label_of; u32 *lorder;
+    u32 *blevel;           // per batch: its step (depth mode) or its level inside its fused chain (agenda mode)
     ChainRec *chains; CLay *clay; u32 *chain_of_lpos;
     SlotRec *slots;
     WorkRec *works_f; WorkRec *works_a;

@@ -805,7 +805,24 @@ __global__ void k_chain_flags(Tables T, const u32 *sval, u32 *flag, u32 n_pad)
     flag[i] = (i < nb && (i == 0 || chain_key(T, sval[i]) != chain_key(T, sval[i - 1]))) ? 1u : 0u;
 }
 
-__global__ void k_chain_recs(Tables T, const u32 *flag, const u32 *flag_excl, CLay *clay_in, u32 n_pad)
+// whether batch c reads a result of batch y through a fusable dependency (the set k_bedges filled)
+__device__ inline bool bset_has(const u32 *bset, u32 c, u32 y)
+{
+    const u32 key = ((c << 13) | (y << 1)) + 1u;
+    u32 h = (key * 2654435761u) & (BSET_SIZE - 1);
+    for (u32 probe = 0; probe < BSET_SIZE; ++probe) {
+        const u32 k = bset[h];
+        if (k == key) return true;
+        if (k == 0u) return false;
+        h = (h + 1) & (BSET_SIZE - 1);
+    }
+    return false;
+}
+
+constexpr u32 LEVEL_MAX_MEMBERS = 32;   // chains with more members keep their step order and one tile group per member
+
+__global__ void k_chain_recs(Tables T, int agenda, const u32 *bset, const u32 *flag, const u32 *flag_excl, CLay *clay_in,
+                             u32 n_pad)
 {
     const u32 i = blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= n_pad) return;
@@ -820,6 +837,31 @@ __global__ void k_chain_recs(Tables T, const u32 *flag, const u32 *flag_excl, CL
         const u32 c = flag_excl[i];
         u32 k = 1;
         while (i + k < nb && !flag[i + k]) ++k;
+        // Members of a chain run level by level, the tiles of one level without a barrier between
+        // them.  In depth mode a member's level is its depth.  Agenda batches are steps of their
+        // own, so there the levels come from the dependencies inside the chain (level = 1 + the
+        // largest level of the members it reads), and the members are put in (level, batch) order.
+        if (!agenda || T.hdr->p0) {
+            for (u32 m = 0; m < k; ++m) T.blevel[T.lorder[i + m]] = T.batches[T.lorder[i + m]].step;
+        } else if (k > LEVEL_MAX_MEMBERS) {
+            for (u32 m = 0; m < k; ++m) T.blevel[T.lorder[i + m]] = m;
+        } else {
+            u32 ids[LEVEL_MAX_MEMBERS], lv[LEVEL_MAX_MEMBERS];
+            for (u32 m = 0; m < k; ++m) {
+                ids[m] = T.lorder[i + m];
+                u32 l = 0;
+                for (u32 mm = 0; mm < m; ++mm)
+                    if (lv[mm] + 1 > l && bset_has(bset, ids[m], ids[mm])) l = lv[mm] + 1;
+                lv[m] = l;
+            }
+            for (u32 m = 1; m < k; ++m) {   // stable insertion sort by level
+                const u32 id = ids[m], l = lv[m];
+                u32 j = m;
+                while (j > 0 && lv[j - 1] > l) { ids[j] = ids[j - 1]; lv[j] = lv[j - 1]; --j; }
+                ids[j] = id; lv[j] = l;
+            }
+            for (u32 m = 0; m < k; ++m) { T.lorder[i + m] = ids[m]; T.blevel[ids[m]] = lv[m]; }
+        }
         const BatchRec r0 = T.batches[T.lorder[i]];
         ChainRec cr;
         cr.first = i; cr.k = k; cr.slot = T.slot_of[T.lorder[i]];
@@ -1204,21 +1246,22 @@ __global__ void k_tiles(Tables T, const CLay *clay_ex, const CLay *total, u32 ca
                 const u32 g0 = rb * cr.Rg;
                 const u32 ng = (g0 + cr.Rg <= cr.G) ? cr.Rg : cr.G - g0;
                 const u32 row0 = g0 * mult + it;
-                // tiles of the same depth that follow this one in run order (this one included)
+                // tiles of the same level that follow this one in run order (this one included)
                 u32 glen = 1;
+                const u32 my_level = T.blevel[T.lorder[cr.first + m]];
                 if (cr.fused) {
                     if (which == 0) {
                         glen = mult - it;
                         for (u32 mm = m + 1; mm < cr.k; ++mm) {
                             const BatchRec &rn = T.batches[T.lorder[cr.first + mm]];
-                            if (rn.step != r.step) break;
+                            if (T.blevel[T.lorder[cr.first + mm]] != my_level) break;
                             glen += rn.B / cr.G;
                         }
                     } else {
                         glen = it + 1;
                         for (u32 mm = m; mm-- > 0;) {
                             const BatchRec &rn = T.batches[T.lorder[cr.first + mm]];
-                            if (rn.step != r.step) break;
+                            if (T.blevel[T.lorder[cr.first + mm]] != my_level) break;
                             glen += rn.B / cr.G;
                         }
                     }
@@ -1383,7 +1426,7 @@ int sched_enqueue(ob_ctx *ctx)
     A(T.s_in_off, u32, n + 1);
     A(T.batch_off, u32, n + 1); A(T.batches, BatchRec, n); A(T.lay, Lay, n); A(T.b_indim, u32, E + 1);
     A(T.val_off, u32, n); A(T.dx_off, u32, n); A(T.opnd_off, u32, E + 1); A(T.dx_gsrc, u32, n);
-    A(T.slot_of, u32, n); A(T.label_of, u32, n);
+    A(T.slot_of, u32, n); A(T.label_of, u32, n); A(T.blevel, u32, n);
     A(T.lorder, u32, n); A(T.chains, ChainRec, n); A(T.clay, CLay, n); A(T.chain_of_lpos, u32, n);
     // a plan has at most one slot per node; twice that leaves room for plans that insert slots
     const size_t slot_cap = 2 * (size_t)n + 4;
@@ -1489,7 +1532,7 @@ int sched_enqueue(ob_ctx *ctx)
     K(k_chain_flags, n, T, ctx->val_a, cflag, n);
     HIP_TRY(ctx, prim_scan_u32(cflag, cflag_excl, n, nullptr, ctx->scratch, s));
     K(k_clay_zero, n, clay_in, n);
-    K(k_chain_recs, n, T, cflag, cflag_excl, clay_in, n);
+    K(k_chain_recs, n, T, agenda, bset, cflag, cflag_excl, clay_in, n);
     HIP_TRY(ctx, prim_scan_clay(clay_in, T.clay, n, clay_total, ctx->scratch, s));
     ctx->n_launch_sched += 6;
     K(k_slot_init, (size_t)n + 2, T);
