@@ -117,6 +117,10 @@ def main():
     ap.add_argument("--mode", default="depth", choices=["depth", "agenda"],
                     help="batching strategy of Section 3.2: depth-based (default, the configuration the stored "
                          "profiles cover) or agenda-based")
+    ap.add_argument("--lookahead", type=int, default=0,
+                    help="minibatches scheduled ahead of the one that executes, each on a schedule stream of its own "
+                         "(default: 1 for depth-based batching, 2 for agenda-based batching, whose scheduling takes longer "
+                         "than its execution)")
     ap.add_argument("--no-pipeline", action="store_true",
                     help="schedule and execute each step back to back on one stream (no overlap between steps)")
     ap.add_argument("--no-fusion", action="store_true", help="one launch per depth level")
@@ -159,18 +163,20 @@ def main():
     # the GPU already schedules step i+1 (scheduling reads only the graph, never the parameters).
     pipeline = not args.no_pipeline
     stream = torch.cuda.Stream()
-    sched_stream = torch.cuda.Stream() if pipeline else None
+    lookahead = args.lookahead if args.lookahead > 0 else (2 if args.mode == "agenda" else 1)
+    lookahead = max(1, min(lookahead, max(1, pool - 2)))
+    sched_streams = [torch.cuda.Stream() for _ in range(lookahead)] if pipeline else [None]
     ctxs = []
     t_up = []
     for j, g in enumerate(graphs):
         if j == 0:
-            c = ob.Context(arena_bytes=arena_bytes, stream=stream, launch=launch, sched_stream=sched_stream,
+            c = ob.Context(arena_bytes=arena_bytes, stream=stream, launch=launch, sched_stream=sched_streams[0],
                            mode=ob.OB_BYAGENDA if args.mode == "agenda" else ob.OB_BYDEPTH)
             c.set_fusion(0 if args.no_fusion else (2 if args.placement == "late" else 1))
             c.params_create(params)
             c.param_grad_zero()
         else:
-            c = ctxs[0].fork(arena_bytes=arena_bytes, stream=stream, sched_stream=sched_stream)
+            c = ctxs[0].fork(arena_bytes=arena_bytes, stream=stream, sched_stream=sched_streams[j % len(sched_streams)])
         t0 = time.perf_counter()
         c.add_bulk(g)
         c.upload()
@@ -199,10 +205,11 @@ def main():
 
     def run(first, count, marks=None):
         if pipeline:
-            sched(first)
+            for a in range(min(lookahead, count)):
+                sched(first + a)
             for i in range(first, first + count):
-                if i + 1 < first + count:
-                    sched(i + 1)
+                if i + lookahead < first + count:
+                    sched(i + lookahead)
                 execute(i)
                 if marks is not None:
                     marks.append(torch.cuda.Event(enable_timing=True))
@@ -363,7 +370,8 @@ def main():
                                    f"{args.instances} instances per minibatch instead of the configuration's own count"),
                    "mode": "by" + args.mode, "launch": args.launch,
                    "fusion": not args.no_fusion, "placement": args.placement, "update": bool(args.update),
-                   "pipeline": "scheduling of step i+1 overlaps execution of step i (second stream)" if pipeline
+                   "pipeline": (f"scheduling of steps i+1..i+{lookahead} overlaps execution of step i ({lookahead} schedule "
+                                f"stream{'s' if lookahead > 1 else ''})") if pipeline
                    else "none (schedule, forward, backward back to back)",
                    "pool": pool, "nodes_per_step": round(n_nodes / args.steps, 1)},
         "nodes_per_s": round(n_nodes / elapsed, 1),
