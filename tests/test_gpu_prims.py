@@ -25,7 +25,7 @@ def test_scan(ctx, n):
 
 
 @pytest.mark.parametrize("n,lo,bits", [(1, 0, 8), (64, 0, 8), (1000, 0, 18), (1025, 32, 10), (4097, 0, 5),
-                                       (240000, 0, 18), (240000, 32, 18)])
+                                       (240000, 0, 18), (240000, 32, 18), (196608, 0, 12), (196609, 3, 12), (80000, 0, 17)])
 def test_radix_sort_is_stable_and_exact(ctx, n, lo, bits):
     rng = np.random.default_rng(n + lo)
     keys = rng.integers(0, 1 << 62, size=n, dtype=np.uint64)
