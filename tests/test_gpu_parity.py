@@ -631,31 +631,34 @@ def test_synthetic_equal_length_tagger_small():
         c.close()
 
 
-def test_full_size_pipelined_loop_as_benchmarked(workload_cache):
+@pytest.mark.parametrize("mode,lookahead", [("depth", 1), ("agenda", 2)])
+def test_full_size_pipelined_loop_as_benchmarked(workload_cache, mode, lookahead):
     """The loop bench.py times, at the tagger's full size: contexts forked from one parameter set,
-    one execution stream, scheduling of step i + 1 queued on a second stream before step i executes,
-    minibatches cycling through the contexts.  After the loop every context's values and node
-    gradients, and the parameter gradients of the last step, match the oracle."""
+    one execution stream, scheduling of steps i + 1 .. i + lookahead queued on schedule streams of
+    their own before step i executes, minibatches cycling through the contexts.  After the loop
+    every context's values and node gradients, and the parameter gradients of the last step, match
+    the oracle, and every context holds the schedule of its strategy (Section 3.2)."""
     import torch
     from paper_1705_07860_amd import binding as ob
     p, g0, o0 = workload_cache("tagger")
     cfg = wl.CONFIGS["tagger"]
-    graphs = [g0] + [cfg["batch"](p, j) for j in (1, 2)]
+    graphs = [g0] + [cfg["batch"](p, j) for j in range(1, 2 + lookahead)]
     oracles = [o0]
     for g in graphs[1:]:
         o = Oracle(g, p, "f64")
         o.forward()
         o.backward(g.root)
         oracles.append(o)
-    ex, sc = torch.cuda.Stream(), torch.cuda.Stream()
+    ex, scs = torch.cuda.Stream(), [torch.cuda.Stream() for _ in range(lookahead)]
     ctxs = []
     for j, g in enumerate(graphs):
         if j == 0:
-            c = ob.Context(arena_bytes=1 << 30, stream=ex, sched_stream=sc)
+            c = ob.Context(arena_bytes=1 << 30, stream=ex, sched_stream=scs[0],
+                           mode=ob.OB_BYAGENDA if mode == "agenda" else ob.OB_BYDEPTH)
             c.params_create(p)
             c.param_grad_zero()
         else:
-            c = ctxs[0].fork(arena_bytes=1 << 30, stream=ex, sched_stream=sc)
+            c = ctxs[0].fork(arena_bytes=1 << 30, stream=ex, sched_stream=scs[j % lookahead])
         c.add_bulk(g)
         c.upload()
         ctxs.append(c)
@@ -666,10 +669,11 @@ def test_full_size_pipelined_loop_as_benchmarked(workload_cache):
         c.reset()
         c.schedule_async(graphs[i % pool].root)
 
-    sched(0)
+    for i in range(lookahead):
+        sched(i)
     for i in range(steps):
-        if i + 1 < steps:
-            sched(i + 1)
+        if i + lookahead < steps:
+            sched(i + lookahead)
         c, g = ctxs[i % pool], graphs[i % pool]
         c.param_grad_zero()
         c.forward(g.root)
@@ -680,8 +684,12 @@ def test_full_size_pipelined_loop_as_benchmarked(workload_cache):
         assert segment_rel_err(c.all_read(0, total), o.val[:total], o.v_off) <= TOL
         assert segment_rel_err(c.all_read(1, total), o.grad[:total], o.v_off) <= TOL
         bo, ids, bd, _ = c.schedule_read()
-        rbo, rids, rbd = S.by_depth(g)
-        assert np.array_equal(bo, rbo) and np.array_equal(ids, rids) and np.array_equal(bd, rbd)
+        if mode == "depth":
+            rbo, rids, rbd = S.by_depth(g)
+            assert np.array_equal(bo, rbo) and np.array_equal(ids, rids) and np.array_equal(bd, rbd)
+        else:
+            rbo, rids, _ = S.by_agenda(g)
+            assert np.array_equal(bo, rbo) and np.array_equal(ids, rids)
     for pid, m in enumerate(p.mats):
         assert rel_err(ctxs[0].param_grad_read(pid, m.shape), oracles[last].param_grad(pid)) <= TOL, p.names[pid]
     for c in reversed(ctxs):
