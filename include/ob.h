@@ -69,6 +69,8 @@ typedef struct ob_ctx ob_ctx;
 #define OB_BYAGENDA 2      /* agenda-based batching (Section 3.2): signatures ranked by the average depth of their
                             * nodes (exact), then cheap before heavy operations, then first node id; at most 1024
                             * distinct signatures per graph, else OB_E_STATE at schedule time */
+#define OB_MANUAL 3        /* manual batching (Section 2): the caller names the batch of every node with
+                            * ob_set_manual_batches; signatures, depths and the agenda are not computed */
 
 /* how the per-step launches are issued */
 #define OB_LAUNCH_STREAM 0     /* one kernel launch per step on the stream            */
@@ -144,6 +146,17 @@ int ob_add_bulk(ob_ctx *ctx, int n, const uint8_t *op, const uint32_t *out_dim,
                 const uint32_t *in_off, const uint32_t *in_idx, const int32_t *param,
                 const int32_t *bias, const int32_t *aux0, const int32_t *aux1,
                 const float *payload, size_t payload_len);
+
+/* Manual batching (Section 2: the programmer groups by hand the operations that run together).
+ * batch_of_node (host, copied) holds one label per node of the current graph, n = its node count:
+ * nodes with equal labels form one batch, batches run in ascending label order, the nodes of a
+ * batch keep ascending id order.  Labels need not be dense.  Checked here, on the host: labels are
+ * >= 0, every operand's label is smaller than its consumer's, and all nodes of a batch agree in
+ * operation, dimensions, arity, shared parameters, slice range and operand dimensions (else
+ * OB_E_ARG, naming the node).  Used by OB_MANUAL only; adding nodes afterwards or ob_graph_new
+ * drops the labels, and scheduling in OB_MANUAL without labels for every scheduled node fails with
+ * OB_E_STATE. */
+int ob_set_manual_batches(ob_ctx *ctx, const int32_t *batch_of_node, size_t n);
 
 /* ---- execution ------------------------------------------------------------------------------ */
 

@@ -18,7 +18,7 @@ import numpy as np
 HERE = Path(__file__).resolve().parent
 LIB_PATH = HERE / "libob.so"
 
-OB_NOBATCH, OB_BYDEPTH, OB_BYAGENDA = 0, 1, 2
+OB_NOBATCH, OB_BYDEPTH, OB_BYAGENDA, OB_MANUAL = 0, 1, 2, 3
 OB_LAUNCH_STREAM, OB_LAUNCH_GRAPH, OB_LAUNCH_PERSISTENT = 0, 1, 2
 OB_DBG_DEPTH, OB_DBG_SIG, OB_DBG_SUCC_OFF, OB_DBG_SUCC_EDGE, OB_DBG_ORDER, OB_DBG_VAL_OFF = range(6)
 OB_DBG_TILES_FWD, OB_DBG_TILES_PULL, OB_DBG_CHAINS = 6, 7, 8
@@ -92,6 +92,7 @@ def lib():
             "ob_add_pick_nls": (i, [vp, i, i]),
             "ob_add_sqnorm": (i, [vp, i]),
             "ob_add_bulk": (i, [vp, i, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz]),
+            "ob_set_manual_batches": (i, [vp, vp, sz]),
             "ob_upload": (i, [vp]),
             "ob_forward": (i, [vp, i]),
             "ob_backward": (i, [vp, i]),
@@ -262,6 +263,11 @@ class Context:
                 c(g.payload, np.float32) if g.payload.size else np.zeros(1, np.float32)]
         return self._ck(self.L.ob_add_bulk(self.h, int(g.op.shape[0]), *[_ptr(a) for a in arrs],
                                            int(g.payload.size)))
+
+    def set_manual_batches(self, batch_of_node):
+        """Manual batching: one batch label per node of the current graph (see OB_MANUAL)."""
+        a = np.ascontiguousarray(batch_of_node, np.int32)
+        self._ck(self.L.ob_set_manual_batches(self.h, _ptr(a), int(a.shape[0])))
 
     # -- execution
     def upload(self):

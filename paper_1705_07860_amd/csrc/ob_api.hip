@@ -87,10 +87,15 @@ int ob_ctx_destroy(ob_ctx *ctx)
     return OB_OK;
 }
 
+static int forget_evaluation(ob_ctx *ctx);
+
 int ob_ctx_set_mode(ob_ctx *ctx, int mode)
 {
     CHECK_CTX(ctx);
-    if (mode != OB_NOBATCH && mode != OB_BYDEPTH && mode != OB_BYAGENDA) return ctx_fail(ctx, OB_E_ARG, "unknown mode %d", mode);
+    if (mode != OB_NOBATCH && mode != OB_BYDEPTH && mode != OB_BYAGENDA && mode != OB_MANUAL)
+        return ctx_fail(ctx, OB_E_ARG, "unknown mode %d", mode);
+    if (mode != ctx->mode && ctx->n_sched)
+        if (int rc = forget_evaluation(ctx)) return rc;
     ctx->mode = mode;
     return OB_OK;
 }
@@ -256,6 +261,7 @@ int ob_graph_new(ob_ctx *ctx)
     ctx->op.clear(); ctx->out_dim.clear(); ctx->in_off.assign(1, 0); ctx->in_idx.clear();
     ctx->param.clear(); ctx->bias.clear(); ctx->aux0.clear(); ctx->aux1.clear(); ctx->payload.clear();
     ctx->items_upto.clear();
+    ctx->manual.clear();
     ctx->sum_out_dim = 0;
     ctx->max_arity = 0;
     ctx->sum_mv_d32 = ctx->sum_mv_k32 = 0;
@@ -348,8 +354,6 @@ static int validate_node(ob_ctx *ctx, u32 n_before, const std::vector<u32> &dims
     }
 }
 
-static int forget_evaluation(ob_ctx *ctx);
-
 static int append_node(ob_ctx *ctx, int op, const u32 *ins, u32 arity, int param, int bias, int a0, int a1, u32 dim)
 {
     // extending a graph that was already evaluated: the evaluation is dropped, the next ob_forward
@@ -358,6 +362,7 @@ static int append_node(ob_ctx *ctx, int op, const u32 *ins, u32 arity, int param
     if (ctx->n_sched)
         if (int rc = forget_evaluation(ctx)) return rc;
     if (ctx->op.size() >= 0x7ffffff0u) return ctx_fail(ctx, OB_E_RANGE, "too many nodes");
+    ctx->manual.clear();   // labels cover the graph they were given for
     ctx->op.push_back((u8)op);
     ctx->out_dim.push_back(dim);
     ctx->in_idx.insert(ctx->in_idx.end(), ins, ins + arity);
@@ -597,11 +602,13 @@ int ob_upload(ob_ctx *ctx)
 
     const size_t n = ctx->op.size(), E = ctx->in_idx.size(), P = ctx->payload.size();
     // one packed image: op | out_dim | in_off | in_idx | param | bias | aux0 | aux1 | payload
-    size_t off[10];
+    size_t off[11];
     size_t cur = 0;
-    const size_t sizes[9] = {n, n * 4, (n + 1) * 4, (E + 1) * 4, n * 4, n * 4, n * 4, n * 4, (P + 1) * 4};
-    for (int i = 0; i < 9; ++i) { off[i] = cur; cur += up256(sizes[i]); }
-    off[9] = cur;
+    const bool labels = ctx->manual.size() == n;
+    const size_t sizes[10] = {n, n * 4, (n + 1) * 4, (E + 1) * 4, n * 4, n * 4, n * 4, n * 4, (P + 1) * 4,
+                              labels ? n * 4 : 0};
+    for (int i = 0; i < 10; ++i) { off[i] = cur; cur += up256(sizes[i]); }
+    off[10] = cur;
     if (cur > ctx->pinned_bytes) {
         if (ctx->pinned) HIP_TRY(ctx, hipHostFree(ctx->pinned));
         ctx->pinned = nullptr;
@@ -618,6 +625,7 @@ int ob_upload(ob_ctx *ctx)
     memcpy(img + off[6], ctx->aux0.data(), n * 4);
     memcpy(img + off[7], ctx->aux1.data(), n * 4);
     if (P) memcpy(img + off[8], ctx->payload.data(), P * 4);
+    if (labels) memcpy(img + off[9], ctx->manual.data(), n * 4);
     char *dev = (char *)arena_alloc(ctx, cur);
     if (!dev) return ctx_fail(ctx, OB_E_OOM, "arena too small for the graph (%zu bytes)", cur);
     HIP_TRY(ctx, hipEventRecord(ctx->ev[0], ctx->sched_stream));
@@ -628,12 +636,55 @@ int ob_upload(ob_ctx *ctx)
     T.op = (const u8 *)(dev + off[0]); T.out_dim = (const u32 *)(dev + off[1]); T.in_off = (const u32 *)(dev + off[2]);
     T.in_idx = (const u32 *)(dev + off[3]); T.param = (const i32 *)(dev + off[4]); T.bias = (const i32 *)(dev + off[5]);
     T.aux0 = (const i32 *)(dev + off[6]); T.aux1 = (const i32 *)(dev + off[7]); T.payload = (const float *)(dev + off[8]);
+    T.manual = labels ? (const u32 *)(dev + off[9]) : nullptr;
     T.params = ctx->params_dev;
     T.n_params = (u32)ctx->params.size();
     T.root = 0xffffffffu;
     ctx->upload_bytes = cur;
     ctx->graph_top = ctx->top;
     ctx->uploaded = true;
+    return OB_OK;
+}
+
+// Manual batching (Section 2): the caller's grouping is checked against the two things any
+// batch needs -- operands come from earlier batches, members are the same operation on the same
+// shapes and shared parameters (the signature tuple of Section 3.2, compared field by field).
+int ob_set_manual_batches(ob_ctx *ctx, const int32_t *batch_of_node, size_t n)
+{
+    CHECK_CTX(ctx);
+    if (!batch_of_node) return ctx_fail(ctx, OB_E_ARG, "null label array");
+    if (n != ctx->op.size()) return ctx_fail(ctx, OB_E_ARG, "%zu labels for a graph of %zu nodes", n, ctx->op.size());
+    if (n == 0) return ctx_fail(ctx, OB_E_STATE, "empty graph");
+    u32 mx = 0;
+    for (size_t v = 0; v < n; ++v) {
+        if (batch_of_node[v] < 0) return ctx_fail(ctx, OB_E_ARG, "node %zu: negative batch label %d", v, batch_of_node[v]);
+        if ((u32)batch_of_node[v] > mx) mx = (u32)batch_of_node[v];
+        for (u32 e = ctx->in_off[v]; e < ctx->in_off[v + 1]; ++e)
+            if (batch_of_node[ctx->in_idx[e]] >= batch_of_node[v])
+                return ctx_fail(ctx, OB_E_ARG, "node %zu (batch %d) reads node %u of batch %d: operands must come from earlier batches",
+                                v, batch_of_node[v], ctx->in_idx[e], batch_of_node[ctx->in_idx[e]]);
+    }
+    // first node of every label, then every node against the first of its label
+    std::vector<u32> head((size_t)mx + 1, 0xffffffffu);
+    for (size_t v = 0; v < n; ++v) {
+        u32 &h = head[(u32)batch_of_node[v]];
+        if (h == 0xffffffffu) { h = (u32)v; continue; }
+        const u32 ar = ctx->in_off[v + 1] - ctx->in_off[v];
+        bool same = ctx->op[v] == ctx->op[h] && ctx->out_dim[v] == ctx->out_dim[h] &&
+                    ar == ctx->in_off[h + 1] - ctx->in_off[h] && ctx->param[v] == ctx->param[h] &&
+                    ctx->bias[v] == ctx->bias[h];
+        if (same && ctx->op[v] == OB_OP_SLICE) same = ctx->aux0[v] == ctx->aux0[h] && ctx->aux1[v] == ctx->aux1[h];
+        for (u32 j = 0; same && j < ar; ++j)
+            same = ctx->out_dim[ctx->in_idx[ctx->in_off[v] + j]] == ctx->out_dim[ctx->in_idx[ctx->in_off[h] + j]];
+        if (!same)
+            return ctx_fail(ctx, OB_E_ARG, "nodes %u and %zu of batch %d differ in operation, shapes or shared parameters",
+                            h, v, batch_of_node[v]);
+    }
+    if (ctx->n_sched)
+        if (int rc = forget_evaluation(ctx)) return rc;
+    ctx->manual.assign((const u32 *)batch_of_node, (const u32 *)batch_of_node + n);
+    ctx->manual_max = mx;
+    ctx->uploaded = false;
     return OB_OK;
 }
 
@@ -647,6 +698,8 @@ static int schedule_begin(ob_ctx *ctx, int node)
         // a node beyond the evaluated prefix: schedule and evaluate the longer prefix from the start
         if (int rc = forget_evaluation(ctx)) return rc;
     }
+    if (ctx->mode == OB_MANUAL && ctx->manual.size() != ctx->op.size())
+        return ctx_fail(ctx, OB_E_STATE, "manual batching: no batch labels for the current graph (ob_set_manual_batches)");
     if (int rc = ob_upload(ctx)) return rc;
     Tables &T = ctx->T;
     T.n = (u32)node + 1;

@@ -44,6 +44,8 @@ struct ob_ctx {
     std::vector<u32> out_dim, in_off, in_idx;
     std::vector<i32> param, bias, aux0, aux1;
     std::vector<float> payload;
+    std::vector<u32> manual;           // OB_MANUAL: the caller's batch label per node (empty = none given)
+    u32 manual_max = 0;                // largest label
     std::vector<u32> items_upto;       // parameter-use items among nodes [0, v]
     u64 sum_out_dim = 0;               // bounds the tile lists
     u32 max_arity = 0;

@@ -187,6 +187,7 @@ struct Tables {
     const u8 *op; const u32 *out_dim; const u32 *in_off; const u32 *in_idx;
     const i32 *param; const i32 *bias; const i32 *aux0; const i32 *aux1;
     const float *payload;
+    const u32 *manual;     // the caller's batch label per node (manual batching only, else null)
     const ParamDesc *params;
     // scheduler tables
     u64 *sig; u32 *step; u32 *indeg; u32 *outdeg; u32 *succ_off; u32 *succ_edge; u32 *edge_cons;

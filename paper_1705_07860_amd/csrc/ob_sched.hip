@@ -25,7 +25,9 @@ __device__ inline u64 comb(u64 h, u64 x) { return mix64(h ^ (x + 0x9e3779b97f4a7
 // PICK_NLS's label and INPUT's payload are data and stay out.  The node's own fields are hashed
 // here; every operand edge then adds a position-salted hash of the operand's dimension
 // (k_edge_init), so nodes with thousands of operands cost no more than a thread per edge.
-__global__ void k_node_init(Tables T, int by_depth)
+// steps: 0 = every node is its own step, 1 = steps come from the depth pass (leaves are queued
+// here), 2 = steps are the caller's batch labels.
+__global__ void k_node_init(Tables T, int steps)
 {
     const u32 v = blockIdx.x * blockDim.x + threadIdx.x;
     if (v >= T.n) return;
@@ -40,12 +42,14 @@ __global__ void k_node_init(Tables T, int by_depth)
     h = comb(h, o == OP_SLICE ? (u64)(u32)T.aux1[v] : 0);
     T.sig[v] = h;
     T.indeg[v] = hi - lo;
-    if (by_depth) {
+    if (steps == 1) {
         if (hi == lo) {
             const u32 pos = atomicAdd(&T.qcount[0], 1u);
             T.queue[pos] = v;
             T.step[v] = 0;
         }
+    } else if (steps == 2) {
+        T.step[v] = T.manual[v];   // manual batching: replaced by the label's rank once batches are cut
     } else {
         T.step[v] = v;   // unbatched: every node is its own step, in id order
     }
@@ -468,11 +472,13 @@ __global__ void k_rep_insert(Tables T)
     T.ht_slot[v] = 0;
 }
 
-__global__ void k_sort_keys(Tables T, u64 *keys, u32 *vals, int by_depth)
+// rep_src: 0 = the node itself (unbatched), 1 = the representative found by k_rep_insert,
+// 2 = none (manual batching: one batch per step, the stable sort keeps ids ascending)
+__global__ void k_sort_keys(Tables T, u64 *keys, u32 *vals, int rep_src)
 {
     const u32 v = blockIdx.x * blockDim.x + threadIdx.x;
     if (v >= T.n) return;
-    const u32 rep = by_depth ? T.ht_vals[T.ht_slot[v]] : v;
+    const u32 rep = rep_src == 1 ? T.ht_vals[T.ht_slot[v]] : (rep_src == 2 ? 0u : v);
     keys[v] = ((u64)T.step[v] << 32) | rep;
     vals[v] = v;
 }
@@ -492,12 +498,13 @@ __global__ void k_heads(Tables T, const u64 *skey, const u32 *sval, u32 *head_fl
     s_items[p] = (o == OP_MATVEC) ? (1u + (T.bias[v] >= 0 ? 1u : 0u)) : (o == OP_LOOKUP ? 1u : 0u);
 }
 
-__global__ void k_batch_off(Tables T, const u32 *head_flag, const u32 *head_excl)
+__global__ void k_batch_off(Tables T, const u32 *head_flag, const u32 *head_excl, int manual)
 {
     const u32 p = blockIdx.x * blockDim.x + threadIdx.x;
     if (p >= T.n) return;
     const u32 b = head_excl[p] + head_flag[p] - 1;
     T.batch_of_pos[p] = b;
+    if (manual) T.step[T.order[p]] = b;   // labels need not be dense: a batch's step is its rank
     if (head_flag[p]) T.batch_off[b] = p;
     if (p == T.n - 1) {
         T.batch_off[b + 1] = T.n;
@@ -1378,7 +1385,9 @@ int sched_enqueue(ob_ctx *ctx)
     Tables &T = ctx->T;
     hipStream_t s = ctx->sched_stream;
     const u32 n = T.n, E = T.E;
-    const int by_depth = ctx->mode != 0;   // batched: steps are depths (mode 1) or agenda iterations (mode 2)
+    const int manual = ctx->mode == 3;     // the caller's batches: no depth pass, no signatures to group by
+    const int by_depth = ctx->mode == 1 || ctx->mode == 2;   // steps are depths (mode 1) or agenda iterations (mode 2)
+    const int batched = ctx->mode != 0;
     const int agenda = ctx->mode == 2;
     ctx->n_launch_sched = 0;
 
@@ -1464,7 +1473,7 @@ int sched_enqueue(ob_ctx *ctx)
     HIP_TRY(ctx, hipMemsetAsync(zero_lo, 0, (size_t)(zero_hi - zero_lo), s));
     HIP_TRY(ctx, hipMemsetAsync(zero_hi, 0xff, (size_t)(ones_hi - zero_hi), s));
     const bool part_depth = by_depth && n_parts <= DEPTH_MAX_PARTS && ctx->max_arity < 60000;
-    K(k_node_init, n, T, by_depth);
+    K(k_node_init, n, T, manual ? 2 : by_depth);
     if (E > 0) K(k_edge_init, E, T, ctx->key_a, ctx->val_a);
     HIP_TRY(ctx, prim_scan_u32(T.outdeg, T.succ_off, (size_t)n + 1, nullptr, ctx->scratch, s));
     ctx->n_launch_sched += 3;
@@ -1491,8 +1500,11 @@ int sched_enqueue(ob_ctx *ctx)
         }
         K(k_rep_insert, n, T);
     }
-    K(k_sort_keys, n, T, ctx->key_a, ctx->val_a, by_depth);
-    if (by_depth) {
+    K(k_sort_keys, n, T, ctx->key_a, ctx->val_a, manual ? 2 : by_depth);
+    if (manual) {
+        HIP_TRY(ctx, prim_sort_pairs(ctx->key_a, ctx->val_a, ctx->key_b, ctx->val_b, n, 32, bit_width_u32(ctx->manual_max | 1u),
+                                     ctx->scratch, s, &ctx->n_launch_sched));
+    } else if (by_depth) {
         const int lb = bit_width_u32(n - 1);
         HIP_TRY(ctx, prim_sort_pairs(ctx->key_a, ctx->val_a, ctx->key_b, ctx->val_b, n, 0, lb, ctx->scratch, s,
                                      &ctx->n_launch_sched));
@@ -1507,7 +1519,7 @@ int sched_enqueue(ob_ctx *ctx)
     HIP_TRY(ctx, prim_scan_u32(s_arity, T.s_in_off, n, nullptr, ctx->scratch, s));
     HIP_TRY(ctx, prim_scan_u32(s_items, s_items, n, nullptr, ctx->scratch, s));
     ctx->n_launch_sched += 9;
-    K(k_batch_off, n, T, head_flag, head_excl);
+    K(k_batch_off, n, T, head_flag, head_excl, manual);
     K(k_batch_layout, n, T, ctx->lay_in);
     HIP_TRY(ctx, prim_scan_lay(ctx->lay_in, T.lay, n, ctx->lay_total, ctx->scratch, s));
     ctx->n_launch_sched += 3;
@@ -1518,7 +1530,7 @@ int sched_enqueue(ob_ctx *ctx)
     if (E > 0) K(k_edges, E, T);
 
     // ---- launch planning: slots, chains, tile descriptors ----
-    const int fuse = by_depth && ctx->fuse;
+    const int fuse = batched && ctx->fuse;
     if (fuse && E > 0) K(k_bedges, E, T, bset, blist);
     hipLaunchKernelGGL(k_slots, dim3(1), dim3(SLOT_THREADS), 0, s, T, (fuse && E > 0) ? ctx->fuse : 0, blist);
     ++ctx->n_launch_sched;
@@ -1532,7 +1544,7 @@ int sched_enqueue(ob_ctx *ctx)
     K(k_chain_flags, n, T, ctx->val_a, cflag, n);
     HIP_TRY(ctx, prim_scan_u32(cflag, cflag_excl, n, nullptr, ctx->scratch, s));
     K(k_clay_zero, n, clay_in, n);
-    K(k_chain_recs, n, T, agenda, bset, cflag, cflag_excl, clay_in, n);
+    K(k_chain_recs, n, T, agenda || manual, bset, cflag, cflag_excl, clay_in, n);
     HIP_TRY(ctx, prim_scan_clay(clay_in, T.clay, n, clay_total, ctx->scratch, s));
     ctx->n_launch_sched += 6;
     K(k_slot_init, (size_t)n + 2, T);

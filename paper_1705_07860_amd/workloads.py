@@ -546,6 +546,20 @@ def sync_tagger_minibatch(params: Params, seed: int = SEED_BASE + 601, n_sent: i
     return g.finish(root, n_sent, lengths=[length] * n_sent, n_tokens=n_sent * length, workload="sync_tagger")
 
 
+def sync_tagger_manual_labels(g: Graph) -> np.ndarray:
+    """Batch labels as a program batched by hand over the sentences would group the nodes
+    (Section 2): every sentence runs the same sequence of statements, so the k-th node of every
+    sentence is one statement over a matrix with a column per sentence.  The label of a node is
+    its index in its sentence's sequence; the closing sum over all losses comes last."""
+    n = int(g.op.shape[0])
+    per, rest = divmod(n - 1, g.n_instances)
+    if rest:
+        raise ValueError("sentences of different structure: no statement-wise batching")
+    lab = np.arange(n, dtype=np.int32) % per
+    lab[n - 1] = per
+    return lab
+
+
 def _sized(fn, key):
     """Minibatch generator with an optional instance count (None: the configuration's own)."""
     def batch(p, j=0, n=None, **kw):

@@ -191,3 +191,26 @@ def validate_agenda_schedule(g, batch_off, node_ids, n=None):
         assert rank[s] == best, f"batch {b}: a signature with a smaller average depth was available"
         executed[ids] = True
     assert executed.all()
+
+
+def manual_schedule(labels, n=None):
+    """What manual batching (Section 2) must produce from the caller's labels: batches in
+    ascending label order, ids ascending inside a batch.  Returns (batch_off, node_ids)."""
+    labels = np.asarray(labels, np.int64)
+    labels = labels if n is None else labels[:n]
+    node_ids = np.argsort(labels, kind="stable")
+    cuts = np.flatnonzero(np.diff(labels[node_ids])) + 1
+    batch_off = np.concatenate(([0], cuts, [len(labels)]))
+    return batch_off.astype(np.int64), node_ids.astype(np.int64)
+
+
+def validate_manual_labels(g, labels):
+    """A labelling is usable when operands carry smaller labels than their consumers and a
+    label never mixes signatures."""
+    labels = np.asarray(labels, np.int64)
+    assert labels.shape == (g.n,) and labels.min() >= 0
+    cons = np.repeat(np.arange(g.n), np.diff(g.in_off.astype(np.int64)))
+    assert np.all(labels[g.in_idx.astype(np.int64)] < labels[cons])
+    sig_of = {}
+    for v in range(g.n):
+        assert sig_of.setdefault(int(labels[v]), sig_string(g, v)) == sig_string(g, v), f"label {labels[v]} mixes signatures"

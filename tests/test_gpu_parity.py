@@ -21,7 +21,7 @@ def say(msg):
     sys.stdout.flush()
 
 
-def run_gpu(p, g, mode, launch=0, arena=2 << 30, n_nodes=None, fuse=2):
+def run_gpu(p, g, mode, launch=0, arena=2 << 30, n_nodes=None, fuse=2, labels=None):
     from paper_1705_07860_amd import binding as ob
     c = ob.Context(arena_bytes=arena, mode=mode, launch=launch)
     c.set_fusion(int(fuse))
@@ -29,6 +29,8 @@ def run_gpu(p, g, mode, launch=0, arena=2 << 30, n_nodes=None, fuse=2):
     assert pids == list(range(len(p.mats)))
     c.param_grad_zero()
     c.add_bulk(g)
+    if labels is not None:
+        c.set_manual_batches(labels)
     root = g.root if n_nodes is None else n_nodes - 1
     c.forward(root)
     return c, root
@@ -629,6 +631,98 @@ def test_synthetic_equal_length_tagger_small():
         assert np.array_equal(bo, rbo) and np.array_equal(ids, rids) and np.array_equal(bd, rbd)
         check_against_oracle(c, p, g, o, root, what=f"sync tagger mode {mode}")
         c.close()
+
+
+def labels_of(batch_off, node_ids):
+    """Per node, the index of the batch that holds it."""
+    lab = np.empty(len(node_ids), np.int32)
+    lab[np.asarray(node_ids, np.int64)] = np.repeat(np.arange(len(batch_off) - 1), np.diff(batch_off))
+    return lab
+
+
+def check_manual(p, g, o, lab, what, fuse=2, arena=2 << 30, n_nodes=None):
+    from paper_1705_07860_amd import binding as ob
+    from tests.helpers import manual_schedule
+    c, root = run_gpu(p, g, ob.OB_MANUAL, arena=arena, fuse=fuse, labels=lab, n_nodes=n_nodes)
+    bo, ids, bd, _ = c.schedule_read()
+    rbo, rids = manual_schedule(lab, n_nodes)
+    assert np.array_equal(bo, rbo) and np.array_equal(ids, rids)
+    assert np.array_equal(bd, np.arange(len(rbo) - 1))
+    st = c.stats()
+    say(f"manual {what}: batches={st['n_batches']} slots={st['n_slots']} sched {st['ms_schedule']:.3f} ms")
+    if n_nodes is None:
+        check_against_oracle(c, p, g, o, root, what=f"{what}/manual")
+    return c
+
+
+@pytest.mark.parametrize("name", ["rnn", "tagger", "tree"])
+def test_manual_batching_given_the_reference_schedules(name, workload_cache):
+    """Manual batching (Section 2) with the batches of the depth-based and of the agenda-based
+    reference schedule handed in as labels (stretched, so that they are not dense): the library
+    runs exactly those batches, and values and gradients match the oracle."""
+    p, g, o = workload_cache(name)
+    for ref in (S.by_depth, S.by_agenda):
+        rbo, rids, _ = ref(g)
+        lab = labels_of(rbo, rids) * 3 + 1
+        c = check_manual(p, g, o, lab, f"{name} {ref.__name__}")
+        bo, ids, _, _ = c.schedule_read()
+        assert np.array_equal(bo, rbo) and np.array_equal(ids, rids)
+        c.close()
+
+
+@pytest.mark.parametrize("fuse", [0, 1, 2])
+def test_manual_batching_by_statement_on_the_equal_length_tagger(fuse):
+    """Section 4.1's labeler over equal-length sentences, batched the way a program written over
+    a batch of sentences would run it: one batch per statement, every launch-fusion level."""
+    p = wl.sync_tagger_params(vocab=50, emb=24, hidden=16, tags=7)
+    g = wl.sync_tagger_minibatch(p, n_sent=5, length=6)
+    o = Oracle(g, p, "f64")
+    o.forward()
+    o.backward(g.root)
+    check_manual(p, g, o, wl.sync_tagger_manual_labels(g), f"sync tagger fuse {fuse}", fuse=fuse, arena=256 << 20).close()
+
+
+def test_manual_batching_full_width_and_prefix():
+    """The labeler at the layer sizes Section 4.1 states (16 sentences of 40 words), then a
+    prefix of the graph under the same labels, then another labelling on the same context."""
+    from paper_1705_07860_amd import binding as ob
+    from tests.helpers import manual_schedule
+    p = wl.sync_tagger_params()
+    g = wl.sync_tagger_minibatch(p, n_sent=16, length=40)
+    o = Oracle(g, p, "f64")
+    o.forward()
+    o.backward(g.root)
+    lab = wl.sync_tagger_manual_labels(g)
+    c = check_manual(p, g, o, lab, "sync tagger 16 x 40")
+    # a prefix: forget the evaluation, evaluate the first sentences' nodes only
+    c.reset()
+    k = 3 * ((g.n - 1) // 16)
+    c.forward(k - 1)
+    bo, ids, _, _ = c.schedule_read()
+    rbo, rids = manual_schedule(lab, k)
+    assert np.array_equal(bo, rbo) and np.array_equal(ids, rids)
+    assert rel_err(c.value_read(k - 1, int(g.out_dim[k - 1])), o.value(k - 1)) <= TOL
+    # new labels on the same graph: the depth-based batches
+    rbo, rids, _ = S.by_depth(g)
+    c.set_manual_batches(labels_of(rbo, rids))
+    c.param_grad_zero()
+    c.forward(g.root)
+    bo, ids, _, _ = c.schedule_read()
+    assert np.array_equal(bo, rbo) and np.array_equal(ids, rids)
+    check_against_oracle(c, p, g, o, g.root, what="relabelled")
+    c.close()
+
+
+@pytest.mark.parametrize("seed", [930, 931, 932, 933])
+def test_manual_batching_on_random_dags(seed):
+    p, g = wl.random_dag(seed, n_nodes=120, dim=8)
+    o = Oracle(g, p, "f64")
+    o.forward()
+    o.backward(g.root)
+    rbo, rids, _ = S.by_depth(g)
+    check_manual(p, g, o, labels_of(rbo, rids), f"dag {seed}", arena=64 << 20).close()
+    # every node a batch of its own is a valid labelling too
+    check_manual(p, g, o, np.arange(g.n, dtype=np.int32), f"dag {seed} singletons", arena=64 << 20).close()
 
 
 @pytest.mark.parametrize("mode,lookahead", [("depth", 1), ("agenda", 2)])

@@ -182,6 +182,56 @@ def test_state_and_argument_errors_without_a_device():
     c.close()
 
 
+def test_manual_batch_labels_are_checked_on_the_host():
+    """Manual batching (Section 2): the library takes a labelling only if operands come from
+    earlier batches and a batch holds one kind of node."""
+    p = wl.rnn_params()
+    c, _ = _host_ctx(p)
+    x0, x1 = c.add_input(np.zeros(32)), c.add_input(np.ones(32))
+    a0, a1 = c.add_matvec(0, 2, x0), c.add_matvec(0, 2, x1)
+    u1 = c.add_matvec(1, -1, x1)
+    t0, t1 = c.add_unary(wl.OP_TANH, a0), c.add_unary(wl.OP_TANH, a1)
+    assert [x0, x1, a0, a1, u1, t0, t1] == list(range(7))
+    c.set_mode(ob.OB_MANUAL)
+    good = [0, 0, 1, 1, 2, 5, 5]                     # labels need not be dense
+    c.set_manual_batches(good)
+    for bad, why in (([0, 0, 1, 1, 2, 5], "one label short"),
+                     ([0, 0, 1, 1, 2, 5, -1], "negative label"),
+                     ([0, 0, 1, 1, 2, 1, 5], "tanh in the batch of its operand"),
+                     ([3, 0, 1, 1, 2, 5, 5], "operand after its consumer"),
+                     ([0, 0, 1, 1, 1, 5, 5], "two matrices in one batch"),
+                     ([0, 0, 1, 1, 2, 5, 5, 6], "one label too many")):
+        with pytest.raises(ob.ObError) as e:
+            c.set_manual_batches(bad)
+        assert e.value.code == -8, why
+    with pytest.raises(ob.ObError) as e:
+        c.forward(6)
+    assert e.value.code == -6                        # labels are fine, but there is no device arena
+    c.add_unary(wl.OP_SIGMOID, t1)                   # the graph grew: the labels are gone
+    with pytest.raises(ob.ObError, match="no batch labels") as e:
+        c.forward(7)
+    assert e.value.code == -6
+    c.close()
+
+
+def test_statement_labels_of_the_equal_length_tagger_are_a_valid_manual_batching():
+    from tests.helpers import validate_manual_labels, manual_schedule
+    p = wl.sync_tagger_params(vocab=50, emb=8, hidden=4, tags=6)
+    g = wl.sync_tagger_minibatch(p, n_sent=3, length=4)
+    lab = wl.sync_tagger_manual_labels(g)
+    validate_manual_labels(g, lab)
+    bo, ids = manual_schedule(lab)
+    assert np.all(np.diff(bo)[:-1] == 3) and bo[-1] - bo[-2] == 1     # every statement over the 3 sentences, then the sum
+    c, _ = _host_ctx(p)
+    c.add_bulk(g)
+    c.set_manual_batches(lab)
+    c.close()
+    h = wl.tagger_minibatch(wl.tagger_params(), n_sent=3)             # unequal lengths: no such labelling
+    if len(set(h.meta["lengths"])) > 1 and (h.n - 1) % 3 == 0:
+        with pytest.raises(AssertionError):
+            validate_manual_labels(h, wl.sync_tagger_manual_labels(h))
+
+
 def test_binding_fails_loudly_without_gpu():
     import torch
     if torch.cuda.is_available():
