@@ -114,9 +114,10 @@ def main():
                     help="instances per minibatch (default: the configuration's own count; other values are sweep "
                          "points, not the headline workload)")
     ap.add_argument("--launch", default="stream", choices=["stream", "graph"])
-    ap.add_argument("--mode", default="depth", choices=["depth", "agenda"],
+    ap.add_argument("--mode", default="depth", choices=["depth", "agenda", "manual"],
                     help="batching strategy of Section 3.2: depth-based (default, the configuration the stored "
-                         "profiles cover) or agenda-based")
+                         "profiles cover) or agenda-based; manual = Section 2's batching by hand, one batch per "
+                         "statement of a program written over a batch of sentences (--workload sync_tagger only)")
     ap.add_argument("--lookahead", type=int, default=0,
                     help="minibatches scheduled ahead of the one that executes, each on a schedule stream of its own "
                          "(default: 1 for depth-based batching, 2 for agenda-based batching, whose scheduling takes longer "
@@ -140,6 +141,10 @@ def main():
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU; --gpus must be 1 (the path has no multi-GPU part)",
               file=sys.stderr)
+        sys.exit(2)
+
+    if args.mode == "manual" and args.workload != "sync_tagger":
+        print("bench.py: --mode manual needs sentences of equal structure (--workload sync_tagger)", file=sys.stderr)
         sys.exit(2)
 
     import torch
@@ -171,7 +176,7 @@ def main():
     for j, g in enumerate(graphs):
         if j == 0:
             c = ob.Context(arena_bytes=arena_bytes, stream=stream, launch=launch, sched_stream=sched_streams[0],
-                           mode=ob.OB_BYAGENDA if args.mode == "agenda" else ob.OB_BYDEPTH)
+                           mode={"agenda": ob.OB_BYAGENDA, "manual": ob.OB_MANUAL}.get(args.mode, ob.OB_BYDEPTH))
             c.set_fusion(0 if args.no_fusion else (2 if args.placement == "late" else 1))
             c.params_create(params)
             c.param_grad_zero()
@@ -179,6 +184,8 @@ def main():
             c = ctxs[0].fork(arena_bytes=arena_bytes, stream=stream, sched_stream=sched_streams[j % len(sched_streams)])
         t0 = time.perf_counter()
         c.add_bulk(g)
+        if args.mode == "manual":
+            c.set_manual_batches(wl.sync_tagger_manual_labels(g))
         c.upload()
         c.sync()
         torch.cuda.synchronize()
@@ -368,7 +375,7 @@ def main():
                    "instances_per_step": graphs[0].n_instances,
                    "sweep_point": (None if args.instances is None else
                                    f"{args.instances} instances per minibatch instead of the configuration's own count"),
-                   "mode": "by" + args.mode, "launch": args.launch,
+                   "mode": "manual" if args.mode == "manual" else "by" + args.mode, "launch": args.launch,
                    "fusion": not args.no_fusion, "placement": args.placement, "update": bool(args.update),
                    "pipeline": (f"scheduling of steps i+1..i+{lookahead} overlaps execution of step i ({lookahead} schedule "
                                 f"stream{'s' if lookahead > 1 else ''})") if pipeline
