@@ -165,11 +165,18 @@ int ob_upload(ob_ctx *ctx);
 /* Evaluates every node with id <= node (Section 3.1: evaluation happens when a value is
  * requested).  Schedules on the GPU (Section 3.2), then runs the batches in order
  * (Section 3.3).  Asynchronous except for one small read of the schedule header.
- * A node beyond the evaluated prefix (a later ob_forward with a larger id, or nodes added after
- * an evaluation) makes the library drop the evaluation and schedule and evaluate the whole longer
- * prefix again: results are the same as Section 3.1's evaluation of only the new nodes, the work
- * is not saved.  Adding a node to an evaluated graph drops the evaluation at once: values and
- * gradients cannot be read again before the next ob_forward. */
+ * When nodes [0, k) already have values (an earlier ob_forward of a smaller id, before or after
+ * more nodes were added), only the nodes [k, node] are evaluated, as a stage of their own
+ * (Section 3.1): they form a graph whose leaves are the earlier nodes they read (values copied on
+ * the GPU), which is scheduled in the context's mode and executed in the arena behind the earlier
+ * evaluations; depths of a stage count from its own leaves.  Earlier values stay readable
+ * throughout (ob_value_read).  While values come from more than one stage: ob_schedule_read and
+ * ob_stats_read describe the last stage; ob_all_read and ob_debug_read fail with OB_E_STATE;
+ * gradients cannot be read; ob_backward first schedules and evaluates everything evaluated so
+ * far once more as one graph (the backward pass needs every consumer of a node in one schedule),
+ * so a graph grown in T steps costs T small forwards and one full one instead of T full ones.
+ * If the arena has no room for another stage, or in OB_MANUAL, the whole prefix is evaluated
+ * again instead.  A schedule that was never executed is dropped when nodes are added. */
 int ob_forward(ob_ctx *ctx, int node);
 /* Only the scheduling half of ob_forward (upload, Section 3.2's batching on the GPU, layout and
  * launch plan); a later ob_forward of the same node then only executes.  Blocks the host for one
@@ -209,7 +216,9 @@ typedef struct ob_stats {
     int32_t n_launch_fwd, n_launch_bwd, n_launch_sched, n_slots;
     uint64_t value_floats, grad_floats, arena_used_bytes, upload_bytes;
     float ms_upload, ms_schedule, ms_forward, ms_backward; /* hipEvent times on the stream */
-    float ms_param_grads, ms_graph_build, reserved1, reserved2;
+    float ms_param_grads, ms_graph_build;
+    int32_t n_stages;  /* evaluations the current values come from (1: one schedule covers every evaluated node) */
+    int32_t n_proxies; /* earlier nodes the last stage read (0 when n_stages is 1) */
 } ob_stats;
 int ob_stats_read(ob_ctx *ctx, ob_stats *out);
 

@@ -39,7 +39,8 @@ class ObStats(ctypes.Structure):
         "n_param_uses", "n_launch_fwd", "n_launch_bwd", "n_launch_sched", "n_slots")] + \
         [(n, c_uint64) for n in ("value_floats", "grad_floats", "arena_used_bytes", "upload_bytes")] + \
         [(n, c_float) for n in ("ms_upload", "ms_schedule", "ms_forward", "ms_backward", "ms_param_grads",
-                                "ms_graph_build", "reserved1", "reserved2")]
+                                "ms_graph_build")] + \
+        [(n, c_int32) for n in ("n_stages", "n_proxies")]
 
     def as_dict(self):
         return {n: getattr(self, n) for n, _ in self._fields_ if not n.startswith("reserved")}

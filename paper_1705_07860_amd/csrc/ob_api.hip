@@ -3,6 +3,7 @@
 #include "../../include/ob.h"
 #include "ob_ctx.h"
 
+#include <algorithm>
 #include <chrono>
 #include <cstdarg>
 #include <cstdio>
@@ -72,9 +73,12 @@ int ob_ctx_fork(ob_ctx *parent, void *arena_dev, size_t arena_bytes, void *hip_s
     return OB_OK;
 }
 
+static void drop_stages(ob_ctx *ctx);
+
 int ob_ctx_destroy(ob_ctx *ctx)
 {
     CHECK_CTX(ctx);
+    drop_stages(ctx);
     if (ctx->uploaded) { (void)hipStreamSynchronize(ctx->sched_stream); (void)hipStreamSynchronize(ctx->stream); }
     if (ctx->gexec_fwd) (void)hipGraphExecDestroy(ctx->gexec_fwd);
     if (ctx->gexec_bwd) (void)hipGraphExecDestroy(ctx->gexec_bwd);
@@ -88,6 +92,10 @@ int ob_ctx_destroy(ob_ctx *ctx)
 }
 
 static int forget_evaluation(ob_ctx *ctx);
+static u32 evaluated_upto(const ob_ctx *ctx);
+static int stage_forward(ob_ctx *ctx, u32 n0, u32 n1);
+static int stage_schedule_read(ob_ctx *ctx, int *n_batches, int *batch_depth, uint64_t *batch_sig, int *batch_off,
+                               int *node_ids, size_t cap_batches, size_t cap_nodes);
 
 int ob_ctx_set_mode(ob_ctx *ctx, int mode)
 {
@@ -262,6 +270,8 @@ int ob_graph_new(ob_ctx *ctx)
     ctx->param.clear(); ctx->bias.clear(); ctx->aux0.clear(); ctx->aux1.clear(); ctx->payload.clear();
     ctx->items_upto.clear();
     ctx->manual.clear();
+    drop_stages(ctx);
+    ctx->image_stale = false;
     ctx->sum_out_dim = 0;
     ctx->max_arity = 0;
     ctx->sum_mv_d32 = ctx->sum_mv_k32 = 0;
@@ -356,10 +366,11 @@ static int validate_node(ob_ctx *ctx, u32 n_before, const std::vector<u32> &dims
 
 static int append_node(ob_ctx *ctx, int op, const u32 *ins, u32 arity, int param, int bias, int a0, int a1, u32 dim)
 {
-    // extending a graph that was already evaluated: the evaluation is dropped, the next ob_forward
-    // schedules and evaluates the whole graph again (Section 3.1's lazy evaluation, without the
-    // saving of evaluating only what is new)
-    if (ctx->n_sched)
+    // extending a graph that was already evaluated keeps the evaluation: the next ob_forward
+    // evaluates only the new nodes (Section 3.1's lazy evaluation).  A schedule that was never
+    // executed holds nothing worth keeping.
+    const bool keep = ctx->n_sched && ctx->forward_done && !ctx->sched_pending;
+    if (ctx->n_sched && !keep)
         if (int rc = forget_evaluation(ctx)) return rc;
     if (ctx->op.size() >= 0x7ffffff0u) return ctx_fail(ctx, OB_E_RANGE, "too many nodes");
     ctx->manual.clear();   // labels cover the graph they were given for
@@ -381,7 +392,7 @@ static int append_node(ob_ctx *ctx, int op, const u32 *ins, u32 arity, int param
         if (!ctx->params_used_w[param]) { ctx->params_used_w[param] = 1; ctx->params_dirty = true; }
         if (bias >= 0 && !ctx->params_used_b[bias]) { ctx->params_used_b[bias] = 1; ctx->params_dirty = true; }
     }
-    ctx->uploaded = false;
+    if (keep) ctx->image_stale = true; else ctx->uploaded = false;
     return (int)ctx->op.size() - 1;
 }
 
@@ -483,8 +494,6 @@ int ob_add_bulk(ob_ctx *ctx, int n, const uint8_t *op, const uint32_t *out_dim, 
     CHECK_CTX(ctx);
     if (n <= 0) return ctx_fail(ctx, OB_E_ARG, "n = %d", n);
     if (!op || !out_dim || !in_off || !param || !bias || !aux0 || !aux1) return ctx_fail(ctx, OB_E_ARG, "null array");
-    if (ctx->n_sched)
-        if (int rc = forget_evaluation(ctx)) return rc;
     sync_used_flags(ctx);
     const u32 n0 = (u32)ctx->op.size();
     if ((u64)n0 + (u64)n >= 0x7ffffff0ull) return ctx_fail(ctx, OB_E_RANGE, "too many nodes");
@@ -694,8 +703,8 @@ static int schedule_begin(ob_ctx *ctx, int node)
 {
     if (node < 0 || node >= (int)ctx->op.size()) return ctx_fail(ctx, OB_E_BADID, "unknown node id %d", node);
     if (ctx->n_sched) {
-        if ((u32)node < ctx->n_sched) return OB_OK;   // already scheduled (or being scheduled)
-        // a node beyond the evaluated prefix: schedule and evaluate the longer prefix from the start
+        if ((u32)node < ctx->n_sched || (u32)node < evaluated_upto(ctx)) return OB_OK;   // already scheduled (or being scheduled)
+        // a node beyond the scheduled prefix: schedule the longer prefix from the start
         if (int rc = forget_evaluation(ctx)) return rc;
     }
     if (ctx->mode == OB_MANUAL && ctx->manual.size() != ctx->op.size())
@@ -740,6 +749,16 @@ int ob_forward(ob_ctx *ctx, int node)
 {
     CHECK_CTX(ctx);
     if (node < 0 || node >= (int)ctx->op.size()) return ctx_fail(ctx, OB_E_BADID, "unknown node id %d", node);
+    if (ctx->forward_done && !ctx->sched_pending) {
+        const u32 done = evaluated_upto(ctx);
+        if ((u32)node < done) return OB_OK;           // already evaluated
+        if (!ctx->is_stage && ctx->mode != OB_MANUAL) {
+            // Section 3.1: only the nodes that have no value yet are evaluated
+            const int rc = stage_forward(ctx, done, (u32)node + 1);
+            if (rc != OB_E_OOM) return rc;
+            // no room to stack another evaluation behind the earlier ones: evaluate everything again instead
+        }
+    }
     if (int rc = ob_schedule(ctx, node)) return rc;
     if (ctx->forward_done) return OB_OK;              // already evaluated
     if (ctx->sched_stream != ctx->stream) HIP_TRY(ctx, hipStreamWaitEvent(ctx->stream, ctx->ev[9], 0));
@@ -755,6 +774,15 @@ int ob_backward(ob_ctx *ctx, int node)
 {
     CHECK_CTX(ctx);
     if (!ctx->forward_done) return ctx_fail(ctx, OB_E_STATE, "ob_backward before ob_forward");
+    if (!ctx->stages.empty()) {
+        // The graph was evaluated in stages.  The backward pass needs one schedule over all of it
+        // (every node's consumers in one pull list), so everything evaluated so far is scheduled
+        // and evaluated once more, together.
+        const u32 done = evaluated_upto(ctx);
+        if (node < 0 || (u32)node >= done) return ctx_fail(ctx, OB_E_BADID, "node %d was not evaluated", node);
+        if (int rc = forget_evaluation(ctx)) return rc;
+        if (int rc = ob_forward(ctx, (int)done - 1)) return rc;
+    }
     if (node < 0 || (u32)node >= ctx->n_sched) return ctx_fail(ctx, OB_E_BADID, "node %d was not evaluated", node);
     if (ctx->out_dim[node] != 1) return ctx_fail(ctx, OB_E_NOTSCALAR, "node %d has %u elements", node, ctx->out_dim[node]);
     ctx->T.root = (u32)node;
@@ -777,14 +805,188 @@ static int wait_own_work(ob_ctx *ctx)
     return 0;
 }
 
+static void drop_stages(ob_ctx *ctx)
+{
+    for (Stage &st : ctx->stages)
+        if (st.c) (void)ob_ctx_destroy(st.c);   // waits for the stage's work first
+    ctx->stages.clear();
+}
+
 static int forget_evaluation(ob_ctx *ctx)
 {
     if (int rc = wait_own_work(ctx)) return rc;
+    drop_stages(ctx);
     ctx->sched_pending = false;
     ctx->n_sched = 0;
     ctx->forward_done = ctx->backward_done = false;
     if (ctx->uploaded) ctx->top = ctx->graph_top;
+    if (ctx->image_stale) { ctx->uploaded = false; ctx->image_stale = false; }
     return 0;
+}
+
+// nodes [0, result) have values
+static u32 evaluated_upto(const ob_ctx *ctx)
+{
+    if (!ctx->forward_done) return 0;
+    return ctx->stages.empty() ? ctx->n_sched : ctx->stages.back().n1;
+}
+
+// Evaluates the nodes [n0, n1) of a graph whose nodes [0, n0) already have values (Section 3.1:
+// a value is computed when it is asked for, and what is computed stays).  The new nodes become a
+// graph of their own: every earlier node they read is a leaf of that graph, holding a copy of the
+// earlier value, and the new nodes follow in id order.  The graph gets a context of its own over
+// the free end of the arena, is scheduled like any other graph (so "depth" counts from the
+// leaves of this stage) and executed; earlier values stay where they are.
+static int stage_forward(ob_ctx *ctx, u32 n0, u32 n1)
+{
+    ctx->stages.emplace_back();
+    Stage &st = ctx->stages.back();
+    st.n0 = n0; st.n1 = n1;
+    auto fail = [&](int rc) {   // the caller has put the message into ctx->err
+        if (st.c) (void)ob_ctx_destroy(st.c);
+        ctx->stages.pop_back();
+        return rc;
+    };
+    auto hip_fail = [&](hipError_t e, const char *what) {
+        return fail(ctx_fail(ctx, OB_E_HIP, "%s failed: %s", what, hipGetErrorString(e)));
+    };
+    // earlier nodes the new ones read
+    for (u32 e = ctx->in_off[n0]; e < ctx->in_off[n1]; ++e)
+        if (ctx->in_idx[e] < n0) st.proxy.push_back(ctx->in_idx[e]);
+    std::sort(st.proxy.begin(), st.proxy.end());
+    st.proxy.erase(std::unique(st.proxy.begin(), st.proxy.end()), st.proxy.end());
+    const u32 P = (u32)st.proxy.size(), nl = P + (n1 - n0);
+    if ((u64)P + (n1 - n0) >= 0x7ffffff0ull) return fail(ctx_fail(ctx, OB_E_RANGE, "too many nodes"));
+
+    // the stage's graph
+    std::vector<u8> op(nl, (u8)OB_OP_INPUT);
+    std::vector<u32> od(nl), ioff((size_t)nl + 1, 0), iidx;
+    std::vector<i32> par(nl, -1), bia(nl, -1), a0(nl, 0), a1(nl, 0);
+    std::vector<float> pay;
+    u64 pfl = 0;
+    for (u32 i = 0; i < P; ++i) {
+        od[i] = ctx->out_dim[st.proxy[i]];
+        a0[i] = (i32)pfl;
+        pfl += od[i];
+    }
+    if (pfl >= 0x7fffffffull) return fail(ctx_fail(ctx, OB_E_RANGE, "the new nodes read too many earlier elements"));
+    pay.assign((size_t)pfl, 0.f);
+    iidx.reserve(ctx->in_off[n1] - ctx->in_off[n0]);
+    for (u32 v = n0; v < n1; ++v) {
+        const u32 l = P + (v - n0);
+        op[l] = ctx->op[v]; od[l] = ctx->out_dim[v];
+        par[l] = ctx->param[v]; bia[l] = ctx->bias[v]; a0[l] = ctx->aux0[v]; a1[l] = ctx->aux1[v];
+        if (ctx->op[v] == OB_OP_INPUT) {
+            a0[l] = (i32)pay.size();
+            pay.insert(pay.end(), ctx->payload.begin() + ctx->aux0[v], ctx->payload.begin() + ctx->aux0[v] + ctx->out_dim[v]);
+        }
+        for (u32 e = ctx->in_off[v]; e < ctx->in_off[v + 1]; ++e) {
+            const u32 u = ctx->in_idx[e];
+            iidx.push_back(u < n0 ? (u32)(std::lower_bound(st.proxy.begin(), st.proxy.end(), u) - st.proxy.begin())
+                                  : P + (u - n0));
+        }
+        ioff[l + 1] = (u32)iidx.size();
+    }
+
+    // its context: the arena behind everything the earlier evaluations hold
+    size_t used = ctx->top;
+    if (ctx->stages.size() > 1) {
+        const Stage &prev = ctx->stages[ctx->stages.size() - 2];
+        used = (size_t)(prev.c->arena - ctx->arena) + prev.c->top;
+    }
+    used = (used + 255) & ~(size_t)255;
+    if (used + (1u << 16) > ctx->arena_bytes) return fail(ctx_fail(ctx, OB_E_OOM, "arena too small for another evaluation stage"));
+    if (int rc = ob_ctx_fork(ctx, ctx->arena + used, ctx->arena_bytes - used, ctx->stream, &st.c)) return fail(rc);
+    ob_ctx *c = st.c;
+    c->sched_stream = ctx->sched_stream;
+    c->is_stage = true;
+    u32 *lists_dev = arena_array<u32>(c, (size_t)3 * P + 1);
+    if (!lists_dev) return fail(ctx_fail(ctx, OB_E_OOM, "arena too small for another evaluation stage"));
+    c->persist_top = c->top;
+    int rc = ob_add_bulk(c, (int)nl, op.data(), od.data(), ioff.data(), iidx.data(), par.data(), bia.data(), a0.data(),
+                         a1.data(), pay.data(), pay.size());
+    if (rc < 0) { ctx->err = c->err; return fail(rc); }
+    if ((rc = ob_upload(c)) != 0) { ctx->err = c->err; return fail(rc); }
+
+    // copies of the earlier values, owner by owner (proxies ascend, and so do the owners' id ranges)
+    st.lists.resize((size_t)3 * P + 1);
+    u32 *src = st.lists.data(), *dst = src + P, *dim = dst + P;
+    for (u32 i = 0; i < P; ++i) { dst[i] = (u32)a0[i]; dim[i] = od[i]; }
+    const size_t n_own = ctx->stages.size() - 1;   // earlier stages (the last entry is the new one)
+    {   // source ids first: the whole list goes to the device in one copy
+        u32 i = 0;
+        for (size_t k = 0; k <= n_own && i < P; ++k) {   // k = 0: the first evaluation, k >= 1: stage k - 1
+            const Stage *own = k ? &ctx->stages[k - 1] : nullptr;
+            const u32 hi = own ? own->n1 : ctx->n_sched;
+            for (; i < P && st.proxy[i] < hi; ++i)
+                src[i] = own ? (u32)own->proxy.size() + (st.proxy[i] - own->n0) : st.proxy[i];
+        }
+    }
+    if (P) {
+        hipError_t e = hipMemcpyAsync(lists_dev, st.lists.data(), (size_t)3 * P * 4, hipMemcpyHostToDevice, ctx->stream);
+        if (e != hipSuccess) return hip_fail(e, "copying the stage lists");
+    }
+    if (ctx->sched_stream != ctx->stream) {   // the stage's image (queued on the schedule stream) must be in place
+        hipError_t e = hipStreamWaitEvent(ctx->stream, c->ev[1], 0);
+        if (e != hipSuccess) return hip_fail(e, "hipStreamWaitEvent");
+    }
+    float *payload_dev = const_cast<float *>(c->T.payload);
+    u32 i = 0;
+    for (size_t k = 0; k <= n_own && i < P; ++k) {
+        const Stage *own = k ? &ctx->stages[k - 1] : nullptr;
+        const u32 hi = own ? own->n1 : ctx->n_sched;
+        const u32 i0 = i;
+        while (i < P && st.proxy[i] < hi) ++i;
+        if (i == i0) continue;
+        const Tables &OT = own ? own->c->T : ctx->T;
+        hipError_t e = exec_stage_fill(OT.V, OT.val_off, lists_dev + i0, lists_dev + P + i0, lists_dev + 2 * (size_t)P + i0,
+                                       i - i0, payload_dev, ctx->stream);
+        if (e != hipSuccess) return hip_fail(e, "copying earlier values");
+    }
+    if ((rc = ob_forward(c, (int)nl - 1)) != 0) { ctx->err = c->err; return fail(rc); }
+    ctx->backward_done = false;   // gradients of the shorter graph are not gradients of this one
+    return OB_OK;
+}
+
+// The last stage's schedule in the caller's node ids: the leaves that stand for earlier nodes are
+// left out, and so are batches that held nothing else.
+static int stage_schedule_read(ob_ctx *ctx, int *n_batches, int *batch_depth, uint64_t *batch_sig, int *batch_off,
+                               int *node_ids, size_t cap_batches, size_t cap_nodes)
+{
+    const Stage &st = ctx->stages.back();
+    const u32 P = (u32)st.proxy.size();
+    int nb = 0;
+    if (int rc = ob_schedule_read(st.c, &nb, nullptr, nullptr, nullptr, nullptr, 0, 0)) { ctx->err = st.c->err; return rc; }
+    const size_t nl = st.c->op.size();
+    std::vector<int> depth((size_t)nb + 1), off((size_t)nb + 1), ids(nl + 1);
+    std::vector<uint64_t> sig((size_t)nb + 1);
+    if (int rc = ob_schedule_read(st.c, &nb, depth.data(), sig.data(), off.data(), ids.data(), (size_t)nb, nl)) {
+        ctx->err = st.c->err;
+        return rc;
+    }
+    std::vector<int> k_depth, k_off(1, 0), k_ids;
+    std::vector<uint64_t> k_sig;
+    for (int b = 0; b < nb; ++b) {
+        const size_t before = k_ids.size();
+        for (int q = off[b]; q < off[b + 1]; ++q)
+            if ((u32)ids[q] >= P) k_ids.push_back((int)(st.n0 + ((u32)ids[q] - P)));
+        if (k_ids.size() == before) continue;
+        k_depth.push_back(depth[b]);
+        k_sig.push_back(sig[b]);
+        k_off.push_back((int)k_ids.size());
+    }
+    if (n_batches) *n_batches = (int)k_depth.size();
+    if (!batch_depth && !batch_sig && !batch_off && !node_ids) return OB_OK;
+    if (cap_batches < k_depth.size() || cap_nodes < k_ids.size())
+        return ctx_fail(ctx, OB_E_RANGE, "schedule has %zu batches, %zu nodes", k_depth.size(), k_ids.size());
+    for (size_t b = 0; b < k_depth.size(); ++b) {
+        if (batch_depth) batch_depth[b] = k_depth[b];
+        if (batch_sig) batch_sig[b] = k_sig[b];
+        if (batch_off) batch_off[b] = k_off[b];
+    }
+    if (batch_off) batch_off[k_depth.size()] = k_off.back();
+    if (node_ids) std::copy(k_ids.begin(), k_ids.end(), node_ids);
+    return OB_OK;
 }
 
 int ob_reset(ob_ctx *ctx)
@@ -806,7 +1008,15 @@ static int node_read(ob_ctx *ctx, int node, float *out, size_t cap, bool grad)
 {
     if (!out) return ctx_fail(ctx, OB_E_ARG, "null output");
     if (!ctx->forward_done || (grad && !ctx->backward_done)) return ctx_fail(ctx, OB_E_STATE, "nothing to read yet");
-    if (node < 0 || (u32)node >= ctx->n_sched) return ctx_fail(ctx, OB_E_BADID, "node %d was not evaluated", node);
+    if (node < 0 || (u32)node >= evaluated_upto(ctx)) return ctx_fail(ctx, OB_E_BADID, "node %d was not evaluated", node);
+    if ((u32)node >= ctx->n_sched) {   // the value lives in a later evaluation stage
+        for (Stage &st : ctx->stages) {
+            if ((u32)node >= st.n1) continue;
+            const int rc = node_read(st.c, (int)(st.proxy.size() + ((u32)node - st.n0)), out, cap, false);
+            if (rc) ctx->err = st.c->err;
+            return rc;
+        }
+    }
     const u32 d = ctx->out_dim[node];
     if (cap < d) return ctx_fail(ctx, OB_E_RANGE, "buffer holds %zu of %u elements", cap, d);
     u32 off = 0;
@@ -834,6 +1044,9 @@ int ob_all_read(ob_ctx *ctx, int which, float *host_out, size_t cap)
     CHECK_CTX(ctx);
     if (!host_out) return ctx_fail(ctx, OB_E_ARG, "null output");
     if (!ctx->forward_done || (which && !ctx->backward_done)) return ctx_fail(ctx, OB_E_STATE, "nothing to read yet");
+    if (!ctx->stages.empty())
+        return ctx_fail(ctx, OB_E_STATE, "the graph was evaluated in %zu stages: read node by node, or after ob_backward",
+                        ctx->stages.size() + 1);
     const u32 n = ctx->n_sched;
     std::vector<u32> off((size_t)n + 1);
     u64 tot = 0;
@@ -861,6 +1074,8 @@ int ob_schedule_read(ob_ctx *ctx, int *n_batches, int *batch_depth, uint64_t *ba
 {
     CHECK_CTX(ctx);
     if (!ctx->forward_done) return ctx_fail(ctx, OB_E_STATE, "no schedule yet");
+    if (!ctx->stages.empty())
+        return stage_schedule_read(ctx, n_batches, batch_depth, batch_sig, batch_off, node_ids, cap_batches, cap_nodes);
     const u32 nb = ctx->hdr.n_batches, n = ctx->n_sched;
     if (n_batches) *n_batches = (int)nb;
     if (!batch_depth && !batch_sig && !batch_off && !node_ids) return OB_OK;
@@ -893,6 +1108,16 @@ int ob_stats_read(ob_ctx *ctx, ob_stats *out)
     out->n_nodes = (int32_t)ctx->op.size();
     out->n_edges = (int32_t)ctx->in_idx.size();
     if (!ctx->forward_done) return OB_OK;
+    if (!ctx->stages.empty()) {   // counters and times of the last stage's evaluation
+        const Stage &st = ctx->stages.back();
+        const int rc = ob_stats_read(st.c, out);
+        if (rc) { ctx->err = st.c->err; return rc; }
+        out->n_nodes = (int32_t)(st.n1 - st.n0);
+        out->n_stages = (int32_t)ctx->stages.size() + 1;
+        out->n_proxies = (int32_t)st.proxy.size();
+        return OB_OK;
+    }
+    out->n_stages = 1;
     HIP_TRY(ctx, hipStreamSynchronize(ctx->sched_stream));
     HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
     out->n_nodes = (int32_t)ctx->n_sched;
@@ -927,6 +1152,7 @@ int ob_debug_read(ob_ctx *ctx, int which, uint32_t *host_out, size_t cap_words, 
 {
     CHECK_CTX(ctx);
     if (!ctx->forward_done) return ctx_fail(ctx, OB_E_STATE, "no schedule yet");
+    if (!ctx->stages.empty()) return ctx_fail(ctx, OB_E_STATE, "the graph was evaluated in stages: no single set of tables");
     const Tables &T = ctx->T;
     const void *src = nullptr;
     size_t words = 0;

@@ -12,6 +12,18 @@ struct HostParam {
     float *grad;   // device, inside the arena
 };
 
+struct ob_ctx;
+
+// One later evaluation of a graph that grew after it was evaluated (Section 3.1): the nodes
+// [n0, n1) as a graph of their own in a context of their own, whose first proxy.size() nodes are
+// leaves that hold copies of the earlier values the new nodes read.
+struct Stage {
+    ob_ctx *c = nullptr;
+    u32 n0 = 0, n1 = 0;
+    std::vector<u32> proxy;     // ascending ids of the earlier nodes; the local id of proxy[i] is i
+    std::vector<u32> lists;     // host copy of the fill lists (kept while the copy to the device may be in flight)
+};
+
 struct ob_ctx {
     // caller-owned resources
     char *arena = nullptr;
@@ -56,6 +68,9 @@ struct ob_ctx {
     void *pinned = nullptr;
     size_t pinned_bytes = 0;
     bool uploaded = false;
+    bool image_stale = false;          // nodes were added behind a live evaluation: the device image lacks them
+    std::vector<Stage> stages;         // evaluations after the first, in order (empty: one schedule covers all)
+    bool is_stage = false;             // this context is a Stage's own
     u32 n_sched = 0;                   // nodes covered by the last schedule (0 = none)
     bool sched_pending = false;        // scheduling is queued on the GPU, its results are not read yet
     u32 hdr_window = 0, n_items_sched = 0;

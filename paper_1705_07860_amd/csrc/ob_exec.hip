@@ -1100,6 +1100,19 @@ __global__ void k_gather_all(Tables T, const float *src, float *dst, const u32 *
     for (u32 c = threadIdx.x; c < d; c += blockDim.x) o[c] = s[c];
 }
 
+// Values of already evaluated nodes, copied into the payload block of a later evaluation stage
+// whose graph holds them as leaves: entry i copies dim[i] elements from the row of node src[i] in
+// the earlier evaluation's value arena to payload + dst[i].
+__global__ void k_stage_fill(const float *V, const u32 *val_off, const u32 *src, const u32 *dst, const u32 *dim,
+                             float *payload)
+{
+    const u32 i = blockIdx.x;
+    const float *s = V + val_off[src[i]];
+    float *o = payload + dst[i];
+    const u32 d = dim[i];
+    for (u32 c = threadIdx.x; c < d; c += blockDim.x) o[c] = s[c];
+}
+
 __global__ __launch_bounds__(WG) void k_test_gemm(const float *A, const float *Bm, float *C, int M, int N, int K)
 {
     __shared__ float lds[LDS_FLOATS];
@@ -1380,6 +1393,14 @@ hipError_t exec_gather_all(const Tables &T, int which, float *dst, const u32 *ds
 {
     if (T.n == 0) return hipSuccess;
     hipLaunchKernelGGL(k_gather_all, dim3(T.n), dim3(64), 0, s, T, which ? T.G : T.V, dst, dst_off);
+    return hipGetLastError();
+}
+
+hipError_t exec_stage_fill(const float *V, const u32 *val_off, const u32 *src, const u32 *dst, const u32 *dim, u32 count,
+                           float *payload, hipStream_t s)
+{
+    if (count == 0) return hipSuccess;
+    hipLaunchKernelGGL(k_stage_fill, dim3(count), dim3(64), 0, s, V, val_off, src, dst, dim, payload);
     return hipGetLastError();
 }
 

@@ -233,6 +233,8 @@ int sched_finish(ob_ctx *ctx);
 int exec_forward(ob_ctx *ctx);
 int exec_backward(ob_ctx *ctx);
 hipError_t exec_gather_all(const Tables &T, int which, float *dst, const u32 *dst_off, hipStream_t s);
+hipError_t exec_stage_fill(const float *V, const u32 *val_off, const u32 *src, const u32 *dst, const u32 *dim, u32 count,
+                           float *payload, hipStream_t s);
 hipError_t exec_launch_probe(float *scratch, int n, int touch, float *us_per_launch, hipStream_t s);
 hipError_t exec_sgd(const ParamDesc *params_dev, u32 n_params, size_t max_count, float lr, int zero_grad, hipStream_t s);
 hipError_t exec_barrier_probe(u32 *state, int n_wg, int iters, u32 *out3, hipStream_t s);

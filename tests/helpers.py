@@ -214,3 +214,43 @@ def validate_manual_labels(g, labels):
     sig_of = {}
     for v in range(g.n):
         assert sig_of.setdefault(int(labels[v]), sig_string(g, v)) == sig_string(g, v), f"label {labels[v]} mixes signatures"
+
+
+def stage_graph(g, n0, n1):
+    """Nodes [n0, n1) of g as a graph of their own (how a forward after earlier forwards sees
+    them, Section 3.1): the earlier nodes they read come first, in id order, as leaves of the
+    same dimension; the new nodes follow in id order.  Returns (graph, ids of the earlier nodes).
+    Only the structure is filled in (no input data)."""
+    from paper_1705_07860_amd.workloads import Graph
+    in_off = g.in_off.astype(np.int64)
+    e0, e1 = int(in_off[n0]), int(in_off[n1])
+    ins = g.in_idx[e0:e1].astype(np.int64)
+    proxy = np.unique(ins[ins < n0])
+    P = len(proxy)
+    local = np.where(ins < n0, np.searchsorted(proxy, ins), P + ins - n0)
+    z = np.zeros(P, np.int32)
+    return Graph(op=np.concatenate((np.zeros(P, np.uint8), g.op[n0:n1])),
+                 out_dim=np.concatenate((g.out_dim[proxy], g.out_dim[n0:n1])).astype(np.uint32),
+                 in_off=np.concatenate((np.zeros(P, np.int64), in_off[n0:n1 + 1] - e0)).astype(np.uint32),
+                 in_idx=local.astype(np.uint32),
+                 param=np.concatenate((z - 1, g.param[n0:n1])).astype(np.int32),
+                 bias=np.concatenate((z - 1, g.bias[n0:n1])).astype(np.int32),
+                 aux0=np.concatenate((z, g.aux0[n0:n1])).astype(np.int32),
+                 aux1=np.concatenate((z, g.aux1[n0:n1])).astype(np.int32),
+                 payload=np.zeros(1, np.float32), root=P + n1 - n0 - 1), proxy
+
+
+def stage_schedule(schedule_fn, g, n0, n1):
+    """The schedule of the stage graph in the ids of g, the stand-in leaves left out and batches
+    that held nothing else dropped.  Returns (batch_off, node_ids, batch_step)."""
+    sg, proxy = stage_graph(g, n0, n1)
+    P = len(proxy)
+    bo, ids, step = schedule_fn(sg)
+    k_off, k_ids, k_step = [0], [], []
+    for b in range(len(bo) - 1):
+        mem = [int(v) - P + n0 for v in ids[bo[b]:bo[b + 1]] if v >= P]
+        if mem:
+            k_ids += mem
+            k_off.append(len(k_ids))
+            k_step.append(int(step[b]))
+    return np.asarray(k_off, np.int64), np.asarray(k_ids, np.int64), np.asarray(k_step, np.int64)

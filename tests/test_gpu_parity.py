@@ -39,7 +39,10 @@ def run_gpu(p, g, mode, launch=0, arena=2 << 30, n_nodes=None, fuse=2, labels=No
 def check_against_oracle(c, p, g, o, root, tol=TOL, what=""):
     n = o.n
     total = int(o.v_off[-1])
-    vals = c.all_read(0, total)
+    if c.stats()["n_stages"] > 1:   # evaluated in stages: values are read node by node
+        vals = np.concatenate([c.value_read(v, int(g.out_dim[v])) for v in range(n)])
+    else:
+        vals = c.all_read(0, total)
     ev = segment_rel_err(vals, o.val[:total], o.v_off)
     say(f"  {what} values: worst tensor rel err {ev:.2e}")
     assert ev <= tol
@@ -272,13 +275,22 @@ def test_edge_cases_single_node_and_prefix_forward():
     assert c.value_read(x, 1)[0] == 1.0
     c.backward(x)
     assert c.grad_read(x, 1)[0] == 1.0
-    # extending an evaluated graph drops the evaluation; the next forward evaluates all of it again
+    # extending an evaluated graph keeps what is evaluated; the next forward evaluates the new node only
     y = c.add_input(np.full(1, 2.5, dtype=np.float32))
+    assert c.value_read(x, 1)[0] == 1.0
     with pytest.raises(ob.ObError) as e:
-        c.value_read(x, 1)                           # nothing is evaluated at the moment
-    assert e.value.code == -6
+        c.value_read(y, 1)                           # no value yet
+    assert e.value.code == -1
     c.forward(y)
     assert c.value_read(x, 1)[0] == 1.0 and c.value_read(y, 1)[0] == 2.5
+    st = c.stats()
+    assert (st["n_stages"], st["n_nodes"], st["n_proxies"]) == (2, 1, 0)
+    with pytest.raises(ob.ObError) as e:
+        c.grad_read(x, 1)                            # the gradient of the shorter graph is gone
+    assert e.value.code == -6
+    c.backward(y)                                    # one schedule over both nodes again
+    assert c.stats()["n_stages"] == 1
+    assert c.grad_read(y, 1)[0] == 1.0 and c.grad_read(x, 1)[0] == 0.0
     # graph_new starts over; forward of a prefix evaluates only ids <= node
     c.graph_new()
     g = wl.rnn_minibatch(p, seed=5, lengths=[2, 4])
@@ -316,10 +328,11 @@ def _graph_part(g, lo, hi):
 
 def test_forward_in_stages_and_graph_extension(workload_cache):
     """Section 3.1: evaluation happens when a value is asked for, and the graph may grow afterwards.
-    A forward of a longer prefix, and a forward after nodes were added to an evaluated graph, give
-    the same values and gradients as one forward of the finished graph (the library evaluates the
-    whole prefix again in both cases)."""
+    A forward of a longer prefix, and a forward after nodes were added to an evaluated graph,
+    evaluate only the nodes that have no value yet; values, and after the backward pass gradients,
+    are those of one forward of the finished graph."""
     from paper_1705_07860_amd import binding as ob
+    from tests.helpers import stage_schedule
     p, g, o = workload_cache("rnn")
     total = int(o.v_off[-1])
     first_sq = int(np.nonzero(g.op == wl.OP_SQNORM)[0][0])
@@ -332,7 +345,19 @@ def test_forward_in_stages_and_graph_extension(workload_cache):
     early = c.value_read(first_sq, 1)[0]
     assert abs(early - o.value(first_sq)[0]) <= TOL * abs(o.value(first_sq)[0])
     c.forward(g.root)
+    st = c.stats()
+    assert (st["n_stages"], st["n_nodes"]) == (2, g.n - first_sq - 1)
+    bo, ids, bd, _ = c.schedule_read()
+    rbo, rids, rbd = stage_schedule(S.by_depth, g, first_sq + 1, g.n)
+    assert np.array_equal(bo, rbo) and np.array_equal(ids, rids) and np.array_equal(bd, rbd)
+    with pytest.raises(ob.ObError) as e:
+        c.all_read(0, total)                         # no single arena to read while values lie in two stages
+    assert e.value.code == -6
     check_against_oracle(c, p, g, o, g.root, what="rnn/staged forward")
+    assert c.stats()["n_stages"] == 1                # the backward pass put everything under one schedule
+    bo, ids, bd, _ = c.schedule_read()
+    rbo, rids, rbd = S.by_depth(g)
+    assert np.array_equal(bo, rbo) and np.array_equal(ids, rids) and np.array_equal(bd, rbd)
     c.close()
     # (b) the graph is built in two parts around an evaluation
     c = ob.Context(arena_bytes=64 << 20)
@@ -344,11 +369,82 @@ def test_forward_in_stages_and_graph_extension(workload_cache):
     assert c.value_read(first_sq, 1)[0] == early
     assert c.add_bulk(_graph_part(g, k, g.n)) == k
     c.forward(g.root)
+    assert c.stats()["n_stages"] == 2
     check_against_oracle(c, p, g, o, g.root, what="rnn/extended graph")
     bo, ids, bd, _ = c.schedule_read()
     rbo, rids, rbd = S.by_depth(g)
     assert np.array_equal(bo, rbo) and np.array_equal(ids, rids) and np.array_equal(bd, rbd)
     c.close()
+
+
+@pytest.mark.parametrize("name,mode", [("tagger", "depth"), ("tree", "depth"), ("parser", "agenda")])
+def test_forward_in_many_stages_at_full_size(name, mode, workload_cache):
+    """A full-size graph evaluated in five stages cut at arbitrary node ids (in the middle of
+    instances and of LSTM cells): after every stage the new values match the oracle, earlier
+    values are still there, and the stage's schedule is the reference schedule of the stage's
+    graph; the backward pass then gives the gradients of the whole graph."""
+    from paper_1705_07860_amd import binding as ob
+    from tests.helpers import stage_schedule
+    p, g, o = workload_cache(name)
+    ref = S.by_depth if mode == "depth" else S.by_agenda
+    rng = np.random.default_rng(77)
+    cuts = sorted(int(x) for x in rng.choice(np.arange(1000, g.n - 1000), size=4, replace=False)) + [g.n]
+    c = ob.Context(arena_bytes=3 << 30, mode=ob.OB_BYDEPTH if mode == "depth" else ob.OB_BYAGENDA)
+    c.params_create(p)
+    c.param_grad_zero()
+    c.add_bulk(g)
+    lo = 0
+    for k, hi in enumerate(cuts):
+        c.forward(hi - 1)
+        st = c.stats()
+        assert (st["n_stages"], st["n_nodes"]) == (k + 1, hi - lo)
+        bo, ids, bd, _ = c.schedule_read()
+        rbo, rids, rbd = ref(g, hi) if k == 0 else stage_schedule(ref, g, lo, hi)
+        assert np.array_equal(bo, rbo) and np.array_equal(ids, rids) and np.array_equal(bd, rbd)
+        probe = np.unique(np.concatenate((rng.integers(lo, hi, size=150), rng.integers(0, hi, size=50), [lo, hi - 1])))
+        worst = max(rel_err(c.value_read(int(v), int(g.out_dim[v])), o.value(int(v))) for v in probe)
+        say(f"  {name} stage {k}: nodes [{lo}, {hi}) read {st['n_proxies']} earlier nodes, batches={st['n_batches']}, "
+            f"sched {st['ms_schedule']:.3f} ms, fwd {st['ms_forward']:.3f} ms, worst rel err {worst:.2e}")
+        assert worst <= TOL
+        lo = hi
+    c.backward(g.root)
+    assert c.stats()["n_stages"] == 1
+    total = int(o.v_off[-1])
+    assert segment_rel_err(c.all_read(0, total), o.val[:total], o.v_off) <= TOL
+    assert segment_rel_err(c.all_read(1, total), o.grad[:total], o.v_off) <= TOL
+    for pid, m in enumerate(p.mats):
+        assert rel_err(c.param_grad_read(pid, m.shape), o.param_grad(pid)) <= TOL, p.names[pid]
+    c.close()
+
+
+def test_graph_grown_node_by_node_and_a_full_arena():
+    """The pattern of a model that looks at a value before it decides what to add (Section 3.1): a
+    graph grown in many small steps, a forward after each.  With an arena too small to stack all
+    stages the library evaluates everything again instead, with the same values."""
+    from paper_1705_07860_amd import binding as ob
+    p, g = wl.random_dag(941, n_nodes=150, dim=8)
+    o = Oracle(g, p, "f64")
+    o.forward()
+    o.backward(g.root)
+    for arena, expect_fallback in ((256 << 20, False), (6 << 20, True)):
+        c = ob.Context(arena_bytes=arena)
+        c.params_create(p)
+        c.param_grad_zero()
+        lo, stages_seen = 0, []
+        while lo < g.n:
+            hi = min(g.n, lo + 1 + (lo * 7) % 13)
+            assert c.add_bulk(_graph_part(g, lo, hi)) == lo
+            c.forward(hi - 1)
+            stages_seen.append(c.stats()["n_stages"])
+            for v in (lo, hi - 1, (lo * 5) % hi):
+                assert rel_err(c.value_read(v, int(g.out_dim[v])), o.value(v)) <= TOL
+            lo = hi
+        say(f"  arena {arena >> 20} MB: stages after each forward {stages_seen}")
+        assert (min(stages_seen[1:]) == 1) == expect_fallback
+        if not expect_fallback:
+            assert stages_seen == list(range(1, len(stages_seen) + 1))
+        check_against_oracle(c, p, g, o, g.root, what=f"grown dag, arena {arena >> 20} MB")
+        c.close()
 
 
 def test_arena_too_small_is_an_error_not_a_crash():
