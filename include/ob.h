@@ -187,7 +187,8 @@ int ob_schedule(ob_ctx *ctx, int node);
 int ob_schedule_async(ob_ctx *ctx, int node);
 /* Reverse-mode differentiation from a 1-element node that ob_forward covered: batches in
  * reverse order (Section 3.3).  Node gradients are overwritten, parameter gradients
- * accumulate. */
+ * accumulate.  After forwards in several stages (see ob_forward) everything evaluated so far is
+ * first scheduled and evaluated again as one graph. */
 int ob_backward(ob_ctx *ctx, int node);
 int ob_sync(ob_ctx *ctx);
 /* Forgets the schedule, values and gradients of the current graph but keeps its nodes (and
@@ -203,9 +204,12 @@ int ob_grad_read(ob_ctx *ctx, int node, float *host_out, size_t cap);
 int ob_all_read(ob_ctx *ctx, int which, float *host_out, size_t cap);
 
 /* The schedule of the last ob_forward: batch b holds node_ids[batch_off[b] .. batch_off[b+1]).
- * batch_depth is the depth (OB_BYDEPTH), the agenda iteration (OB_BYAGENDA) or the step index (OB_NOBATCH); batch_sig is the
- * 64-bit signature hash (Appendix B) and is informational.  cap_batches / cap_nodes are the
- * capacities of the per-batch arrays (batch_off needs cap_batches + 1) and of node_ids. */
+ * batch_depth is the depth (OB_BYDEPTH), the agenda iteration (OB_BYAGENDA), the rank of the
+ * batch's label (OB_MANUAL) or the step index (OB_NOBATCH); batch_sig is the 64-bit signature
+ * hash (Appendix B) and is informational.  cap_batches / cap_nodes are the capacities of the
+ * per-batch arrays (batch_off needs cap_batches + 1) and of node_ids.  After a forward that
+ * evaluated a stage (see ob_forward) this is the stage's schedule: only its nodes, depths
+ * counted from its leaves. */
 int ob_schedule_read(ob_ctx *ctx, int *n_batches, int *batch_depth, uint64_t *batch_sig,
                      int *batch_off, int *node_ids, size_t cap_batches, size_t cap_nodes);
 

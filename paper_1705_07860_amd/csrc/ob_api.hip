@@ -79,6 +79,8 @@ int ob_ctx_destroy(ob_ctx *ctx)
 {
     CHECK_CTX(ctx);
     drop_stages(ctx);
+    for (ob_ctx *c : ctx->stage_pool) (void)ob_ctx_destroy(c);
+    ctx->stage_pool.clear();
     if (ctx->uploaded) { (void)hipStreamSynchronize(ctx->sched_stream); (void)hipStreamSynchronize(ctx->stream); }
     if (ctx->gexec_fwd) (void)hipGraphExecDestroy(ctx->gexec_fwd);
     if (ctx->gexec_bwd) (void)hipGraphExecDestroy(ctx->gexec_bwd);
@@ -805,11 +807,36 @@ static int wait_own_work(ob_ctx *ctx)
     return 0;
 }
 
+// Stage contexts are kept for later stages: creating events and pinned buffers costs more than
+// evaluating a small stage.
 static void drop_stages(ob_ctx *ctx)
 {
-    for (Stage &st : ctx->stages)
-        if (st.c) (void)ob_ctx_destroy(st.c);   // waits for the stage's work first
+    if (ctx->stages.empty()) return;
+    // everything the stages queued runs in order on the two streams of this context: when the
+    // last stage has finished, all have
+    bool waited = wait_own_work(ctx->stages.back().c) == 0;
+    for (Stage &st : ctx->stages) {
+        if (!st.c) continue;
+        if (waited) { st.c->uploaded = false; ctx->stage_pool.push_back(st.c); }
+        else (void)ob_ctx_destroy(st.c);   // waits for the streams itself
+    }
     ctx->stages.clear();
+}
+
+// A retired stage context, set up again over another part of the owner's arena.
+static void stage_rebase(ob_ctx *c, ob_ctx *owner, char *arena, size_t bytes)
+{
+    (void)ob_graph_new(c);   // nothing of it is in flight (see drop_stages), so this only empties the host graph store
+    c->arena = arena; c->arena_bytes = bytes;
+    c->persist_top = c->top = 0;
+    c->stream = owner->stream; c->sched_stream = owner->sched_stream;
+    c->mode = owner->mode; c->launch = owner->launch; c->fuse = owner->fuse;
+    c->params = owner->params; c->max_param_rows = owner->max_param_rows;
+    c->params_used_w.assign(c->params.size(), 0);
+    c->params_used_b.assign(c->params.size(), 0);
+    c->params_dev = nullptr; c->wtiles_dev = c->btiles_dev = nullptr;
+    c->params_dirty = true;
+    c->err.clear();
 }
 
 static int forget_evaluation(ob_ctx *ctx)
@@ -896,7 +923,13 @@ static int stage_forward(ob_ctx *ctx, u32 n0, u32 n1)
     }
     used = (used + 255) & ~(size_t)255;
     if (used + (1u << 16) > ctx->arena_bytes) return fail(ctx_fail(ctx, OB_E_OOM, "arena too small for another evaluation stage"));
-    if (int rc = ob_ctx_fork(ctx, ctx->arena + used, ctx->arena_bytes - used, ctx->stream, &st.c)) return fail(rc);
+    if (!ctx->stage_pool.empty()) {
+        st.c = ctx->stage_pool.back();
+        ctx->stage_pool.pop_back();
+        stage_rebase(st.c, ctx, ctx->arena + used, ctx->arena_bytes - used);
+    } else if (int rc = ob_ctx_fork(ctx, ctx->arena + used, ctx->arena_bytes - used, ctx->stream, &st.c)) {
+        return fail(rc);
+    }
     ob_ctx *c = st.c;
     c->sched_stream = ctx->sched_stream;
     c->is_stage = true;
@@ -906,6 +939,12 @@ static int stage_forward(ob_ctx *ctx, u32 n0, u32 n1)
     int rc = ob_add_bulk(c, (int)nl, op.data(), od.data(), ioff.data(), iidx.data(), par.data(), bia.data(), a0.data(),
                          a1.data(), pay.data(), pay.size());
     if (rc < 0) { ctx->err = c->err; return fail(rc); }
+    if (ctx->params_dev) {
+        // a stage only runs forward: the owner's parameter table serves (its entries do not depend on
+        // which parameters a graph uses), and the tile lists of the parameter-gradient kernels are not needed
+        c->params_dev = ctx->params_dev; c->wtiles_dev = ctx->wtiles_dev; c->btiles_dev = ctx->btiles_dev;
+        c->params_dirty = false;
+    }
     if ((rc = ob_upload(c)) != 0) { ctx->err = c->err; return fail(rc); }
 
     // copies of the earlier values, owner by owner (proxies ascend, and so do the owners' id ranges)

@@ -71,6 +71,7 @@ struct ob_ctx {
     bool image_stale = false;          // nodes were added behind a live evaluation: the device image lacks them
     std::vector<Stage> stages;         // evaluations after the first, in order (empty: one schedule covers all)
     bool is_stage = false;             // this context is a Stage's own
+    std::vector<ob_ctx *> stage_pool;  // retired stage contexts (events and pinned buffers are kept for the next stage)
     u32 n_sched = 0;                   // nodes covered by the last schedule (0 = none)
     bool sched_pending = false;        // scheduling is queued on the GPU, its results are not read yet
     u32 hdr_window = 0, n_items_sched = 0;
