@@ -94,6 +94,33 @@ __global__ __launch_bounds__(SCAN_THREADS) void k_scan_add(T *out, const T *bloc
         if (base + i < n) out[base + i] = out[base + i] + add;
 }
 
+// Short inputs: one workgroup walks the chunks with a carry, one launch instead of two or three
+// (the scheduler of a small graph is bound by the number of its launches).  in == out is fine.
+constexpr size_t SCAN_SMALL_MAX = 4 * SCAN_BLOCK;
+template <typename T>
+__global__ __launch_bounds__(SCAN_THREADS) void k_scan_small(const T *in, T *out, size_t n, T *total_out)
+{
+    __shared__ T lds[SCAN_THREADS];
+    T carry = zero_of<T>();
+    for (size_t c0 = 0; c0 < n; c0 += SCAN_BLOCK) {
+        const size_t base = c0 + (size_t)threadIdx.x * SCAN_ITEMS;
+        T item[SCAN_ITEMS];
+        T sum = zero_of<T>();
+        for (int i = 0; i < SCAN_ITEMS; ++i) {
+            item[i] = (base + i < n) ? in[base + i] : zero_of<T>();
+            sum = sum + item[i];
+        }
+        T total;
+        T run = carry + block_exclusive<T>(sum, lds, &total);
+        for (int i = 0; i < SCAN_ITEMS; ++i) {
+            if (base + i < n) out[base + i] = run;
+            run = run + item[i];
+        }
+        carry = carry + total;
+    }
+    if (threadIdx.x == 0 && total_out) *total_out = carry;
+}
+
 template <typename T>
 hipError_t scan_impl(const T *in, T *out, size_t n, T *total_dev, void *scratch, hipStream_t s)
 {
@@ -101,6 +128,10 @@ hipError_t scan_impl(const T *in, T *out, size_t n, T *total_dev, void *scratch,
         // total = 0
         if (total_dev) return hipMemsetAsync(total_dev, 0, sizeof(T), s);
         return hipSuccess;
+    }
+    if (n <= SCAN_SMALL_MAX) {
+        hipLaunchKernelGGL(k_scan_small<T>, dim3(1), dim3(SCAN_THREADS), 0, s, in, out, n, total_dev);
+        return hipGetLastError();
     }
     const size_t nblk = (n + SCAN_BLOCK - 1) / SCAN_BLOCK;
     T *sums = (T *)scratch;
@@ -194,6 +225,84 @@ __global__ __launch_bounds__(RS_THREADS) void k_rs_scatter(const u64 *keys, cons
     }
 }
 
+// Short inputs: the whole sort in one workgroup, all passes in one launch.  Every pass counts the
+// digits of all keys, scans the 256 counts, then scatters tile by tile (1024 keys, one per thread):
+// lanes of a wave with equal digits are ranked by lane id, waves by their order in the tile, tiles
+// by the running start of every digit, which keeps the sort stable.  Passes alternate between the
+// two buffer pairs in global memory; a workgroup sees its own global writes after a barrier.
+constexpr int RSS_THREADS = 1024;
+constexpr int RSS_WAVES = RSS_THREADS / 64;
+constexpr size_t RS_SMALL_MAX = 8192;
+__global__ __launch_bounds__(RSS_THREADS) void k_rs_small(u64 *keys, u32 *vals, u64 *keys_tmp, u32 *vals_tmp, u32 n,
+                                                         int lo_bit, int n_bits)
+{
+    __shared__ u32 start[RS_RADIX];             // running first output position of every digit
+    __shared__ u32 cnt[RSS_WAVES][RS_RADIX];
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, t = threadIdx.x;
+    u64 *kin = keys, *kout = keys_tmp;
+    u32 *vin = vals, *vout = vals_tmp;
+    for (int b = 0; b < n_bits; b += RS_BITS) {
+        const int bits = (n_bits - b < RS_BITS) ? (n_bits - b) : RS_BITS;
+        const u32 mask = (1u << bits) - 1u;
+        const int shift = lo_bit + b;
+        if (t < RS_RADIX) start[t] = 0;
+        __syncthreads();
+        for (u32 i = t; i < n; i += RSS_THREADS) atomicAdd(&start[digit_of(kin[i], shift, mask)], 1u);
+        __syncthreads();
+        if (t < RS_RADIX) cnt[0][t] = start[t];
+        __syncthreads();
+        for (int off = 1; off < RS_RADIX; off <<= 1) {
+            u32 add = 0;
+            if (t < RS_RADIX && t >= off) add = cnt[0][t - off];
+            __syncthreads();
+            if (t < RS_RADIX) cnt[0][t] += add;
+            __syncthreads();
+        }
+        if (t < RS_RADIX) start[t] = cnt[0][t] - start[t];   // inclusive -> exclusive
+        __syncthreads();
+        for (u32 t0 = 0; t0 < n; t0 += RSS_THREADS) {
+            for (int i = 0; i < RSS_WAVES * RS_RADIX / RSS_THREADS; ++i) (&cnt[0][0])[i * RSS_THREADS + t] = 0;
+            __syncthreads();
+            const u32 idx = t0 + t;
+            const bool ok = idx < n;
+            const u64 key = ok ? kin[idx] : 0;
+            const u32 val = ok ? vin[idx] : 0;
+            const u32 d = digit_of(key, shift, mask);
+            u64 peers = __ballot(ok);
+            for (int q = 0; q < RS_BITS; ++q) {
+                const bool bit = (d >> q) & 1u;
+                const u64 m = __ballot(bit);
+                peers &= bit ? m : ~m;
+            }
+            if (!ok) peers = 0;
+            const u32 rank = (u32)__popcll(peers & ((1ull << lane) - 1ull));
+            const int leader = peers ? (__ffsll((unsigned long long)peers) - 1) : lane;
+            if (ok && leader == lane) cnt[w][d] = (u32)__popcll(peers);
+            __syncthreads();
+            if (t < RS_RADIX) {
+                u32 run = start[t];
+                for (int i = 0; i < RSS_WAVES; ++i) {
+                    const u32 c = cnt[i][t];
+                    cnt[i][t] = run;
+                    run += c;
+                }
+                start[t] = run;
+            }
+            __syncthreads();
+            if (ok) {
+                const u32 pos = cnt[w][d] + rank;
+                kout[pos] = key;
+                vout[pos] = val;
+            }
+            __syncthreads();
+        }
+        u64 *tk = kin; kin = kout; kout = tk;
+        u32 *tv = vin; vin = vout; vout = tv;
+    }
+    if (kin != keys)   // an odd number of passes: the result sits in the second pair
+        for (u32 i = t; i < n; i += RSS_THREADS) { keys[i] = kin[i]; vals[i] = vin[i]; }
+}
+
 }  // namespace
 
 // ---- host wrappers -------------------------------------------------------------------------------
@@ -240,6 +349,12 @@ hipError_t prim_sort_pairs(u64 *keys, u32 *vals, u64 *keys_tmp, u32 *vals_tmp, s
                            int n_bits, void *scratch, hipStream_t s, int *n_launches)
 {
     if (n <= 1 || n_bits <= 0) return hipSuccess;
+    if (n <= RS_SMALL_MAX) {
+        hipLaunchKernelGGL(k_rs_small, dim3(1), dim3(RSS_THREADS), 0, s, keys, vals, keys_tmp, vals_tmp, (u32)n, lo_bit,
+                           n_bits);
+        if (n_launches) *n_launches += 1;
+        return hipGetLastError();
+    }
     const u32 nblk = (u32)((n + RS_BLOCK - 1) / RS_BLOCK);
     u32 *table = (u32 *)scratch;
     void *scan_scratch = (char *)scratch + align256((size_t)RS_RADIX * nblk * sizeof(u32));
@@ -258,7 +373,7 @@ hipError_t prim_sort_pairs(u64 *keys, u32 *vals, u64 *keys_tmp, u32 *vals_tmp, s
         u64 *tk = kin; kin = kout; kout = tk;
         u32 *tv = vin; vin = vout; vout = tv;
         ++passes;
-        if (n_launches) *n_launches += 2 + ((size_t)RS_RADIX * nblk > SCAN_BLOCK ? 3 : 2);
+        if (n_launches) *n_launches += 2 + ((size_t)RS_RADIX * nblk > SCAN_SMALL_MAX ? 3 : 1);
     }
     if (passes & 1) {  // result sits in the tmp arrays: copy back
         hipError_t e = hipMemcpyAsync(keys, kin, n * sizeof(u64), hipMemcpyDeviceToDevice, s);

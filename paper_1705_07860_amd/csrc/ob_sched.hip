@@ -1476,7 +1476,8 @@ int sched_enqueue(ob_ctx *ctx)
     K(k_node_init, n, T, manual ? 2 : by_depth);
     if (E > 0) K(k_edge_init, E, T, ctx->key_a, ctx->val_a);
     HIP_TRY(ctx, prim_scan_u32(T.outdeg, T.succ_off, (size_t)n + 1, nullptr, ctx->scratch, s));
-    ctx->n_launch_sched += 3;
+    const int scan_launches = (size_t)n + 1 <= 4096 ? 1 : 3;   // a scan of a short array is one launch
+    ctx->n_launch_sched += scan_launches;
     if (E > 0) {
         HIP_TRY(ctx, prim_sort_pairs(ctx->key_a, ctx->val_a, ctx->key_b, ctx->val_b, E, 0,
                                      bit_width_u32(n - 1), ctx->scratch, s, &ctx->n_launch_sched));
@@ -1518,11 +1519,11 @@ int sched_enqueue(ob_ctx *ctx)
     HIP_TRY(ctx, prim_scan_u32(head_flag, head_excl, n, nullptr, ctx->scratch, s));
     HIP_TRY(ctx, prim_scan_u32(s_arity, T.s_in_off, n, nullptr, ctx->scratch, s));
     HIP_TRY(ctx, prim_scan_u32(s_items, s_items, n, nullptr, ctx->scratch, s));
-    ctx->n_launch_sched += 9;
+    ctx->n_launch_sched += 3 * scan_launches;
     K(k_batch_off, n, T, head_flag, head_excl, manual);
     K(k_batch_layout, n, T, ctx->lay_in);
     HIP_TRY(ctx, prim_scan_lay(ctx->lay_in, T.lay, n, ctx->lay_total, ctx->scratch, s));
-    ctx->n_launch_sched += 3;
+    ctx->n_launch_sched += scan_launches;
     K(k_batch_finish, n, T, T.lay, ctx->lay_total);
     K(k_node_offsets, n, T);
     K(k_member_check, n, T);
@@ -1546,7 +1547,7 @@ int sched_enqueue(ob_ctx *ctx)
     K(k_clay_zero, n, clay_in, n);
     K(k_chain_recs, n, T, agenda || manual, bset, cflag, cflag_excl, clay_in, n);
     HIP_TRY(ctx, prim_scan_clay(clay_in, T.clay, n, clay_total, ctx->scratch, s));
-    ctx->n_launch_sched += 6;
+    ctx->n_launch_sched += 2 * scan_launches;
     K(k_slot_init, (size_t)n + 2, T);
     K(k_slot_tables, n, T, T.clay, clay_total);
     if (fuse) K(k_slot_fill, (size_t)n + 2, T);

@@ -14,7 +14,7 @@ def ctx():
     c.close()
 
 
-@pytest.mark.parametrize("n", [0, 1, 255, 1024, 1025, 5000, 300001])
+@pytest.mark.parametrize("n", [0, 1, 255, 1024, 1025, 4095, 4096, 4097, 5000, 300001])
 def test_scan(ctx, n):
     rng = np.random.default_rng(n)
     a = rng.integers(0, 1000, size=n).astype(np.uint32)
@@ -24,7 +24,8 @@ def test_scan(ctx, n):
     assert tot == int(a.sum())
 
 
-@pytest.mark.parametrize("n,lo,bits", [(1, 0, 8), (64, 0, 8), (1000, 0, 18), (1025, 32, 10), (4097, 0, 5),
+@pytest.mark.parametrize("n,lo,bits", [(1, 0, 8), (2, 0, 1), (64, 0, 8), (1000, 0, 18), (1023, 5, 26), (1025, 32, 10),
+                                       (4097, 0, 5), (4097, 0, 26), (8192, 0, 24), (8192, 7, 17), (8193, 0, 9),
                                        (240000, 0, 18), (240000, 32, 18), (196608, 0, 12), (196609, 3, 12), (80000, 0, 17)])
 def test_radix_sort_is_stable_and_exact(ctx, n, lo, bits):
     rng = np.random.default_rng(n + lo)
