@@ -223,8 +223,11 @@ hipError_t prim_scan_clay(const CLay *in, CLay *out, size_t n, CLay *total_dev, 
 size_t prim_sort_scratch_bytes(size_t n);
 // Stable LSD radix sort of (key, val) pairs on bits [lo_bit, lo_bit + n_bits) of the key.
 // keys/vals are overwritten with the sorted result; tmp arrays have the same sizes.
+// n_dev (device, optional): the caller promises that pairs from index *n_dev on already sit where
+// a stable sort would leave them (padding with the largest key); short inputs then sort only the
+// first *n_dev pairs.
 hipError_t prim_sort_pairs(u64 *keys, u32 *vals, u64 *keys_tmp, u32 *vals_tmp, size_t n, int lo_bit,
-                           int n_bits, void *scratch, hipStream_t s, int *n_launches);
+                           int n_bits, void *scratch, hipStream_t s, int *n_launches, const u32 *n_dev = nullptr);
 
 // ---- scheduler / executor entry points ---------------------------------------------------
 struct ob_ctx;

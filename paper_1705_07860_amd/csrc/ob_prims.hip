@@ -234,8 +234,9 @@ constexpr int RSS_THREADS = 1024;
 constexpr int RSS_WAVES = RSS_THREADS / 64;
 constexpr size_t RS_SMALL_MAX = 8192;
 __global__ __launch_bounds__(RSS_THREADS) void k_rs_small(u64 *keys, u32 *vals, u64 *keys_tmp, u32 *vals_tmp, u32 n,
-                                                         int lo_bit, int n_bits)
+                                                         int lo_bit, int n_bits, const u32 *n_dev)
 {
+    if (n_dev) n = *n_dev < n ? *n_dev : n;   // the same value for every thread: barriers below stay uniform
     __shared__ u32 start[RS_RADIX];             // running first output position of every digit
     __shared__ u32 cnt[RSS_WAVES][RS_RADIX];
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, t = threadIdx.x;
@@ -346,12 +347,12 @@ size_t prim_sort_scratch_bytes(size_t n)
 }
 
 hipError_t prim_sort_pairs(u64 *keys, u32 *vals, u64 *keys_tmp, u32 *vals_tmp, size_t n, int lo_bit,
-                           int n_bits, void *scratch, hipStream_t s, int *n_launches)
+                           int n_bits, void *scratch, hipStream_t s, int *n_launches, const u32 *n_dev)
 {
     if (n <= 1 || n_bits <= 0) return hipSuccess;
     if (n <= RS_SMALL_MAX) {
         hipLaunchKernelGGL(k_rs_small, dim3(1), dim3(RSS_THREADS), 0, s, keys, vals, keys_tmp, vals_tmp, (u32)n, lo_bit,
-                           n_bits);
+                           n_bits, n_dev);
         if (n_launches) *n_launches += 1;
         return hipGetLastError();
     }

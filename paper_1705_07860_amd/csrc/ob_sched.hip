@@ -1538,8 +1538,9 @@ int sched_enqueue(ob_ctx *ctx)
     K(k_launch_keys, n, T, ctx->key_a, ctx->val_a, n);
     if (fuse && E > 0) {
         const size_t n_sort = n < SLOT_MAX_NB + 1 ? n : SLOT_MAX_NB + 1;
+        // entries from n_batches on carry the largest key and stay where they are
         HIP_TRY(ctx, prim_sort_pairs(ctx->key_a, ctx->val_a, ctx->key_b, ctx->val_b, n_sort, 0, 2 * SLOT_BITS,
-                                     ctx->scratch, s, &ctx->n_launch_sched));
+                                     ctx->scratch, s, &ctx->n_launch_sched, &T.hdr->n_batches));
     }
     u32 *cflag = ctx->tmp_u32_a, *cflag_excl = ctx->tmp_u32_b;
     K(k_chain_flags, n, T, ctx->val_a, cflag, n);
