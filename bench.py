@@ -92,7 +92,7 @@ def stored_traffic(args, kernel):
     runs, FETCH_SIZE and WRITE_SIZE, scaled by a plain copy of known size).  Counters cannot be
     read inside a timing run, so the figure is the stored one and only applies to the default
     launch configuration of the workload it was taken on; otherwise null."""
-    if args.launch != "stream" or args.no_fusion or args.placement != "late" or args.mode != "depth":
+    if args.launch != "stream" or args.no_fusion or args.placement != "late" or args.mode != "depth" or args.epilogue:
         return None
     path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles", f"{args.workload}_bydepth_hbm_traffic.json")
     try:
@@ -125,6 +125,9 @@ def main():
     ap.add_argument("--no-pipeline", action="store_true",
                     help="schedule and execute each step back to back on one stream (no overlap between steps)")
     ap.add_argument("--no-fusion", action="store_true", help="one launch per depth level")
+    ap.add_argument("--epilogue", action="store_true",
+                    help="fusion level 3: component-wise chains are evaluated behind the tiles of the matrix product they "
+                         "read (half the forward launches of an LSTM workload, but slower launches: not the default)")
     ap.add_argument("--placement", default="late", choices=["early", "late"],
                     help="fused plans launch a batch as early as its operands / as late as its consumers allow")
     ap.add_argument("--update", action="store_true",
@@ -177,7 +180,7 @@ def main():
         if j == 0:
             c = ob.Context(arena_bytes=arena_bytes, stream=stream, launch=launch, sched_stream=sched_streams[0],
                            mode={"agenda": ob.OB_BYAGENDA, "manual": ob.OB_MANUAL}.get(args.mode, ob.OB_BYDEPTH))
-            c.set_fusion(0 if args.no_fusion else (2 if args.placement == "late" else 1))
+            c.set_fusion(0 if args.no_fusion else (1 if args.placement == "early" else (3 if args.epilogue else 2)))
             c.params_create(params)
             c.param_grad_zero()
         else:

@@ -95,13 +95,17 @@ int ob_ctx_destroy(ob_ctx *ctx);
 int ob_ctx_set_schedule_stream(ob_ctx *ctx, void *hip_stream);
 int ob_ctx_set_mode(ob_ctx *ctx, int mode);
 int ob_ctx_set_launch(ob_ctx *ctx, int launch);
-/* Launch fusion (default on, OB_BYDEPTH only): component-wise batches whose operands are
+/* Launch fusion (default 2; every batching mode): component-wise batches whose operands are
  * row-aligned with their producer batch run inside the producer's launch (Section 3.3: inputs
  * that are already contiguous and in order are used as they are), so a chain of such batches
  * costs one launch instead of one per depth level.  Batches and their order do not change.
  * on: 0 = one launch per depth level; 1 = fused, every batch launched as early as its operands
  * allow; 2 = fused, every batch launched as late as its consumers allow (batches off the longest
- * dependency path then share the launches next to their consumers).  Other values: OB_E_ARG. */
+ * dependency path then share the launches next to their consumers); 3 = 2, and a fused chain that
+ * reads a matrix product row for row (an LSTM cell behind W_h h) is evaluated forward behind every
+ * tile of that product, in the product's launch, when its members' widths are multiples of a
+ * common segment width and the product has 1, 2 or 4 such segments and at least 16 rows (values
+ * are bit-identical to level 2; fewer, longer launches).  Other values: OB_E_ARG. */
 int ob_ctx_set_fusion(ob_ctx *ctx, int on);
 /* Library-owned message for the last failing call on this context (valid until the next
  * call); ctx may be NULL for errors of ob_ctx_create. */
@@ -237,6 +241,10 @@ int ob_stats_read(ob_ctx *ctx, ob_stats *out);
 #define OB_DBG_TILES_FWD 6 /* forward tile descriptors in launch order, 40 words each (internal layout) */
 #define OB_DBG_TILES_PULL 7 /* backward pull tile descriptors in launch order, 48 words each (internal layout) */
 #define OB_DBG_CHAINS 8    /* launch chains, 8 words each: first, members, slot, fused, groups, groups per block, blocks, tiles per block */
+#define OB_DBG_EPI_TAIL 9  /* u32 per launch chain: the chain a matrix-product chain evaluates behind its tiles (0xffffffff: none) */
+#define OB_DBG_EPI_MAP 10  /* u32 per launch chain: with a tail, a | s << 16 (product row i = row a + s i of the tail); a product
+                            * chain without one holds 0xE0000000 | the number of the test that refused the pairing */
+#define OB_DBG_LORDER 11   /* u32 per batch: batch ids in launch order (the members of chain c are entries first .. first + members - 1) */
 int ob_debug_read(ob_ctx *ctx, int which, uint32_t *host_out, size_t cap_words, size_t *n_words);
 
 /* Stand-alone device primitives, exposed so that tests can check them directly.  All

@@ -21,7 +21,7 @@ LIB_PATH = HERE / "libob.so"
 OB_NOBATCH, OB_BYDEPTH, OB_BYAGENDA, OB_MANUAL = 0, 1, 2, 3
 OB_LAUNCH_STREAM, OB_LAUNCH_GRAPH, OB_LAUNCH_PERSISTENT = 0, 1, 2
 OB_DBG_DEPTH, OB_DBG_SIG, OB_DBG_SUCC_OFF, OB_DBG_SUCC_EDGE, OB_DBG_ORDER, OB_DBG_VAL_OFF = range(6)
-OB_DBG_TILES_FWD, OB_DBG_TILES_PULL, OB_DBG_CHAINS = 6, 7, 8
+OB_DBG_TILES_FWD, OB_DBG_TILES_PULL, OB_DBG_CHAINS, OB_DBG_EPI_TAIL, OB_DBG_EPI_MAP, OB_DBG_LORDER = 6, 7, 8, 9, 10, 11
 
 ERRORS = {0: "OB_OK", -1: "OB_E_BADID", -2: "OB_E_DIM", -3: "OB_E_RANGE", -4: "OB_E_NOTSCALAR",
           -5: "OB_E_OOM", -6: "OB_E_STATE", -7: "OB_E_HIP", -8: "OB_E_ARG"}

@@ -121,7 +121,7 @@ int ob_ctx_set_schedule_stream(ob_ctx *ctx, void *hip_stream)
 int ob_ctx_set_fusion(ob_ctx *ctx, int on)
 {
     CHECK_CTX(ctx);
-    if (on < 0 || on > 2) return ctx_fail(ctx, OB_E_ARG, "fusion level %d (0, 1 or 2)", on);
+    if (on < 0 || on > 3) return ctx_fail(ctx, OB_E_ARG, "fusion level %d (0 .. 3)", on);
     ctx->fuse = on;
     return OB_OK;
 }
@@ -1205,6 +1205,9 @@ int ob_debug_read(ob_ctx *ctx, int which, uint32_t *host_out, size_t cap_words, 
     case OB_DBG_TILES_FWD: src = T.tiles_f; words = (size_t)ctx->hdr.tiles_fwd * (sizeof(TileDesc) / 4); break;
     case OB_DBG_TILES_PULL: src = T.tiles_a; words = (size_t)ctx->hdr.tiles_pull * (sizeof(PullDesc) / 4); break;
     case OB_DBG_CHAINS: src = T.chains; words = (size_t)ctx->hdr.n_chains * (sizeof(ChainRec) / 4); break;
+    case OB_DBG_EPI_TAIL: src = T.epi_tail; words = ctx->hdr.n_chains; break;
+    case OB_DBG_EPI_MAP: src = T.epi_map; words = ctx->hdr.n_chains; break;
+    case OB_DBG_LORDER: src = T.lorder; words = ctx->hdr.n_batches; break;
     default: return ctx_fail(ctx, OB_E_ARG, "unknown table %d", which);
     }
     if (n_words) *n_words = words;

@@ -33,7 +33,8 @@ struct ob_ctx {
     ob_ctx *parent = nullptr;            // forked contexts share the parent's parameters
     int mode = 1;      // OB_BYDEPTH
     int launch = 0;    // OB_LAUNCH_STREAM
-    int fuse = 2;      // launch fusion level: 0 off, 1 fused with early placement, 2 fused with late placement
+    int fuse = 2;      // launch fusion level: 0 off, 1 fused with early placement, 2 fused with late placement,
+                       // 3 = 2 and chains evaluated behind the tiles of the matrix product they read
     std::string err;
 
     // arena bump allocator: [0, persist_top) parameters; [persist_top, top) current graph

@@ -838,6 +838,8 @@ __global__ void k_chain_recs(Tables T, int agenda, const u32 *bset, const u32 *f
     if (i < nb) {
         const u32 c = flag_excl[i] + flag[i] - 1;
         T.chain_of_lpos[i] = c;
+        T.chain_of_batch[T.lorder[i]] = c;   // (a chain's members may still be reordered below: same chain)
+        T.epi_head[i] = EPI_NONE; T.epi_tail[i] = EPI_NONE; T.epi_cnt[i] = 0; T.epi_chk[i] = 0; T.epi_map[i] = 0;
         if (i == nb - 1) T.hdr->n_chains = c + 1;
     }
     if (i < nb && flag[i]) {
@@ -927,13 +929,197 @@ __global__ void k_clay_zero(CLay *clay_in, u32 n_pad)
 // floats of a fused chain's LDS copy taken by one member: its rows of a block of groups, rounded up to 4
 __device__ inline u32 chain_region(const ChainRec &cr, const BatchRec &r) { return (cr.Rg * (r.B / cr.G) * r.d + 3u) & ~3u; }
 
+// ---- GEMM-headed runs ---------------------------------------------------------------------------
+// A recurrence step is a matrix product followed by a chain of component-wise batches that reads
+// it row for row (the LSTM cell behind W_h h).  The product's 32 x 32 tiles and the chain's row
+// blocks cut the same data in different directions, which is why the chain waits for a launch
+// boundary.  If every member of the chain has the product's row count and a width that is a
+// multiple of Hs = the narrowest member's width, and wide members are only ever read through
+// slices at multiples of Hs, then element (row, unit u) of every member depends only on elements
+// (row, u + s * Hs) of its operands.  A product tile that covers the columns u0 .. u0 + w - 1 of
+// every one of the q = d / Hs segments (w = 32 / q) then holds all the chain needs for 32 rows x w
+// units, and the workgroup evaluates the whole chain for them right behind the tile, one thread
+// per (row, unit), values handed on through a per-thread file in LDS: the chain's forward work
+// moves into the product's launch and its own launch disappears.  Values, storage and the
+// backward pass do not change.
+//
+// Batches of component-wise nodes carry no parameter, so the cells of several recurrences that
+// run in step (the two directions of a BiLSTM) share their batches: the chain then has one
+// product per recurrence, and row a + s * i of every member belongs to row i of product number a
+// of s.  Every product gets a run of its own over its rows of the chain; the chain's own forward
+// work disappears when its s row classes have all found their product.
+//
+// One wave per chain looks for the pairing (product chain P -> consumer chain C) and checks it.
+__device__ inline bool epi_member_op(u32 op, u32 arity)
+{
+    return (op == OP_ADD && arity <= 4) || op == OP_CMULT || op == OP_TANH || op == OP_SIGMOID || op == OP_SLICE;
+}
+
+__global__ void k_epi_find(Tables T)
+{
+    const u32 c = (blockIdx.x * blockDim.x + threadIdx.x) >> 6;
+    const u32 lane = threadIdx.x & 63;
+    if (c >= T.hdr->n_chains || T.hdr->p0) return;
+    const ChainRec cp = T.chains[c];
+    if (cp.fused || cp.k != 1) return;
+    const u32 pb = T.lorder[cp.first];
+    const BatchRec P = T.batches[pb];
+    if (P.op != OP_MATVEC || (P.vec4 & TF_WIDE) || (P.d & 31u) || P.B > 4096u) return;
+    if (P.B < 16u) { if (lane == 0) T.epi_map[c] = 0xE0000000u | 21u; return; }   // keeps the tile list within the host's bound
+    // every row of P has one consumer; all consumers lie in one batch y of a fused chain with G
+    // groups (a group = the rows of one recurrence cell; y may hold several rows per group): row i
+    // of P feeds group a + s * i, s = G / rows of P, always at the same place ty inside the group
+    u32 yb = EPI_NONE, a = 0, st = 1, ty = 0, my = 1;
+    {
+        u32 mine = EPI_NONE, row = 0;
+        bool fine = true;
+        if (lane == 0) {
+            const u32 u = T.order[P.pos0];
+            const u32 q0 = T.succ_off[u];
+            fine = T.succ_off[u + 1] - q0 == 1u;
+            if (fine) {
+                const u32 pv = T.pos_of[T.edge_cons[T.succ_edge[q0]]];
+                mine = T.batch_of_pos[pv];
+                row = pv - T.batches[mine].pos0;
+            }
+        }
+        yb = __builtin_amdgcn_readfirstlane(mine);
+        a = __builtin_amdgcn_readfirstlane(row);
+        if (yb == EPI_NONE) { if (lane == 0) T.epi_map[c] = 0xE0000000u | 1u; return; }
+        const ChainRec cy = T.chains[T.chain_of_batch[yb]];
+        const u32 By = T.batches[yb].B;
+        if (!cy.fused || cy.G % P.B || By % cy.G) { if (lane == 0) T.epi_map[c] = 0xE0000000u | 2u; return; }
+        st = cy.G / P.B;
+        my = By / cy.G;
+        ty = a % my;
+        a = a / my;
+        if (a >= st || st > 255u) { if (lane == 0) T.epi_map[c] = 0xE0000000u | 3u; return; }
+    }
+    for (u32 i0 = 0; i0 < P.B; i0 += 64) {
+        const u32 i = i0 + lane;
+        bool fine = true;
+        if (i < P.B) {
+            const u32 u = T.order[P.pos0 + i];
+            const u32 q0 = T.succ_off[u];
+            fine = T.succ_off[u + 1] - q0 == 1u;
+            if (fine) {
+                const u32 pv = T.pos_of[T.edge_cons[T.succ_edge[q0]]];
+                fine = T.batch_of_pos[pv] == yb && pv - T.batches[yb].pos0 == (a + st * i) * my + ty;
+            }
+        }
+        if (__ballot(!fine) != 0ull) { if (lane == 0) T.epi_map[c] = 0xE0000000u | 4u; return; }
+    }
+    const u32 cc = T.chain_of_batch[yb];
+    const ChainRec cr = T.chains[cc];
+    if (!cr.fused || cr.k > EPI_MAX_MEMBERS || cr.slot <= cp.slot) { if (lane == 0) T.epi_map[c] = 0xE0000000u | 5u; return; }
+    // members: row count, operations, widths
+    u32 Hs = 0xffffffffu;
+    for (u32 m = 0; m < cr.k; ++m) {
+        const BatchRec &r = T.batches[T.lorder[cr.first + m]];
+        if (r.B % cr.G || !epi_member_op(r.op, r.arity)) { if (lane == 0) T.epi_map[c] = 0xE0000000u | 6u; return; }
+        Hs = r.d < Hs ? r.d : Hs;
+    }
+    if (1u + cr.kt > RUN_STAGE_DESCS) { if (lane == 0) T.epi_map[c] = 0xE0000000u | 18u; return; }
+    if (Hs == 0 || P.d % Hs) { if (lane == 0) T.epi_map[c] = 0xE0000000u | 7u; return; }
+    const u32 q = P.d / Hs;
+    if (q != 1 && q != 2 && q != 4) { if (lane == 0) T.epi_map[c] = 0xE0000000u | 8u; return; }
+    const u32 w = 32u / q;
+    if (Hs % w) { if (lane == 0) T.epi_map[c] = 0xE0000000u | 9u; return; }
+    u32 segs = q;
+    for (u32 m = 0; m < cr.k; ++m) {
+        const BatchRec &r = T.batches[T.lorder[cr.first + m]];
+        if (r.d % Hs || r.d / Hs > 4u) { if (lane == 0) T.epi_map[c] = 0xE0000000u | 10u; return; }
+        if (r.op == OP_SLICE && ((u32)r.aux0 % Hs)) { if (lane == 0) T.epi_map[c] = 0xE0000000u | 11u; return; }
+        segs += (r.B / cr.G) * (r.d / Hs);
+    }
+    if (segs * 32u * w > EPI_FILE_FLOATS) { if (lane == 0) T.epi_map[c] = 0xE0000000u | 12u; return; }
+    // operands of this product's groups: every slot of every row of a group reads, for all of
+    // these groups alike, one row of the same group of an earlier member, or row i of P, or a value
+    // that is complete before P's slot (the run executes in P's slot, ahead of the chain's own)
+    u32 n_ext = 0;
+    for (u32 m = 0; m < cr.k; ++m) {
+        const BatchRec &r = T.batches[T.lorder[cr.first + m]];
+        const u32 mult = r.B / cr.G;
+        for (u32 t = 0; t < mult; ++t)
+            for (u32 j = 0; j < r.arity; ++j) {
+                const u32 *op = T.opnd_off + r.opnd + j * r.B;
+                const u32 dj = T.b_indim[r.indim + j];
+                if (r.op != OP_SLICE && dj != r.d) { if (lane == 0) T.epi_map[c] = 0xE0000000u | 13u; return; }
+                if (r.op == OP_SLICE && (dj % Hs || dj / Hs > 4u)) { if (lane == 0) T.epi_map[c] = 0xE0000000u | 14u; return; }
+                // the first of these groups decides which case this slot is
+                const u32 o0 = op[a * mult + t];
+                u32 src_off = EPI_NONE, src_d = 0, src_mult = 1, src_t = 0;
+                bool from_p = false;
+                if (o0 >= P.val_off && o0 < P.val_off + P.B * P.d) { from_p = true; src_d = P.d; }
+                for (u32 mm = 0; mm < cr.k; ++mm) {
+                    const BatchRec &y = T.batches[T.lorder[cr.first + mm]];
+                    if (o0 >= y.val_off && o0 < y.val_off + y.B * y.d) {
+                        if (mm >= m) { if (lane == 0) T.epi_map[c] = 0xE0000000u | 15u; return; }   // not an order one thread can follow
+                        src_off = y.val_off; src_d = y.d; src_mult = y.B / cr.G;
+                        const u32 prow = (o0 - y.val_off) / y.d;
+                        if (prow / src_mult != a) { if (lane == 0) T.epi_map[c] = 0xE0000000u | 19u; return; }
+                        src_t = prow % src_mult;
+                    }
+                }
+                if ((from_p || src_off != EPI_NONE) && src_d != dj) { if (lane == 0) T.epi_map[c] = 0xE0000000u | 16u; return; }
+                if (!from_p && src_off == EPI_NONE) n_ext += r.d / Hs;
+                bool bad = false;
+                for (u32 i0 = 0; i0 < P.B; i0 += 64) {
+                    const u32 i = i0 + lane;
+                    if (i >= P.B) continue;
+                    const u32 grp = a + st * i;
+                    const u32 row = grp * mult + t;
+                    const u32 o = op[row];
+                    if (from_p) {
+                        bad = bad || o != P.val_off + i * P.d;
+                    } else if (src_off != EPI_NONE) {
+                        bad = bad || o != src_off + (grp * src_mult + src_t) * src_d;
+                    } else {
+                        const u32 v = T.order[r.pos0 + row];
+                        const u32 by = T.batch_of_pos[T.pos_of[T.in_idx[T.in_off[v] + j]]];
+                        bad = bad || T.slot_of[by] >= cp.slot;
+                    }
+                }
+                if (__ballot(bad) != 0ull) { if (lane == 0) T.epi_map[c] = 0xE0000000u | 17u; return; }
+            }
+    }
+    if (n_ext > EPI_MAX_EXT || (segs + n_ext) * 32u * w > EPI_FILE_FLOATS) { if (lane == 0) T.epi_map[c] = 0xE0000000u | 20u; return; }
+    if (lane == 0) {
+        // all products of a chain must agree on the slot and on s; the chain counts them
+        const u32 chk = ((cp.slot << 8) | st) + 1u;
+        const u32 old = atomicCAS(&T.epi_chk[cc], 0u, chk);
+        if (old != 0u && old != chk) atomicOr(&T.epi_chk[cc], EPI_BAD);
+        T.epi_tail[c] = cc;
+        T.epi_map[c] = a | (st << 16) | (n_ext << 24);
+        atomicAdd(&T.epi_cnt[cc], 1u);
+    }
+}
+
+// Per chain: a pairing holds when the chain's row classes all found their product; then the
+// chain's forward work moves into the products' tile lists.
+__global__ void k_epi_apply(Tables T, CLay *clay_in)
+{
+    const u32 c = blockIdx.x * blockDim.x + threadIdx.x;
+    if (c >= T.hdr->n_chains) return;
+    const u32 cc = T.epi_tail[c];
+    if (cc == EPI_NONE) return;
+    const u32 st = (T.epi_map[c] >> 16) & 0xffu;
+    const u32 chk = T.epi_chk[cc];
+    if ((chk & EPI_BAD) || T.epi_cnt[cc] != st) { T.epi_tail[c] = EPI_NONE; return; }
+    clay_in[c].tf = clay_in[c].wf * (1u + T.chains[cc].kt);   // the product tile, then every row of a group of every member
+    clay_in[cc].tf = 0;     // (every product of the chain writes the same)
+    clay_in[cc].wf = 0;
+    T.epi_head[cc] = c;
+}
+
 // every entry a plan can use (n_slots + 1 <= n + 2) starts out as "no batch here"
 __global__ void k_slot_init(Tables T)
 {
     const u32 s = blockIdx.x * blockDim.x + threadIdx.x;
     if (s > T.hdr->n_slots) return;
     SlotRec r; r.wf = r.wa = r.tb = r.tf = r.ta = r.lmin = r.nlmax = r.dx_free = 0xffffffffu;
-    r.lds_need = r.pad1 = r.pad2 = 0;
+    r.lds_need = 0;
+    r.lminf = r.nlmaxf = 0xffffffffu;
     r.plain = 0xffffffffu;
     T.slots[s] = r;
 }
@@ -960,6 +1146,28 @@ __global__ void k_slot_tables(Tables T, const CLay *clay_ex, const CLay *total)
     const u32 len = cr.fused ? cr.kt : 1u;
     atomicMin(&S.lmin, len);
     atomicMin(&S.nlmax, ~len);
+    // forward run lengths: a GEMM-headed run has its own, the chain it absorbed has no forward work
+    if (T.epi_head[c] == EPI_NONE) {
+        u32 lenf = len;
+        const u32 tail = T.epi_tail[c];
+        if (tail != EPI_NONE) {
+            const ChainRec ct = T.chains[tail];
+            lenf = 1u + ct.kt;
+            const BatchRec &P = T.batches[T.lorder[cr.first]];
+            u32 Hs = 0xffffffffu, segs = 0;
+            for (u32 m = 0; m < ct.k; ++m) { const u32 dm = T.batches[T.lorder[ct.first + m]].d; Hs = dm < Hs ? dm : Hs; }
+            const u32 q = P.d / Hs;
+            segs = q;
+            for (u32 m = 0; m < ct.k; ++m) {
+                const BatchRec &rm = T.batches[T.lorder[ct.first + m]];
+                segs += (rm.B / ct.G) * (rm.d / Hs);
+            }
+            segs += T.epi_map[c] >> 24;   // values fetched from outside the run
+            atomicMax(&S.lds_need, (u32)EPI_LDS_BASE + segs * 32u * (32u / q));
+        }
+        atomicMin(&S.lminf, lenf);
+        atomicMin(&S.nlmaxf, ~lenf);
+    }
     if (c == nc - 1) {
         const CLay t = *total;
         SlotRec &E = T.slots[s + 1];
@@ -1221,13 +1429,71 @@ __global__ void k_tiles(Tables T, const CLay *clay_ex, const CLay *total, u32 ca
             const u32 c = chain_of_index(clay_ex, nc, which, x);
             const ChainRec cr = T.chains[c];
             const u32 xx = x - clay_field(clay_ex[c], which);
-            if (which >= 3) {   // work item = one block of a fused chain, or one tile
+            const u32 tail = T.epi_tail[c];
+            if (which >= 3) {   // work item = one block of a fused chain, one tile, or one GEMM-headed run
                 WorkRec w;
                 const bool fwd = which == 3;
-                const u32 len = cr.fused ? cr.kt : 1u;
+                u32 len = cr.fused ? cr.kt : 1u;
+                if (fwd && tail != EPI_NONE) len = 1u + T.chains[tail].kt;
                 w.first = (fwd ? clay_ex[c].tf : clay_ex[c].ta) + xx * len;
                 w.len = len;
                 (fwd ? T.works_f : T.works_a)[x] = w;
+            } else if (which == 0 && tail != EPI_NONE) {
+                // GEMM-headed run: the product tile, then every member of the absorbed chain on the
+                // tile's rows; the member descriptors say where operands sit in the run's value file
+                const ChainRec ct = T.chains[tail];
+                const u32 per = 1u + ct.kt;
+                const u32 item = xx / per, sub = xx % per;
+                const BatchRec P = T.batches[T.lorder[cr.first]];
+                u32 Hs = 0xffffffffu;
+                for (u32 m = 0; m < ct.k; ++m) { const u32 dm = T.batches[T.lorder[ct.first + m]].d; Hs = dm < Hs ? dm : Hs; }
+                const u32 q = P.d / Hs;
+                TileDesc d;
+                if (sub == 0) {
+                    fill_tile_desc(T, P, item, false, false, 0, 0, 1, d);
+                    d.flags |= TF_EPI;
+                    u32 segs = q;   // file segments of the product and of all members: values from outside come behind them
+                    for (u32 m = 0; m < ct.k; ++m) {
+                        const BatchRec &rm = T.batches[T.lorder[ct.first + m]];
+                        segs += (rm.B / ct.G) * (rm.d / Hs);
+                    }
+                    d.lds_out = segs;
+                } else {
+                    // row `it` of every group of member m; its values take the file segments from `seg` on
+                    u32 m = 0, it = sub - 1, mult = 1, seg = q;
+                    for (;; ++m) {
+                        const BatchRec &rm = T.batches[T.lorder[ct.first + m]];
+                        mult = rm.B / ct.G;
+                        if (it < mult) { seg += it * (rm.d / Hs); break; }
+                        it -= mult;
+                        seg += mult * (rm.d / Hs);
+                    }
+                    const BatchRec r = T.batches[T.lorder[ct.first + m]];
+                    const u32 ntn = P.d / 32u;
+                    const u32 pr0 = (item / ntn) * 32u;                       // first row of the product tile
+                    const u32 nr = P.B - pr0 < 32u ? P.B - pr0 : 32u;
+                    const u32 ma = T.epi_map[c] & 0xffffu, ms = (T.epi_map[c] >> 16) & 0xffu;
+                    const u32 g0 = ma + ms * pr0;                             // its group of the chain
+                    fill_tile_desc(T, r, item, false, true, g0 * mult + it, nr, ms * mult, d);
+                    d.flags = (d.flags & ~(u32)TF_SIMPLE) | TF_EPI;
+                    d.lds_out = seg;
+                    for (u32 j = 0; j < r.arity && j < 4; ++j) {
+                        if (d.base[j] >= P.val_off && d.base[j] < P.val_off + P.B * P.d) { d.flags |= TF_SRC_LDS << j; d.lds_src[j] = 0; }
+                        u32 sb = q;
+                        for (u32 mm = 0; mm < m; ++mm) {
+                            const BatchRec &y = T.batches[T.lorder[ct.first + mm]];
+                            const u32 ym = y.B / ct.G;
+                            if (d.base[j] >= y.val_off && d.base[j] < y.val_off + y.B * y.d) {
+                                const u32 prow = (d.base[j] - y.val_off) / y.d;     // = g0 * ym + its place in the group
+                                d.flags |= TF_SRC_LDS << j;
+                                d.lds_src[j] = sb + (prow - g0 * ym) * (y.d / Hs);
+                            }
+                            sb += ym * (y.d / Hs);
+                        }
+                    }
+                }
+                d.pad = Hs | (q << 24);
+                T.tiles_f[x] = d;
             } else if (which == 2 || (which == 0 && !cr.fused)) {
                 const BatchRec r = T.batches[T.lorder[cr.first]];
                 TileDesc d;
@@ -1401,7 +1667,9 @@ int sched_enqueue(ob_ctx *ctx)
     if (!by_depth) ht_size = 1;
     // upper bounds of the three tile lists from sums the host keeps while nodes are added
     // (a node contributes at most one component-wise / reduction tile; MATVEC nodes their GEMM tiles)
-    const size_t cap_f = (size_t)n + (size_t)ctx->sum_mv_d32 + 16;
+    // (a GEMM-headed run repeats up to 31 member descriptors behind every product tile; with at
+    // least 16 rows in the product that is at most twice the product's own bound)
+    const size_t cap_f = (size_t)n + (size_t)ctx->sum_mv_d32 * (ctx->fuse >= 3 ? 2 : 1) + 16;
     const size_t cap_a = (size_t)n + 16;
     const size_t cap_b = (size_t)ctx->sum_mv_k32 + 16;
 #define A(field, type, count)                                               \
@@ -1436,6 +1704,8 @@ int sched_enqueue(ob_ctx *ctx)
     A(T.batch_off, u32, n + 1); A(T.batches, BatchRec, n); A(T.lay, Lay, n); A(T.b_indim, u32, E + 1);
     A(T.val_off, u32, n); A(T.dx_off, u32, n); A(T.opnd_off, u32, E + 1); A(T.dx_gsrc, u32, n);
     A(T.slot_of, u32, n); A(T.label_of, u32, n); A(T.blevel, u32, n);
+    A(T.chain_of_batch, u32, n); A(T.epi_head, u32, n); A(T.epi_tail, u32, n);
+    A(T.epi_map, u32, n); A(T.epi_cnt, u32, n); A(T.epi_chk, u32, n);
     A(T.lorder, u32, n); A(T.chains, ChainRec, n); A(T.clay, CLay, n); A(T.chain_of_lpos, u32, n);
     // a plan has at most one slot per node; twice that leaves room for plans that insert slots
     const size_t slot_cap = 2 * (size_t)n + 4;
@@ -1533,7 +1803,7 @@ int sched_enqueue(ob_ctx *ctx)
     // ---- launch planning: slots, chains, tile descriptors ----
     const int fuse = batched && ctx->fuse;
     if (fuse && E > 0) K(k_bedges, E, T, bset, blist);
-    hipLaunchKernelGGL(k_slots, dim3(1), dim3(SLOT_THREADS), 0, s, T, (fuse && E > 0) ? ctx->fuse : 0, blist);
+    hipLaunchKernelGGL(k_slots, dim3(1), dim3(SLOT_THREADS), 0, s, T, (fuse && E > 0) ? (ctx->fuse > 2 ? 2 : ctx->fuse) : 0, blist);
     ++ctx->n_launch_sched;
     K(k_launch_keys, n, T, ctx->key_a, ctx->val_a, n);
     if (fuse && E > 0) {
@@ -1547,6 +1817,11 @@ int sched_enqueue(ob_ctx *ctx)
     HIP_TRY(ctx, prim_scan_u32(cflag, cflag_excl, n, nullptr, ctx->scratch, s));
     K(k_clay_zero, n, clay_in, n);
     K(k_chain_recs, n, T, agenda || manual, bset, cflag, cflag_excl, clay_in, n);
+    if (fuse && ctx->fuse >= 3 && E > 0) {
+        const size_t max_chains = n < SLOT_MAX_NB + 1 ? n : SLOT_MAX_NB + 1;   // a fused plan has at most that many batches
+        K(k_epi_find, max_chains * 64, T);
+        K(k_epi_apply, max_chains, T, clay_in);
+    }
     HIP_TRY(ctx, prim_scan_clay(clay_in, T.clay, n, clay_total, ctx->scratch, s));
     ctx->n_launch_sched += 2 * scan_launches;
     K(k_slot_init, (size_t)n + 2, T);
