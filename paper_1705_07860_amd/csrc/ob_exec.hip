@@ -1164,8 +1164,10 @@ extern __shared__ __align__(16) float dyn_lds[];   // sized per launch: GEMM red
 
 // LEAN: the launch holds component-wise work only; this instantiation carries no GEMM or
 // reduction code, needs half the registers and keeps twice the waves per CU.
-template <bool LEAN>
-__global__ __launch_bounds__(WG, LEAN ? 6 : 4) void k_fwd_step(u32 work_lo, u32 work_hi, u32 tile_lo, u32 run_len,
+// EPI: the launch may hold GEMM-headed runs; only that instantiation carries their code (it costs
+// registers that the plain GEMM tiles would otherwise pay for with spills).
+template <bool LEAN, bool EPI = false>
+__global__ __launch_bounds__(WG, LEAN ? 6 : (EPI ? 2 : 4)) void k_fwd_step(u32 work_lo, u32 work_hi, u32 tile_lo, u32 run_len,
                                                                 const TileDesc *tiles_f, const WorkRec *works_f, Tables T)
 {
     // the leading arguments arrive in scalar registers with the wave (so the descriptor loads start
@@ -1188,7 +1190,7 @@ __global__ __launch_bounds__(WG, LEAN ? 6 : 4) void k_fwd_step(u32 work_lo, u32 
             __syncthreads();
             stage_descriptors<sizeof(TileDesc) / 4, WG>(tiles_f + wr.first + c0, sdesc, cn);
             __syncthreads();
-            if (!LEAN && (__builtin_amdgcn_readfirstlane(sdesc[0].flags) & TF_EPI)) {
+            if (EPI && (__builtin_amdgcn_readfirstlane(sdesc[0].flags) & TF_EPI)) {
                 // GEMM-headed run (at most RUN_STAGE descriptors, so this is its only stage): the
                 // product tile, one barrier, then the members with no barrier between them
                 epi_run(T, sdesc, cn, lds);
@@ -1374,7 +1376,8 @@ static hipError_t allow_large_dynamic_lds()
 {
     static hipError_t result = [] {
         const int bytes = (int)(CHAIN_LDS_FLOATS * 4);
-        const void *kernels[4] = {(const void *)k_fwd_step<false>, (const void *)k_fwd_step<true>,
+        const void *kernels[5] = {(const void *)k_fwd_step<false>, (const void *)k_fwd_step<true>,
+                                  (const void *)k_fwd_step<false, true>,
                                   (const void *)k_bwd_step<false>, (const void *)k_bwd_step<true>};
         hipError_t e = hipSuccess;
         for (const void *k : kernels)
@@ -1394,9 +1397,12 @@ static int launch_forward_steps(ob_ctx *ctx)
         const SlotRec &r = ctx->slots[st];
         const u32 lo = r.wf, hi = ctx->slots[st + 1].wf;
         if (hi > lo) {
-            if (r.plain)
+            if (r.plain & 1u)
                 hipLaunchKernelGGL(k_fwd_step<true>, dim3(grid_for(hi - lo, GRID_CAP)), dim3(WG), slot_lds_bytes(r, 16), s,
                                    lo, hi, r.tf, slot_run_len_fwd(r), T.tiles_f, T.works_f, T);
+            else if (!(r.plain & 2u))
+                hipLaunchKernelGGL((k_fwd_step<false, true>), dim3(grid_for(hi - lo, GRID_CAP)), dim3(WG),
+                                   slot_lds_bytes(r, FWD_LDS_MIN), s, lo, hi, r.tf, slot_run_len_fwd(r), T.tiles_f, T.works_f, T);
             else
                 hipLaunchKernelGGL(k_fwd_step<false>, dim3(grid_for(hi - lo, GRID_CAP)), dim3(WG),
                                    slot_lds_bytes(r, FWD_LDS_MIN), s, lo, hi, r.tf, slot_run_len_fwd(r), T.tiles_f, T.works_f, T);

@@ -162,8 +162,9 @@ struct WorkRec { u32 first, len; };   // a workgroup runs tiles [first, first + 
 // lds_need: floats of LDS the slot's fused chains use to hand results on (0: none); the step
 // kernels are launched with that much dynamic LDS (and at least their GEMM reduction space), so
 // slots without such chains keep more workgroups resident per CU.
-// plain != 0: every forward work item of the slot is component-wise (no GEMM, reduction or wide-sum
-// tile), so the slot can run the lean instantiation of the forward kernel.
+// plain bit 0: every forward work item of the slot is component-wise (no GEMM, reduction or wide-sum
+// tile), so the slot can run the lean instantiation of the forward kernel; bit 1: the slot holds no
+// GEMM-headed run (cleared: it needs the instantiation that carries the run code).
 // lminf / nlmaxf: the same pair of run lengths over the slot's forward work items alone (a GEMM-headed run has
 // forward items of its own length and leaves the chain it absorbed without forward work).
 struct SlotRec { u32 wf, wa, tb, tf, ta, lmin, nlmax, dx_free, lds_need, plain, lminf, nlmaxf; };

@@ -1137,7 +1137,7 @@ __global__ void k_slot_tables(Tables T, const CLay *clay_ex, const CLay *total)
     if (c == 0 || T.chains[c - 1].slot != s) { S.wf = L.wf; S.wa = L.wa; S.tb = L.tb; S.tf = L.tf; S.ta = L.ta; }
     const BatchRec &hb = T.batches[T.lorder[cr.first]];
     if (hb.op == OP_MATVEC && !(hb.vec4 & TF_G_ALIAS)) S.dx_free = 0;   // this slot's dX tiles need the slot's own pull first
-    if (!cr.fused) S.plain = 0;     // a GEMM, reduction or wide-sum batch runs in this slot
+    if (!cr.fused) atomicAnd(&S.plain, ~1u);     // a GEMM, reduction or wide-sum batch runs in this slot
     if (cr.fused == 2u) {
         u32 need = 0;
         for (u32 m = 0; m < cr.k; ++m) need += chain_region(cr, T.batches[T.lorder[cr.first + m]]);
@@ -1164,6 +1164,7 @@ __global__ void k_slot_tables(Tables T, const CLay *clay_ex, const CLay *total)
             }
             segs += T.epi_map[c] >> 24;   // values fetched from outside the run
             atomicMax(&S.lds_need, (u32)EPI_LDS_BASE + segs * 32u * (32u / q));
+            atomicAnd(&S.plain, ~2u);   // the slot needs the forward kernel that carries the run code
         }
         atomicMin(&S.lminf, lenf);
         atomicMin(&S.nlmaxf, ~lenf);
