@@ -518,6 +518,35 @@ def test_forward_in_many_stages_at_full_size(name, mode, workload_cache):
     c.close()
 
 
+@pytest.mark.parametrize("mode,launch,fuse", [("nobatch", 0, 2), ("agenda", 1, 2), ("depth", 0, 3), ("depth", 0, 0)])
+def test_stages_in_every_mode_and_on_a_forked_context(mode, launch, fuse):
+    """Staged forwards under the other batching modes, under hipGraph launches and the other fusion
+    levels, on a context forked from the one that owns the parameters."""
+    from paper_1705_07860_amd import binding as ob
+    p, g = wl.make("rnn")
+    o = Oracle(g, p, "f64")
+    o.forward()
+    o.backward(g.root)
+    owner = ob.Context(arena_bytes=64 << 20, mode={"nobatch": ob.OB_NOBATCH, "agenda": ob.OB_BYAGENDA, "depth": ob.OB_BYDEPTH}[mode],
+                       launch=launch)
+    owner.set_fusion(fuse)
+    owner.params_create(p)
+    owner.param_grad_zero()
+    c = owner.fork(arena_bytes=128 << 20)
+    cuts = [40, 41, 150, g.n]
+    lo = 0
+    for k, hi in enumerate(cuts):
+        assert c.add_bulk(_graph_part(g, lo, hi)) == lo
+        c.forward(hi - 1)
+        assert c.stats()["n_stages"] == k + 1
+        for v in range(lo, hi, 7):
+            assert rel_err(c.value_read(v, int(g.out_dim[v])), o.value(v)) <= TOL
+        lo = hi
+    check_against_oracle(c, p, g, o, g.root, what=f"stages {mode} launch {launch} fuse {fuse}")
+    c.close()
+    owner.close()
+
+
 def test_graph_grown_node_by_node_and_a_full_arena():
     """The pattern of a model that looks at a value before it decides what to add (Section 3.1): a
     graph grown in many small steps, a forward after each.  With an arena too small to stack all
