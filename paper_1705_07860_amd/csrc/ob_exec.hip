@@ -1225,6 +1225,7 @@ __global__ __launch_bounds__(BWD_THREADS, LEAN ? 5 : 4) void k_bwd_step(u32 work
     __shared__ __align__(16) PullDesc sdesc[RUN_STAGE];
     const u32 lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const u32 n_dx = dx_hi - dx_lo, n_items = n_dx + (work_hi - work_lo);
+    float sink = 0.f;   // keeps the early requests of a run alive; never stored
     for (u32 item = blockIdx.x; item < n_items; item += gridDim.x) {
         if (!LEAN && item < n_dx) {
             const TileDesc d = tiles_b[dx_lo + item];
@@ -1246,6 +1247,20 @@ __global__ __launch_bounds__(BWD_THREADS, LEAN ? 5 : 4) void k_bwd_step(u32 work
             stage_descriptors<sizeof(PullDesc) / 4, BWD_THREADS>(tiles_a + wr.first + c0, sdesc, cn);
             __syncthreads();
             const bool heavy = __ballot(lane < cn && (sdesc[lane < cn ? lane : 0].lflags & TF_GLOBAL_DEP)) != 0ull;
+            // Every level of the run reads forward values (and gradients from outside the run) that
+            // no level before it touches: ask for all of them now, one lane per 128-byte line, so the
+            // levels find them in the cache instead of each waiting for memory in turn.
+            for (u32 x = threadIdx.x; x < cn * 32u; x += BWD_THREADS) {
+                const PullDesc &pd = sdesc[x >> 5];
+                const u32 j = (x >> 3) & 3u, el = (x & 7u) * 32u;
+                if (pd.n_uni != PULL_GENERIC && j < pd.n_uni && el < pd.nrows * pd.d) {
+                    const UEdge ue = pd.e[j];
+                    const u32 dr = el / pd.d, col = el % pd.d;
+                    if (ue.kind == EK_MUL || ue.kind == EK_DTANH || ue.kind == EK_DSIGM) sink += T.V[ue.voff + dr * ue.vs + col];
+                    if (!(pd.lflags & (TF_SRC_LDS << j)) && (ue.kind == EK_PLAIN || ue.kind == EK_MUL || ue.kind == EK_DTANH || ue.kind == EK_DSIGM))
+                        sink += T.G[ue.goff + dr * ue.gs + col];
+                }
+            }
             u32 i = 0;
             while (i < cn) {
                 u32 glen = __builtin_amdgcn_readfirstlane(sdesc[i].grp_len);
@@ -1259,6 +1274,7 @@ __global__ __launch_bounds__(BWD_THREADS, LEAN ? 5 : 4) void k_bwd_step(u32 work
         }
         __syncthreads();
     }
+    if (sink != sink && work_lo == 0xffffffffu) T.G[0] = sink;   // (no launch has this range)
 }
 
 __global__ void k_set_root(Tables T) { T.root_pos[0] = T.pos_of[T.root]; }
