@@ -56,18 +56,15 @@ def part(G, lo: int, hi: int):
                     payload=G.payload, root=hi - 1)
 
 
-def main():
-    ap = argparse.ArgumentParser(description=__doc__, formatter_class=argparse.RawDescriptionHelpFormatter)
-    ap.add_argument("--chains", type=int, default=64)
-    ap.add_argument("--steps", type=int, default=40)
-    ap.add_argument("--repeats", type=int, default=3)
-    args = ap.parse_args()
+def run_all(chains: int, steps: int, repeats: int, arena_bytes: int = 6 << 30, report=print, **sizes):
+    """Runs the three ways `repeats` times on one context; returns [(kind, forward s, total s, loss)]."""
     import torch
-    p, G, bounds = build(args.chains, args.steps)
+    p, G, bounds = build(chains, steps, **sizes)
     parts = [part(G, bounds[k], bounds[k + 1]) for k in range(len(bounds) - 1)]
-    print(f"{G.n} nodes, grown in {len(parts)} pieces")
-    c = ob.Context(arena_bytes=6 << 30)
+    report(f"{G.n} nodes, grown in {len(parts)} pieces")
+    c = ob.Context(arena_bytes=arena_bytes)
     c.params_create(p)
+    results = []
 
     def run(kind):
         c.graph_new()
@@ -94,12 +91,22 @@ def main():
         c.sync()
         return t_f, time.perf_counter() - t0, loss, per
 
-    for kind in ["oneshot", "stages", "again"] * args.repeats:
+    for kind in ["oneshot", "stages", "again"] * repeats:
         t_f, t_all, loss, per = run(kind)
-        steps = f"; per piece: median {np.median(per) * 1e3:.2f} ms, last step {per[-2] * 1e3:.2f} ms" if per else ""
-        print(f"{kind:8s} forward phase {t_f * 1e3:8.2f} ms, with backward {t_all * 1e3:8.2f} ms, loss {loss:.4f}{steps}",
-              flush=True)
+        pieces = f"; per piece: median {np.median(per) * 1e3:.2f} ms, last step {per[-2] * 1e3:.2f} ms" if per else ""
+        report(f"{kind:8s} forward phase {t_f * 1e3:8.2f} ms, with backward {t_all * 1e3:8.2f} ms, loss {loss:.4f}{pieces}")
+        results.append((kind, t_f, t_all, loss))
     c.close()
+    return results
+
+
+def main():
+    ap = argparse.ArgumentParser(description=__doc__, formatter_class=argparse.RawDescriptionHelpFormatter)
+    ap.add_argument("--chains", type=int, default=64)
+    ap.add_argument("--steps", type=int, default=40)
+    ap.add_argument("--repeats", type=int, default=3)
+    args = ap.parse_args()
+    run_all(args.chains, args.steps, args.repeats, report=lambda m: print(m, flush=True))
 
 
 if __name__ == "__main__":

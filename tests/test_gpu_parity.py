@@ -547,6 +547,17 @@ def test_stages_in_every_mode_and_on_a_forked_context(mode, launch, fuse):
     owner.close()
 
 
+def test_growing_graph_demo_agrees_with_itself():
+    """The runnable demo at a small size: growing the graph in stages, evaluating the prefix again
+    every time and one forward of the finished graph give the same loss."""
+    from paper_1705_07860_amd import grow_demo
+    res = grow_demo.run_all(chains=5, steps=4, repeats=2, arena_bytes=256 << 20, report=say, hidden=32, emb=16, classes=7)
+    losses = {kind: loss for kind, _, _, loss in res}
+    assert set(losses) == {"oneshot", "stages", "again"}
+    ref = losses["oneshot"]
+    assert all(abs(v - ref) <= 1e-5 * abs(ref) for v in losses.values())
+
+
 def test_graph_grown_node_by_node_and_a_full_arena():
     """The pattern of a model that looks at a value before it decides what to add (Section 3.1): a
     graph grown in many small steps, a forward after each.  With an arena too small to stack all
