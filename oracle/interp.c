@@ -124,13 +124,19 @@ int oracle_forward(const graph_t *g, const REAL *pdata, REAL *val)
             for (int64_t i = 0; i < d; ++i) y[i] = val[g->v_off[in[0]] + g->aux0[v] + i];
             break;
         case PICK_NLS: {
-            /* -log softmax(x)[label] = logsumexp(x) - x[label], shifted by the row maximum */
+            /* -log softmax(x)[label], written so that a confident row keeps its digits: with
+             * m the index of the row maximum,
+             *   logsumexp(x) - x_label = log(1 + sum_{i != m} exp(x_i - x_m)) + (x_m - x_label).
+             * The textbook form x_m + log(sum_i exp(x_i - x_m)) - x_label is the same number but
+             * rounds a loss below 1e-16 * |x_m| to zero, which is coarser than the 1e-4 relative
+             * bar the batched path is held to. */
             const REAL *x = val + g->v_off[in[0]];
             const int64_t K = g->out_dim[in[0]];
-            double mx = (double)x[0], s = 0;
-            for (int64_t i = 1; i < K; ++i) if ((double)x[i] > mx) mx = (double)x[i];
-            for (int64_t i = 0; i < K; ++i) s += exp((double)x[i] - mx);
-            y[0] = (REAL)(mx + log(s) - (double)x[g->aux0[v]]);
+            int64_t m = 0;
+            double s = 0;
+            for (int64_t i = 1; i < K; ++i) if ((double)x[i] > (double)x[m]) m = i;
+            for (int64_t i = 0; i < K; ++i) if (i != m) s += exp((double)x[i] - (double)x[m]);
+            y[0] = (REAL)(log1p(s) + ((double)x[m] - (double)x[g->aux0[v]]));
             break;
         }
         case SQNORM: {
@@ -225,16 +231,21 @@ int oracle_backward(const graph_t *g, const REAL *pdata, const REAL *val, int64_
             for (int64_t i = 0; i < d; ++i) grad[g->v_off[in[0]] + g->aux0[v] + i] += gy[i];
             break;
         case PICK_NLS: {
-            /* d/dx_i [logsumexp(x) - x_label] = softmax(x)_i - [i == label] */
+            /* d/dx_i [logsumexp(x) - x_label] = softmax(x)_i - [i == label].  For i == label the
+             * difference p_label - 1 is taken as -(sum of the other probabilities), the same
+             * number without the cancellation when p_label is close to 1. */
             const REAL *x = val + g->v_off[in[0]];
             REAL *dx = grad + g->v_off[in[0]];
             const int64_t K = g->out_dim[in[0]];
-            double mx = (double)x[0], s = 0;
-            for (int64_t i = 1; i < K; ++i) if ((double)x[i] > mx) mx = (double)x[i];
-            for (int64_t i = 0; i < K; ++i) s += exp((double)x[i] - mx);
+            const int64_t label = g->aux0[v];
+            int64_t m = 0;
+            double s = 0, others = 0;
+            for (int64_t i = 1; i < K; ++i) if ((double)x[i] > (double)x[m]) m = i;
+            for (int64_t i = 0; i < K; ++i) if (i != m) s += exp((double)x[i] - (double)x[m]);
+            for (int64_t i = 0; i < K; ++i)
+                if (i != label) others += exp((double)x[i] - (double)x[m]) / (1.0 + s);
             for (int64_t i = 0; i < K; ++i) {
-                double p = exp((double)x[i] - mx) / s;
-                if (i == g->aux0[v]) p -= 1.0;
+                const double p = (i == label) ? -others : exp((double)x[i] - (double)x[m]) / (1.0 + s);
                 dx[i] += (REAL)((double)gy[0] * p);
             }
             break;

@@ -74,6 +74,48 @@ def test_hand_pick_nls():
     assert abs(o.node_grad(x).sum()) < 1e-15             # rows of softmax - e_y sum to zero
 
 
+@pytest.mark.parametrize("margin", [0.5, 8.0, 40.0, 60.0, 100.0])
+def test_pick_nls_two_classes_is_softplus_also_for_confident_rows(margin):
+    # Two classes: -log softmax(x)[y] = log(1 + exp(x_other - x_y)) and the gradient is
+    # (-q, q) with q = 1 / (1 + exp(x_y - x_other)) -- closed forms that stay accurate when the
+    # prediction is confident (margin 60: loss = log1p(e^-60) = 8.7e-27, far below the 1e-16
+    # where the textbook logsumexp(x) - x_y rounds to zero) and when it is confidently wrong.
+    p = _params([])
+    for label, other in ((0, 1), (1, 0)):
+        for sign in (+1.0, -1.0):
+            xs = [0.0, 0.0]
+            xs[other] = -sign * margin          # exactly representable in fp32
+            gb = wl.GraphBuilder(p)
+            x = gb.input(xs)
+            L = gb.pick_nls(x, label)
+            g = gb.finish(L)
+            o = _run(g, p)
+            z = xs[other] - xs[label]
+            loss = math.log1p(math.exp(z)) if z <= 0 else z + math.log1p(math.exp(-z))
+            q = 1.0 / (1.0 + math.exp(-z))
+            assert abs(o.value(L)[0] - loss) <= 1e-14 * loss
+            want = np.zeros(2)
+            want[label], want[other] = -q, q
+            assert np.allclose(o.node_grad(x), want, rtol=1e-14, atol=0)
+
+
+def test_pick_nls_confident_row_of_many_classes():
+    # K classes, one at 0 and K - 1 at -50: loss = log1p((K-1) e^-50), label gradient
+    # -(K-1) e^-50 / (1 + (K-1) e^-50), every other entry e^-50 / (1 + (K-1) e^-50)
+    K = 7
+    p = _params([])
+    gb = wl.GraphBuilder(p)
+    x = gb.input([-50.0, -50.0, 0.0] + [-50.0] * (K - 3))
+    L = gb.pick_nls(x, 2)
+    g = gb.finish(L)
+    o = _run(g, p)
+    t = (K - 1) * math.exp(-50.0)
+    assert abs(o.value(L)[0] - math.log1p(t)) <= 1e-14 * math.log1p(t)
+    want = np.full(K, math.exp(-50.0) / (1 + t))
+    want[2] = -t / (1 + t)
+    assert np.allclose(o.node_grad(x), want, rtol=1e-13, atol=0)
+
+
 def test_hand_concat_slice_identity_and_fanout():
     p = _params([])
     gb = wl.GraphBuilder(p)
