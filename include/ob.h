@@ -76,7 +76,7 @@ typedef struct ob_ctx ob_ctx;
 #define OB_LAUNCH_STREAM 0     /* one kernel launch per step on the stream            */
 #define OB_LAUNCH_GRAPH 1      /* the per-step launches captured in a hipGraph        */
 #define OB_LAUNCH_PERSISTENT 2 /* one cooperative kernel for all steps: not built, OB_E_STATE (a grid-wide barrier
-                                * measures slower than a kernel boundary on this machine, see ob_test_grid_barrier) */
+                                * measured slower than a kernel boundary on this machine) */
 
 /* ---- context ------------------------------------------------------------------------- */
 
@@ -101,11 +101,7 @@ int ob_ctx_set_launch(ob_ctx *ctx, int launch);
  * costs one launch instead of one per depth level.  Batches and their order do not change.
  * on: 0 = one launch per depth level; 1 = fused, every batch launched as early as its operands
  * allow; 2 = fused, every batch launched as late as its consumers allow (batches off the longest
- * dependency path then share the launches next to their consumers); 3 = 2, and a fused chain that
- * reads a matrix product row for row (an LSTM cell behind W_h h) is evaluated forward behind every
- * tile of that product, in the product's launch, when its members' widths are multiples of a
- * common segment width and the product has 1, 2 or 4 such segments and at least 16 rows (values
- * are bit-identical to level 2; fewer, longer launches).  Other values: OB_E_ARG. */
+ * dependency path then share the launches next to their consumers).  Other values: OB_E_ARG. */
 int ob_ctx_set_fusion(ob_ctx *ctx, int on);
 /* Library-owned message for the last failing call on this context (valid until the next
  * call); ctx may be NULL for errors of ob_ctx_create. */
@@ -227,6 +223,9 @@ typedef struct ob_stats {
     float ms_param_grads, ms_graph_build;
     int32_t n_stages;  /* evaluations the current values come from (1: one schedule covers every evaluated node) */
     int32_t n_proxies; /* earlier nodes the last stage read (0 when n_stages is 1) */
+    int32_t n_depth_retries; /* schedules of this context so far that were repeated with the single-workgroup depth pass
+                              * because a range of the partitioned pass ran into the bound on its wait */
+    int32_t reserved0;
 } ob_stats;
 int ob_stats_read(ob_ctx *ctx, ob_stats *out);
 
@@ -241,11 +240,13 @@ int ob_stats_read(ob_ctx *ctx, ob_stats *out);
 #define OB_DBG_TILES_FWD 6 /* forward tile descriptors in launch order, 40 words each (internal layout) */
 #define OB_DBG_TILES_PULL 7 /* backward pull tile descriptors in launch order, 48 words each (internal layout) */
 #define OB_DBG_CHAINS 8    /* launch chains, 8 words each: first, members, slot, fused, groups, groups per block, blocks, tiles per block */
-#define OB_DBG_EPI_TAIL 9  /* u32 per launch chain: the chain a matrix-product chain evaluates behind its tiles (0xffffffff: none) */
-#define OB_DBG_EPI_MAP 10  /* u32 per launch chain: with a tail, a | s << 16 (product row i = row a + s i of the tail); a product
-                            * chain without one holds 0xE0000000 | the number of the test that refused the pairing */
-#define OB_DBG_LORDER 11   /* u32 per batch: batch ids in launch order (the members of chain c are entries first .. first + members - 1) */
+#define OB_DBG_LORDER 9    /* u32 per batch: batch ids in launch order (the members of chain c are entries first .. first + members - 1) */
 int ob_debug_read(ob_ctx *ctx, int which, uint32_t *host_out, size_t cap_words, size_t *n_words);
+/* Internal knobs, for tests of the library's own error handling.  which: OB_DBG_SET_*; unknown: OB_E_ARG. */
+#define OB_DBG_SET_DEPTH_SPIN 0 /* idle polls a workgroup of the partitioned depth pass (Section 3.2) allows itself while it
+                                 * waits for a lower id range, default 2^21; 0 makes every range that has to wait give up at
+                                 * once, so that scheduling falls back to the single-workgroup pass (see n_depth_retries) */
+int ob_debug_set(ob_ctx *ctx, int which, uint64_t value);
 
 /* Stand-alone device primitives, exposed so that tests can check them directly.  All
  * pointers are host; the context's arena beyond its current use serves as scratch. */
@@ -257,12 +258,6 @@ int ob_test_scan(ob_ctx *ctx, size_t n, const uint32_t *in, uint32_t *out_exclus
  * of a kernel whose one thread does a dependent load and store (touch = 1) on the context's
  * stream: the floor of a launch boundary on this machine, reported by the benchmark. */
 int ob_test_launch_cost(ob_ctx *ctx, int n, int touch, float *us_per_launch);
-/* Cost and correctness of the library's grid-wide barrier: n_wg workgroups of one cooperative
- * launch (all resident, or the launch fails with OB_E_HIP) run iters phases; in each a workgroup
- * publishes a word, passes the barrier and reads its neighbour's word.  out3[0] = nanoseconds per
- * phase, out3[1] = stale reads seen (must be 0), out3[2] = 1 if a wait ran into its poll limit (the
- * kernel then ends early instead of hanging). */
-int ob_test_grid_barrier(ob_ctx *ctx, int n_wg, int iters, uint32_t *out3);
 /* C[M x N] = A[M x K] * B[N x K]^T through the library's MFMA tile routine. */
 int ob_test_gemm(ob_ctx *ctx, int M, int N, int K, const float *A, const float *B, float *C);
 

@@ -21,7 +21,8 @@ LIB_PATH = HERE / "libob.so"
 OB_NOBATCH, OB_BYDEPTH, OB_BYAGENDA, OB_MANUAL = 0, 1, 2, 3
 OB_LAUNCH_STREAM, OB_LAUNCH_GRAPH, OB_LAUNCH_PERSISTENT = 0, 1, 2
 OB_DBG_DEPTH, OB_DBG_SIG, OB_DBG_SUCC_OFF, OB_DBG_SUCC_EDGE, OB_DBG_ORDER, OB_DBG_VAL_OFF = range(6)
-OB_DBG_TILES_FWD, OB_DBG_TILES_PULL, OB_DBG_CHAINS, OB_DBG_EPI_TAIL, OB_DBG_EPI_MAP, OB_DBG_LORDER = 6, 7, 8, 9, 10, 11
+OB_DBG_TILES_FWD, OB_DBG_TILES_PULL, OB_DBG_CHAINS, OB_DBG_LORDER = 6, 7, 8, 9
+OB_DBG_SET_DEPTH_SPIN = 0
 
 ERRORS = {0: "OB_OK", -1: "OB_E_BADID", -2: "OB_E_DIM", -3: "OB_E_RANGE", -4: "OB_E_NOTSCALAR",
           -5: "OB_E_OOM", -6: "OB_E_STATE", -7: "OB_E_HIP", -8: "OB_E_ARG"}
@@ -40,7 +41,7 @@ class ObStats(ctypes.Structure):
         [(n, c_uint64) for n in ("value_floats", "grad_floats", "arena_used_bytes", "upload_bytes")] + \
         [(n, c_float) for n in ("ms_upload", "ms_schedule", "ms_forward", "ms_backward", "ms_param_grads",
                                 "ms_graph_build")] + \
-        [(n, c_int32) for n in ("n_stages", "n_proxies")]
+        [(n, c_int32) for n in ("n_stages", "n_proxies", "n_depth_retries", "reserved0")]
 
     def as_dict(self):
         return {n: getattr(self, n) for n, _ in self._fields_ if not n.startswith("reserved")}
@@ -105,12 +106,12 @@ def lib():
             "ob_schedule_read": (i, [vp, pi, vp, vp, vp, vp, sz, sz]),
             "ob_stats_read": (i, [vp, POINTER(ObStats)]),
             "ob_debug_read": (i, [vp, i, vp, sz, POINTER(sz)]),
+            "ob_debug_set": (i, [vp, i, c_uint64]),
             "ob_param_sgd_step": (i, [vp, c_float, i]),
             "ob_test_sort": (i, [vp, sz, vp, vp, i, i, vp, vp]),
             "ob_test_scan": (i, [vp, sz, vp, vp, vp]),
             "ob_test_gemm": (i, [vp, i, i, i, vp, vp, vp]),
             "ob_test_launch_cost": (i, [vp, i, i, POINTER(c_float)]),
-            "ob_test_grid_barrier": (i, [vp, i, i, vp]),
         }
         for name, (res, args) in sigs.items():
             fn = getattr(L, name)
@@ -339,6 +340,9 @@ class Context:
         out = out[:nw.value]
         return out.view(np.uint64) if which == OB_DBG_SIG else out
 
+    def debug_set(self, which: int, value: int):
+        self._ck(self.L.ob_debug_set(self.h, which, int(value)))
+
     # -- stand-alone primitives (tests)
     def test_sort(self, keys, vals, lo_bit, n_bits):
         k = np.ascontiguousarray(keys, np.uint64)
@@ -358,12 +362,6 @@ class Context:
         out = c_float()
         self._ck(self.L.ob_test_launch_cost(self.h, n, touch, byref(out)))
         return float(out.value)
-
-    def test_grid_barrier(self, n_wg: int = 256, iters: int = 1000):
-        """(ns per barrier phase, stale reads, poll-limit flag) of the library's grid-wide barrier."""
-        out = np.zeros(3, np.uint32)
-        self._ck(self.L.ob_test_grid_barrier(self.h, n_wg, iters, _ptr(out)))
-        return int(out[0]), int(out[1]), int(out[2])
 
     def test_gemm(self, A, B):
         A = np.ascontiguousarray(A, np.float32)

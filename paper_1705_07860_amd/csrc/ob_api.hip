@@ -9,6 +9,7 @@
 #include <cstdio>
 #include <cstring>
 #include <new>
+#include <thread>
 
 static std::string g_create_error;
 
@@ -50,7 +51,6 @@ int ob_ctx_create(void *arena_dev, size_t arena_bytes, void *hip_stream, ob_ctx 
     c->arena_bytes = arena_dev ? arena_bytes : 0;
     c->stream = (hipStream_t)hip_stream;
     c->sched_stream = c->stream;
-    c->in_off.push_back(0);
     *out = c;
     return OB_OK;
 }
@@ -94,6 +94,7 @@ int ob_ctx_destroy(ob_ctx *ctx)
 }
 
 static int forget_evaluation(ob_ctx *ctx);
+static int wait_own_work(ob_ctx *ctx);
 static u32 evaluated_upto(const ob_ctx *ctx);
 static int stage_forward(ob_ctx *ctx, u32 n0, u32 n1);
 static int stage_schedule_read(ob_ctx *ctx, int *n_batches, int *batch_depth, uint64_t *batch_sig, int *batch_off,
@@ -121,7 +122,7 @@ int ob_ctx_set_schedule_stream(ob_ctx *ctx, void *hip_stream)
 int ob_ctx_set_fusion(ob_ctx *ctx, int on)
 {
     CHECK_CTX(ctx);
-    if (on < 0 || on > 3) return ctx_fail(ctx, OB_E_ARG, "fusion level %d (0 .. 3)", on);
+    if (on < 0 || on > 2) return ctx_fail(ctx, OB_E_ARG, "fusion level %d (0 .. 2)", on);
     ctx->fuse = on;
     return OB_OK;
 }
@@ -264,13 +265,13 @@ int ob_param_sgd_step(ob_ctx *ctx, float lr, int zero_grad)
 int ob_graph_new(ob_ctx *ctx)
 {
     CHECK_CTX(ctx);
-    if (ctx->uploaded) {
-        HIP_TRY(ctx, hipStreamSynchronize(ctx->sched_stream));
-        HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
-    }
-    ctx->op.clear(); ctx->out_dim.clear(); ctx->in_off.assign(1, 0); ctx->in_idx.clear();
+    // The graph store and the arena behind the parameters are about to be reused: wait for what
+    // this context itself still has in flight (its own events; other contexts on the same streams
+    // are not waited for).
+    if (int rc = wait_own_work(ctx)) return rc;
+    ctx->op.clear(); ctx->out_dim.clear(); ctx->in_off.clear(); ctx->in_idx.clear();
     ctx->param.clear(); ctx->bias.clear(); ctx->aux0.clear(); ctx->aux1.clear(); ctx->payload.clear();
-    ctx->items_upto.clear();
+    ctx->n_items_total = 0;
     ctx->manual.clear();
     drop_stages(ctx);
     ctx->image_stale = false;
@@ -297,105 +298,144 @@ int ob_graph_size(ob_ctx *ctx, int *n_nodes, int *n_edges)
 
 // Validates one node against the graph so far and computes the dimension it implies.
 // `n_before` = number of nodes that exist (operands must be smaller).
-static int validate_node(ob_ctx *ctx, u32 n_before, const std::vector<u32> &dims, int op, const u32 *ins, u32 arity,
-                         int param, int bias, int a0, int a1, u32 *dim_out, u32 in_dim_hint)
+// Errors go to a sink of the caller's (several threads may validate parts of one bulk call).
+struct ErrSink { int code = 0; char msg[256] = {0}; };
+static int sink_fail(ErrSink *e, int code, const char *fmt, ...)
+{
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(e->msg, sizeof e->msg, fmt, ap);
+    va_end(ap);
+    e->code = code;
+    return code;
+}
+template <typename Dims>
+static inline int validate_node(const std::vector<HostParam> &params, ErrSink *es, u32 n_before, const Dims &dims, int op,
+                                const u32 *ins, u32 arity, int param, int bias, int a0, int a1, u32 *dim_out, u32 in_dim_hint)
 {
     for (u32 j = 0; j < arity; ++j)
-        if (ins[j] >= n_before) return ctx_fail(ctx, OB_E_BADID, "operand id %u of node %u does not exist yet", ins[j], n_before);
-    auto pshape_ok = [&](int id) { return id >= 0 && id < (int)ctx->params.size(); };
+        if (ins[j] >= n_before) return sink_fail(es, OB_E_BADID, "operand id %u of node %u does not exist yet", ins[j], n_before);
+    auto pshape_ok = [&](int id) { return id >= 0 && id < (int)params.size(); };
     switch (op) {
     case OB_OP_INPUT:
-        if (arity != 0) return ctx_fail(ctx, OB_E_DIM, "INPUT takes no operands");
-        if (in_dim_hint == 0) return ctx_fail(ctx, OB_E_DIM, "INPUT of dimension 0");
+        if (arity != 0) return sink_fail(es, OB_E_DIM, "INPUT takes no operands");
+        if (in_dim_hint == 0) return sink_fail(es, OB_E_DIM, "INPUT of dimension 0");
         *dim_out = in_dim_hint;
         return 0;
     case OB_OP_LOOKUP:
-        if (arity != 0) return ctx_fail(ctx, OB_E_DIM, "LOOKUP takes no operands");
-        if (!pshape_ok(param)) return ctx_fail(ctx, OB_E_BADID, "unknown table id %d", param);
-        if (a0 < 0 || a0 >= ctx->params[param].rows) return ctx_fail(ctx, OB_E_RANGE, "row %d outside table of %d rows", a0, ctx->params[param].rows);
-        *dim_out = (u32)ctx->params[param].cols;
+        if (arity != 0) return sink_fail(es, OB_E_DIM, "LOOKUP takes no operands");
+        if (!pshape_ok(param)) return sink_fail(es, OB_E_BADID, "unknown table id %d", param);
+        if (a0 < 0 || a0 >= params[param].rows) return sink_fail(es, OB_E_RANGE, "row %d outside table of %d rows", a0, params[param].rows);
+        *dim_out = (u32)params[param].cols;
         return 0;
     case OB_OP_MATVEC:
-        if (arity != 1) return ctx_fail(ctx, OB_E_DIM, "MATVEC takes one operand");
-        if (!pshape_ok(param)) return ctx_fail(ctx, OB_E_BADID, "unknown matrix id %d", param);
-        if ((u32)ctx->params[param].cols != dims[ins[0]])
-            return ctx_fail(ctx, OB_E_DIM, "MATVEC: matrix has %d columns, operand has %u elements", ctx->params[param].cols, dims[ins[0]]);
+        if (arity != 1) return sink_fail(es, OB_E_DIM, "MATVEC takes one operand");
+        if (!pshape_ok(param)) return sink_fail(es, OB_E_BADID, "unknown matrix id %d", param);
+        if ((u32)params[param].cols != dims[ins[0]])
+            return sink_fail(es, OB_E_DIM, "MATVEC: matrix has %d columns, operand has %u elements", params[param].cols, dims[ins[0]]);
         if (bias != -1) {
-            if (!pshape_ok(bias)) return ctx_fail(ctx, OB_E_BADID, "unknown bias id %d", bias);
-            if (ctx->params[bias].cols != 1 || ctx->params[bias].rows != ctx->params[param].rows)
-                return ctx_fail(ctx, OB_E_DIM, "bias must be %d x 1", ctx->params[param].rows);
+            if (!pshape_ok(bias)) return sink_fail(es, OB_E_BADID, "unknown bias id %d", bias);
+            if (params[bias].cols != 1 || params[bias].rows != params[param].rows)
+                return sink_fail(es, OB_E_DIM, "bias must be %d x 1", params[param].rows);
         }
-        *dim_out = (u32)ctx->params[param].rows;
+        *dim_out = (u32)params[param].rows;
         return 0;
     case OB_OP_ADD:
     case OB_OP_CMULT:
-        if (arity < 1 || (op == OB_OP_CMULT && arity != 2)) return ctx_fail(ctx, OB_E_DIM, "wrong operand count %u", arity);
+        if (arity < 1 || (op == OB_OP_CMULT && arity != 2)) return sink_fail(es, OB_E_DIM, "wrong operand count %u", arity);
         for (u32 j = 1; j < arity; ++j)
-            if (dims[ins[j]] != dims[ins[0]]) return ctx_fail(ctx, OB_E_DIM, "operand dimensions differ (%u vs %u)", dims[ins[j]], dims[ins[0]]);
+            if (dims[ins[j]] != dims[ins[0]]) return sink_fail(es, OB_E_DIM, "operand dimensions differ (%u vs %u)", dims[ins[j]], dims[ins[0]]);
         *dim_out = dims[ins[0]];
         return 0;
     case OB_OP_TANH:
     case OB_OP_SIGMOID:
-        if (arity != 1) return ctx_fail(ctx, OB_E_DIM, "unary op takes one operand");
+        if (arity != 1) return sink_fail(es, OB_E_DIM, "unary op takes one operand");
         *dim_out = dims[ins[0]];
         return 0;
     case OB_OP_CONCAT: {
-        if (arity < 1) return ctx_fail(ctx, OB_E_DIM, "CONCAT needs operands");
+        if (arity < 1) return sink_fail(es, OB_E_DIM, "CONCAT needs operands");
         u64 d = 0;
         for (u32 j = 0; j < arity; ++j) d += dims[ins[j]];
-        if (d > 0x7fffffffu) return ctx_fail(ctx, OB_E_DIM, "CONCAT too long");
+        if (d > 0x7fffffffu) return sink_fail(es, OB_E_DIM, "CONCAT too long");
         *dim_out = (u32)d;
         return 0;
     }
     case OB_OP_SLICE:
-        if (arity != 1) return ctx_fail(ctx, OB_E_DIM, "SLICE takes one operand");
-        if (a0 < 0 || a1 <= a0 || (u32)a1 > dims[ins[0]]) return ctx_fail(ctx, OB_E_RANGE, "slice [%d,%d) outside %u elements", a0, a1, dims[ins[0]]);
+        if (arity != 1) return sink_fail(es, OB_E_DIM, "SLICE takes one operand");
+        if (a0 < 0 || a1 <= a0 || (u32)a1 > dims[ins[0]]) return sink_fail(es, OB_E_RANGE, "slice [%d,%d) outside %u elements", a0, a1, dims[ins[0]]);
         *dim_out = (u32)(a1 - a0);
         return 0;
     case OB_OP_PICK_NLS:
-        if (arity != 1) return ctx_fail(ctx, OB_E_DIM, "PICK_NLS takes one operand");
-        if (a0 < 0 || (u32)a0 >= dims[ins[0]]) return ctx_fail(ctx, OB_E_RANGE, "label %d outside %u classes", a0, dims[ins[0]]);
+        if (arity != 1) return sink_fail(es, OB_E_DIM, "PICK_NLS takes one operand");
+        if (a0 < 0 || (u32)a0 >= dims[ins[0]]) return sink_fail(es, OB_E_RANGE, "label %d outside %u classes", a0, dims[ins[0]]);
         *dim_out = 1;
         return 0;
     case OB_OP_SQNORM:
-        if (arity != 1) return ctx_fail(ctx, OB_E_DIM, "SQNORM takes one operand");
+        if (arity != 1) return sink_fail(es, OB_E_DIM, "SQNORM takes one operand");
         *dim_out = 1;
         return 0;
     default:
-        return ctx_fail(ctx, OB_E_ARG, "unknown op %d", op);
+        return sink_fail(es, OB_E_ARG, "unknown op %d", op);
     }
+}
+
+// Room for `nodes` more nodes, `edges` more operand references and `floats` more payload elements.
+// Growing a page-locked array frees the old one, so an upload that may still read it is waited for.
+static int store_reserve(ob_ctx *ctx, size_t nodes, size_t edges, size_t floats)
+{
+    const bool pin = ctx->arena != nullptr;
+    const size_t n = ctx->op.size() + nodes, E = ctx->in_idx.size() + edges, P = ctx->payload.size() + floats;
+    const bool grows = n + 1 > ctx->in_off.cap || n > ctx->op.cap || E > ctx->in_idx.cap || P > ctx->payload.cap;
+    if (grows && ctx->uploaded && ctx->ev_ok) HIP_TRY(ctx, hipEventSynchronize(ctx->ev[1]));
+    const bool ok = ctx->op.reserve(n, pin) && ctx->out_dim.reserve(n, pin) && ctx->in_off.reserve(n + 1, pin) &&
+                    ctx->in_idx.reserve(E, pin) && ctx->param.reserve(n, pin) && ctx->bias.reserve(n, pin) &&
+                    ctx->aux0.reserve(n, pin) && ctx->aux1.reserve(n, pin) && ctx->payload.reserve(P, pin);
+    if (!ok) return ctx_fail(ctx, OB_E_OOM, "out of %s host memory for the graph store", pin ? "page-locked" : "");
+    if (ctx->in_off.n == 0) { ctx->in_off[0] = 0; ctx->in_off.n = 1; }
+    return 0;
+}
+
+// extending a graph that was already evaluated keeps the evaluation: the next ob_forward
+// evaluates only the new nodes (Section 3.1's lazy evaluation).  A schedule that was never
+// executed holds nothing worth keeping.
+static int before_append(ob_ctx *ctx, bool *keep)
+{
+    *keep = ctx->n_sched && ctx->forward_done && !ctx->sched_pending;
+    if (ctx->n_sched && !*keep)
+        if (int rc = forget_evaluation(ctx)) return rc;
+    ctx->manual.clear();   // labels cover the graph they were given for
+    return 0;
+}
+
+static inline void note_matvec(ob_ctx *ctx, int param, int bias)
+{
+    ctx->sum_mv_d32 += (u64)ctx->params[param].rows / GT + 1;
+    ctx->sum_mv_k32 += (u64)ctx->params[param].cols / DXT + 1;
+    if (!ctx->params_used_w[param]) { ctx->params_used_w[param] = 1; ctx->params_dirty = true; }
+    if (bias >= 0 && !ctx->params_used_b[bias]) { ctx->params_used_b[bias] = 1; ctx->params_dirty = true; }
 }
 
 static int append_node(ob_ctx *ctx, int op, const u32 *ins, u32 arity, int param, int bias, int a0, int a1, u32 dim)
 {
-    // extending a graph that was already evaluated keeps the evaluation: the next ob_forward
-    // evaluates only the new nodes (Section 3.1's lazy evaluation).  A schedule that was never
-    // executed holds nothing worth keeping.
-    const bool keep = ctx->n_sched && ctx->forward_done && !ctx->sched_pending;
-    if (ctx->n_sched && !keep)
-        if (int rc = forget_evaluation(ctx)) return rc;
+    bool keep;
+    if (int rc = before_append(ctx, &keep)) return rc;
     if (ctx->op.size() >= 0x7ffffff0u) return ctx_fail(ctx, OB_E_RANGE, "too many nodes");
-    ctx->manual.clear();   // labels cover the graph they were given for
-    ctx->op.push_back((u8)op);
-    ctx->out_dim.push_back(dim);
-    ctx->in_idx.insert(ctx->in_idx.end(), ins, ins + arity);
-    ctx->in_off.push_back((u32)ctx->in_idx.size());
-    ctx->param.push_back(param);
-    ctx->bias.push_back(bias);
-    ctx->aux0.push_back(a0);
-    ctx->aux1.push_back(a1);
+    if (int rc = store_reserve(ctx, 1, arity, 0)) return rc;
+    const size_t v = ctx->op.n, e0 = ctx->in_idx.n;
+    ctx->op[v] = (u8)op; ctx->out_dim[v] = dim;
+    for (u32 j = 0; j < arity; ++j) ctx->in_idx[e0 + j] = ins[j];
+    ctx->in_idx.n = e0 + arity;
+    ctx->in_off[v + 1] = (u32)ctx->in_idx.n;
+    ctx->param[v] = param; ctx->bias[v] = bias; ctx->aux0[v] = a0; ctx->aux1[v] = a1;
+    ctx->op.n = ctx->out_dim.n = ctx->param.n = ctx->bias.n = ctx->aux0.n = ctx->aux1.n = v + 1;
+    ctx->in_off.n = v + 2;
     const u32 items = (op == OB_OP_MATVEC) ? (1u + (bias >= 0 ? 1u : 0u)) : (op == OB_OP_LOOKUP ? 1u : 0u);
-    ctx->items_upto.push_back((ctx->items_upto.empty() ? 0u : ctx->items_upto.back()) + items);
+    ctx->n_items_total += items;
     ctx->sum_out_dim += dim;
     if (arity > ctx->max_arity) ctx->max_arity = arity;
-    if (op == OB_OP_MATVEC) {
-        ctx->sum_mv_d32 += (u64)ctx->params[param].rows / GT + 1;
-        ctx->sum_mv_k32 += (u64)ctx->params[param].cols / DXT + 1;
-        if (!ctx->params_used_w[param]) { ctx->params_used_w[param] = 1; ctx->params_dirty = true; }
-        if (bias >= 0 && !ctx->params_used_b[bias]) { ctx->params_used_b[bias] = 1; ctx->params_dirty = true; }
-    }
+    if (op == OB_OP_MATVEC) note_matvec(ctx, param, bias);
     if (keep) ctx->image_stale = true; else ctx->uploaded = false;
-    return (int)ctx->op.size() - 1;
+    return (int)v;
 }
 
 static void sync_used_flags(ob_ctx *ctx)
@@ -409,12 +449,16 @@ static int add_one(ob_ctx *ctx, int op, const u32 *ins, u32 arity, int param, in
 {
     sync_used_flags(ctx);
     u32 dim = 0;
-    if (int rc = validate_node(ctx, (u32)ctx->op.size(), ctx->out_dim, op, ins, arity, param, bias, a0, a1, &dim, in_dim_hint))
-        return rc;
+    ErrSink es;
+    if (int rc = validate_node(ctx->params, &es, (u32)ctx->op.size(), ctx->out_dim, op, ins, arity, param, bias, a0, a1, &dim,
+                               in_dim_hint))
+        return ctx_fail(ctx, rc, "%s", es.msg);
     if (op == OB_OP_INPUT) {
         if (!payload) return ctx_fail(ctx, OB_E_ARG, "INPUT without data");
+        if (int rc = store_reserve(ctx, 0, 0, dim)) return rc;
         a0 = (int)ctx->payload.size();
-        ctx->payload.insert(ctx->payload.end(), payload, payload + dim);
+        memcpy(ctx->payload.data() + ctx->payload.n, payload, (size_t)dim * 4);
+        ctx->payload.n += dim;
     }
     return append_node(ctx, op, ins, arity, param, bias, a0, a1, dim);
 }
@@ -500,34 +544,101 @@ int ob_add_bulk(ob_ctx *ctx, int n, const uint8_t *op, const uint32_t *out_dim, 
     const u32 n0 = (u32)ctx->op.size();
     if ((u64)n0 + (u64)n >= 0x7ffffff0ull) return ctx_fail(ctx, OB_E_RANGE, "too many nodes");
     if (in_off[0] != 0) return ctx_fail(ctx, OB_E_ARG, "in_off[0] must be 0");
-    // pass 1: validate everything against a scratch copy of the dimensions (nothing is appended on error)
-    std::vector<u32> dims(ctx->out_dim);
-    dims.reserve((size_t)n0 + n);
-    for (int i = 0; i < n; ++i) {
-        if (in_off[i + 1] < in_off[i]) return ctx_fail(ctx, OB_E_ARG, "in_off not monotone at %d", i);
-        const u32 ar = in_off[i + 1] - in_off[i];
-        if (ar && !in_idx) return ctx_fail(ctx, OB_E_ARG, "null in_idx");
-        u32 dim = 0;
-        u32 hint = 0;
-        if (op[i] == OB_OP_INPUT) {
-            hint = out_dim[i];
-            if (aux0[i] < 0 || (size_t)aux0[i] + out_dim[i] > payload_len || (!payload && out_dim[i]))
-                return ctx_fail(ctx, OB_E_RANGE, "INPUT payload of node %d outside the payload array", i);
+    // The new nodes are validated and written behind the end of the graph store, in up to four
+    // threads over ranges of node ids, and only a call that found no error moves the end (nothing
+    // is appended on error).  An operand's dimension is the stored one for a node that already
+    // exists and the caller's out_dim for an earlier node of this call: every node's out_dim is
+    // checked against the dimension its operation implies, so if all checks pass all were right.
+    const size_t E_new = in_off[n];
+    if (E_new && !in_idx) return ctx_fail(ctx, OB_E_ARG, "null in_idx");
+    if (int rc = store_reserve(ctx, (size_t)n, E_new, payload_len)) return rc;
+    const u32 pay0 = (u32)ctx->payload.size(), e0 = (u32)ctx->in_idx.size();
+    struct DimView {
+        const u32 *old; u32 n0; const u32 *fresh;
+        u32 operator[](u32 u) const { return u < n0 ? old[u] : fresh[u - n0]; }
+    } dims{ctx->out_dim.data(), n0, out_dim};
+    struct Part {
+        ErrSink es; u64 sum_dim = 0, mv_d32 = 0, mv_k32 = 0; u32 max_ar = 0, items = 0;
+        std::vector<u8> used_w, used_b;
+    };
+    const int n_parts = n >= 32768 ? 4 : 1;
+    std::vector<Part> parts((size_t)n_parts);
+    const std::vector<HostParam> &params = ctx->params;
+    auto work = [&](int t) {
+        Part &P = parts[(size_t)t];
+        P.used_w.assign(params.size(), 0); P.used_b.assign(params.size(), 0);
+        const int a = (int)((long long)n * t / n_parts), b = (int)((long long)n * (t + 1) / n_parts);
+        i32 *a0_out = ctx->aux0.data() + n0;
+        for (int i = a; i < b; ++i) {
+            if (in_off[i + 1] < in_off[i] || in_off[i + 1] > E_new) { sink_fail(&P.es, OB_E_ARG, "in_off not monotone at %d", i); return; }
+            const u32 ar = in_off[i + 1] - in_off[i];
+            u32 dim = 0, hint = 0;
+            const u8 o = op[i];
+            if (o == OB_OP_INPUT) {
+                hint = out_dim[i];
+                if (aux0[i] < 0 || (size_t)aux0[i] + out_dim[i] > payload_len || (!payload && out_dim[i])) {
+                    sink_fail(&P.es, OB_E_RANGE, "INPUT payload of node %d outside the payload array", i);
+                    return;
+                }
+            }
+            if (validate_node(params, &P.es, n0 + (u32)i, dims, o, in_idx + in_off[i], ar, param[i], bias[i], aux0[i], aux1[i],
+                              &dim, hint))
+                return;
+            if (dim != out_dim[i]) { sink_fail(&P.es, OB_E_DIM, "node %d: out_dim %u but the operation implies %u", i, out_dim[i], dim); return; }
+            P.sum_dim += dim;
+            if (ar > P.max_ar) P.max_ar = ar;
+            a0_out[i] = (o == OB_OP_INPUT) ? (i32)(pay0 + (u32)aux0[i]) : aux0[i];
+            if (o == OB_OP_MATVEC) {
+                P.items += 1u + (bias[i] >= 0 ? 1u : 0u);
+                P.mv_d32 += (u64)params[param[i]].rows / GT + 1;
+                P.mv_k32 += (u64)params[param[i]].cols / DXT + 1;
+                P.used_w[param[i]] = 1;
+                if (bias[i] >= 0) P.used_b[bias[i]] = 1;
+            } else if (o == OB_OP_LOOKUP) {
+                P.items += 1u;
+            }
         }
-        if (int rc = validate_node(ctx, n0 + (u32)i, dims, op[i], in_idx + in_off[i], ar, param[i], bias[i], aux0[i],
-                                   aux1[i], &dim, hint))
-            return rc;
-        if (dim != out_dim[i]) return ctx_fail(ctx, OB_E_DIM, "node %d: out_dim %u but the operation implies %u", i, out_dim[i], dim);
-        dims.push_back(dim);
+        // this range's share of the plain copies
+        const size_t cnt = (size_t)(b - a);
+        memcpy(ctx->op.data() + n0 + a, op + a, cnt);
+        memcpy(ctx->out_dim.data() + n0 + a, out_dim + a, cnt * 4);
+        memcpy(ctx->param.data() + n0 + a, param + a, cnt * 4);
+        memcpy(ctx->bias.data() + n0 + a, bias + a, cnt * 4);
+        memcpy(ctx->aux1.data() + n0 + a, aux1 + a, cnt * 4);
+        if (e0 == 0) memcpy(ctx->in_off.data() + n0 + 1 + a, in_off + 1 + a, cnt * 4);
+        else for (int i = a; i < b; ++i) ctx->in_off[n0 + 1 + (size_t)i] = e0 + in_off[i + 1];
+        if (in_off[b] > in_off[a]) memcpy(ctx->in_idx.data() + e0 + in_off[a], in_idx + in_off[a], (size_t)(in_off[b] - in_off[a]) * 4);
+        const size_t pa = payload_len * (size_t)t / (size_t)n_parts, pb = payload_len * (size_t)(t + 1) / (size_t)n_parts;
+        if (pb > pa) memcpy(ctx->payload.data() + pay0 + pa, payload + pa, (pb - pa) * 4);
+    };
+    if (n_parts == 1) {
+        work(0);
+    } else {
+        std::vector<std::thread> th;
+        for (int t = 1; t < n_parts; ++t) th.emplace_back(work, t);
+        work(0);
+        for (auto &x : th) x.join();
     }
-    // pass 2: append
-    const u32 pay0 = (u32)ctx->payload.size();
-    if (payload_len) ctx->payload.insert(ctx->payload.end(), payload, payload + payload_len);
-    for (int i = 0; i < n; ++i) {
-        const u32 ar = in_off[i + 1] - in_off[i];
-        const int a0 = (op[i] == OB_OP_INPUT) ? (int)(pay0 + (u32)aux0[i]) : aux0[i];
-        append_node(ctx, op[i], in_idx + in_off[i], ar, param[i], bias[i], a0, aux1[i], out_dim[i]);
+    for (const Part &P : parts)   // the first failing range holds the first failing node
+        if (P.es.code) return ctx_fail(ctx, P.es.code, "%s", P.es.msg);
+    bool keep;
+    if (int rc = before_append(ctx, &keep)) return rc;
+    for (const Part &P : parts) {
+        ctx->sum_out_dim += P.sum_dim;
+        if (P.max_ar > ctx->max_arity) ctx->max_arity = P.max_ar;
+        ctx->n_items_total += P.items;
+        ctx->sum_mv_d32 += P.mv_d32; ctx->sum_mv_k32 += P.mv_k32;
+        for (size_t q = 0; q < params.size(); ++q) {
+            if (P.used_w[q] && !ctx->params_used_w[q]) { ctx->params_used_w[q] = 1; ctx->params_dirty = true; }
+            if (P.used_b[q] && !ctx->params_used_b[q]) { ctx->params_used_b[q] = 1; ctx->params_dirty = true; }
+        }
     }
+    const size_t n1 = (size_t)n0 + n;
+    ctx->op.n = ctx->out_dim.n = ctx->param.n = ctx->bias.n = ctx->aux0.n = ctx->aux1.n = n1;
+    ctx->in_off.n = n1 + 1;
+    ctx->in_idx.n = e0 + E_new;
+    ctx->payload.n = pay0 + payload_len;
+    if (keep) ctx->image_stale = true; else ctx->uploaded = false;
     return (int)n0;
 }
 
@@ -612,7 +723,8 @@ int ob_upload(ob_ctx *ctx)
     }
 
     const size_t n = ctx->op.size(), E = ctx->in_idx.size(), P = ctx->payload.size();
-    // one packed image: op | out_dim | in_off | in_idx | param | bias | aux0 | aux1 | payload
+    // one block of the arena: op | out_dim | in_off | in_idx | param | bias | aux0 | aux1 | payload | labels,
+    // each array copied straight from the page-locked graph store
     size_t off[11];
     size_t cur = 0;
     const bool labels = ctx->manual.size() == n;
@@ -620,28 +732,28 @@ int ob_upload(ob_ctx *ctx)
                               labels ? n * 4 : 0};
     for (int i = 0; i < 10; ++i) { off[i] = cur; cur += up256(sizes[i]); }
     off[10] = cur;
-    if (cur > ctx->pinned_bytes) {
+    if (labels && n * 4 > ctx->pinned_bytes) {
         if (ctx->pinned) HIP_TRY(ctx, hipHostFree(ctx->pinned));
         ctx->pinned = nullptr;
-        ctx->pinned_bytes = cur + cur / 2;
+        ctx->pinned_bytes = n * 4 + n * 2;
         HIP_TRY(ctx, hipHostMalloc(&ctx->pinned, ctx->pinned_bytes, hipHostMallocDefault));
     }
-    char *img = (char *)ctx->pinned;
-    memcpy(img + off[0], ctx->op.data(), n);
-    memcpy(img + off[1], ctx->out_dim.data(), n * 4);
-    memcpy(img + off[2], ctx->in_off.data(), (n + 1) * 4);
-    if (E) memcpy(img + off[3], ctx->in_idx.data(), E * 4);
-    memcpy(img + off[4], ctx->param.data(), n * 4);
-    memcpy(img + off[5], ctx->bias.data(), n * 4);
-    memcpy(img + off[6], ctx->aux0.data(), n * 4);
-    memcpy(img + off[7], ctx->aux1.data(), n * 4);
-    if (P) memcpy(img + off[8], ctx->payload.data(), P * 4);
-    if (labels) memcpy(img + off[9], ctx->manual.data(), n * 4);
+    if (labels) memcpy(ctx->pinned, ctx->manual.data(), n * 4);
     char *dev = (char *)arena_alloc(ctx, cur);
     if (!dev) return ctx_fail(ctx, OB_E_OOM, "arena too small for the graph (%zu bytes)", cur);
-    HIP_TRY(ctx, hipEventRecord(ctx->ev[0], ctx->sched_stream));
-    HIP_TRY(ctx, hipMemcpyAsync(dev, img, cur, hipMemcpyHostToDevice, ctx->sched_stream));
-    HIP_TRY(ctx, hipEventRecord(ctx->ev[1], ctx->sched_stream));
+    hipStream_t us = ctx->sched_stream;
+    HIP_TRY(ctx, hipEventRecord(ctx->ev[0], us));
+    const void *src[10] = {ctx->op.data(), ctx->out_dim.data(), ctx->in_off.data(), ctx->in_idx.data(), ctx->param.data(),
+                           ctx->bias.data(), ctx->aux0.data(), ctx->aux1.data(), ctx->payload.data(), ctx->pinned};
+    const size_t bytes[10] = {n, n * 4, (n + 1) * 4, E * 4, n * 4, n * 4, n * 4, n * 4, P * 4, labels ? n * 4 : 0};
+    size_t total = 0;
+    for (int i = 0; i < 10; ++i) {
+        if (!bytes[i]) continue;
+        HIP_TRY(ctx, hipMemcpyAsync(dev + off[i], src[i], bytes[i], hipMemcpyHostToDevice, us));
+        total += bytes[i];
+    }
+    HIP_TRY(ctx, hipEventRecord(ctx->ev[1], us));
+    cur = total;
     Tables &T = ctx->T;
     T = Tables{};
     T.op = (const u8 *)(dev + off[0]); T.out_dim = (const u32 *)(dev + off[1]); T.in_off = (const u32 *)(dev + off[2]);
@@ -905,7 +1017,7 @@ static int stage_forward(ob_ctx *ctx, u32 n0, u32 n1)
         par[l] = ctx->param[v]; bia[l] = ctx->bias[v]; a0[l] = ctx->aux0[v]; a1[l] = ctx->aux1[v];
         if (ctx->op[v] == OB_OP_INPUT) {
             a0[l] = (i32)pay.size();
-            pay.insert(pay.end(), ctx->payload.begin() + ctx->aux0[v], ctx->payload.begin() + ctx->aux0[v] + ctx->out_dim[v]);
+            pay.insert(pay.end(), ctx->payload.data() + ctx->aux0[v], ctx->payload.data() + ctx->aux0[v] + ctx->out_dim[v]);
         }
         for (u32 e = ctx->in_off[v]; e < ctx->in_off[v + 1]; ++e) {
             const u32 u = ctx->in_idx[e];
@@ -1183,8 +1295,21 @@ int ob_stats_read(ob_ctx *ctx, ob_stats *out)
         (void)hipEventElapsedTime(&out->ms_param_grads, ctx->ev[6], ctx->ev[5]);
     }
     out->ms_graph_build = ctx->ms_graph;
+    out->n_depth_retries = ctx->n_depth_retries;
     (void)hipGetLastError();
     return OB_OK;
+}
+
+int ob_debug_set(ob_ctx *ctx, int which, uint64_t value)
+{
+    CHECK_CTX(ctx);
+    switch (which) {
+    case OB_DBG_SET_DEPTH_SPIN:
+        ctx->depth_spin_limit = value > 0xffffffffull ? 0xffffffffu : (u32)value;
+        return OB_OK;
+    default:
+        return ctx_fail(ctx, OB_E_ARG, "unknown knob %d", which);
+    }
 }
 
 int ob_debug_read(ob_ctx *ctx, int which, uint32_t *host_out, size_t cap_words, size_t *n_words)
@@ -1205,8 +1330,6 @@ int ob_debug_read(ob_ctx *ctx, int which, uint32_t *host_out, size_t cap_words, 
     case OB_DBG_TILES_FWD: src = T.tiles_f; words = (size_t)ctx->hdr.tiles_fwd * (sizeof(TileDesc) / 4); break;
     case OB_DBG_TILES_PULL: src = T.tiles_a; words = (size_t)ctx->hdr.tiles_pull * (sizeof(PullDesc) / 4); break;
     case OB_DBG_CHAINS: src = T.chains; words = (size_t)ctx->hdr.n_chains * (sizeof(ChainRec) / 4); break;
-    case OB_DBG_EPI_TAIL: src = T.epi_tail; words = ctx->hdr.n_chains; break;
-    case OB_DBG_EPI_MAP: src = T.epi_map; words = ctx->hdr.n_chains; break;
     case OB_DBG_LORDER: src = T.lorder; words = ctx->hdr.n_batches; break;
     default: return ctx_fail(ctx, OB_E_ARG, "unknown table %d", which);
     }
@@ -1278,21 +1401,6 @@ int ob_test_launch_cost(ob_ctx *ctx, int n, int touch, float *us_per_launch)
     hipError_t e = hipMemsetAsync(scratch, 0, 256, ctx->stream);
     if (e == hipSuccess) e = exec_launch_probe(scratch, n, touch, us_per_launch, ctx->stream);
     if (e != hipSuccess) rc = ctx_fail(ctx, OB_E_HIP, "launch probe failed: %s", hipGetErrorString(e));
-    ctx->top = save;
-    return rc;
-}
-
-int ob_test_grid_barrier(ob_ctx *ctx, int n_wg, int iters, uint32_t *out3)
-{
-    CHECK_CTX(ctx);
-    if (!ctx->arena) return ctx_fail(ctx, OB_E_STATE, "no arena");
-    if (n_wg <= 0 || n_wg > 4096 || iters <= 0 || iters > 100000 || !out3) return ctx_fail(ctx, OB_E_ARG, "bad argument");
-    const size_t save = ctx->top;
-    u32 *state = arena_array<u32>(ctx, 64 + (size_t)n_wg);
-    if (!state) return ctx_fail(ctx, OB_E_OOM, "arena too small");
-    int rc = OB_OK;
-    hipError_t e = exec_barrier_probe(state, n_wg, iters, out3, ctx->stream);
-    if (e != hipSuccess) rc = ctx_fail(ctx, OB_E_HIP, "barrier probe failed: %s", hipGetErrorString(e));
     ctx->top = save;
     return rc;
 }

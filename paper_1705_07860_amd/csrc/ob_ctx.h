@@ -1,10 +1,53 @@
 // Host-side context of the library (not part of the ABI).
 #pragma once
 
+#include <cstdlib>
+#include <cstring>
 #include <string>
 #include <vector>
 
 #include "ob_internal.h"
+
+// Growable host array of the graph store.  In a context that owns a device arena the memory is
+// page-locked (hipHostMalloc), so that the upload copies straight from where the nodes were
+// written; a host-only context (no arena, no GPU) uses ordinary memory.  Capacity is kept
+// across graphs, so a training loop stops allocating after its first few minibatches.
+template <typename T> struct HostVec {
+    T *p = nullptr;
+    size_t n = 0, cap = 0;
+    bool pinned = false;
+    HostVec() = default;
+    HostVec(const HostVec &) = delete;
+    HostVec &operator=(const HostVec &) = delete;
+    ~HostVec() { release(); }
+    void release()
+    {
+        if (p) { if (pinned) (void)hipHostFree(p); else free(p); }
+        p = nullptr; n = cap = 0;
+    }
+    // false when memory cannot be had; the old contents stay valid then
+    bool reserve(size_t want, bool pin)
+    {
+        if (want <= cap) return true;
+        size_t c = cap ? cap : 1024;
+        while (c < want) c *= 2;
+        T *q = nullptr;
+        if (pin) { if (hipHostMalloc((void **)&q, c * sizeof(T), hipHostMallocDefault) != hipSuccess) { (void)hipGetLastError(); return false; } }
+        else q = (T *)malloc(c * sizeof(T));
+        if (!q) return false;
+        if (n) memcpy(q, p, n * sizeof(T));
+        if (p) { if (pinned) (void)hipHostFree(p); else free(p); }
+        p = q; cap = c; pinned = pin;
+        return true;
+    }
+    size_t size() const { return n; }
+    bool empty() const { return n == 0; }
+    T *data() { return p; }
+    const T *data() const { return p; }
+    T &operator[](size_t i) { return p[i]; }
+    const T &operator[](size_t i) const { return p[i]; }
+    void clear() { n = 0; }
+};
 
 struct HostParam {
     int rows, cols;
@@ -33,8 +76,7 @@ struct ob_ctx {
     ob_ctx *parent = nullptr;            // forked contexts share the parent's parameters
     int mode = 1;      // OB_BYDEPTH
     int launch = 0;    // OB_LAUNCH_STREAM
-    int fuse = 2;      // launch fusion level: 0 off, 1 fused with early placement, 2 fused with late placement,
-                       // 3 = 2 and chains evaluated behind the tiles of the matrix product they read
+    int fuse = 2;      // launch fusion level: 0 off, 1 fused with early placement, 2 fused with late placement
     std::string err;
 
     // arena bump allocator: [0, persist_top) parameters; [persist_top, top) current graph
@@ -52,21 +94,21 @@ struct ob_ctx {
     std::vector<std::vector<float>> pending;      // host copies of parameter data not yet on the device
     std::vector<u8> params_used_w, params_used_b; // parameter appeared as a MATVEC matrix / bias
 
-    // host graph store (pinned staging is allocated on upload)
-    std::vector<u8> op;
-    std::vector<u32> out_dim, in_off, in_idx;
-    std::vector<i32> param, bias, aux0, aux1;
-    std::vector<float> payload;
+    // host graph store: in_off always holds size(op) + 1 entries
+    HostVec<u8> op;
+    HostVec<u32> out_dim, in_off, in_idx;
+    HostVec<i32> param, bias, aux0, aux1;
+    HostVec<float> payload;
     std::vector<u32> manual;           // OB_MANUAL: the caller's batch label per node (empty = none given)
     u32 manual_max = 0;                // largest label
-    std::vector<u32> items_upto;       // parameter-use items among nodes [0, v]
+    u32 n_items_total = 0;             // parameter-use items (MATVEC matrix / bias uses, LOOKUPs) of the whole graph
     u64 sum_out_dim = 0;               // bounds the tile lists
     u32 max_arity = 0;
     u64 sum_mv_d32 = 0, sum_mv_k32 = 0; // sums over MATVEC nodes of rows/32+1 and cols/32+1 (bound the GEMM tiles)
     size_t graph_top = 0;              // arena top right after the uploaded graph image
 
     // device state of the current graph
-    void *pinned = nullptr;
+    void *pinned = nullptr;            // staging for the batch labels of manual batching
     size_t pinned_bytes = 0;
     bool uploaded = false;
     bool image_stale = false;          // nodes were added behind a live evaluation: the device image lacks them
@@ -76,6 +118,10 @@ struct ob_ctx {
     u32 n_sched = 0;                   // nodes covered by the last schedule (0 = none)
     bool sched_pending = false;        // scheduling is queued on the GPU, its results are not read yet
     u32 hdr_window = 0, n_items_sched = 0;
+    u32 depth_spin_limit = 1u << 21;   // idle polls a range of the partitioned depth pass allows itself before it gives up
+    bool depth_partitioned = false;    // the last schedule used the partitioned depth pass
+    bool force_frontier = false;       // schedule with the single-workgroup depth pass (retry after a range gave up)
+    int n_depth_retries = 0;           // schedules of this context that had to be repeated that way
     bool forward_done = false, backward_done = false;
     Tables T{};
     SchedHeader hdr{};

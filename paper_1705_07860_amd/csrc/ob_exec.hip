@@ -894,222 +894,6 @@ __device__ inline void pull_tile(const Tables &T, const PullDesc &d, lds_float *
 // ------------------------------------------------------------------------------------------------
 // kernels
 // ------------------------------------------------------------------------------------------------
-// ---- GEMM-headed run ------------------------------------------------------------------------------
-// The head tile covers 32 rows and, of each of the q segments of Hs columns, the w = 32 / q columns
-// u0 .. u0 + w - 1 (tile column c is column (c / w) * Hs + u0 + c % w).  Its results go to the
-// value arena and, segment-major, into the run's value file: file[(segment) * 32 w + r * w + jj]
-// for tile row r and unit u0 + jj.  The members behind it are evaluated one (row, unit) pair per
-// thread, every segment of the member for that pair; operands produced in the run come from the
-// same pair's entries of the file, so the threads never wait for each other.
-static_assert(EPI_LDS_BASE == (u32)LDS_FLOATS, "the value file lies behind the reduction space");
-
-__device__ inline void epi_head_tile(const Tables &T, const TileDesc &d, float *lds)
-{
-    const u32 Hs = d.pad & 0xffffffu, q = d.pad >> 24, w_ = 32u / q;
-    const u32 ntn = d.d / 32u;
-    const u32 r0 = (d.t / ntn) * 32u, u0 = (d.t % ntn) * w_;
-    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
-    const u32 l32 = lane & 31, h = lane >> 5;
-    const u32 col = (l32 / w_) * Hs + u0 + l32 % w_;
-    const u32 row = r0 + l32;
-    const bool row_ok = row < d.B;
-    const float *xrow = T.V + (row_ok ? opnd_row(T, d, 0, row - d.row0, row) : 0u);
-    gl_float *wrow = as_global(d.w) + (size_t)col * d.k;
-    const u32 K = d.k;
-    const bool fast = (d.flags & 2u) && (K & 3u) == 0;
-    u32 lo, hi;
-    wave_range<4>(K, lo, hi);
-    floatx16 acc;
-    for (int v = 0; v < 16; ++v) acc[v] = 0.f;
-    const float4 z4 = make_float4(0.f, 0.f, 0.f, 0.f);
-    if (fast) {
-        for (u32 kb = lo; kb < hi; kb += 8 * KU) {
-            float4 a[KU], b[KU];
-#pragma unroll
-            for (int u = 0; u < KU; ++u) {
-                const u32 k0 = kb + 8 * u + 4 * h;
-                const bool in = kb + 8 * u < hi && k0 < K;
-                a[u] = (in && row_ok) ? ld4(xrow + k0) : z4;
-                b[u] = in ? gl_ld4(wrow + k0) : z4;
-            }
-#pragma unroll
-            for (int u = 0; u < KU; ++u) acc = mfma4(a[u], b[u], acc);
-        }
-    } else {
-        for (u32 kb = lo; kb < hi; kb += 8) {
-            const u32 k0 = kb + 4 * h;
-            float av[4] = {0.f, 0.f, 0.f, 0.f}, bv[4] = {0.f, 0.f, 0.f, 0.f};
-            for (int s = 0; s < 4; ++s)
-                if (k0 + s < K) {
-                    if (row_ok) av[s] = xrow[k0 + s];
-                    bv[s] = wrow[k0 + s];
-                }
-            acc = mfma4(make_float4(av[0], av[1], av[2], av[3]), make_float4(bv[0], bv[1], bv[2], bv[3]), acc);
-        }
-    }
-    float out[4];
-    reduce_waves<4>(acc, lds, out);
-    const float bb = d.b ? as_global(d.b)[col] : 0.f;
-    float *file = lds + EPI_LDS_BASE;
-    for (int i = 0; i < 4; ++i) {
-        const u32 r = 8 * w + 4 * h + i;       // tile row
-        const float y = out[i] + bb;
-        if (r0 + r < d.B) T.V[d.val_off + (size_t)(r0 + r) * d.d + col] = y;
-        file[(l32 / w_) * 32u * w_ + r * w_ + l32 % w_] = y;
-    }
-}
-
-// Operand j of a member for tile row r / unit jj, segment sg, read from the value arena.
-__device__ inline float epi_ld_global(const Tables &T, const TileDesc &d, u32 j, u32 r, u32 col)
-{
-    const u32 row = d.row0 + r * d.rstride;
-    return T.V[opnd_row(T, d, j, r, row) + (d.op == OP_SLICE ? (u32)d.aux0 : 0u) + col];
-}
-
-__device__ inline void epi_member_tile(const Tables &T, const TileDesc &d, float *lds)
-{
-    const u32 Hs = d.pad & 0xffffffu, q = d.pad >> 24, w_ = 32u / q;
-    const u32 pairs = 32u * w_;
-    const u32 u0 = (d.t % ((Hs * q) / 32u)) * w_;
-    const u32 qm = d.d / Hs;
-    const u32 shift = d.op == OP_SLICE ? (u32)d.aux0 / Hs : 0u;
-    float *file = lds + EPI_LDS_BASE;
-    for (u32 p = threadIdx.x; p < pairs; p += WG) {
-        const u32 r = p / w_, jj = p % w_;
-        if (r >= d.nrows) continue;
-        const u32 row = d.row0 + r * d.rstride;
-        for (u32 sg = 0; sg < qm; ++sg) {
-            const u32 col = sg * Hs + u0 + jj;
-            // four operand values at most, kept in registers (no indexed array)
-            float x0 = 0.f, x1 = 0.f, x2 = 0.f, x3 = 0.f;
-            if (d.arity > 0) x0 = (d.flags & (TF_SRC_LDS << 0)) ? file[(d.lds_src[0] + sg + shift) * pairs + p] : epi_ld_global(T, d, 0, r, col);
-            if (d.arity > 1) x1 = (d.flags & (TF_SRC_LDS << 1)) ? file[(d.lds_src[1] + sg) * pairs + p] : epi_ld_global(T, d, 1, r, col);
-            if (d.arity > 2) x2 = (d.flags & (TF_SRC_LDS << 2)) ? file[(d.lds_src[2] + sg) * pairs + p] : epi_ld_global(T, d, 2, r, col);
-            if (d.arity > 3) x3 = (d.flags & (TF_SRC_LDS << 3)) ? file[(d.lds_src[3] + sg) * pairs + p] : epi_ld_global(T, d, 3, r, col);
-            float y;
-            switch (d.op) {
-            case OP_ADD: y = ((x0 + x1) + x2) + x3; break;
-            case OP_CMULT: y = x0 * x1; break;
-            case OP_TANH: y = tanhf(x0); break;
-            case OP_SIGMOID: y = sigmoidf_(x0); break;
-            default: y = x0; break;   // SLICE
-            }
-            T.V[d.val_off + (size_t)row * d.d + col] = y;
-            file[(d.lds_out + sg) * pairs + p] = y;
-        }
-    }
-}
-
-// The whole run: descriptors sdesc[0 .. cn) staged in LDS.  Values the members read from outside
-// the run (the other addend of the gates, the previous cell state) are requested before the
-// product starts, so their latency passes behind it; they join the value file after it.  The
-// staged member descriptors are patched to read them from there.
-__device__ inline void epi_run(const Tables &T, TileDesc *sdesc, u32 cn, float *lds)
-{
-    __shared__ u32 s_elist[EPI_MAX_EXT];
-    __shared__ u32 s_next;
-    const TileDesc &h = sdesc[0];
-    const u32 Hs = h.pad & 0xffffffu, q = h.pad >> 24, w_ = 32u / q;
-    const u32 pairs = 32u * w_;
-    const u32 segs = h.lds_out;
-    float *file = lds + EPI_LDS_BASE;
-    const bool prefetch = pairs <= (u32)WG;   // one (row, unit) pair per thread
-    u32 n_ext = 0;
-    float ext[EPI_MAX_EXT];
-#pragma unroll
-    for (u32 e = 0; e < EPI_MAX_EXT; ++e) ext[e] = 0.f;
-    if (prefetch) {
-        if (threadIdx.x == 0) s_next = 0;
-        if (threadIdx.x < EPI_MAX_EXT) s_elist[threadIdx.x] = EPI_NONE;
-        __syncthreads();
-        for (u32 x = threadIdx.x; x < (cn - 1) * 4u; x += WG) {
-            const u32 t = 1u + x / 4u, j = x % 4u;
-            TileDesc &dm = sdesc[t];
-            if (j < dm.arity && !(dm.flags & (TF_SRC_LDS << j))) {
-                const u32 qm = dm.d / Hs;
-                const u32 base = atomicAdd(&s_next, qm);
-                if (base + qm <= EPI_MAX_EXT) {
-                    for (u32 sg = 0; sg < qm; ++sg) s_elist[base + sg] = t | (j << 8) | (sg << 16);
-                    const u32 shift = (dm.op == OP_SLICE && j == 0) ? (u32)dm.aux0 / Hs : 0u;
-                    dm.lds_src[j] = segs + base - shift;
-                    atomicOr(&dm.flags, TF_SRC_LDS << j);
-                }
-            }
-        }
-        __syncthreads();
-        n_ext = s_next < EPI_MAX_EXT ? s_next : EPI_MAX_EXT;   // (entries that did not fit stay global reads)
-        const u32 p = threadIdx.x, r = p / w_, jj = p % w_;
-        const u32 u0 = (h.t % (h.d / 32u)) * w_;
-#pragma unroll
-        for (u32 e = 0; e < EPI_MAX_EXT; ++e) {
-            const u32 k = s_elist[e];
-            if (e < n_ext && p < pairs && k != EPI_NONE) {
-                const TileDesc &dm = sdesc[k & 0xffu];
-                if (r < dm.nrows) ext[e] = epi_ld_global(T, dm, (k >> 8) & 0xffu, r, (k >> 16) * Hs + u0 + jj);
-            }
-        }
-    }
-    // compact form of every member whose operands all come from the file: eight words, decoded
-    // by one thread per member while the others start the product
-    __shared__ __align__(16) u32 s_mop[RUN_STAGE_DESCS][8];
-    if (threadIdx.x >= 1 && threadIdx.x < cn) {
-        const TileDesc &dm = sdesc[threadIdx.x];
-        const u32 qm = dm.d / Hs;
-        const u32 mask = (dm.flags / TF_SRC_LDS) & 0xfu;
-        const bool all_file = mask == ((1u << dm.arity) - 1u) && dm.arity <= 4u;
-        const u32 shift = dm.op == OP_SLICE ? (u32)dm.aux0 / Hs : 0u;
-        u32 *m = s_mop[threadIdx.x];
-        m[0] = dm.op | (dm.arity << 8) | (qm << 16) | ((all_file ? 1u : 0u) << 24);
-        m[1] = ((dm.lds_src[0] + shift) & 0xffu) | ((dm.lds_src[1] & 0xffu) << 8) | ((dm.lds_src[2] & 0xffu) << 16) | ((dm.lds_src[3] & 0xffu) << 24);
-        m[2] = dm.lds_out;
-        m[3] = dm.val_off;
-        m[4] = dm.d;
-        m[5] = dm.row0;
-        m[6] = dm.rstride;
-        m[7] = dm.nrows;
-    }
-    epi_head_tile(T, h, lds);
-    if (prefetch && threadIdx.x < pairs) {
-#pragma unroll
-        for (u32 e = 0; e < EPI_MAX_EXT; ++e)
-            if (e < n_ext) file[(segs + e) * pairs + threadIdx.x] = ext[e];
-    }
-    __syncthreads();
-    const u32 u0 = (h.t % (h.d / 32u)) * w_;
-    for (u32 t = 1; t < cn; ++t) {
-        const uint4 a = *reinterpret_cast<const uint4 *>(&s_mop[t][0]);
-        const uint4 b = *reinterpret_cast<const uint4 *>(&s_mop[t][4]);
-        const u32 m0 = __builtin_amdgcn_readfirstlane(a.x);
-        if (!(m0 >> 24) || !prefetch) { epi_member_tile(T, sdesc[t], lds); continue; }
-        const u32 m1 = __builtin_amdgcn_readfirstlane(a.y), dst = __builtin_amdgcn_readfirstlane(a.z);
-        const u32 val_off = __builtin_amdgcn_readfirstlane(a.w), dd = __builtin_amdgcn_readfirstlane(b.x);
-        const u32 row0 = __builtin_amdgcn_readfirstlane(b.y), rstride = __builtin_amdgcn_readfirstlane(b.z);
-        const u32 nrows = __builtin_amdgcn_readfirstlane(b.w);
-        const u32 op = m0 & 0xffu, arity = (m0 >> 8) & 0xffu, qm = (m0 >> 16) & 0xffu;
-        const u32 p = threadIdx.x, r = p / w_, jj = p % w_;
-        if (p >= pairs || r >= nrows) continue;
-        float *out = T.V + val_off + (size_t)(row0 + r * rstride) * dd + u0 + jj;
-        for (u32 sg = 0; sg < qm; ++sg) {
-            const float x0 = file[((m1 & 0xffu) + sg) * pairs + p];
-            float y;
-            switch (op) {
-            case OP_ADD: {
-                y = x0 + file[(((m1 >> 8) & 0xffu) + sg) * pairs + p];
-                if (arity > 2) y += file[(((m1 >> 16) & 0xffu) + sg) * pairs + p];
-                if (arity > 3) y += file[((m1 >> 24) + sg) * pairs + p];
-                break;
-            }
-            case OP_CMULT: y = x0 * file[(((m1 >> 8) & 0xffu) + sg) * pairs + p]; break;
-            case OP_TANH: y = tanhf(x0); break;
-            case OP_SIGMOID: y = sigmoidf_(x0); break;
-            default: y = x0; break;   // SLICE
-            }
-            out[sg * Hs] = y;
-            file[(dst + sg) * pairs + p] = y;
-        }
-    }
-}
-
 __device__ inline void run_fwd_tile(const Tables &T, const TileDesc &d, float *lds)
 {
     switch (d.op) {
@@ -1164,10 +948,8 @@ extern __shared__ __align__(16) float dyn_lds[];   // sized per launch: GEMM red
 
 // LEAN: the launch holds component-wise work only; this instantiation carries no GEMM or
 // reduction code, needs half the registers and keeps twice the waves per CU.
-// EPI: the launch may hold GEMM-headed runs; only that instantiation carries their code (it costs
-// registers that the plain GEMM tiles would otherwise pay for with spills).
-template <bool LEAN, bool EPI = false>
-__global__ __launch_bounds__(WG, LEAN ? 6 : (EPI ? 2 : 4)) void k_fwd_step(u32 work_lo, u32 work_hi, u32 tile_lo, u32 run_len,
+template <bool LEAN>
+__global__ __launch_bounds__(WG, LEAN ? 6 : 4) void k_fwd_step(u32 work_lo, u32 work_hi, u32 tile_lo, u32 run_len,
                                                                 const TileDesc *tiles_f, const WorkRec *works_f, Tables T)
 {
     // the leading arguments arrive in scalar registers with the wave (so the descriptor loads start
@@ -1190,12 +972,6 @@ __global__ __launch_bounds__(WG, LEAN ? 6 : (EPI ? 2 : 4)) void k_fwd_step(u32 w
             __syncthreads();
             stage_descriptors<sizeof(TileDesc) / 4, WG>(tiles_f + wr.first + c0, sdesc, cn);
             __syncthreads();
-            if (EPI && (__builtin_amdgcn_readfirstlane(sdesc[0].flags) & TF_EPI)) {
-                // GEMM-headed run (at most RUN_STAGE descriptors, so this is its only stage): the
-                // product tile, one barrier, then the members with no barrier between them
-                epi_run(T, sdesc, cn, lds);
-                continue;
-            }
             const bool heavy = __ballot(lane < cn && (sdesc[lane < cn ? lane : 0].flags & TF_GLOBAL_DEP)) != 0ull;
             u32 i = 0;
             while (i < cn) {
@@ -1375,7 +1151,6 @@ constexpr u32 GRID_CAP = 4096;
 // run length to pass to a step kernel: the slot's common tiles-per-work-item count, or 0 when its
 // chains differ (the kernel then reads each work item's record)
 static inline u32 slot_run_len(const SlotRec &r) { return r.lmin == ~r.nlmax ? r.lmin : 0u; }
-static inline u32 slot_run_len_fwd(const SlotRec &r) { return r.lminf == ~r.nlmaxf ? r.lminf : 0u; }
 
 // dynamic LDS of a step launch: the slot's fused chains' need, at least the GEMM reduction space
 constexpr size_t FWD_LDS_MIN = (size_t)(WIDE_LDS_FLOATS > (u32)LDS_FLOATS ? WIDE_LDS_FLOATS : (u32)LDS_FLOATS) * 4;   // staged wide tile / accumulator blocks
@@ -1392,8 +1167,7 @@ static hipError_t allow_large_dynamic_lds()
 {
     static hipError_t result = [] {
         const int bytes = (int)(CHAIN_LDS_FLOATS * 4);
-        const void *kernels[5] = {(const void *)k_fwd_step<false>, (const void *)k_fwd_step<true>,
-                                  (const void *)k_fwd_step<false, true>,
+        const void *kernels[4] = {(const void *)k_fwd_step<false>, (const void *)k_fwd_step<true>,
                                   (const void *)k_bwd_step<false>, (const void *)k_bwd_step<true>};
         hipError_t e = hipSuccess;
         for (const void *k : kernels)
@@ -1415,13 +1189,10 @@ static int launch_forward_steps(ob_ctx *ctx)
         if (hi > lo) {
             if (r.plain & 1u)
                 hipLaunchKernelGGL(k_fwd_step<true>, dim3(grid_for(hi - lo, GRID_CAP)), dim3(WG), slot_lds_bytes(r, 16), s,
-                                   lo, hi, r.tf, slot_run_len_fwd(r), T.tiles_f, T.works_f, T);
-            else if (!(r.plain & 2u))
-                hipLaunchKernelGGL((k_fwd_step<false, true>), dim3(grid_for(hi - lo, GRID_CAP)), dim3(WG),
-                                   slot_lds_bytes(r, FWD_LDS_MIN), s, lo, hi, r.tf, slot_run_len_fwd(r), T.tiles_f, T.works_f, T);
+                                   lo, hi, r.tf, slot_run_len(r), T.tiles_f, T.works_f, T);
             else
                 hipLaunchKernelGGL(k_fwd_step<false>, dim3(grid_for(hi - lo, GRID_CAP)), dim3(WG),
-                                   slot_lds_bytes(r, FWD_LDS_MIN), s, lo, hi, r.tf, slot_run_len_fwd(r), T.tiles_f, T.works_f, T);
+                                   slot_lds_bytes(r, FWD_LDS_MIN), s, lo, hi, r.tf, slot_run_len(r), T.tiles_f, T.works_f, T);
             ++ctx->n_launch_fwd;
         }
     }
@@ -1551,76 +1322,6 @@ hipError_t exec_launch_probe(float *scratch, int n, int touch, float *us_per_lau
     *us_per_launch = n > 0 ? ms * 1000.0f / (float)n : 0.f;
     (void)hipEventDestroy(e0);
     (void)hipEventDestroy(e1);
-    return e;
-}
-
-// ---- grid-wide barrier (all workgroups of a cooperative launch) --------------------------------
-// counter counts arrivals over the whole launch: phase p is complete when it reaches
-// (p + 1) * gridDim.x.  Every wave first makes its own stores visible device-wide; thread 0
-// arrives and polls with a bounded number of polls (on overrun it raises *fail, which every other
-// waiter also watches, so that all workgroups leave and the kernel ends); then every wave drops
-// what it may have cached of other workgroups' data.  Returns false after a failure.
-// Measured on MI355X: 2.3 us per phase with 8 workgroups, 13 us with 128, 23 us with 256 (the
-// arrivals serialise on one address), against 2.3 us for a kernel boundary: the step kernels
-// therefore stay one launch per slot and this barrier is only kept as a measured probe.
-__device__ inline bool grid_barrier(u32 *counter, u32 *fail, u32 phase, u32 spin_limit)
-{
-    __shared__ u32 s_ok;
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        const u32 target = (phase + 1u) * gridDim.x;
-        __hip_atomic_fetch_add(counter, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        u32 spins = 0, ok = 1;
-        while (__hip_atomic_load(counter, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < target) {
-            if (++spins > spin_limit || __hip_atomic_load(fail, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0u) {
-                __hip_atomic_store(fail, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                ok = 0;
-                break;
-            }
-            __builtin_amdgcn_s_sleep(1);
-        }
-        s_ok = ok;
-    }
-    __syncthreads();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
-    return s_ok != 0u;
-}
-
-// state: [0] arrival counter, [1] failure flag, [2] mismatches seen, [3] ns per phase (workgroup 0),
-// [64 ...] one word per workgroup.  Each phase a workgroup publishes the phase number and, after
-// the barrier, checks what its right-hand neighbour published.
-__global__ __launch_bounds__(WG) void k_barrier_probe(u32 *state, u32 iters, u32 spin_limit)
-{
-    u32 *slots = state + 64;
-    const u64 t0 = wall_clock64();
-    u32 bad = 0;
-    for (u32 p = 0; p < iters; ++p) {
-        if (threadIdx.x == 0) slots[blockIdx.x] = p + 1u;
-        if (!grid_barrier(state, state + 1, p, spin_limit)) break;
-        if (threadIdx.x == 0 && slots[(blockIdx.x + 1u) % gridDim.x] < p + 1u) ++bad;
-    }
-    if (threadIdx.x == 0) {
-        if (bad) atomicAdd(state + 2, bad);
-        if (blockIdx.x == 0) state[3] = (u32)((wall_clock64() - t0) * 10ull / (iters ? iters : 1u));
-    }
-}
-
-// n_wg workgroups, all resident (cooperative launch), iters barrier phases; out: ns per phase,
-// mismatches, failure flag
-hipError_t exec_barrier_probe(u32 *state, int n_wg, int iters, u32 *out3, hipStream_t s)
-{
-    hipError_t e = hipMemsetAsync(state, 0, (64 + (size_t)n_wg) * 4, s);
-    if (e != hipSuccess) return e;
-    u32 it = (u32)iters, lim = 1u << 16;
-    void *args[] = {&state, &it, &lim};
-    e = hipLaunchCooperativeKernel((const void *)k_barrier_probe, dim3((unsigned)n_wg), dim3(WG), args, 0, s);
-    if (e != hipSuccess) return e;
-    u32 h[4];
-    e = hipMemcpyAsync(h, state, 16, hipMemcpyDeviceToHost, s);
-    if (e != hipSuccess) return e;
-    e = hipStreamSynchronize(s);
-    out3[0] = h[3]; out3[1] = h[2]; out3[2] = h[1];
     return e;
 }
 

@@ -29,13 +29,7 @@ __host__ __device__ inline u32 dx_tile_edge(u32 batch_flags, u32 k) { return ((b
 constexpr int ROWS_PER_RED_TILE = 4;  // rows of one row-reduction tile (one wave per row)
 constexpr int WIDE_ADD_ARITY = 9;     // ADD with at least this many operands reduces per row
 constexpr u32 VAL_ALIGN = 64;         // batch blocks start at multiples of 64 floats (256 B)
-constexpr u32 EPI_NONE = 0xffffffffu;
-constexpr u32 EPI_BAD = 0x80000000u;      // set in epi_head while the plan is checked: the pairing does not hold
-constexpr u32 EPI_MAX_MEMBERS = 24;       // members of a chain a GEMM-headed run may absorb
-constexpr u32 EPI_FILE_FLOATS = 8192;     // LDS floats of a run's per-thread value file (32 KB)
-constexpr u32 EPI_LDS_BASE = 4096;        // the file lies behind the GEMM tile's reduction space
-constexpr u32 EPI_MAX_EXT = 8;            // values per (row, unit) a run fetches from outside itself (kept in registers across the product)
-constexpr u32 RUN_STAGE_DESCS = 32;       // descriptors a step kernel stages at a time; a GEMM-headed run fits in one stage
+constexpr u32 RUN_STAGE_DESCS = 32;       // descriptors a step kernel stages at a time
 constexpr u32 CHAIN_LDS_FLOATS = 16384;   // LDS a fused chain may use to hand results from one member to the next (64 KB)
 
 // Descriptor flag bits of a tile inside a fused chain (TileDesc::flags, PullDesc::lflags).
@@ -47,10 +41,7 @@ enum : u32 {
     TF_SRC_LDS = 16u,        // << j: operand slot / consumer edge j is read from the chain's LDS copy
     TF_OUT_LDS = 256u,       // the tile also writes its result to the chain's LDS copy
     TF_GLOBAL_DEP = 512u,    // reads a result of an earlier member of the same chain from global memory
-    TF_SIMPLE = 1024u,       // float4 tile of ADD (<= 4 operands) / CMULT / TANH / SIGMOID / SLICE whose operand rows are all evenly spaced
-    TF_EPI = 2048u           // tile of a GEMM-headed run: the MATVEC tile at its head, or a component-wise member evaluated
-                             // on the head's rows and unit columns right behind it (lds_out / lds_src[] are then segment
-                             // indices of the run's per-thread value file, pad = Hs | q << 24)
+    TF_SIMPLE = 1024u        // float4 tile of ADD (<= 4 operands) / CMULT / TANH / SIGMOID / SLICE whose operand rows are all evenly spaced
 };
 
 // Kinds of consumer-edge records read by the backward pull (one per graph edge).
@@ -162,12 +153,9 @@ struct WorkRec { u32 first, len; };   // a workgroup runs tiles [first, first + 
 // lds_need: floats of LDS the slot's fused chains use to hand results on (0: none); the step
 // kernels are launched with that much dynamic LDS (and at least their GEMM reduction space), so
 // slots without such chains keep more workgroups resident per CU.
-// plain bit 0: every forward work item of the slot is component-wise (no GEMM, reduction or wide-sum
-// tile), so the slot can run the lean instantiation of the forward kernel; bit 1: the slot holds no
-// GEMM-headed run (cleared: it needs the instantiation that carries the run code).
-// lminf / nlmaxf: the same pair of run lengths over the slot's forward work items alone (a GEMM-headed run has
-// forward items of its own length and leaves the chain it absorbed without forward work).
-struct SlotRec { u32 wf, wa, tb, tf, ta, lmin, nlmax, dx_free, lds_need, plain, lminf, nlmaxf; };
+// plain != 0: every forward work item of the slot is component-wise (no GEMM, reduction or wide-sum
+// tile), so the slot can run the lean instantiation of the forward kernel.
+struct SlotRec { u32 wf, wa, tb, tf, ta, lmin, nlmax, dx_free, lds_need, plain, pad0, pad1; };
 
 // Static tile of the deferred parameter-gradient kernels (built on the host per parameter set).
 struct PTile { i32 param; i32 i0, j0; i32 pad; };
@@ -215,12 +203,6 @@ struct Tables {
     u32 *slot_of; u32 *label_of; u32 *lorder;
     u32 *blevel;           // per batch: its step (depth mode) or its level inside its fused chain (agenda mode)
     u32 *chain_of_batch;   // per batch: index of its launch chain
-    u32 *epi_head;         // per chain: a MATVEC chain whose tiles also evaluate this chain's forward work (EPI_NONE: the chain has its own)
-    u32 *epi_tail;         // per chain: the fused chain this MATVEC chain evaluates behind each of its tiles (EPI_NONE: none)
-    u32 *epi_map;          // per MATVEC chain with a tail: a | s << 16 | x << 24: row i of the product belongs to group a + s * i of the
-                           // tail; x = values per (row, unit) that the run reads from outside itself
-    u32 *epi_cnt;          // per chain: products that found it
-    u32 *epi_chk;          // per chain: (slot << 8 | s) + 1 of its first product, EPI_BAD once two disagree
     ChainRec *chains; CLay *clay; u32 *chain_of_lpos;
     SlotRec *slots;
     WorkRec *works_f; WorkRec *works_a;
@@ -260,5 +242,4 @@ hipError_t exec_stage_fill(const float *V, const u32 *val_off, const u32 *src, c
                            float *payload, hipStream_t s);
 hipError_t exec_launch_probe(float *scratch, int n, int touch, float *us_per_launch, hipStream_t s);
 hipError_t exec_sgd(const ParamDesc *params_dev, u32 n_params, size_t max_count, float lr, int zero_grad, hipStream_t s);
-hipError_t exec_barrier_probe(u32 *state, int n_wg, int iters, u32 *out3, hipStream_t s);
 hipError_t exec_test_gemm(int M, int N, int K, const float *A, const float *B, float *C, hipStream_t s);

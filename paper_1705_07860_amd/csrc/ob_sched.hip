@@ -142,12 +142,32 @@ __global__ __launch_bounds__(FRONTIER_THREADS) void k_depth_frontier(Tables T, c
 // waits for lower ranges and the lowest never waits, whenever each workgroup happens to start (a
 // range reads its nodes' external counts from the fixed copy, never from the counters that lower
 // ranges are already taking down); every wait is bounded.
-constexpr u32 DEPTH_SCAP = 12288;
-constexpr u32 DEPTH_THREADS = 256;    // a range's frontier is small: four waves keep the barriers cheap     // successor entries of a range held in LDS
+constexpr u32 DEPTH_SCAP = 12288;     // successor entries of a range held in LDS
+constexpr u32 DEPTH_THREADS = 256;    // set-up and write-out; the level loop itself runs on one wave
 constexpr u32 DEPTH_MAX_PARTS = 240;
-constexpr u32 DEPTH_SPIN_LIMIT = 1u << 21;
+constexpr u32 DEPTH_NONE = 0xffffffffu;
+
+// one successor of a frontier node: raise its depth bound, take one dependency off; true when it was the last
+__device__ inline bool depth_resolve(u32 sn, u32 d1, u32 lo, u32 hi, u32 *s_dep, u32 *s_pending, const Tables &T, u32 *g_dep,
+                                     u32 *inbox, u32 *inbox_tail)
+{
+    if (sn < hi) {   // successors have larger ids than their producer, so sn >= lo
+        const u32 sl = sn - lo;
+        atomicMax(&s_dep[sl], d1);
+        return atomicSub(&s_pending[sl], 1u) == 1u;
+    }
+    atomicMax(&g_dep[sn], d1);
+    __threadfence();
+    if (atomicSub(&T.ext_left[sn], 1u) == 1u) {
+        const u32 k2 = sn / DEPTH_PART;
+        const u32 slot = atomicAdd(&inbox_tail[k2], 1u);
+        __hip_atomic_store(&inbox[k2 * DEPTH_PART + slot], sn, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    return false;
+}
+
 __global__ __launch_bounds__(DEPTH_THREADS) void k_depth_partitioned(Tables T, const u32 *succ_node, u32 *g_dep,
-                                                                         u32 *inbox, u32 *inbox_tail)
+                                                                         u32 *inbox, u32 *inbox_tail, u32 spin_limit)
 {
     __shared__ u32 s_pending[DEPTH_PART];
     __shared__ u32 s_dep[DEPTH_PART];
@@ -178,10 +198,13 @@ __global__ __launch_bounds__(DEPTH_THREADS) void k_depth_partitioned(Tables T, c
     __syncthreads();
     // The frontier of a range is small (tens of nodes per level), so after the cooperative set-up
     // one wave runs the loop alone: its LDS operations complete in program order, the loop state
-    // sits in registers, and no workgroup barrier is needed between levels.  The other waves wait
-    // at the barrier behind the loop and help with the write-out.
+    // (head, tail, counters) sits in scalar registers, new frontier entries get their queue
+    // positions from a ballot instead of an LDS counter, and a level costs four dependent LDS
+    // round trips (queue entry; depth and successor range; up to four successors at once; their
+    // counters).  The other waves wait at the barrier behind the loop and help with the write-out.
     if (tid < 64) {
         const u32 lane = tid;
+        const u64 lt_mask = (1ull << lane) - 1ull;
         u32 head = 0, tail = __builtin_amdgcn_readfirstlane(s_next), done = 0, seen = 0, avail = 0, spin = 0, iter = 0;
         while (!(head == tail && done == cnt)) {
             // The inbox counter lives in coherent memory: look at it only when the frontier is
@@ -190,52 +213,60 @@ __global__ __launch_bounds__(DEPTH_THREADS) void k_depth_partitioned(Tables T, c
             if (head == tail || (iter & 7u) == 0)
                 avail = __builtin_amdgcn_readfirstlane(__hip_atomic_load(&inbox_tail[k], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
             ++iter;
-            for (u32 i = head + lane; i < tail; i += 64) {
-                const u32 ul = s_queue[i];
-                const u32 d = s_dep[ul];
-                const u32 e1 = s_soff[ul + 1];
-                for (u32 e = s_soff[ul]; e < e1; ++e) {
-                    const u32 sn = e < DEPTH_SCAP ? s_snode[e] : succ_node[ebase + e];
-                    if (sn < hi) {   // successors have larger ids than u, so sn >= lo
-                        const u32 sl = sn - lo;
-                        atomicMax(&s_dep[sl], d + 1);
-                        if (atomicSub(&s_pending[sl], 1u) == 1u) s_queue[atomicAdd(&s_next, 1u)] = (unsigned short)sl;
-                    } else {
-                        atomicMax(&g_dep[sn], d + 1);
-                        __threadfence();
-                        if (atomicSub(&T.ext_left[sn], 1u) == 1u) {
-                            const u32 k2 = sn / DEPTH_PART;
-                            const u32 slot = atomicAdd(&inbox_tail[k2], 1u);
-                            __hip_atomic_store(&inbox[k2 * DEPTH_PART + slot], sn, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
-                        }
+            u32 new_tail = tail;
+            for (u32 base = head; base < tail; base += 64) {
+                const u32 i = base + lane;
+                const bool act = i < tail;
+                const u32 ul = act ? s_queue[i] : 0u;
+                const u32 d1 = s_dep[ul] + 1u;
+                u32 e = s_soff[ul];
+                const u32 e1 = act ? s_soff[ul + 1] : e;
+                while (__ballot(e < e1) != 0ull) {
+                    u32 sn[4];
+#pragma unroll
+                    for (u32 j = 0; j < 4; ++j)
+                        sn[j] = e + j < e1 ? (e + j < DEPTH_SCAP ? s_snode[e + j] : succ_node[ebase + e + j]) : DEPTH_NONE;
+                    bool ready[4];
+#pragma unroll
+                    for (u32 j = 0; j < 4; ++j)
+                        ready[j] = sn[j] != DEPTH_NONE && depth_resolve(sn[j], d1, lo, hi, s_dep, s_pending, T, g_dep, inbox, inbox_tail);
+#pragma unroll
+                    for (u32 j = 0; j < 4; ++j) {
+                        const u64 m = __ballot(ready[j]);
+                        if (ready[j]) s_queue[new_tail + (u32)__popcll(m & lt_mask)] = (unsigned short)(sn[j] - lo);
+                        new_tail += (u32)__popcll(m);
                     }
+                    e += 4;
                 }
             }
             __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
             // inbox entries are posted after their slot is reserved: take them in order, stop at a hole
             while (seen < avail) {
                 const u32 j = seen + lane;
-                u32 sn = 0xffffffffu;
+                u32 sn = DEPTH_NONE;
                 if (j < avail) sn = __hip_atomic_load(&inbox[k * DEPTH_PART + j], __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_AGENT);
                 const u32 in_chunk = avail - seen < 64u ? avail - seen : 64u;
-                const u64 holes = __ballot(j < avail && sn == 0xffffffffu);
+                const u64 holes = __ballot(j < avail && sn == DEPTH_NONE);
                 const u32 good = holes ? (u32)__builtin_ctzll(holes) : in_chunk;
+                bool ready = false;
                 if (lane < good) {
                     const u32 sl = sn - lo;
                     atomicMax(&s_dep[sl], __hip_atomic_load(&g_dep[sn], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
-                    if (atomicSub(&s_pending[sl], 1u) == 1u) s_queue[atomicAdd(&s_next, 1u)] = (unsigned short)sl;
+                    ready = atomicSub(&s_pending[sl], 1u) == 1u;
                 }
+                const u64 m = __ballot(ready);
+                if (ready) s_queue[new_tail + (u32)__popcll(m & lt_mask)] = (unsigned short)(sn - lo);
+                new_tail += (u32)__popcll(m);
                 seen += good;
                 if (holes) break;
             }
             __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
-            const u32 new_tail = __builtin_amdgcn_readfirstlane(s_next);
             done += tail - head;
             const bool idle = head == tail && new_tail == tail;   // nothing to do: waiting for another range
             head = tail;
             tail = new_tail;
             if (idle) {
-                if (++spin > DEPTH_SPIN_LIMIT) break;
+                if (++spin > spin_limit) break;     // bounded: the host then runs the single-workgroup pass instead
                 __builtin_amdgcn_s_sleep(8);
             } else {
                 spin = 0;
@@ -391,8 +422,10 @@ __global__ void k_class_of(Tables T, AgendaTables A)
     if (v >= T.n) return;
     const u32 rank = A.rank_of[T.ht_slot[v]];
     A.cls[v] = rank;
-    if (T.indeg[v] >> AG_COUNT_BITS) atomicOr(&T.hdr->err, (u32)ERR_CLASSES);
-    A.pending[v] = (rank << AG_COUNT_BITS) | T.indeg[v];
+    // the operand count comes from the graph itself: the single-workgroup depth pass counts T.indeg down to zero
+    const u32 arity = T.in_off[v + 1] - T.in_off[v];
+    if (arity >> AG_COUNT_BITS) atomicOr(&T.hdr->err, (u32)ERR_CLASSES);
+    A.pending[v] = (rank << AG_COUNT_BITS) | arity;
 }
 
 // One workgroup runs the agenda.  head / tail of every rank's ready list live in LDS; the lists
@@ -594,7 +627,9 @@ __global__ void k_member_check(Tables T)
     if (r.op == OP_INPUT) vec = vec && ((u32)T.aux0[v] & 3u) == 0;
     if (!same) atomicOr(&T.hdr->err, (u32)ERR_COLLISION);
     if (!vec) atomicAnd(&r.vec4, ~(u32)TF_VEC4);
-    if (r.op == OP_MATVEC && (T.outdeg[v] != 1 || v == T.root)) atomicAnd(&r.vec4, ~(u32)TF_G_ALIAS);
+    // A one-element MATVEC node may become the backward root (chosen after scheduling): its gradient is
+    // the seed, not its consumer's row, so such batches never alias.
+    if (r.op == OP_MATVEC && (T.outdeg[v] != 1 || r.d == 1)) atomicAnd(&r.vec4, ~(u32)TF_G_ALIAS);
 }
 
 // Per edge: operand row offsets per batch (slot-major), operand dimensions of the batch, the
@@ -839,7 +874,6 @@ __global__ void k_chain_recs(Tables T, int agenda, const u32 *bset, const u32 *f
         const u32 c = flag_excl[i] + flag[i] - 1;
         T.chain_of_lpos[i] = c;
         T.chain_of_batch[T.lorder[i]] = c;   // (a chain's members may still be reordered below: same chain)
-        T.epi_head[i] = EPI_NONE; T.epi_tail[i] = EPI_NONE; T.epi_cnt[i] = 0; T.epi_chk[i] = 0; T.epi_map[i] = 0;
         if (i == nb - 1) T.hdr->n_chains = c + 1;
     }
     if (i < nb && flag[i]) {
@@ -929,189 +963,6 @@ __global__ void k_clay_zero(CLay *clay_in, u32 n_pad)
 // floats of a fused chain's LDS copy taken by one member: its rows of a block of groups, rounded up to 4
 __device__ inline u32 chain_region(const ChainRec &cr, const BatchRec &r) { return (cr.Rg * (r.B / cr.G) * r.d + 3u) & ~3u; }
 
-// ---- GEMM-headed runs ---------------------------------------------------------------------------
-// A recurrence step is a matrix product followed by a chain of component-wise batches that reads
-// it row for row (the LSTM cell behind W_h h).  The product's 32 x 32 tiles and the chain's row
-// blocks cut the same data in different directions, which is why the chain waits for a launch
-// boundary.  If every member of the chain has the product's row count and a width that is a
-// multiple of Hs = the narrowest member's width, and wide members are only ever read through
-// slices at multiples of Hs, then element (row, unit u) of every member depends only on elements
-// (row, u + s * Hs) of its operands.  A product tile that covers the columns u0 .. u0 + w - 1 of
-// every one of the q = d / Hs segments (w = 32 / q) then holds all the chain needs for 32 rows x w
-// units, and the workgroup evaluates the whole chain for them right behind the tile, one thread
-// per (row, unit), values handed on through a per-thread file in LDS: the chain's forward work
-// moves into the product's launch and its own launch disappears.  Values, storage and the
-// backward pass do not change.
-//
-// Batches of component-wise nodes carry no parameter, so the cells of several recurrences that
-// run in step (the two directions of a BiLSTM) share their batches: the chain then has one
-// product per recurrence, and row a + s * i of every member belongs to row i of product number a
-// of s.  Every product gets a run of its own over its rows of the chain; the chain's own forward
-// work disappears when its s row classes have all found their product.
-//
-// One wave per chain looks for the pairing (product chain P -> consumer chain C) and checks it.
-__device__ inline bool epi_member_op(u32 op, u32 arity)
-{
-    return (op == OP_ADD && arity <= 4) || op == OP_CMULT || op == OP_TANH || op == OP_SIGMOID || op == OP_SLICE;
-}
-
-__global__ void k_epi_find(Tables T)
-{
-    const u32 c = (blockIdx.x * blockDim.x + threadIdx.x) >> 6;
-    const u32 lane = threadIdx.x & 63;
-    if (c >= T.hdr->n_chains || T.hdr->p0) return;
-    const ChainRec cp = T.chains[c];
-    if (cp.fused || cp.k != 1) return;
-    const u32 pb = T.lorder[cp.first];
-    const BatchRec P = T.batches[pb];
-    if (P.op != OP_MATVEC || (P.vec4 & TF_WIDE) || (P.d & 31u) || P.B > 4096u) return;
-    if (P.B < 16u) { if (lane == 0) T.epi_map[c] = 0xE0000000u | 21u; return; }   // keeps the tile list within the host's bound
-    // every row of P has one consumer; all consumers lie in one batch y of a fused chain with G
-    // groups (a group = the rows of one recurrence cell; y may hold several rows per group): row i
-    // of P feeds group a + s * i, s = G / rows of P, always at the same place ty inside the group
-    u32 yb = EPI_NONE, a = 0, st = 1, ty = 0, my = 1;
-    {
-        u32 mine = EPI_NONE, row = 0;
-        bool fine = true;
-        if (lane == 0) {
-            const u32 u = T.order[P.pos0];
-            const u32 q0 = T.succ_off[u];
-            fine = T.succ_off[u + 1] - q0 == 1u;
-            if (fine) {
-                const u32 pv = T.pos_of[T.edge_cons[T.succ_edge[q0]]];
-                mine = T.batch_of_pos[pv];
-                row = pv - T.batches[mine].pos0;
-            }
-        }
-        yb = __builtin_amdgcn_readfirstlane(mine);
-        a = __builtin_amdgcn_readfirstlane(row);
-        if (yb == EPI_NONE) { if (lane == 0) T.epi_map[c] = 0xE0000000u | 1u; return; }
-        const ChainRec cy = T.chains[T.chain_of_batch[yb]];
-        const u32 By = T.batches[yb].B;
-        if (!cy.fused || cy.G % P.B || By % cy.G) { if (lane == 0) T.epi_map[c] = 0xE0000000u | 2u; return; }
-        st = cy.G / P.B;
-        my = By / cy.G;
-        ty = a % my;
-        a = a / my;
-        if (a >= st || st > 255u) { if (lane == 0) T.epi_map[c] = 0xE0000000u | 3u; return; }
-    }
-    for (u32 i0 = 0; i0 < P.B; i0 += 64) {
-        const u32 i = i0 + lane;
-        bool fine = true;
-        if (i < P.B) {
-            const u32 u = T.order[P.pos0 + i];
-            const u32 q0 = T.succ_off[u];
-            fine = T.succ_off[u + 1] - q0 == 1u;
-            if (fine) {
-                const u32 pv = T.pos_of[T.edge_cons[T.succ_edge[q0]]];
-                fine = T.batch_of_pos[pv] == yb && pv - T.batches[yb].pos0 == (a + st * i) * my + ty;
-            }
-        }
-        if (__ballot(!fine) != 0ull) { if (lane == 0) T.epi_map[c] = 0xE0000000u | 4u; return; }
-    }
-    const u32 cc = T.chain_of_batch[yb];
-    const ChainRec cr = T.chains[cc];
-    if (!cr.fused || cr.k > EPI_MAX_MEMBERS || cr.slot <= cp.slot) { if (lane == 0) T.epi_map[c] = 0xE0000000u | 5u; return; }
-    // members: row count, operations, widths
-    u32 Hs = 0xffffffffu;
-    for (u32 m = 0; m < cr.k; ++m) {
-        const BatchRec &r = T.batches[T.lorder[cr.first + m]];
-        if (r.B % cr.G || !epi_member_op(r.op, r.arity)) { if (lane == 0) T.epi_map[c] = 0xE0000000u | 6u; return; }
-        Hs = r.d < Hs ? r.d : Hs;
-    }
-    if (1u + cr.kt > RUN_STAGE_DESCS) { if (lane == 0) T.epi_map[c] = 0xE0000000u | 18u; return; }
-    if (Hs == 0 || P.d % Hs) { if (lane == 0) T.epi_map[c] = 0xE0000000u | 7u; return; }
-    const u32 q = P.d / Hs;
-    if (q != 1 && q != 2 && q != 4) { if (lane == 0) T.epi_map[c] = 0xE0000000u | 8u; return; }
-    const u32 w = 32u / q;
-    if (Hs % w) { if (lane == 0) T.epi_map[c] = 0xE0000000u | 9u; return; }
-    u32 segs = q;
-    for (u32 m = 0; m < cr.k; ++m) {
-        const BatchRec &r = T.batches[T.lorder[cr.first + m]];
-        if (r.d % Hs || r.d / Hs > 4u) { if (lane == 0) T.epi_map[c] = 0xE0000000u | 10u; return; }
-        if (r.op == OP_SLICE && ((u32)r.aux0 % Hs)) { if (lane == 0) T.epi_map[c] = 0xE0000000u | 11u; return; }
-        segs += (r.B / cr.G) * (r.d / Hs);
-    }
-    if (segs * 32u * w > EPI_FILE_FLOATS) { if (lane == 0) T.epi_map[c] = 0xE0000000u | 12u; return; }
-    // operands of this product's groups: every slot of every row of a group reads, for all of
-    // these groups alike, one row of the same group of an earlier member, or row i of P, or a value
-    // that is complete before P's slot (the run executes in P's slot, ahead of the chain's own)
-    u32 n_ext = 0;
-    for (u32 m = 0; m < cr.k; ++m) {
-        const BatchRec &r = T.batches[T.lorder[cr.first + m]];
-        const u32 mult = r.B / cr.G;
-        for (u32 t = 0; t < mult; ++t)
-            for (u32 j = 0; j < r.arity; ++j) {
-                const u32 *op = T.opnd_off + r.opnd + j * r.B;
-                const u32 dj = T.b_indim[r.indim + j];
-                if (r.op != OP_SLICE && dj != r.d) { if (lane == 0) T.epi_map[c] = 0xE0000000u | 13u; return; }
-                if (r.op == OP_SLICE && (dj % Hs || dj / Hs > 4u)) { if (lane == 0) T.epi_map[c] = 0xE0000000u | 14u; return; }
-                // the first of these groups decides which case this slot is
-                const u32 o0 = op[a * mult + t];
-                u32 src_off = EPI_NONE, src_d = 0, src_mult = 1, src_t = 0;
-                bool from_p = false;
-                if (o0 >= P.val_off && o0 < P.val_off + P.B * P.d) { from_p = true; src_d = P.d; }
-                for (u32 mm = 0; mm < cr.k; ++mm) {
-                    const BatchRec &y = T.batches[T.lorder[cr.first + mm]];
-                    if (o0 >= y.val_off && o0 < y.val_off + y.B * y.d) {
-                        if (mm >= m) { if (lane == 0) T.epi_map[c] = 0xE0000000u | 15u; return; }   // not an order one thread can follow
-                        src_off = y.val_off; src_d = y.d; src_mult = y.B / cr.G;
-                        const u32 prow = (o0 - y.val_off) / y.d;
-                        if (prow / src_mult != a) { if (lane == 0) T.epi_map[c] = 0xE0000000u | 19u; return; }
-                        src_t = prow % src_mult;
-                    }
-                }
-                if ((from_p || src_off != EPI_NONE) && src_d != dj) { if (lane == 0) T.epi_map[c] = 0xE0000000u | 16u; return; }
-                if (!from_p && src_off == EPI_NONE) n_ext += r.d / Hs;
-                bool bad = false;
-                for (u32 i0 = 0; i0 < P.B; i0 += 64) {
-                    const u32 i = i0 + lane;
-                    if (i >= P.B) continue;
-                    const u32 grp = a + st * i;
-                    const u32 row = grp * mult + t;
-                    const u32 o = op[row];
-                    if (from_p) {
-                        bad = bad || o != P.val_off + i * P.d;
-                    } else if (src_off != EPI_NONE) {
-                        bad = bad || o != src_off + (grp * src_mult + src_t) * src_d;
-                    } else {
-                        const u32 v = T.order[r.pos0 + row];
-                        const u32 by = T.batch_of_pos[T.pos_of[T.in_idx[T.in_off[v] + j]]];
-                        bad = bad || T.slot_of[by] >= cp.slot;
-                    }
-                }
-                if (__ballot(bad) != 0ull) { if (lane == 0) T.epi_map[c] = 0xE0000000u | 17u; return; }
-            }
-    }
-    if (n_ext > EPI_MAX_EXT || (segs + n_ext) * 32u * w > EPI_FILE_FLOATS) { if (lane == 0) T.epi_map[c] = 0xE0000000u | 20u; return; }
-    if (lane == 0) {
-        // all products of a chain must agree on the slot and on s; the chain counts them
-        const u32 chk = ((cp.slot << 8) | st) + 1u;
-        const u32 old = atomicCAS(&T.epi_chk[cc], 0u, chk);
-        if (old != 0u && old != chk) atomicOr(&T.epi_chk[cc], EPI_BAD);
-        T.epi_tail[c] = cc;
-        T.epi_map[c] = a | (st << 16) | (n_ext << 24);
-        atomicAdd(&T.epi_cnt[cc], 1u);
-    }
-}
-
-// Per chain: a pairing holds when the chain's row classes all found their product; then the
-// chain's forward work moves into the products' tile lists.
-__global__ void k_epi_apply(Tables T, CLay *clay_in)
-{
-    const u32 c = blockIdx.x * blockDim.x + threadIdx.x;
-    if (c >= T.hdr->n_chains) return;
-    const u32 cc = T.epi_tail[c];
-    if (cc == EPI_NONE) return;
-    const u32 st = (T.epi_map[c] >> 16) & 0xffu;
-    const u32 chk = T.epi_chk[cc];
-    if ((chk & EPI_BAD) || T.epi_cnt[cc] != st) { T.epi_tail[c] = EPI_NONE; return; }
-    clay_in[c].tf = clay_in[c].wf * (1u + T.chains[cc].kt);   // the product tile, then every row of a group of every member
-    clay_in[cc].tf = 0;     // (every product of the chain writes the same)
-    clay_in[cc].wf = 0;
-    T.epi_head[cc] = c;
-}
-
 // every entry a plan can use (n_slots + 1 <= n + 2) starts out as "no batch here"
 __global__ void k_slot_init(Tables T)
 {
@@ -1119,7 +970,6 @@ __global__ void k_slot_init(Tables T)
     if (s > T.hdr->n_slots) return;
     SlotRec r; r.wf = r.wa = r.tb = r.tf = r.ta = r.lmin = r.nlmax = r.dx_free = 0xffffffffu;
     r.lds_need = 0;
-    r.lminf = r.nlmaxf = 0xffffffffu;
     r.plain = 0xffffffffu;
     T.slots[s] = r;
 }
@@ -1146,29 +996,6 @@ __global__ void k_slot_tables(Tables T, const CLay *clay_ex, const CLay *total)
     const u32 len = cr.fused ? cr.kt : 1u;
     atomicMin(&S.lmin, len);
     atomicMin(&S.nlmax, ~len);
-    // forward run lengths: a GEMM-headed run has its own, the chain it absorbed has no forward work
-    if (T.epi_head[c] == EPI_NONE) {
-        u32 lenf = len;
-        const u32 tail = T.epi_tail[c];
-        if (tail != EPI_NONE) {
-            const ChainRec ct = T.chains[tail];
-            lenf = 1u + ct.kt;
-            const BatchRec &P = T.batches[T.lorder[cr.first]];
-            u32 Hs = 0xffffffffu, segs = 0;
-            for (u32 m = 0; m < ct.k; ++m) { const u32 dm = T.batches[T.lorder[ct.first + m]].d; Hs = dm < Hs ? dm : Hs; }
-            const u32 q = P.d / Hs;
-            segs = q;
-            for (u32 m = 0; m < ct.k; ++m) {
-                const BatchRec &rm = T.batches[T.lorder[ct.first + m]];
-                segs += (rm.B / ct.G) * (rm.d / Hs);
-            }
-            segs += T.epi_map[c] >> 24;   // values fetched from outside the run
-            atomicMax(&S.lds_need, (u32)EPI_LDS_BASE + segs * 32u * (32u / q));
-            atomicAnd(&S.plain, ~2u);   // the slot needs the forward kernel that carries the run code
-        }
-        atomicMin(&S.lminf, lenf);
-        atomicMin(&S.nlmaxf, ~lenf);
-    }
     if (c == nc - 1) {
         const CLay t = *total;
         SlotRec &E = T.slots[s + 1];
@@ -1430,71 +1257,13 @@ __global__ void k_tiles(Tables T, const CLay *clay_ex, const CLay *total, u32 ca
             const u32 c = chain_of_index(clay_ex, nc, which, x);
             const ChainRec cr = T.chains[c];
             const u32 xx = x - clay_field(clay_ex[c], which);
-            const u32 tail = T.epi_tail[c];
-            if (which >= 3) {   // work item = one block of a fused chain, one tile, or one GEMM-headed run
+            if (which >= 3) {   // work item = one block of a fused chain, or one tile
                 WorkRec w;
                 const bool fwd = which == 3;
-                u32 len = cr.fused ? cr.kt : 1u;
-                if (fwd && tail != EPI_NONE) len = 1u + T.chains[tail].kt;
+                const u32 len = cr.fused ? cr.kt : 1u;
                 w.first = (fwd ? clay_ex[c].tf : clay_ex[c].ta) + xx * len;
                 w.len = len;
                 (fwd ? T.works_f : T.works_a)[x] = w;
-            } else if (which == 0 && tail != EPI_NONE) {
-                // GEMM-headed run: the product tile, then every member of the absorbed chain on the
-                // tile's rows; the member descriptors say where operands sit in the run's value file
-                const ChainRec ct = T.chains[tail];
-                const u32 per = 1u + ct.kt;
-                const u32 item = xx / per, sub = xx % per;
-                const BatchRec P = T.batches[T.lorder[cr.first]];
-                u32 Hs = 0xffffffffu;
-                for (u32 m = 0; m < ct.k; ++m) { const u32 dm = T.batches[T.lorder[ct.first + m]].d; Hs = dm < Hs ? dm : Hs; }
-                const u32 q = P.d / Hs;
-                TileDesc d;
-                if (sub == 0) {
-                    fill_tile_desc(T, P, item, false, false, 0, 0, 1, d);
-                    d.flags |= TF_EPI;
-                    u32 segs = q;   // file segments of the product and of all members: values from outside come behind them
-                    for (u32 m = 0; m < ct.k; ++m) {
-                        const BatchRec &rm = T.batches[T.lorder[ct.first + m]];
-                        segs += (rm.B / ct.G) * (rm.d / Hs);
-                    }
-                    d.lds_out = segs;
-                } else {
-                    // row `it` of every group of member m; its values take the file segments from `seg` on
-                    u32 m = 0, it = sub - 1, mult = 1, seg = q;
-                    for (;; ++m) {
-                        const BatchRec &rm = T.batches[T.lorder[ct.first + m]];
-                        mult = rm.B / ct.G;
-                        if (it < mult) { seg += it * (rm.d / Hs); break; }
-                        it -= mult;
-                        seg += mult * (rm.d / Hs);
-                    }
-                    const BatchRec r = T.batches[T.lorder[ct.first + m]];
-                    const u32 ntn = P.d / 32u;
-                    const u32 pr0 = (item / ntn) * 32u;                       // first row of the product tile
-                    const u32 nr = P.B - pr0 < 32u ? P.B - pr0 : 32u;
-                    const u32 ma = T.epi_map[c] & 0xffffu, ms = (T.epi_map[c] >> 16) & 0xffu;
-                    const u32 g0 = ma + ms * pr0;                             // its group of the chain
-                    fill_tile_desc(T, r, item, false, true, g0 * mult + it, nr, ms * mult, d);
-                    d.flags = (d.flags & ~(u32)TF_SIMPLE) | TF_EPI;
-                    d.lds_out = seg;
-                    for (u32 j = 0; j < r.arity && j < 4; ++j) {
-                        if (d.base[j] >= P.val_off && d.base[j] < P.val_off + P.B * P.d) { d.flags |= TF_SRC_LDS << j; d.lds_src[j] = 0; }
-                        u32 sb = q;
-                        for (u32 mm = 0; mm < m; ++mm) {
-                            const BatchRec &y = T.batches[T.lorder[ct.first + mm]];
-                            const u32 ym = y.B / ct.G;
-                            if (d.base[j] >= y.val_off && d.base[j] < y.val_off + y.B * y.d) {
-                                const u32 prow = (d.base[j] - y.val_off) / y.d;     // = g0 * ym + its place in the group
-                                d.flags |= TF_SRC_LDS << j;
-                                d.lds_src[j] = sb + (prow - g0 * ym) * (y.d / Hs);
-                            }
-                            sb += ym * (y.d / Hs);
-                        }
-                    }
-                }
-                d.pad = Hs | (q << 24);
-                T.tiles_f[x] = d;
             } else if (which == 2 || (which == 0 && !cr.fused)) {
                 const BatchRec r = T.batches[T.lorder[cr.first]];
                 TileDesc d;
@@ -1659,7 +1428,12 @@ int sched_enqueue(ob_ctx *ctx)
     ctx->n_launch_sched = 0;
 
     const size_t maxne = (size_t)(n > E ? n : E) + 1;
-    u32 n_items = ctx->items_upto[n - 1];
+    u32 n_items = ctx->n_items_total;
+    if ((size_t)n != ctx->op.size()) {   // a prefix of the graph: count its parameter uses
+        n_items = 0;
+        for (u32 v = 0; v < n; ++v)
+            n_items += ctx->op[v] == OP_MATVEC ? 1u + (ctx->bias[v] >= 0 ? 1u : 0u) : (ctx->op[v] == OP_LOOKUP ? 1u : 0u);
+    }
     const size_t n_slots = (size_t)ctx->params.size() * 4 + 4;
 
     // ---- allocation (all from the caller's arena) ----
@@ -1668,9 +1442,7 @@ int sched_enqueue(ob_ctx *ctx)
     if (!by_depth) ht_size = 1;
     // upper bounds of the three tile lists from sums the host keeps while nodes are added
     // (a node contributes at most one component-wise / reduction tile; MATVEC nodes their GEMM tiles)
-    // (a GEMM-headed run repeats up to 31 member descriptors behind every product tile; with at
-    // least 16 rows in the product that is at most twice the product's own bound)
-    const size_t cap_f = (size_t)n + (size_t)ctx->sum_mv_d32 * (ctx->fuse >= 3 ? 2 : 1) + 16;
+    const size_t cap_f = (size_t)n + (size_t)ctx->sum_mv_d32 + 16;
     const size_t cap_a = (size_t)n + 16;
     const size_t cap_b = (size_t)ctx->sum_mv_k32 + 16;
 #define A(field, type, count)                                               \
@@ -1705,8 +1477,7 @@ int sched_enqueue(ob_ctx *ctx)
     A(T.batch_off, u32, n + 1); A(T.batches, BatchRec, n); A(T.lay, Lay, n); A(T.b_indim, u32, E + 1);
     A(T.val_off, u32, n); A(T.dx_off, u32, n); A(T.opnd_off, u32, E + 1); A(T.dx_gsrc, u32, n);
     A(T.slot_of, u32, n); A(T.label_of, u32, n); A(T.blevel, u32, n);
-    A(T.chain_of_batch, u32, n); A(T.epi_head, u32, n); A(T.epi_tail, u32, n);
-    A(T.epi_map, u32, n); A(T.epi_cnt, u32, n); A(T.epi_chk, u32, n);
+    A(T.chain_of_batch, u32, n);
     A(T.lorder, u32, n); A(T.chains, ChainRec, n); A(T.clay, CLay, n); A(T.chain_of_lpos, u32, n);
     // a plan has at most one slot per node; twice that leaves room for plans that insert slots
     const size_t slot_cap = 2 * (size_t)n + 4;
@@ -1743,7 +1514,8 @@ int sched_enqueue(ob_ctx *ctx)
     // ---- stage 1 ----
     HIP_TRY(ctx, hipMemsetAsync(zero_lo, 0, (size_t)(zero_hi - zero_lo), s));
     HIP_TRY(ctx, hipMemsetAsync(zero_hi, 0xff, (size_t)(ones_hi - zero_hi), s));
-    const bool part_depth = by_depth && n_parts <= DEPTH_MAX_PARTS && ctx->max_arity < 60000;
+    const bool part_depth = by_depth && n_parts <= DEPTH_MAX_PARTS && ctx->max_arity < 60000 && !ctx->force_frontier;
+    ctx->depth_partitioned = part_depth;
     K(k_node_init, n, T, manual ? 2 : by_depth);
     if (E > 0) K(k_edge_init, E, T, ctx->key_a, ctx->val_a);
     HIP_TRY(ctx, prim_scan_u32(T.outdeg, T.succ_off, (size_t)n + 1, nullptr, ctx->scratch, s));
@@ -1759,7 +1531,7 @@ int sched_enqueue(ob_ctx *ctx)
     if (by_depth) {
         if (part_depth)
             hipLaunchKernelGGL(k_depth_partitioned, dim3(n_parts), dim3(DEPTH_THREADS), 0, s, T, succ_node, g_dep, inbox,
-                               inbox_tail);
+                               inbox_tail, ctx->depth_spin_limit);
         else
             hipLaunchKernelGGL(k_depth_frontier, dim3(1), dim3(FRONTIER_THREADS), 0, s, T, succ_node);
         ++ctx->n_launch_sched;
@@ -1804,7 +1576,7 @@ int sched_enqueue(ob_ctx *ctx)
     // ---- launch planning: slots, chains, tile descriptors ----
     const int fuse = batched && ctx->fuse;
     if (fuse && E > 0) K(k_bedges, E, T, bset, blist);
-    hipLaunchKernelGGL(k_slots, dim3(1), dim3(SLOT_THREADS), 0, s, T, (fuse && E > 0) ? (ctx->fuse > 2 ? 2 : ctx->fuse) : 0, blist);
+    hipLaunchKernelGGL(k_slots, dim3(1), dim3(SLOT_THREADS), 0, s, T, (fuse && E > 0) ? ctx->fuse : 0, blist);
     ++ctx->n_launch_sched;
     K(k_launch_keys, n, T, ctx->key_a, ctx->val_a, n);
     if (fuse && E > 0) {
@@ -1818,11 +1590,6 @@ int sched_enqueue(ob_ctx *ctx)
     HIP_TRY(ctx, prim_scan_u32(cflag, cflag_excl, n, nullptr, ctx->scratch, s));
     K(k_clay_zero, n, clay_in, n);
     K(k_chain_recs, n, T, agenda || manual, bset, cflag, cflag_excl, clay_in, n);
-    if (fuse && ctx->fuse >= 3 && E > 0) {
-        const size_t max_chains = n < SLOT_MAX_NB + 1 ? n : SLOT_MAX_NB + 1;   // a fused plan has at most that many batches
-        K(k_epi_find, max_chains * 64, T);
-        K(k_epi_apply, max_chains, T, clay_in);
-    }
     HIP_TRY(ctx, prim_scan_clay(clay_in, T.clay, n, clay_total, ctx->scratch, s));
     ctx->n_launch_sched += 2 * scan_launches;
     K(k_slot_init, (size_t)n + 2, T);
@@ -1872,9 +1639,25 @@ int sched_finish(ob_ctx *ctx)
     HIP_TRY(ctx, hipEventSynchronize(ctx->ev[9]));
     const char *hp = (const char *)ctx->hdr_pinned;
     ctx->hdr = *(const SchedHeader *)hp;
+    if ((ctx->hdr.err & ERR_CYCLE) && ctx->depth_partitioned) {
+        // A range of the partitioned depth pass ran into the bound on its wait for another range.
+        // Node ids are a topological order (checked when nodes are added), so the graph has no
+        // cycle: schedule once more with the single-workgroup pass, which waits for nothing.
+        ++ctx->n_depth_retries;
+        ctx->force_frontier = true;
+        ctx->top = ctx->graph_top;
+        int rc = sched_enqueue(ctx);
+        ctx->force_frontier = false;
+        if (rc) return rc;
+        HIP_TRY(ctx, hipEventRecord(ctx->ev[9], s));
+        HIP_TRY(ctx, hipEventSynchronize(ctx->ev[9]));
+        hp = (const char *)ctx->hdr_pinned;
+        ctx->hdr = *(const SchedHeader *)hp;
+    }
     ctx->hdr.n_items = ctx->n_items_sched;
     if (ctx->hdr.err & ERR_CYCLE)
-        return ctx_fail(ctx, -6, "the depth / agenda pass resolved %u of %u nodes (cyclic or malformed graph)",
+        return ctx_fail(ctx, -6, "%s resolved %u of %u nodes: the graph on the device is cyclic or damaged",
+                        ctx->mode == 2 ? "the single-workgroup depth pass / the agenda" : "the single-workgroup depth pass",
                         ctx->hdr.frontier_done, T.n);
     if (ctx->hdr.err & ERR_COLLISION) return ctx_fail(ctx, -6, "signature hash collision detected");
     if (ctx->hdr.err & ERR_TABLE_FULL) return ctx_fail(ctx, -6, "signature table full");

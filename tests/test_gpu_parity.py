@@ -221,44 +221,11 @@ def test_early_placement_and_launch_plan_invariants(name, workload_cache):
     assert slots[1] == slots[2]     # both placements keep the longest dependency path
 
 
-@pytest.mark.parametrize("name,mode", [("tagger", "depth"), ("parser", "depth"), ("tagger_char", "depth"),
-                                       ("tagger", "agenda"), ("tree", "depth"), ("rnn", "depth")])
-def test_chains_evaluated_behind_their_matrix_product(name, mode, workload_cache):
-    """Fusion level 3 evaluates a recurrence step's component-wise chain behind each tile of the
-    matrix product it reads (Section 3.3: one batched call where many small ones were).  The
-    arithmetic per element is unchanged, so every value and gradient is bit-identical to level 2;
-    the LSTM workloads lose a forward launch per time step; everything matches the oracle."""
-    from paper_1705_07860_amd import binding as ob
-    p, g, o = workload_cache(name)
-    total = int(o.v_off[-1])
-    m = ob.OB_BYDEPTH if mode == "depth" else ob.OB_BYAGENDA
-    out = {}
-    for level in (2, 3):
-        c, root = run_gpu(p, g, m, fuse=level)
-        st = c.stats()
-        vals = c.all_read(0, total)
-        c.backward(root)
-        out[level] = (vals, c.all_read(1, total), [c.param_grad_read(pid, mm.shape) for pid, mm in enumerate(p.mats)],
-                      st["n_launch_fwd"], st["n_slots"])
-        c.close()
-    say(f"  {name}/{mode}: forward launches {out[2][3]} -> {out[3][3]} ({out[3][4]} slots)")
-    assert np.array_equal(out[2][0], out[3][0])
-    assert np.array_equal(out[2][1], out[3][1])
-    for a, b in zip(out[2][2], out[3][2]):
-        assert np.array_equal(a, b)
-    assert out[3][4] == out[2][4] and out[3][3] <= out[2][3]
-    if name in ("tagger", "parser"):
-        assert out[3][3] <= 0.8 * out[2][3]
-    c, root = run_gpu(p, g, m, fuse=3)
-    check_against_oracle(c, p, g, o, root, what=f"{name}/{mode}/level 3")
-    c.close()
-
-
 @pytest.mark.parametrize("rows,H,q", [(20, 32, 2), (37, 16, 2), (16, 64, 1), (45, 8, 4)])
-def test_matrix_product_runs_on_small_gated_cells(rows, H, q):
-    """Fusion level 3 on cells whose product has q = 1, 2 or 4 segments of H columns, with a row
-    count that leaves a ragged last tile: h' = z * h + tanh(n) style cells over `rows` chains, three
-    steps.  Level 3 must pair the later steps, agree bit for bit with level 2 and match the oracle."""
+def test_small_gated_cells_at_every_fusion_level(rows, H, q):
+    """Cells whose matrix product has q = 1, 2 or 4 segments of H columns, with a row count that
+    leaves a ragged last tile: h' = z * h + tanh(n) style cells over `rows` chains, three steps.
+    Every launch-fusion level gives bit-identical results and matches the oracle."""
     from paper_1705_07860_amd import binding as ob
     rng = np.random.default_rng(rows * 100 + H)
     pb = wl.ParamBuilder(rng, std=0.3)
@@ -285,41 +252,37 @@ def test_matrix_product_runs_on_small_gated_cells(rows, H, q):
     o.backward(g.root)
     total = int(o.v_off[-1])
     out = {}
-    for level in (2, 3):
+    for level in (0, 1, 2):
         c, _ = run_gpu(p, g, ob.OB_BYDEPTH, fuse=level, arena=128 << 20)
         st = c.stats()
-        tails = c.debug_read(ob.OB_DBG_EPI_TAIL)
         vals = c.all_read(0, total)
         c.backward(g.root)
-        out[level] = (vals, c.all_read(1, total), c.param_grad_read(W, p.mats[W].shape), st["n_launch_fwd"],
-                      int((tails != 0xffffffff).sum()))
+        out[level] = (vals, c.all_read(1, total), c.param_grad_read(W, p.mats[W].shape), st["n_launch_fwd"])
         c.close()
-    say(f"  rows {rows} H {H} q {q}: forward launches {out[2][3]} -> {out[3][3]}, paired products {out[3][4]}")
-    # (the first step's chain also holds the batch of all input leaves, so it keeps its own launch)
-    assert out[2][4] == 0 and out[3][4] >= 2
-    assert out[3][3] == out[2][3] - out[3][4]
+    say(f"  rows {rows} H {H} q {q}: forward launches {out[0][3]} / {out[1][3]} / {out[2][3]}")
+    assert out[2][3] <= out[0][3]
     for k in range(3):
-        assert np.array_equal(out[2][k], out[3][k])
-    c, root_ = run_gpu(p, g, ob.OB_BYDEPTH, fuse=3, arena=128 << 20)
+        assert np.array_equal(out[0][k], out[2][k]) and np.array_equal(out[1][k], out[2][k])
+    c, root_ = run_gpu(p, g, ob.OB_BYDEPTH, fuse=2, arena=128 << 20)
     check_against_oracle(c, p, g, o, root_, what=f"gated cells q={q}")
     c.close()
 
 
-@pytest.mark.parametrize("seed", [951, 954, 956, 957, 961, 963])
-def test_random_dags_at_fusion_level_3(seed):
-    """Unstructured graphs of 400 nodes: whatever the pairing test accepts or refuses, results do
-    not change.  (Seeds whose graph holds a loss below 1e-9 are left out: with 400 nodes some
-    predictions get so confident that the reference's logsumexp(x) - x_label rounds to exactly 0 in
-    fp64, which leaves nothing to measure a relative error against.)"""
+@pytest.mark.parametrize("seed", range(950, 964))
+def test_random_dags_of_400_nodes(seed):
+    """Unstructured graphs of 400 nodes, consecutive seeds, nothing left out: some of these graphs
+    hold softmax rows so confident that their loss is below 1e-20 (seed 953: 9.5e-25), and values
+    and gradients still agree with the reference to 1e-4 of their own size at every fusion level."""
     from paper_1705_07860_amd import binding as ob
     dim = (32, 64)[seed % 2]
     p, g = wl.random_dag(seed, n_nodes=400, dim=dim)
     o = Oracle(g, p, "f64")
     o.forward()
     o.backward(g.root)
-    c, root = run_gpu(p, g, ob.OB_BYDEPTH, fuse=3, arena=256 << 20)
-    check_against_oracle(c, p, g, o, root, what=f"dag {seed} level 3")
-    c.close()
+    for level in (2, 0):
+        c, root = run_gpu(p, g, ob.OB_BYDEPTH, fuse=level, arena=256 << 20)
+        check_against_oracle(c, p, g, o, root, what=f"dag {seed} level {level}")
+        c.close()
 
 
 @pytest.mark.parametrize("name", ["tagger", "tree"])
@@ -415,6 +378,94 @@ def test_edge_cases_single_node_and_prefix_forward():
     with pytest.raises(ob.ObError) as e:
         c.value_read(0, 3)                           # capacity too small
     assert e.value.code == -3
+    c.close()
+
+
+def _wide_sum_graph(n_leaves=60500):
+    """A sum over more than 60 000 one-element leaves (some behind a tanh): a node of that arity
+    takes the scheduler off its partitioned depth pass onto the single-workgroup one."""
+    p = wl.Params([], [])
+    rng = np.random.default_rng(77)
+    gb = wl.GraphBuilder(p)
+    xs = [gb.input(rng.standard_normal(1)) for _ in range(n_leaves)]
+    ts = [gb.tanh(x) for x in xs[:200]]
+    ss = [gb.sigmoid(t) for t in ts[:50]]
+    root = gb.add(ss + ts[50:] + xs[200:])
+    return p, gb.finish(root, 1)
+
+
+@pytest.mark.parametrize("mode", ["depth", "agenda"])
+def test_single_workgroup_depth_pass_on_a_very_wide_sum(mode):
+    """The fallback depth pass (taken for nodes with 60 000 or more operands) leaves everything the
+    later stages read intact: schedule bit-exact and values / gradients right in depth and in
+    agenda mode."""
+    from paper_1705_07860_amd import binding as ob
+    p, g = _wide_sum_graph()
+    o = Oracle(g, p, "f64")
+    o.forward()
+    o.backward(g.root)
+    c, root = run_gpu(p, g, ob.OB_BYDEPTH if mode == "depth" else ob.OB_BYAGENDA, arena=1 << 30)
+    bo, ids, bd, _ = c.schedule_read()
+    rbo, rids, rbd = (S.by_depth if mode == "depth" else S.by_agenda)(g)
+    assert np.array_equal(bo, rbo) and np.array_equal(ids, rids) and np.array_equal(bd, rbd)
+    assert c.stats()["n_depth_retries"] == 0
+    check_against_oracle(c, p, g, o, root, what=f"wide sum/{mode}")
+    c.close()
+
+
+@pytest.mark.parametrize("name,mode", [("tagger", "depth"), ("parser", "agenda")])
+def test_depth_pass_that_gives_up_is_repeated_with_the_single_workgroup_pass(name, mode, workload_cache):
+    """With no idle polls allowed, every id range of the partitioned depth pass that has to wait for
+    a lower range gives up at once (all kernels still end normally).  The library then schedules
+    again with the single-workgroup pass instead of reporting a cycle, and the result is the same
+    schedule."""
+    from paper_1705_07860_amd import binding as ob
+    p, g, o = workload_cache(name)
+    c = ob.Context(arena_bytes=2 << 30, mode=ob.OB_BYDEPTH if mode == "depth" else ob.OB_BYAGENDA)
+    c.debug_set(ob.OB_DBG_SET_DEPTH_SPIN, 0)
+    c.params_create(p)
+    c.param_grad_zero()
+    c.add_bulk(g)
+    c.forward(g.root)
+    st = c.stats()
+    say(f"  {name}/{mode}: depth retries {st['n_depth_retries']}")
+    assert st["n_depth_retries"] == 1
+    bo, ids, bd, _ = c.schedule_read()
+    rbo, rids, rbd = (S.by_depth if mode == "depth" else S.by_agenda)(g)
+    assert np.array_equal(bo, rbo) and np.array_equal(ids, rids) and np.array_equal(bd, rbd)
+    check_against_oracle(c, p, g, o, g.root, what=f"{name}/{mode} after a depth retry")
+    c.close()
+
+
+def test_backward_from_a_one_row_matrix_product_with_one_consumer():
+    """A prefix backward whose root is a 1-element MATVEC node with exactly one plain consumer: the
+    root's gradient is the seed, not the (zero) gradient row of its consumer."""
+    from paper_1705_07860_amd import binding as ob
+    rng = np.random.default_rng(5)
+    pb = wl.ParamBuilder(rng, std=0.5)
+    W1 = pb.add("W1", 8, 6)
+    w = pb.add("w", 1, 8)
+    p = pb.done()
+    gb = wl.GraphBuilder(p)
+    x = gb.input(rng.standard_normal(6))
+    h = gb.tanh(gb.matvec(W1, -1, x))
+    y = gb.matvec(w, -1, h)                      # 1 element, one consumer below
+    z = gb.add((y, gb.input(np.ones(1))))
+    g = gb.finish(z, 1)
+    o = Oracle(g, p, "f64", n_nodes=y + 1)
+    o.forward()
+    o.backward(y)
+    c = ob.Context(arena_bytes=64 << 20)
+    c.params_create(p)
+    c.param_grad_zero()
+    c.add_bulk(g)
+    c.forward(z)
+    c.backward(y)
+    for v in (y, h, x):
+        assert rel_err(c.grad_read(v, int(g.out_dim[v])), o.node_grad(v)) <= TOL, v
+    for pid, m in enumerate(p.mats):
+        assert rel_err(c.param_grad_read(pid, m.shape), o.param_grad(pid)) <= TOL
+    assert c.grad_read(z, 1)[0] == 0.0           # not an ancestor of the root
     c.close()
 
 
@@ -518,7 +569,7 @@ def test_forward_in_many_stages_at_full_size(name, mode, workload_cache):
     c.close()
 
 
-@pytest.mark.parametrize("mode,launch,fuse", [("nobatch", 0, 2), ("agenda", 1, 2), ("depth", 0, 3), ("depth", 0, 0)])
+@pytest.mark.parametrize("mode,launch,fuse", [("nobatch", 0, 2), ("agenda", 1, 2), ("depth", 0, 1), ("depth", 0, 0)])
 def test_stages_in_every_mode_and_on_a_forked_context(mode, launch, fuse):
     """Staged forwards under the other batching modes, under hipGraph launches and the other fusion
     levels, on a context forked from the one that owns the parameters."""
@@ -907,7 +958,7 @@ def test_manual_batching_given_the_reference_schedules(name, workload_cache):
         c.close()
 
 
-@pytest.mark.parametrize("fuse", [0, 1, 2, 3])
+@pytest.mark.parametrize("fuse", [0, 1, 2])
 def test_manual_batching_by_statement_on_the_equal_length_tagger(fuse):
     """Section 4.1's labeler over equal-length sentences, batched the way a program written over
     a batch of sentences would run it: one batch per statement, every launch-fusion level."""

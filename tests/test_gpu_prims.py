@@ -63,16 +63,3 @@ def test_mfma_tile_gemm(ctx, M, N, K):
     ref = A.astype(np.float64) @ B.astype(np.float64).T
     err = np.max(np.abs(C - ref)) / max(np.max(np.abs(ref)), 1e-30)
     assert err < 1e-5, err
-
-
-@pytest.mark.gpu
-@pytest.mark.parametrize("n_wg", [8, 128, 256])
-def test_grid_barrier_orders_memory(n_wg):
-    """Every workgroup sees what its neighbour published before the barrier, in every phase, and
-    no wait runs into its poll limit."""
-    from paper_1705_07860_amd import binding as ob
-    c = ob.Context(arena_bytes=16 << 20)
-    ns, stale, failed = c.test_grid_barrier(n_wg, 500)
-    print(f"grid barrier, {n_wg} workgroups: {ns} ns per phase", flush=True)
-    assert stale == 0 and failed == 0
-    c.close()
