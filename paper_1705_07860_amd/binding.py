@@ -180,6 +180,11 @@ class Context:
         except Exception:
             pass
 
+    def set_schedule_stream(self, stream):
+        """Upload and scheduling go to `stream` (a torch stream) from the next upload on; only while no graph is on the device."""
+        self._sched_stream = stream
+        self._ck(self.L.ob_ctx_set_schedule_stream(self.h, c_void_p(stream.cuda_stream)))
+
     def set_mode(self, mode: int):
         self._ck(self.L.ob_ctx_set_mode(self.h, mode))
 
