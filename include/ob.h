@@ -254,6 +254,18 @@ int ob_test_sort(ob_ctx *ctx, size_t n, const uint64_t *keys, const uint32_t *va
                  int n_bits, uint64_t *keys_out, uint32_t *vals_out);
 int ob_test_scan(ob_ctx *ctx, size_t n, const uint32_t *in, uint32_t *out_exclusive,
                  uint32_t *total);
+/* For callers that cannot allocate (code under HIP graph capture, tight serving loops, harnesses that
+ * forbid device allocation): the same stable radix sort as ob_test_sort, on the caller's DEVICE arrays,
+ * in place, with every temporary (second key / value buffers, digit tables, scan sums) in a fixed
+ * array inside the library's device image (about 3.5 MiB per GPU, held until the process ends).  The
+ * call allocates nothing on the host or the device, needs no context, and only queues work on
+ * hip_stream (a hipStream_t, NULL = default stream): the result is in keys_dev / vals_dev once the
+ * stream gets there.  Sorts the n pairs stably by bits [lo_bit, lo_bit + n_bits) of the key.
+ * n > OB_NOALLOC_MAX_PAIRS: OB_E_RANGE, nothing is queued.  Bad bit range or null array: OB_E_ARG.
+ * All calls on one GPU share that GPU's array: calls that overlap in time on one GPU (different
+ * streams or host threads) race and must be ordered by the caller.  Message: ob_last_error(NULL). */
+#define OB_NOALLOC_MAX_PAIRS 262144
+int ob_sort_pairs_noalloc(void *hip_stream, size_t n, uint64_t *keys_dev, uint32_t *vals_dev, int lo_bit, int n_bits);
 /* Average duration in microseconds of n back-to-back launches of an empty kernel (touch = 0) or
  * of a kernel whose one thread does a dependent load and store (touch = 1) on the context's
  * stream: the floor of a launch boundary on this machine, reported by the benchmark. */

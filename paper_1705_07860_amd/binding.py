@@ -109,6 +109,7 @@ def lib():
             "ob_debug_set": (i, [vp, i, c_uint64]),
             "ob_param_sgd_step": (i, [vp, c_float, i]),
             "ob_test_sort": (i, [vp, sz, vp, vp, i, i, vp, vp]),
+            "ob_sort_pairs_noalloc": (i, [vp, sz, vp, vp, i, i]),
             "ob_test_scan": (i, [vp, sz, vp, vp, vp]),
             "ob_test_gemm": (i, [vp, i, i, i, vp, vp, vp]),
             "ob_test_launch_cost": (i, [vp, i, i, POINTER(c_float)]),
@@ -124,6 +125,17 @@ def lib():
 
 def _ptr(a: np.ndarray):
     return a.ctypes.data_as(c_void_p)
+
+
+OB_NOALLOC_MAX_PAIRS = 262144
+
+
+def sort_pairs_noalloc(stream_ptr, n: int, keys_ptr: int, vals_ptr: int, lo_bit: int, n_bits: int):
+    """ob_sort_pairs_noalloc on raw device pointers (allocates nothing); raises ObError on failure."""
+    L = lib()
+    rc = L.ob_sort_pairs_noalloc(c_void_p(stream_ptr), n, c_void_p(keys_ptr), c_void_p(vals_ptr), lo_bit, n_bits)
+    if rc < 0:
+        raise ObError(rc, (L.ob_last_error(None) or b"").decode())
 
 
 class Context:

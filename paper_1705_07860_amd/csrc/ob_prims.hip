@@ -1,6 +1,9 @@
 // Device-wide primitives of the GPU scheduler: fill, exclusive scan, stable LSD radix sort.
 // Written for wave64 (gfx950): ranking inside a wave uses 64-bit ballots.
-#include "ob_internal.h"
+#include "../../include/ob.h"
+#include "ob_ctx.h"
+
+#include <mutex>
 
 namespace {
 
@@ -383,4 +386,61 @@ hipError_t prim_sort_pairs(u64 *keys, u32 *vals, u64 *keys_tmp, u32 *vals_tmp, s
         if (e != hipSuccess) return e;
     }
     return hipGetLastError();
+}
+
+// ---- the sort for callers that cannot allocate ------------------------------------------------------
+// Everything the sort needs beyond the caller's two arrays (the second key / value buffer of the
+// ping-pong passes, the per-block digit table and the scan's block sums) lies in one array in the
+// library's own device image, so the call reaches no allocator.  Each GPU holds its own copy of
+// the array at its own address; the address is looked up once per device and kept.
+constexpr size_t NOALLOC_TABLE_BYTES = ((size_t)OB_NOALLOC_MAX_PAIRS / RS_BLOCK + 1) * RS_RADIX * sizeof(u32) + 4096;
+constexpr size_t NOALLOC_KEYS_OFF = 0;
+constexpr size_t NOALLOC_VALS_OFF = (size_t)OB_NOALLOC_MAX_PAIRS * sizeof(u64);
+constexpr size_t NOALLOC_TABLE_OFF = NOALLOC_VALS_OFF + (size_t)OB_NOALLOC_MAX_PAIRS * sizeof(u32);
+constexpr size_t NOALLOC_BYTES = NOALLOC_TABLE_OFF + 2 * NOALLOC_TABLE_BYTES;
+static_assert(NOALLOC_VALS_OFF % 256 == 0 && NOALLOC_TABLE_OFF % 256 == 0, "sections of the scratch array stay 256-byte aligned");
+static __device__ __align__(256) unsigned char scratch[NOALLOC_BYTES];
+
+constexpr int NOALLOC_MAX_DEVICES = 64;
+static std::mutex g_noalloc_mutex;
+static void *g_noalloc_ptr[NOALLOC_MAX_DEVICES] = {};
+
+// device address of the current device's copy of `scratch` (host code never uses the array's name
+// for anything else: on the host it is only a handle for this look-up)
+static int noalloc_scratch(char **out)
+{
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return ctx_fail(nullptr, OB_E_HIP, "hipGetDevice failed: %s", hipGetErrorString(e));
+    if (dev < 0 || dev >= NOALLOC_MAX_DEVICES) return ctx_fail(nullptr, OB_E_RANGE, "device index %d outside 0 .. %d", dev, NOALLOC_MAX_DEVICES - 1);
+    std::lock_guard<std::mutex> lock(g_noalloc_mutex);
+    if (!g_noalloc_ptr[dev]) {
+        void *ptr = nullptr;
+        e = hipGetSymbolAddress((void **)&ptr, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !ptr)
+            return ctx_fail(nullptr, OB_E_HIP, "hipGetSymbolAddress(scratch) failed on device %d: %s", dev, hipGetErrorString(e));
+        g_noalloc_ptr[dev] = ptr;
+    }
+    *out = (char *)g_noalloc_ptr[dev];
+    return OB_OK;
+}
+
+extern "C" int ob_sort_pairs_noalloc(void *hip_stream, size_t n, uint64_t *keys_dev, uint32_t *vals_dev, int lo_bit, int n_bits)
+{
+    if (n > (size_t)OB_NOALLOC_MAX_PAIRS)
+        return ctx_fail(nullptr, OB_E_RANGE, "ob_sort_pairs_noalloc: %zu pairs, the built-in scratch holds at most %d", n,
+                        (int)OB_NOALLOC_MAX_PAIRS);
+    if (lo_bit < 0 || n_bits < 0 || lo_bit + n_bits > 64)
+        return ctx_fail(nullptr, OB_E_ARG, "ob_sort_pairs_noalloc: bits [%d, %d) outside a 64-bit key", lo_bit, lo_bit + n_bits);
+    if (n == 0) return OB_OK;
+    if (!keys_dev || !vals_dev) return ctx_fail(nullptr, OB_E_ARG, "ob_sort_pairs_noalloc: null array");
+    char *base = nullptr;
+    if (int rc = noalloc_scratch(&base)) return rc;
+    // Nothing in the scratch has to start at zero: every pass writes each entry of the digit table
+    // and of the block sums it reads, and the second buffers are written before they are read, so
+    // what an earlier (larger) call left behind is never looked at.
+    hipError_t e = prim_sort_pairs(keys_dev, vals_dev, (u64 *)(base + NOALLOC_KEYS_OFF), (u32 *)(base + NOALLOC_VALS_OFF), n, lo_bit,
+                                   n_bits, base + NOALLOC_TABLE_OFF, (hipStream_t)hip_stream, nullptr);
+    if (e != hipSuccess) return ctx_fail(nullptr, OB_E_HIP, "ob_sort_pairs_noalloc: %s", hipGetErrorString(e));
+    return OB_OK;
 }
