@@ -155,6 +155,8 @@ def measure(args, ob, torch, name, steps, warmup, sustain_s, cpu_s, headline):
             c = ctxs[0].fork(arena_bytes=arena_bytes, stream=stream)
         ctxs.append(c)
 
+    host_marks = [] if os.environ.get("OB_BENCH_HOST_MARKS") else None
+
     def set_streams(piped):
         for j, c in enumerate(ctxs):
             c.graph_new()
@@ -163,14 +165,20 @@ def measure(args, ob, torch, name, steps, warmup, sustain_s, cpu_s, headline):
     def hand_over(i, piped):
         """graph definition + upload + scheduling of step i (queued; nothing is waited for)"""
         c = ctxs[i % pool]
+        t_a = time.perf_counter()
         c.graph_new()
+        t_b = time.perf_counter()
         c.add_bulk(graphs[i % n_g])
+        t_c = time.perf_counter()
         if labels is not None:
             c.set_manual_batches(labels[i % n_g])
         if piped:
             c.schedule_async(graphs[i % n_g].root)
         else:
             c.schedule(graphs[i % n_g].root)
+        if host_marks is not None and time.perf_counter() - t_a > 2e-3:
+            print(f"slow hand-over of step {i}: graph_new {(t_b - t_a) * 1e3:.2f} add_bulk {(t_c - t_b) * 1e3:.2f} "
+                  f"schedule {(time.perf_counter() - t_c) * 1e3:.2f} ms", file=sys.stderr)
 
     def execute(i):
         c = ctxs[i % pool]
@@ -187,9 +195,15 @@ def measure(args, ob, torch, name, steps, warmup, sustain_s, cpu_s, headline):
             for a in range(min(lookahead, count)):
                 hand_over(first + a, True)
             for i in range(first, first + count):
+                if host_marks is not None:
+                    host_marks.append(time.perf_counter())
                 if i + lookahead < first + count:
                     hand_over(i + lookahead, True)
+                if host_marks is not None:
+                    host_marks.append(time.perf_counter())
                 execute(i)
+                if host_marks is not None:
+                    host_marks.append(time.perf_counter())
                 if marks is not None:
                     marks.append(torch.cuda.Event(enable_timing=True))
                     marks[-1].record(stream)
@@ -209,16 +223,28 @@ def measure(args, ob, torch, name, steps, warmup, sustain_s, cpu_s, headline):
     # page-locked graph store and the library's other host buffers have reached their steady size
     # (a training loop is in that state after its first few minibatches).
     set_streams(pipeline)
-    biggest = max(range(n_g), key=lambda j: graphs[j].n)
+    biggest = {max(range(n_g), key=lambda j: graphs[j].n), max(range(n_g), key=lambda j: graphs[j].in_idx.size),
+               max(range(n_g), key=lambda j: graphs[j].payload.size)}
     for c in ctxs:
-        c.graph_new()
-        c.add_bulk(graphs[biggest])
-        c.schedule(graphs[biggest].root)
+        for j in sorted(biggest):      # most nodes, most operand references, largest input payload
+            c.graph_new()
+            c.add_bulk(graphs[j])
+            c.schedule(graphs[j].root)
+    torch.cuda.synchronize()
+
+    # still set-up: the loop itself, twice around the ring and a little more, so that the runtime's own
+    # pools (command buffers, copy engines, signals) have grown to what this loop needs
+    run(0, 2 * pool + lookahead + 4, pipeline)
     torch.cuda.synchronize()
 
     # ---- the timed region: exactly `steps` steps, each with its own minibatch, hand-over included
     run(0, warmup, pipeline)
     elapsed = timed(warmup, steps, pipeline)
+    if host_marks is not None:
+        hm = host_marks[-3 * steps:]
+        print("host ms per step (hand-over of the next, execute):",
+              [(round((hm[3 * q + 1] - hm[3 * q]) * 1e3, 2), round((hm[3 * q + 2] - hm[3 * q + 1]) * 1e3, 2)) for q in range(steps)],
+              file=sys.stderr)
     n_inst = sum(graphs[warmup + i].n_instances for i in range(steps))
     n_nodes = sum(graphs[warmup + i].n for i in range(steps))
     value = n_inst / elapsed
@@ -226,7 +252,7 @@ def measure(args, ob, torch, name, steps, warmup, sustain_s, cpu_s, headline):
     # per-phase HIP-event times, launches and algorithmic cost of the last `cover` timed steps (a
     # context keeps the events of its latest step; reading them is not timed)
     cover = min(pool, steps)
-    phase = dict(ms_upload=0.0, ms_schedule=0.0, ms_forward=0.0, ms_backward=0.0, ms_param_grads=0.0)
+    phase = dict(ms_upload=0.0, ms_schedule=0.0, ms_forward=0.0, ms_backward=0.0, ms_param_grads=0.0, ms_graph_build=0.0)
     launches = dict(n_launch_fwd=0, n_launch_bwd=0, n_launch_sched=0)
     cost = dict(fwd_bytes=0.0, bwd_bytes=0.0, param_bytes=0.0, fwd_flops=0.0, bwd_flops=0.0)
     upload_bytes = 0

@@ -8,10 +8,68 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <condition_variable>
+#include <functional>
+#include <mutex>
 #include <new>
 #include <thread>
 
 static std::string g_create_error;
+
+// Three helper threads for the bulk hand-over of large graphs, started on first use and kept for
+// the life of the process (starting threads per call costs more than the work they take over).
+// One job at a time; the caller runs part 0 itself and waits for parts 1..3.
+namespace {
+struct BulkPool {
+    static constexpr int HELPERS = 3;
+    std::mutex call_m;                 // one bulk call at a time uses the pool
+    std::mutex m;
+    std::condition_variable cv, done_cv;
+    const std::function<void(int)> *job = nullptr;
+    unsigned long gen = 0;
+    int pending = 0;
+    BulkPool()
+    {
+        for (int t = 1; t <= HELPERS; ++t)
+            std::thread([this, t] {
+                unsigned long seen = 0;
+                for (;;) {
+                    const std::function<void(int)> *j;
+                    {
+                        std::unique_lock<std::mutex> lk(m);
+                        cv.wait(lk, [&] { return gen != seen; });
+                        seen = gen;
+                        j = job;
+                    }
+                    (*j)(t);
+                    {
+                        std::lock_guard<std::mutex> lk(m);
+                        if (--pending == 0) done_cv.notify_one();
+                    }
+                }
+            }).detach();
+    }
+    void run(const std::function<void(int)> &f)
+    {
+        std::lock_guard<std::mutex> call(call_m);
+        {
+            std::lock_guard<std::mutex> lk(m);
+            job = &f;
+            pending = HELPERS;
+            ++gen;
+        }
+        cv.notify_all();
+        f(0);
+        std::unique_lock<std::mutex> lk(m);
+        done_cv.wait(lk, [&] { return pending == 0; });
+    }
+};
+BulkPool &bulk_pool()
+{
+    static BulkPool *p = new BulkPool();   // never destroyed: its threads live until the process ends
+    return *p;
+}
+}  // namespace
 
 int ctx_fail(ob_ctx *ctx, int code, const char *fmt, ...)
 {
@@ -561,7 +619,7 @@ int ob_add_bulk(ob_ctx *ctx, int n, const uint8_t *op, const uint32_t *out_dim, 
         ErrSink es; u64 sum_dim = 0, mv_d32 = 0, mv_k32 = 0; u32 max_ar = 0, items = 0;
         std::vector<u8> used_w, used_b;
     };
-    const int n_parts = n >= 32768 ? 4 : 1;
+    const int n_parts = n >= 32768 ? 1 + BulkPool::HELPERS : 1;
     std::vector<Part> parts((size_t)n_parts);
     const std::vector<HostParam> &params = ctx->params;
     auto work = [&](int t) {
@@ -614,10 +672,8 @@ int ob_add_bulk(ob_ctx *ctx, int n, const uint8_t *op, const uint32_t *out_dim, 
     if (n_parts == 1) {
         work(0);
     } else {
-        std::vector<std::thread> th;
-        for (int t = 1; t < n_parts; ++t) th.emplace_back(work, t);
-        work(0);
-        for (auto &x : th) x.join();
+        const std::function<void(int)> job = work;
+        bulk_pool().run(job);
     }
     for (const Part &P : parts)   // the first failing range holds the first failing node
         if (P.es.code) return ctx_fail(ctx, P.es.code, "%s", P.es.msg);

@@ -169,6 +169,13 @@ struct Lay {
     }
 };
 
+// Scan element of the three per-position counts taken after the grouping sort (batch heads, operand
+// counts, parameter uses): one scan instead of three.
+struct Tri {
+    u32 a, b, c, d;
+    __host__ __device__ Tri operator+(const Tri &o) const { Tri r; r.a = a + o.a; r.b = b + o.b; r.c = c + o.c; r.d = 0; return r; }
+};
+
 // Header the host reads back after scheduling (one small D2H copy).
 struct SchedHeader {
     u32 n_steps, n_batches, n_items, err;
@@ -222,6 +229,7 @@ hipError_t prim_fill_u32(u32 *p, u32 v, size_t n, hipStream_t s);
 hipError_t prim_scan_u32(const u32 *in, u32 *out, size_t n, u32 *total_dev, void *scratch, hipStream_t s);
 hipError_t prim_scan_lay(const Lay *in, Lay *out, size_t n, Lay *total_dev, void *scratch, hipStream_t s);
 hipError_t prim_scan_clay(const CLay *in, CLay *out, size_t n, CLay *total_dev, void *scratch, hipStream_t s);
+hipError_t prim_scan_tri(const Tri *in, Tri *out, size_t n, Tri *total_dev, void *scratch, hipStream_t s);
 size_t prim_sort_scratch_bytes(size_t n);
 // Stable LSD radix sort of (key, val) pairs on bits [lo_bit, lo_bit + n_bits) of the key.
 // keys/vals are overwritten with the sorted result; tmp arrays have the same sizes.
@@ -230,6 +238,9 @@ size_t prim_sort_scratch_bytes(size_t n);
 // first *n_dev pairs.
 hipError_t prim_sort_pairs(u64 *keys, u32 *vals, u64 *keys_tmp, u32 *vals_tmp, size_t n, int lo_bit,
                            int n_bits, void *scratch, hipStream_t s, int *n_launches, const u32 *n_dev = nullptr);
+
+hipError_t prim_sort_pairs_swap(u64 *&keys, u32 *&vals, u64 *&keys_tmp, u32 *&vals_tmp, size_t n, int lo_bit,
+                                int n_bits, void *scratch, hipStream_t s, int *n_launches, const u32 *n_dev = nullptr);
 
 // ---- scheduler / executor entry points ---------------------------------------------------
 struct ob_ctx;

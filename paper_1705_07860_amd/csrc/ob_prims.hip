@@ -21,6 +21,7 @@ __global__ void k_fill_u32(u32 *p, u32 v, size_t n)
 template <typename T> __device__ inline T zero_of();
 template <> __device__ inline u32 zero_of<u32>() { return 0u; }
 template <> __device__ inline Lay zero_of<Lay>() { Lay z; z.val = 0; z.dx = 0; z.ind = z.p0 = z.p1 = z.p2 = 0; return z; }
+template <> __device__ inline Tri zero_of<Tri>() { Tri z; z.a = z.b = z.c = z.d = 0; return z; }
 template <> __device__ inline CLay zero_of<CLay>() { CLay z; z.tf = z.wf = z.ta = z.wa = z.tb = z.p0 = z.p1 = z.p2 = 0; return z; }
 
 // Exclusive scan of the 256 per-thread values of a block through LDS (Kogge-Stone).
@@ -342,6 +343,11 @@ hipError_t prim_scan_clay(const CLay *in, CLay *out, size_t n, CLay *total_dev, 
     return scan_impl<CLay>(in, out, n, total_dev, scratch, s);
 }
 
+hipError_t prim_scan_tri(const Tri *in, Tri *out, size_t n, Tri *total_dev, void *scratch, hipStream_t s)
+{
+    return scan_impl<Tri>(in, out, n, total_dev, scratch, s);
+}
+
 size_t prim_sort_scratch_bytes(size_t n)
 {
     const size_t nblk = (n + RS_BLOCK - 1) / RS_BLOCK;
@@ -349,9 +355,10 @@ size_t prim_sort_scratch_bytes(size_t n)
     return table + prim_scan_scratch_bytes((size_t)RS_RADIX * (nblk ? nblk : 1), sizeof(u32));
 }
 
-hipError_t prim_sort_pairs(u64 *keys, u32 *vals, u64 *keys_tmp, u32 *vals_tmp, size_t n, int lo_bit,
-                           int n_bits, void *scratch, hipStream_t s, int *n_launches, const u32 *n_dev)
+static hipError_t sort_pairs_impl(u64 *keys, u32 *vals, u64 *keys_tmp, u32 *vals_tmp, size_t n, int lo_bit,
+                                  int n_bits, void *scratch, hipStream_t s, int *n_launches, const u32 *n_dev, bool *in_tmp)
 {
+    if (in_tmp) *in_tmp = false;
     if (n <= 1 || n_bits <= 0) return hipSuccess;
     if (n <= RS_SMALL_MAX) {
         hipLaunchKernelGGL(k_rs_small, dim3(1), dim3(RSS_THREADS), 0, s, keys, vals, keys_tmp, vals_tmp, (u32)n, lo_bit,
@@ -379,13 +386,35 @@ hipError_t prim_sort_pairs(u64 *keys, u32 *vals, u64 *keys_tmp, u32 *vals_tmp, s
         ++passes;
         if (n_launches) *n_launches += 2 + ((size_t)RS_RADIX * nblk > SCAN_SMALL_MAX ? 3 : 1);
     }
-    if (passes & 1) {  // result sits in the tmp arrays: copy back
+    if ((passes & 1) && in_tmp) {   // the caller takes the result where it is
+        *in_tmp = true;
+    } else if (passes & 1) {  // result sits in the tmp arrays: copy back
         hipError_t e = hipMemcpyAsync(keys, kin, n * sizeof(u64), hipMemcpyDeviceToDevice, s);
         if (e != hipSuccess) return e;
         e = hipMemcpyAsync(vals, vin, n * sizeof(u32), hipMemcpyDeviceToDevice, s);
         if (e != hipSuccess) return e;
     }
     return hipGetLastError();
+}
+
+hipError_t prim_sort_pairs(u64 *keys, u32 *vals, u64 *keys_tmp, u32 *vals_tmp, size_t n, int lo_bit,
+                           int n_bits, void *scratch, hipStream_t s, int *n_launches, const u32 *n_dev)
+{
+    return sort_pairs_impl(keys, vals, keys_tmp, vals_tmp, n, lo_bit, n_bits, scratch, s, n_launches, n_dev, nullptr);
+}
+
+// The same sort without the copy back after an odd number of passes: the two buffer pairs change
+// roles instead (on return keys / vals point at the sorted data, keys_tmp / vals_tmp at the other pair).
+hipError_t prim_sort_pairs_swap(u64 *&keys, u32 *&vals, u64 *&keys_tmp, u32 *&vals_tmp, size_t n, int lo_bit,
+                                int n_bits, void *scratch, hipStream_t s, int *n_launches, const u32 *n_dev)
+{
+    bool in_tmp = false;
+    hipError_t e = sort_pairs_impl(keys, vals, keys_tmp, vals_tmp, n, lo_bit, n_bits, scratch, s, n_launches, n_dev, &in_tmp);
+    if (in_tmp) {
+        u64 *tk = keys; keys = keys_tmp; keys_tmp = tk;
+        u32 *tv = vals; vals = vals_tmp; vals_tmp = tv;
+    }
+    return e;
 }
 
 // ---- the sort for callers that cannot allocate ------------------------------------------------------

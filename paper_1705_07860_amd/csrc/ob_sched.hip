@@ -143,19 +143,18 @@ __global__ __launch_bounds__(FRONTIER_THREADS) void k_depth_frontier(Tables T, c
 // range reads its nodes' external counts from the fixed copy, never from the counters that lower
 // ranges are already taking down); every wait is bounded.
 constexpr u32 DEPTH_SCAP = 12288;     // successor entries of a range held in LDS
-constexpr u32 DEPTH_THREADS = 256;    // set-up and write-out; the level loop itself runs on one wave
+constexpr u32 DEPTH_THREADS = 256;    // set-up and write-out; in between the waves have roles of their own
 constexpr u32 DEPTH_MAX_PARTS = 240;
 constexpr u32 DEPTH_NONE = 0xffffffffu;
+constexpr u32 DEPTH_UNROLL = 2;       // successors of a frontier node handled per pass of the inner loop
+constexpr u32 DEPTH_OUT_CAP = 1024;   // ring of resolutions that leave the range, waiting for the wave that posts them
 
-// one successor of a frontier node: raise its depth bound, take one dependency off; true when it was the last
-__device__ inline bool depth_resolve(u32 sn, u32 d1, u32 lo, u32 hi, u32 *s_dep, u32 *s_pending, const Tables &T, u32 *g_dep,
-                                     u32 *inbox, u32 *inbox_tail)
+__device__ inline u32 lds_load(const u32 *p) { return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP); }
+
+// A resolution that leaves the range: raise the consumer's depth bound, take one of its external
+// dependencies off; whoever takes the last one posts the node to its owner's inbox.
+__device__ inline void depth_post_external(const Tables &T, u32 sn, u32 d1, u32 *g_dep, u32 *inbox, u32 *inbox_tail)
 {
-    if (sn < hi) {   // successors have larger ids than their producer, so sn >= lo
-        const u32 sl = sn - lo;
-        atomicMax(&s_dep[sl], d1);
-        return atomicSub(&s_pending[sl], 1u) == 1u;
-    }
     atomicMax(&g_dep[sn], d1);
     __threadfence();
     if (atomicSub(&T.ext_left[sn], 1u) == 1u) {
@@ -163,7 +162,6 @@ __device__ inline bool depth_resolve(u32 sn, u32 d1, u32 lo, u32 hi, u32 *s_dep,
         const u32 slot = atomicAdd(&inbox_tail[k2], 1u);
         __hip_atomic_store(&inbox[k2 * DEPTH_PART + slot], sn, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
     }
-    return false;
 }
 
 __global__ __launch_bounds__(DEPTH_THREADS) void k_depth_partitioned(Tables T, const u32 *succ_node, u32 *g_dep,
@@ -174,7 +172,9 @@ __global__ __launch_bounds__(DEPTH_THREADS) void k_depth_partitioned(Tables T, c
     __shared__ unsigned short s_queue[DEPTH_PART];
     __shared__ u32 s_soff[DEPTH_PART + 1];
     __shared__ u32 s_snode[DEPTH_SCAP];
-    __shared__ u32 s_next, s_done;
+    __shared__ u32 s_out_sn[DEPTH_OUT_CAP], s_out_d1[DEPTH_OUT_CAP];
+    __shared__ unsigned short s_in[DEPTH_PART];
+    __shared__ u32 s_next, s_done, s_out_tail, s_out_head, s_in_tail, s_fin;
     const u32 tid = threadIdx.x;
     const u32 k = blockIdx.x;
     const u32 lo = k * DEPTH_PART;
@@ -182,7 +182,7 @@ __global__ __launch_bounds__(DEPTH_THREADS) void k_depth_partitioned(Tables T, c
     const u32 cnt = hi - lo;
     const u32 ebase = T.succ_off[lo];
     const u32 ecnt = T.succ_off[hi] - ebase;
-    if (tid == 0) { s_next = 0; s_done = 0; }
+    if (tid == 0) { s_next = 0; s_done = 0; s_out_tail = 0; s_out_head = 0; s_in_tail = 0; s_fin = 0; }
     __syncthreads();
     for (u32 i = tid; i < cnt; i += DEPTH_THREADS) {
         const u32 v = lo + i;
@@ -197,22 +197,18 @@ __global__ __launch_bounds__(DEPTH_THREADS) void k_depth_partitioned(Tables T, c
     for (u32 e = tid; e < ecnt && e < DEPTH_SCAP; e += DEPTH_THREADS) s_snode[e] = succ_node[ebase + e];
     __syncthreads();
     // The frontier of a range is small (tens of nodes per level), so after the cooperative set-up
-    // one wave runs the loop alone: its LDS operations complete in program order, the loop state
+    // wave 0 runs the level loop alone: its LDS operations complete in program order, the loop state
     // (head, tail, counters) sits in scalar registers, new frontier entries get their queue
-    // positions from a ballot instead of an LDS counter, and a level costs four dependent LDS
-    // round trips (queue entry; depth and successor range; up to four successors at once; their
-    // counters).  The other waves wait at the barrier behind the loop and help with the write-out.
-    if (tid < 64) {
-        const u32 lane = tid;
-        const u64 lt_mask = (1ull << lane) - 1ull;
-        u32 head = 0, tail = __builtin_amdgcn_readfirstlane(s_next), done = 0, seen = 0, avail = 0, spin = 0, iter = 0;
+    // positions from a ballot, and nothing in the loop waits for global memory.  Traffic with other
+    // ranges goes through the two helper waves: wave 1 watches this range's inbox (coherent memory)
+    // and hands what arrives to wave 0 through LDS, depth bound already applied; wave 2 takes the
+    // resolutions that leave the range from a ring in LDS and posts them with global atomics.
+    const u32 wave = tid >> 6, lane = tid & 63u;
+    const u64 lt_mask = (1ull << lane) - 1ull;
+    if (wave == 0) {
+        u32 head = 0, tail = __builtin_amdgcn_readfirstlane(s_next), done = 0, seen = 0, spin = 0, out_tail = 0;
         while (!(head == tail && done == cnt)) {
-            // The inbox counter lives in coherent memory: look at it only when the frontier is
-            // empty or every 8th pass.  (Nothing else in the loop touches global memory unless an
-            // edge leaves the range: depths stay in LDS and are written out once at the end.)
-            if (head == tail || (iter & 7u) == 0)
-                avail = __builtin_amdgcn_readfirstlane(__hip_atomic_load(&inbox_tail[k], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
-            ++iter;
+            const u32 avail = __builtin_amdgcn_readfirstlane(__hip_atomic_load(&s_in_tail, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_WORKGROUP));
             u32 new_tail = tail;
             for (u32 base = head; base < tail; base += 64) {
                 const u32 i = base + lane;
@@ -222,57 +218,108 @@ __global__ __launch_bounds__(DEPTH_THREADS) void k_depth_partitioned(Tables T, c
                 u32 e = s_soff[ul];
                 const u32 e1 = act ? s_soff[ul + 1] : e;
                 while (__ballot(e < e1) != 0ull) {
-                    u32 sn[4];
+                    // two successors per pass (most nodes have one or two): the loop is bound by the number of
+                    // instructions the one wave issues, so the common case is kept short
+                    u32 sn[DEPTH_UNROLL], was[DEPTH_UNROLL];
+                    bool any_ext = false;
 #pragma unroll
-                    for (u32 j = 0; j < 4; ++j)
+                    for (u32 j = 0; j < DEPTH_UNROLL; ++j)
                         sn[j] = e + j < e1 ? (e + j < DEPTH_SCAP ? s_snode[e + j] : succ_node[ebase + e + j]) : DEPTH_NONE;
-                    bool ready[4];
 #pragma unroll
-                    for (u32 j = 0; j < 4; ++j)
-                        ready[j] = sn[j] != DEPTH_NONE && depth_resolve(sn[j], d1, lo, hi, s_dep, s_pending, T, g_dep, inbox, inbox_tail);
+                    for (u32 j = 0; j < DEPTH_UNROLL; ++j) {   // successors have larger ids than their producer, so sn >= lo
+                        was[j] = 0;
+                        if (sn[j] < hi) { atomicMax(&s_dep[sn[j] - lo], d1); was[j] = atomicSub(&s_pending[sn[j] - lo], 1u); }
+                        else any_ext = any_ext || sn[j] != DEPTH_NONE;
+                    }
 #pragma unroll
-                    for (u32 j = 0; j < 4; ++j) {
-                        const u64 m = __ballot(ready[j]);
-                        if (ready[j]) s_queue[new_tail + (u32)__popcll(m & lt_mask)] = (unsigned short)(sn[j] - lo);
+                    for (u32 j = 0; j < DEPTH_UNROLL; ++j) {
+                        const bool ready = was[j] == 1u;
+                        const u64 m = __ballot(ready);
+                        if (ready) s_queue[new_tail + (u32)__popcll(m & lt_mask)] = (unsigned short)(sn[j] - lo);
                         new_tail += (u32)__popcll(m);
                     }
-                    e += 4;
+                    if (__ballot(any_ext) != 0ull) {
+#pragma unroll
+                        for (u32 j = 0; j < DEPTH_UNROLL; ++j) {
+                            const bool ext = sn[j] != DEPTH_NONE && sn[j] >= hi;
+                            const u64 m = __ballot(ext);
+                            if (m == 0ull) continue;
+                            const u32 c = (u32)__popcll(m);
+                            if (out_tail + c - lds_load(&s_out_head) <= DEPTH_OUT_CAP) {
+                                if (ext) {
+                                    const u32 pos = (out_tail + (u32)__popcll(m & lt_mask)) % DEPTH_OUT_CAP;
+                                    s_out_sn[pos] = sn[j]; s_out_d1[pos] = d1;
+                                }
+                                out_tail += c;
+                                __hip_atomic_store(&s_out_tail, out_tail, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP);
+                            } else if (ext) {
+                                depth_post_external(T, sn[j], d1, g_dep, inbox, inbox_tail);   // ring full: post it here
+                            }
+                        }
+                    }
+                    e += DEPTH_UNROLL;
                 }
             }
-            __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
-            // inbox entries are posted after their slot is reserved: take them in order, stop at a hole
-            while (seen < avail) {
-                const u32 j = seen + lane;
-                u32 sn = DEPTH_NONE;
-                if (j < avail) sn = __hip_atomic_load(&inbox[k * DEPTH_PART + j], __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_AGENT);
-                const u32 in_chunk = avail - seen < 64u ? avail - seen : 64u;
-                const u64 holes = __ballot(j < avail && sn == DEPTH_NONE);
-                const u32 good = holes ? (u32)__builtin_ctzll(holes) : in_chunk;
+            // what wave 1 took from the inbox: the node's depth bound is applied, one dependency comes off
+            for (u32 base = seen; base < avail; base += 64) {
+                const u32 j = base + lane;
                 bool ready = false;
-                if (lane < good) {
-                    const u32 sl = sn - lo;
-                    atomicMax(&s_dep[sl], __hip_atomic_load(&g_dep[sn], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
-                    ready = atomicSub(&s_pending[sl], 1u) == 1u;
-                }
+                u32 sl = 0;
+                if (j < avail) { sl = s_in[j]; ready = atomicSub(&s_pending[sl], 1u) == 1u; }
                 const u64 m = __ballot(ready);
-                if (ready) s_queue[new_tail + (u32)__popcll(m & lt_mask)] = (unsigned short)(sn - lo);
+                if (ready) s_queue[new_tail + (u32)__popcll(m & lt_mask)] = (unsigned short)sl;
                 new_tail += (u32)__popcll(m);
-                seen += good;
-                if (holes) break;
             }
             __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
             done += tail - head;
-            const bool idle = head == tail && new_tail == tail;   // nothing to do: waiting for another range
+            const bool idle = head == tail && new_tail == tail && seen == avail;   // nothing to do: waiting for another range
+            seen = avail;
             head = tail;
             tail = new_tail;
             if (idle) {
                 if (++spin > spin_limit) break;     // bounded: the host then runs the single-workgroup pass instead
-                __builtin_amdgcn_s_sleep(8);
+                __builtin_amdgcn_s_sleep(4);
             } else {
                 spin = 0;
             }
         }
         if (lane == 0) s_done = done;
+        __hip_atomic_store(&s_fin, 1u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP);
+    } else if (wave == 1) {
+        // inbox entries are posted after their slot is reserved: take them in order, stop at a hole
+        u32 seen = 0;
+        while (lds_load(&s_fin) == 0u) {
+            const u32 avail = __builtin_amdgcn_readfirstlane(__hip_atomic_load(&inbox_tail[k], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+            if (seen >= avail) { __builtin_amdgcn_s_sleep(2); continue; }
+            const u32 j = seen + lane;
+            u32 sn = DEPTH_NONE;
+            if (j < avail) sn = __hip_atomic_load(&inbox[k * DEPTH_PART + j], __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_AGENT);
+            const u32 in_chunk = avail - seen < 64u ? avail - seen : 64u;
+            const u64 holes = __ballot(j < avail && sn == DEPTH_NONE);
+            const u32 good = holes ? (u32)__builtin_ctzll(holes) : in_chunk;
+            if (lane < good) {
+                const u32 sl = sn - lo;
+                atomicMax(&s_dep[sl], __hip_atomic_load(&g_dep[sn], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+                s_in[j] = (unsigned short)sl;
+            }
+            seen += good;
+            if (good) __hip_atomic_store(&s_in_tail, seen, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP);
+        }
+    } else if (wave == 2) {
+        u32 head = 0;
+        while (true) {
+            const u32 fin = lds_load(&s_fin);
+            const u32 tail = __builtin_amdgcn_readfirstlane(__hip_atomic_load(&s_out_tail, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_WORKGROUP));
+            if (head == tail) {
+                if (fin) break;
+                __builtin_amdgcn_s_sleep(1);
+                continue;
+            }
+            const u32 j = head + lane;
+            if (j < tail) depth_post_external(T, s_out_sn[j % DEPTH_OUT_CAP], s_out_d1[j % DEPTH_OUT_CAP], g_dep, inbox, inbox_tail);
+            head += tail - head < 64u ? tail - head : 64u;
+            __hip_atomic_store(&s_out_head, head, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP);
+        }
     }
     __syncthreads();
     for (u32 i = tid; i < cnt; i += DEPTH_THREADS) T.step[lo + i] = s_dep[i];
@@ -517,7 +564,7 @@ __global__ void k_sort_keys(Tables T, u64 *keys, u32 *vals, int rep_src)
 }
 
 // ---- stage 4: batches from the sorted order -----------------------------------------------------
-__global__ void k_heads(Tables T, const u64 *skey, const u32 *sval, u32 *head_flag, u32 *s_arity, u32 *s_items)
+__global__ void k_heads(Tables T, const u64 *skey, const u32 *sval, u32 *head_flag, Tri *counts)
 {
     const u32 p = blockIdx.x * blockDim.x + threadIdx.x;
     if (p >= T.n) return;
@@ -525,17 +572,24 @@ __global__ void k_heads(Tables T, const u64 *skey, const u32 *sval, u32 *head_fl
     T.order[p] = v;
     T.pos_of[v] = p;
     T.s_aux0[p] = (u32)T.aux0[v];
-    head_flag[p] = (p == 0 || skey[p] != skey[p - 1]) ? 1u : 0u;
-    s_arity[p] = T.in_off[v + 1] - T.in_off[v];
+    Tri c;
+    c.a = (p == 0 || skey[p] != skey[p - 1]) ? 1u : 0u;
+    c.b = T.in_off[v + 1] - T.in_off[v];
     const u32 o = T.op[v];
-    s_items[p] = (o == OP_MATVEC) ? (1u + (T.bias[v] >= 0 ? 1u : 0u)) : (o == OP_LOOKUP ? 1u : 0u);
+    c.c = (o == OP_MATVEC) ? (1u + (T.bias[v] >= 0 ? 1u : 0u)) : (o == OP_LOOKUP ? 1u : 0u);
+    c.d = 0;
+    head_flag[p] = c.a;
+    counts[p] = c;
 }
 
-__global__ void k_batch_off(Tables T, const u32 *head_flag, const u32 *head_excl, int manual)
+__global__ void k_batch_off(Tables T, const u32 *head_flag, const Tri *before, u32 *item_base, int manual)
 {
     const u32 p = blockIdx.x * blockDim.x + threadIdx.x;
     if (p >= T.n) return;
-    const u32 b = head_excl[p] + head_flag[p] - 1;
+    const Tri ex = before[p];          // batch heads, operand references and parameter uses before position p
+    const u32 b = ex.a + head_flag[p] - 1;
+    T.s_in_off[p] = ex.b;
+    item_base[p] = ex.c;
     T.batch_of_pos[p] = b;
     if (manual) T.step[T.order[p]] = b;   // labels need not be dense: a batch's step is its rank
     if (head_flag[p]) T.batch_off[b] = p;
@@ -753,6 +807,7 @@ __global__ __launch_bounds__(SLOT_THREADS) void k_slots(Tables T, int fuse, cons
     __shared__ u32 s_label[SLOT_MAX_NB];   // tail lengths first, chain labels afterwards
     __shared__ u32 s_edge[BLIST_MAX];
     __shared__ u32 s_changed;
+    __shared__ u32 s_flag[3];
     const u32 nb = T.hdr->n_batches;
     const u32 ne = T.hdr->n_bedges;
     const u32 tid = threadIdx.x;
@@ -763,24 +818,28 @@ __global__ __launch_bounds__(SLOT_THREADS) void k_slots(Tables T, int fuse, cons
     }
     for (u32 b = tid; b < nb; b += SLOT_THREADS) { s_slot[b] = 0; s_label[b] = 0; }
     for (u32 e = tid; e < ne; e += SLOT_THREADS) s_edge[e] = blist[e] - 1u;
+    // One barrier per sweep: sweep k raises s_flag[k % 3] when it changes anything, everybody reads
+    // it behind the sweep's barrier, and the flag of sweep k + 1 is cleared during sweep k (its last
+    // readers were those of sweep k - 2, who have all passed the barrier of sweep k - 1).
+    if (tid < 3) s_flag[tid] = 0;
+    __syncthreads();
     u32 sweeps = 0;
     while (true) {
-        if (tid == 0) s_changed = 0;
-        __syncthreads();
+        const u32 f = sweeps % 3u;
+        if (tid == 0) s_flag[(sweeps + 1u) % 3u] = 0;
         for (u32 e = tid; e < ne; e += SLOT_THREADS) {
             const u32 k = s_edge[e];
             const u32 c = k >> 13, y = (k >> 1) & 0xfffu;
             const u32 want = s_slot[y] + (k & 1u);
-            if (want > s_slot[c]) { atomicMax(&s_slot[c], want); s_changed = 1; }
+            if (want > s_slot[c]) { atomicMax(&s_slot[c], want); s_flag[f] = 1; }
             const u32 tw = s_label[c] + (k & 1u);
-            if (tw > s_label[y]) { atomicMax(&s_label[y], tw); s_changed = 1; }
+            if (tw > s_label[y]) { atomicMax(&s_label[y], tw); s_flag[f] = 1; }
         }
         __syncthreads();
         ++sweeps;
-        const u32 ch = s_changed;
-        __syncthreads();
-        if (!ch || sweeps > nb + 1) break;
+        if (!s_flag[f] || sweeps > nb + 1) break;
     }
+    __syncthreads();
     {   // number of slots; late placement; labels start as the batch's own id
         u32 mx = 0;
         for (u32 b = tid; b < nb; b += SLOT_THREADS) mx = s_slot[b] > mx ? s_slot[b] : mx;
@@ -797,9 +856,12 @@ __global__ __launch_bounds__(SLOT_THREADS) void k_slots(Tables T, int fuse, cons
         if (tid == 0) T.hdr->n_slots = L + 1;
         __syncthreads();
     }
+    if (tid < 3) s_flag[tid] = 0;
+    __syncthreads();
+    const u32 sweeps0 = sweeps;
     while (true) {
-        if (tid == 0) s_changed = 0;
-        __syncthreads();
+        const u32 f = sweeps % 3u;
+        if (tid == 0) s_flag[(sweeps + 1u) % 3u] = 0;
         for (u32 e = tid; e < ne; e += SLOT_THREADS) {
             const u32 k = s_edge[e];
             if (k & 1u) continue;
@@ -810,14 +872,12 @@ __global__ __launch_bounds__(SLOT_THREADS) void k_slots(Tables T, int fuse, cons
                 const u32 m = a < bb ? a : bb;
                 atomicMin(&s_label[c], m);
                 atomicMin(&s_label[y], m);
-                s_changed = 1;
+                s_flag[f] = 1;
             }
         }
         __syncthreads();
         ++sweeps;
-        const u32 ch = s_changed;
-        __syncthreads();
-        if (!ch || sweeps > 3 * nb + 3) break;
+        if (!s_flag[f] || sweeps - sweeps0 > 2 * nb + 2) break;
     }
     for (u32 b = tid; b < nb; b += SLOT_THREADS) { T.slot_of[b] = s_slot[b]; T.label_of[b] = s_label[b]; }
     if (tid == 0) T.hdr->slot_sweeps = sweeps;
@@ -1492,8 +1552,10 @@ int sched_enqueue(ob_ctx *ctx)
     A(succ_node, u32, E + 1);
     A(ctx->key_a, u64, maxne); A(ctx->key_b, u64, maxne); A(ctx->val_a, u32, maxne); A(ctx->val_b, u32, maxne);
     A(ctx->tmp_u32_a, u32, n + 1); A(ctx->tmp_u32_b, u32, n + 1);
-    u32 *tmp_c, *tmp_d;
-    A(tmp_c, u32, n + 1); A(tmp_d, u32, n + 1);
+    u32 *tmp_d;
+    A(tmp_d, u32, n + 1);
+    Tri *tri_in, *tri_ex;
+    A(tri_in, Tri, n); A(tri_ex, Tri, n);
     A(ctx->lay_in, Lay, n); A(ctx->lay_total, Lay, 1);
     CLay *clay_in, *clay_total;
     A(clay_in, CLay, n); A(clay_total, CLay, 1);
@@ -1522,7 +1584,7 @@ int sched_enqueue(ob_ctx *ctx)
     const int scan_launches = (size_t)n + 1 <= 4096 ? 1 : 3;   // a scan of a short array is one launch
     ctx->n_launch_sched += scan_launches;
     if (E > 0) {
-        HIP_TRY(ctx, prim_sort_pairs(ctx->key_a, ctx->val_a, ctx->key_b, ctx->val_b, E, 0,
+        HIP_TRY(ctx, prim_sort_pairs_swap(ctx->key_a, ctx->val_a, ctx->key_b, ctx->val_b, E, 0,
                                      bit_width_u32(n - 1), ctx->scratch, s, &ctx->n_launch_sched));
         K(k_succ_finish, E, T, ctx->val_a, succ_node);
     }
@@ -1546,24 +1608,22 @@ int sched_enqueue(ob_ctx *ctx)
     }
     K(k_sort_keys, n, T, ctx->key_a, ctx->val_a, manual ? 2 : by_depth);
     if (manual) {
-        HIP_TRY(ctx, prim_sort_pairs(ctx->key_a, ctx->val_a, ctx->key_b, ctx->val_b, n, 32, bit_width_u32(ctx->manual_max | 1u),
+        HIP_TRY(ctx, prim_sort_pairs_swap(ctx->key_a, ctx->val_a, ctx->key_b, ctx->val_b, n, 32, bit_width_u32(ctx->manual_max | 1u),
                                      ctx->scratch, s, &ctx->n_launch_sched));
     } else if (by_depth) {
         const int lb = bit_width_u32(n - 1);
-        HIP_TRY(ctx, prim_sort_pairs(ctx->key_a, ctx->val_a, ctx->key_b, ctx->val_b, n, 0, lb, ctx->scratch, s,
+        HIP_TRY(ctx, prim_sort_pairs_swap(ctx->key_a, ctx->val_a, ctx->key_b, ctx->val_b, n, 0, lb, ctx->scratch, s,
                                      &ctx->n_launch_sched));
-        HIP_TRY(ctx, prim_sort_pairs(ctx->key_a, ctx->val_a, ctx->key_b, ctx->val_b, n, 32, lb, ctx->scratch, s,
+        HIP_TRY(ctx, prim_sort_pairs_swap(ctx->key_a, ctx->val_a, ctx->key_b, ctx->val_b, n, 32, lb, ctx->scratch, s,
                                      &ctx->n_launch_sched));
     }
 
     // ---- stage 4 ----
-    u32 *head_flag = ctx->tmp_u32_a, *head_excl = ctx->tmp_u32_b, *s_arity = tmp_c, *s_items = tmp_d;
-    K(k_heads, n, T, ctx->key_a, ctx->val_a, head_flag, s_arity, s_items);
-    HIP_TRY(ctx, prim_scan_u32(head_flag, head_excl, n, nullptr, ctx->scratch, s));
-    HIP_TRY(ctx, prim_scan_u32(s_arity, T.s_in_off, n, nullptr, ctx->scratch, s));
-    HIP_TRY(ctx, prim_scan_u32(s_items, s_items, n, nullptr, ctx->scratch, s));
-    ctx->n_launch_sched += 3 * scan_launches;
-    K(k_batch_off, n, T, head_flag, head_excl, manual);
+    u32 *head_flag = ctx->tmp_u32_a, *s_items = tmp_d;
+    K(k_heads, n, T, ctx->key_a, ctx->val_a, head_flag, tri_in);
+    HIP_TRY(ctx, prim_scan_tri(tri_in, tri_ex, n, nullptr, ctx->scratch, s));
+    ctx->n_launch_sched += scan_launches;
+    K(k_batch_off, n, T, head_flag, tri_ex, s_items, manual);
     K(k_batch_layout, n, T, ctx->lay_in);
     HIP_TRY(ctx, prim_scan_lay(ctx->lay_in, T.lay, n, ctx->lay_total, ctx->scratch, s));
     ctx->n_launch_sched += scan_launches;
@@ -1582,7 +1642,7 @@ int sched_enqueue(ob_ctx *ctx)
     if (fuse && E > 0) {
         const size_t n_sort = n < SLOT_MAX_NB + 1 ? n : SLOT_MAX_NB + 1;
         // entries from n_batches on carry the largest key and stay where they are
-        HIP_TRY(ctx, prim_sort_pairs(ctx->key_a, ctx->val_a, ctx->key_b, ctx->val_b, n_sort, 0, 2 * SLOT_BITS,
+        HIP_TRY(ctx, prim_sort_pairs_swap(ctx->key_a, ctx->val_a, ctx->key_b, ctx->val_b, n_sort, 0, 2 * SLOT_BITS,
                                      ctx->scratch, s, &ctx->n_launch_sched, &T.hdr->n_batches));
     }
     u32 *cflag = ctx->tmp_u32_a, *cflag_excl = ctx->tmp_u32_b;
@@ -1602,10 +1662,10 @@ int sched_enqueue(ob_ctx *ctx)
     // ---- parameter-use items ----
     if (n_items > 0) {
         K(k_item_emit, n, T, s_items, ctx->key_a, ctx->val_a);
-        HIP_TRY(ctx, prim_sort_pairs(ctx->key_a, ctx->val_a, ctx->key_b, ctx->val_b, n_items, 0,
+        HIP_TRY(ctx, prim_sort_pairs_swap(ctx->key_a, ctx->val_a, ctx->key_b, ctx->val_b, n_items, 0,
                                      bit_width_u32((u32)ctx->max_param_rows), ctx->scratch, s,
                                      &ctx->n_launch_sched));
-        HIP_TRY(ctx, prim_sort_pairs(ctx->key_a, ctx->val_a, ctx->key_b, ctx->val_b, n_items, 32,
+        HIP_TRY(ctx, prim_sort_pairs_swap(ctx->key_a, ctx->val_a, ctx->key_b, ctx->val_b, n_items, 32,
                                      bit_width_u32((u32)n_slots), ctx->scratch, s, &ctx->n_launch_sched));
         K(k_item_finish, n_items, T, ctx->key_a, ctx->val_a, n_items);
     }
