@@ -239,7 +239,7 @@ int ob_stats_read(ob_ctx *ctx, ob_stats *out);
 #define OB_DBG_VAL_OFF 5   /* u32[n]  element offset of each node's row in the value arena */
 #define OB_DBG_TILES_FWD 6 /* forward tile descriptors in launch order, 40 words each (internal layout) */
 #define OB_DBG_TILES_PULL 7 /* backward pull tile descriptors in launch order, 48 words each (internal layout) */
-#define OB_DBG_CHAINS 8    /* launch chains, 8 words each: first, members, slot, fused, groups, groups per block, blocks, tiles per block */
+#define OB_DBG_CHAINS 8    /* launch chains, 12 words each: first, members, slot, fused, groups, groups per block, blocks, tiles per block, forward tiles per block, 3 reserved */
 #define OB_DBG_LORDER 9    /* u32 per batch: batch ids in launch order (the members of chain c are entries first .. first + members - 1) */
 int ob_debug_read(ob_ctx *ctx, int which, uint32_t *host_out, size_t cap_words, size_t *n_words);
 /* Internal knobs, for tests of the library's own error handling.  which: OB_DBG_SET_*; unknown: OB_E_ARG. */

@@ -208,6 +208,8 @@ static int params_to_device(ob_ctx *ctx)
         if (v.empty()) continue;
         HIP_TRY(ctx, hipMemcpyAsync(ctx->params[i].data, v.data(), v.size() * 4, hipMemcpyHostToDevice, ctx->stream));
         HIP_TRY(ctx, hipMemsetAsync(ctx->params[i].grad, 0, v.size() * 4, ctx->stream));
+        HIP_TRY(ctx, hipMemsetAsync(ctx->params[i].marks, 0, 256, ctx->stream));
+        HIP_TRY(ctx, hipMemsetAsync(ctx->params[i].row_flag, 0, (size_t)ctx->params[i].rows * 4, ctx->stream));
     }
     HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
     ctx->pending.clear();
@@ -229,7 +231,11 @@ int ob_param_create(ob_ctx *ctx, int rows, int cols, const float *host_init, int
     p.rows = rows; p.cols = cols;
     p.data = arena_array<float>(ctx, count);
     p.grad = arena_array<float>(ctx, count);
-    if (ctx->arena && (!p.data || !p.grad)) return ctx_fail(ctx, OB_E_OOM, "arena too small for a %d x %d parameter", rows, cols);
+    p.marks = arena_array<u32>(ctx, 64);
+    p.touched = arena_array<u32>(ctx, (size_t)rows);
+    p.row_flag = arena_array<u32>(ctx, (size_t)rows);
+    if (ctx->arena && (!p.data || !p.grad || !p.marks || !p.touched || !p.row_flag))
+        return ctx_fail(ctx, OB_E_OOM, "arena too small for a %d x %d parameter", rows, cols);
     ctx->persist_top = ctx->top;
     ctx->params.push_back(p);
     ctx->pending.resize(ctx->params.size());
@@ -299,8 +305,11 @@ int ob_param_grad_zero(ob_ctx *ctx)
         return OB_OK;
     }
     // parameters and their gradients are adjacent allocations; zero each gradient block
-    for (auto &p : ctx->params)
+    for (auto &p : ctx->params) {
         HIP_TRY(ctx, hipMemsetAsync(p.grad, 0, (size_t)p.rows * p.cols * 4, ctx->stream));
+        HIP_TRY(ctx, hipMemsetAsync(p.marks, 0, 256, ctx->stream));
+        HIP_TRY(ctx, hipMemsetAsync(p.row_flag, 0, (size_t)p.rows * 4, ctx->stream));
+    }
     return OB_OK;
 }
 
@@ -717,6 +726,7 @@ static int upload_param_tables(ob_ctx *ctx)
     for (size_t p = 0; p < ctx->params.size(); ++p) {
         const HostParam &hp = ctx->params[p];
         desc[p].data = hp.data; desc[p].grad = hp.grad; desc[p].rows = hp.rows; desc[p].cols = hp.cols;
+        desc[p].marks = hp.marks; desc[p].touched = hp.touched; desc[p].row_flag = hp.row_flag;
         if (ctx->params_used_w[p]) {
             // Workgroup g of a launch runs on XCD g % 8, and every XCD has its own L2.  A dW tile
             // (i0, j0) reads columns i0.. of every gradient row and columns j0.. of every operand
@@ -1227,7 +1237,7 @@ static int node_read(ob_ctx *ctx, int node, float *out, size_t cap, bool grad)
     const u32 d = ctx->out_dim[node];
     if (cap < d) return ctx_fail(ctx, OB_E_RANGE, "buffer holds %zu of %u elements", cap, d);
     u32 off = 0;
-    HIP_TRY(ctx, hipMemcpyAsync(&off, ctx->T.val_off + node, 4, hipMemcpyDeviceToHost, ctx->stream));
+    HIP_TRY(ctx, hipMemcpyAsync(&off, (grad ? ctx->T.nat_off : ctx->T.val_off) + node, 4, hipMemcpyDeviceToHost, ctx->stream));
     HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
     HIP_TRY(ctx, hipMemcpyAsync(out, (grad ? ctx->T.G : ctx->T.V) + off, (size_t)d * 4, hipMemcpyDeviceToHost, ctx->stream));
     HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));

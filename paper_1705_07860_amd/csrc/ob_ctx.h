@@ -53,6 +53,9 @@ struct HostParam {
     int rows, cols;
     float *data;   // device, inside the arena
     float *grad;   // device, inside the arena
+    u32 *marks;    // device: [0] dense gradient written, [1] number of touched rows (see ParamDesc)
+    u32 *touched;  // device: rows that LOOKUP gradients were added to
+    u32 *row_flag; // device: one word per row, 1 = listed in `touched`
 };
 
 struct ob_ctx;

@@ -726,6 +726,7 @@ __device__ inline void param_w_tile(const Tables &T, const PTile &pt, float *lds
             if (rr < m) P.grad[(size_t)rr * K + j] += out[q];
         }
     }
+    if (threadIdx.x == 0) P.marks[0] = 1u;   // this parameter's gradient is dense now
 }
 
 // db[i] += sum over uses of g[i].  A tile is 32 rows; the 8 groups of 32 threads take every 8th
@@ -759,6 +760,7 @@ __device__ inline void param_b_tile(const Tables &T, const PTile &pt, float *lds
         for (int q = 0; q < 8; ++q) s += lds[q * 32 + l32];
         P.grad[i] += s;
     }
+    if (threadIdx.x == 0) P.marks[0] = 1u;
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -845,7 +847,7 @@ __device__ inline void pull_tile(const Tables &T, const PullDesc &d, lds_float *
     const u32 total = d.nrows * d.d;
     const u32 root_pos = T.root_pos[0];
     const bool keep = (d.lflags & TF_OUT_LDS) != 0;
-    if (d.n_uni != PULL_GENERIC && d.vec4) {
+    if (d.n_uni != PULL_GENERIC && (d.vec4 & 1u)) {
         for (u32 x = tid * 4; x < total; x += nthr * 4) {
             const u32 dr = x / d.d, col = x % d.d, row = d.row0 + dr * d.rstride;
             const u32 own = d.val_off + row * d.d;
@@ -880,10 +882,11 @@ __device__ inline void pull_tile(const Tables &T, const PullDesc &d, lds_float *
             }
         } else {
             const u32 u = T.order[d.pos0 + row];
+            const u32 ownv = (d.vec4 & 2u) ? T.val_off[u] : own;   // a view's own values lie in its operand's row
             const u32 q1 = T.succ_off[u + 1];
             for (u32 q = T.succ_off[u]; q < q1; ++q) {
                 const EdgeRec er = T.edges[q];
-                acc += edge_term(T, cl, false, 0u, er.kind, er.goff, er.voff, er.a0, er.a1, own, col);
+                acc += edge_term(T, cl, false, 0u, er.kind, er.goff, er.voff, er.a0, er.a1, ownv, col);
             }
         }
         T.G[own + col] = acc;
@@ -1088,30 +1091,61 @@ __global__ __launch_bounds__(WG) void k_param_e(Tables T, u32 n_items)
             for (u32 it = i; it < end; ++it) acc += T.G[T.it_goff[it] + c];
             P.grad[(size_t)rowi * P.cols + c] += acc;
         }
+        // list the row for the update (once, however many minibatches add to it before the next clearing)
+        if (lane == 0 && atomicExch(&P.row_flag[rowi], 1u) == 0u) P.touched[atomicAdd(&P.marks[1], 1u)] = rowi;
     }
 }
 
 // theta <- theta - lr * gradient for every parameter (blockIdx.y = parameter); with zero_grad the
-// gradient is cleared in the same pass, ready for the next minibatch
+// gradient is cleared in the same pass, ready for the next minibatch (zero_grad == 2: only clear).
+// A parameter that only LOOKUPs have added to since its gradient was last cleared (an embedding
+// table) is walked by its touched rows, one workgroup per row: every other row has gradient zero,
+// so leaving it alone gives the same bits as the dense update (Section 2's update line touches the
+// parameters an instance used).  k_sgd_reset then empties the lists.
 __global__ __launch_bounds__(WG) void k_sgd(const ParamDesc *params, float lr, int zero_grad)
 {
     const ParamDesc P = params[blockIdx.y];
     const size_t count = (size_t)P.rows * P.cols;
-    if (zero_grad == 2) {   // only clear the gradients
-        for (size_t i = (size_t)blockIdx.x * WG + threadIdx.x; i < count; i += (size_t)gridDim.x * WG) P.grad[i] = 0.f;
+    if (P.marks[0]) {
+        if (zero_grad == 2) {
+            for (size_t i = (size_t)blockIdx.x * WG + threadIdx.x; i < count; i += (size_t)gridDim.x * WG) P.grad[i] = 0.f;
+            return;
+        }
+        for (size_t i = (size_t)blockIdx.x * WG + threadIdx.x; i < count; i += (size_t)gridDim.x * WG) {
+            P.data[i] -= lr * P.grad[i];
+            if (zero_grad) P.grad[i] = 0.f;
+        }
         return;
     }
-    for (size_t i = (size_t)blockIdx.x * WG + threadIdx.x; i < count; i += (size_t)gridDim.x * WG) {
-        P.data[i] -= lr * P.grad[i];
-        if (zero_grad) P.grad[i] = 0.f;
+    const u32 nt = P.marks[1];
+    for (u32 t = blockIdx.x; t < nt; t += gridDim.x) {
+        const size_t base = (size_t)P.touched[t] * P.cols;
+        for (u32 c = threadIdx.x; c < (u32)P.cols; c += WG) {
+            if (zero_grad != 2) P.data[base + c] -= lr * P.grad[base + c];
+            if (zero_grad) P.grad[base + c] = 0.f;
+        }
     }
 }
 
-__global__ void k_gather_all(Tables T, const float *src, float *dst, const u32 *dst_off)
+// after k_sgd with zero_grad: the gradients are zero again, so no row is touched and nothing is dense
+__global__ __launch_bounds__(WG) void k_sgd_reset(const ParamDesc *params)
+{
+    const ParamDesc P = params[blockIdx.x];
+    const u32 nt = P.marks[1];
+    if (P.marks[0]) {   // (a dense gradient may hide touched rows beyond the list's reach: clear every flag)
+        for (u32 r = threadIdx.x; r < (u32)P.rows; r += WG) P.row_flag[r] = 0u;
+    } else {
+        for (u32 t = threadIdx.x; t < nt; t += WG) P.row_flag[P.touched[t]] = 0u;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) { P.marks[0] = 0u; P.marks[1] = 0u; }
+}
+
+__global__ void k_gather_all(Tables T, const float *src, const u32 *src_off, float *dst, const u32 *dst_off)
 {
     const u32 v = blockIdx.x;
     const u32 d = T.out_dim[v];
-    const float *s = src + T.val_off[v];
+    const float *s = src + src_off[v];
     float *o = dst + dst_off[v];
     for (u32 c = threadIdx.x; c < d; c += blockDim.x) o[c] = s[c];
 }
@@ -1151,6 +1185,7 @@ constexpr u32 GRID_CAP = 4096;
 // run length to pass to a step kernel: the slot's common tiles-per-work-item count, or 0 when its
 // chains differ (the kernel then reads each work item's record)
 static inline u32 slot_run_len(const SlotRec &r) { return r.lmin == ~r.nlmax ? r.lmin : 0u; }
+static inline u32 slot_run_len_fwd(const SlotRec &r) { return r.lminf == ~r.nlmaxf ? r.lminf : 0u; }
 
 // dynamic LDS of a step launch: the slot's fused chains' need, at least the GEMM reduction space
 constexpr size_t FWD_LDS_MIN = (size_t)(WIDE_LDS_FLOATS > (u32)LDS_FLOATS ? WIDE_LDS_FLOATS : (u32)LDS_FLOATS) * 4;   // staged wide tile / accumulator blocks
@@ -1189,10 +1224,10 @@ static int launch_forward_steps(ob_ctx *ctx)
         if (hi > lo) {
             if (r.plain & 1u)
                 hipLaunchKernelGGL(k_fwd_step<true>, dim3(grid_for(hi - lo, GRID_CAP)), dim3(WG), slot_lds_bytes(r, 16), s,
-                                   lo, hi, r.tf, slot_run_len(r), T.tiles_f, T.works_f, T);
+                                   lo, hi, r.tf, slot_run_len_fwd(r), T.tiles_f, T.works_f, T);
             else
                 hipLaunchKernelGGL(k_fwd_step<false>, dim3(grid_for(hi - lo, GRID_CAP)), dim3(WG),
-                                   slot_lds_bytes(r, FWD_LDS_MIN), s, lo, hi, r.tf, slot_run_len(r), T.tiles_f, T.works_f, T);
+                                   slot_lds_bytes(r, FWD_LDS_MIN), s, lo, hi, r.tf, slot_run_len_fwd(r), T.tiles_f, T.works_f, T);
             ++ctx->n_launch_fwd;
         }
     }
@@ -1332,13 +1367,14 @@ hipError_t exec_sgd(const ParamDesc *params_dev, u32 n_params, size_t max_count,
     if (bx < 1) bx = 1;
     if (bx > 1024) bx = 1024;
     hipLaunchKernelGGL(k_sgd, dim3((unsigned)bx, n_params), dim3(WG), 0, s, params_dev, lr, zero_grad);
+    if (zero_grad) hipLaunchKernelGGL(k_sgd_reset, dim3(n_params), dim3(WG), 0, s, params_dev);
     return hipGetLastError();
 }
 
 hipError_t exec_gather_all(const Tables &T, int which, float *dst, const u32 *dst_off, hipStream_t s)
 {
     if (T.n == 0) return hipSuccess;
-    hipLaunchKernelGGL(k_gather_all, dim3(T.n), dim3(64), 0, s, T, which ? T.G : T.V, dst, dst_off);
+    hipLaunchKernelGGL(k_gather_all, dim3(T.n), dim3(64), 0, s, T, which ? T.G : T.V, which ? T.nat_off : T.val_off, dst, dst_off);
     return hipGetLastError();
 }
 

@@ -41,7 +41,9 @@ enum : u32 {
     TF_SRC_LDS = 16u,        // << j: operand slot / consumer edge j is read from the chain's LDS copy
     TF_OUT_LDS = 256u,       // the tile also writes its result to the chain's LDS copy
     TF_GLOBAL_DEP = 512u,    // reads a result of an earlier member of the same chain from global memory
-    TF_SIMPLE = 1024u        // float4 tile of ADD (<= 4 operands) / CMULT / TANH / SIGMOID / SLICE whose operand rows are all evenly spaced
+    TF_SIMPLE = 1024u,       // float4 tile of ADD (<= 4 operands) / CMULT / TANH / SIGMOID / SLICE whose operand rows are all evenly spaced
+    TF_VIEW = 2048u          // batch flag: a SLICE batch; its rows are not copied, every reader is pointed at the range of the
+                             // operand row instead (Section 3.3: inputs that already lie in place are used as they are)
 };
 
 // Kinds of consumer-edge records read by the backward pull (one per graph edge).
@@ -77,9 +79,16 @@ struct BatchRec {  // one per batch, 64 bytes
     u32 vec4;            // TF_VEC4 | TF_ALIGNED | TF_G_ALIAS
 };
 
+// marks[0]: a dense gradient kernel (dW / db) has added to this parameter since its gradient was last
+// cleared; marks[1]: number of rows in `touched`.  touched / row_flag: the rows of the parameter that
+// LOOKUP gradients have been added to since then (each once; row_flag[r] = 1 for listed rows).  With
+// these the update and the clearing of an embedding table walk the touched rows only.
 struct ParamDesc {
     float *data;
     float *grad;
+    u32 *marks;
+    u32 *touched;
+    u32 *row_flag;
     i32 rows, cols;
 };
 
@@ -134,6 +143,7 @@ struct ChainRec {
     u32 first, k;          // members are lorder[first .. first + k)
     u32 slot, fused;       // fused: component-wise members tiled by group blocks (2: with results handed on through LDS)
     u32 G, Rg, nrb, kt;    // groups, groups per block, number of blocks, tiles per block (sum of rows per group)
+    u32 ktf, pad0, pad1, pad2;   // forward tiles per block: kt without the members that are views (they have no forward work)
 };
 struct CLay {              // scan element of the per-chain launch layout
     u32 tf, wf, ta, wa, tb, p0, p1, p2;   // forward tiles/work items, pull tiles/work items, dX tiles
@@ -155,7 +165,8 @@ struct WorkRec { u32 first, len; };   // a workgroup runs tiles [first, first + 
 // slots without such chains keep more workgroups resident per CU.
 // plain != 0: every forward work item of the slot is component-wise (no GEMM, reduction or wide-sum
 // tile), so the slot can run the lean instantiation of the forward kernel.
-struct SlotRec { u32 wf, wa, tb, tf, ta, lmin, nlmax, dx_free, lds_need, plain, pad0, pad1; };
+// lminf / nlmaxf: the same pair of run lengths over the slot's forward work items (views have none).
+struct SlotRec { u32 wf, wa, tb, tf, ta, lmin, nlmax, dx_free, lds_need, plain, lminf, nlmaxf; };
 
 // Static tile of the deferred parameter-gradient kernels (built on the host per parameter set).
 struct PTile { i32 param; i32 i0, j0; i32 pad; };
@@ -205,7 +216,9 @@ struct Tables {
     u64 *ht_keys; u32 *ht_vals; u32 ht_mask; u32 *ht_slot;
     u32 *order; u32 *pos_of; u32 *batch_of_pos; u32 *s_aux0; u32 *s_in_off;
     u32 *batch_off; BatchRec *batches; Lay *lay; u32 *b_indim;
-    u32 *val_off; u32 *dx_off; u32 *opnd_off;
+    u32 *val_off;          // per node: where its value row lies in V (for a SLICE node: inside its operand's row)
+    u32 *nat_off;          // per node: its row in its batch's own block; the gradient arena uses this one
+    u32 *dx_off; u32 *opnd_off;
     u32 *dx_gsrc;          // per schedule position of a MATVEC node with one consumer: where that consumer's gradient row lies
     u32 *slot_of; u32 *label_of; u32 *lorder;
     u32 *blevel;           // per batch: its step (depth mode) or its level inside its fused chain (agenda mode)

@@ -621,6 +621,7 @@ __global__ void k_batch_layout(Tables T, Lay *lay_in)
         r.opnd = T.s_in_off[p0];
         r.vec4 = TF_VEC4 | TF_ALIGNED | TF_G_ALIAS;   // cleared below by whatever a member violates
         if (r.op == OP_MATVEC && B >= WIDE_MIN_ROWS && r.d >= (u32)GTW) r.vec4 |= TF_WIDE;
+        if (r.op == OP_SLICE) r.vec4 |= TF_VIEW;
         T.batches[b] = r;
         const u64 vs = (u64)B * r.d;
         L.val = (vs + VAL_ALIGN - 1) / VAL_ALIGN * VAL_ALIGN;
@@ -659,8 +660,20 @@ __global__ void k_node_offsets(Tables T)
     const BatchRec &r = T.batches[T.batch_of_pos[p]];
     const u32 row = p - r.pos0;
     const u32 v = T.order[p];
-    T.val_off[v] = r.val_off + row * r.d;
+    T.val_off[v] = T.nat_off[v] = r.val_off + row * r.d;
     T.dx_off[v] = (r.op == OP_MATVEC) ? r.dx_off + row * r.k : 0u;
+}
+
+// SLICE nodes are views: their value is the range [lo, hi) of the operand's row where it lies
+// (through any number of slices of slices), so nothing is copied forward and every reader of the
+// node is pointed there.  Their gradient rows stay in their own batch's block (nat_off).
+__global__ void k_view_offsets(Tables T)
+{
+    const u32 v = blockIdx.x * blockDim.x + threadIdx.x;
+    if (v >= T.n || T.op[v] != OP_SLICE) return;
+    u32 x = v, acc = 0;
+    while (T.op[x] == OP_SLICE) { acc += (u32)T.aux0[x]; x = T.in_idx[T.in_off[x]]; }   // ids fall: ends at a node that owns its row
+    T.val_off[v] = T.nat_off[x] + acc;
 }
 
 // Per node: the check that every member of a batch really has the signature tuple of the batch
@@ -975,10 +988,11 @@ __global__ void k_chain_recs(Tables T, int agenda, const u32 *bset, const u32 *f
             dmax = rm.d > dmax ? rm.d : dmax;
             G = gcd_u32(G, rm.B);
         }
-        u32 kt = 0, per_group = 0;   // tiles per block; floats one group of every member takes
+        u32 kt = 0, ktf = 0, per_group = 0;   // tiles per block (all members / members with forward work); floats one group of every member takes
         for (u32 m = 0; m < k; ++m) {
             const BatchRec &rm = T.batches[T.lorder[i + m]];
             kt += rm.B / G;
+            if (!(rm.vec4 & TF_VIEW)) ktf += rm.B / G;
             per_group += (rm.B / G) * rm.d;
         }
         cr.G = G; cr.Rg = rows_per_block(dmax);
@@ -989,9 +1003,10 @@ __global__ void k_chain_recs(Tables T, int agenda, const u32 *bset, const u32 *f
             if (fit >= 1) { cr.fused = 2u; if (fit < cr.Rg) cr.Rg = fit; }
         }
         cr.nrb = cdiv(G, cr.Rg); cr.kt = cr.fused ? kt : 1u;
+        cr.ktf = cr.fused ? ktf : 1u; cr.pad0 = cr.pad1 = cr.pad2 = 0;
         if (cr.fused) {
-            L.tf = L.ta = cr.nrb * kt;
-            L.wf = L.wa = cr.nrb;
+            L.ta = cr.nrb * kt; L.wa = cr.nrb;
+            L.tf = cr.nrb * ktf; L.wf = ktf ? cr.nrb : 0u;     // a chain of views only has no forward work
         } else {
             switch (r0.op) {
             case OP_MATVEC: {
@@ -1030,6 +1045,7 @@ __global__ void k_slot_init(Tables T)
     if (s > T.hdr->n_slots) return;
     SlotRec r; r.wf = r.wa = r.tb = r.tf = r.ta = r.lmin = r.nlmax = r.dx_free = 0xffffffffu;
     r.lds_need = 0;
+    r.lminf = r.nlmaxf = 0xffffffffu;
     r.plain = 0xffffffffu;
     T.slots[s] = r;
 }
@@ -1056,6 +1072,11 @@ __global__ void k_slot_tables(Tables T, const CLay *clay_ex, const CLay *total)
     const u32 len = cr.fused ? cr.kt : 1u;
     atomicMin(&S.lmin, len);
     atomicMin(&S.nlmax, ~len);
+    const u32 lenf = cr.fused ? cr.ktf : 1u;
+    if (lenf) {   // (a chain of views has no forward work item)
+        atomicMin(&S.lminf, lenf);
+        atomicMin(&S.nlmaxf, ~lenf);
+    }
     if (c == nc - 1) {
         const CLay t = *total;
         SlotRec &E = T.slots[s + 1];
@@ -1224,7 +1245,7 @@ __device__ inline void fill_pull_base(const Tables &T, const BatchRec &r, u32 ro
     d.pos0 = r.pos0; d.B = r.B; d.d = r.d; d.val_off = r.val_off;
     d.depth = r.step; d.row0 = row0; d.nrows = nrows; d.n_uni = PULL_GENERIC; d.rstride = rstride;
     for (int j = 0; j < 4; ++j) { UEdge z; z.kind = 0; z.goff = z.voff = z.gs = z.vs = 0; z.a0 = z.a1 = 0; d.e[j] = z; }
-    d.grp_len = 1; d.vec4 = 0;
+    d.grp_len = 1; d.vec4 = (r.vec4 & TF_VIEW) ? 2u : 0u;   // bit 1: the batch is a view (its values lie in its operands' rows)
     if (nrows > PULL_MAX_ROWS) return;
     const u32 u0 = T.order[r.pos0 + row0];
     const u32 q0 = T.succ_off[u0];
@@ -1234,6 +1255,7 @@ __device__ inline void fill_pull_base(const Tables &T, const BatchRec &r, u32 ro
     for (u32 j = 0; j < cnt; ++j) {
         first[j] = T.edges[q0 + j];
         if (first[j].kind == EK_NLS) return;     // the label is per-row data
+        if (first[j].kind == EK_SQN && (r.vec4 & TF_VIEW)) return;   // needs the rows' own values, which a view keeps elsewhere
         UEdge ue; ue.kind = first[j].kind; ue.goff = first[j].goff; ue.voff = first[j].voff;
         ue.gs = ue.vs = 0; ue.a0 = first[j].a0; ue.a1 = first[j].a1;
         d.e[j] = ue;
@@ -1259,7 +1281,7 @@ __device__ inline void fill_pull_base(const Tables &T, const BatchRec &r, u32 ro
         if ((ue.kind == EK_MUL || ue.kind == EK_DTANH || ue.kind == EK_DSIGM) && ((ue.voff | ue.vs) & 3u)) vec = false;
         if (ue.kind == EK_RANGE && (((u32)ue.a0 | (u32)ue.a1) & 3u)) vec = false;
     }
-    d.vec4 = vec ? 1u : 0u;
+    d.vec4 = (d.vec4 & 2u) | (vec ? 1u : 0u);
 }
 
 __device__ inline void fill_pull_desc(const Tables &T, const BatchRec &r, u32 row0, u32 nrows, u32 rstride, PullDesc &d,
@@ -1272,7 +1294,7 @@ __device__ inline void fill_pull_desc(const Tables &T, const BatchRec &r, u32 ro
     if (cc->cr.fused != 2u) { d.lflags = TF_GLOBAL_DEP; return; }
     d.lds_out = chain_own_delta(T, *cc, r);
     d.lflags = TF_OUT_LDS;
-    if (d.lds_out & 3u) d.vec4 = 0;
+    if (d.lds_out & 3u) d.vec4 &= ~1u;
     if (d.n_uni == PULL_GENERIC) { d.lflags |= TF_GLOBAL_DEP; return; }
     u32 lo[4], hi[4], state[4], delta[4];
     for (u32 j = 0; j < d.n_uni; ++j) {
@@ -1281,7 +1303,7 @@ __device__ inline void fill_pull_desc(const Tables &T, const BatchRec &r, u32 ro
     }
     chain_lookup(T, *cc, d.n_uni, lo, hi, state, delta);
     for (u32 j = 0; j < d.n_uni; ++j) {
-        if (state[j] == 1 && (!d.vec4 || (delta[j] & 3u) == 0)) { d.lflags |= TF_SRC_LDS << j; d.lds_g[j] = delta[j]; }
+        if (state[j] == 1 && (!(d.vec4 & 1u) || (delta[j] & 3u) == 0)) { d.lflags |= TF_SRC_LDS << j; d.lds_g[j] = delta[j]; }
         else if (state[j] != 0) d.lflags |= TF_GLOBAL_DEP;
     }
 }
@@ -1320,7 +1342,7 @@ __global__ void k_tiles(Tables T, const CLay *clay_ex, const CLay *total, u32 ca
             if (which >= 3) {   // work item = one block of a fused chain, or one tile
                 WorkRec w;
                 const bool fwd = which == 3;
-                const u32 len = cr.fused ? cr.kt : 1u;
+                const u32 len = cr.fused ? (fwd ? cr.ktf : cr.kt) : 1u;
                 w.first = (fwd ? clay_ex[c].tf : clay_ex[c].ta) + xx * len;
                 w.len = len;
                 (fwd ? T.works_f : T.works_a)[x] = w;
@@ -1332,13 +1354,17 @@ __global__ void k_tiles(Tables T, const CLay *clay_ex, const CLay *total, u32 ca
             } else {
                 // tile `it` of block rb: member m, its q-th row of every group in the block
                 // (pull tiles walk the members deepest first)
-                const u32 rb = xx / cr.kt;
-                u32 it = xx % cr.kt;
-                if (which == 1) it = cr.kt - 1 - it;
+                // (forward: members that are views have no tiles and are stepped over)
+                const u32 ktx = which == 0 ? cr.ktf : cr.kt;
+                const u32 rb = xx / ktx;
+                u32 it = xx % ktx;
+                if (which == 1) it = ktx - 1 - it;
                 u32 m = 0, mult = 1;
                 if (cr.fused) {
                     for (;; ++m) {
-                        mult = T.batches[T.lorder[cr.first + m]].B / cr.G;
+                        const BatchRec &rq = T.batches[T.lorder[cr.first + m]];
+                        if (which == 0 && (rq.vec4 & TF_VIEW)) continue;
+                        mult = rq.B / cr.G;
                         if (it < mult) break;
                         it -= mult;
                     }
@@ -1358,7 +1384,7 @@ __global__ void k_tiles(Tables T, const CLay *clay_ex, const CLay *total, u32 ca
                         for (u32 mm = m + 1; mm < cr.k; ++mm) {
                             const BatchRec &rn = T.batches[T.lorder[cr.first + mm]];
                             if (T.blevel[T.lorder[cr.first + mm]] != my_level) break;
-                            glen += rn.B / cr.G;
+                            if (!(rn.vec4 & TF_VIEW)) glen += rn.B / cr.G;
                         }
                     } else {
                         glen = it + 1;
@@ -1370,7 +1396,7 @@ __global__ void k_tiles(Tables T, const CLay *clay_ex, const CLay *total, u32 ca
                     }
                 }
                 ChainCtx cc; cc.cr = cr; cc.m = m; cc.g0 = g0; cc.ng = ng;
-                const ChainCtx *pcc = (cr.fused && cr.kt > 1) ? &cc : nullptr;
+                const ChainCtx *pcc = (cr.fused && ktx > 1) ? &cc : nullptr;
                 if (which == 1) {
                     PullDesc d;
                     fill_pull_desc(T, r, row0, ng, mult, d, pcc);
@@ -1397,7 +1423,7 @@ __global__ void k_edges(Tables T)
     const u32 v = T.edge_cons[e];
     const u32 lo = T.in_off[v];
     const u32 j = e - lo;
-    EdgeRec r; r.kind = EK_PLAIN; r.goff = T.val_off[v]; r.voff = 0; r.a0 = 0; r.a1 = 0;
+    EdgeRec r; r.kind = EK_PLAIN; r.goff = T.nat_off[v]; r.voff = 0; r.a0 = 0; r.a1 = 0;
     switch (T.op[v]) {
     case OP_MATVEC: r.goff = T.dx_off[v]; break;
     case OP_ADD: break;
@@ -1453,7 +1479,7 @@ __global__ void k_item_finish(Tables T, const u64 *keys, const u32 *vals, u32 n_
     const u32 v = T.order[p];
     T.it_key[i] = k;
     T.it_pos[i] = p;
-    T.it_goff[i] = T.val_off[v];
+    T.it_goff[i] = T.nat_off[v];
     T.it_xoff[i] = (T.op[v] == OP_MATVEC) ? T.val_off[T.in_idx[T.in_off[v]]] : 0u;
     if (i == 0 || (u32)(keys[i - 1] >> 32) != slot) T.pu_start[slot] = i;
     if (i == n_items - 1 || (u32)(keys[i + 1] >> 32) != slot) T.pu_end[slot] = i + 1;
@@ -1535,7 +1561,7 @@ int sched_enqueue(ob_ctx *ctx)
     A(T.order, u32, n); A(T.pos_of, u32, n); A(T.batch_of_pos, u32, n); A(T.s_aux0, u32, n);
     A(T.s_in_off, u32, n + 1);
     A(T.batch_off, u32, n + 1); A(T.batches, BatchRec, n); A(T.lay, Lay, n); A(T.b_indim, u32, E + 1);
-    A(T.val_off, u32, n); A(T.dx_off, u32, n); A(T.opnd_off, u32, E + 1); A(T.dx_gsrc, u32, n);
+    A(T.val_off, u32, n); A(T.nat_off, u32, n); A(T.dx_off, u32, n); A(T.opnd_off, u32, E + 1); A(T.dx_gsrc, u32, n);
     A(T.slot_of, u32, n); A(T.label_of, u32, n); A(T.blevel, u32, n);
     A(T.chain_of_batch, u32, n);
     A(T.lorder, u32, n); A(T.chains, ChainRec, n); A(T.clay, CLay, n); A(T.chain_of_lpos, u32, n);
@@ -1629,6 +1655,7 @@ int sched_enqueue(ob_ctx *ctx)
     ctx->n_launch_sched += scan_launches;
     K(k_batch_finish, n, T, T.lay, ctx->lay_total);
     K(k_node_offsets, n, T);
+    K(k_view_offsets, n, T);
     K(k_member_check, n, T);
     if (E > 0) K(k_opnd, E, T);
     if (E > 0) K(k_edges, E, T);

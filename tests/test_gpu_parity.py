@@ -210,7 +210,7 @@ def test_early_placement_and_launch_plan_invariants(name, workload_cache):
         c, root = run_gpu(p, g, ob.OB_BYDEPTH, fuse=level)
         bo, ids, bd, _ = c.schedule_read()
         assert np.array_equal(bo, rbo) and np.array_equal(ids, rids) and np.array_equal(bd, rbd)
-        ch = c.debug_read(ob.OB_DBG_CHAINS).reshape(-1, 8)
+        ch = c.debug_read(ob.OB_DBG_CHAINS).reshape(-1, 12)
         st = c.stats()
         assert int(ch[:, 1].sum()) == st["n_batches"]                      # members partition the batches
         assert np.array_equal(ch[:, 0], np.concatenate([[0], np.cumsum(ch[:, 1])[:-1]]))
@@ -467,6 +467,54 @@ def test_backward_from_a_one_row_matrix_product_with_one_consumer():
         assert rel_err(c.param_grad_read(pid, m.shape), o.param_grad(pid)) <= TOL
     assert c.grad_read(z, 1)[0] == 0.0           # not an ancestor of the root
     c.close()
+
+
+@pytest.mark.parametrize("mode", ["depth", "agenda", "nobatch"])
+def test_slices_are_views_of_their_operand_rows(mode):
+    """SLICE nodes are never copied: readers are pointed at the range of the operand's row.  Covers
+    slices of slices, ranges that are not multiples of 4, slices of leaves and of matrix products,
+    slices read by every kind of consumer (including the per-row reductions, which need the slice's
+    own values in the backward pass), a slice as the operand of a shared-weight product (its rows
+    feed the weight gradient), fan-out from one row into overlapping slices, and reading a slice's
+    value and gradient back."""
+    from paper_1705_07860_amd import binding as ob
+    rng = np.random.default_rng(8)
+    pb = wl.ParamBuilder(rng, std=0.4)
+    W = pb.add("W", 12, 10)
+    b = pb.add("b", 12, 1)
+    U = pb.add("U", 5, 6)
+    E = pb.add("E", 9, 10)
+    p = pb.done()
+    gb = wl.GraphBuilder(p)
+    losses = []
+    for i in range(7):
+        x = gb.input(rng.standard_normal(10)) if i % 2 else gb.lookup(E, i)
+        y = gb.matvec(W, b, x)                       # 12
+        s1 = gb.slice(y, 1, 11)                      # 10, unaligned
+        s2 = gb.slice(s1, 2, 8)                      # 6: slice of a slice = y[3:9)
+        s3 = gb.slice(y, 4, 12)                      # overlaps s1
+        s4 = gb.slice(x, 3, 9)                       # slice of a leaf
+        t = gb.tanh(s2)
+        m = gb.cmult(gb.sigmoid(s4), s2)
+        z = gb.matvec(U, -1, s2)                     # a view as GEMM operand (dW reads its rows)
+        cat = gb.concat((s3, t, gb.slice(s3, 0, 4)))
+        losses += [gb.sqnorm(s1), gb.pick_nls(s3, i % 8), gb.sqnorm(gb.add((m, t))), gb.pick_nls(z, i % 5),
+                   gb.sqnorm(cat), gb.sqnorm(gb.slice(cat, 5, 9))]
+    root = gb.add(losses)
+    g = gb.finish(root, 7)
+    o = Oracle(g, p, "f64")
+    o.forward()
+    o.backward(g.root)
+    m_ = {"depth": ob.OB_BYDEPTH, "agenda": ob.OB_BYAGENDA, "nobatch": ob.OB_NOBATCH}[mode]
+    for fuse in ((2, 0) if mode == "depth" else (2,)):
+        c, root_ = run_gpu(p, g, m_, fuse=fuse, arena=128 << 20)
+        check_against_oracle(c, p, g, o, root_, what=f"slice views/{mode}/fuse {fuse}")
+        for v in np.nonzero(g.op == wl.OP_SLICE)[0][:9]:
+            assert rel_err(c.value_read(int(v), int(g.out_dim[v])), o.value(int(v))) <= TOL
+            assert rel_err(c.grad_read(int(v), int(g.out_dim[v])), o.node_grad(int(v))) <= TOL
+        st = c.stats()
+        c.close()
+    say(f"  slice views/{mode}: {st['n_batches']} batches, {st['n_tiles_fwd']} forward tiles")
 
 
 def _graph_part(g, lo, hi):
@@ -902,6 +950,73 @@ def test_sgd_step_matches_the_oracle_and_lowers_the_loss():
     say(f"  loss {loss0:.5f} -> {loss1:.5f}")
     assert loss1 < loss0
     c.close()
+
+
+def test_update_walks_the_touched_rows_of_an_embedding_table():
+    """Two minibatches (two contexts on one parameter set) add their gradients before one update:
+    the table's touched rows are the union of both, every other row keeps its bits, the dense
+    matrices are updated as before, and afterwards every gradient is zero again, so that a third
+    backward pass gives that minibatch's gradient alone.  Then the same with the gradients only
+    cleared (no update)."""
+    from paper_1705_07860_amd import binding as ob
+    p = wl.tagger_params()
+    ga = wl.tagger_minibatch(p, seed=wl.SEED_BASE + 41, lengths=[4, 7, 2])
+    gb_ = wl.tagger_minibatch(p, seed=wl.SEED_BASE + 42, lengths=[6, 3])
+    oa, ob_ = Oracle(ga, p, "f64"), Oracle(gb_, p, "f64")
+    for o, g in ((oa, ga), (ob_, gb_)):
+        o.forward()
+        o.backward(g.root)
+    ca = ob.Context(arena_bytes=512 << 20)
+    ca.params_create(p)
+    ca.param_grad_zero()
+    cb = ca.fork(arena_bytes=512 << 20, stream=ca._stream)
+    for c, g in ((ca, ga), (cb, gb_)):
+        c.add_bulk(g)
+        c.forward(g.root)
+        c.backward(g.root)
+    emb = p.index("E") if "E" in p.names else max(range(len(p.mats)), key=lambda i: p.mats[i].shape[0])
+    before = [m.copy() for m in p.mats]
+    lr = 0.1
+    ca.sgd_step(lr, zero_grad=True)
+    rows_a = set(int(r) for r in ga.aux0[ga.op == wl.OP_LOOKUP])
+    rows_b = set(int(r) for r in gb_.aux0[gb_.op == wl.OP_LOOKUP])
+    touched = sorted(rows_a | rows_b)
+    for pid, m in enumerate(p.mats):
+        ref = m.astype(np.float64) - lr * (oa.param_grad(pid) + ob_.param_grad(pid))
+        got = ca.param_read(pid, m.shape)
+        assert rel_err(got, ref) <= TOL, p.names[pid]
+        assert not np.any(ca.param_grad_read(pid, m.shape)), p.names[pid]
+    got_e = ca.param_read(emb, p.mats[emb].shape)
+    untouched = np.ones(p.mats[emb].shape[0], bool)
+    untouched[touched] = False
+    assert np.array_equal(got_e[untouched], before[emb][untouched])       # bit for bit
+    assert np.all(np.any(got_e[touched] != before[emb][touched], axis=1))
+    # a third backward pass: this minibatch's gradient alone (nothing left over in rows only the others touched)
+    cb.reset()
+    cb.forward(gb_.root)
+    cb.backward(gb_.root)
+    params_now = wl.Params([ca.param_read(pid, m.shape) for pid, m in enumerate(p.mats)], p.names)
+    o3 = Oracle(gb_, params_now, "f64")
+    o3.forward()
+    o3.backward(gb_.root)
+    for pid, m in enumerate(p.mats):
+        assert rel_err(cb.param_grad_read(pid, m.shape), o3.param_grad(pid)) <= TOL, p.names[pid]
+    only_a = sorted(rows_a - rows_b)
+    assert not np.any(cb.param_grad_read(emb, p.mats[emb].shape)[only_a])
+    # clearing alone walks the touched rows too
+    ca.param_grad_zero()
+    for pid, m in enumerate(p.mats):
+        assert not np.any(ca.param_grad_read(pid, m.shape)), p.names[pid]
+    ca.reset()
+    ca.forward(ga.root)
+    ca.backward(ga.root)
+    o4 = Oracle(ga, params_now, "f64")
+    o4.forward()
+    o4.backward(ga.root)
+    for pid, m in enumerate(p.mats):
+        assert rel_err(ca.param_grad_read(pid, m.shape), o4.param_grad(pid)) <= TOL, p.names[pid]
+    cb.close()
+    ca.close()
 
 
 def test_synthetic_equal_length_tagger_small():
