@@ -280,7 +280,7 @@ def measure(args, ob, torch, name, steps, warmup, sustain_s, cpu_s, headline):
     # is measured live.  Each kernel has two instantiations (k_..._step<false>: any work;
     # k_..._step<true>: launches with component-wise work only); the figures cover both.
     fwd_ms, n_fwd = phase["ms_forward"], max(launches["n_launch_fwd"], 1)
-    bwd_ms, n_bwd = phase["ms_backward"] - phase["ms_param_grads"], max(launches["n_launch_bwd"] - 4 * cover, 1)
+    bwd_ms, n_bwd = phase["ms_backward"] - phase["ms_param_grads"], max(launches["n_launch_bwd"] - 5 * cover, 1)
 
     def kernel_figures(kname, ms, nl, nbytes):
         ach = nbytes / (ms * 1e-3) / 1e9

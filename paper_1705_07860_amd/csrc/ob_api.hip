@@ -732,11 +732,11 @@ static int upload_param_tables(ob_ctx *ctx)
             // (i0, j0) reads columns i0.. of every gradient row and columns j0.. of every operand
             // row, so tiles are ordered such that an XCD keeps to one eighth of the gradient
             // columns: the (larger) gradient block is then fetched once instead of once per XCD.
-            const int R = (hp.rows + GT - 1) / GT, C = (hp.cols + GT - 1) / GT;
+            const int R = (hp.rows + PWTILE - 1) / PWTILE, C = (hp.cols + PWTILE - 1) / PWTILE;
             std::vector<std::vector<PTile>> group(8);
             for (int rt = 0; rt < R; ++rt)
                 for (int ct = 0; ct < C; ++ct)
-                    group[(size_t)((long long)rt * 8 / R)].push_back(PTile{(i32)p, rt * GT, ct * GT, 0});
+                    group[(size_t)((long long)rt * 8 / R)].push_back(PTile{(i32)p, rt * PWTILE, ct * PWTILE, R * C >= 32 ? 4 : (R * C >= 8 ? 8 : PW_SPLIT_MAX)});
             size_t left = (size_t)R * C;
             std::vector<size_t> next(8, 0);
             while (left) {
@@ -757,7 +757,13 @@ static int upload_param_tables(ob_ctx *ctx)
     ctx->params_dev = arena_array<ParamDesc>(ctx, desc.size() + 1);
     ctx->wtiles_dev = arena_array<PTile>(ctx, ctx->wtiles.size() + 1);
     ctx->btiles_dev = arena_array<PTile>(ctx, ctx->btiles.size() + 1);
-    if (!ctx->params_dev || !ctx->wtiles_dev || !ctx->btiles_dev) return ctx_fail(ctx, OB_E_OOM, "arena too small for parameter tables");
+    // a matrix of few tiles gets more workgroups per tile; pad = runs | first partial block << 8
+    size_t n_part = 0;
+    for (PTile &t : ctx->wtiles) { const size_t runs = (size_t)t.pad; t.pad = (i32)(runs | (n_part << 8)); n_part += runs; }
+    if (n_part >= (1u << 23)) return ctx_fail(ctx, OB_E_RANGE, "too many weight-gradient tiles");
+    ctx->wpart_dev = arena_array<float>(ctx, n_part * (size_t)PWTILE * PWTILE + 1);
+    if (!ctx->params_dev || !ctx->wtiles_dev || !ctx->btiles_dev || !ctx->wpart_dev)
+        return ctx_fail(ctx, OB_E_OOM, "arena too small for parameter tables");
     ctx->persist_top = ctx->top;
     if (!desc.empty())
         HIP_TRY(ctx, hipMemcpyAsync(ctx->params_dev, desc.data(), desc.size() * sizeof(ParamDesc), hipMemcpyHostToDevice, ctx->stream));
@@ -1012,7 +1018,7 @@ static void stage_rebase(ob_ctx *c, ob_ctx *owner, char *arena, size_t bytes)
     c->params = owner->params; c->max_param_rows = owner->max_param_rows;
     c->params_used_w.assign(c->params.size(), 0);
     c->params_used_b.assign(c->params.size(), 0);
-    c->params_dev = nullptr; c->wtiles_dev = c->btiles_dev = nullptr;
+    c->params_dev = nullptr; c->wtiles_dev = c->btiles_dev = nullptr; c->wpart_dev = nullptr;
     c->params_dirty = true;
     c->err.clear();
 }
@@ -1121,6 +1127,7 @@ static int stage_forward(ob_ctx *ctx, u32 n0, u32 n1)
         // a stage only runs forward: the owner's parameter table serves (its entries do not depend on
         // which parameters a graph uses), and the tile lists of the parameter-gradient kernels are not needed
         c->params_dev = ctx->params_dev; c->wtiles_dev = ctx->wtiles_dev; c->btiles_dev = ctx->btiles_dev;
+        c->wpart_dev = ctx->wpart_dev;
         c->params_dirty = false;
     }
     if ((rc = ob_upload(c)) != 0) { ctx->err = c->err; return fail(rc); }

@@ -93,6 +93,7 @@ struct ob_ctx {
     bool params_frozen = false;        // set by the first graph upload
     std::vector<PTile> wtiles, btiles; // static tiles of the deferred dW / db kernels
     PTile *wtiles_dev = nullptr, *btiles_dev = nullptr;
+    float *wpart_dev = nullptr;        // partial dW blocks of the workgroups that share a tile
     int max_param_rows = 1;
     std::vector<std::vector<float>> pending;      // host copies of parameter data not yet on the device
     std::vector<u8> params_used_w, params_used_b; // parameter appeared as a MATVEC matrix / bias

@@ -677,53 +677,156 @@ __device__ inline void matvec_dx_tile(const Tables &T, const TileDesc &d, float 
     __syncthreads();
 }
 
-// dW[m x K] += sum over uses of g x^T (deferred: once per parameter over every use in the graph)
-__device__ inline void param_w_tile(const Tables &T, const PTile &pt, float *lds)
+// dW[m x K] += sum over uses of g x^T (deferred: once per parameter over every use in the graph).
+// A workgroup owns a 64 x 64 block of dW; wave w the 32 x 32 quarter (w / 2, w % 2) over all uses,
+// so no partial sums cross waves and the order of the sum is the order of the sorted use list.
+// The uses are walked in chunks of 32: the 64-float pieces of the 32 gradient rows and of the 32
+// operand rows are loaded by 16 adjacent lanes each (two full lines per row) into LDS, the MFMA
+// operands are LDS reads, and the next chunk (and the row offsets of the one after) are on their
+// way while the current one is multiplied.
+constexpr u32 PWT = 64;              // dW tile edge
+constexpr u32 PWC = 32;              // uses per chunk
+constexpr u32 PWLD = PWT + 4;        // padded LDS row
+constexpr u32 PW_LDS_FLOATS = 2 * PWC * PWLD;
+static_assert(PWT == (u32)PWTILE, "host tile list and kernel agree on the tile edge");
+
+// four consecutive floats of a row that may end early (n valid) or start unaligned
+__device__ inline float4 ld4_guard(const float *base, u32 off, u32 n)
 {
-    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    if (n >= 4u && ((off & 3u) == 0u)) return ld4(base + off);
+    float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (n > 0u) v.x = base[off];
+    if (n > 1u) v.y = base[off + 1];
+    if (n > 2u) v.z = base[off + 2];
+    if (n > 3u) v.w = base[off + 3];
+    return v;
+}
+
+// The use list of a tile is cut into up to `nsp` runs of whole chunks, one workgroup each (a tile
+// alone would walk 1000+ uses one chunk after the other, with one chunk's loads in flight).  Each
+// workgroup leaves its partial block in `part`; a second small kernel adds the partial blocks, in
+// run order, to the gradient (a kernel boundary costs less here than device-wide fences between
+// workgroups, which write back every dirty line of an XCD's L2).
+__device__ inline void param_w_tile(const Tables &T, const PTile &pt, float *lds, u32 sp, float *part)
+{
+    const u32 nsp = (u32)pt.pad & 0xffu, pbase = (u32)pt.pad >> 8;
+    if (sp >= nsp) return;
+    const u32 tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
     const u32 l32 = lane & 31, h = lane >> 5;
     const u32 slot = (u32)pt.param * 4u;
     const u32 start = T.pu_start[slot], end = T.pu_end[slot];
     if (start == end) return;
     const ParamDesc P = T.params[pt.param];
     const u32 m = (u32)P.rows, K = (u32)P.cols;
-    const u32 i = (u32)pt.i0 + l32, j = (u32)pt.j0 + l32;
-    const bool i_ok = i < m, j_ok = j < K;
-    u32 lo, hi;
-    wave_range<4>(end - start, lo, hi);
+    const u32 i0 = (u32)pt.i0, j0 = (u32)pt.j0;
+    lds_float *gs = (lds_float *)lds, *xs = gs + PWC * PWLD;
+    // loader role: piece c4 of the rows of uses lu and lu + 16 of the chunk
+    const u32 lu = tid >> 4, c4 = (tid & 15u) * 4u;
+    const u32 gi = i0 + c4, xj = j0 + c4;
+    const u32 gn = gi < m ? m - gi : 0u, xn = xj < K ? K - xj : 0u;    // valid elements from this piece on
+    const u32 all_chunks = (end - start + PWC - 1) / PWC;
+    const u32 nsp_eff = all_chunks < nsp ? all_chunks : nsp;      // runs that hold at least one chunk
+    if (sp >= nsp_eff) return;
+    const u32 per = (all_chunks + nsp_eff - 1) / nsp_eff;
+    const u32 c_lo = sp * per, c_hi = (sp + 1) * per < all_chunks ? (sp + 1) * per : all_chunks;
+    const u32 n_uses = end - start;
+    u32 go[2], xo[2];
+    bool ok[2];
+    auto offsets = [&](u32 c) {
+#pragma unroll
+        for (int p = 0; p < 2; ++p) {
+            const u32 it = c * PWC + lu + 16u * p;
+            ok[p] = it < n_uses;
+            go[p] = ok[p] ? T.it_goff[start + it] : 0u;
+            xo[p] = ok[p] ? T.it_xoff[start + it] : 0u;
+        }
+    };
+    const float4 z4 = make_float4(0.f, 0.f, 0.f, 0.f);
+    float4 pg[2], px[2];
+    auto fetch = [&]() {
+#pragma unroll
+        for (int p = 0; p < 2; ++p) {
+            pg[p] = ok[p] ? ld4_guard(T.G, go[p] + gi, gn) : z4;
+            px[p] = ok[p] ? ld4_guard(T.V, xo[p] + xj, xn) : z4;
+        }
+    };
     floatx16 acc;
     for (int v = 0; v < 16; ++v) acc[v] = 0.f;
-    for (u32 ib = lo; ib < hi; ib += 8 * KU) {
-        u32 go[KU][4], xo[KU][4];
-        bool ok[KU][4];
-#pragma unroll
-        for (int u = 0; u < KU; ++u)
-#pragma unroll
-            for (int s = 0; s < 4; ++s) {
-                const u32 it = start + ib + 8 * u + 4 * h + s;
-                ok[u][s] = ib + 8 * u < hi && it < end;
-                go[u][s] = ok[u][s] ? T.it_goff[it] : 0u;
-                xo[u][s] = ok[u][s] ? T.it_xoff[it] : 0u;
-            }
-        float av[KU][4], bv[KU][4];
-#pragma unroll
-        for (int u = 0; u < KU; ++u)
-#pragma unroll
-            for (int s = 0; s < 4; ++s) {
-                av[u][s] = (ok[u][s] && i_ok) ? T.G[go[u][s] + i] : 0.f;
-                bv[u][s] = (ok[u][s] && j_ok) ? T.V[xo[u][s] + j] : 0.f;
-            }
-#pragma unroll
-        for (int u = 0; u < KU; ++u)
-            acc = mfma4(make_float4(av[u][0], av[u][1], av[u][2], av[u][3]),
-                        make_float4(bv[u][0], bv[u][1], bv[u][2], bv[u][3]), acc);
+    const u32 n_chunks = c_hi;
+    if (c_lo < c_hi) {
+        offsets(c_lo);
+        fetch();
+        if (c_lo + 1 < c_hi) offsets(c_lo + 1);
     }
-    float out[4];
-    reduce_waves<4>(acc, lds, out);
-    if (j_ok) {
-        for (int q = 0; q < 4; ++q) {
-            const u32 rr = (u32)pt.i0 + 8 * w + 4 * h + q;
-            if (rr < m) P.grad[(size_t)rr * K + j] += out[q];
+    const u32 acol = 32u * (w >> 1) + l32, bcol = 32u * (w & 1u) + l32;
+    for (u32 c = c_lo; c < n_chunks; ++c) {
+        __syncthreads();            // the previous chunk has been read
+#pragma unroll
+        for (int p = 0; p < 2; ++p) {
+            lds_st4(gs + (lu + 16u * p) * PWLD + c4, pg[p]);
+            lds_st4(xs + (lu + 16u * p) * PWLD + c4, px[p]);
+        }
+        __syncthreads();
+        if (c + 1 < n_chunks) {
+            fetch();                                   // chunk c + 1, offsets already here
+            if (c + 2 < n_chunks) offsets(c + 2);
+        }
+#pragma unroll
+        for (u32 b8 = 0; b8 < PWC / 8; ++b8) {
+            const u32 r = (8u * b8 + 4u * h) * PWLD;
+            const float4 a = make_float4(gs[r + acol], gs[r + PWLD + acol], gs[r + 2 * PWLD + acol], gs[r + 3 * PWLD + acol]);
+            const float4 bq = make_float4(xs[r + bcol], xs[r + PWLD + bcol], xs[r + 2 * PWLD + bcol], xs[r + 3 * PWLD + bcol]);
+            acc = mfma4(a, bq, acc);
+        }
+    }
+    // partial block, accumulator register v of lane l of wave w at (w * 16 + v) * 64 + l
+    float *mine = part + ((size_t)pbase + sp) * (PWT * PWT);
+    for (int v = 0; v < 16; ++v) mine[(w * 16 + v) * 64 + lane] = acc[v];
+}
+
+// second half: the partial blocks of a tile, added in run order, join the gradient
+__device__ inline void param_w_reduce(const Tables &T, const PTile &pt, const float *part)
+{
+    const u32 nsp = (u32)pt.pad & 0xffu, pbase = (u32)pt.pad >> 8;
+    const u32 slot = (u32)pt.param * 4u;
+    const u32 start = T.pu_start[slot], end = T.pu_end[slot];
+    if (start == end) return;
+    const ParamDesc P = T.params[pt.param];
+    const u32 m = (u32)P.rows, K = (u32)P.cols;
+    const u32 i0 = (u32)pt.i0, j0 = (u32)pt.j0;
+    const u32 all_chunks = (end - start + PWC - 1) / PWC;
+    const u32 nsp_eff = all_chunks < nsp ? all_chunks : nsp;
+    const float *all = part + (size_t)pbase * (PWT * PWT);
+    // four consecutive entries of a partial block are four consecutive columns of one row; all loads of
+    // a thread are issued before the first sum
+    constexpr u32 PER = PWT * PWT / 4 / WG;   // float4 groups per thread
+    float4 sum[PER];
+#pragma unroll
+    for (u32 g = 0; g < PER; ++g) sum[g] = ld4(all + 4u * (threadIdx.x + g * WG));
+    for (u32 q = 1; q < nsp_eff; ++q) {
+        float4 t[PER];
+#pragma unroll
+        for (u32 g = 0; g < PER; ++g) t[g] = ld4(all + (size_t)q * (PWT * PWT) + 4u * (threadIdx.x + g * WG));
+#pragma unroll
+        for (u32 g = 0; g < PER; ++g) { sum[g].x += t[g].x; sum[g].y += t[g].y; sum[g].z += t[g].z; sum[g].w += t[g].w; }
+    }
+#pragma unroll
+    for (u32 g = 0; g < PER; ++g) {
+        const u32 idx = 4u * (threadIdx.x + g * WG);
+        const u32 l = idx & 63u, v = (idx >> 6) & 15u, ww = idx >> 10;
+        const u32 rr = i0 + 32u * (ww >> 1) + 8u * (v >> 2) + 4u * (l >> 5) + (v & 3u);
+        const u32 jj = j0 + 32u * (ww & 1u) + (l & 31u);
+        if (rr >= m || jj >= K) continue;
+        float *gp = P.grad + (size_t)rr * K + jj;
+        if (jj + 3u < K && (((size_t)rr * K + jj) & 3u) == 0u) {
+            float4 o = ld4(gp);
+            o.x += sum[g].x; o.y += sum[g].y; o.z += sum[g].z; o.w += sum[g].w;
+            st4(gp, o);
+        } else {
+            gp[0] += sum[g].x;
+            if (jj + 1u < K) gp[1] += sum[g].y;
+            if (jj + 2u < K) gp[2] += sum[g].z;
+            if (jj + 3u < K) gp[3] += sum[g].w;
         }
     }
     if (threadIdx.x == 0) P.marks[0] = 1u;   // this parameter's gradient is dense now
@@ -1058,10 +1161,20 @@ __global__ __launch_bounds__(BWD_THREADS, LEAN ? 5 : 4) void k_bwd_step(u32 work
 
 __global__ void k_set_root(Tables T) { T.root_pos[0] = T.pos_of[T.root]; }
 
-__global__ __launch_bounds__(WG) void k_param_w(Tables T, const PTile *tiles)
+// Workgroup g runs on XCD g % 8 and the tile list is ordered so that tile t belongs on XCD t % 8 (an
+// XCD then keeps to one eighth of the gradient columns, which fit its L2): the runs of a tile are
+// therefore a multiple of eight workgroups apart.
+__global__ __launch_bounds__(WG) void k_param_w(Tables T, const PTile *tiles, u32 n_tiles, u32 n_tiles_pad, float *part)
 {
-    __shared__ float lds[LDS_FLOATS];
-    param_w_tile(T, tiles[blockIdx.x], lds);
+    __shared__ __align__(16) float lds[PW_LDS_FLOATS];
+    const u32 tile = blockIdx.x % n_tiles_pad, sp = blockIdx.x / n_tiles_pad;
+    if (tile >= n_tiles) return;
+    param_w_tile(T, tiles[tile], lds, sp, part);
+}
+
+__global__ __launch_bounds__(WG) void k_param_w_sum(Tables T, const PTile *tiles, const float *part)
+{
+    param_w_reduce(T, tiles[blockIdx.x], part);
 }
 
 __global__ __launch_bounds__(WG) void k_param_b(Tables T, const PTile *tiles)
@@ -1272,8 +1385,12 @@ static int launch_param_grads(ob_ctx *ctx)
     hipStream_t s = ctx->stream;
     if (ctx->hdr.n_items == 0) return 0;
     if (!ctx->wtiles.empty()) {
-        hipLaunchKernelGGL(k_param_w, dim3((unsigned)ctx->wtiles.size()), dim3(WG), 0, s, T, ctx->wtiles_dev);
-        ++ctx->n_launch_bwd;
+        const u32 n_tiles = (u32)ctx->wtiles.size(), n_pad = (n_tiles + 7u) & ~7u;
+        hipLaunchKernelGGL(k_param_w, dim3(n_pad * PW_SPLIT_MAX), dim3(WG), 0, s, T, ctx->wtiles_dev, n_tiles, n_pad,
+                           ctx->wpart_dev);
+        hipLaunchKernelGGL(k_param_w_sum, dim3((unsigned)ctx->wtiles.size()), dim3(WG), 0, s, T, ctx->wtiles_dev,
+                           (const float *)ctx->wpart_dev);
+        ctx->n_launch_bwd += 2;
     }
     if (!ctx->btiles.empty()) {
         hipLaunchKernelGGL(k_param_b, dim3((unsigned)ctx->btiles.size()), dim3(WG), 0, s, T, ctx->btiles_dev);

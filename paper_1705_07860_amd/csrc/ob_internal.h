@@ -20,6 +20,8 @@ enum : u32 {
 constexpr int WG = 256;               // threads per workgroup of every tile kernel (4 wave64)
 constexpr int EW_TILE = 1024;         // elements of one elementwise / pull tile
 constexpr int GT = 32;                // forward / dW GEMM tile edge (one 32x32 MFMA accumulator block)
+constexpr int PWTILE = 64;            // dW tile edge of the deferred weight-gradient kernel
+constexpr int PW_SPLIT_MAX = 16;       // most workgroups that share the use list of one dW tile (matrices of many tiles take 4 or 8)
 constexpr int GTW = 64;               // forward GEMM tile edge of batches with at least WIDE_MIN_ROWS rows
 constexpr u32 WIDE_MIN_ROWS = 256;
 constexpr int DXT = 16;               // dX GEMM tile edge (16x16 blocks: its output is small, more tiles fill more CUs)
@@ -169,7 +171,7 @@ struct WorkRec { u32 first, len; };   // a workgroup runs tiles [first, first + 
 struct SlotRec { u32 wf, wa, tb, tf, ta, lmin, nlmax, dx_free, lds_need, plain, lminf, nlmaxf; };
 
 // Static tile of the deferred parameter-gradient kernels (built on the host per parameter set).
-struct PTile { i32 param; i32 i0, j0; i32 pad; };
+struct PTile { i32 param; i32 i0, j0; i32 pad; };   // dW tiles: pad = runs of the use list | index of the tile's first partial block << 8
 
 // Scan element of the per-batch layout pass.
 struct Lay {
