@@ -17,6 +17,7 @@ launch per node), and the CPU oracle timed on a bounded sample.  `--workload X` 
 from __future__ import annotations
 
 import argparse
+import gc
 import json
 import os
 import sys
@@ -218,6 +219,11 @@ def measure(args, ob, torch, name, steps, warmup, sustain_s, cpu_s, headline):
         run(first, count, piped)
         torch.cuda.synchronize()
         return time.perf_counter() - t0
+
+    # The interpreter's cyclic garbage collector stays out of the loops: a full collection walks every
+    # container object of the process (tens of milliseconds here) at a moment of its own choosing.
+    gc.collect()
+    gc.disable()
 
     # Set-up, untimed: every context of the ring takes the largest minibatch once, so that its
     # page-locked graph store and the library's other host buffers have reached their steady size
@@ -448,6 +454,7 @@ def measure(args, ob, torch, name, steps, warmup, sustain_s, cpu_s, headline):
                                    sample=f"{ns} of the run's minibatches ({inst} instances, {dt:.1f} s): fp32 build of the "
                                           f"node-at-a-time interpreter, forward+backward, 1 thread of {os.cpu_count()} host cores")
     out["paper_context"] = PAPER_CONTEXT.get(name)
+    gc.enable()
     for c in ctxs[1:]:
         c.close()
     ctxs[0].close()
