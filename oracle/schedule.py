@@ -59,7 +59,22 @@ def signature(g, v: int) -> tuple:
     return (op, int(g.out_dim[v]), hi - lo, int(g.param[v]), int(g.bias[v]), s_lo, s_hi) + in_dims
 
 
-def by_depth(g, n=None):
+OP_ADD, OP_CMULT, OP_TANH, OP_SIGMOID = 3, 4, 5, 6
+
+
+def signature_as_printed(g, v: int) -> tuple:
+    """The signature exactly as Section 3.2 / Appendix A word it: component-wise operations
+    (sum, product, tanh, logistic) are identified by the operation alone, whatever the shape of
+    their operands; every other operation keeps dimensions, ranges and shared parameters.  The
+    library and `signature` add the operand shapes for every operation (uniform-row batches);
+    this variant only serves to count what that reading costs in batches."""
+    op = int(g.op[v])
+    if op in (OP_ADD, OP_CMULT, OP_TANH, OP_SIGMOID):
+        return (op,)
+    return signature(g, v)
+
+
+def by_depth(g, n=None, sig=signature):
     """Canonical depth-based schedule.
 
     Returns (batch_off[nb+1], node_ids[n], batch_depth[nb]) as int64 arrays.
@@ -68,7 +83,7 @@ def by_depth(g, n=None):
     d = depths(g, n)
     groups = {}
     for v in range(n):
-        groups.setdefault((int(d[v]), signature(g, v)), []).append(v)
+        groups.setdefault((int(d[v]), sig(g, v)), []).append(v)
     batches = sorted(groups.items(), key=lambda kv: (kv[0][0], kv[1][0]))
     batch_off = [0]
     node_ids = []
@@ -160,3 +175,18 @@ def by_agenda(g, n=None):
                     agenda.setdefault(sig_of[v], []).append(v)
     nb = len(batch_off) - 1
     return (np.asarray(batch_off, np.int64), np.asarray(node_ids, np.int64), np.arange(nb, dtype=np.int64))
+
+
+if __name__ == "__main__":
+    # batches per configuration under the library's signature (operand shapes in every signature) and
+    # under the signature as the paper words it (component-wise operations by name alone)
+    import os
+    import sys
+    sys.path.insert(0, os.path.dirname(os.path.dirname(os.path.abspath(__file__))))
+    from paper_1705_07860_amd import workloads as wl
+    print("config        nodes  levels  batches(shapes in every signature)  batches(component-wise by name)")
+    for name in ("rnn", "tagger", "tagger_char", "tree", "parser"):
+        _p, _g = wl.make(name, 0)
+        a = by_depth(_g)
+        b = by_depth(_g, sig=signature_as_printed)
+        print(f"{name:12s} {_g.n:6d} {int(a[2].max()) + 1:7d} {len(a[2]):10d} {len(b[2]):34d}")

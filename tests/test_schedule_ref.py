@@ -185,3 +185,30 @@ def test_generators_take_an_instance_count_and_keep_their_default():
         assert small.n_instances == 3 and small.n < g0.n
         bo, ids, bd = S.by_depth(small)
         assert np.array_equal(np.sort(ids), np.arange(small.n))
+
+
+def test_signature_as_the_paper_words_it_is_coarser_or_equal():
+    """Section 3.2 identifies component-wise operations by their name alone; the library (and the
+    reference scheduler) add operand shapes to every signature.  The printed form can only merge
+    batches: every batch of the shape-aware schedule lies inside one batch of the printed one, the
+    counts agree where all component-wise work of a depth has one width (RNN chains), and a graph
+    with two widths at one depth shows the difference."""
+    from oracle import schedule as S
+    from paper_1705_07860_amd import workloads as wl
+    p, g = wl.make("rnn", 0)
+    a, b = S.by_depth(g), S.by_depth(g, sig=S.signature_as_printed)
+    assert len(a[2]) == len(b[2]) == 31
+    p = wl.Params([], [])
+    gb = wl.GraphBuilder(p)
+    xs = [gb.input(np.ones(4)), gb.input(np.ones(6))]
+    ts = [gb.tanh(x) for x in xs]                 # same depth, two widths
+    root = gb.add([gb.sqnorm(t) for t in ts])
+    g = gb.finish(root, 1)
+    a, b = S.by_depth(g), S.by_depth(g, sig=S.signature_as_printed)
+    assert len(a[2]) == len(b[2]) + 1             # the two tanh nodes share a batch only in the printed form
+    owner = {}
+    for k in range(len(b[2])):
+        for v in b[1][b[0][k]:b[0][k + 1]]:
+            owner[int(v)] = k
+    for k in range(len(a[2])):
+        assert len({owner[int(v)] for v in a[1][a[0][k]:a[0][k + 1]]}) == 1
