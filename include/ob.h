@@ -170,11 +170,9 @@ int ob_upload(ob_ctx *ctx);
  * (Section 3.1): they form a graph whose leaves are the earlier nodes they read (values copied on
  * the GPU), which is scheduled in the context's mode and executed in the arena behind the earlier
  * evaluations; depths of a stage count from its own leaves.  Earlier values stay readable
- * throughout (ob_value_read).  While values come from more than one stage: ob_schedule_read and
- * ob_stats_read describe the last stage; ob_all_read and ob_debug_read fail with OB_E_STATE;
- * gradients cannot be read; ob_backward first schedules and evaluates everything evaluated so
- * far once more as one graph (the backward pass needs every consumer of a node in one schedule),
- * so a graph grown in T steps costs T small forwards and one full one instead of T full ones.
+ * throughout (ob_value_read, ob_all_read).  While values come from more than one stage:
+ * ob_schedule_read and ob_stats_read describe the last stage; ob_debug_read fails with OB_E_STATE;
+ * ob_backward runs over the stages as they are (see there).
  * If the arena has no room for another stage, or in OB_MANUAL, the whole prefix is evaluated
  * again instead.  A schedule that was never executed is dropped when nodes are added. */
 int ob_forward(ob_ctx *ctx, int node);
@@ -187,8 +185,12 @@ int ob_schedule(ob_ctx *ctx, int node);
 int ob_schedule_async(ob_ctx *ctx, int node);
 /* Reverse-mode differentiation from a 1-element node that ob_forward covered: batches in
  * reverse order (Section 3.3).  Node gradients are overwritten, parameter gradients
- * accumulate.  After forwards in several stages (see ob_forward) everything evaluated so far is
- * first scheduled and evaluated again as one graph. */
+ * accumulate.  After forwards in several stages (see ob_forward) nothing is evaluated again: the
+ * stages run backward one after the other, last first, and what a stage computes for the earlier
+ * nodes it read is handed down to them before their own stage runs.  This needs room in the arena
+ * behind the last stage for one block of gradient size per earlier stage, and every parameter a
+ * later stage uses must already occur in the first evaluation; otherwise (and never silently wrong)
+ * everything evaluated so far is scheduled and evaluated once more as one graph first. */
 int ob_backward(ob_ctx *ctx, int node);
 int ob_sync(ob_ctx *ctx);
 /* Forgets the schedule, values and gradients of the current graph but keeps its nodes (and
@@ -200,7 +202,8 @@ int ob_reset(ob_ctx *ctx);
 
 int ob_value_read(ob_ctx *ctx, int node, float *host_out, size_t cap);
 int ob_grad_read(ob_ctx *ctx, int node, float *host_out, size_t cap);
-/* All node values (which = 0) or node gradients (which = 1) concatenated in node-id order. */
+/* All node values (which = 0) or node gradients (which = 1) concatenated in node-id order (gathered from every
+ * evaluation stage; staging space comes from the free end of the arena, OB_E_OOM if there is none). */
 int ob_all_read(ob_ctx *ctx, int which, float *host_out, size_t cap);
 
 /* The schedule of the last ob_forward: batch b holds node_ids[batch_off[b] .. batch_off[b+1]).

@@ -155,6 +155,8 @@ static int forget_evaluation(ob_ctx *ctx);
 static int wait_own_work(ob_ctx *ctx);
 static u32 evaluated_upto(const ob_ctx *ctx);
 static int stage_forward(ob_ctx *ctx, u32 n0, u32 n1);
+static int staged_backward(ob_ctx *ctx, u32 node);
+constexpr int STAGED_FALLBACK = 1;   // staged_backward cannot serve: evaluate everything again as one graph
 static int stage_schedule_read(ob_ctx *ctx, int *n_batches, int *batch_depth, uint64_t *batch_sig, int *batch_off,
                                int *node_ids, size_t cap_batches, size_t cap_nodes);
 
@@ -961,17 +963,22 @@ int ob_backward(ob_ctx *ctx, int node)
     CHECK_CTX(ctx);
     if (!ctx->forward_done) return ctx_fail(ctx, OB_E_STATE, "ob_backward before ob_forward");
     if (!ctx->stages.empty()) {
-        // The graph was evaluated in stages.  The backward pass needs one schedule over all of it
-        // (every node's consumers in one pull list), so everything evaluated so far is scheduled
-        // and evaluated once more, together.
+        // The graph was evaluated in stages.  The backward pass runs stage by stage, last first:
+        // what a stage computes for its stand-ins of earlier nodes is handed down to those nodes'
+        // owners.  Where that is not possible (see staged_backward) everything evaluated so far is
+        // scheduled and evaluated once more as one graph instead.
         const u32 done = evaluated_upto(ctx);
         if (node < 0 || (u32)node >= done) return ctx_fail(ctx, OB_E_BADID, "node %d was not evaluated", node);
-        if (int rc = forget_evaluation(ctx)) return rc;
-        if (int rc = ob_forward(ctx, (int)done - 1)) return rc;
+        if (ctx->out_dim[node] != 1) return ctx_fail(ctx, OB_E_NOTSCALAR, "node %d has %u elements", node, ctx->out_dim[node]);
+        const int rc = staged_backward(ctx, (u32)node);
+        if (rc != STAGED_FALLBACK) return rc;
+        if (int rc2 = forget_evaluation(ctx)) return rc2;
+        if (int rc2 = ob_forward(ctx, (int)done - 1)) return rc2;
     }
     if (node < 0 || (u32)node >= ctx->n_sched) return ctx_fail(ctx, OB_E_BADID, "node %d was not evaluated", node);
     if (ctx->out_dim[node] != 1) return ctx_fail(ctx, OB_E_NOTSCALAR, "node %d has %u elements", node, ctx->out_dim[node]);
     ctx->T.root = (u32)node;
+    ctx->T.Gx = nullptr;
     HIP_TRY(ctx, hipEventRecord(ctx->ev[4], ctx->stream));
     if (int rc = exec_backward(ctx)) return rc;
     HIP_TRY(ctx, hipEventRecord(ctx->ev[5], ctx->stream));
@@ -1119,6 +1126,7 @@ static int stage_forward(ob_ctx *ctx, u32 n0, u32 n1)
     c->is_stage = true;
     u32 *lists_dev = arena_array<u32>(c, (size_t)3 * P + 1);
     if (!lists_dev) return fail(ctx_fail(ctx, OB_E_OOM, "arena too small for another evaluation stage"));
+    st.lists_dev = lists_dev;
     c->persist_top = c->top;
     int rc = ob_add_bulk(c, (int)nl, op.data(), od.data(), ioff.data(), iidx.data(), par.data(), bia.data(), a0.data(),
                          a1.data(), pay.data(), pay.size());
@@ -1128,6 +1136,7 @@ static int stage_forward(ob_ctx *ctx, u32 n0, u32 n1)
         // which parameters a graph uses), and the tile lists of the parameter-gradient kernels are not needed
         c->params_dev = ctx->params_dev; c->wtiles_dev = ctx->wtiles_dev; c->btiles_dev = ctx->btiles_dev;
         c->wpart_dev = ctx->wpart_dev;
+        c->wtiles = ctx->wtiles; c->btiles = ctx->btiles;   // (a backward pass over the stages runs the owner's tile lists)
         c->params_dirty = false;
     }
     if ((rc = ob_upload(c)) != 0) { ctx->err = c->err; return fail(rc); }
@@ -1169,6 +1178,70 @@ static int stage_forward(ob_ctx *ctx, u32 n0, u32 n1)
     }
     if ((rc = ob_forward(c, (int)nl - 1)) != 0) { ctx->err = c->err; return fail(rc); }
     ctx->backward_done = false;   // gradients of the shorter graph are not gradients of this one
+    return OB_OK;
+}
+
+// Backward pass over a graph that was evaluated in stages (Section 3.1 / 3.3), without evaluating
+// anything again.  Units: the first evaluation (nodes [0, n_sched)) and every stage.  They run in
+// reverse order, each a backward pass of its own graph; a unit's pull adds, per node, the gradient
+// that later units have handed down (an extra block with the offsets of the gradient arena, zero at
+// first), and after a stage has run, the gradients of its leaves that stand for earlier nodes are
+// added to those nodes' entries of their owners' blocks.  Needs room for the extra blocks behind
+// the last stage, and every parameter the stages use among the owner's gradient tiles; otherwise
+// STAGED_FALLBACK.
+static int staged_backward(ob_ctx *ctx, u32 node)
+{
+    const size_t S = ctx->stages.size();
+    for (const Stage &st : ctx->stages)
+        for (size_t p = 0; p < ctx->params.size(); ++p) {
+            const bool w = p < st.c->params_used_w.size() && st.c->params_used_w[p];
+            const bool b = p < st.c->params_used_b.size() && st.c->params_used_b[p];
+            if ((w && !(p < ctx->params_used_w.size() && ctx->params_used_w[p])) ||
+                (b && !(p < ctx->params_used_b.size() && ctx->params_used_b[p])))
+                return STAGED_FALLBACK;
+        }
+    if (ctx->params_dirty || !ctx->params_dev) return STAGED_FALLBACK;
+    auto unit = [&](size_t k) { return k ? ctx->stages[k - 1].c : ctx; };
+    ob_ctx *last = unit(S);
+    std::vector<float *> gx(S + 1, nullptr);
+    const size_t save = last->top;
+    for (size_t k = 0; k < S; ++k) {   // (nothing comes after the last unit)
+        const size_t floats = (size_t)unit(k)->hdr.grad_floats + VAL_ALIGN;
+        gx[k] = arena_array<float>(last, floats);
+        if (!gx[k]) { last->top = save; return STAGED_FALLBACK; }
+        HIP_TRY(ctx, hipMemsetAsync(gx[k], 0, floats * sizeof(float), ctx->stream));
+    }
+    for (size_t k = S + 1; k-- > 0;) {
+        ob_ctx *u = unit(k);
+        u32 root = 0xffffffffu;
+        if (k == 0) { if (node < ctx->n_sched) root = node; }
+        else {
+            const Stage &st = ctx->stages[k - 1];
+            if (node >= st.n0 && node < st.n1) root = (u32)st.proxy.size() + (node - st.n0);
+        }
+        u->T.root = root;
+        u->T.Gx = gx[k];
+        HIP_TRY(ctx, hipEventRecord(u->ev[4], ctx->stream));
+        if (int rc = exec_backward(u)) { if (u != ctx) ctx->err = u->err; return rc; }
+        HIP_TRY(ctx, hipEventRecord(u->ev[5], ctx->stream));
+        u->backward_done = true;
+        if (k == 0) break;
+        // hand the leaves' gradients down, owner by owner (leaves ascend, and so do the owners' id ranges)
+        const Stage &st = ctx->stages[k - 1];
+        const u32 P = (u32)st.proxy.size();
+        u32 i = 0;
+        for (size_t o = 0; o < k && i < P; ++o) {
+            const Stage *own = o ? &ctx->stages[o - 1] : nullptr;
+            const u32 hi = own ? own->n1 : ctx->n_sched;
+            const u32 i0 = i;
+            while (i < P && st.proxy[i] < hi) ++i;
+            if (i == i0) continue;
+            hipError_t e = exec_stage_scatter(u->T.G, u->T.nat_off, i0, st.lists_dev + i0, st.lists_dev + 2 * (size_t)P + i0, i - i0,
+                                              unit(o)->T.nat_off, gx[o], ctx->stream);
+            if (e != hipSuccess) return ctx_fail(ctx, OB_E_HIP, "handing gradients to an earlier stage failed: %s", hipGetErrorString(e));
+        }
+    }
+    ctx->backward_done = true;
     return OB_OK;
 }
 
@@ -1236,7 +1309,7 @@ static int node_read(ob_ctx *ctx, int node, float *out, size_t cap, bool grad)
     if ((u32)node >= ctx->n_sched) {   // the value lives in a later evaluation stage
         for (Stage &st : ctx->stages) {
             if ((u32)node >= st.n1) continue;
-            const int rc = node_read(st.c, (int)(st.proxy.size() + ((u32)node - st.n0)), out, cap, false);
+            const int rc = node_read(st.c, (int)(st.proxy.size() + ((u32)node - st.n0)), out, cap, grad);
             if (rc) ctx->err = st.c->err;
             return rc;
         }
@@ -1268,28 +1341,44 @@ int ob_all_read(ob_ctx *ctx, int which, float *host_out, size_t cap)
     CHECK_CTX(ctx);
     if (!host_out) return ctx_fail(ctx, OB_E_ARG, "null output");
     if (!ctx->forward_done || (which && !ctx->backward_done)) return ctx_fail(ctx, OB_E_STATE, "nothing to read yet");
-    if (!ctx->stages.empty())
-        return ctx_fail(ctx, OB_E_STATE, "the graph was evaluated in %zu stages: read node by node, or after ob_backward",
-                        ctx->stages.size() + 1);
-    const u32 n = ctx->n_sched;
+    // Units: the first evaluation and every later stage; each gathers its own nodes (a stage's leaves
+    // that stand for earlier nodes are left out) into one staging block behind the last unit.
+    const size_t S = ctx->stages.size();
+    const u32 n = evaluated_upto(ctx);
     std::vector<u32> off((size_t)n + 1);
     u64 tot = 0;
     for (u32 v = 0; v < n; ++v) { off[v] = (u32)tot; tot += ctx->out_dim[v]; }
     if (tot > 0xffffffffull) return ctx_fail(ctx, OB_E_RANGE, "too many elements");
     if (cap < tot) return ctx_fail(ctx, OB_E_RANGE, "buffer holds %zu of %llu elements", cap, (unsigned long long)tot);
-    const size_t save = ctx->top;
-    u32 *off_dev = arena_array<u32>(ctx, (size_t)n + 1);
-    float *dst = arena_array<float>(ctx, tot + 1);
-    if (!off_dev || !dst) { ctx->top = save; return ctx_fail(ctx, OB_E_OOM, "arena too small for the read-back staging"); }
+    ob_ctx *last = S ? ctx->stages.back().c : ctx;
+    const size_t save = last->top;
+    float *dst = arena_array<float>(last, tot + 1);
     int rc = OB_OK;
-    do {
-        hipError_t e = hipMemcpyAsync(off_dev, off.data(), (size_t)n * 4, hipMemcpyHostToDevice, ctx->stream);
-        if (e == hipSuccess) e = exec_gather_all(ctx->T, which, dst, off_dev, ctx->stream);
-        if (e == hipSuccess) e = hipMemcpyAsync(host_out, dst, tot * 4, hipMemcpyDeviceToHost, ctx->stream);
+    std::vector<std::vector<u32>> keep(S + 1);    // host lists stay alive until the copies have run
+    for (size_t k = 0; k <= S && rc == OB_OK && dst; ++k) {
+        ob_ctx *u = k ? ctx->stages[k - 1].c : ctx;
+        if (which && !u->backward_done) { rc = ctx_fail(ctx, OB_E_STATE, "no gradients in evaluation stage %zu", k); break; }
+        const u32 P = k ? (u32)ctx->stages[k - 1].proxy.size() : 0u;
+        const u32 n0 = k ? ctx->stages[k - 1].n0 : 0u;
+        const u32 nl = u->T.n;
+        std::vector<u32> &loc = keep[k];
+        loc.assign((size_t)nl + 1, 0xffffffffu);
+        for (u32 l = P; l < nl; ++l) loc[l] = off[n0 + (l - P)];
+        u32 *off_dev = arena_array<u32>(last, (size_t)nl + 1);
+        if (!off_dev) { dst = nullptr; break; }
+        hipError_t e = hipMemcpyAsync(off_dev, loc.data(), (size_t)nl * 4, hipMemcpyHostToDevice, ctx->stream);
+        if (e == hipSuccess) e = exec_gather_some(u->T, which, dst, off_dev, ctx->stream);
+        if (e != hipSuccess) rc = ctx_fail(ctx, OB_E_HIP, "read-back failed: %s", hipGetErrorString(e));
+    }
+    if (!dst) { last->top = save; return ctx_fail(ctx, OB_E_OOM, "arena too small for the read-back staging"); }
+    if (rc == OB_OK) {
+        hipError_t e = hipMemcpyAsync(host_out, dst, tot * 4, hipMemcpyDeviceToHost, ctx->stream);
         if (e == hipSuccess) e = hipStreamSynchronize(ctx->stream);
         if (e != hipSuccess) rc = ctx_fail(ctx, OB_E_HIP, "read-back failed: %s", hipGetErrorString(e));
-    } while (0);
-    ctx->top = save;
+    } else {
+        (void)hipStreamSynchronize(ctx->stream);
+    }
+    last->top = save;
     return rc;
 }
 

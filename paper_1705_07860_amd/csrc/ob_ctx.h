@@ -68,6 +68,7 @@ struct Stage {
     u32 n0 = 0, n1 = 0;
     std::vector<u32> proxy;     // ascending ids of the earlier nodes; the local id of proxy[i] is i
     std::vector<u32> lists;     // host copy of the fill lists (kept while the copy to the device may be in flight)
+    u32 *lists_dev = nullptr;   // the same lists on the device: source ids | payload offsets | dimensions, proxy.size() each
 };
 
 struct ob_ctx {

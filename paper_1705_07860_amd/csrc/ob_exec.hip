@@ -554,7 +554,7 @@ __device__ inline void matvec_dx_tile_wide(const Tables &T, const TileDesc &d, f
     const u32 row = r0 + l32, col = c0 + l32;
     const bool row_ok = row < d.B, col_ok = col < K;
     const u32 grow_row = row_ok ? row : r0;
-    const float *grow = T.G + ((d.flags & TF_G_ALIAS) ? ((d.contig & 1u) ? d.base[0] + (grow_row - r0) * d.sstride[0]
+    const float *grow = T.G + (((d.flags & TF_G_ALIAS) && !T.Gx) ? ((d.contig & 1u) ? d.base[0] + (grow_row - r0) * d.sstride[0]
                                                                              : T.dx_gsrc[d.pos0 + grow_row])
                                                         : d.val_off + grow_row * m);
     gl_float *wcol = as_global(d.w) + (col_ok ? col : 0u);
@@ -617,7 +617,7 @@ __device__ inline void matvec_dx_tile(const Tables &T, const TileDesc &d, float 
     const bool row_ok = row < d.B, col_ok = col < K;
     // this lane's gradient row: the batch's own block, or (TF_G_ALIAS) the one consumer's row as it is
     const u32 grow_row = row_ok ? row : r0;
-    const float *grow = T.G + ((d.flags & TF_G_ALIAS) ? ((d.contig & 1u) ? d.base[0] + (grow_row - r0) * d.sstride[0]
+    const float *grow = T.G + (((d.flags & TF_G_ALIAS) && !T.Gx) ? ((d.contig & 1u) ? d.base[0] + (grow_row - r0) * d.sstride[0]
                                                                              : T.dx_gsrc[d.pos0 + grow_row])
                                                         : d.val_off + grow_row * m);
     gl_float *wcol = as_global(d.w) + (col_ok ? col : 0u);
@@ -956,6 +956,7 @@ __device__ inline void pull_tile(const Tables &T, const PullDesc &d, lds_float *
             const u32 own = d.val_off + row * d.d;
             const float seed = (d.pos0 + row == root_pos) ? 1.0f : 0.0f;   // a root has d == 1, never here
             float4 acc = make_float4(seed, seed, seed, seed);
+            if (T.Gx) { const float4 e = ld4(T.Gx + own + col); acc.x += e.x; acc.y += e.y; acc.z += e.z; acc.w += e.w; }
 #pragma unroll
             for (u32 j = 0; j < 4; ++j) {
                 if (j < d.n_uni) {
@@ -974,6 +975,7 @@ __device__ inline void pull_tile(const Tables &T, const PullDesc &d, lds_float *
         const u32 dr = x / d.d, col = x % d.d, row = d.row0 + dr * d.rstride;
         const u32 own = d.val_off + row * d.d;
         float acc = (d.pos0 + row == root_pos) ? 1.0f : 0.0f;
+        if (T.Gx) acc += T.Gx[own + col];     // what consumers in later evaluation stages passed down
         if (d.n_uni != PULL_GENERIC) {
 #pragma unroll
             for (u32 j = 0; j < 4; ++j) {
@@ -1159,7 +1161,7 @@ __global__ __launch_bounds__(BWD_THREADS, LEAN ? 5 : 4) void k_bwd_step(u32 work
     if (sink != sink && work_lo == 0xffffffffu) T.G[0] = sink;   // (no launch has this range)
 }
 
-__global__ void k_set_root(Tables T) { T.root_pos[0] = T.pos_of[T.root]; }
+__global__ void k_set_root(Tables T) { T.root_pos[0] = T.root == 0xffffffffu ? 0xffffffffu : T.pos_of[T.root]; }   // (no root in this graph: nothing is seeded)
 
 // Workgroup g runs on XCD g % 8 and the tile list is ordered so that tile t belongs on XCD t % 8 (an
 // XCD then keeps to one eighth of the gradient columns, which fit its L2): the runs of a tile are
@@ -1359,7 +1361,9 @@ static int launch_backward_steps(ob_ctx *ctx)
         const SlotRec &r = ctx->slots[st], &e = ctx->slots[st + 1];
         const u32 n_pull = e.wa - r.wa, n_dx = e.tb - r.tb;
         const size_t lds_bytes = slot_lds_bytes(r, BWD_LDS_MIN);
-        if (n_pull && n_dx && r.dx_free) {
+        // (with gradients arriving from later stages a product's gradient is no longer its one consumer's row:
+        // the dX tiles then read the rows the slot's own pull has just written)
+        if (n_pull && n_dx && r.dx_free && !T.Gx) {
             hipLaunchKernelGGL(k_bwd_step<false>, dim3(grid_for(n_pull + n_dx, GRID_CAP)), dim3(BWD_THREADS), lds_bytes, s,
                                r.wa, e.wa, r.ta, slot_run_len(r), r.tb, e.tb, T.tiles_a, T.works_a, T.tiles_b, T);
             ++ctx->n_launch_bwd;
@@ -1492,6 +1496,45 @@ hipError_t exec_gather_all(const Tables &T, int which, float *dst, const u32 *ds
 {
     if (T.n == 0) return hipSuccess;
     hipLaunchKernelGGL(k_gather_all, dim3(T.n), dim3(64), 0, s, T, which ? T.G : T.V, which ? T.nat_off : T.val_off, dst, dst_off);
+    return hipGetLastError();
+}
+
+// The backward counterpart of k_stage_fill: the gradient a stage computed for leaf i (its stand-in
+// for an earlier node) is added to that node's row of its owner's incoming-gradient block.
+__global__ void k_stage_scatter(const float *G, const u32 *nat_off, u32 first_proxy, const u32 *src, const u32 *dim,
+                                const u32 *owner_nat_off, float *owner_gx)
+{
+    const u32 i = blockIdx.x;
+    const float *g = G + nat_off[first_proxy + i];
+    float *o = owner_gx + owner_nat_off[src[i]];
+    const u32 d = dim[i];
+    for (u32 c = threadIdx.x; c < d; c += blockDim.x) o[c] += g[c];
+}
+
+hipError_t exec_stage_scatter(const float *G, const u32 *nat_off, u32 first_proxy, const u32 *src, const u32 *dim, u32 count,
+                              const u32 *owner_nat_off, float *owner_gx, hipStream_t s)
+{
+    if (count == 0) return hipSuccess;
+    hipLaunchKernelGGL(k_stage_scatter, dim3(count), dim3(64), 0, s, G, nat_off, first_proxy, src, dim, owner_nat_off, owner_gx);
+    return hipGetLastError();
+}
+
+// k_gather_all for one evaluation stage of several: nodes whose destination is 0xffffffff (the
+// stage's stand-ins for earlier nodes) are left out.
+__global__ void k_gather_some(Tables T, const float *src, const u32 *src_off, float *dst, const u32 *dst_off)
+{
+    const u32 v = blockIdx.x;
+    if (dst_off[v] == 0xffffffffu) return;
+    const u32 d = T.out_dim[v];
+    const float *s = src + src_off[v];
+    float *o = dst + dst_off[v];
+    for (u32 c = threadIdx.x; c < d; c += blockDim.x) o[c] = s[c];
+}
+
+hipError_t exec_gather_some(const Tables &T, int which, float *dst, const u32 *dst_off, hipStream_t s)
+{
+    if (T.n == 0) return hipSuccess;
+    hipLaunchKernelGGL(k_gather_some, dim3(T.n), dim3(64), 0, s, T, which ? T.G : T.V, which ? T.nat_off : T.val_off, dst, dst_off);
     return hipGetLastError();
 }
 

@@ -236,6 +236,7 @@ struct Tables {
     SchedHeader *hdr;
     // arenas
     float *V; float *G;
+    const float *Gx;       // gradients that reach this graph's nodes from later evaluation stages (same offsets as G), or null
 };
 
 // ---- primitives (ob_prims.hip) ------------------------------------------------------------
@@ -264,6 +265,9 @@ int sched_finish(ob_ctx *ctx);
 int exec_forward(ob_ctx *ctx);
 int exec_backward(ob_ctx *ctx);
 hipError_t exec_gather_all(const Tables &T, int which, float *dst, const u32 *dst_off, hipStream_t s);
+hipError_t exec_stage_scatter(const float *G, const u32 *nat_off, u32 first_proxy, const u32 *src, const u32 *dim, u32 count,
+                              const u32 *owner_nat_off, float *owner_gx, hipStream_t s);
+hipError_t exec_gather_some(const Tables &T, int which, float *dst, const u32 *dst_off, hipStream_t s);
 hipError_t exec_stage_fill(const float *V, const u32 *val_off, const u32 *src, const u32 *dst, const u32 *dim, u32 count,
                            float *payload, hipStream_t s);
 hipError_t exec_launch_probe(float *scratch, int n, int touch, float *us_per_launch, hipStream_t s);
