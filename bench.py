@@ -259,7 +259,7 @@ def measure(args, ob, torch, name, steps, warmup, sustain_s, cpu_s, headline):
     # context keeps the events of its latest step; reading them is not timed)
     cover = min(pool, steps)
     phase = dict(ms_upload=0.0, ms_schedule=0.0, ms_forward=0.0, ms_backward=0.0, ms_param_grads=0.0, ms_graph_build=0.0)
-    launches = dict(n_launch_fwd=0, n_launch_bwd=0, n_launch_sched=0)
+    launches = dict(n_launch_fwd=0, n_launch_bwd=0, n_launch_bwd_steps=0, n_launch_sched=0)
     cost = dict(fwd_bytes=0.0, bwd_bytes=0.0, param_bytes=0.0, fwd_flops=0.0, bwd_flops=0.0)
     upload_bytes = 0
     st = None
@@ -286,7 +286,7 @@ def measure(args, ob, torch, name, steps, warmup, sustain_s, cpu_s, headline):
     # is measured live.  Each kernel has two instantiations (k_..._step<false>: any work;
     # k_..._step<true>: launches with component-wise work only); the figures cover both.
     fwd_ms, n_fwd = phase["ms_forward"], max(launches["n_launch_fwd"], 1)
-    bwd_ms, n_bwd = phase["ms_backward"] - phase["ms_param_grads"], max(launches["n_launch_bwd"] - 5 * cover, 1)
+    bwd_ms, n_bwd = phase["ms_backward"] - phase["ms_param_grads"], max(launches["n_launch_bwd_steps"], 1)
 
     def kernel_figures(kname, ms, nl, nbytes):
         ach = nbytes / (ms * 1e-3) / 1e9

@@ -228,7 +228,8 @@ typedef struct ob_stats {
     int32_t n_proxies; /* earlier nodes the last stage read (0 when n_stages is 1) */
     int32_t n_depth_retries; /* schedules of this context so far that were repeated with the single-workgroup depth pass
                               * because a range of the partitioned pass ran into the bound on its wait */
-    int32_t reserved0;
+    int32_t n_launch_bwd_steps; /* launches of the backward step kernel alone (n_launch_bwd also counts the kernel that
+                                 * places the root and the deferred parameter-gradient kernels) */
 } ob_stats;
 int ob_stats_read(ob_ctx *ctx, ob_stats *out);
 

@@ -41,7 +41,7 @@ class ObStats(ctypes.Structure):
         [(n, c_uint64) for n in ("value_floats", "grad_floats", "arena_used_bytes", "upload_bytes")] + \
         [(n, c_float) for n in ("ms_upload", "ms_schedule", "ms_forward", "ms_backward", "ms_param_grads",
                                 "ms_graph_build")] + \
-        [(n, c_int32) for n in ("n_stages", "n_proxies", "n_depth_retries", "reserved0")]
+        [(n, c_int32) for n in ("n_stages", "n_proxies", "n_depth_retries", "n_launch_bwd_steps")]
 
     def as_dict(self):
         return {n: getattr(self, n) for n, _ in self._fields_ if not n.startswith("reserved")}

@@ -754,7 +754,9 @@ static int upload_param_tables(ob_ctx *ctx)
             }
         }
         if (ctx->params_used_b[p])
-            for (int i0 = 0; i0 < hp.rows; i0 += 32) ctx->btiles.push_back(PTile{(i32)p, i0, 0, 0});
+            for (int i0 = 0; i0 < hp.rows; i0 += 256) {   // pad = runs | first partial block << 8
+                ctx->btiles.push_back(PTile{(i32)p, i0, 0, (i32)((u32)PB_SPLIT | ((u32)ctx->btiles.size() * PB_SPLIT) << 8)});
+            }
     }
     ctx->params_dev = arena_array<ParamDesc>(ctx, desc.size() + 1);
     ctx->wtiles_dev = arena_array<PTile>(ctx, ctx->wtiles.size() + 1);
@@ -764,7 +766,8 @@ static int upload_param_tables(ob_ctx *ctx)
     for (PTile &t : ctx->wtiles) { const size_t runs = (size_t)t.pad; t.pad = (i32)(runs | (n_part << 8)); n_part += runs; }
     if (n_part >= (1u << 23)) return ctx_fail(ctx, OB_E_RANGE, "too many weight-gradient tiles");
     ctx->wpart_dev = arena_array<float>(ctx, n_part * (size_t)PWTILE * PWTILE + 1);
-    if (!ctx->params_dev || !ctx->wtiles_dev || !ctx->btiles_dev || !ctx->wpart_dev)
+    ctx->bpart_dev = arena_array<float>(ctx, ctx->btiles.size() * (size_t)PB_SPLIT * 256 + 1);
+    if (!ctx->params_dev || !ctx->wtiles_dev || !ctx->btiles_dev || !ctx->wpart_dev || !ctx->bpart_dev)
         return ctx_fail(ctx, OB_E_OOM, "arena too small for parameter tables");
     ctx->persist_top = ctx->top;
     if (!desc.empty())
@@ -1025,7 +1028,7 @@ static void stage_rebase(ob_ctx *c, ob_ctx *owner, char *arena, size_t bytes)
     c->params = owner->params; c->max_param_rows = owner->max_param_rows;
     c->params_used_w.assign(c->params.size(), 0);
     c->params_used_b.assign(c->params.size(), 0);
-    c->params_dev = nullptr; c->wtiles_dev = c->btiles_dev = nullptr; c->wpart_dev = nullptr;
+    c->params_dev = nullptr; c->wtiles_dev = c->btiles_dev = nullptr; c->wpart_dev = nullptr; c->bpart_dev = nullptr;
     c->params_dirty = true;
     c->err.clear();
 }
@@ -1135,7 +1138,7 @@ static int stage_forward(ob_ctx *ctx, u32 n0, u32 n1)
         // a stage only runs forward: the owner's parameter table serves (its entries do not depend on
         // which parameters a graph uses), and the tile lists of the parameter-gradient kernels are not needed
         c->params_dev = ctx->params_dev; c->wtiles_dev = ctx->wtiles_dev; c->btiles_dev = ctx->btiles_dev;
-        c->wpart_dev = ctx->wpart_dev;
+        c->wpart_dev = ctx->wpart_dev; c->bpart_dev = ctx->bpart_dev;
         c->wtiles = ctx->wtiles; c->btiles = ctx->btiles;   // (a backward pass over the stages runs the owner's tile lists)
         c->params_dirty = false;
     }
@@ -1458,6 +1461,7 @@ int ob_stats_read(ob_ctx *ctx, ob_stats *out)
     }
     out->ms_graph_build = ctx->ms_graph;
     out->n_depth_retries = ctx->n_depth_retries;
+    out->n_launch_bwd_steps = ctx->n_launch_bwd_steps;
     (void)hipGetLastError();
     return OB_OK;
 }

@@ -95,6 +95,7 @@ struct ob_ctx {
     std::vector<PTile> wtiles, btiles; // static tiles of the deferred dW / db kernels
     PTile *wtiles_dev = nullptr, *btiles_dev = nullptr;
     float *wpart_dev = nullptr;        // partial dW blocks of the workgroups that share a tile
+    float *bpart_dev = nullptr;        // partial db sums, 256 floats per (bias tile, run)
     int max_param_rows = 1;
     std::vector<std::vector<float>> pending;      // host copies of parameter data not yet on the device
     std::vector<u8> params_used_w, params_used_b; // parameter appeared as a MATVEC matrix / bias
@@ -145,6 +146,7 @@ struct ob_ctx {
     bool ev_ok = false;
     float ms_upload = 0, ms_schedule = 0, ms_forward = 0, ms_backward = 0, ms_param_grads = 0, ms_graph = 0;
     int n_launch_fwd = 0, n_launch_bwd = 0, n_launch_sched = 0;
+    int n_launch_bwd_steps = 0;        // launches of the backward step kernel alone (n_launch_bwd also counts the root and parameter kernels)
     size_t upload_bytes = 0;
 
     // hipGraph of the per-step launches (rebuilt per schedule)

@@ -832,35 +832,43 @@ __device__ inline void param_w_reduce(const Tables &T, const PTile &pt, const fl
     if (threadIdx.x == 0) P.marks[0] = 1u;   // this parameter's gradient is dense now
 }
 
-// db[i] += sum over uses of g[i].  A tile is 32 rows; the 8 groups of 32 threads take every 8th
-// use, 16 uses in flight per thread, and the partial sums are added in a fixed order.
-constexpr int PB_UNROLL = 16;
-__device__ inline void param_b_tile(const Tables &T, const PTile &pt, float *lds)
+// db[i] += sum over uses of g[i].  A tile is 256 rows (one per thread: a use's rows are one
+// contiguous kilobyte) and one of PB_SPLIT equal runs of the parameter's use list; it leaves a
+// partial sum, and the summing kernel adds the runs' partial sums in run order.
+constexpr u32 PB_ROWS = 256;
+constexpr u32 PB_UNROLL = 8;
+__device__ inline void param_b_tile(const Tables &T, const PTile &pt, u32 sp, float *part)
 {
     const u32 slot = (u32)pt.param * 4u + 1u;
     const u32 start = T.pu_start[slot], end = T.pu_end[slot];
     if (start == end) return;
     const ParamDesc P = T.params[pt.param];
-    const u32 l32 = threadIdx.x & 31, grp = threadIdx.x >> 5;
-    const u32 i = (u32)pt.i0 + l32;
+    const u32 nsp = (u32)pt.pad & 0xffu, pbase = (u32)pt.pad >> 8;
+    const u32 i = (u32)pt.i0 + threadIdx.x;
     const bool i_ok = i < (u32)P.rows;
+    const u32 n_uses = end - start, per = (n_uses + nsp - 1) / nsp;
+    const u32 lo = start + (sp * per < n_uses ? sp * per : n_uses), hi = start + ((sp + 1) * per < n_uses ? (sp + 1) * per : n_uses);
     float acc = 0.f;
-    for (u32 it0 = start + grp; it0 < end; it0 += 8 * PB_UNROLL) {
-        u32 go[PB_UNROLL];
-        bool ok[PB_UNROLL];
-#pragma unroll
-        for (int s = 0; s < PB_UNROLL; ++s) { const u32 it = it0 + 8 * s; ok[s] = it < end; go[s] = ok[s] ? T.it_goff[it] : 0u; }
+    for (u32 it0 = lo; it0 < hi; it0 += PB_UNROLL) {
         float g[PB_UNROLL];
 #pragma unroll
-        for (int s = 0; s < PB_UNROLL; ++s) g[s] = (ok[s] && i_ok) ? T.G[go[s] + i] : 0.f;
+        for (u32 q = 0; q < PB_UNROLL; ++q) g[q] = (it0 + q < hi && i_ok) ? T.G[T.it_goff[it0 + q] + i] : 0.f;
 #pragma unroll
-        for (int s = 0; s < PB_UNROLL; s += 4) acc += (g[s] + g[s + 1]) + (g[s + 2] + g[s + 3]);
+        for (u32 q = 0; q < PB_UNROLL; q += 4) acc += (g[q] + g[q + 1]) + (g[q + 2] + g[q + 3]);
     }
-    lds[grp * 32 + l32] = acc;
-    __syncthreads();
-    if (grp == 0 && i_ok) {
+    part[((size_t)pbase + sp) * PB_ROWS + threadIdx.x] = acc;
+}
+
+__device__ inline void param_b_reduce(const Tables &T, const PTile &pt, const float *part)
+{
+    const u32 slot = (u32)pt.param * 4u + 1u;
+    if (T.pu_start[slot] == T.pu_end[slot]) return;
+    const ParamDesc P = T.params[pt.param];
+    const u32 nsp = (u32)pt.pad & 0xffu, pbase = (u32)pt.pad >> 8;
+    const u32 i = (u32)pt.i0 + threadIdx.x;
+    if (i < (u32)P.rows) {
         float s = 0.f;
-        for (int q = 0; q < 8; ++q) s += lds[q * 32 + l32];
+        for (u32 q = 0; q < nsp; ++q) s += part[((size_t)pbase + q) * PB_ROWS + threadIdx.x];
         P.grad[i] += s;
     }
     if (threadIdx.x == 0) P.marks[0] = 1u;
@@ -1166,23 +1174,27 @@ __global__ void k_set_root(Tables T) { T.root_pos[0] = T.root == 0xffffffffu ? 0
 // Workgroup g runs on XCD g % 8 and the tile list is ordered so that tile t belongs on XCD t % 8 (an
 // XCD then keeps to one eighth of the gradient columns, which fit its L2): the runs of a tile are
 // therefore a multiple of eight workgroups apart.
-__global__ __launch_bounds__(WG) void k_param_w(Tables T, const PTile *tiles, u32 n_tiles, u32 n_tiles_pad, float *part)
+// (the workgroups behind the dW ones take the bias tiles: PB_SPLIT consecutive workgroups per tile)
+__global__ __launch_bounds__(WG) void k_param_w(Tables T, const PTile *tiles, u32 n_tiles, u32 n_tiles_pad, float *part,
+                                                const PTile *btiles, float *bpart)
 {
     __shared__ __align__(16) float lds[PW_LDS_FLOATS];
+    const u32 w_blocks = n_tiles_pad * PW_SPLIT_MAX;
+    if (blockIdx.x >= w_blocks) {
+        const u32 x = blockIdx.x - w_blocks;
+        param_b_tile(T, btiles[x / PB_SPLIT], x % PB_SPLIT, bpart);
+        return;
+    }
     const u32 tile = blockIdx.x % n_tiles_pad, sp = blockIdx.x / n_tiles_pad;
     if (tile >= n_tiles) return;
     param_w_tile(T, tiles[tile], lds, sp, part);
 }
 
-__global__ __launch_bounds__(WG) void k_param_w_sum(Tables T, const PTile *tiles, const float *part)
+__global__ __launch_bounds__(WG) void k_param_w_sum(Tables T, const PTile *tiles, u32 n_tiles, const float *part, const PTile *btiles,
+                                                    const float *bpart)
 {
+    if (blockIdx.x >= n_tiles) { param_b_reduce(T, btiles[blockIdx.x - n_tiles], bpart); return; }
     param_w_reduce(T, tiles[blockIdx.x], part);
-}
-
-__global__ __launch_bounds__(WG) void k_param_b(Tables T, const PTile *tiles)
-{
-    __shared__ float lds[WG];
-    param_b_tile(T, tiles[blockIdx.x], lds);
 }
 
 // dE[row, :] += sum of the gradients of every LOOKUP of (table, row): one wave per run of equal
@@ -1357,6 +1369,7 @@ static int launch_backward_steps(ob_ctx *ctx)
     const u32 ns = ctx->hdr.n_slots;
     hipLaunchKernelGGL(k_set_root, dim3(1), dim3(1), 0, s, T);
     ++ctx->n_launch_bwd;
+    const int before_steps = ctx->n_launch_bwd;
     for (u32 st = ns; st-- > 0;) {
         const SlotRec &r = ctx->slots[st], &e = ctx->slots[st + 1];
         const u32 n_pull = e.wa - r.wa, n_dx = e.tb - r.tb;
@@ -1380,6 +1393,7 @@ static int launch_backward_steps(ob_ctx *ctx)
             ++ctx->n_launch_bwd;
         }
     }
+    ctx->n_launch_bwd_steps = ctx->n_launch_bwd - before_steps;
     return 0;
 }
 
@@ -1388,17 +1402,13 @@ static int launch_param_grads(ob_ctx *ctx)
     const Tables &T = ctx->T;
     hipStream_t s = ctx->stream;
     if (ctx->hdr.n_items == 0) return 0;
-    if (!ctx->wtiles.empty()) {
-        const u32 n_tiles = (u32)ctx->wtiles.size(), n_pad = (n_tiles + 7u) & ~7u;
-        hipLaunchKernelGGL(k_param_w, dim3(n_pad * PW_SPLIT_MAX), dim3(WG), 0, s, T, ctx->wtiles_dev, n_tiles, n_pad,
-                           ctx->wpart_dev);
-        hipLaunchKernelGGL(k_param_w_sum, dim3((unsigned)ctx->wtiles.size()), dim3(WG), 0, s, T, ctx->wtiles_dev,
-                           (const float *)ctx->wpart_dev);
+    if (!ctx->wtiles.empty() || !ctx->btiles.empty()) {
+        const u32 n_tiles = (u32)ctx->wtiles.size(), n_pad = (n_tiles + 7u) & ~7u, n_b = (u32)ctx->btiles.size();
+        hipLaunchKernelGGL(k_param_w, dim3(n_pad * PW_SPLIT_MAX + n_b * PB_SPLIT), dim3(WG), 0, s, T, ctx->wtiles_dev, n_tiles, n_pad,
+                           ctx->wpart_dev, ctx->btiles_dev, ctx->bpart_dev);
+        hipLaunchKernelGGL(k_param_w_sum, dim3(n_tiles + n_b), dim3(WG), 0, s, T, ctx->wtiles_dev, n_tiles,
+                           (const float *)ctx->wpart_dev, ctx->btiles_dev, (const float *)ctx->bpart_dev);
         ctx->n_launch_bwd += 2;
-    }
-    if (!ctx->btiles.empty()) {
-        hipLaunchKernelGGL(k_param_b, dim3((unsigned)ctx->btiles.size()), dim3(WG), 0, s, T, ctx->btiles_dev);
-        ++ctx->n_launch_bwd;
     }
     u32 blocks = (ctx->hdr.n_items + 3) / 4;
     if (blocks > 2048) blocks = 2048;

@@ -21,6 +21,7 @@ constexpr int WG = 256;               // threads per workgroup of every tile ker
 constexpr int EW_TILE = 1024;         // elements of one elementwise / pull tile
 constexpr int GT = 32;                // forward / dW GEMM tile edge (one 32x32 MFMA accumulator block)
 constexpr int PWTILE = 64;            // dW tile edge of the deferred weight-gradient kernel
+constexpr int PB_SPLIT = 16;           // workgroups that share the use list of one 256-row bias-gradient tile
 constexpr int PW_SPLIT_MAX = 16;       // most workgroups that share the use list of one dW tile (matrices of many tiles take 4 or 8)
 constexpr int GTW = 64;               // forward GEMM tile edge of batches with at least WIDE_MIN_ROWS rows
 constexpr u32 WIDE_MIN_ROWS = 256;

@@ -157,9 +157,10 @@ constexpr int RS_BLOCK = RS_WAVE_KEYS * RS_WAVES;  // 1024 keys per block
 
 __device__ inline u32 digit_of(u64 key, int shift, u32 mask) { return (u32)(key >> shift) & mask; }
 
-// table[d * nblk + blk] = number of keys of block blk whose digit is d
+// number of keys of block blk whose digit is d: table[blk * 256 + d], or (dmajor, many blocks: the
+// table is then scanned as it lies) table[d * nblk + blk]
 __global__ __launch_bounds__(RS_THREADS) void k_rs_hist(const u64 *keys, size_t n, int shift, u32 mask,
-                                                       u32 *table, u32 nblk)
+                                                       u32 *table, u32 nblk, u32 dmajor)
 {
     __shared__ u32 hist[RS_RADIX];
     hist[threadIdx.x] = 0;
@@ -170,14 +171,67 @@ __global__ __launch_bounds__(RS_THREADS) void k_rs_hist(const u64 *keys, size_t 
         if (idx < n) atomicAdd(&hist[digit_of(keys[idx], shift, mask)], 1u);
     }
     __syncthreads();
-    table[(size_t)threadIdx.x * nblk + blockIdx.x] = hist[threadIdx.x];
+    table[dmajor ? (size_t)threadIdx.x * nblk + blockIdx.x : (size_t)blockIdx.x * RS_RADIX + threadIdx.x] = hist[threadIdx.x];
+}
+
+// One workgroup turns the per-block digit counts into the blocks' first output positions (an
+// exclusive scan in digit-major, block-minor order) in place: thread (segment, digit) first sums
+// its quarter of the blocks for its digit, the 256 digit totals are scanned in LDS, then every
+// thread walks its blocks again with a running position.  One launch where a general scan of the
+// table takes three.
+constexpr int RSO_THREADS = 1024;
+constexpr int RSO_SEGS = RSO_THREADS / RS_RADIX;
+constexpr u32 RSO_MAX_BLOCKS = 256;
+__global__ __launch_bounds__(RSO_THREADS) void k_rs_offsets(u32 *table, u32 nblk)
+{
+    __shared__ u32 seg_sum[RSO_SEGS][RS_RADIX];
+    __shared__ u32 dig[RS_RADIX];
+    const u32 d = threadIdx.x & (RS_RADIX - 1), seg = threadIdx.x / RS_RADIX;
+    const u32 per = (nblk + RSO_SEGS - 1) / RSO_SEGS;
+    const u32 b0 = seg * per < nblk ? seg * per : nblk, b1 = (seg + 1) * per < nblk ? (seg + 1) * per : nblk;
+    u32 sum = 0;
+    for (u32 b = b0; b < b1; b += 8) {       // eight loads in flight per thread
+        u32 c[8];
+#pragma unroll
+        for (u32 q = 0; q < 8; ++q) c[q] = b + q < b1 ? table[(size_t)(b + q) * RS_RADIX + d] : 0u;
+#pragma unroll
+        for (u32 q = 0; q < 8; ++q) sum += c[q];
+    }
+    seg_sum[seg][d] = sum;
+    __syncthreads();
+    if (seg == 0) {
+        u32 tot = 0;
+        for (int q = 0; q < RSO_SEGS; ++q) tot += seg_sum[q][d];
+        dig[d] = tot;
+    }
+    __syncthreads();
+    // inclusive scan of the digit totals (Kogge-Stone over 256 entries; the other threads only keep step at the barriers)
+    for (u32 off = 1; off < (u32)RS_RADIX; off <<= 1) {
+        u32 add = 0;
+        if (seg == 0 && d >= off) add = dig[d - off];
+        __syncthreads();
+        if (seg == 0) dig[d] += add;
+        __syncthreads();
+    }
+    u32 run = d ? dig[d - 1] : 0u;     // keys with a smaller digit
+    for (u32 q = 0; q < seg; ++q) run += seg_sum[q][d];
+    for (u32 b = b0; b < b1; b += 8) {
+        u32 c[8];
+#pragma unroll
+        for (u32 q = 0; q < 8; ++q) c[q] = b + q < b1 ? table[(size_t)(b + q) * RS_RADIX + d] : 0u;
+#pragma unroll
+        for (u32 q = 0; q < 8; ++q) {
+            if (b + q < b1) table[(size_t)(b + q) * RS_RADIX + d] = run;
+            run += c[q];
+        }
+    }
 }
 
 // Stable scatter.  Wave w of a block owns keys [w*256, w*256+256) of the block's chunk and
 // walks them in 4 rounds of 64; inside a round lanes with equal digits are ranked by lane id.
 __global__ __launch_bounds__(RS_THREADS) void k_rs_scatter(const u64 *keys, const u32 *vals, u64 *keys_out,
                                                           u32 *vals_out, size_t n, int shift, u32 mask,
-                                                          const u32 *table, u32 nblk)
+                                                          const u32 *table, u32 nblk, u32 dmajor)
 {
     __shared__ u32 cnt[RS_WAVES][RS_RADIX];
     const int lane = threadIdx.x & 63;
@@ -199,7 +253,7 @@ __global__ __launch_bounds__(RS_THREADS) void k_rs_scatter(const u64 *keys, cons
     __syncthreads();
     {   // thread d turns the per-wave counts of digit d into per-wave start positions
         const int d = threadIdx.x;
-        u32 run = table[(size_t)d * nblk + blockIdx.x];
+        u32 run = table[dmajor ? (size_t)d * nblk + blockIdx.x : (size_t)blockIdx.x * RS_RADIX + d];
         for (int i = 0; i < RS_WAVES; ++i) {
             const u32 c = cnt[i][d];
             cnt[i][d] = run;
@@ -376,15 +430,22 @@ static hipError_t sort_pairs_impl(u64 *keys, u32 *vals, u64 *keys_tmp, u32 *vals
         const int bits = (n_bits - b < RS_BITS) ? (n_bits - b) : RS_BITS;
         const u32 mask = (1u << bits) - 1u;
         const int shift = lo_bit + b;
-        hipLaunchKernelGGL(k_rs_hist, dim3(nblk), dim3(RS_THREADS), 0, s, kin, n, shift, mask, table, nblk);
-        hipError_t e = scan_impl<u32>(table, table, (size_t)RS_RADIX * nblk, (u32 *)nullptr, scan_scratch, s);
-        if (e != hipSuccess) return e;
+        // up to RSO_MAX_BLOCKS blocks one workgroup turns the counts into positions in one launch; beyond, the
+        // table is laid out digit-major and scanned by the general three-launch scan
+        const u32 dmajor = nblk > RSO_MAX_BLOCKS ? 1u : 0u;
+        hipLaunchKernelGGL(k_rs_hist, dim3(nblk), dim3(RS_THREADS), 0, s, kin, n, shift, mask, table, nblk, dmajor);
+        if (dmajor) {
+            hipError_t e = scan_impl<u32>(table, table, (size_t)RS_RADIX * nblk, (u32 *)nullptr, scan_scratch, s);
+            if (e != hipSuccess) return e;
+        } else {
+            hipLaunchKernelGGL(k_rs_offsets, dim3(1), dim3(RSO_THREADS), 0, s, table, nblk);
+        }
         hipLaunchKernelGGL(k_rs_scatter, dim3(nblk), dim3(RS_THREADS), 0, s, kin, vin, kout, vout, n, shift,
-                           mask, table, nblk);
+                           mask, table, nblk, dmajor);
         u64 *tk = kin; kin = kout; kout = tk;
         u32 *tv = vin; vin = vout; vout = tv;
         ++passes;
-        if (n_launches) *n_launches += 2 + ((size_t)RS_RADIX * nblk > SCAN_SMALL_MAX ? 3 : 1);
+        if (n_launches) *n_launches += dmajor ? 5 : 3;
     }
     if ((passes & 1) && in_tmp) {   // the caller takes the result where it is
         *in_tmp = true;

@@ -26,7 +26,8 @@ def test_scan(ctx, n):
 
 @pytest.mark.parametrize("n,lo,bits", [(1, 0, 8), (2, 0, 1), (64, 0, 8), (1000, 0, 18), (1023, 5, 26), (1025, 32, 10),
                                        (4097, 0, 5), (4097, 0, 26), (8192, 0, 24), (8192, 7, 17), (8193, 0, 9),
-                                       (240000, 0, 18), (240000, 32, 18), (196608, 0, 12), (196609, 3, 12), (80000, 0, 17)])
+                                       (240000, 0, 18), (240000, 32, 18), (196608, 0, 12), (196609, 3, 12), (80000, 0, 17),
+                                       (262144, 0, 9), (262145, 0, 16), (700001, 4, 12)])
 def test_radix_sort_is_stable_and_exact(ctx, n, lo, bits):
     rng = np.random.default_rng(n + lo)
     keys = rng.integers(0, 1 << 62, size=n, dtype=np.uint64)
