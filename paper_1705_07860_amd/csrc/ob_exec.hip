@@ -894,15 +894,43 @@ __device__ inline float4 ldg4(const Tables &T, const lds_float *cl, bool from_ld
     return v;
 }
 
+// What the consumer's gradient is multiplied by, from the forward value y the edge names: 1 (plain and range
+// edges), y (product), 1 - y^2 (tanh), y (1 - y) (logistic).  Every routine that evaluates such an edge forms
+// gradient x factor with these and with separately rounded products and sums, so that a node's gradient does
+// not depend on which routine its tile went through.
+__device__ inline float mul_r(float a, float b)
+{
+#pragma clang fp contract(off)
+    return a * b;
+}
+__device__ inline float add_r(float a, float b)
+{
+#pragma clang fp contract(off)
+    return a + b;
+}
+__device__ inline float edge_factor(u32 kind, float y)
+{
+    const float ft = __builtin_fmaf(-y, y, 1.0f), fs = mul_r(y, 1.0f - y);
+    float f = 1.0f;
+    f = kind == (u32)EK_MUL ? y : f;
+    f = kind == (u32)EK_DTANH ? ft : f;
+    f = kind == (u32)EK_DSIGM ? fs : f;
+    return f;
+}
+__device__ inline float4 edge_factor4(u32 kind, float4 y)
+{
+    return make_float4(edge_factor(kind, y.x), edge_factor(kind, y.y), edge_factor(kind, y.z), edge_factor(kind, y.w));
+}
+
 __device__ inline float edge_term(const Tables &T, const lds_float *cl, bool fl, u32 dl, u32 kind, u32 goff, u32 voff, i32 a0,
                                   i32 a1, u32 own, u32 col)
 {
     switch (kind) {
     case EK_PLAIN: return ldg(T, cl, fl, dl, goff + col);
     case EK_RANGE: return ((i32)col >= a0 && (i32)col < a1) ? ldg(T, cl, fl, dl, goff + col - (u32)a0) : 0.f;
-    case EK_MUL: return ldg(T, cl, fl, dl, goff + col) * T.V[voff + col];
-    case EK_DTANH: { const float y = T.V[voff + col]; return ldg(T, cl, fl, dl, goff + col) * (1.0f - y * y); }
-    case EK_DSIGM: { const float y = T.V[voff + col]; return ldg(T, cl, fl, dl, goff + col) * y * (1.0f - y); }
+    case EK_MUL:
+    case EK_DTANH:
+    case EK_DSIGM: return mul_r(ldg(T, cl, fl, dl, goff + col), edge_factor(kind, T.V[voff + col]));
     case EK_NLS: {   // a1: the row's dimension
         const float lse = T.V[voff] + T.V[own + (u32)a0];
         float p;
@@ -930,19 +958,11 @@ __device__ inline float4 edge_term4(const Tables &T, const lds_float *cl, bool f
     switch (kind) {
     case EK_PLAIN: return ldg4(T, cl, fl, dl, goff + col);
     case EK_RANGE: return ((i32)col >= a0 && (i32)col < a1) ? ldg4(T, cl, fl, dl, goff + col - (u32)a0) : z;
-    case EK_MUL: {
-        const float4 g = ldg4(T, cl, fl, dl, goff + col), v = ld4(T.V + voff + col);
-        return make_float4(g.x * v.x, g.y * v.y, g.z * v.z, g.w * v.w);
-    }
-    case EK_DTANH: {
-        const float4 g = ldg4(T, cl, fl, dl, goff + col), y = ld4(T.V + voff + col);
-        return make_float4(g.x * (1.0f - y.x * y.x), g.y * (1.0f - y.y * y.y), g.z * (1.0f - y.z * y.z),
-                           g.w * (1.0f - y.w * y.w));
-    }
+    case EK_MUL:
+    case EK_DTANH:
     case EK_DSIGM: {
-        const float4 g = ldg4(T, cl, fl, dl, goff + col), y = ld4(T.V + voff + col);
-        return make_float4(g.x * y.x * (1.0f - y.x), g.y * y.y * (1.0f - y.y), g.z * y.z * (1.0f - y.z),
-                           g.w * y.w * (1.0f - y.w));
+        const float4 g = ldg4(T, cl, fl, dl, goff + col), f = edge_factor4(kind, ld4(T.V + voff + col));
+        return make_float4(mul_r(g.x, f.x), mul_r(g.y, f.y), mul_r(g.z, f.z), mul_r(g.w, f.w));
     }
     case EK_SQN: {
         const float g2 = 2.0f * T.G[goff];
@@ -969,9 +989,9 @@ __device__ inline void pull_tile(const Tables &T, const PullDesc &d, lds_float *
             for (u32 j = 0; j < 4; ++j) {
                 if (j < d.n_uni) {
                     const UEdge ue = d.e[j];
-                    const float4 t = edge_term4(T, cl, (d.lflags & (TF_SRC_LDS << j)) != 0, d.lds_g[j], ue.kind,
+                    const float4 t = edge_term4(T, cl, (d.lflags & (TF_SRC_LDS << j)) != 0, d.e[j].dl, ue.kind,
                                                 ue.goff + dr * ue.gs, ue.voff + dr * ue.vs, ue.a0, ue.a1, own, col);
-                    acc.x += t.x; acc.y += t.y; acc.z += t.z; acc.w += t.w;
+                    acc.x = add_r(acc.x, t.x); acc.y = add_r(acc.y, t.y); acc.z = add_r(acc.z, t.z); acc.w = add_r(acc.w, t.w);
                 }
             }
             st4(T.G + own + col, acc);
@@ -989,8 +1009,8 @@ __device__ inline void pull_tile(const Tables &T, const PullDesc &d, lds_float *
             for (u32 j = 0; j < 4; ++j) {
                 if (j < d.n_uni) {
                     const UEdge ue = d.e[j];
-                    acc += edge_term(T, cl, (d.lflags & (TF_SRC_LDS << j)) != 0, d.lds_g[j], ue.kind, ue.goff + dr * ue.gs,
-                                     ue.voff + dr * ue.vs, ue.a0, ue.a1, own, col);
+                    acc = add_r(acc, edge_term(T, cl, (d.lflags & (TF_SRC_LDS << j)) != 0, d.e[j].dl, ue.kind, ue.goff + dr * ue.gs,
+                                     ue.voff + dr * ue.vs, ue.a0, ue.a1, own, col));
                 }
             }
         } else {
@@ -999,11 +1019,84 @@ __device__ inline void pull_tile(const Tables &T, const PullDesc &d, lds_float *
             const u32 q1 = T.succ_off[u + 1];
             for (u32 q = T.succ_off[u]; q < q1; ++q) {
                 const EdgeRec er = T.edges[q];
-                acc += edge_term(T, cl, false, 0u, er.kind, er.goff, er.voff, er.a0, er.a1, ownv, col);
+                acc = add_r(acc, edge_term(T, cl, false, 0u, er.kind, er.goff, er.voff, er.a0, er.a1, ownv, col));
             }
         }
         T.G[own + col] = acc;
         if (keep) cl[(u32)(own + col + d.lds_out)] = acc;
+    }
+}
+
+// The tile of a fused backward run as it nearly always is: every row has the same (at most four) consumer
+// edges up to constant row strides, of the kinds that need one gradient and at most one forward value per
+// column, and the columns go by fours (bit 2 of the descriptor's vec4 field; its edges are stored resolved).
+// A level of a run is one such tile per wave, so what a level costs is the number of instructions this
+// routine issues: the descriptor comes in twelve 16-byte LDS reads asked for together, control values go to
+// scalar registers, a tile of one row per thread block (the usual case) needs no row arithmetic, absent
+// edges are skipped, and everything the thread's columns need is asked for before any of it is used.
+// d must lie in LDS.
+typedef u32 vec4u __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(3))) const vec4u lds_vec4u;
+__device__ inline uint4 lds_q(const PullDesc &d, u32 k)
+{
+    const vec4u t = ((lds_vec4u *)(&d))[k];
+    return make_uint4(t.x, t.y, t.z, t.w);
+}
+__device__ inline u32 sreg(u32 v) { return __builtin_amdgcn_readfirstlane(v); }
+
+// One or two edges of such a tile: loads first, sums after.
+template <u32 J0, u32 NJ>
+__device__ inline void pull_uni4_edges(const Tables &T, const uint4 *q, lds_float *cl, u32 n_uni, u32 lflags, bool one_row, u32 dr,
+                                       u32 col, float4 &acc)
+{
+    float4 g[NJ], v[NJ];
+    u32 kind[NJ];
+#pragma unroll
+    for (u32 jj = 0; jj < NJ; ++jj) {
+        const u32 j = J0 + jj;
+        if (j < n_uni) {
+            const uint4 ea = q[2 + 2 * j], eb = q[3 + 2 * j];   // kind, goff, voff, gs | vs, a0, a1, dl
+            kind[jj] = sreg(ea.x);
+            u32 gi = ea.y + col, vi = ea.z + col;
+            if (!one_row) { gi += dr * ea.w; vi += dr * eb.x; }
+            if (kind[jj] >= (u32)EK_MUL) v[jj] = ld4(T.V + vi);
+            const bool in = kind[jj] != (u32)EK_RANGE || (col >= eb.y && col < eb.z);
+            g[jj] = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (lflags & (TF_SRC_LDS << j)) { if (in) g[jj] = lds_ld4(cl + gi); }
+            else if (in) g[jj] = ld4(T.G + gi);
+        }
+    }
+#pragma unroll
+    for (u32 jj = 0; jj < NJ; ++jj) {
+        if (J0 + jj < n_uni) {
+            float4 t = g[jj];
+            if (kind[jj] >= (u32)EK_MUL) {
+                const float4 f = edge_factor4(kind[jj], v[jj]);
+                t = make_float4(mul_r(t.x, f.x), mul_r(t.y, f.y), mul_r(t.z, f.z), mul_r(t.w, f.w));
+            }
+            acc.x = add_r(acc.x, t.x); acc.y = add_r(acc.y, t.y); acc.z = add_r(acc.z, t.z); acc.w = add_r(acc.w, t.w);
+        }
+    }
+}
+
+// q: the tile's descriptor as its twelve 16-byte words, already asked for by the caller
+__device__ inline void pull_tile_uni4(const Tables &T, const uint4 *q, lds_float *cl, u32 tid, u32 nthr)
+{
+    const u32 dd = q[0].z, n_uni = sreg(q[1].z), nrows = sreg(q[1].w), lflags = sreg(q[10].w);
+    const u32 lds_out = q[11].x, dshift = sreg(q[11].y), own0 = q[11].z, rowstep = q[11].w;
+    const bool one_row = nrows == 1u;
+    const u32 total = one_row ? dd : nrows << dshift;
+    const float *Gx = T.Gx;
+    for (u32 x = tid * 4u; x < total; x += nthr * 4u) {
+        u32 dr = 0, col = x;
+        if (!one_row) { dr = x >> dshift; col = x & (dd - 1u); }
+        const u32 own = own0 + col + (one_row ? 0u : dr * rowstep);
+        float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (Gx) acc = ld4(Gx + own);
+        pull_uni4_edges<0, 2>(T, q, cl, n_uni, lflags, one_row, dr, col, acc);
+        if (n_uni > 2u) pull_uni4_edges<2, 2>(T, q, cl, n_uni, lflags, one_row, dr, col, acc);
+        st4(T.G + own, acc);
+        if (lflags & TF_OUT_LDS) lds_st4(cl + (u32)(own + lds_out), acc);
     }
 }
 
@@ -1109,7 +1202,7 @@ __global__ __launch_bounds__(WG, LEAN ? 6 : 4) void k_fwd_step(u32 work_lo, u32 
 // pull computes; otherwise the host launches the pull range and the dX range one after the other.
 constexpr int BWD_THREADS = DX_WAVES * 64;
 template <bool LEAN>
-__global__ __launch_bounds__(BWD_THREADS, LEAN ? 5 : 4) void k_bwd_step(u32 work_lo, u32 work_hi, u32 tile_lo, u32 run_len,
+__global__ __launch_bounds__(BWD_THREADS, 4) void k_bwd_step(u32 work_lo, u32 work_hi, u32 tile_lo, u32 run_len,
                                                                         u32 dx_lo, u32 dx_hi, const PullDesc *tiles_a,
                                                                         const WorkRec *works_a, const TileDesc *tiles_b, Tables T)
 {
@@ -1127,42 +1220,65 @@ __global__ __launch_bounds__(BWD_THREADS, LEAN ? 5 : 4) void k_bwd_step(u32 work
         const u32 w = work_lo + (item - n_dx);
         WorkRec wr;
         if (run_len) { wr.first = tile_lo + (w - work_lo) * run_len; wr.len = run_len; }
-        else wr = works_a[w];
-        if (wr.len == 1) {
-            const PullDesc d = tiles_a[wr.first];
-            pull_tile(T, d, (lds_float *)lds, threadIdx.x, BWD_THREADS);
-            continue;
-        }
+        else { wr = works_a[w]; wr.first = sreg(wr.first); wr.len = sreg(wr.len); }
         for (u32 c0 = 0; c0 < wr.len; c0 += RUN_STAGE) {
             const u32 cn = wr.len - c0 < RUN_STAGE ? wr.len - c0 : RUN_STAGE;
             __syncthreads();
             stage_descriptors<sizeof(PullDesc) / 4, BWD_THREADS>(tiles_a + wr.first + c0, sdesc, cn);
             __syncthreads();
             const bool heavy = __ballot(lane < cn && (sdesc[lane < cn ? lane : 0].lflags & TF_GLOBAL_DEP)) != 0ull;
-            // Every level of the run reads forward values (and gradients from outside the run) that
-            // no level before it touches: ask for all of them now, one lane per 128-byte line, so the
-            // levels find them in the cache instead of each waiting for memory in turn.
-            for (u32 x = threadIdx.x; x < cn * 32u; x += BWD_THREADS) {
-                const PullDesc &pd = sdesc[x >> 5];
-                const u32 j = (x >> 3) & 3u, el = (x & 7u) * 32u;
-                if (pd.n_uni != PULL_GENERIC && j < pd.n_uni && el < pd.nrows * pd.d) {
-                    const UEdge ue = pd.e[j];
-                    const u32 dr = el / pd.d, col = el % pd.d;
-                    if (ue.kind == EK_MUL || ue.kind == EK_DTANH || ue.kind == EK_DSIGM) sink += T.V[ue.voff + dr * ue.vs + col];
-                    if (!(pd.lflags & (TF_SRC_LDS << j)) && (ue.kind == EK_PLAIN || ue.kind == EK_MUL || ue.kind == EK_DTANH || ue.kind == EK_DSIGM))
-                        sink += T.G[ue.goff + dr * ue.gs + col];
+            // Every level of a run reads forward values (and gradients from outside the run) that no
+            // level before it touches: ask for all of them now, one lane per 128-byte line, so the
+            // levels find them in the cache instead of each waiting for memory in turn.  Nothing waits
+            // for these loads themselves: their sum is taken when the run is over.
+            float early[4] = {0.f, 0.f, 0.f, 0.f};
+            if (cn > 1) {
+#pragma unroll
+                for (u32 h = 0; h < 2; ++h) {
+                    const u32 x = threadIdx.x + h * BWD_THREADS;
+                    if (x < cn * 32u) {
+                        const PullDesc &pd = sdesc[x >> 5];
+                        const u32 j = (x >> 3) & 3u, el = (x & 7u) * 32u;
+                        if (pd.n_uni != PULL_GENERIC && j < pd.n_uni && el < pd.nrows * pd.d) {
+                            const UEdge ue = pd.e[j];
+                            const u32 dr = el / pd.d, col = el % pd.d;
+                            const bool uses_v = ue.kind == EK_MUL || ue.kind == EK_DTANH || ue.kind == EK_DSIGM;
+                            const bool far_g = !(pd.lflags & (TF_SRC_LDS << j)) && (ue.kind == EK_PLAIN || uses_v);
+                            if (uses_v) early[2 * h] = T.V[ue.voff + dr * ue.vs + col];
+                            if (far_g) early[2 * h + 1] = T.G[ue.goff + dr * ue.gs + col];
+                        }
+                    }
                 }
             }
+            // Tiles of one level are spread over the waves: with fewer than eight of them a tile is cut
+            // into parts (8 / tiles, rounded down), one wave each.  Where the levels start is found once,
+            // as a bit mask over the staged tiles (a tile starts a level when the one before it ends one).
+            unsigned long long starts =
+                __ballot(lane < cn && (lane == 0u || sdesc[lane == 0u || lane >= cn ? 0u : lane - 1u].grp_len <= 1u));
             u32 i = 0;
             while (i < cn) {
-                u32 glen = __builtin_amdgcn_readfirstlane(sdesc[i].grp_len);
-                if (glen == 0) glen = 1;
-                if (glen > cn - i) glen = cn - i;
-                if (glen == 1) pull_tile(T, sdesc[i], (lds_float *)lds, threadIdx.x, BWD_THREADS);
-                else for (u32 t = i + wave; t < i + glen; t += BWD_THREADS / 64) pull_tile(T, sdesc[t], (lds_float *)lds, lane, 64);
-                i += glen;
+                starts &= starts - 1ull;
+                const u32 next = starts ? (u32)__builtin_ctzll(starts) : cn;
+                const u32 glen = next - i;
+                const u32 g8 = glen < 8u ? glen : 8u;
+                const u32 parts = g8 == 1u ? 8u : g8 == 2u ? 4u : g8 <= 4u ? 2u : 1u;
+                u32 part = 0, tw = wave;
+                if (g8 == 1u) { part = wave; tw = 0; }
+                else while (tw >= g8) { tw -= g8; ++part; }
+                if (part < parts) {
+                    for (u32 t = i + tw; t < next; t += BWD_THREADS / 64) {
+                        const PullDesc &d = sdesc[t];
+                        uint4 q[12];
+#pragma unroll
+                        for (u32 k = 0; k < 12; ++k) q[k] = lds_q(d, k);
+                        if (sreg(q[10].z) & 4u) pull_tile_uni4(T, q, (lds_float *)lds, part * 64u + lane, parts * 64u);
+                        else pull_tile(T, d, (lds_float *)lds, part * 64u + lane, parts * 64u);
+                    }
+                }
+                i = next;
                 if (i < cn) run_barrier(heavy);
             }
+            sink += (early[0] + early[1]) + (early[2] + early[3]);
         }
         __syncthreads();
     }

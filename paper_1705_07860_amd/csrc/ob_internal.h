@@ -119,22 +119,29 @@ struct TileDesc {
 };
 static_assert(sizeof(TileDesc) == 160, "TileDesc must be 160 bytes");
 
-// A consumer edge that is the same for every row of a pull tile up to constant row strides.
-struct UEdge { u32 kind, goff, voff, gs, vs; i32 a0, a1; };
+// A consumer edge that is the same for every row of a pull tile up to constant row strides (32 bytes, two
+// aligned 16-byte reads).  dl: with TF_SRC_LDS << j in the tile's lflags, the consumer's gradient is read
+// from the fused run's LDS copy at index (gradient-arena offset + dl) in u32 wrap-around arithmetic.
+struct UEdge { u32 kind, goff, voff, gs, vs; i32 a0, a1; u32 dl; };
 
 // One backward pull tile.  n_uni <= 4: every row of the tile has exactly n_uni consumer edges and
 // edge j of row r is e[j] shifted by (r - row0) * (gs, vs); n_uni == PULL_GENERIC: rows differ,
-// walk the consumer CSR per element.
+// walk the consumer CSR per element.  The record is twelve aligned 16-byte words.
 constexpr u32 PULL_GENERIC = 0xffffffffu;
+constexpr u32 PULL_NO_SHIFT = 0xffffffffu;
 struct PullDesc {
     u32 pos0, B, d, val_off;
     u32 depth, row0, n_uni, nrows;   // rows row0 + i * rstride, i < nrows, of the batch, all columns
     UEdge e[4];                      // edge j of the i-th row: e[j] shifted by i * (gs, vs)
     u32 rstride, grp_len;            // grp_len: tiles of the same depth that follow in the run, this one included
-    u32 vec4, lflags;                // vec4: d % 4 == 0 and every offset / stride / range of e[] is a multiple of 4
-    u32 lds_out, lds_g[4];           // LDS index = gradient-arena offset + lds_out (own rows) / + lds_g[j] (edge j)
-    u32 pad[3];
+    u32 vec4, lflags;                // vec4 bit 0: d % 4 == 0 and every offset / stride / range of e[] is a multiple of 4;
+                                     // bit 1: the batch is a view; bit 2: bit 0 and no edge kind beyond EK_DSIGM (the short routine applies)
+    u32 lds_out, dshift;             // LDS index of the own rows = gradient-arena offset + lds_out; dshift: log2(d), or PULL_NO_SHIFT
+    u32 own0, rowstep;               // val_off + row0 * d and rstride * d: the tile's i-th row starts at own0 + i * rowstep
 };
+// With bit 2 of vec4 set the edges are stored resolved for the short routine: goff already has the slice's
+// lower bound subtracted (EK_RANGE) and, for a consumer read from the run's LDS copy, dl added, so the
+// routine's index of column c of the tile's i-th row is goff + i * gs + c in either memory.
 static_assert(sizeof(PullDesc) == 192, "PullDesc must be 192 bytes");
 
 // A launch chain: batches that run in the same launch slot.  A fused chain holds component-wise

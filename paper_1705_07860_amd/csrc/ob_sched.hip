@@ -1240,11 +1240,11 @@ constexpr u32 PULL_MAX_ROWS = 16;
 __device__ inline void fill_pull_base(const Tables &T, const BatchRec &r, u32 row0, u32 nrows, u32 rstride, PullDesc &d)
 {
     d.lflags = 0; d.lds_out = 0;
-    for (int j = 0; j < 4; ++j) d.lds_g[j] = 0;
-    d.pad[0] = d.pad[1] = d.pad[2] = 0;
+    d.own0 = r.val_off + row0 * r.d; d.rowstep = rstride * r.d;
+    d.dshift = (r.d & (r.d - 1u)) == 0u && r.d ? (u32)__ffs(r.d) - 1u : PULL_NO_SHIFT;
     d.pos0 = r.pos0; d.B = r.B; d.d = r.d; d.val_off = r.val_off;
     d.depth = r.step; d.row0 = row0; d.nrows = nrows; d.n_uni = PULL_GENERIC; d.rstride = rstride;
-    for (int j = 0; j < 4; ++j) { UEdge z; z.kind = 0; z.goff = z.voff = z.gs = z.vs = 0; z.a0 = z.a1 = 0; d.e[j] = z; }
+    for (int j = 0; j < 4; ++j) { UEdge z; z.kind = 0; z.goff = z.voff = z.gs = z.vs = 0; z.a0 = z.a1 = 0; z.dl = 0; d.e[j] = z; }
     d.grp_len = 1; d.vec4 = (r.vec4 & TF_VIEW) ? 2u : 0u;   // bit 1: the batch is a view (its values lie in its operands' rows)
     if (nrows > PULL_MAX_ROWS) return;
     const u32 u0 = T.order[r.pos0 + row0];
@@ -1257,7 +1257,7 @@ __device__ inline void fill_pull_base(const Tables &T, const BatchRec &r, u32 ro
         if (first[j].kind == EK_NLS) return;     // the label is per-row data
         if (first[j].kind == EK_SQN && (r.vec4 & TF_VIEW)) return;   // needs the rows' own values, which a view keeps elsewhere
         UEdge ue; ue.kind = first[j].kind; ue.goff = first[j].goff; ue.voff = first[j].voff;
-        ue.gs = ue.vs = 0; ue.a0 = first[j].a0; ue.a1 = first[j].a1;
+        ue.gs = ue.vs = 0; ue.a0 = first[j].a0; ue.a1 = first[j].a1; ue.dl = 0;
         d.e[j] = ue;
     }
     for (u32 i = 1; i < nrows; ++i) {
@@ -1281,7 +1281,11 @@ __device__ inline void fill_pull_base(const Tables &T, const BatchRec &r, u32 ro
         if ((ue.kind == EK_MUL || ue.kind == EK_DTANH || ue.kind == EK_DSIGM) && ((ue.voff | ue.vs) & 3u)) vec = false;
         if (ue.kind == EK_RANGE && (((u32)ue.a0 | (u32)ue.a1) & 3u)) vec = false;
     }
-    d.vec4 = (d.vec4 & 2u) | (vec ? 1u : 0u);
+    u32 worst = 0;
+    for (u32 j = 0; j < cnt; ++j) worst = d.e[j].kind > worst ? d.e[j].kind : worst;
+    // (the short routine finds rows and columns by shifting: one row, or a power of two of columns)
+    const bool shifts = nrows == 1u || d.dshift != PULL_NO_SHIFT;
+    d.vec4 = (d.vec4 & 2u) | (vec ? 1u : 0u) | (vec && shifts && worst <= (u32)EK_DSIGM ? 4u : 0u);
 }
 
 __device__ inline void fill_pull_desc(const Tables &T, const BatchRec &r, u32 row0, u32 nrows, u32 rstride, PullDesc &d,
@@ -1294,7 +1298,7 @@ __device__ inline void fill_pull_desc(const Tables &T, const BatchRec &r, u32 ro
     if (cc->cr.fused != 2u) { d.lflags = TF_GLOBAL_DEP; return; }
     d.lds_out = chain_own_delta(T, *cc, r);
     d.lflags = TF_OUT_LDS;
-    if (d.lds_out & 3u) d.vec4 &= ~1u;
+    if (d.lds_out & 3u) d.vec4 &= ~5u;
     if (d.n_uni == PULL_GENERIC) { d.lflags |= TF_GLOBAL_DEP; return; }
     u32 lo[4], hi[4], state[4], delta[4];
     for (u32 j = 0; j < d.n_uni; ++j) {
@@ -1303,8 +1307,18 @@ __device__ inline void fill_pull_desc(const Tables &T, const BatchRec &r, u32 ro
     }
     chain_lookup(T, *cc, d.n_uni, lo, hi, state, delta);
     for (u32 j = 0; j < d.n_uni; ++j) {
-        if (state[j] == 1 && (!(d.vec4 & 1u) || (delta[j] & 3u) == 0)) { d.lflags |= TF_SRC_LDS << j; d.lds_g[j] = delta[j]; }
+        if (state[j] == 1 && (!(d.vec4 & 1u) || (delta[j] & 3u) == 0)) { d.lflags |= TF_SRC_LDS << j; d.e[j].dl = delta[j]; }
         else if (state[j] != 0) d.lflags |= TF_GLOBAL_DEP;
+    }
+}
+
+// Tiles for the short routine carry their edges resolved (see PullDesc).
+__device__ inline void resolve_pull_desc(PullDesc &d)
+{
+    if (!(d.vec4 & 4u)) return;
+    for (u32 j = 0; j < d.n_uni; ++j) {
+        if (d.e[j].kind == EK_RANGE) d.e[j].goff -= (u32)d.e[j].a0;
+        if (d.lflags & (TF_SRC_LDS << j)) d.e[j].goff += d.e[j].dl;
     }
 }
 
@@ -1400,6 +1414,7 @@ __global__ void k_tiles(Tables T, const CLay *clay_ex, const CLay *total, u32 ca
                 if (which == 1) {
                     PullDesc d;
                     fill_pull_desc(T, r, row0, ng, mult, d, pcc);
+                    resolve_pull_desc(d);
                     d.grp_len = glen;
                     T.tiles_a[x] = d;
                 } else {
