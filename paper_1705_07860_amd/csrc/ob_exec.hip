@@ -936,9 +936,16 @@ __device__ inline float edge_term(const Tables &T, const lds_float *cl, bool fl,
         float p;
         if ((i32)col == a0) {
             // p_label - 1 as minus the sum of the other probabilities: no cancellation when p_label is close to 1
+            // (eight logits are asked for at a time: one after the other, each would wait for memory in turn)
             float others = 0.f;
-            for (i32 c = 0; c < a1; ++c)
-                if (c != a0) others += expf(T.V[own + (u32)c] - lse);
+            for (i32 c0 = 0; c0 < a1; c0 += 8) {
+                float xv[8];
+#pragma unroll
+                for (i32 k = 0; k < 8; ++k) xv[k] = T.V[own + (u32)(c0 + k < a1 ? c0 + k : a1 - 1)];
+#pragma unroll
+                for (i32 k = 0; k < 8; ++k)
+                    if (c0 + k < a1 && c0 + k != a0) others += expf(xv[k] - lse);
+            }
             p = -others;
         } else {
             p = expf(T.V[own + col] - lse);
