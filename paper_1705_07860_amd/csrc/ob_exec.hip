@@ -923,11 +923,11 @@ __device__ inline float4 edge_factor4(u32 kind, float4 y)
 }
 
 __device__ inline float edge_term(const Tables &T, const lds_float *cl, bool fl, u32 dl, u32 kind, u32 goff, u32 voff, i32 a0,
-                                  i32 a1, u32 own, u32 col)
+                                  i32 a1, u32 own, u32 col, bool resolved = false)
 {
     switch (kind) {
     case EK_PLAIN: return ldg(T, cl, fl, dl, goff + col);
-    case EK_RANGE: return ((i32)col >= a0 && (i32)col < a1) ? ldg(T, cl, fl, dl, goff + col - (u32)a0) : 0.f;
+    case EK_RANGE: return ((i32)col >= a0 && (i32)col < a1) ? ldg(T, cl, fl, dl, goff + col - (resolved ? 0u : (u32)a0)) : 0.f;
     case EK_MUL:
     case EK_DTANH:
     case EK_DSIGM: return mul_r(ldg(T, cl, fl, dl, goff + col), edge_factor(kind, T.V[voff + col]));
@@ -959,12 +959,12 @@ __device__ inline float edge_term(const Tables &T, const lds_float *cl, bool fl,
 
 // four consecutive columns of one uniform edge (all offsets are multiples of 4; EK_NLS never is uniform)
 __device__ inline float4 edge_term4(const Tables &T, const lds_float *cl, bool fl, u32 dl, u32 kind, u32 goff, u32 voff, i32 a0,
-                                    i32 a1, u32 own, u32 col)
+                                    i32 a1, u32 own, u32 col, bool resolved = false)
 {
     const float4 z = make_float4(0.f, 0.f, 0.f, 0.f);
     switch (kind) {
     case EK_PLAIN: return ldg4(T, cl, fl, dl, goff + col);
-    case EK_RANGE: return ((i32)col >= a0 && (i32)col < a1) ? ldg4(T, cl, fl, dl, goff + col - (u32)a0) : z;
+    case EK_RANGE: return ((i32)col >= a0 && (i32)col < a1) ? ldg4(T, cl, fl, dl, goff + col - (resolved ? 0u : (u32)a0)) : z;
     case EK_MUL:
     case EK_DTANH:
     case EK_DSIGM: {
@@ -996,8 +996,8 @@ __device__ inline void pull_tile(const Tables &T, const PullDesc &d, lds_float *
             for (u32 j = 0; j < 4; ++j) {
                 if (j < d.n_uni) {
                     const UEdge ue = d.e[j];
-                    const float4 t = edge_term4(T, cl, (d.lflags & (TF_SRC_LDS << j)) != 0, d.e[j].dl, ue.kind,
-                                                ue.goff + dr * ue.gs, ue.voff + dr * ue.vs, ue.a0, ue.a1, own, col);
+                    const float4 t = edge_term4(T, cl, (d.lflags & (TF_SRC_LDS << j)) != 0, 0u, ue.kind,
+                                                ue.goff + dr * ue.gs, ue.voff + dr * ue.vs, ue.a0, ue.a1, own, col, true);
                     acc.x = add_r(acc.x, t.x); acc.y = add_r(acc.y, t.y); acc.z = add_r(acc.z, t.z); acc.w = add_r(acc.w, t.w);
                 }
             }
@@ -1016,8 +1016,8 @@ __device__ inline void pull_tile(const Tables &T, const PullDesc &d, lds_float *
             for (u32 j = 0; j < 4; ++j) {
                 if (j < d.n_uni) {
                     const UEdge ue = d.e[j];
-                    acc = add_r(acc, edge_term(T, cl, (d.lflags & (TF_SRC_LDS << j)) != 0, d.e[j].dl, ue.kind, ue.goff + dr * ue.gs,
-                                     ue.voff + dr * ue.vs, ue.a0, ue.a1, own, col));
+                    acc = add_r(acc, edge_term(T, cl, (d.lflags & (TF_SRC_LDS << j)) != 0, 0u, ue.kind, ue.goff + dr * ue.gs,
+                                     ue.voff + dr * ue.vs, ue.a0, ue.a1, own, col, true));
                 }
             }
         } else {
@@ -1165,7 +1165,7 @@ extern __shared__ __align__(16) float dyn_lds[];   // sized per launch: GEMM red
 // LEAN: the launch holds component-wise work only; this instantiation carries no GEMM or
 // reduction code, needs half the registers and keeps twice the waves per CU.
 template <bool LEAN>
-__global__ __launch_bounds__(WG, LEAN ? 6 : 4) void k_fwd_step(u32 work_lo, u32 work_hi, u32 tile_lo, u32 run_len,
+__global__ __launch_bounds__(WG, LEAN ? 6 : 3) void k_fwd_step(u32 work_lo, u32 work_hi, u32 tile_lo, u32 run_len,
                                                                 const TileDesc *tiles_f, const WorkRec *works_f, Tables T)
 {
     // the leading arguments arrive in scalar registers with the wave (so the descriptor loads start
@@ -1228,6 +1228,11 @@ __global__ __launch_bounds__(BWD_THREADS, 4) void k_bwd_step(u32 work_lo, u32 wo
         WorkRec wr;
         if (run_len) { wr.first = tile_lo + (w - work_lo) * run_len; wr.len = run_len; }
         else { wr = works_a[w]; wr.first = sreg(wr.first); wr.len = sreg(wr.len); }
+        if (wr.len == 1) {
+            const PullDesc d = tiles_a[wr.first];
+            pull_tile(T, d, (lds_float *)lds, threadIdx.x, BWD_THREADS);
+            continue;
+        }
         for (u32 c0 = 0; c0 < wr.len; c0 += RUN_STAGE) {
             const u32 cn = wr.len - c0 < RUN_STAGE ? wr.len - c0 : RUN_STAGE;
             __syncthreads();
@@ -1239,7 +1244,7 @@ __global__ __launch_bounds__(BWD_THREADS, 4) void k_bwd_step(u32 work_lo, u32 wo
             // levels find them in the cache instead of each waiting for memory in turn.  Nothing waits
             // for these loads themselves: their sum is taken when the run is over.
             float early[4] = {0.f, 0.f, 0.f, 0.f};
-            if (cn > 1) {
+            if (LEAN) {   // (runs are rare in launches that also hold GEMM tiles, and that instantiation has no registers to spare)
 #pragma unroll
                 for (u32 h = 0; h < 2; ++h) {
                     const u32 x = threadIdx.x + h * BWD_THREADS;
@@ -1275,11 +1280,13 @@ __global__ __launch_bounds__(BWD_THREADS, 4) void k_bwd_step(u32 work_lo, u32 wo
                 if (part < parts) {
                     for (u32 t = i + tw; t < next; t += BWD_THREADS / 64) {
                         const PullDesc &d = sdesc[t];
-                        uint4 q[12];
+                        if (LEAN) {   // (the instantiation with the GEMM tiles has no registers to spare for the short routine)
+                            uint4 q[12];
 #pragma unroll
-                        for (u32 k = 0; k < 12; ++k) q[k] = lds_q(d, k);
-                        if (sreg(q[10].z) & 4u) pull_tile_uni4(T, q, (lds_float *)lds, part * 64u + lane, parts * 64u);
-                        else pull_tile(T, d, (lds_float *)lds, part * 64u + lane, parts * 64u);
+                            for (u32 k = 0; k < 12; ++k) q[k] = lds_q(d, k);
+                            if (sreg(q[10].z) & 4u) { pull_tile_uni4(T, q, (lds_float *)lds, part * 64u + lane, parts * 64u); continue; }
+                        }
+                        pull_tile(T, d, (lds_float *)lds, part * 64u + lane, parts * 64u);
                     }
                 }
                 i = next;

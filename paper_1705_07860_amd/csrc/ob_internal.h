@@ -139,9 +139,9 @@ struct PullDesc {
     u32 lds_out, dshift;             // LDS index of the own rows = gradient-arena offset + lds_out; dshift: log2(d), or PULL_NO_SHIFT
     u32 own0, rowstep;               // val_off + row0 * d and rstride * d: the tile's i-th row starts at own0 + i * rowstep
 };
-// With bit 2 of vec4 set the edges are stored resolved for the short routine: goff already has the slice's
-// lower bound subtracted (EK_RANGE) and, for a consumer read from the run's LDS copy, dl added, so the
-// routine's index of column c of the tile's i-th row is goff + i * gs + c in either memory.
+// Uniform edges (n_uni != PULL_GENERIC) are stored resolved: goff already has the slice's lower bound
+// subtracted (EK_RANGE) and, for a consumer read from the run's LDS copy, dl added, so the index of column c
+// of the tile's i-th row is goff + i * gs + c in either memory.
 static_assert(sizeof(PullDesc) == 192, "PullDesc must be 192 bytes");
 
 // A launch chain: batches that run in the same launch slot.  A fused chain holds component-wise

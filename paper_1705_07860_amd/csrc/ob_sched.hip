@@ -1312,10 +1312,10 @@ __device__ inline void fill_pull_desc(const Tables &T, const BatchRec &r, u32 ro
     }
 }
 
-// Tiles for the short routine carry their edges resolved (see PullDesc).
+// Tiles with uniform edges carry them resolved (see PullDesc).
 __device__ inline void resolve_pull_desc(PullDesc &d)
 {
-    if (!(d.vec4 & 4u)) return;
+    if (d.n_uni == PULL_GENERIC) return;
     for (u32 j = 0; j < d.n_uni; ++j) {
         if (d.e[j].kind == EK_RANGE) d.e[j].goff -= (u32)d.e[j].a0;
         if (d.lflags & (TF_SRC_LDS << j)) d.e[j].goff += d.e[j].dl;
