@@ -235,6 +235,8 @@ def measure(args, ob, torch, name, steps, warmup, sustain_s, cpu_s, headline):
         for j in sorted(biggest):      # most nodes, most operand references, largest input payload
             c.graph_new()
             c.add_bulk(graphs[j])
+            if labels is not None:
+                c.set_manual_batches(labels[j])
             c.schedule(graphs[j].root)
     torch.cuda.synchronize()
 
