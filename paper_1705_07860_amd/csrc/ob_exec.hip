@@ -980,6 +980,33 @@ __device__ inline float4 edge_term4(const Tables &T, const lds_float *cl, bool f
     }
 }
 
+// four consecutive floats at an index that need not be a multiple of four
+__device__ inline float4 ldu4(const float *base, u32 idx)
+{
+    if ((idx & 3u) == 0u) return ld4(base + idx);
+    return make_float4(base[idx], base[idx + 1], base[idx + 2], base[idx + 3]);
+}
+
+// Columns col .. col + 3 of one consumer edge as it stands in the edge list (nothing resolved, any alignment):
+// the arithmetic of edge_term, four columns at a time.
+__device__ inline float4 edge_term4_any(const Tables &T, const EdgeRec &er, u32 own, u32 col)
+{
+    switch (er.kind) {
+    case EK_PLAIN: return ldu4(T.G, er.goff + col);
+    case EK_MUL:
+    case EK_DTANH:
+    case EK_DSIGM: {
+        const float4 g = ldu4(T.G, er.goff + col), f = edge_factor4(er.kind, ldu4(T.V, er.voff + col));
+        return make_float4(mul_r(g.x, f.x), mul_r(g.y, f.y), mul_r(g.z, f.z), mul_r(g.w, f.w));
+    }
+    default:   // a slice's range may cut the four columns, a label is one of them: column by column
+        return make_float4(edge_term(T, nullptr, false, 0u, er.kind, er.goff, er.voff, er.a0, er.a1, own, col),
+                           edge_term(T, nullptr, false, 0u, er.kind, er.goff, er.voff, er.a0, er.a1, own, col + 1u),
+                           edge_term(T, nullptr, false, 0u, er.kind, er.goff, er.voff, er.a0, er.a1, own, col + 2u),
+                           edge_term(T, nullptr, false, 0u, er.kind, er.goff, er.voff, er.a0, er.a1, own, col + 3u));
+    }
+}
+
 __device__ inline void pull_tile(const Tables &T, const PullDesc &d, lds_float *cl, u32 tid, u32 nthr)
 {
     const u32 total = d.nrows * d.d;
@@ -1003,6 +1030,30 @@ __device__ inline void pull_tile(const Tables &T, const PullDesc &d, lds_float *
             }
             st4(T.G + own + col, acc);
             if (keep) lds_st4(cl + (u32)(own + col + d.lds_out), acc);
+        }
+        return;
+    }
+    if (d.n_uni == PULL_GENERIC && (d.d & 3u) == 0u) {
+        // rows whose consumer edges differ, four columns per thread: what is looked up per row (the node, its
+        // edge range, the edge records) is looked up once for four columns, and the columns come as float4
+        for (u32 x = tid * 4; x < total; x += nthr * 4) {
+            const u32 dr = x / d.d, col = x % d.d, row = d.row0 + dr * d.rstride;
+            const u32 own = d.val_off + row * d.d;
+            float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);        // (a root has one column, never here)
+            if (T.Gx) acc = ld4(T.Gx + own + col);
+            const u32 u = T.order[d.pos0 + row];
+            const u32 ownv = (d.vec4 & 2u) ? T.val_off[u] : own;
+            const u32 q1 = T.succ_off[u + 1];
+            for (u32 q = T.succ_off[u]; q < q1; ++q) {
+                const EdgeRec er = T.edges[q];
+                const float4 t = edge_term4_any(T, er, ownv, col);
+                acc.x = add_r(acc.x, t.x); acc.y = add_r(acc.y, t.y); acc.z = add_r(acc.z, t.z); acc.w = add_r(acc.w, t.w);
+            }
+            st4(T.G + own + col, acc);
+            if (keep) {
+                lds_float *o = cl + (u32)(own + col + d.lds_out);
+                o[0] = acc.x; o[1] = acc.y; o[2] = acc.z; o[3] = acc.w;
+            }
         }
         return;
     }
