@@ -744,7 +744,7 @@ def test_odd_dimensions_duplicate_lookups_and_wide_sum():
     c.close()
 
 
-@pytest.mark.parametrize("dims", [(50, 70, 300), (64, 128, 523), (40, 132, 300)])
+@pytest.mark.parametrize("dims", [(50, 70, 300), (64, 128, 523), (40, 132, 300), (96, 200, 400)])
 def test_large_batches_of_matrix_products(dims):
     """Matrix-product batches with hundreds of rows (the wide forward tiles): ragged rows and
     columns, a contraction length that is not a multiple of 4 in the first case, operands that are
