@@ -466,6 +466,46 @@ def test_backward_from_a_one_row_matrix_product_with_one_consumer():
     c.close()
 
 
+def test_rows_with_differing_consumers_four_columns_at_a_time():
+    """Batches whose rows have different consumer edges (so no tile of them is uniform) and whose width is a
+    multiple of 4 take the backward routine that works four columns per thread straight from the edge list:
+    slices at bounds that are not multiples of 4 (a range may cut the four columns), views as operands of
+    tanh / sigmoid / products, labels among the four columns, fan-out that differs from row to row."""
+    from paper_1705_07860_amd import binding as ob
+    rng = np.random.default_rng(77)
+    pb = wl.ParamBuilder(rng, std=0.4)
+    W = pb.add("W", 8, 12)
+    E = pb.add("E", 11, 12)
+    p = pb.done()
+    gb = wl.GraphBuilder(p)
+    losses = []
+    for i in range(23):
+        x = gb.lookup(E, i % 11) if i % 3 else gb.input(rng.standard_normal(12))      # 12 wide
+        s = gb.slice(x, 3, 11)                          # 8 wide, bounds not multiples of 4
+        t = gb.tanh(s)
+        parts = [gb.sqnorm(t)]
+        if i % 2:
+            parts.append(gb.sqnorm(gb.cmult(gb.sigmoid(s), t)))     # one more consumer of s and of t on odd rows
+        if i % 3 == 0:
+            parts.append(gb.pick_nls(s, i % 8))                      # a label among s's columns
+        if i % 4 == 1:
+            parts.append(gb.sqnorm(gb.slice(x, 0, 4)))               # another range of the same row
+        y = gb.matvec(W, -1, x)                         # 8 wide
+        if i % 5:
+            parts.append(gb.pick_nls(y, i % 8))
+        if i % 2 == 0:
+            parts.append(gb.sqnorm(gb.add((y, s))))
+        losses += parts
+    g = gb.finish(gb.add(losses), 23)
+    o = Oracle(g, p, "f64")
+    o.forward()
+    o.backward(g.root)
+    for mode, fuse in ((ob.OB_BYDEPTH, 2), (ob.OB_BYDEPTH, 0), (ob.OB_BYAGENDA, 2)):
+        c, root_ = run_gpu(p, g, mode, fuse=fuse, arena=128 << 20)
+        check_against_oracle(c, p, g, o, root_, what=f"differing consumers/{mode}/fuse {fuse}")
+        c.close()
+
+
 @pytest.mark.parametrize("mode", ["depth", "agenda", "nobatch"])
 def test_slices_are_views_of_their_operand_rows(mode):
     """SLICE nodes are never copied: readers are pointed at the range of the operand's row.  Covers
