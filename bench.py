@@ -143,8 +143,19 @@ def measure(args, ob, torch, name, steps, warmup, sustain_s, cpu_s, headline):
     pipeline = not args.no_pipeline
     lookahead = args.lookahead if args.lookahead > 0 else (2 if args.mode == "agenda" else 1)
     pool = max(args.pool, lookahead + 3)
-    stream = torch.cuda.Stream()
-    sched_streams = [torch.cuda.Stream() for _ in range(lookahead)]
+    # With pipelining the schedule streams and the execution stream get disjoint compute units: scheduling
+    # kernels that share units with the latency-bound execution launches slow those by about a tenth.
+    raw_streams = []
+    n_cu = torch.cuda.get_device_properties(0).multi_processor_count
+    if pipeline and 0 < args.cu_split < n_cu:
+        def on_cus(first, count):
+            raw_streams.append(ob.stream_create_on_cus(first, count))
+            return torch.cuda.ExternalStream(raw_streams[-1])
+        stream = on_cus(args.cu_split, n_cu - args.cu_split)
+        sched_streams = [on_cus(0, args.cu_split) for _ in range(lookahead)]
+    else:
+        stream = torch.cuda.Stream()
+        sched_streams = [torch.cuda.Stream() for _ in range(lookahead)]
     ctxs = []
     for j in range(pool):
         if j == 0:
@@ -460,6 +471,9 @@ def measure(args, ob, torch, name, steps, warmup, sustain_s, cpu_s, headline):
     for c in ctxs[1:]:
         c.close()
     ctxs[0].close()
+    torch.cuda.synchronize()
+    for h in raw_streams:
+        ob.stream_destroy(h)
     return out
 
 
@@ -472,6 +486,9 @@ def main():
                     help="all (default): the five listed configurations, config 3 as the headline; or one workload alone")
     ap.add_argument("--other-steps", type=int, default=20, help="timed steps of the four non-headline configurations")
     ap.add_argument("--pool", type=int, default=8, help="contexts in the ring (a context is reused every `pool` steps)")
+    ap.add_argument("--cu-split", type=int, default=32, metavar="N",
+                    help="with pipelining: the schedule streams run on compute units [0, N), the execution stream on the "
+                         "rest (0: ordinary streams, every kernel anywhere on the chip)")
     ap.add_argument("--instances", type=int, default=None,
                     help="instances per minibatch (default: the configuration's own count; other values are sweep "
                          "points, not the headline workload)")
@@ -553,6 +570,8 @@ def main():
                    "pipeline": (f"hand-over and scheduling of steps i+1..i+{lookahead} overlap the execution of step i "
                                 f"({lookahead} schedule stream{'s' if lookahead > 1 else ''})") if not args.no_pipeline
                    else "none (hand-over, schedule, forward, backward back to back)",
+                   "compute_units": (f"schedule streams on units [0, {args.cu_split}), execution stream on the other units"
+                                     if (not args.no_pipeline and args.cu_split > 0) else "every stream on the whole chip"),
                    "timed_region": head["timed_region"],
                    "nodes_per_step": head["nodes_per_step"]},
     }

@@ -93,6 +93,15 @@ int ob_ctx_destroy(ob_ctx *ctx);
 /* Upload and scheduling go to this stream instead of the context's stream; execution waits for
  * them through an event.  Call before the first upload. */
 int ob_ctx_set_schedule_stream(ob_ctx *ctx, void *hip_stream);
+/* A HIP stream whose kernels run on the compute units [first_cu, first_cu + n_cus) only (the device's units
+ * are numbered 0 .. count - 1 in the order of hipExtStreamCreateWithCUMask's bit mask), at the default
+ * priority.  For callers that give the schedule stream and the execution stream disjoint parts of the chip:
+ * scheduling kernels that share compute units with the latency-bound execution launches slow those by about a
+ * tenth, on parts of their own they do not.  The stream belongs to the caller (any context may use it, as its
+ * stream or its schedule stream) and is released with ob_stream_destroy once no context uses it and its work
+ * is done.  OB_E_ARG: empty range or one beyond the device's units; OB_E_HIP: the runtime refused. */
+int ob_stream_create_on_cus(int first_cu, int n_cus, void **hip_stream_out);
+int ob_stream_destroy(void *hip_stream);
 int ob_ctx_set_mode(ob_ctx *ctx, int mode);
 int ob_ctx_set_launch(ob_ctx *ctx, int launch);
 /* Launch fusion (default 2; every batching mode): component-wise batches whose operands are

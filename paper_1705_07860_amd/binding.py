@@ -110,6 +110,8 @@ def lib():
             "ob_param_sgd_step": (i, [vp, c_float, i]),
             "ob_test_sort": (i, [vp, sz, vp, vp, i, i, vp, vp]),
             "ob_sort_pairs_noalloc": (i, [vp, sz, vp, vp, i, i]),
+            "ob_stream_create_on_cus": (i, [i, i, POINTER(vp)]),
+            "ob_stream_destroy": (i, [vp]),
             "ob_test_scan": (i, [vp, sz, vp, vp, vp]),
             "ob_test_gemm": (i, [vp, i, i, i, vp, vp, vp]),
             "ob_test_launch_cost": (i, [vp, i, i, POINTER(c_float)]),
@@ -134,6 +136,23 @@ def sort_pairs_noalloc(stream_ptr, n: int, keys_ptr: int, vals_ptr: int, lo_bit:
     """ob_sort_pairs_noalloc on raw device pointers (allocates nothing); raises ObError on failure."""
     L = lib()
     rc = L.ob_sort_pairs_noalloc(c_void_p(stream_ptr), n, c_void_p(keys_ptr), c_void_p(vals_ptr), lo_bit, n_bits)
+    if rc < 0:
+        raise ObError(rc, (L.ob_last_error(None) or b"").decode())
+
+
+def stream_create_on_cus(first_cu: int, n_cus: int) -> int:
+    """ob_stream_create_on_cus: the raw hipStream_t (wrap it with torch.cuda.ExternalStream to record events on it)."""
+    L = lib()
+    h = c_void_p()
+    rc = L.ob_stream_create_on_cus(first_cu, n_cus, ctypes.byref(h))
+    if rc < 0:
+        raise ObError(rc, (L.ob_last_error(None) or b"").decode())
+    return h.value
+
+
+def stream_destroy(stream_ptr: int):
+    L = lib()
+    rc = L.ob_stream_destroy(c_void_p(stream_ptr))
     if rc < 0:
         raise ObError(rc, (L.ob_last_error(None) or b"").decode())
 

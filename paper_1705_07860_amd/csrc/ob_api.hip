@@ -179,6 +179,33 @@ int ob_ctx_set_schedule_stream(ob_ctx *ctx, void *hip_stream)
     return OB_OK;
 }
 
+int ob_stream_create_on_cus(int first_cu, int n_cus, void **hip_stream_out)
+{
+    if (!hip_stream_out) return ctx_fail(nullptr, OB_E_ARG, "ob_stream_create_on_cus: no place for the stream");
+    *hip_stream_out = nullptr;
+    int dev = 0, count = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e == hipSuccess) e = hipDeviceGetAttribute(&count, hipDeviceAttributeMultiprocessorCount, dev);
+    if (e != hipSuccess) return ctx_fail(nullptr, OB_E_HIP, "ob_stream_create_on_cus: %s", hipGetErrorString(e));
+    if (first_cu < 0 || n_cus <= 0 || first_cu + n_cus > count)
+        return ctx_fail(nullptr, OB_E_ARG, "ob_stream_create_on_cus: units [%d, %d) of a device with %d", first_cu, first_cu + n_cus, count);
+    std::vector<uint32_t> mask((size_t)(count + 31) / 32, 0u);
+    for (int b = first_cu; b < first_cu + n_cus; ++b) mask[(size_t)b / 32] |= 1u << (b % 32);
+    hipStream_t s = nullptr;
+    e = hipExtStreamCreateWithCUMask(&s, (uint32_t)mask.size(), mask.data());
+    if (e != hipSuccess) return ctx_fail(nullptr, OB_E_HIP, "hipExtStreamCreateWithCUMask: %s", hipGetErrorString(e));
+    *hip_stream_out = (void *)s;
+    return OB_OK;
+}
+
+int ob_stream_destroy(void *hip_stream)
+{
+    if (!hip_stream) return OB_OK;
+    const hipError_t e = hipStreamDestroy((hipStream_t)hip_stream);
+    if (e != hipSuccess) return ctx_fail(nullptr, OB_E_HIP, "hipStreamDestroy: %s", hipGetErrorString(e));
+    return OB_OK;
+}
+
 int ob_ctx_set_fusion(ob_ctx *ctx, int on)
 {
     CHECK_CTX(ctx);

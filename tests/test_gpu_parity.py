@@ -833,10 +833,12 @@ def test_parameter_gradients_accumulate_until_zeroed(workload_cache):
     c.close()
 
 
-def test_forked_contexts_share_parameters_and_pipeline_scheduling():
+@pytest.mark.parametrize("streams", ["whole chip", "disjoint compute units"])
+def test_forked_contexts_share_parameters_and_pipeline_scheduling(streams):
     """Two graphs in flight: a forked context schedules its graph on a second stream while the
     first one executes; both share one parameter set, and the accumulated parameter gradient is
-    the sum of the two minibatches' gradients."""
+    the sum of the two minibatches' gradients.  Second case: the streams come from
+    ob_stream_create_on_cus, scheduling on compute units [0, 32), execution on the rest."""
     import torch
     from paper_1705_07860_amd import binding as ob
     p = wl.tagger_params()
@@ -847,7 +849,16 @@ def test_forked_contexts_share_parameters_and_pipeline_scheduling():
         o.forward()
         o.backward(g.root)
         os_.append(o)
-    ex, sc = torch.cuda.Stream(), torch.cuda.Stream()
+    raw = []
+    if streams == "whole chip":
+        ex, sc = torch.cuda.Stream(), torch.cuda.Stream()
+    else:
+        n_cu = torch.cuda.get_device_properties(0).multi_processor_count
+        with pytest.raises(ob.ObError) as e:
+            ob.stream_create_on_cus(n_cu - 8, 16)          # reaches beyond the device's units
+        assert e.value.code == -8
+        raw = [ob.stream_create_on_cus(32, n_cu - 32), ob.stream_create_on_cus(0, 32)]
+        ex, sc = torch.cuda.ExternalStream(raw[0]), torch.cuda.ExternalStream(raw[1])
     a = ob.Context(arena_bytes=256 << 20, stream=ex, sched_stream=sc)
     a.params_create(p)
     a.param_grad_zero()
@@ -887,6 +898,9 @@ def test_forked_contexts_share_parameters_and_pipeline_scheduling():
         assert rel_err(a.param_grad_read(pid, m.shape), ref) <= TOL, p.names[pid]
     b.close()
     a.close()
+    torch.cuda.synchronize()
+    for h in raw:
+        ob.stream_destroy(h)
 
 
 def test_stacked_matrix_products():
