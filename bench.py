@@ -147,13 +147,15 @@ def measure(args, ob, torch, name, steps, warmup, sustain_s, cpu_s, headline):
     # kernels that share units with the latency-bound execution launches slow those by about a tenth.
     raw_streams = []
     n_cu = torch.cuda.get_device_properties(0).multi_processor_count
-    if pipeline and 0 < args.cu_split < n_cu:
+    cu_split = args.cu_split if args.cu_split >= 0 else (32 if max(g.n for g in graphs) <= 300000 else 0)
+    if pipeline and 0 < cu_split < n_cu:
         def on_cus(first, count):
             raw_streams.append(ob.stream_create_on_cus(first, count))
             return torch.cuda.ExternalStream(raw_streams[-1])
-        stream = on_cus(args.cu_split, n_cu - args.cu_split)
-        sched_streams = [on_cus(0, args.cu_split) for _ in range(lookahead)]
+        stream = on_cus(cu_split, n_cu - cu_split)
+        sched_streams = [on_cus(0, cu_split) for _ in range(lookahead)]
     else:
+        cu_split = 0
         stream = torch.cuda.Stream()
         sched_streams = [torch.cuda.Stream() for _ in range(lookahead)]
     ctxs = []
@@ -467,6 +469,7 @@ def measure(args, ob, torch, name, steps, warmup, sustain_s, cpu_s, headline):
                                    sample=f"{ns} of the run's minibatches ({inst} instances, {dt:.1f} s): fp32 build of the "
                                           f"node-at-a-time interpreter, forward+backward, 1 thread of {os.cpu_count()} host cores")
     out["paper_context"] = PAPER_CONTEXT.get(name)
+    out["cu_split"] = cu_split
     gc.enable()
     for c in ctxs[1:]:
         c.close()
@@ -486,9 +489,10 @@ def main():
                     help="all (default): the five listed configurations, config 3 as the headline; or one workload alone")
     ap.add_argument("--other-steps", type=int, default=20, help="timed steps of the four non-headline configurations")
     ap.add_argument("--pool", type=int, default=8, help="contexts in the ring (a context is reused every `pool` steps)")
-    ap.add_argument("--cu-split", type=int, default=32, metavar="N",
+    ap.add_argument("--cu-split", type=int, default=-1, metavar="N",
                     help="with pipelining: the schedule streams run on compute units [0, N), the execution stream on the "
-                         "rest (0: ordinary streams, every kernel anywhere on the chip)")
+                         "rest (0: ordinary streams, every kernel anywhere on the chip; default: 32 for minibatches of "
+                         "up to 300 000 nodes, whose scheduling on 32 units still hides behind their execution, else 0)")
     ap.add_argument("--instances", type=int, default=None,
                     help="instances per minibatch (default: the configuration's own count; other values are sweep "
                          "points, not the headline workload)")
@@ -570,8 +574,8 @@ def main():
                    "pipeline": (f"hand-over and scheduling of steps i+1..i+{lookahead} overlap the execution of step i "
                                 f"({lookahead} schedule stream{'s' if lookahead > 1 else ''})") if not args.no_pipeline
                    else "none (hand-over, schedule, forward, backward back to back)",
-                   "compute_units": (f"schedule streams on units [0, {args.cu_split}), execution stream on the other units"
-                                     if (not args.no_pipeline and args.cu_split > 0) else "every stream on the whole chip"),
+                   "compute_units": (f"schedule streams on units [0, {head['cu_split']}), execution stream on the other units"
+                                     if head["cu_split"] > 0 else "every stream on the whole chip"),
                    "timed_region": head["timed_region"],
                    "nodes_per_step": head["nodes_per_step"]},
     }
