@@ -176,6 +176,9 @@ def test_values_and_gradients_by_depth(name, workload_cache):
     st = c.stats()
     say(f"  sched {st['ms_schedule']:.3f} ms fwd {st['ms_forward']:.3f} ms bwd {st['ms_backward']:.3f} ms "
         f"(param grads {st['ms_param_grads']:.3f}) launches fwd={st['n_launch_fwd']} bwd={st['n_launch_bwd']}")
+    # the backward step kernel alone: everything but the root kernel and the (at most three) deferred parameter kernels
+    assert 0 < st["n_launch_bwd_steps"] <= st["n_launch_bwd"] - 2 and st["n_launch_bwd"] - st["n_launch_bwd_steps"] <= 4
+    assert st["n_depth_retries"] == 0
     c.close()
 
 
