@@ -1194,6 +1194,72 @@ def test_manual_batching_on_random_dags(seed):
     check_manual(p, g, o, np.arange(g.n, dtype=np.int32), f"dag {seed} singletons", arena=64 << 20).close()
 
 
+def test_headline_loop_as_benchmarked(workload_cache):
+    """The loop bench.py times by default, on the headline configuration (config 3, full size): a ring of
+    contexts forked from one parameter set; every step hands a minibatch over anew (ob_graph_new,
+    ob_add_bulk, upload and scheduling on the schedule stream, queued one step ahead of the execution),
+    the schedule stream confined to compute units [0, 32) and the execution stream to the others.  The
+    minibatches differ in size, so a context's graph store and tables are reused for graphs larger and
+    smaller than the ones before.  After the loop every context's values and node gradients, and the
+    parameter gradients of the last step, match the oracle and the schedule is the reference one."""
+    import torch
+    from paper_1705_07860_amd import binding as ob
+    p, g0, o0 = workload_cache("tagger_char")
+    cfg = wl.CONFIGS["tagger_char"]
+    graphs = [g0] + [cfg["batch"](p, j) for j in (1, 2)]
+    oracles = [o0]
+    for g in graphs[1:]:
+        o = Oracle(g, p, "f64")
+        o.forward()
+        o.backward(g.root)
+        oracles.append(o)
+    n_cu = torch.cuda.get_device_properties(0).multi_processor_count
+    raw = [ob.stream_create_on_cus(32, n_cu - 32), ob.stream_create_on_cus(0, 32)]
+    ex, sc = torch.cuda.ExternalStream(raw[0]), torch.cuda.ExternalStream(raw[1])
+    pool, steps = 4, 9                      # step i runs graph i % 3 in context i % 4
+    ctxs = []
+    for j in range(pool):
+        if j == 0:
+            c = ob.Context(arena_bytes=1 << 30, stream=ex, sched_stream=sc)
+            c.params_create(p)
+            c.param_grad_zero()
+        else:
+            c = ctxs[0].fork(arena_bytes=1 << 30, stream=ex, sched_stream=sc)
+        ctxs.append(c)
+
+    def hand_over(i):
+        c = ctxs[i % pool]
+        c.graph_new()
+        c.add_bulk(graphs[i % 3])
+        c.schedule_async(graphs[i % 3].root)
+
+    hand_over(0)
+    for i in range(steps):
+        if i + 1 < steps:
+            hand_over(i + 1)
+        c, g = ctxs[i % pool], graphs[i % 3]
+        c.param_grad_zero()
+        c.forward(g.root)
+        c.backward(g.root)
+    for i in range(steps - pool, steps):    # the last step of every context
+        c, g, o = ctxs[i % pool], graphs[i % 3], oracles[i % 3]
+        total = int(o.v_off[-1])
+        assert segment_rel_err(c.all_read(0, total), o.val[:total], o.v_off) <= TOL
+        assert segment_rel_err(c.all_read(1, total), o.grad[:total], o.v_off) <= TOL
+        bo, ids, bd, _ = c.schedule_read()
+        rbo, rids, rbd = S.by_depth(g)
+        assert np.array_equal(bo, rbo) and np.array_equal(ids, rids) and np.array_equal(bd, rbd)
+        assert c.stats()["n_depth_retries"] == 0
+    last = oracles[(steps - 1) % 3]
+    for pid, m in enumerate(p.mats):
+        assert rel_err(ctxs[0].param_grad_read(pid, m.shape), last.param_grad(pid)) <= TOL, p.names[pid]
+    for c in reversed(ctxs):
+        c.close()
+    torch.cuda.synchronize()
+    for h in raw:
+        ob.stream_destroy(h)
+
+
 @pytest.mark.parametrize("mode,lookahead", [("depth", 1), ("agenda", 2)])
 def test_full_size_pipelined_loop_as_benchmarked(workload_cache, mode, lookahead):
     """The loop bench.py times, at the tagger's full size: contexts forked from one parameter set,
