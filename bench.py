@@ -339,6 +339,12 @@ def measure(args, ob, torch, name, steps, warmup, sustain_s, cpu_s, headline):
         "phases_cover": f"the last {cover} timed steps",
         "depth_levels": st["n_steps"], "launch_slots": st["n_slots"], "batches": st["n_batches"],
         "batch_size_histogram": batch_hist,
+        # Section 3.3: batches of the last step whose rows the forward pass never writes (SLICE batches are views of their
+        # operand rows; CONCAT batches that only matrix products read are read in pieces where the pieces lie)
+        "copy_elision": {"slice_view_batches": st["n_view_batches"], "slice_view_tiles": int(-(-st["view_floats"] // 1024)),
+                         "concat_uncopied_batches": st["n_uncopied_batches"],
+                         "concat_uncopied_tiles": int(-(-st["uncopied_floats"] // 1024)),
+                         "forward_bytes_saved": int(8 * (st["view_floats"] + st["uncopied_floats"]))},
         "host_generation_ms_per_minibatch": round(t_gen * 1e3, 2),
         "roofline": roofline,
     }

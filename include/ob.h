@@ -239,6 +239,11 @@ typedef struct ob_stats {
                               * because a range of the partitioned pass ran into the bound on its wait */
     int32_t n_launch_bwd_steps; /* launches of the backward step kernel alone (n_launch_bwd also counts the kernel that
                                  * places the root and the deferred parameter-gradient kernels) */
+    int32_t n_view_batches;     /* SLICE batches: views, nothing is copied forward (Section 3.3) */
+    int32_t n_uncopied_batches; /* CONCAT batches that only matrix products read: the products read the pieces where
+                                 * they lie and the forward pass writes nothing for the batch (Section 3.3); their rows are
+                                 * filled in when a value is read */
+    uint64_t view_floats, uncopied_floats; /* elements of those batches (forward bytes saved: 8 per element) */
 } ob_stats;
 int ob_stats_read(ob_ctx *ctx, ob_stats *out);
 
@@ -255,10 +260,13 @@ int ob_stats_read(ob_ctx *ctx, ob_stats *out);
 #define OB_DBG_CHAINS 8    /* launch chains, 12 words each: first, members, slot, fused, groups, groups per block, blocks, tiles per block, forward tiles per block, 3 reserved */
 #define OB_DBG_LORDER 9    /* u32 per batch: batch ids in launch order (the members of chain c are entries first .. first + members - 1) */
 int ob_debug_read(ob_ctx *ctx, int which, uint32_t *host_out, size_t cap_words, size_t *n_words);
-/* Internal knobs, for tests of the library's own error handling.  which: OB_DBG_SET_*; unknown: OB_E_ARG. */
+/* Internal knobs, for tests of the library's own error handling and of its alternative paths.  which: OB_DBG_SET_*;
+ * unknown: OB_E_ARG. */
 #define OB_DBG_SET_DEPTH_SPIN 0 /* idle polls a workgroup of the partitioned depth pass (Section 3.2) allows itself while it
                                  * waits for a lower id range, default 2^21; 0 makes every range that has to wait give up at
                                  * once, so that scheduling falls back to the single-workgroup pass (see n_depth_retries) */
+#define OB_DBG_SET_CONCAT_COPY 1 /* nonzero: every CONCAT batch is copied by the forward pass from the next schedule on
+                                  * (default 0: batches that only matrix products read stay uncopied, see ob_stats) */
 int ob_debug_set(ob_ctx *ctx, int which, uint64_t value);
 
 /* Stand-alone device primitives, exposed so that tests can check them directly.  All

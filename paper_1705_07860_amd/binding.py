@@ -23,6 +23,7 @@ OB_LAUNCH_STREAM, OB_LAUNCH_GRAPH, OB_LAUNCH_PERSISTENT = 0, 1, 2
 OB_DBG_DEPTH, OB_DBG_SIG, OB_DBG_SUCC_OFF, OB_DBG_SUCC_EDGE, OB_DBG_ORDER, OB_DBG_VAL_OFF = range(6)
 OB_DBG_TILES_FWD, OB_DBG_TILES_PULL, OB_DBG_CHAINS, OB_DBG_LORDER = 6, 7, 8, 9
 OB_DBG_SET_DEPTH_SPIN = 0
+OB_DBG_SET_CONCAT_COPY = 1
 
 ERRORS = {0: "OB_OK", -1: "OB_E_BADID", -2: "OB_E_DIM", -3: "OB_E_RANGE", -4: "OB_E_NOTSCALAR",
           -5: "OB_E_OOM", -6: "OB_E_STATE", -7: "OB_E_HIP", -8: "OB_E_ARG"}
@@ -41,7 +42,9 @@ class ObStats(ctypes.Structure):
         [(n, c_uint64) for n in ("value_floats", "grad_floats", "arena_used_bytes", "upload_bytes")] + \
         [(n, c_float) for n in ("ms_upload", "ms_schedule", "ms_forward", "ms_backward", "ms_param_grads",
                                 "ms_graph_build")] + \
-        [(n, c_int32) for n in ("n_stages", "n_proxies", "n_depth_retries", "n_launch_bwd_steps")]
+        [(n, c_int32) for n in ("n_stages", "n_proxies", "n_depth_retries", "n_launch_bwd_steps",
+                                "n_view_batches", "n_uncopied_batches")] + \
+        [(n, c_uint64) for n in ("view_floats", "uncopied_floats")]
 
     def as_dict(self):
         return {n: getattr(self, n) for n, _ in self._fields_ if not n.startswith("reserved")}

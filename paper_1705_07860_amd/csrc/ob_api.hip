@@ -132,6 +132,7 @@ int ob_ctx_fork(ob_ctx *parent, void *arena_dev, size_t arena_bytes, void *hip_s
 }
 
 static void drop_stages(ob_ctx *ctx);
+static int fill_uncopied(ob_ctx *u, hipStream_t s);
 
 int ob_ctx_destroy(ob_ctx *ctx)
 {
@@ -373,6 +374,7 @@ int ob_graph_new(ob_ctx *ctx)
     ctx->image_stale = false;
     ctx->sum_out_dim = 0;
     ctx->max_arity = 0;
+    ctx->n_concat = 0;
     ctx->sum_mv_d32 = ctx->sum_mv_k32 = 0;
     ctx->top = ctx->persist_top;
     ctx->uploaded = false;
@@ -529,6 +531,7 @@ static int append_node(ob_ctx *ctx, int op, const u32 *ins, u32 arity, int param
     ctx->n_items_total += items;
     ctx->sum_out_dim += dim;
     if (arity > ctx->max_arity) ctx->max_arity = arity;
+    if (op == OB_OP_CONCAT) ++ctx->n_concat;
     if (op == OB_OP_MATVEC) note_matvec(ctx, param, bias);
     if (keep) ctx->image_stale = true; else ctx->uploaded = false;
     return (int)v;
@@ -654,7 +657,7 @@ int ob_add_bulk(ob_ctx *ctx, int n, const uint8_t *op, const uint32_t *out_dim, 
         u32 operator[](u32 u) const { return u < n0 ? old[u] : fresh[u - n0]; }
     } dims{ctx->out_dim.data(), n0, out_dim};
     struct Part {
-        ErrSink es; u64 sum_dim = 0, mv_d32 = 0, mv_k32 = 0; u32 max_ar = 0, items = 0;
+        ErrSink es; u64 sum_dim = 0, mv_d32 = 0, mv_k32 = 0; u32 max_ar = 0, items = 0, concats = 0;
         std::vector<u8> used_w, used_b;
     };
     const int n_parts = n >= 32768 ? 1 + BulkPool::HELPERS : 1;
@@ -692,6 +695,8 @@ int ob_add_bulk(ob_ctx *ctx, int n, const uint8_t *op, const uint32_t *out_dim, 
                 if (bias[i] >= 0) P.used_b[bias[i]] = 1;
             } else if (o == OB_OP_LOOKUP) {
                 P.items += 1u;
+            } else if (o == OB_OP_CONCAT) {
+                ++P.concats;
             }
         }
         // this range's share of the plain copies
@@ -721,6 +726,7 @@ int ob_add_bulk(ob_ctx *ctx, int n, const uint8_t *op, const uint32_t *out_dim, 
         ctx->sum_out_dim += P.sum_dim;
         if (P.max_ar > ctx->max_arity) ctx->max_arity = P.max_ar;
         ctx->n_items_total += P.items;
+        ctx->n_concat += P.concats;
         ctx->sum_mv_d32 += P.mv_d32; ctx->sum_mv_k32 += P.mv_k32;
         for (size_t q = 0; q < params.size(); ++q) {
             if (P.used_w[q] && !ctx->params_used_w[q]) { ctx->params_used_w[q] = 1; ctx->params_dirty = true; }
@@ -984,6 +990,7 @@ int ob_forward(ob_ctx *ctx, int node)
     if (int rc = exec_forward(ctx)) return rc;
     HIP_TRY(ctx, hipEventRecord(ctx->ev[3], ctx->stream));
     ctx->forward_done = true;
+    ctx->uncopied_filled = false;
     ctx->backward_done = false;
     return OB_OK;
 }
@@ -1154,6 +1161,7 @@ static int stage_forward(ob_ctx *ctx, u32 n0, u32 n1)
     ob_ctx *c = st.c;
     c->sched_stream = ctx->sched_stream;
     c->is_stage = true;
+    c->concat_views = ctx->concat_views;
     u32 *lists_dev = arena_array<u32>(c, (size_t)3 * P + 1);
     if (!lists_dev) return fail(ctx_fail(ctx, OB_E_OOM, "arena too small for another evaluation stage"));
     st.lists_dev = lists_dev;
@@ -1202,6 +1210,7 @@ static int stage_forward(ob_ctx *ctx, u32 n0, u32 n1)
         while (i < P && st.proxy[i] < hi) ++i;
         if (i == i0) continue;
         const Tables &OT = own ? own->c->T : ctx->T;
+        if (int frc = fill_uncopied(own ? own->c : ctx, ctx->stream)) { if (own) ctx->err = own->c->err; return fail(frc); }
         hipError_t e = exec_stage_fill(OT.V, OT.val_off, lists_dev + i0, lists_dev + P + i0, lists_dev + 2 * (size_t)P + i0,
                                        i - i0, payload_dev, ctx->stream);
         if (e != hipSuccess) return hip_fail(e, "copying earlier values");
@@ -1331,6 +1340,18 @@ int ob_sync(ob_ctx *ctx)
 
 // ---- reads ----------------------------------------------------------------------------------------
 
+// The forward pass leaves the rows of CONCAT batches that only matrix products read unwritten (the products
+// read the pieces in place).  Whoever reads values of evaluation unit u from outside the forward pass (a value
+// read, the leaves of a later evaluation stage) calls this first: the rows are written once, on stream s.
+static int fill_uncopied(ob_ctx *u, hipStream_t s)
+{
+    if (!u->forward_done || u->uncopied_filled || u->hdr.virt_batches == 0) return OB_OK;
+    hipError_t e = exec_fill_uncopied(u->T, s);
+    if (e != hipSuccess) return ctx_fail(u, OB_E_HIP, "filling in uncopied rows failed: %s", hipGetErrorString(e));
+    u->uncopied_filled = true;
+    return OB_OK;
+}
+
 static int node_read(ob_ctx *ctx, int node, float *out, size_t cap, bool grad)
 {
     if (!out) return ctx_fail(ctx, OB_E_ARG, "null output");
@@ -1346,6 +1367,7 @@ static int node_read(ob_ctx *ctx, int node, float *out, size_t cap, bool grad)
     }
     const u32 d = ctx->out_dim[node];
     if (cap < d) return ctx_fail(ctx, OB_E_RANGE, "buffer holds %zu of %u elements", cap, d);
+    if (!grad) if (int rc = fill_uncopied(ctx, ctx->stream)) return rc;
     u32 off = 0;
     HIP_TRY(ctx, hipMemcpyAsync(&off, (grad ? ctx->T.nat_off : ctx->T.val_off) + node, 4, hipMemcpyDeviceToHost, ctx->stream));
     HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
@@ -1396,6 +1418,7 @@ int ob_all_read(ob_ctx *ctx, int which, float *host_out, size_t cap)
         for (u32 l = P; l < nl; ++l) loc[l] = off[n0 + (l - P)];
         u32 *off_dev = arena_array<u32>(last, (size_t)nl + 1);
         if (!off_dev) { dst = nullptr; break; }
+        if (!which && fill_uncopied(u, ctx->stream)) { rc = ctx_fail(ctx, OB_E_HIP, "%s", u->err.c_str()); break; }
         hipError_t e = hipMemcpyAsync(off_dev, loc.data(), (size_t)nl * 4, hipMemcpyHostToDevice, ctx->stream);
         if (e == hipSuccess) e = exec_gather_some(u->T, which, dst, off_dev, ctx->stream);
         if (e != hipSuccess) rc = ctx_fail(ctx, OB_E_HIP, "read-back failed: %s", hipGetErrorString(e));
@@ -1489,6 +1512,10 @@ int ob_stats_read(ob_ctx *ctx, ob_stats *out)
     out->ms_graph_build = ctx->ms_graph;
     out->n_depth_retries = ctx->n_depth_retries;
     out->n_launch_bwd_steps = ctx->n_launch_bwd_steps;
+    out->n_view_batches = (int32_t)ctx->hdr.view_batches;
+    out->n_uncopied_batches = (int32_t)ctx->hdr.virt_batches;
+    out->view_floats = ctx->hdr.view_floats;
+    out->uncopied_floats = ctx->hdr.virt_floats;
     (void)hipGetLastError();
     return OB_OK;
 }
@@ -1499,6 +1526,9 @@ int ob_debug_set(ob_ctx *ctx, int which, uint64_t value)
     switch (which) {
     case OB_DBG_SET_DEPTH_SPIN:
         ctx->depth_spin_limit = value > 0xffffffffull ? 0xffffffffu : (u32)value;
+        return OB_OK;
+    case OB_DBG_SET_CONCAT_COPY:
+        ctx->concat_views = value == 0;
         return OB_OK;
     default:
         return ctx_fail(ctx, OB_E_ARG, "unknown knob %d", which);
@@ -1603,6 +1633,7 @@ int ob_test_gemm(ob_ctx *ctx, int M, int N, int K, const float *A, const float *
     CHECK_CTX(ctx);
     if (!ctx->arena) return ctx_fail(ctx, OB_E_STATE, "no arena");
     if (M <= 0 || N <= 0 || K <= 0) return ctx_fail(ctx, OB_E_ARG, "bad shape");
+    if ((u64)M * (u64)K >= 0xffffffffull) return ctx_fail(ctx, OB_E_RANGE, "operand of more than 2^32 elements");
     const size_t save = ctx->top;
     float *a = arena_array<float>(ctx, (size_t)M * K), *b = arena_array<float>(ctx, (size_t)N * K);
     float *c = arena_array<float>(ctx, (size_t)M * N);

@@ -110,6 +110,9 @@ struct ob_ctx {
     u32 n_items_total = 0;             // parameter-use items (MATVEC matrix / bias uses, LOOKUPs) of the whole graph
     u64 sum_out_dim = 0;               // bounds the tile lists
     u32 max_arity = 0;
+    u32 n_concat = 0;                  // CONCAT nodes in the graph store
+    bool concat_views = true;          // CONCAT batches that only matrix products read are not copied
+    bool uncopied_filled = false;      // their rows have been written after all (somebody read values)
     u64 sum_mv_d32 = 0, sum_mv_k32 = 0; // sums over MATVEC nodes of rows/32+1 and cols/32+1 (bound the GEMM tiles)
     size_t graph_top = 0;              // arena top right after the uploaded graph image
 

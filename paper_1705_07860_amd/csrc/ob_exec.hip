@@ -348,11 +348,58 @@ __device__ inline void wave_range(u32 total, u32 &lo, u32 &hi)
 }
 
 constexpr int KU = 8;   // blocks of 8 contraction indices whose loads are issued together
+
+// The operand row of one product row.  Read whole, it starts at o0.  Read in pieces (the operand is a
+// CONCAT node that was never copied, Section 3.3), contraction index k lies at o<q> + k for the piece q that
+// holds k (c<q> = first index behind piece q, 0xffffffff from the last piece on; the piece's first index
+// is already subtracted from o<q>, in wrap-around arithmetic).  Pieces are multiples of four indices long.
+struct XRow { u32 o0, o1, o2, o3; };
+struct XCuts { u32 c0, c1, c2; };
+static_assert(XP_MAX == 4, "XRow holds four piece offsets");
+template <bool XP>
+__device__ inline u32 x_at(const XRow &x, const XCuts &c, u32 k)
+{
+    u32 o = x.o0;
+    if (XP) {
+        // (the empty statements keep the three selects as they are: taken together the compiler would turn them
+        // into an indexed read of a four-entry table in scratch memory)
+        if (k >= c.c0) o = x.o1;
+        asm volatile("" : "+v"(o));
+        if (k >= c.c1) o = x.o2;
+        asm volatile("" : "+v"(o));
+        if (k >= c.c2) o = x.o3;
+    }
+    return o + k;
+}
+__device__ inline XCuts x_cuts(const TileDesc &d)
+{
+    XCuts c;
+    u32 s = d.sdim[0];
+    c.c0 = d.arity > 1 ? s : 0xffffffffu; s += d.sdim[1];
+    c.c1 = d.arity > 2 ? s : 0xffffffffu; s += d.sdim[2];
+    c.c2 = d.arity > 3 ? s : 0xffffffffu;
+    return c;
+}
+template <bool XP>
+__device__ inline XRow x_row(const Tables &T, const TileDesc &d, bool row_ok, u32 i, u32 row)
+{
+    XRow x;
+    x.o0 = row_ok ? opnd_row(T, d, 0, i, row) : 0u;
+    x.o1 = x.o2 = x.o3 = x.o0;
+    if (XP && row_ok) {
+        if (d.arity > 1) x.o1 = opnd_row(T, d, 1, i, row);
+        if (d.arity > 2) x.o2 = opnd_row(T, d, 2, i, row);
+        if (d.arity > 3) x.o3 = opnd_row(T, d, 3, i, row);
+    }
+    return x;
+}
+
 constexpr int DX_WAVES = 8;   // the dX kernel splits its long contraction (rows of W) over 8 waves
 
 // Y[B x m] = X[B x K] W^T + b.   xrow: this lane's X row (valid when row_ok), W row-major [m x K].
-__device__ inline void gemm_nt_tile(const float *xrow, bool row_ok, u32 B, const float *W, const float *bias, u32 m,
-                                    u32 K, bool fast, float *Y, u32 r0, u32 i0, float *lds)
+template <bool XP>
+__device__ inline void gemm_nt_tile(const float *V, const XRow &xr, const XCuts &xc, bool row_ok, u32 B, const float *W,
+                                    const float *bias, u32 m, u32 K, bool fast, float *Y, u32 r0, u32 i0, float *lds)
 {
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
     const u32 l32 = lane & 31, h = lane >> 5;
@@ -371,7 +418,7 @@ __device__ inline void gemm_nt_tile(const float *xrow, bool row_ok, u32 B, const
             for (int u = 0; u < KU; ++u) {
                 const u32 k0 = kb + 8 * u + 4 * h;
                 const bool in = kb + 8 * u < hi && k0 < K;
-                a[u] = (in && row_ok) ? ld4(xrow + k0) : z4;
+                a[u] = (in && row_ok) ? ld4(V + x_at<XP>(xr, xc, k0)) : z4;
                 b[u] = (in && col_ok) ? gl_ld4(wrow + k0) : z4;
             }
 #pragma unroll
@@ -383,7 +430,7 @@ __device__ inline void gemm_nt_tile(const float *xrow, bool row_ok, u32 B, const
             float av[4] = {0.f, 0.f, 0.f, 0.f}, bv[4] = {0.f, 0.f, 0.f, 0.f};
             for (int s = 0; s < 4; ++s)
                 if (k0 + s < K) {
-                    if (row_ok) av[s] = xrow[k0 + s];
+                    if (row_ok) av[s] = V[x_at<XP>(xr, xc, k0 + s)];
                     if (col_ok) bv[s] = wrow[k0 + s];
                 }
             acc = mfma4(make_float4(av[0], av[1], av[2], av[3]), make_float4(bv[0], bv[1], bv[2], bv[3]), acc);
@@ -402,6 +449,7 @@ __device__ inline void gemm_nt_tile(const float *xrow, bool row_ok, u32 B, const
 
 // Batches with many rows: a workgroup covers 64 x 64 outputs, wave w the 32x32 block (w / 2, w % 2)
 // over the whole contraction, so no partial sums cross waves and nothing goes through LDS.
+template <bool XP>
 __device__ inline void matvec_fwd_tile_wide(const Tables &T, const TileDesc &d)
 {
     const u32 lane = threadIdx.x & 63, w = threadIdx.x >> 6;
@@ -411,7 +459,8 @@ __device__ inline void matvec_fwd_tile_wide(const Tables &T, const TileDesc &d)
     const u32 row = r0 + l32, col = i0 + l32;
     const bool row_ok = row < d.B, col_ok = col < d.d;
     const u32 K = d.k;
-    const float *xrow = T.V + (row_ok ? opnd_row(T, d, 0, row - d.row0, row) : 0u);
+    const XRow xr = x_row<XP>(T, d, row_ok, row - d.row0, row);
+    const XCuts xc = x_cuts(d);
     gl_float *wrow = as_global(d.w) + (size_t)(col_ok ? col : 0u) * K;
     const bool fast = (d.flags & TF_ALIGNED) && (K & 3u) == 0;
     floatx16 acc;
@@ -425,7 +474,7 @@ __device__ inline void matvec_fwd_tile_wide(const Tables &T, const TileDesc &d)
             for (int u = 0; u < KU; ++u) {
                 const u32 k0 = kb + 8 * u + 4 * h;
                 const bool in = k0 < K;
-                a[u] = (in && row_ok) ? ld4(xrow + k0) : z4;
+                a[u] = (in && row_ok) ? ld4(T.V + x_at<XP>(xr, xc, k0)) : z4;
                 b[u] = (in && col_ok) ? gl_ld4(wrow + k0) : z4;
             }
 #pragma unroll
@@ -437,7 +486,7 @@ __device__ inline void matvec_fwd_tile_wide(const Tables &T, const TileDesc &d)
             float av[4] = {0.f, 0.f, 0.f, 0.f}, bv[4] = {0.f, 0.f, 0.f, 0.f};
             for (int s = 0; s < 4; ++s)
                 if (k0 + s < K) {
-                    if (row_ok) av[s] = xrow[k0 + s];
+                    if (row_ok) av[s] = T.V[x_at<XP>(xr, xc, k0 + s)];
                     if (col_ok) bv[s] = wrow[k0 + s];
                 }
             acc = mfma4(make_float4(av[0], av[1], av[2], av[3]), make_float4(bv[0], bv[1], bv[2], bv[3]), acc);
@@ -463,6 +512,7 @@ __device__ inline void matvec_fwd_tile_wide(const Tables &T, const TileDesc &d)
 constexpr u32 WKC = 64;             // contraction chunk
 constexpr u32 WLD = WKC + 4;        // padded LDS row
 constexpr u32 WIDE_LDS_FLOATS = 2 * GTW * WLD;   // X tile + W tile
+template <bool XP>
 __device__ inline void matvec_fwd_tile_wide_lds(const Tables &T, const TileDesc &d, float *lds)
 {
     const u32 tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
@@ -473,24 +523,28 @@ __device__ inline void matvec_fwd_tile_wide_lds(const Tables &T, const TileDesc 
     lds_float *xs = (lds_float *)lds, *ws = xs + GTW * WLD;
     // loader role: piece c4 (four floats) of rows lr + 16 p, p < 4
     const u32 lr = tid >> 4, c4 = (tid & 15u) * 4u;
-    u32 xoff[4];
+    XRow xr[4];
+    const XCuts xc = x_cuts(d);
     bool xok[4], wok[4];
 #pragma unroll
     for (int p = 0; p < 4; ++p) {
         const u32 row = r0 + lr + 16u * p, col = i0 + lr + 16u * p;
         xok[p] = row < d.B;
         wok[p] = col < m;
-        xoff[p] = xok[p] ? opnd_row(T, d, 0, row - d.row0, row) : 0u;
+        xr[p] = x_row<XP>(T, d, xok[p], row - d.row0, row);
     }
     gl_float *W = as_global(d.w);
-    const float4 z4 = make_float4(0.f, 0.f, 0.f, 0.f);
     float4 px[4], pw[4];
     auto prefetch = [&](u32 kc) {
         const u32 k = kc + c4;
 #pragma unroll
         for (int p = 0; p < 4; ++p) {
-            px[p] = (xok[p] && k < K) ? ld4(T.V + xoff[p] + k) : z4;
-            pw[p] = (wok[p] && k < K) ? gl_ld4(W + (size_t)(i0 + lr + 16u * p) * K + k) : z4;
+            // (zeros written out: a zero vector captured by reference becomes a stack object here and the
+            // choice between it and the load a choice between two addresses)
+            px[p] = make_float4(0.f, 0.f, 0.f, 0.f);
+            pw[p] = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (xok[p] && k < K) px[p] = ld4(T.V + x_at<XP>(xr[p], xc, k));
+            if (wok[p] && k < K) pw[p] = gl_ld4(W + (size_t)(i0 + lr + 16u * p) * K + k);
         }
     };
     floatx16 acc;
@@ -522,11 +576,14 @@ __device__ inline void matvec_fwd_tile_wide_lds(const Tables &T, const TileDesc 
     __syncthreads();                // the LDS space is free for the workgroup's next tile
 }
 
+// XP: the launch holds products whose operand rows are read in pieces (a slot with such a batch runs the
+// step kernel built with XP; products read whole take the same code there, with no cut inside the row).
+template <bool XP>
 __device__ inline void matvec_fwd_tile(const Tables &T, const TileDesc &d, float *lds)
 {
     if (d.flags & TF_WIDE) {
-        if ((d.flags & TF_ALIGNED) && (d.k & 3u) == 0) matvec_fwd_tile_wide_lds(T, d, lds);
-        else matvec_fwd_tile_wide(T, d);
+        if ((d.flags & TF_ALIGNED) && (d.k & 3u) == 0) matvec_fwd_tile_wide_lds<XP>(T, d, lds);
+        else matvec_fwd_tile_wide<XP>(T, d);
         return;
     }
     const u32 ntn = (d.d + GT - 1) / GT;
@@ -534,8 +591,8 @@ __device__ inline void matvec_fwd_tile(const Tables &T, const TileDesc &d, float
     const bool fast = (d.flags & 2u) && (d.k & 3u) == 0;
     const u32 row = r0 + (threadIdx.x & 31);
     const bool row_ok = row < d.B;
-    const float *xrow = T.V + (row_ok ? opnd_row(T, d, 0, row - d.row0, row) : 0u);
-    gemm_nt_tile(xrow, row_ok, d.B, d.w, d.b, d.d, d.k, fast, T.V + d.val_off, r0, i0, lds);
+    gemm_nt_tile<XP>(T.V, x_row<XP>(T, d, row_ok, row - d.row0, row), x_cuts(d), row_ok, d.B, d.w, d.b, d.d, d.k, fast,
+                     T.V + d.val_off, r0, i0, lds);
 }
 
 // dX[B x K] = G[B x m] W, contraction over m.  G rows are the batch's own contiguous block.
@@ -739,6 +796,12 @@ __device__ inline void param_w_tile(const Tables &T, const PTile &pt, float *lds
             ok[p] = it < n_uses;
             go[p] = ok[p] ? T.it_goff[start + it] : 0u;
             xo[p] = ok[p] ? T.it_xoff[start + it] : 0u;
+            if (xo[p] == XP_LIST) {
+                // the use's operand row is in pieces (its batch reads through an uncopied CONCAT): this thread's
+                // four columns lie in one piece
+                const uint4 o = T.it_xrec[2 * (size_t)(start + it)], c = T.it_xrec[2 * (size_t)(start + it) + 1];
+                xo[p] = xj >= c.z ? o.w : (xj >= c.y ? o.z : (xj >= c.x ? o.y : o.x));
+            }
         }
     };
     const float4 z4 = make_float4(0.f, 0.f, 0.f, 0.f);
@@ -1161,10 +1224,11 @@ __device__ inline void pull_tile_uni4(const Tables &T, const uint4 *q, lds_float
 // ------------------------------------------------------------------------------------------------
 // kernels
 // ------------------------------------------------------------------------------------------------
+template <bool XP>
 __device__ inline void run_fwd_tile(const Tables &T, const TileDesc &d, float *lds)
 {
     switch (d.op) {
-    case OP_MATVEC: matvec_fwd_tile(T, d, lds); break;
+    case OP_MATVEC: matvec_fwd_tile<XP>(T, d, lds); break;
     case OP_PICK_NLS:
     case OP_SQNORM: red_fwd_tile(T, d); break;
     case OP_ADD:
@@ -1213,10 +1277,12 @@ __device__ inline void stage_descriptors(const void *src, void *dst, u32 n)
 // tile_lo + (w - work_lo) * run_len and the work records are not read.
 extern __shared__ __align__(16) float dyn_lds[];   // sized per launch: GEMM reduction space or a fused chain's copy
 
-// LEAN: the launch holds component-wise work only; this instantiation carries no GEMM or
-// reduction code, needs half the registers and keeps twice the waves per CU.
-template <bool LEAN>
-__global__ __launch_bounds__(WG, LEAN ? 6 : 3) void k_fwd_step(u32 work_lo, u32 work_hi, u32 tile_lo, u32 run_len,
+// KIND: FWD_ANY every kind of tile; FWD_LEAN the launch holds component-wise work only (this instantiation
+// carries no GEMM or reduction code, needs half the registers and keeps twice the waves per CU); FWD_XP every
+// kind, and the products may read their operand rows in pieces.
+enum : int { FWD_ANY = 0, FWD_LEAN = 1, FWD_XP = 2 };
+template <int KIND>
+__global__ __launch_bounds__(WG, KIND == FWD_LEAN ? 6 : 3) void k_fwd_step(u32 work_lo, u32 work_hi, u32 tile_lo, u32 run_len,
                                                                 const TileDesc *tiles_f, const WorkRec *works_f, Tables T)
 {
     // the leading arguments arrive in scalar registers with the wave (so the descriptor loads start
@@ -1230,8 +1296,8 @@ __global__ __launch_bounds__(WG, LEAN ? 6 : 3) void k_fwd_step(u32 work_lo, u32 
         else wr = works_f[w];
         if (wr.len == 1) {
             const TileDesc d = tiles_f[wr.first];
-            if (LEAN) ew_fwd_tile(T, d, (lds_float *)lds, threadIdx.x, WG);
-            else run_fwd_tile(T, d, lds);
+            if (KIND == FWD_LEAN) ew_fwd_tile(T, d, (lds_float *)lds, threadIdx.x, WG);
+            else run_fwd_tile<KIND == FWD_XP>(T, d, lds);
             continue;
         }
         for (u32 c0 = 0; c0 < wr.len; c0 += RUN_STAGE) {
@@ -1458,6 +1524,23 @@ __global__ void k_gather_all(Tables T, const float *src, const u32 *src_off, flo
     for (u32 c = threadIdx.x; c < d; c += blockDim.x) o[c] = s[c];
 }
 
+// Rows of the CONCAT batches that the forward pass left uncopied (TF_VIRT), written when somebody outside the
+// forward pass asks for values: one workgroup per node, the operands' rows copied side by side.
+__global__ void k_fill_uncopied(Tables T)
+{
+    const u32 v = blockIdx.x;
+    if (T.op[v] != OP_CONCAT) return;
+    if (!(T.batches[T.batch_of_pos[T.pos_of[v]]].vec4 & TF_VIRT)) return;
+    float *o = T.V + T.val_off[v];
+    for (u32 e = T.in_off[v]; e < T.in_off[v + 1]; ++e) {
+        const u32 u = T.in_idx[e];
+        const u32 d = T.out_dim[u];
+        const float *s = T.V + T.val_off[u];
+        for (u32 c = threadIdx.x; c < d; c += blockDim.x) o[c] = s[c];
+        o += d;
+    }
+}
+
 // Values of already evaluated nodes, copied into the payload block of a later evaluation stage
 // whose graph holds them as leaves: entry i copies dim[i] elements from the row of node src[i] in
 // the earlier evaluation's value arena to payload + dst[i].
@@ -1479,8 +1562,11 @@ __global__ __launch_bounds__(WG) void k_test_gemm(const float *A, const float *B
     const u32 Ku = (u32)K;
     const u32 row = r0 + (threadIdx.x & 31);
     const bool row_ok = row < (u32)M;
-    gemm_nt_tile(A + (size_t)(row_ok ? row : 0u) * Ku, row_ok, (u32)M, Bm, nullptr, (u32)N, Ku, (Ku & 3u) == 0, C, r0,
-                 i0, lds);
+    XRow xr;
+    xr.o0 = xr.o1 = xr.o2 = xr.o3 = (row_ok ? row : 0u) * Ku;
+    XCuts xc;
+    xc.c0 = xc.c1 = xc.c2 = 0xffffffffu;
+    gemm_nt_tile<false>(A, xr, xc, row_ok, (u32)M, Bm, nullptr, (u32)N, Ku, (Ku & 3u) == 0, C, r0, i0, lds);
 }
 
 inline u32 grid_for(u32 tiles, u32 cap) { return tiles < cap ? tiles : cap; }
@@ -1510,7 +1596,8 @@ static hipError_t allow_large_dynamic_lds()
 {
     static hipError_t result = [] {
         const int bytes = (int)(CHAIN_LDS_FLOATS * 4);
-        const void *kernels[4] = {(const void *)k_fwd_step<false>, (const void *)k_fwd_step<true>,
+        const void *kernels[5] = {(const void *)k_fwd_step<FWD_ANY>, (const void *)k_fwd_step<FWD_LEAN>,
+                                  (const void *)k_fwd_step<FWD_XP>,
                                   (const void *)k_bwd_step<false>, (const void *)k_bwd_step<true>};
         hipError_t e = hipSuccess;
         for (const void *k : kernels)
@@ -1531,10 +1618,13 @@ static int launch_forward_steps(ob_ctx *ctx)
         const u32 lo = r.wf, hi = ctx->slots[st + 1].wf;
         if (hi > lo) {
             if (r.plain & 1u)
-                hipLaunchKernelGGL(k_fwd_step<true>, dim3(grid_for(hi - lo, GRID_CAP)), dim3(WG), slot_lds_bytes(r, 16), s,
+                hipLaunchKernelGGL(k_fwd_step<FWD_LEAN>, dim3(grid_for(hi - lo, GRID_CAP)), dim3(WG), slot_lds_bytes(r, 16), s,
                                    lo, hi, r.tf, slot_run_len_fwd(r), T.tiles_f, T.works_f, T);
-            else
-                hipLaunchKernelGGL(k_fwd_step<false>, dim3(grid_for(hi - lo, GRID_CAP)), dim3(WG),
+            else if (r.plain & 2u)
+                hipLaunchKernelGGL(k_fwd_step<FWD_ANY>, dim3(grid_for(hi - lo, GRID_CAP)), dim3(WG),
+                                   slot_lds_bytes(r, FWD_LDS_MIN), s, lo, hi, r.tf, slot_run_len_fwd(r), T.tiles_f, T.works_f, T);
+            else   // a product of the slot reads its operand rows in pieces
+                hipLaunchKernelGGL(k_fwd_step<FWD_XP>, dim3(grid_for(hi - lo, GRID_CAP)), dim3(WG),
                                    slot_lds_bytes(r, FWD_LDS_MIN), s, lo, hi, r.tf, slot_run_len_fwd(r), T.tiles_f, T.works_f, T);
             ++ctx->n_launch_fwd;
         }
@@ -1687,6 +1777,13 @@ hipError_t exec_gather_all(const Tables &T, int which, float *dst, const u32 *ds
 {
     if (T.n == 0) return hipSuccess;
     hipLaunchKernelGGL(k_gather_all, dim3(T.n), dim3(64), 0, s, T, which ? T.G : T.V, which ? T.nat_off : T.val_off, dst, dst_off);
+    return hipGetLastError();
+}
+
+hipError_t exec_fill_uncopied(const Tables &T, hipStream_t s)
+{
+    if (T.n == 0) return hipSuccess;
+    hipLaunchKernelGGL(k_fill_uncopied, dim3(T.n), dim3(64), 0, s, T);
     return hipGetLastError();
 }
 

@@ -45,9 +45,18 @@ enum : u32 {
     TF_OUT_LDS = 256u,       // the tile also writes its result to the chain's LDS copy
     TF_GLOBAL_DEP = 512u,    // reads a result of an earlier member of the same chain from global memory
     TF_SIMPLE = 1024u,       // float4 tile of ADD (<= 4 operands) / CMULT / TANH / SIGMOID / SLICE whose operand rows are all evenly spaced
-    TF_VIEW = 2048u          // batch flag: a SLICE batch; its rows are not copied, every reader is pointed at the range of the
+    TF_VIEW = 2048u,         // batch flag: a SLICE batch; its rows are not copied, every reader is pointed at the range of the
                              // operand row instead (Section 3.3: inputs that already lie in place are used as they are)
+    TF_VIRT = 4096u,         // batch flag: a CONCAT batch that only matrix products read; its rows are not written by the forward
+                             // pass, the products read the pieces where their producers left them (TF_XP).  The rows are filled
+                             // in when a value is read from outside the forward pass.
+    TF_XP = 8192u            // batch flag: a MATVEC batch whose operand is read piece by piece (BatchRec::aux1 pieces of
+                             // the dimensions b_indim[indim ..]); piece q of row r lies at opnd_off[opnd + q * B + r] + k for the
+                             // contraction indices k of the piece (the piece's first index is already subtracted)
 };
+constexpr u32 TF_NOFWD = TF_VIEW | TF_VIRT;   // batches without forward work
+constexpr u32 XP_MAX = 4;                     // most pieces of an operand that is read through a CONCAT
+constexpr u32 XP_LIST = 0xffffffffu;          // it_xoff entry of a use whose operand row is in pieces (see Tables::it_xrec)
 
 // Kinds of consumer-edge records read by the backward pull (one per graph edge).
 enum : u32 {
@@ -72,7 +81,8 @@ struct BatchRec {  // one per batch, 64 bytes
     u32 d;         // out_dim
     u32 arity;
     i32 param, bias;
-    i32 aux0, aux1;      // SLICE lo / hi (the only aux fields that are part of a signature)
+    i32 aux0, aux1;      // SLICE lo / hi (the only aux fields that are part of a signature); MATVEC: aux0 = the CONCAT batch
+                         // whose pieces the batch's operand rows follow (-1: none), aux1 = number of pieces (0: read whole)
     u32 step;
     u32 val_off;         // element offset of row 0 in the value arena (same in the grad arena)
     u32 dx_off;          // MATVEC: element offset of the dX block in the grad arena
@@ -173,8 +183,9 @@ struct WorkRec { u32 first, len; };   // a workgroup runs tiles [first, first + 
 // lds_need: floats of LDS the slot's fused chains use to hand results on (0: none); the step
 // kernels are launched with that much dynamic LDS (and at least their GEMM reduction space), so
 // slots without such chains keep more workgroups resident per CU.
-// plain != 0: every forward work item of the slot is component-wise (no GEMM, reduction or wide-sum
-// tile), so the slot can run the lean instantiation of the forward kernel.
+// plain bit 0: every forward work item of the slot is component-wise (no GEMM, reduction or wide-sum
+// tile), so the slot can run the lean instantiation of the forward kernel.  Bit 1: no product of the slot
+// reads its operand rows in pieces (otherwise the slot runs the instantiation that can).
 // lminf / nlmaxf: the same pair of run lengths over the slot's forward work items (views have none).
 struct SlotRec { u32 wf, wa, tb, tf, ta, lmin, nlmax, dx_free, lds_need, plain, lminf, nlmaxf; };
 
@@ -204,6 +215,7 @@ struct SchedHeader {
     u32 tiles_fwd, tiles_pull, tiles_dx, frontier_done;
     u32 n_slots, n_chains, works_fwd, works_pull;
     u32 n_bedges, slot_sweeps, p0, p1;
+    u32 view_batches, view_floats, virt_batches, virt_floats;   // SLICE batches that are views / CONCAT batches never copied, and their sizes
 };
 enum : u32 { ERR_CYCLE = 1, ERR_COLLISION = 2, ERR_TABLE_FULL = 4, ERR_OVERFLOW = 8, ERR_CLASSES = 16 };
 
@@ -241,6 +253,8 @@ struct Tables {
     EdgeRec *edges;
     // parameter-use items (deferred dW / db / dE)
     u64 *it_key; u32 *it_pos; u32 *it_goff; u32 *it_xoff; u32 *pu_start; u32 *pu_end;
+    uint4 *it_xrec;        // per MATVEC use with it_xoff == XP_LIST, two entries: the operand row's offset per piece (contraction
+                           // index k of piece q lies at offset q + k) and the first index behind pieces 0, 1, 2 (0xffffffff: none)
     SchedHeader *hdr;
     // arenas
     float *V; float *G;
@@ -275,6 +289,7 @@ int exec_backward(ob_ctx *ctx);
 hipError_t exec_gather_all(const Tables &T, int which, float *dst, const u32 *dst_off, hipStream_t s);
 hipError_t exec_stage_scatter(const float *G, const u32 *nat_off, u32 first_proxy, const u32 *src, const u32 *dim, u32 count,
                               const u32 *owner_nat_off, float *owner_gx, hipStream_t s);
+hipError_t exec_fill_uncopied(const Tables &T, hipStream_t s);
 hipError_t exec_gather_some(const Tables &T, int which, float *dst, const u32 *dst_off, hipStream_t s);
 hipError_t exec_stage_fill(const float *V, const u32 *val_off, const u32 *src, const u32 *dst, const u32 *dim, u32 count,
                            float *payload, hipStream_t s);

@@ -574,8 +574,8 @@ __global__ void k_heads(Tables T, const u64 *skey, const u32 *sval, u32 *head_fl
     T.s_aux0[p] = (u32)T.aux0[v];
     Tri c;
     c.a = (p == 0 || skey[p] != skey[p - 1]) ? 1u : 0u;
-    c.b = T.in_off[v + 1] - T.in_off[v];
     const u32 o = T.op[v];
+    c.b = (o == OP_MATVEC) ? XP_MAX : T.in_off[v + 1] - T.in_off[v];   // a product's operand may be listed in up to XP_MAX pieces
     c.c = (o == OP_MATVEC) ? (1u + (T.bias[v] >= 0 ? 1u : 0u)) : (o == OP_LOOKUP ? 1u : 0u);
     c.d = 0;
     head_flag[p] = c.a;
@@ -602,7 +602,7 @@ __global__ void k_batch_off(Tables T, const u32 *head_flag, const Tri *before, u
 __host__ __device__ inline u32 cdiv(u64 a, u32 b) { return (u32)((a + b - 1) / b); }
 
 // one thread per batch: record + sizes for the layout scan (entries b >= n_batches are zero)
-__global__ void k_batch_layout(Tables T, Lay *lay_in)
+__global__ void k_batch_layout(Tables T, Lay *lay_in, int virt)
 {
     const u32 b = blockIdx.x * blockDim.x + threadIdx.x;
     if (b >= T.n) return;
@@ -615,6 +615,7 @@ __global__ void k_batch_layout(Tables T, Lay *lay_in)
         r.arity = T.in_off[h + 1] - T.in_off[h];
         r.param = T.param[h]; r.bias = T.bias[h];
         r.aux0 = T.aux0[h]; r.aux1 = T.aux1[h];
+        if (r.op == OP_MATVEC) { r.aux0 = -1; r.aux1 = 0; }
         r.step = T.step[h];
         r.k = r.arity ? T.out_dim[T.in_idx[T.in_off[h]]] : 0;
         r.val_off = r.dx_off = r.indim = 0;
@@ -622,6 +623,8 @@ __global__ void k_batch_layout(Tables T, Lay *lay_in)
         r.vec4 = TF_VEC4 | TF_ALIGNED | TF_G_ALIAS;   // cleared below by whatever a member violates
         if (r.op == OP_MATVEC && B >= WIDE_MIN_ROWS && r.d >= (u32)GTW) r.vec4 |= TF_WIDE;
         if (r.op == OP_SLICE) r.vec4 |= TF_VIEW;
+        if (r.op == OP_CONCAT && virt) r.vec4 |= TF_VIRT;   // taken back by k_member_check / k_virt_check
+        if (r.op == OP_MATVEC && virt) r.vec4 |= TF_XP;     // taken back by k_xp_check
         T.batches[b] = r;
         const u64 vs = (u64)B * r.d;
         L.val = (vs + VAL_ALIGN - 1) / VAL_ALIGN * VAL_ALIGN;
@@ -629,7 +632,7 @@ __global__ void k_batch_layout(Tables T, Lay *lay_in)
             const u64 xs = (u64)B * r.k;
             L.dx = (xs + VAL_ALIGN - 1) / VAL_ALIGN * VAL_ALIGN;
         }
-        L.ind = r.arity;
+        L.ind = r.op == OP_MATVEC ? XP_MAX : r.arity;
     }
     lay_in[b] = L;
 }
@@ -657,11 +660,23 @@ __global__ void k_node_offsets(Tables T)
 {
     const u32 p = blockIdx.x * blockDim.x + threadIdx.x;
     if (p >= T.n) return;
-    const BatchRec &r = T.batches[T.batch_of_pos[p]];
+    BatchRec &r = T.batches[T.batch_of_pos[p]];
     const u32 row = p - r.pos0;
     const u32 v = T.order[p];
     T.val_off[v] = T.nat_off[v] = r.val_off + row * r.d;
     T.dx_off[v] = (r.op == OP_MATVEC) ? r.dx_off + row * r.k : 0u;
+    // a CONCAT batch can stay uncopied only with at most XP_MAX pieces whose dimensions are multiples of 4
+    if (r.op == OP_CONCAT && (r.vec4 & TF_VIRT)) {
+        const u32 ar = T.in_off[v + 1] - T.in_off[v];
+        bool ok = ar <= XP_MAX;
+        for (u32 j = 0; ok && j < ar; ++j) ok = (T.out_dim[T.in_idx[T.in_off[v] + j]] & 3u) == 0;
+        if (!ok) atomicAnd(&r.vec4, ~(u32)TF_VIRT);
+    }
+    // a product whose operand is a CONCAT node: the lowest such CONCAT batch gives the piece structure of the batch
+    if (r.op == OP_MATVEC && (r.vec4 & TF_XP)) {
+        const u32 x = T.in_idx[T.in_off[v]];
+        if (T.op[x] == OP_CONCAT) atomicMin((u32 *)&r.aux0, T.batch_of_pos[T.pos_of[x]]);
+    }
 }
 
 // SLICE nodes are views: their value is the range [lo, hi) of the operand's row where it lies
@@ -674,6 +689,29 @@ __global__ void k_view_offsets(Tables T)
     u32 x = v, acc = 0;
     while (T.op[x] == OP_SLICE) { acc += (u32)T.aux0[x]; x = T.in_idx[T.in_off[x]]; }   // ids fall: ends at a node that owns its row
     T.val_off[v] = T.nat_off[x] + acc;
+}
+
+// CONCAT batches that only matrix products read are not copied (Section 3.3: operands that already lie in
+// memory are used where they are): the product reads each row's pieces from their producers' rows.  This needs
+// one piece structure per product batch.  Per product row whose operand is a CONCAT node: its pieces must
+// have the dimensions of the batch's reference CONCAT batch (aux0), which must itself qualify; rows with any
+// other operand are read whole, which every piece structure allows.  (The reference batch and the CONCAT batches
+// that qualify at all were settled by k_node_offsets.)
+__device__ inline void xp_check(const Tables &T, u32 p, BatchRec &r)
+{
+    if (r.op != OP_MATVEC || !(r.vec4 & TF_XP) || r.aux0 < 0) return;
+    const u32 x = T.in_idx[T.in_off[T.order[p]]];
+    if (T.op[x] != OP_CONCAT) return;
+    const BatchRec &rr = T.batches[r.aux0];
+    const u32 hr = T.order[rr.pos0];
+    const u32 P = rr.arity;
+    bool ok = (rr.vec4 & TF_VIRT) && T.in_off[x + 1] - T.in_off[x] == P;
+    for (u32 j = 0; ok && j < P; ++j) ok = T.out_dim[T.in_idx[T.in_off[x] + j]] == T.out_dim[T.in_idx[T.in_off[hr] + j]];
+    if (!ok) { atomicAnd(&r.vec4, ~(u32)TF_XP); return; }
+    if (T.batch_of_pos[T.pos_of[x]] == (u32)r.aux0) {   // (every such row writes the same values)
+        r.aux1 = (i32)P;
+        for (u32 j = 0; j < P; ++j) T.b_indim[r.indim + j] = T.out_dim[T.in_idx[T.in_off[x] + j]];
+    }
 }
 
 // Per node: the check that every member of a batch really has the signature tuple of the batch
@@ -697,7 +735,23 @@ __global__ void k_member_check(Tables T)
     // A one-element MATVEC node may become the backward root (chosen after scheduling): its gradient is
     // the seed, not its consumer's row, so such batches never alias.
     if (r.op == OP_MATVEC && (T.outdeg[v] != 1 || r.d == 1)) atomicAnd(&r.vec4, ~(u32)TF_G_ALIAS);
+    xp_check(T, p, r);
 }
+
+// Per edge into a CONCAT node: any reader that is not a product reading in pieces needs the row in place.
+__global__ void k_virt_check(Tables T)
+{
+    const u32 e = blockIdx.x * blockDim.x + threadIdx.x;
+    if (e >= T.E) return;
+    const u32 u = T.in_idx[e];
+    if (T.op[u] != OP_CONCAT) return;
+    BatchRec &ru = T.batches[T.batch_of_pos[T.pos_of[u]]];
+    if (!(ru.vec4 & TF_VIRT)) return;
+    const BatchRec &rv = T.batches[T.batch_of_pos[T.pos_of[T.edge_cons[e]]]];
+    if (!(rv.op == OP_MATVEC && (rv.vec4 & TF_XP) && rv.aux1 > 0)) atomicAnd(&ru.vec4, ~(u32)TF_VIRT);
+}
+
+__device__ inline bool batch_xp(const BatchRec &r) { return r.op == OP_MATVEC && (r.vec4 & TF_XP) && r.aux1 > 0; }
 
 // Per edge: operand row offsets per batch (slot-major), operand dimensions of the batch, the
 // operand part of the membership check, and the alignment flags.
@@ -715,6 +769,19 @@ __global__ void k_opnd(Tables T)
     const u32 du = T.out_dim[u];
     if (j >= r.arity || du != T.out_dim[T.in_idx[T.in_off[h] + j]]) {
         atomicOr(&T.hdr->err, (u32)ERR_COLLISION);
+        return;
+    }
+    if (batch_xp(r)) {
+        // the operand in pieces: the rows of an uncopied CONCAT node's operands, or the whole row once per piece
+        const u32 P = (u32)r.aux1;
+        const bool pieces = T.op[u] == OP_CONCAT && (T.batches[T.batch_of_pos[T.pos_of[u]]].vec4 & TF_VIRT);
+        u32 start = 0;
+        for (u32 q = 0; q < P; ++q) {
+            u32 off = T.val_off[u];
+            if (pieces) { const u32 w = T.in_idx[T.in_off[u] + q]; off = T.val_off[w] - start; start += T.out_dim[w]; }
+            T.opnd_off[r.opnd + q * r.B + row] = off;
+            if (off & 3u) atomicAnd(&r.vec4, ~(u32)(TF_VEC4 | TF_ALIGNED));
+        }
         return;
     }
     const u32 off = T.val_off[u];
@@ -899,9 +966,27 @@ __global__ __launch_bounds__(SLOT_THREADS) void k_slots(Tables T, int fuse, cons
 __global__ void k_launch_keys(Tables T, u64 *keys, u32 *vals, u32 n_pad)
 {
     const u32 b = blockIdx.x * blockDim.x + threadIdx.x;
-    if (b >= n_pad) return;
-    vals[b] = b;
-    if (b >= T.hdr->n_batches) { keys[b] = ~0ull; return; }
+    const bool in = b < n_pad;
+    if (in) vals[b] = b;
+    // batches without forward work, counted for the statistics: summed over the wave first (every lane takes
+    // part), one atomic per wave
+    const bool live = in && b < T.hdr->n_batches;
+    u32 cnt[4] = {0u, 0u, 0u, 0u};
+    if (live) {
+        const BatchRec &r = T.batches[b];
+        if (r.vec4 & TF_VIEW) { cnt[0] = 1u; cnt[1] = r.B * r.d; }
+        if (r.vec4 & TF_VIRT) { cnt[2] = 1u; cnt[3] = r.B * r.d; }
+    }
+    if (__ballot(cnt[0] | cnt[2]) != 0ull) {
+        for (int q = 0; q < 4; ++q)
+            for (int o = 32; o > 0; o >>= 1) cnt[q] += __shfl_xor(cnt[q], o);
+        if ((threadIdx.x & 63u) == 0u) {
+            if (cnt[0]) { atomicAdd(&T.hdr->view_batches, cnt[0]); atomicAdd(&T.hdr->view_floats, cnt[1]); }
+            if (cnt[2]) { atomicAdd(&T.hdr->virt_batches, cnt[2]); atomicAdd(&T.hdr->virt_floats, cnt[3]); }
+        }
+    }
+    if (!in) return;
+    if (!live) { keys[b] = ~0ull; return; }
     // unfused plans are already in launch order (slot = step): equal keys keep that order
     keys[b] = T.hdr->p0 ? 0ull : (((u64)T.slot_of[b] << SLOT_BITS) | T.label_of[b]);
 }
@@ -992,7 +1077,7 @@ __global__ void k_chain_recs(Tables T, int agenda, const u32 *bset, const u32 *f
         for (u32 m = 0; m < k; ++m) {
             const BatchRec &rm = T.batches[T.lorder[i + m]];
             kt += rm.B / G;
-            if (!(rm.vec4 & TF_VIEW)) ktf += rm.B / G;
+            if (!(rm.vec4 & TF_NOFWD)) ktf += rm.B / G;
             per_group += (rm.B / G) * rm.d;
         }
         cr.G = G; cr.Rg = rows_per_block(dmax);
@@ -1064,6 +1149,7 @@ __global__ void k_slot_tables(Tables T, const CLay *clay_ex, const CLay *total)
     const BatchRec &hb = T.batches[T.lorder[cr.first]];
     if (hb.op == OP_MATVEC && !(hb.vec4 & TF_G_ALIAS)) S.dx_free = 0;   // this slot's dX tiles need the slot's own pull first
     if (!cr.fused) atomicAnd(&S.plain, ~1u);     // a GEMM, reduction or wide-sum batch runs in this slot
+    if (batch_xp(hb) && hb.aux1 > 1) atomicAnd(&S.plain, ~2u);   // a product that reads its operand rows in pieces
     if (cr.fused == 2u) {
         u32 need = 0;
         for (u32 m = 0; m < cr.k; ++m) need += chain_region(cr, T.batches[T.lorder[cr.first + m]]);
@@ -1195,7 +1281,9 @@ __device__ inline void fill_tile_desc(const Tables &T, const BatchRec &r, u32 t,
         if (r_hi >= r.B) r_hi = r.B - 1;
         d.row0 = row0 = r_lo; d.nrows = nrows = r_hi - r_lo + 1; d.rstride = rstride = 1;
     }
-    const u32 ns = r.arity < 4 ? r.arity : 4;
+    const bool xp = batch_xp(r);
+    const u32 ns = xp ? (u32)r.aux1 : (r.arity < 4 ? r.arity : 4);   // a product reading in pieces: one operand slot per piece
+    if (xp) d.arity = ns;
     u32 lo[4], hi[4];
     for (u32 j = 0; j < ns; ++j) {
         const u32 *op = T.opnd_off + r.opnd + j * r.B;
@@ -1377,7 +1465,7 @@ __global__ void k_tiles(Tables T, const CLay *clay_ex, const CLay *total, u32 ca
                 if (cr.fused) {
                     for (;; ++m) {
                         const BatchRec &rq = T.batches[T.lorder[cr.first + m]];
-                        if (which == 0 && (rq.vec4 & TF_VIEW)) continue;
+                        if (which == 0 && (rq.vec4 & TF_NOFWD)) continue;
                         mult = rq.B / cr.G;
                         if (it < mult) break;
                         it -= mult;
@@ -1398,7 +1486,7 @@ __global__ void k_tiles(Tables T, const CLay *clay_ex, const CLay *total, u32 ca
                         for (u32 mm = m + 1; mm < cr.k; ++mm) {
                             const BatchRec &rn = T.batches[T.lorder[cr.first + mm]];
                             if (T.blevel[T.lorder[cr.first + mm]] != my_level) break;
-                            if (!(rn.vec4 & TF_VIEW)) glen += rn.B / cr.G;
+                            if (!(rn.vec4 & TF_NOFWD)) glen += rn.B / cr.G;
                         }
                     } else {
                         glen = it + 1;
@@ -1495,7 +1583,26 @@ __global__ void k_item_finish(Tables T, const u64 *keys, const u32 *vals, u32 n_
     T.it_key[i] = k;
     T.it_pos[i] = p;
     T.it_goff[i] = T.nat_off[v];
-    T.it_xoff[i] = (T.op[v] == OP_MATVEC) ? T.val_off[T.in_idx[T.in_off[v]]] : 0u;
+    u32 xoff = 0;
+    if (T.op[v] == OP_MATVEC) {
+        const BatchRec &r = T.batches[T.batch_of_pos[p]];
+        xoff = T.val_off[T.in_idx[T.in_off[v]]];
+        if (batch_xp(r)) {
+            // the operand row in pieces: the row's offsets from the batch's operand list and the cuts between pieces
+            xoff = XP_LIST;
+            const u32 P = (u32)r.aux1, row = p - r.pos0;
+            u32 o[XP_MAX], c[XP_MAX];
+            u32 end = 0;
+            for (u32 q = 0; q < XP_MAX; ++q) {
+                o[q] = T.opnd_off[r.opnd + (q < P ? q : P - 1) * r.B + row];
+                end += q < P ? T.b_indim[r.indim + q] : 0u;
+                c[q] = q + 1 < P ? end : 0xffffffffu;
+            }
+            T.it_xrec[2 * (size_t)i] = make_uint4(o[0], o[1], o[2], o[3]);
+            T.it_xrec[2 * (size_t)i + 1] = make_uint4(c[0], c[1], c[2], 0u);
+        }
+    }
+    T.it_xoff[i] = xoff;
     if (i == 0 || (u32)(keys[i - 1] >> 32) != slot) T.pu_start[slot] = i;
     if (i == n_items - 1 || (u32)(keys[i + 1] >> 32) != slot) T.pu_end[slot] = i + 1;
 }
@@ -1575,8 +1682,8 @@ int sched_enqueue(ob_ctx *ctx)
     T.ht_mask = ht_size - 1;
     A(T.order, u32, n); A(T.pos_of, u32, n); A(T.batch_of_pos, u32, n); A(T.s_aux0, u32, n);
     A(T.s_in_off, u32, n + 1);
-    A(T.batch_off, u32, n + 1); A(T.batches, BatchRec, n); A(T.lay, Lay, n); A(T.b_indim, u32, E + 1);
-    A(T.val_off, u32, n); A(T.nat_off, u32, n); A(T.dx_off, u32, n); A(T.opnd_off, u32, E + 1); A(T.dx_gsrc, u32, n);
+    A(T.batch_off, u32, n + 1); A(T.batches, BatchRec, n); A(T.lay, Lay, n); A(T.b_indim, u32, E + (size_t)XP_MAX * n + 1);
+    A(T.val_off, u32, n); A(T.nat_off, u32, n); A(T.dx_off, u32, n); A(T.opnd_off, u32, E + (size_t)XP_MAX * n + 1); A(T.dx_gsrc, u32, n);
     A(T.slot_of, u32, n); A(T.label_of, u32, n); A(T.blevel, u32, n);
     A(T.chain_of_batch, u32, n);
     A(T.lorder, u32, n); A(T.chains, ChainRec, n); A(T.clay, CLay, n); A(T.chain_of_lpos, u32, n);
@@ -1589,6 +1696,8 @@ int sched_enqueue(ob_ctx *ctx)
     A(T.edges, EdgeRec, E + 1);
     A(T.it_key, u64, n_items + 1); A(T.it_pos, u32, n_items + 1); A(T.it_goff, u32, n_items + 1);
     A(T.it_xoff, u32, n_items + 1);
+    T.it_xrec = nullptr;
+    if (ctx->concat_views && ctx->n_concat > 0) A(T.it_xrec, uint4, 2 * ((size_t)n_items + 1));
     u32 *succ_node;
     A(succ_node, u32, E + 1);
     A(ctx->key_a, u64, maxne); A(ctx->key_b, u64, maxne); A(ctx->val_a, u32, maxne); A(ctx->val_b, u32, maxne);
@@ -1665,13 +1774,15 @@ int sched_enqueue(ob_ctx *ctx)
     HIP_TRY(ctx, prim_scan_tri(tri_in, tri_ex, n, nullptr, ctx->scratch, s));
     ctx->n_launch_sched += scan_launches;
     K(k_batch_off, n, T, head_flag, tri_ex, s_items, manual);
-    K(k_batch_layout, n, T, ctx->lay_in);
+    const int virt = ctx->concat_views && ctx->n_concat > 0;   // CONCAT batches that only products read stay uncopied
+    K(k_batch_layout, n, T, ctx->lay_in, virt);
     HIP_TRY(ctx, prim_scan_lay(ctx->lay_in, T.lay, n, ctx->lay_total, ctx->scratch, s));
     ctx->n_launch_sched += scan_launches;
     K(k_batch_finish, n, T, T.lay, ctx->lay_total);
     K(k_node_offsets, n, T);
     K(k_view_offsets, n, T);
     K(k_member_check, n, T);
+    if (virt && E > 0) K(k_virt_check, E, T);
     if (E > 0) K(k_opnd, E, T);
     if (E > 0) K(k_edges, E, T);
 

@@ -557,6 +557,140 @@ def test_slices_are_views_of_their_operand_rows(mode):
     say(f"  slice views/{mode}: {st['n_batches']} batches, {st['n_tiles_fwd']} forward tiles")
 
 
+def _concat_graph(rows, H, seed=21):
+    """Rows of a small network in which CONCAT nodes of every kind feed shared matrices: two, three and four
+    pieces (leaves, component-wise results, views, a piece used twice), a batch of products that mixes
+    CONCAT operands with plain ones, a single-piece CONCAT, a piece that starts off a 16-byte boundary, and
+    the cases that must still be copied (five pieces, a piece width that is no multiple of 4, a CONCAT that
+    something other than a product reads, two piece structures into one batch of products)."""
+    rng = np.random.default_rng(seed)
+    pb = wl.ParamBuilder(rng, std=0.3)
+    M = max(H, 12)
+    E = pb.add("E", 9, H)
+    Wy = pb.add("Wy", 2 * H + 4, H)
+    by = pb.add("by", 2 * H + 4, 1)
+    W1 = pb.add("W1", M, H)
+    W2 = pb.add("W2", M, 2 * H)
+    b2 = pb.add("b2", M, 1)
+    W2c = pb.add("W2c", M, 2 * H)
+    W2n = pb.add("W2n", M, 3 * H + 4)
+    W3 = pb.add("W3", M, 3 * H)
+    W3b = pb.add("W3b", M, 3 * H)
+    W4 = pb.add("W4", M, 4 * H)
+    b4 = pb.add("b4", M, 1)
+    W5 = pb.add("W5", M, 5 * H)
+    W6 = pb.add("W6", M, 16)
+    p = pb.done()
+    gb = wl.GraphBuilder(p)
+    losses, kinds = [], {k: [] for k in ("c1", "c2", "c3", "c4", "cu", "c5", "c6", "cn", "cd")}
+    for i in range(rows):
+        a = gb.tanh(gb.lookup(E, i % 9))
+        b = gb.input(rng.standard_normal(H))
+        y = gb.matvec(Wy, by, b)                      # 2H + 4
+        s = gb.slice(y, 4, 4 + H)                     # a view, 16-byte aligned
+        su = gb.slice(y, 2, 2 + H)                    # a view that starts off a 16-byte boundary
+        c1 = gb.concat((a,))
+        c2 = gb.concat((a, b)) if i % 2 == 0 else gb.input(rng.standard_normal(2 * H))
+        c3 = gb.concat((a, s, b))
+        c4 = gb.concat((a, b, s, a))
+        cu = gb.concat((su, a))
+        c5 = gb.concat((a, b, a, b, a))
+        c6 = gb.concat((gb.slice(y, 0, 6), gb.slice(y, 6, 16)))
+        cn = gb.concat((b, y))                        # also read by a tanh: copied
+        cd = gb.concat((a, gb.slice(y, 0, 2 * H))) if i % 2 else gb.concat((gb.slice(y, 0, 2 * H), a))
+        for k, v in (("c1", c1), ("c3", c3), ("c4", c4), ("cu", cu), ("c5", c5), ("c6", c6), ("cn", cn), ("cd", cd)):
+            kinds[k].append(v)
+        if i % 2 == 0:
+            kinds["c2"].append(c2)
+        outs = [gb.matvec(W1, -1, c1), gb.matvec(W2, b2, c2), gb.matvec(W3, -1, c3), gb.matvec(W4, b4, c4),
+                gb.matvec(W2c, -1, cu), gb.matvec(W5, -1, c5), gb.matvec(W6, -1, c6), gb.matvec(W2n, -1, cn),
+                gb.matvec(W3b, -1, cd)]
+        losses += [gb.sqnorm(t) for t in outs[:-2]] + [gb.pick_nls(outs[-2], i % M), gb.pick_nls(outs[-1], (3 * i) % M)]
+        losses.append(gb.sqnorm(gb.tanh(cn)))
+    root = gb.add(losses)
+    return p, gb.finish(root, rows), kinds
+
+
+@pytest.mark.parametrize("mode,rows,H", [("depth", 7, 8), ("agenda", 7, 8), ("nobatch", 5, 8), ("depth", 300, 64)])
+def test_concats_that_only_products_read_are_not_copied(mode, rows, H):
+    """Section 3.3 (operands that already lie in memory are used where they are): a CONCAT batch whose only
+    readers are matrix products is not written by the forward pass; the products read every row's pieces from
+    the rows of their producers, and so do the weight-gradient tiles.  Values, gradients and parameter
+    gradients against the oracle, bit-identical to the run that copies every CONCAT, which batches stay
+    uncopied, and reading such a node's value (its row is filled in on demand)."""
+    from paper_1705_07860_amd import binding as ob
+    p, g, kinds = _concat_graph(rows, H)
+    o = Oracle(g, p, "f64")
+    o.forward()
+    o.backward(g.root)
+    total = int(o.v_off[-1])
+    m_ = {"depth": ob.OB_BYDEPTH, "agenda": ob.OB_BYAGENDA, "nobatch": ob.OB_NOBATCH}[mode]
+    say(f"  concat graph: {g.n} nodes, mode {mode}, {rows} rows, H {H}")
+    c, root = run_gpu(p, g, m_, arena=512 << 20)
+    st = c.stats()
+    uncopied = sum(len(kinds[k]) * w for k, w in (("c1", H), ("c2", 2 * H), ("c3", 3 * H), ("c4", 4 * H), ("cu", 2 * H)))
+    if mode == "nobatch":
+        uncopied += len(kinds["cd"]) * 3 * H      # one product per batch: no second piece structure in any batch
+    assert st["uncopied_floats"] == uncopied, (st["uncopied_floats"], uncopied)
+    if mode == "depth":
+        assert st["n_uncopied_batches"] == 5
+    v = kinds["c3"][-1]
+    assert rel_err(c.value_read(int(v), 3 * H), o.value(int(v))) <= TOL       # filled in when asked for
+    check_against_oracle(c, p, g, o, root, what=f"concat in place/{mode}")
+    vals, grads = c.all_read(0, total), c.all_read(1, total)
+    pg = [c.param_grad_read(pid, m.shape) for pid, m in enumerate(p.mats)]
+    c.close()
+    # the same graph with every CONCAT copied: same bits everywhere
+    c = ob.Context(arena_bytes=512 << 20, mode=m_)
+    c.debug_set(ob.OB_DBG_SET_CONCAT_COPY, 1)
+    c.params_create(p)
+    c.param_grad_zero()
+    c.add_bulk(g)
+    c.forward(g.root)
+    assert c.stats()["n_uncopied_batches"] == 0
+    c.backward(g.root)
+    assert np.array_equal(c.all_read(0, total), vals)
+    assert np.array_equal(c.all_read(1, total), grads)
+    for pid, m in enumerate(p.mats):
+        assert np.array_equal(c.param_grad_read(pid, m.shape), pg[pid]), p.names[pid]
+    c.close()
+
+
+def test_uncopied_concat_rows_are_filled_in_for_a_later_evaluation_stage():
+    """A CONCAT that only a product reads when it is evaluated is not copied; nodes added (or evaluated)
+    afterwards that read it in any other way get its row filled in first (Section 3.1 and 3.3 together)."""
+    from paper_1705_07860_amd import binding as ob
+    rng = np.random.default_rng(5)
+    pb = wl.ParamBuilder(rng, std=0.3)
+    H = 8
+    W = pb.add("W", 12, 2 * H)
+    p = pb.done()
+    gb = wl.GraphBuilder(p)
+    cats, first = [], []
+    for i in range(6):
+        a, b = gb.tanh(gb.input(rng.standard_normal(H))), gb.input(rng.standard_normal(H))
+        cats.append(gb.concat((a, b)))
+        first.append(gb.sqnorm(gb.matvec(W, -1, cats[-1])))
+    r1 = gb.add(first)
+    later = [gb.sqnorm(gb.cmult(gb.tanh(cc), cc)) for cc in cats] + [gb.sqnorm(gb.matvec(W, -1, cats[0]))]
+    root = gb.add(later + [r1])
+    g = gb.finish(root, 6)
+    o = Oracle(g, p, "f64")
+    o.forward()
+    o.backward(g.root)
+    c = ob.Context(arena_bytes=64 << 20)
+    c.params_create(p)
+    c.param_grad_zero()
+    c.add_bulk(g)
+    c.forward(r1)
+    assert c.stats()["n_uncopied_batches"] == 1
+    c.forward(g.root)
+    assert c.stats()["n_stages"] == 2
+    check_against_oracle(c, p, g, o, g.root, what="uncopied concat read by a later stage")
+    assert c.stats()["n_stages"] == 2
+    c.close()
+
+
 def _graph_part(g, lo, hi):
     """Nodes lo .. hi-1 of a graph as the arrays of one bulk call (operand ids stay global)."""
     from paper_1705_07860_amd.workloads import Graph
