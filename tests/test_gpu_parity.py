@@ -166,12 +166,49 @@ def test_nobatch_schedule_is_one_node_per_batch(workload_cache):
 
 # ------------------------------------------------------------------ values and gradients
 
+def expected_uncopied_concats(g, bo, ids):
+    """Which CONCAT batches of a schedule need no copy, from the rule alone (plain loops over the graph): at most
+    four pieces, each a multiple of four wide; every reader of every node is a matrix product; and in every batch
+    of products that reads one, all CONCAT operands have the piece widths of the lowest CONCAT batch among them.
+    Returns (number of batches, number of elements)."""
+    bo, ids = np.asarray(bo), np.asarray(ids)
+    batch_of = np.empty(g.n, np.int64)
+    for b in range(len(bo) - 1):
+        batch_of[ids[bo[b]:bo[b + 1]]] = b
+    pieces = lambda v: tuple(int(g.out_dim[u]) for u in g.in_idx[g.in_off[v]:g.in_off[v + 1]])
+    cat_batches = [b for b in range(len(bo) - 1) if g.op[ids[bo[b]]] == wl.OP_CONCAT]
+    ok = {b: len(pieces(ids[bo[b]])) <= 4 and all(w % 4 == 0 for w in pieces(ids[bo[b]])) for b in cat_batches}
+    readers = {}                                      # product batch -> CONCAT operand nodes
+    for v in range(g.n):
+        for u in g.in_idx[g.in_off[v]:g.in_off[v + 1]]:
+            if g.op[u] == wl.OP_CONCAT:
+                if g.op[v] == wl.OP_MATVEC:
+                    readers.setdefault(int(batch_of[v]), []).append(int(u))
+                else:
+                    ok[int(batch_of[u])] = False
+    for mb, cats in readers.items():
+        ref = min(int(batch_of[u]) for u in cats)
+        if not ok[ref] or any(pieces(u) != pieces(ids[bo[ref]]) for u in cats):
+            for u in cats:
+                ok[int(batch_of[u])] = False
+    good = [b for b in cat_batches if ok[b]]
+    return len(good), int(sum((bo[b + 1] - bo[b]) * g.out_dim[ids[bo[b]]] for b in good))
+
+
 @pytest.mark.parametrize("name", ["rnn", "tagger", "tagger_char", "tree", "parser"])
 def test_values_and_gradients_by_depth(name, workload_cache):
     from paper_1705_07860_amd import binding as ob
     p, g, o = workload_cache(name)
     say(f"parity {name}: n={g.n}")
     c, root = run_gpu(p, g, ob.OB_BYDEPTH)
+    st = c.stats()
+    bo, ids, _, _ = c.schedule_read()
+    n_cat = int(np.sum(g.op[np.asarray(ids)[np.asarray(bo[:-1])]] == wl.OP_CONCAT))
+    want = expected_uncopied_concats(g, bo, ids)
+    say(f"  {n_cat} CONCAT batches, {want[0]} of them ({want[1]} elements) need no copy; "
+        f"{st['n_view_batches']} SLICE batches are views")
+    assert (st["n_uncopied_batches"], st["uncopied_floats"]) == want
+    assert st["n_view_batches"] == int(np.sum(g.op[np.asarray(ids)[np.asarray(bo[:-1])]] == wl.OP_SLICE))
     check_against_oracle(c, p, g, o, root, what=name)
     st = c.stats()
     say(f"  sched {st['ms_schedule']:.3f} ms fwd {st['ms_forward']:.3f} ms bwd {st['ms_backward']:.3f} ms "
@@ -632,6 +669,8 @@ def test_concats_that_only_products_read_are_not_copied(mode, rows, H):
     if mode == "nobatch":
         uncopied += len(kinds["cd"]) * 3 * H      # one product per batch: no second piece structure in any batch
     assert st["uncopied_floats"] == uncopied, (st["uncopied_floats"], uncopied)
+    bo, ids, _, _ = c.schedule_read()
+    assert (st["n_uncopied_batches"], st["uncopied_floats"]) == expected_uncopied_concats(g, bo, ids)
     if mode == "depth":
         assert st["n_uncopied_batches"] == 5
     v = kinds["c3"][-1]
