@@ -623,7 +623,7 @@ __global__ void k_batch_layout(Tables T, Lay *lay_in, int virt)
         r.vec4 = TF_VEC4 | TF_ALIGNED | TF_G_ALIAS;   // cleared below by whatever a member violates
         if (r.op == OP_MATVEC && B >= WIDE_MIN_ROWS && r.d >= (u32)GTW) r.vec4 |= TF_WIDE;
         if (r.op == OP_SLICE) r.vec4 |= TF_VIEW;
-        if (r.op == OP_CONCAT && virt) r.vec4 |= TF_VIRT;   // taken back by k_member_check / k_virt_check
+        if (r.op == OP_CONCAT && virt) r.vec4 |= TF_VIRT;   // taken back by k_node_offsets / k_opnd
         if (r.op == OP_MATVEC && virt) r.vec4 |= TF_XP;     // taken back by k_xp_check
         T.batches[b] = r;
         const u64 vs = (u64)B * r.d;
@@ -738,19 +738,6 @@ __global__ void k_member_check(Tables T)
     xp_check(T, p, r);
 }
 
-// Per edge into a CONCAT node: any reader that is not a product reading in pieces needs the row in place.
-__global__ void k_virt_check(Tables T)
-{
-    const u32 e = blockIdx.x * blockDim.x + threadIdx.x;
-    if (e >= T.E) return;
-    const u32 u = T.in_idx[e];
-    if (T.op[u] != OP_CONCAT) return;
-    BatchRec &ru = T.batches[T.batch_of_pos[T.pos_of[u]]];
-    if (!(ru.vec4 & TF_VIRT)) return;
-    const BatchRec &rv = T.batches[T.batch_of_pos[T.pos_of[T.edge_cons[e]]]];
-    if (!(rv.op == OP_MATVEC && (rv.vec4 & TF_XP) && rv.aux1 > 0)) atomicAnd(&ru.vec4, ~(u32)TF_VIRT);
-}
-
 __device__ inline bool batch_xp(const BatchRec &r) { return r.op == OP_MATVEC && (r.vec4 & TF_XP) && r.aux1 > 0; }
 
 // Per edge: operand row offsets per batch (slot-major), operand dimensions of the batch, the
@@ -771,10 +758,17 @@ __global__ void k_opnd(Tables T)
         atomicOr(&T.hdr->err, (u32)ERR_COLLISION);
         return;
     }
-    if (batch_xp(r)) {
-        // the operand in pieces: the rows of an uncopied CONCAT node's operands, or the whole row once per piece
+    const bool xp = batch_xp(r);
+    // an edge into a CONCAT node: any reader that is not a product reading in pieces needs the row in place
+    if (T.op[u] == OP_CONCAT && !xp) {
+        BatchRec &ru = T.batches[T.batch_of_pos[T.pos_of[u]]];
+        if (ru.vec4 & TF_VIRT) atomicAnd(&ru.vec4, ~(u32)TF_VIRT);
+    }
+    if (xp) {
+        // the operand in pieces: the rows of a CONCAT node's operands (where the producers left them, whether or
+        // not the CONCAT batch ends up copied for another reader's sake), or the whole row once per piece
         const u32 P = (u32)r.aux1;
-        const bool pieces = T.op[u] == OP_CONCAT && (T.batches[T.batch_of_pos[T.pos_of[u]]].vec4 & TF_VIRT);
+        const bool pieces = T.op[u] == OP_CONCAT;
         u32 start = 0;
         for (u32 q = 0; q < P; ++q) {
             u32 off = T.val_off[u];
@@ -1782,7 +1776,6 @@ int sched_enqueue(ob_ctx *ctx)
     K(k_node_offsets, n, T);
     K(k_view_offsets, n, T);
     K(k_member_check, n, T);
-    if (virt && E > 0) K(k_virt_check, E, T);
     if (E > 0) K(k_opnd, E, T);
     if (E > 0) K(k_edges, E, T);
 
