@@ -867,8 +867,13 @@ __global__ void k_bedges(Tables T, u32 *bset, u32 *blist)
 }
 
 // One workgroup.  Over the batch dependencies, where a fusable edge costs 0 and any other edge one
-// launch boundary, relaxed to a fixed point over the distinct dependencies held in LDS:
-// head(b) = longest path from any source to b, tail(b) = longest path from b to any sink.  The
+// launch boundary: head(b) = longest path from any source to b, tail(b) = longest path from b to any
+// sink.  Batch ids are a topological order (a batch's operands lie in earlier batches in every batching
+// mode), so the distinct dependencies are first put in the order of their consumer (a counting sort in
+// LDS) and then walked once by one wave, 64 at a time: forward for the heads (every producer of a chunk's
+// consumers was settled by an earlier chunk or is settled inside the chunk, which is passed over until
+// nothing changes), backward for the tails.  That is as many dependent steps as the list has chunks
+// instead of as many as the longest path has edges.  The
 // plan has L + 1 slots, L = max head.  fuse == 1 places a batch as early as possible (slot =
 // head), fuse == 2 as late as possible (slot = L - tail): batches off the critical path then
 // gather in the slots next to their consumers instead of trailing the recurrence one small
@@ -882,6 +887,7 @@ __global__ __launch_bounds__(SLOT_THREADS) void k_slots(Tables T, int fuse, cons
     __shared__ u32 s_edge[BLIST_MAX];
     __shared__ u32 s_changed;
     __shared__ u32 s_flag[3];
+    __shared__ u32 s_wsum[SLOT_THREADS / 64];
     const u32 nb = T.hdr->n_batches;
     const u32 ne = T.hdr->n_bedges;
     const u32 tid = threadIdx.x;
@@ -890,28 +896,66 @@ __global__ __launch_bounds__(SLOT_THREADS) void k_slots(Tables T, int fuse, cons
         if (tid == 0) { T.hdr->n_slots = T.hdr->n_steps; T.hdr->slot_sweeps = 0; T.hdr->p0 = 1; }
         return;
     }
-    for (u32 b = tid; b < nb; b += SLOT_THREADS) { s_slot[b] = 0; s_label[b] = 0; }
-    for (u32 e = tid; e < ne; e += SLOT_THREADS) s_edge[e] = blist[e] - 1u;
-    // One barrier per sweep: sweep k raises s_flag[k % 3] when it changes anything, everybody reads
-    // it behind the sweep's barrier, and the flag of sweep k + 1 is cleared during sweep k (its last
-    // readers were those of sweep k - 2, who have all passed the barrier of sweep k - 1).
-    if (tid < 3) s_flag[tid] = 0;
+    // ---- the dependencies in the order of their consumer: count per consumer (in s_label), exclusive scan,
+    // scatter (the order among one consumer's entries does not matter: only maxima and minima are taken)
+    for (u32 b = tid; b < SLOT_MAX_NB; b += SLOT_THREADS) { s_slot[b] = 0; s_label[b] = 0; }
     __syncthreads();
-    u32 sweeps = 0;
-    while (true) {
-        const u32 f = sweeps % 3u;
-        if (tid == 0) s_flag[(sweeps + 1u) % 3u] = 0;
-        for (u32 e = tid; e < ne; e += SLOT_THREADS) {
-            const u32 k = s_edge[e];
-            const u32 c = k >> 13, y = (k >> 1) & 0xfffu;
-            const u32 want = s_slot[y] + (k & 1u);
-            if (want > s_slot[c]) { atomicMax(&s_slot[c], want); s_flag[f] = 1; }
-            const u32 tw = s_label[c] + (k & 1u);
-            if (tw > s_label[y]) { atomicMax(&s_label[y], tw); s_flag[f] = 1; }
-        }
+    for (u32 e = tid; e < ne; e += SLOT_THREADS) atomicAdd(&s_label[(blist[e] - 1u) >> 13], 1u);
+    __syncthreads();
+    {
+        constexpr u32 PER = SLOT_MAX_NB / SLOT_THREADS;   // consecutive counters per thread
+        u32 c[PER], sum = 0;
+        for (u32 i = 0; i < PER; ++i) { c[i] = s_label[tid * PER + i]; sum += c[i]; }
+        u32 inc = sum;                                     // inclusive scan over the wave
+        for (u32 o = 1; o < 64; o <<= 1) { const u32 v = (u32)__shfl_up((int)inc, o); if ((tid & 63u) >= o) inc += v; }
+        if ((tid & 63u) == 63u) s_wsum[tid >> 6] = inc;
         __syncthreads();
-        ++sweeps;
-        if (!s_flag[f] || sweeps > nb + 1) break;
+        u32 before = inc - sum;
+        for (u32 w = 0; w < (tid >> 6); ++w) before += s_wsum[w];
+        for (u32 i = 0; i < PER; ++i) { s_label[tid * PER + i] = before; before += c[i]; }
+    }
+    __syncthreads();
+    for (u32 e = tid; e < ne; e += SLOT_THREADS) {
+        const u32 k = blist[e] - 1u;
+        s_edge[atomicAdd(&s_label[k >> 13], 1u)] = k;
+    }
+    __syncthreads();
+    for (u32 b = tid; b < SLOT_MAX_NB; b += SLOT_THREADS) s_label[b] = 0;
+    __syncthreads();
+    // ---- heads forward, tails backward: one wave, chunk by chunk (its LDS operations complete in order)
+    u32 walked = 0;      // passes over chunks, for the statistics
+    if (tid < 64) {
+        const u32 n_chunks = (ne + 63u) / 64u;
+        for (u32 ch = 0; ch < n_chunks; ++ch) {
+            const u32 e = ch * 64u + tid;
+            const bool valid = e < ne;
+            const u32 k = valid ? s_edge[e] : 0u;
+            const u32 c = k >> 13, y = (k >> 1) & 0xfffu, cost = k & 1u;
+            for (u32 rep = 0; rep < 66u; ++rep) {          // (a chain inside a chunk has at most 64 links)
+                bool changed = false;
+                if (valid) {
+                    const u32 want = lds_load(&s_slot[y]) + cost;
+                    if (want > lds_load(&s_slot[c])) { atomicMax(&s_slot[c], want); changed = true; }
+                }
+                ++walked;
+                if (__ballot(changed) == 0ull) break;
+            }
+        }
+        for (u32 ch = n_chunks; ch-- > 0;) {
+            const u32 e = ch * 64u + tid;
+            const bool valid = e < ne;
+            const u32 k = valid ? s_edge[e] : 0u;
+            const u32 c = k >> 13, y = (k >> 1) & 0xfffu, cost = k & 1u;
+            for (u32 rep = 0; rep < 66u; ++rep) {
+                bool changed = false;
+                if (valid) {
+                    const u32 tw = lds_load(&s_label[c]) + cost;
+                    if (tw > lds_load(&s_label[y])) { atomicMax(&s_label[y], tw); changed = true; }
+                }
+                ++walked;
+                if (__ballot(changed) == 0ull) break;
+            }
+        }
     }
     __syncthreads();
     {   // number of slots; late placement; labels start as the batch's own id
@@ -930,9 +974,12 @@ __global__ __launch_bounds__(SLOT_THREADS) void k_slots(Tables T, int fuse, cons
         if (tid == 0) T.hdr->n_slots = L + 1;
         __syncthreads();
     }
+    // One barrier per sweep: sweep k raises s_flag[k % 3] when it changes anything, everybody reads
+    // it behind the sweep's barrier, and the flag of sweep k + 1 is cleared during sweep k (its last
+    // readers were those of sweep k - 2, who have all passed the barrier of sweep k - 1).
     if (tid < 3) s_flag[tid] = 0;
     __syncthreads();
-    const u32 sweeps0 = sweeps;
+    u32 sweeps = 0;
     while (true) {
         const u32 f = sweeps % 3u;
         if (tid == 0) s_flag[(sweeps + 1u) % 3u] = 0;
@@ -951,10 +998,10 @@ __global__ __launch_bounds__(SLOT_THREADS) void k_slots(Tables T, int fuse, cons
         }
         __syncthreads();
         ++sweeps;
-        if (!s_flag[f] || sweeps - sweeps0 > 2 * nb + 2) break;
+        if (!s_flag[f] || sweeps > 2 * nb + 2) break;
     }
     for (u32 b = tid; b < nb; b += SLOT_THREADS) { T.slot_of[b] = s_slot[b]; T.label_of[b] = s_label[b]; }
-    if (tid == 0) T.hdr->slot_sweeps = sweeps;
+    if (tid == 0) T.hdr->slot_sweeps = walked + sweeps;
 }
 
 __global__ void k_launch_keys(Tables T, u64 *keys, u32 *vals, u32 n_pad)
