@@ -539,10 +539,17 @@ __global__ void k_rep_insert(Tables T)
     if (v >= T.n) return;
     const u64 k = batch_key(T.sig[v], T.step[v]);
     u32 slot = (u32)k & T.ht_mask;
+    // Thousands of nodes share a key: a node first looks (keys never change once set, values only fall, so
+    // whatever a look returns is safe to act on) and takes the atomic path only for an empty slot or a value
+    // above its own id; low ids mostly run first, so most nodes end up with two reads.
     for (u32 probe = 0; probe <= T.ht_mask; ++probe) {
-        const u64 old = atomicCAS((unsigned long long *)&T.ht_keys[slot], 0ULL, (unsigned long long)k);
-        if (old == 0 || old == k) {
-            atomicMin(&T.ht_vals[slot], v);
+        u64 cur = __hip_atomic_load(&T.ht_keys[slot], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (cur == 0) {
+            cur = atomicCAS((unsigned long long *)&T.ht_keys[slot], 0ULL, (unsigned long long)k);
+            if (cur == 0) cur = k;
+        }
+        if (cur == k) {
+            if (__hip_atomic_load(&T.ht_vals[slot], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) > v) atomicMin(&T.ht_vals[slot], v);
             T.ht_slot[v] = slot;
             return;
         }
@@ -854,7 +861,10 @@ __global__ void k_bedges(Tables T, u32 *bset, u32 *blist)
     const u32 key = ((b << 13) | (by << 1) | (ok ? 0u : 1u)) + 1u;
     u32 h = (key * 2654435761u) & (BSET_SIZE - 1);
     for (u32 probe = 0; probe < BSET_SIZE; ++probe) {
-        const u32 old = atomicCAS(&bset[h], 0u, key);
+        // (all edges between two batches carry the same triple: look before the compare-and-swap)
+        u32 old = __hip_atomic_load(&bset[h], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (old == key) return;
+        if (old == 0u) old = atomicCAS(&bset[h], 0u, key);
         if (old == key) return;
         if (old == 0u) {
             const u32 i = atomicAdd(&T.hdr->n_bedges, 1u);
@@ -1300,7 +1310,13 @@ __device__ inline void fill_tile_desc(const Tables &T, const BatchRec &r, u32 t,
             u32 ss = 0;
             if (r_hi > r_lo) {
                 ss = gs[r_lo + 1] - base;
-                for (u32 i = 2; ok && r_lo + i <= r_hi; ++i) ok = gs[r_lo + i] == base + i * ss;
+                for (u32 i0 = 2; r_lo + i0 <= r_hi; i0 += 8) {      // eight reads in flight
+                    u32 o[8];
+#pragma unroll
+                    for (u32 q = 0; q < 8; ++q) o[q] = gs[r_lo + (r_lo + i0 + q <= r_hi ? i0 + q : 0u)];
+#pragma unroll
+                    for (u32 q = 0; q < 8; ++q) ok = ok && (r_lo + i0 + q > r_hi || o[q] == base + (i0 + q) * ss);
+                }
             }
             d.base[0] = base; d.sstride[0] = ss;
             if (ok) d.contig |= 1u;
@@ -1335,10 +1351,16 @@ __device__ inline void fill_tile_desc(const Tables &T, const BatchRec &r, u32 t,
         lo[j] = hi[j] = base;
         if (ok && nrows > 1) {
             ss = op[row0 + rstride] - base;
-            for (u32 i = 1; i < nrows; ++i) {
-                const u32 o = op[row0 + i * rstride];
-                ok = ok && o == base + i * ss;
-                lo[j] = o < lo[j] ? o : lo[j]; hi[j] = o > hi[j] ? o : hi[j];
+            for (u32 i0 = 1; i0 < nrows; i0 += 8) {      // eight reads in flight
+                u32 o[8];
+#pragma unroll
+                for (u32 q = 0; q < 8; ++q) o[q] = op[row0 + (i0 + q < nrows ? i0 + q : 0u) * rstride];
+#pragma unroll
+                for (u32 q = 0; q < 8; ++q) {
+                    if (i0 + q >= nrows) continue;
+                    ok = ok && o[q] == base + (i0 + q) * ss;
+                    lo[j] = o[q] < lo[j] ? o[q] : lo[j]; hi[j] = o[q] > hi[j] ? o[q] : hi[j];
+                }
             }
         }
         d.sstride[j] = ss;
@@ -1389,16 +1411,33 @@ __device__ inline void fill_pull_base(const Tables &T, const BatchRec &r, u32 ro
         ue.gs = ue.vs = 0; ue.a0 = first[j].a0; ue.a1 = first[j].a1; ue.dl = 0;
         d.e[j] = ue;
     }
-    for (u32 i = 1; i < nrows; ++i) {
-        const u32 u = T.order[r.pos0 + row0 + i * rstride];
-        const u32 q = T.succ_off[u];
-        if (T.succ_off[u + 1] - q != cnt) return;
+    // The other rows must have the same edges, shifted by constant strides.  Every step is a read that
+    // depends on the one before (row -> node -> its consumer list -> the edge records), so each step is
+    // taken for all rows at once (rows past the tile's last repeat row 0: no read leaves the lists).
+    if (nrows > 1) {
+        u32 qs[PULL_MAX_ROWS];
+        bool same = true;
+#pragma unroll
+        for (u32 i = 1; i < PULL_MAX_ROWS; ++i) {
+            const u32 u = T.order[r.pos0 + row0 + (i < nrows ? i : 0u) * rstride];
+            qs[i] = T.succ_off[u];
+            same = same && T.succ_off[u + 1] - qs[i] == cnt;
+        }
+        if (!same) return;
         for (u32 j = 0; j < cnt; ++j) {
-            const EdgeRec er = T.edges[q + j];
-            if (er.kind != first[j].kind || er.a0 != first[j].a0 || er.a1 != first[j].a1) return;
-            const u32 dg = er.goff - first[j].goff, dv = er.voff - first[j].voff;
-            if (i == 1) { d.e[j].gs = dg; d.e[j].vs = dv; }
-            else if (dg != d.e[j].gs * i || dv != d.e[j].vs * i) return;
+            EdgeRec er[PULL_MAX_ROWS];
+#pragma unroll
+            for (u32 i = 1; i < PULL_MAX_ROWS; ++i) er[i] = T.edges[qs[i] + j];
+            const u32 gs = er[1].goff - first[j].goff, vs = er[1].voff - first[j].voff;
+            bool ok = true;
+#pragma unroll
+            for (u32 i = 1; i < PULL_MAX_ROWS; ++i) {
+                if (i >= nrows) continue;
+                ok = ok && er[i].kind == first[j].kind && er[i].a0 == first[j].a0 && er[i].a1 == first[j].a1 &&
+                     er[i].goff - first[j].goff == gs * i && er[i].voff - first[j].voff == vs * i;
+            }
+            if (!ok) return;
+            d.e[j].gs = gs; d.e[j].vs = vs;
         }
     }
     d.n_uni = cnt;
@@ -1471,6 +1510,11 @@ __global__ void k_tiles(Tables T, const CLay *clay_ex, const CLay *total, u32 ca
 {
     const u32 nc = T.hdr->n_chains;
     const u32 gtid = blockIdx.x * blockDim.x + threadIdx.x, gsz = gridDim.x * blockDim.x;
+    // the five lists laid end to end, one entry per thread and pass: an entry is a chain of dependent reads
+    // (chain, batch, operand rows), so a thread that took one entry of each list in turn would take five
+    // times as long as the slowest entry
+    u32 nts[5];
+#pragma unroll
     for (int which = 0; which < 5; ++which) {
         u32 nt = clay_field(*total, which);
         const u32 cap = (which == 0 || which == 3) ? cap_f : ((which == 1 || which == 4) ? cap_a : cap_b);
@@ -1478,7 +1522,13 @@ __global__ void k_tiles(Tables T, const CLay *clay_ex, const CLay *total, u32 ca
             if (gtid == 0) atomicOr(&T.hdr->err, (u32)ERR_OVERFLOW);
             nt = cap;
         }
-        for (u32 x = gtid; x < nt; x += gsz) {
+        nts[which] = nt;
+    }
+    const u32 f1 = nts[0], f2 = f1 + nts[1], f3 = f2 + nts[2], f4 = f3 + nts[3], f5 = f4 + nts[4];
+    for (u32 idx = gtid; idx < f5; idx += gsz) {
+        const int which = (idx >= f1) + (idx >= f2) + (idx >= f3) + (idx >= f4);
+        {
+            const u32 x = idx - (which == 0 ? 0u : (which == 1 ? f1 : (which == 2 ? f2 : (which == 3 ? f3 : f4))));
             const u32 c = chain_of_index(clay_ex, nc, which, x);
             const ChainRec cr = T.chains[c];
             const u32 xx = x - clay_field(clay_ex[c], which);
