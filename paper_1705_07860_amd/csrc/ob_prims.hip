@@ -98,6 +98,37 @@ __global__ __launch_bounds__(SCAN_THREADS) void k_scan_add(T *out, const T *bloc
         if (base + i < n) out[base + i] = out[base + i] + add;
 }
 
+// Up to SCAN_THREADS blocks: every block adds up the sums of the blocks before it itself (a few hundred
+// integers), so the launch that scans the block sums is not needed.  Block 0 also leaves the total.
+template <typename T>
+__device__ inline T block_sum(T mine, T *lds)
+{
+    const int t = threadIdx.x;
+    lds[t] = mine;
+    __syncthreads();
+    for (int off = SCAN_THREADS / 2; off > 0; off >>= 1) {
+        if (t < off) lds[t] = lds[t] + lds[t + off];
+        __syncthreads();
+    }
+    const T r = lds[0];
+    __syncthreads();
+    return r;
+}
+template <typename T>
+__global__ __launch_bounds__(SCAN_THREADS) void k_scan_add_own(T *out, const T *block_sums, size_t nblk, size_t n, T *total_out)
+{
+    __shared__ T lds[SCAN_THREADS];
+    const size_t t = threadIdx.x;
+    const T add = block_sum<T>(t < blockIdx.x ? block_sums[t] : zero_of<T>(), lds);
+    const size_t base = (size_t)blockIdx.x * SCAN_BLOCK + t * SCAN_ITEMS;
+    for (int i = 0; i < SCAN_ITEMS; ++i)
+        if (base + i < n) out[base + i] = out[base + i] + add;
+    if (blockIdx.x == 0 && total_out) {
+        const T total = block_sum<T>(t < nblk ? block_sums[t] : zero_of<T>(), lds);
+        if (t == 0) *total_out = total;
+    }
+}
+
 // Short inputs: one workgroup walks the chunks with a carry, one launch instead of two or three
 // (the scheduler of a small graph is bound by the number of its launches).  in == out is fine.
 constexpr size_t SCAN_SMALL_MAX = 4 * SCAN_BLOCK;
@@ -140,6 +171,10 @@ hipError_t scan_impl(const T *in, T *out, size_t n, T *total_dev, void *scratch,
     const size_t nblk = (n + SCAN_BLOCK - 1) / SCAN_BLOCK;
     T *sums = (T *)scratch;
     hipLaunchKernelGGL(k_scan_local<T>, dim3((unsigned)nblk), dim3(SCAN_THREADS), 0, s, in, out, sums, n);
+    if (nblk <= (size_t)SCAN_THREADS) {
+        hipLaunchKernelGGL(k_scan_add_own<T>, dim3((unsigned)nblk), dim3(SCAN_THREADS), 0, s, out, sums, nblk, n, total_dev);
+        return hipGetLastError();
+    }
     hipLaunchKernelGGL(k_scan_sums<T>, dim3(1), dim3(SCAN_THREADS), 0, s, sums, nblk, total_dev);
     if (nblk > 1)
         hipLaunchKernelGGL(k_scan_add<T>, dim3((unsigned)nblk), dim3(SCAN_THREADS), 0, s, out, sums, n);

@@ -1822,7 +1822,8 @@ int sched_enqueue(ob_ctx *ctx)
     K(k_node_init, n, T, manual ? 2 : by_depth);
     if (E > 0) K(k_edge_init, E, T, ctx->key_a, ctx->val_a);
     HIP_TRY(ctx, prim_scan_u32(T.outdeg, T.succ_off, (size_t)n + 1, nullptr, ctx->scratch, s));
-    const int scan_launches = (size_t)n + 1 <= 4096 ? 1 : 3;   // a scan of a short array is one launch
+    // a scan of a short array is one launch, up to 256 blocks of 1024 elements two, beyond that three
+    const int scan_launches = (size_t)n + 1 <= 4096 ? 1 : ((size_t)n + 1 <= 256 * 1024 ? 2 : 3);
     ctx->n_launch_sched += scan_launches;
     if (E > 0) {
         HIP_TRY(ctx, prim_sort_pairs_swap(ctx->key_a, ctx->val_a, ctx->key_b, ctx->val_b, E, 0,
