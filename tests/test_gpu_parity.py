@@ -695,6 +695,27 @@ def test_concats_that_only_products_read_are_not_copied(mode, rows, H):
     c.close()
 
 
+@pytest.mark.parametrize("seed", range(6))
+def test_random_dags_with_concats_read_in_place(seed):
+    """Random graphs over every operation with rows of 8 elements: CONCAT nodes of views, leaves and results feed
+    products, sums, slices and losses in every mix.  Which CONCAT batches stay uncopied must follow the rule, and
+    values and gradients must match the oracle, in depth and in agenda mode."""
+    from paper_1705_07860_amd import binding as ob
+    p, g = wl.random_dag(1200 + seed, n_nodes=400, dim=8)
+    o = Oracle(g, p, "f64")
+    o.forward()
+    o.backward(g.root)
+    for mode in (ob.OB_BYDEPTH, ob.OB_BYAGENDA):
+        c, root = run_gpu(p, g, mode, arena=256 << 20)
+        st = c.stats()
+        bo, ids, _, _ = c.schedule_read()
+        want = expected_uncopied_concats(g, bo, ids)
+        say(f"  dag {seed}, mode {mode}: {want[0]} CONCAT batches need no copy")
+        assert (st["n_uncopied_batches"], st["uncopied_floats"]) == want
+        check_against_oracle(c, p, g, o, root, what=f"concat dag {seed}/mode {mode}")
+        c.close()
+
+
 def test_uncopied_concat_rows_are_filled_in_for_a_later_evaluation_stage():
     """A CONCAT that only a product reads when it is evaluated is not copied; nodes added (or evaluated)
     afterwards that read it in any other way get its row filled in first (Section 3.1 and 3.3 together)."""
