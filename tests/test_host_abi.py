@@ -31,6 +31,26 @@ def test_library_exports_every_declared_symbol():
     assert set(L._ob_names) == declared, "binding and header disagree"
 
 
+def test_stats_record_of_the_binding_matches_the_header():
+    """ob_stats_read fills a caller-owned record: the ctypes mirror must list the header's fields in the
+    header's order with the header's types, or the library would write past it."""
+    import ctypes
+    header = (ROOT / "include" / "ob.h").read_text()
+    body = re.search(r"typedef struct ob_stats \{(.*?)\} ob_stats;", header, re.S).group(1)
+    body = re.sub(r"/\*.*?\*/", "", body, flags=re.S)
+    ctype = {"int32_t": ctypes.c_int32, "uint64_t": ctypes.c_uint64, "float": ctypes.c_float}
+    want = []
+    for decl in body.split(";"):
+        decl = decl.strip()
+        if not decl:
+            continue
+        t, names = decl.split(None, 1)
+        want += [(n.strip(), ctype[t]) for n in names.split(",")]
+    got = [(n, t) for n, t in ob.ObStats._fields_]
+    assert got == want
+    assert ctypes.sizeof(ob.ObStats) == sum(ctypes.sizeof(t) for _, t in want)   # (no padding: 8-byte fields fall on 8-byte offsets)
+
+
 def _host_ctx(params=None):
     c = ob.Context(arena_bytes=0)
     ids = c.params_create(params) if params is not None else []
