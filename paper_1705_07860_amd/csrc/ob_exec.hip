@@ -787,21 +787,29 @@ __device__ inline void param_w_tile(const Tables &T, const PTile &pt, float *lds
     const u32 per = (all_chunks + nsp_eff - 1) / nsp_eff;
     const u32 c_lo = sp * per, c_hi = (sp + 1) * per < all_chunks ? (sp + 1) * per : all_chunks;
     const u32 n_uses = end - start;
-    u32 go[2], xo[2];
-    bool ok[2];
-    auto offsets = [&](u32 c) {
+    // Row offsets run ahead of the rows in two steps, each a round trip to memory of its own: heads() asks for
+    // the offsets of the chunk after next, resolve() makes the next chunk's offsets current and, for a use whose
+    // operand row is in pieces (its batch reads through an uncopied CONCAT: it_xoff is XP_LIST), asks for the
+    // use's piece record; fetch() picks the piece this thread's four columns lie in and asks for the rows.
+    u32 go[2] = {0u, 0u}, xo[2] = {0u, 0u}, ngo[2] = {0u, 0u}, nxo[2] = {0u, 0u}, rec[2] = {0u, 0u};
+    uint4 ro[2] = {make_uint4(0u, 0u, 0u, 0u), make_uint4(0u, 0u, 0u, 0u)}, rc[2] = {ro[0], ro[0]};
+    bool ok[2] = {false, false}, nok[2] = {false, false};
+    auto heads = [&](u32 c) {
 #pragma unroll
         for (int p = 0; p < 2; ++p) {
             const u32 it = c * PWC + lu + 16u * p;
-            ok[p] = it < n_uses;
-            go[p] = ok[p] ? T.it_goff[start + it] : 0u;
-            xo[p] = ok[p] ? T.it_xoff[start + it] : 0u;
-            if (xo[p] == XP_LIST) {
-                // the use's operand row is in pieces (its batch reads through an uncopied CONCAT): this thread's
-                // four columns lie in one piece
-                const uint4 o = T.it_xrec[2 * (size_t)(start + it)], c = T.it_xrec[2 * (size_t)(start + it) + 1];
-                xo[p] = xj >= c.z ? o.w : (xj >= c.y ? o.z : (xj >= c.x ? o.y : o.x));
-            }
+            nok[p] = it < n_uses;
+            rec[p] = start + it;
+            ngo[p] = nok[p] ? T.it_goff[start + it] : 0u;
+            nxo[p] = nok[p] ? T.it_xoff[start + it] : 0u;
+        }
+    };
+    u32 crec[2] = {0u, 0u};
+    auto resolve = [&]() {
+#pragma unroll
+        for (int p = 0; p < 2; ++p) {
+            ok[p] = nok[p]; go[p] = ngo[p]; xo[p] = nxo[p]; crec[p] = rec[p];
+            if (ok[p] && xo[p] == XP_LIST) { ro[p] = T.it_xrec[2 * (size_t)crec[p]]; rc[p] = T.it_xrec[2 * (size_t)crec[p] + 1]; }
         }
     };
     const float4 z4 = make_float4(0.f, 0.f, 0.f, 0.f);
@@ -809,17 +817,24 @@ __device__ inline void param_w_tile(const Tables &T, const PTile &pt, float *lds
     auto fetch = [&]() {
 #pragma unroll
         for (int p = 0; p < 2; ++p) {
+            u32 x = xo[p];
+            if (ok[p] && x == XP_LIST) x = xj >= rc[p].z ? ro[p].w : (xj >= rc[p].y ? ro[p].z : (xj >= rc[p].x ? ro[p].y : ro[p].x));
             pg[p] = ok[p] ? ld4_guard(T.G, go[p] + gi, gn) : z4;
-            px[p] = ok[p] ? ld4_guard(T.V, xo[p] + xj, xn) : z4;
+            px[p] = ok[p] ? ld4_guard(T.V, x + xj, xn) : z4;
         }
     };
     floatx16 acc;
     for (int v = 0; v < 16; ++v) acc[v] = 0.f;
     const u32 n_chunks = c_hi;
     if (c_lo < c_hi) {
-        offsets(c_lo);
+        heads(c_lo);
+        resolve();
+        if (c_lo + 1 < c_hi) heads(c_lo + 1);
         fetch();
-        if (c_lo + 1 < c_hi) offsets(c_lo + 1);
+        if (c_lo + 1 < c_hi) {
+            resolve();
+            if (c_lo + 2 < c_hi) heads(c_lo + 2);
+        }
     }
     const u32 acol = 32u * (w >> 1) + l32, bcol = 32u * (w & 1u) + l32;
     for (u32 c = c_lo; c < n_chunks; ++c) {
@@ -831,8 +846,11 @@ __device__ inline void param_w_tile(const Tables &T, const PTile &pt, float *lds
         }
         __syncthreads();
         if (c + 1 < n_chunks) {
-            fetch();                                   // chunk c + 1, offsets already here
-            if (c + 2 < n_chunks) offsets(c + 2);
+            fetch();                                   // chunk c + 1: its offsets (and piece records) are here
+            if (c + 2 < n_chunks) {
+                resolve();                             // chunk c + 2
+                if (c + 3 < n_chunks) heads(c + 3);
+            }
         }
 #pragma unroll
         for (u32 b8 = 0; b8 < PWC / 8; ++b8) {
